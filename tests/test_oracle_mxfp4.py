@@ -1,0 +1,225 @@
+"""Pins for the oracle's two-pass MXFP4 decomposition and W4A16 GEMM (Sec. 3.2.1, Alg. 2,
+Sec. 3.4.1).  Checks: Theorem 2 and the intermediate bounds of its proof, the clip rate and
+tightness the paper tabulates, an independently written exact-rational implementation,
+exhaustive single-element blocks, brute-force block dots and the fp64 truth."""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_13915_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+with open(os.path.join(GOLDEN, "paper_tables.json")) as _f:
+    GOLD = json.load(_f)
+
+
+def unpack_quarters(q):
+    """nibble-packed sign-magnitude codes -> integer k (value k/4), shape [M][K]."""
+    M, K2 = q.shape
+    nib = np.empty((M, K2 * 2), np.int32)
+    nib[:, 0::2] = q & 15
+    nib[:, 1::2] = q >> 4
+    return np.where(nib & 8, -(nib & 7), nib & 7)
+
+
+def reconstruct(q1, q2, e, shift=4):
+    k1 = unpack_quarters(q1).astype(np.float64)
+    k2 = unpack_quarters(q2).astype(np.float64)
+    a = np.exp2(e.astype(np.float64) - 127)
+    a = np.repeat(a, 32, axis=1)
+    return a * k1 / 4 + a / 2 ** shift * k2 / 4, a, k1, k2
+
+
+def f32(bits):
+    return synth.bf16_bits_to_f32(bits).astype(np.float64)
+
+
+@pytest.mark.parametrize("dist,scale,key", [("normal", 1.0, "normal_1.0"), ("normal", 0.1, "normal_0.1"),
+                                            ("uniform", 1.0, "uniform_1"), ("laplace", 1.0, "laplace_1.0")])
+def test_theorem2_and_proof_steps(dist, scale, key):
+    x = synth.activations(31, 256, 2048, outliers=False, dist=dist, scale=scale)
+    q1, q2, e = oracle.decompose_mxfp4(x)
+    xf = f32(x)
+    rec, a, k1, k2 = reconstruct(q1, q2, e)
+    err = np.abs(xf - rec)
+    # Thm 2: error <= alpha/64 ; proof: pass-1 residual <= alpha/8, |r/beta| <= 2
+    assert np.all(err <= a / 64)
+    r = xf - a * k1 / 4
+    assert np.all(np.abs(r) <= a / 8)
+    assert np.all(np.abs(r / (a / 16)) <= 2.0)
+    # alpha selection: M_b/alpha in (1.859375/2, 1.859375]
+    Mb = np.abs(xf).reshape(256, -1, 32).max(axis=2)
+    ratio = Mb / np.exp2(e.astype(np.float64) - 127)
+    assert np.all(ratio <= 1.859375) and np.all(ratio > 1.859375 / 2)
+    # tightness and clip rate as tabulated (Sec. 6.5.4): ratio -> 1, clip ~ 12.5 %
+    tight = (err / (a / 64)).max()
+    assert 0.99 < tight <= 1.0
+    clip = np.mean(np.abs(r / (a / 16)) > 1.75)
+    assert abs(clip - GOLD["mxfp4_bound"]["theoretical_clip_rate"]) < 0.02
+    # loose: relative L2 / effective bits of the decomposition (Sec. 6.5.1 table)
+    l2 = np.linalg.norm(xf - rec) / np.linalg.norm(xf)
+    g = GOLD["mxfp4_decomposition"][key]
+    assert abs(l2 - g["rel_l2"]) / g["rel_l2"] < 0.12
+    assert abs(-math.log2(l2) - g["eff_bits"]) < 0.2
+    # codes use the printed grid only
+    grid = set(GOLD["fp4_grid"]["positive_values"])
+    assert set(np.unique(np.abs(k1) / 4)) <= grid and set(np.unique(np.abs(k2) / 4)) <= grid
+
+
+def _exact_block(vals, hi=Fraction(119, 64), shift=4):
+    """Independent exact-rational Alg. 2 for one block of python floats."""
+    fr = [Fraction(v) for v in vals]
+    Mb = max(abs(v) for v in fr)
+    if Mb == 0:
+        return -123, [0] * len(fr), [0] * len(fr)
+    # smallest integer e with Mb / hi <= 2^e (float log2 as a first guess, then exact correction)
+    e = math.ceil(math.log2(Mb / hi))
+    while Fraction(2) ** e < Mb / hi:
+        e += 1
+    while Fraction(2) ** (e - 1) >= Mb / hi:
+        e -= 1
+    e = max(-123, min(127, e))
+    alpha = Fraction(2) ** e
+
+    def rne(fr_):
+        fl = math.floor(fr_)
+        d = fr_ - fl
+        if d > Fraction(1, 2) or (d == Fraction(1, 2) and fl % 2 == 1):
+            fl += 1
+        return fl
+
+    k1s, k2s = [], []
+    for v in fr:
+        k1 = max(-7, min(7, rne(4 * v / alpha)))
+        r = v - alpha * k1 / 4
+        k2 = max(-7, min(7, rne(4 * r / (alpha / 2 ** shift))))
+        k1s.append(k1)
+        k2s.append(k2)
+    return e, k1s, k2s
+
+
+def test_against_exact_rational_implementation():
+    rng = np.random.default_rng(32)
+    x = synth.activations(32, 8, 256, outliers=True)
+    # plant equality / tie cases: block max exactly 1.859375 * 2^e, values on code midpoints
+    xf = synth.bf16_bits_to_f32(x).copy()
+    xf[0, :32] = 0
+    xf[0, 0] = 1.859375
+    xf[0, 1] = 0.125       # tie between 0 and 0.25 at alpha = 1
+    xf[0, 2] = 0.375
+    xf[0, 3] = -1.8125
+    xf[1, :32] = 0
+    xf[1, 7] = 1.8671875   # just above the relaxed bound -> alpha doubles
+    xf[2, :32] = 0         # all-zero block
+    x = synth.f32_to_bf16_bits(xf)
+    q1, q2, e = oracle.decompose_mxfp4(x)
+    k1 = unpack_quarters(q1)
+    k2 = unpack_quarters(q2)
+    xf = synth.bf16_bits_to_f32(x)
+    for m in range(8):
+        for b in range(8):
+            ee, a1, a2 = _exact_block([float(v) for v in xf[m, b * 32:(b + 1) * 32]])
+            assert ee == int(e[m, b]) - 127
+            assert a1 == k1[m, b * 32:(b + 1) * 32].tolist()
+            assert a2 == k2[m, b * 32:(b + 1) * 32].tolist()
+    assert int(e[0, 0]) - 127 == 0 and int(e[1, 0]) - 127 == 1 and int(e[2, 0]) - 127 == -123
+    assert k1[0, 0] == 7 and k2[0, 0] == 7 and k1[0, 1] == 0 and k2[0, 1] == 7
+
+
+def test_exhaustive_single_element_blocks():
+    # every finite non-negative BF16 value in the normal range as the sole non-zero of a block:
+    # alpha follows from the value alone and the reconstruction error obeys Thm 2.
+    bits = np.arange(0x0080, 0x7F80, dtype=np.uint16)       # all positive normal BF16
+    vals = synth.bf16_bits_to_f32(bits).astype(np.float64)
+    keep = (vals > 2.0 ** -120) & (vals < 2.0 ** 126)
+    bits, vals = bits[keep], vals[keep]
+    x = np.zeros((len(bits), 32), np.uint16)
+    x[:, 3] = bits
+    q1, q2, e = oracle.decompose_mxfp4(x)
+    rec, a, k1, k2 = reconstruct(q1, q2, e)
+    ratio = vals / a[:, 3]
+    assert np.all(ratio <= 1.859375) and np.all(ratio > 1.859375 / 2)
+    assert np.all(np.abs(vals - rec[:, 3]) <= a[:, 3] / 64)
+    assert not k1[:, :3].any() and not k2[:, 4:].any()
+    # sign symmetry
+    xn = x.copy()
+    xn[:, 3] |= 0x8000
+    q1n, q2n, en = oracle.decompose_mxfp4(xn)
+    assert np.array_equal(en, e)
+    assert np.array_equal(unpack_quarters(q1n), -k1.astype(np.int32))
+    assert np.array_equal(unpack_quarters(q2n), -k2.astype(np.int32))
+
+
+def test_variants_v1_v2_follow_the_evolution_table():
+    # Sec. 3.3 table: v1 (1.75, beta=alpha/8) never clips; v2 (1.75, alpha/16) clips ~12.5 %.
+    x = synth.activations(33, 128, 2048, outliers=False)
+    xf = f32(x)
+    errs = {}
+    for v, shift in ((1, 3), (2, 4), (3, 4)):
+        q1, q2, e = oracle.decompose_mxfp4(x, variant=v)
+        rec, a, k1, k2 = reconstruct(q1, q2, e, shift)
+        r = xf - a * k1 / 4
+        Mb = np.abs(xf).reshape(128, -1, 32).max(axis=2)
+        ratio = Mb / np.exp2(e.astype(np.float64) - 127)
+        hi = GOLD["mxfp4_evolution"]["v%d" % v]["alpha_bound"]
+        assert np.all(ratio <= hi) and np.all(ratio > hi / 2)
+        clip = np.mean(np.abs(r / (a / 2 ** shift)) > 1.75)
+        assert abs(clip - GOLD["mxfp4_evolution"]["v%d" % v]["clip"]) < 0.02
+        errs[v] = np.linalg.norm(xf - rec) / np.linalg.norm(xf)
+    assert errs[1] > errs[2] > errs[3]
+    assert 1.5 < errs[1] / errs[3] < 2.1     # 0.0182 / 0.0101 in the table
+
+
+# ------------------------------------------------------------------ W4A16 GEMM
+
+def _e2m1(n):
+    mag = [0, 0.5, 1, 1.5, 2, 3, 4, 6][n & 7]
+    return -mag if n & 8 else mag
+
+
+def test_w4_gemm_exact_rational_tiny():
+    x = synth.activations(41, 2, 64, outliers=False)
+    codes, exps = synth.mxfp4_weights(41, 3, 64)
+    y, t = oracle.gemm_w4a16(x, codes, exps, taps=True)
+    k1 = unpack_quarters(t["q1"])
+    k2 = unpack_quarters(t["q2"])
+    for m in range(2):
+        for n in range(3):
+            tot = Fraction(0)
+            for k in range(64):
+                byte = int(codes[n, k // 2])
+                w = Fraction(_e2m1((byte >> 4) if k & 1 else (byte & 15))) * Fraction(2) ** (int(exps[n, k // 32]) - 127)
+                a = Fraction(2) ** (int(t["e8m0"][m, k // 32]) - 127)
+                tot += w * (a * Fraction(int(k1[m, k]), 4) + a / 16 * Fraction(int(k2[m, k]), 4))
+            assert abs(Fraction(float(y[m, n])) - tot) <= abs(tot) * Fraction(1, 2 ** 23)
+    q1, q2, e = oracle.decompose_mxfp4(x)
+    assert np.array_equal(q1, t["q1"]) and np.array_equal(q2, t["q2"]) and np.array_equal(e, t["e8m0"])
+
+
+def test_w4_truth_matches_numpy_and_output_bound():
+    x = synth.activations(42, 4, 512)
+    codes, exps = synth.mxfp4_weights(42, 48, 512)
+    Wd = synth.dequantize_mxfp4(codes, exps).astype(np.float64)
+    truth = oracle.truth_gemm_w4(x, codes, exps)
+    assert np.allclose(truth, f32(x) @ Wd.T, rtol=1e-12, atol=1e-15)
+    y, t = oracle.gemm_w4a16(x, codes, exps, taps=True)
+    a = np.exp2(t["e8m0"].astype(np.float64) - 127)                      # [M][K/32]
+    wabs = np.abs(Wd).reshape(48, -1, 32).sum(axis=2)                     # [N][K/32]
+    bound = (a / 64) @ wabs.T
+    assert np.all(np.abs(y - truth) <= bound * (1 + 1e-6) + np.abs(truth) * 2.0 ** -23)
+
+
+def test_w4_gemm_loose_accuracy_pin():
+    # Sec. 6.5.2: N(0, 0.5) activations against MXFP4 weights: rel. L2 ~ 0.0109.
+    x = synth.activations(43, 8, 2048, outliers=False, scale=0.5)
+    codes, exps = synth.mxfp4_weights(43, 512, 2048, std=1.0)
+    truth = oracle.truth_gemm_w4(x, codes, exps)
+    y = oracle.gemm_w4a16(x, codes, exps)
+    l2 = np.linalg.norm(y - truth) / np.linalg.norm(truth)
+    g = GOLD["mxfp4_gemm"]["normal_0.5"]["rel_l2"]
+    assert abs(l2 - g) / g < 0.15
