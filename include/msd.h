@@ -1,0 +1,162 @@
+/*
+ * msd.h -- C ABI of the MI355X (gfx950) Multi-Scale Dequant library.
+ *
+ * Multi-Scale Dequant keeps quantised weights / KV caches in their storage format and
+ * instead splits every BF16 activation vector into two low-precision components with
+ * their own scales, x ~ alpha*x1 + beta*x2, so that both products run on native
+ * low-precision matrix instructions and are merged by an fp32 epilogue (paper Sec. 1.2,
+ * Sec. 3.1).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees, retains or synchronises: work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the null stream) and the call returns.
+ *   - Scratch memory comes from a caller-provided device `workspace` of at least
+ *     msd_*_workspace_bytes(...) bytes, 256-byte aligned.  Its contents are undefined
+ *     after the call.  Calls that share a workspace must be ordered on one stream.
+ *   - BF16 tensors are raw 16-bit patterns.  Inputs must be finite.
+ *   - GEMM shapes are (M, K, N): M activation rows (the paper's batch b), K the
+ *     contraction length (the paper's n), N output channels (the paper's m).  Weights
+ *     are stored [N][K] with K contiguous, so y[M][N] = X * W^T.
+ *   - Return value: MSD_OK, or a negative error code; nothing is enqueued on error
+ *     except for MSD_ERR_HIP, after which msd_last_hip_error() holds the hipError_t.
+ *   - Results are deterministic run to run (no floating-point atomics).
+ */
+#ifndef MSD_H_
+#define MSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MSD_OK = 0,
+  MSD_ERR_INVALID_ARG = -1, /* null / misaligned pointer, bad enum value */
+  MSD_ERR_SHAPE = -2,       /* unsupported or inconsistent sizes */
+  MSD_ERR_WORKSPACE = -3,   /* workspace null or too small */
+  MSD_ERR_HIP = -4,         /* a HIP call failed; see msd_last_hip_error() */
+  MSD_ERR_UNSUPPORTED = -5  /* valid request that this build has no kernel for */
+};
+
+enum { MSD_INT8 = 0, MSD_MXFP4 = 1 };             /* decomposition format */
+enum { MSD_F32 = 0, MSD_BF16 = 1 };               /* output dtype */
+enum { MSD_PER_TOKEN = 0, MSD_PER_CHANNEL = 1 };  /* KV-cache scale granularity */
+
+/*
+ * Optional observation points ("taps").  Any member may be NULL.  They exist so that the
+ * integer intermediates of the method, which must be exact, can be compared from outside.
+ *   GEMM W8A16 : q1,q2 int8 [M][K]; scale float alpha[M]; acc1,acc2 int32 [M][N]
+ *   GEMM W4A16 : q1,q2 packed 4-bit codes [M][K/2]; scale uint8 E8M0 [M][K/32]; acc* unused
+ *   attention  : q1,q2 int8 [B][Hq][d]; scale float alpha_Q [B][Hq]; acc1,acc2 int32 [B][Hq][L]
+ *                (the two integer score rows S1, S2)
+ */
+typedef struct msd_debug_taps {
+  void* q1;
+  void* q2;
+  void* scale;
+  int32_t* acc1;
+  int32_t* acc2;
+} msd_debug_taps;
+
+/* hipError_t of the most recent failing HIP call made by this library on the calling thread. */
+int msd_last_hip_error(void);
+/* "major.minor" of this library; static storage. */
+const char* msd_version(void);
+
+/*
+ * Two-pass activation decomposition of every row of x (paper Sec. 3.2, Eqs. for alpha, x1,
+ * r, beta, x2; Sec. 3.2.1 / Alg. 2 for MXFP4).
+ *   x_bf16 : [M][ldx] BF16, row m starts at x_bf16 + m*ldx; ldx >= K.
+ *   fmt = MSD_INT8 : alpha = max|x_row| / 127, x1 = clamp(rne(x/alpha)), r = x - alpha*x1
+ *       (fused multiply-add, one rounding), beta = alpha / 254, x2 = clamp(rne(r/beta));
+ *       all in IEEE fp32 with correctly rounded division and round-half-to-even.
+ *       q1,q2: int8 [M][K];  scale: float alpha[M] (beta is alpha/254).  K % 16 == 0.
+ *       An all-zero row yields alpha = 0 and zero codes.
+ *   fmt = MSD_MXFP4 : per block of 32 along K: alpha = 2^e with e the smallest integer such
+ *       that max|x_block| <= 1.859375 * 2^e (clamped to [-123, 127]), q1 = nearest point of the
+ *       uniform grid {k/4 : |k| <= 7} to x/alpha, r = x - alpha*q1 (exact), beta = alpha/16,
+ *       q2 = nearest grid point to r/beta, saturating at +-7/4; ties to even k.
+ *       q1,q2: uint8 [M][K/2], two 4-bit sign-magnitude codes per byte (bit 3 sign, bits 2..0 = k),
+ *       low nibble = even k, -0 stored as +0;  scale: uint8 [M][K/32], E8M0 byte e+127 of alpha
+ *       (beta's byte is that minus 4).  K % 32 == 0.  A zero block yields e = -123, zero codes.
+ * Errors: INVALID_ARG (null pointer, bad fmt, x not 2-byte aligned), SHAPE (M,K < 0, ldx < K,
+ * K not a multiple of 16 / 32).  M == 0 or K == 0 is a successful no-op.
+ */
+int msd_decompose(int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, void* q1,
+                  void* q2, void* scale, void* stream);
+
+/*
+ * MSD linear layer with INT8 weights (paper Alg. 1; Sec. 3.1 last equation; fused tiled
+ * realisation of Sec. 3.9):  y = s_W (.) (alpha * (x1 W^T) + beta * (x2 W^T)).
+ *   x_bf16  : [M][ldx] BF16 activations.
+ *   W       : int8 [N][K], K contiguous, 16-byte aligned;  w_scale: float [N] per output channel.
+ *   y       : [M][ldy] float (MSD_F32) or BF16 (MSD_BF16, round-to-nearest-even of the fp32 value).
+ *   Both integer products are exact int32 accumulations (|K| <= 131072 guarantees no overflow);
+ *   the merge and the weight scale are applied in fp32: y = s_W*(alpha*acc1 + beta*acc2).
+ *   taps    : nullable, see msd_debug_taps.
+ * Errors: INVALID_ARG, SHAPE (K % 16 != 0, K > 131072, ldx < K, ldy < N, negative sizes),
+ * WORKSPACE.  M == 0 or N == 0 is a successful no-op; K == 0 writes zeros.
+ */
+int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                   const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                   void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                   void* stream);
+size_t msd_gemm_w8a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * MSD linear layer with MXFP4 weights (paper Sec. 3.2.1, Alg. 2, Sec. 3.4.1): the two
+ * 4-bit activation components of every 32-block are multiplied against the MXFP4 weights
+ * with block scales on both operands and summed in one fp32 accumulator.
+ *   W_fp4  : uint8 [N][K/2], OCP E2M1 codes (bit 3 sign, bits 2..1 exponent, bit 0 mantissa),
+ *            low nibble = even k, 16-byte aligned;  W_e8m0: uint8 [N][K/32], scale 2^(byte-127).
+ *   y[m][n] = sum_blocks 2^(eW-127) * ( alpha_b * <q1_b, w_b> + beta_b * <q2_b, w_b> ), fp32.
+ * Errors as msd_gemm_w8a16, with K % 32 != 0 a SHAPE error.
+ */
+int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
+                   const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
+                   void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                   void* stream);
+size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * One decode step of attention over an INT8 KV cache without dequantising it (paper
+ * Sec. 4.2, Alg. 3; tiling of Sec. 4.3): Q and the softmax numerator P are decomposed into
+ * two INT8 components each, Q K^T and P V run as INT8 products, softmax is fp32 and online.
+ *   q_bf16 : [B][Hq][d] BF16;  K, V: int8 [B][Hkv][L][d];  query head h reads KV head h/(Hq/Hkv).
+ *   scale_mode MSD_PER_CHANNEL: k_scale, v_scale float [Hkv][d]; s_K is folded into Q before
+ *       the decomposition, s_V multiplies the output (Alg. 3 as printed), alpha_P = 1/127.
+ *   scale_mode MSD_PER_TOKEN : k_scale, v_scale float [B][Hkv][L]; s_K[t] multiplies score
+ *       column t in the merge; P_t*s_V[t] is decomposed with alpha_P = (max s_V over the KV tile)/127.
+ *   kv_len : nullable int32 [B], valid tokens per batch entry (<= L); NULL means L everywhere.
+ *   out    : [B][Hq][d] float or BF16.  Entries with kv_len == 0 produce zeros.
+ *   d must be 128 (64 and 256 are SHAPE errors in this version); Hq % Hkv == 0; Hq/Hkv <= 8.
+ */
+int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
+                           const float* k_scale, const float* v_scale, int scale_mode, int B,
+                           int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, void* out,
+                           int out_dtype, void* workspace, size_t workspace_bytes,
+                           const msd_debug_taps* taps, void* stream);
+size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
+
+/*
+ * Comparison kernels (the conventional path the paper argues against, Sec. 3.1 first
+ * equation): weights are lifted to BF16 inside the kernel (bf16(s_W*W) for INT8, exact for
+ * MXFP4) and multiplied on BF16 matrix instructions with fp32 accumulation.  Same
+ * arguments as the MSD entry points; taps are ignored.
+ */
+int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                           const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                           void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                           void* stream);
+int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                           const uint8_t* W_fp4, const uint8_t* W_e8m0, int64_t N, void* y,
+                           int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,
+                           const msd_debug_taps* taps, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSD_H_ */

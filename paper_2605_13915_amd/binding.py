@@ -1,0 +1,212 @@
+"""Thin Python binding over the C-ABI library (argument marshalling only).
+
+PyTorch provides device memory and the stream; every step of the path runs inside
+``libmsd.so``.  The functions carry the names of the C entry points declared in
+``include/msd.h``.  There is no fallback: if the library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmsd.so")
+
+MSD_INT8, MSD_MXFP4 = 0, 1
+MSD_F32, MSD_BF16 = 0, 1
+MSD_PER_TOKEN, MSD_PER_CHANNEL = 0, 1
+
+_ERR = {-1: "MSD_ERR_INVALID_ARG", -2: "MSD_ERR_SHAPE", -3: "MSD_ERR_WORKSPACE", -4: "MSD_ERR_HIP",
+        -5: "MSD_ERR_UNSUPPORTED"}
+
+
+class MsdError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, _ERR.get(code, "?"), code))
+
+
+class Taps(C.Structure):
+    _fields_ = [("q1", C.c_void_p), ("q2", C.c_void_p), ("scale", C.c_void_p),
+                ("acc1", C.c_void_p), ("acc2", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libmsd.so (built by paper_2605_13915_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library %s is missing: run `python -m paper_2605_13915_amd.build` "
+                               "(or __graft_entry__.build()) first" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        i64, vp, ci, sz = C.c_int64, C.c_void_p, C.c_int, C.c_size_t
+        L.msd_last_hip_error.restype = ci
+        L.msd_version.restype = C.c_char_p
+        L.msd_decompose.argtypes = [ci, vp, i64, i64, i64, vp, vp, vp, vp]
+        gemm8 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
+        gemm4 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
+        L.msd_gemm_w8a16.argtypes = gemm8
+        L.msd_dequant_gemm_w8a16.argtypes = gemm8
+        L.msd_gemm_w4a16.argtypes = gemm4
+        L.msd_dequant_gemm_w4a16.argtypes = gemm4
+        for f in (L.msd_gemm_w8a16_workspace_bytes, L.msd_gemm_w4a16_workspace_bytes):
+            f.argtypes = [i64, i64, i64]
+            f.restype = sz
+        L.msd_attn_decode_int8kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, i64, vp, ci, vp, sz,
+                                             vp, vp]
+        L.msd_attn_decode_int8kv_workspace_bytes.argtypes = [ci, ci, ci, ci, i64]
+        L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
+        for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
+                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise MsdError(rc, where)
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype):
+        raise TypeError("%s must be a CUDA tensor of dtype %s" % (name, dtype))
+    return t
+
+
+_ws_cache = {}
+
+
+def workspace(nbytes, device):
+    """A cached uint8 device buffer of at least nbytes (torch allocations are 256-B aligned)."""
+    key = (str(device),)
+    buf = _ws_cache.get(key)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(max(int(nbytes), 1 << 20), dtype=torch.uint8, device=device)
+        _ws_cache[key] = buf
+    return buf
+
+
+def _out_code(dtype):
+    if dtype == torch.float32:
+        return MSD_F32
+    if dtype == torch.bfloat16:
+        return MSD_BF16
+    raise TypeError("out dtype must be float32 or bfloat16")
+
+
+def msd_decompose(fmt, x):
+    """x: bf16 [M][K] (row stride may exceed K).  Returns (q1, q2, scale) device tensors."""
+    _dev(x, torch.bfloat16, "x")
+    M, K = x.shape
+    assert x.stride(1) == 1
+    if fmt == MSD_INT8:
+        q1 = torch.empty((M, K), dtype=torch.int8, device=x.device)
+        q2 = torch.empty_like(q1)
+        sc = torch.empty((M,), dtype=torch.float32, device=x.device)
+    else:
+        q1 = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+        q2 = torch.empty_like(q1)
+        sc = torch.empty((M, K // 32), dtype=torch.uint8, device=x.device)
+    rc = lib().msd_decompose(fmt, _ptr(x), M, K, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(q1),
+                             _ptr(q2), _ptr(sc), _stream())
+    _check(rc, "msd_decompose")
+    return q1, q2, sc
+
+
+def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws):
+    L = lib()
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=out_dtype, device=x.device)
+    if ws is None:
+        ws = workspace(getattr(L, ws_fn)(M, K, N), x.device)
+    tp = None
+    keep = {}
+    if taps:
+        if fn_name.endswith("w8a16"):
+            keep = dict(q1=torch.empty((M, K), dtype=torch.int8, device=x.device),
+                        q2=torch.empty((M, K), dtype=torch.int8, device=x.device),
+                        scale=torch.empty((M,), dtype=torch.float32, device=x.device),
+                        acc1=torch.empty((M, N), dtype=torch.int32, device=x.device),
+                        acc2=torch.empty((M, N), dtype=torch.int32, device=x.device))
+        else:
+            keep = dict(q1=torch.empty((M, K // 2), dtype=torch.uint8, device=x.device),
+                        q2=torch.empty((M, K // 2), dtype=torch.uint8, device=x.device),
+                        scale=torch.empty((M, K // 32), dtype=torch.uint8, device=x.device))
+        tp = Taps(keep["q1"].data_ptr(), keep["q2"].data_ptr(), keep["scale"].data_ptr(),
+                  keep["acc1"].data_ptr() if "acc1" in keep else None,
+                  keep["acc2"].data_ptr() if "acc2" in keep else None)
+    ldx = x.stride(0) if M > 1 else max(K, x.stride(0))
+    rc = getattr(L, fn_name)(_ptr(x), M, K, ldx, *w_args, N, _ptr(y), _out_code(y.dtype), y.stride(0),
+                             _ptr(ws), ws.numel(), C.byref(tp) if tp is not None else None, _stream())
+    _check(rc, fn_name)
+    return (y, keep) if taps else y
+
+
+def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, ws=None):
+    _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
+    assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
+    return _gemm_common("msd_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
+                        W.shape[0], out_dtype, taps, y, ws)
+
+
+def msd_dequant_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, y=None, ws=None):
+    _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
+    assert W.is_contiguous()
+    return _gemm_common("msd_dequant_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x,
+                        (_ptr(W), _ptr(w_scale)), W.shape[0], out_dtype, False, y, ws)
+
+
+def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None):
+    _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
+    assert W_fp4.is_contiguous() and W_e8m0.is_contiguous() and W_fp4.shape[1] * 2 == x.shape[1]
+    return _gemm_common("msd_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x, (_ptr(W_fp4), _ptr(W_e8m0)),
+                        W_fp4.shape[0], out_dtype, taps, y, ws)
+
+
+def msd_dequant_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws=None):
+    _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
+    return _gemm_common("msd_dequant_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x,
+                        (_ptr(W_fp4), _ptr(W_e8m0)), W_fp4.shape[0], out_dtype, False, y, ws)
+
+
+def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,
+                           taps=False, out=None, ws=None):
+    _dev(q, torch.bfloat16, "q"); _dev(K, torch.int8, "K"); _dev(V, torch.int8, "V")
+    _dev(k_scale, torch.float32, "k_scale"); _dev(v_scale, torch.float32, "v_scale")
+    B, Hq, d = q.shape
+    _, Hkv, Lmax, _ = K.shape
+    assert q.is_contiguous() and K.is_contiguous() and V.is_contiguous()
+    L = lib()
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=out_dtype, device=q.device)
+    if ws is None:
+        ws = workspace(L.msd_attn_decode_int8kv_workspace_bytes(B, Hq, Hkv, d, Lmax), q.device)
+    tp = None
+    keep = {}
+    if taps:
+        keep = dict(q1=torch.empty((B, Hq, d), dtype=torch.int8, device=q.device),
+                    q2=torch.empty((B, Hq, d), dtype=torch.int8, device=q.device),
+                    scale=torch.empty((B, Hq), dtype=torch.float32, device=q.device),
+                    acc1=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device),
+                    acc2=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device))
+        tp = Taps(*(keep[k].data_ptr() for k in ("q1", "q2", "scale", "acc1", "acc2")))
+    if kv_len is not None:
+        _dev(kv_len, torch.int32, "kv_len")
+    rc = L.msd_attn_decode_int8kv(_ptr(q), _ptr(K), _ptr(V), _ptr(k_scale), _ptr(v_scale), scale_mode, B, Hq,
+                                  Hkv, d, _ptr(kv_len), Lmax, _ptr(out), _out_code(out.dtype), _ptr(ws),
+                                  ws.numel(), C.byref(tp) if tp is not None else None, _stream())
+    _check(rc, "msd_attn_decode_int8kv")
+    return (out, keep) if taps else out

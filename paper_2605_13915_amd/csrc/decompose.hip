@@ -1,0 +1,269 @@
+// Activation decomposition kernels (paper Sec. 3.2 and Sec. 3.2.1 / Alg. 2) for gfx950.
+//
+// INT8:   one workgroup per activation row: 16-byte loads, wave/LDS max-reduction for
+//         ||x||_inf, then both quantisation passes from registers; each thread writes 16
+//         codes per 16-byte store.  HBM/L2-bound: 2 B in, 2 B out per element.
+// MXFP4:  one thread per 32-element block (no cross-lane reduction: the block max is the
+//         only reduction and beta needs none).  Writes the ABI format (4-bit codes) and/or
+//         the GEMM's internal operand format (FP6-E2M3 codes, 24 B per block in a 32 B slot).
+#include "kernels.hpp"
+
+namespace msd {
+
+// ---------------------------------------------------------------- INT8
+constexpr int kDecThreads = 256;
+constexpr int kDecRegChunks = 4;  // 16-element chunks cached in registers per thread
+
+struct Chunk16 {
+  uint32_t w[8];  // 16 BF16 values
+};
+
+__device__ __forceinline__ Chunk16 load_chunk16(const uint16_t* p, bool aligned) {
+  Chunk16 c;
+  if (aligned) {
+    const uint4* q = reinterpret_cast<const uint4*>(p);
+    uint4 a = q[0], b = q[1];
+    c.w[0] = a.x; c.w[1] = a.y; c.w[2] = a.z; c.w[3] = a.w;
+    c.w[4] = b.x; c.w[5] = b.y; c.w[6] = b.z; c.w[7] = b.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) c.w[i] = (uint32_t)p[2 * i] | ((uint32_t)p[2 * i + 1] << 16);
+  }
+  return c;
+}
+
+__device__ __forceinline__ float chunk_absmax(const Chunk16& c) {
+  float m = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    m = fmaxf(m, fabsf(__uint_as_float(c.w[i] << 16)));
+    m = fmaxf(m, fabsf(__uint_as_float(c.w[i] & 0xFFFF0000u)));
+  }
+  return m;
+}
+
+__device__ __forceinline__ void chunk_codes(const Chunk16& c, float alpha, float beta, uint4& o1,
+                                            uint4& o2) {
+  uint32_t a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    uint32_t pa = 0, pb = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = c.w[j * 2 + (e >> 1)];
+      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+      int c1, c2;
+      int8_codes(x, alpha, beta, c1, c2);
+      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
+      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
+    }
+    a[j] = pa;
+    b[j] = pb;
+  }
+  o1 = make_uint4(a[0], a[1], a[2], a[3]);
+  o2 = make_uint4(b[0], b[1], b[2], b[3]);
+}
+
+__global__ __launch_bounds__(kDecThreads) void decompose_int8_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int K, int8_t* __restrict__ q1,
+    int8_t* __restrict__ q2, int64_t ldq, float* __restrict__ alpha_out, int aligned) {
+  __shared__ float s_red[kDecThreads / kWave];
+  const int64_t m = blockIdx.x;
+  const uint16_t* xr = x + m * ldx;
+  const int nchunks = K / 16;
+  Chunk16 cache[kDecRegChunks];
+  float mx = 0.f;
+#pragma unroll
+  for (int i = 0; i < kDecRegChunks; ++i) {
+    const int c = threadIdx.x + i * kDecThreads;
+    if (c < nchunks) {
+      cache[i] = load_chunk16(xr + c * 16, aligned);
+      mx = fmaxf(mx, chunk_absmax(cache[i]));
+    }
+  }
+  for (int c = threadIdx.x + kDecRegChunks * kDecThreads; c < nchunks; c += kDecThreads)
+    mx = fmaxf(mx, chunk_absmax(load_chunk16(xr + c * 16, aligned)));
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  const float alpha = __fdiv_rn(mx, 127.0f);
+  const float beta = __fdiv_rn(alpha, 254.0f);
+  if (threadIdx.x == 0) alpha_out[m] = alpha;
+  uint4* o1 = reinterpret_cast<uint4*>(q1 + m * ldq);
+  uint4* o2 = reinterpret_cast<uint4*>(q2 + m * ldq);
+  if (mx == 0.f) {  // all-zero row: zero codes, zero scales
+    for (int c = threadIdx.x; c < nchunks; c += kDecThreads) {
+      o1[c] = make_uint4(0, 0, 0, 0);
+      o2[c] = make_uint4(0, 0, 0, 0);
+    }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < kDecRegChunks; ++i) {
+    const int c = threadIdx.x + i * kDecThreads;
+    if (c < nchunks) {
+      uint4 a, b;
+      chunk_codes(cache[i], alpha, beta, a, b);
+      o1[c] = a;
+      o2[c] = b;
+    }
+  }
+  for (int c = threadIdx.x + kDecRegChunks * kDecThreads; c < nchunks; c += kDecThreads) {
+    uint4 a, b;
+    chunk_codes(load_chunk16(xr + c * 16, aligned), alpha, beta, a, b);
+    o1[c] = a;
+    o2[c] = b;
+  }
+}
+
+int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
+                          int8_t* q2, int64_t ldq, float* alpha, hipStream_t stream) {
+  if (M == 0 || K == 0) return MSD_OK;
+  const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(decompose_int8_kernel, dim3((unsigned)M), dim3(kDecThreads), 0, stream, x, ldx,
+                     (int)K, q1, q2, ldq, alpha, aligned);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+// ---------------------------------------------------------------- MXFP4
+// Exponent e of alpha = 2^e for a block with max-abs mb: smallest e with mb <= 1.859375 * 2^e,
+// read off the fp32 fields (1.859375 has mantissa field 0x6E0000); clamped to [-123, 127].
+__device__ __forceinline__ int mx_alpha_exponent(float mb) {
+  const uint32_t u = __float_as_uint(mb);
+  int e = (int)(u >> 23) - 127;
+  if ((u & 0x7FFFFFu) > 0x6E0000u) e += 1;
+  return min(max(e, -123), 127);
+}
+
+__device__ __forceinline__ float pow2f(int e) {  // e in [-126, 127]
+  return __uint_as_float((uint32_t)(e + 127) << 23);
+}
+
+// 32 BF16 values of one block -> integer grid codes k1, k2 (value k/4) and exponent e.
+__device__ __forceinline__ int mx_block_codes(const uint32_t (&w)[16], int (&k1)[32], int (&k2)[32]) {
+  float mb = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    mb = fmaxf(mb, fabsf(__uint_as_float(w[i] << 16)));
+    mb = fmaxf(mb, fabsf(__uint_as_float(w[i] & 0xFFFF0000u)));
+  }
+  const int e = mx_alpha_exponent(mb);
+  const float up = pow2f(2 - e);    // 4/alpha
+  const float down = pow2f(e - 2);  // alpha/4
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const float x = (i & 1) ? __uint_as_float(w[i >> 1] & 0xFFFF0000u) : __uint_as_float(w[i >> 1] << 16);
+    const float a = fminf(fmaxf(rintf(x * up), -7.f), 7.f);
+    const float r = __fmaf_rn(-a, down, x);  // exact
+    const float b = fminf(fmaxf(rintf(r * up * 16.0f), -7.f), 7.f);
+    k1[i] = (int)a;
+    k2[i] = (int)b;
+  }
+  return e;
+}
+
+__device__ __forceinline__ uint32_t nibble4(int k) {  // sign-magnitude, -0 -> +0
+  return k < 0 ? (8u | (uint32_t)(-k)) : (uint32_t)k;
+}
+__device__ __forceinline__ uint32_t e2m3_code(int k) {  // value k/4 as FP6 E2M3: magnitude field 2|k|
+  return k < 0 ? (32u | (uint32_t)(-2 * k)) : (uint32_t)(2 * k);
+}
+
+// Pack 32 six-bit codes into 6 dwords, element i at bits [6i, 6i+6).
+__device__ __forceinline__ void pack_fp6(const int (&k)[32], uint32_t (&out)[6]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {  // 16 codes -> 96 bits -> 3 dwords
+    uint64_t lo = 0;             // bits 0..63
+    uint32_t hi = 0;             // bits 64..95
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint64_t c = e2m3_code(k[h * 16 + i]);
+      const int bit = 6 * i;
+      if (bit + 6 <= 64) {
+        lo |= c << bit;
+      } else if (bit >= 64) {
+        hi |= (uint32_t)c << (bit - 64);
+      } else {  // straddles bit 64 (i = 10: bits 60..65)
+        lo |= c << bit;
+        hi |= (uint32_t)(c >> (64 - bit));
+      }
+    }
+    out[h * 3 + 0] = (uint32_t)lo;
+    out[h * 3 + 1] = (uint32_t)(lo >> 32);
+    out[h * 3 + 2] = hi;
+  }
+}
+
+// abi_q1/abi_q2/abi_e8m0: ABI outputs (nullable).  op_q1/op_q2: FP6 operand slots, 32 B per
+// block ([M][K/32][32 B], first 24 B used), op_e8m0: alpha bytes [M][K/32] (nullable group).
+__global__ __launch_bounds__(256) void decompose_mxfp4_kernel(
+    const uint16_t* __restrict__ x, int64_t ldx, int64_t M, int KB, uint8_t* __restrict__ abi_q1,
+    uint8_t* __restrict__ abi_q2, uint8_t* __restrict__ abi_e8m0, uint32_t* __restrict__ op_q1,
+    uint32_t* __restrict__ op_q2, uint8_t* __restrict__ op_e8m0, int aligned) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= M * KB) return;
+  const int64_t m = gid / KB;
+  const int b = (int)(gid % KB);
+  const uint16_t* xb = x + m * ldx + (int64_t)b * 32;
+  uint32_t w[16];
+  if (aligned) {
+    const uint4* q = reinterpret_cast<const uint4*>(xb);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4 v = q[i];
+      w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
+  }
+  int k1[32], k2[32];
+  const int e = mx_block_codes(w, k1, k2);
+  const uint8_t ebyte = (uint8_t)(e + 127);
+  if (abi_q1) {
+    uint32_t a[4], c[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t pa = 0, pc = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pa |= nibble4(k1[j * 8 + i]) << (4 * i);
+        pc |= nibble4(k2[j * 8 + i]) << (4 * i);
+      }
+      a[j] = pa;
+      c[j] = pc;
+    }
+    reinterpret_cast<uint4*>(abi_q1 + (m * KB + b) * 16)[0] = make_uint4(a[0], a[1], a[2], a[3]);
+    reinterpret_cast<uint4*>(abi_q2 + (m * KB + b) * 16)[0] = make_uint4(c[0], c[1], c[2], c[3]);
+    abi_e8m0[m * KB + b] = ebyte;
+  }
+  if (op_q1) {
+    uint32_t p[6];
+    pack_fp6(k1, p);
+    uint32_t* d1 = op_q1 + (m * KB + b) * 8;
+    reinterpret_cast<uint4*>(d1)[0] = make_uint4(p[0], p[1], p[2], p[3]);
+    reinterpret_cast<uint2*>(d1)[2] = make_uint2(p[4], p[5]);
+    pack_fp6(k2, p);
+    uint32_t* d2 = op_q2 + (m * KB + b) * 8;
+    reinterpret_cast<uint4*>(d2)[0] = make_uint4(p[0], p[1], p[2], p[3]);
+    reinterpret_cast<uint2*>(d2)[2] = make_uint2(p[4], p[5]);
+    op_e8m0[m * KB + b] = ebyte;
+  }
+}
+
+int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
+                           uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
+                           uint8_t* op_e8m0, hipStream_t stream) {
+  if (M == 0 || K == 0) return MSD_OK;
+  const int KB = (int)(K / 32);
+  const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
+  const int64_t total = M * KB;
+  hipLaunchKernelGGL(decompose_mxfp4_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, stream,
+                     x, ldx, M, KB, abi_q1, abi_q2, abi_e8m0, op_q1, op_q2, op_e8m0, aligned);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+}  // namespace msd

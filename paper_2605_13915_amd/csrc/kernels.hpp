@@ -1,0 +1,78 @@
+// Internal launcher declarations of the gfx950 MSD library.
+#pragma once
+#include "msd_common.hpp"
+
+namespace msd {
+
+// ---- decomposition (decompose.hip)
+int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
+                          int8_t* q2, int64_t ldq, float* alpha, hipStream_t stream);
+int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
+                           uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
+                           uint8_t* op_e8m0, hipStream_t stream);
+
+// ---- W8A16 dual INT8 GEMM + dual-scale epilogue (gemm_w8.hip)
+struct GemmW8Args {
+  const int8_t* q1;  // [M][ldq] first component codes
+  const int8_t* q2;  // [M][ldq] residual component codes
+  int64_t ldq;
+  const float* alpha;  // [M]
+  const int8_t* W;     // [N][K]
+  const float* w_scale;
+  void* y;
+  int out_bf16;
+  int64_t ldy;
+  int32_t* acc1;  // nullable taps [M][N]
+  int32_t* acc2;
+  int64_t M, K, N;
+  // split-K scratch (nullable when unused): int32 partial sums [2][M][N] and tile counters
+  int32_t* part;
+  uint32_t* counters;
+};
+int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);
+// scratch the GEMM wants beyond q1/q2/alpha: bytes of split-K partials and counters
+void gemm_w8_scratch(int64_t M, int64_t K, int64_t N, size_t* part_bytes, size_t* counter_bytes);
+
+// ---- W4A16 (gemm_w4.hip)
+struct GemmW4Args {
+  const uint32_t* q1;  // FP6 operand slots [M][K/32][8 dwords]
+  const uint32_t* q2;
+  const uint8_t* e8m0;  // alpha bytes [M][K/32]
+  const uint8_t* W;     // [N][K/2]
+  const uint8_t* We;    // [N][K/32]
+  void* y;
+  int out_bf16;
+  int64_t ldy;
+  int64_t M, K, N;
+};
+int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
+
+// ---- attention (attn.hip)
+struct AttnArgs {
+  const uint16_t* q;
+  const int8_t* K;
+  const int8_t* V;
+  const float* k_scale;
+  const float* v_scale;
+  int scale_mode;
+  int B, Hq, Hkv, d;
+  const int32_t* kv_len;
+  int64_t L;
+  void* out;
+  int out_bf16;
+  void* workspace;
+  size_t workspace_bytes;
+  const msd_debug_taps* taps;
+};
+int launch_attn_decode(const AttnArgs& a, hipStream_t stream);
+size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
+
+// ---- comparison kernels (dequant_gemm.hip)
+int launch_dequant_gemm_w8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                           const float* w_scale, int64_t N, void* y, int out_bf16, int64_t ldy,
+                           hipStream_t stream);
+int launch_dequant_gemm_w4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const uint8_t* W,
+                           const uint8_t* We, int64_t N, void* y, int out_bf16, int64_t ldy,
+                           hipStream_t stream);
+
+}  // namespace msd

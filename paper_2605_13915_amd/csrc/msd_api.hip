@@ -1,0 +1,244 @@
+// C-ABI entry points: argument validation, workspace carving, kernel dispatch.
+#include "kernels.hpp"
+
+namespace msd {
+thread_local int g_last_hip_error = 0;
+
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+static int fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s) {
+  if (n == 0) return MSD_OK;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, s, p, n, v);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+static bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// workspace layout of msd_gemm_w8a16
+struct W8Layout {
+  size_t q1, q2, alpha, part, counters, total;
+  size_t part_bytes, counter_bytes;
+};
+static W8Layout w8_layout(int64_t M, int64_t K, int64_t N) {
+  W8Layout l{};
+  size_t off = 0;
+  l.q1 = off; off = align_up(off + (size_t)M * K, 256);
+  l.q2 = off; off = align_up(off + (size_t)M * K, 256);
+  l.alpha = off; off = align_up(off + (size_t)M * sizeof(float), 256);
+  gemm_w8_scratch(M, K, N, &l.part_bytes, &l.counter_bytes);
+  l.part = off; off = align_up(off + l.part_bytes, 256);
+  l.counters = off; off = align_up(off + l.counter_bytes, 256);
+  l.total = off;
+  return l;
+}
+
+// workspace layout of msd_gemm_w4a16
+struct W4Layout {
+  size_t q1, q2, e8m0, abi_q1, abi_q2, abi_e, total;
+};
+static W4Layout w4_layout(int64_t M, int64_t K, int64_t /*N*/) {
+  W4Layout l{};
+  const size_t KB = (size_t)K / 32;
+  size_t off = 0;
+  l.q1 = off; off = align_up(off + (size_t)M * KB * 32, 256);
+  l.q2 = off; off = align_up(off + (size_t)M * KB * 32, 256);
+  l.e8m0 = off; off = align_up(off + (size_t)M * KB, 256);
+  l.total = off;
+  return l;
+}
+}  // namespace msd
+
+using namespace msd;
+
+extern "C" {
+
+int msd_last_hip_error(void) { return g_last_hip_error; }
+const char* msd_version(void) { return "0.1"; }
+
+int msd_decompose(int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, void* q1, void* q2,
+                  void* scale, void* stream) {
+  if (fmt != MSD_INT8 && fmt != MSD_MXFP4) return MSD_ERR_INVALID_ARG;
+  if (M < 0 || K < 0 || ldx < K) return MSD_ERR_SHAPE;
+  if (M == 0 || K == 0) return MSD_OK;
+  if (!x_bf16 || !q1 || !q2 || !scale) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(x_bf16, 2) || !aligned_to(q1, 16) || !aligned_to(q2, 16)) return MSD_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  if (fmt == MSD_INT8) {
+    if (K % 16 != 0) return MSD_ERR_SHAPE;
+    if (!aligned_to(scale, 4)) return MSD_ERR_INVALID_ARG;
+    return launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)q1, (int8_t*)q2, K,
+                                 (float*)scale, s);
+  }
+  if (K % 32 != 0) return MSD_ERR_SHAPE;
+  return launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, (uint8_t*)q1, (uint8_t*)q2,
+                                (uint8_t*)scale, nullptr, nullptr, nullptr, s);
+}
+
+size_t msd_gemm_w8a16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+  if (M <= 0 || K < 0 || N <= 0) return 256;
+  return w8_layout(M, K, N).total + 256;
+}
+
+int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                   const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                   size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (K % 16 != 0 || K > 131072) return MSD_ERR_SHAPE;
+  if (M == 0 || N == 0) return MSD_OK;
+  if (!y || !w_scale || (K > 0 && (!x_bf16 || !W))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W, 16) || !aligned_to(x_bf16, 2) || !aligned_to(w_scale, 4) ||
+      !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
+    return MSD_ERR_INVALID_ARG;
+  const W8Layout l = w8_layout(M, K, N);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  GemmW8Args a{};
+  a.q1 = (int8_t*)(ws + l.q1);
+  a.q2 = (int8_t*)(ws + l.q2);
+  a.ldq = K;
+  a.alpha = (float*)(ws + l.alpha);
+  a.W = W;
+  a.w_scale = w_scale;
+  a.y = y;
+  a.out_bf16 = out_dtype == MSD_BF16;
+  a.ldy = ldy;
+  a.M = M; a.K = K; a.N = N;
+  a.acc1 = taps ? taps->acc1 : nullptr;
+  a.acc2 = taps ? taps->acc2 : nullptr;
+  a.part = l.part_bytes ? (int32_t*)(ws + l.part) : nullptr;
+  a.counters = l.counter_bytes ? (uint32_t*)(ws + l.counters) : nullptr;
+  if (K > 0) {
+    int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
+                                   (float*)a.alpha, s);
+    if (rc) return rc;
+  } else {
+    int rc = fill_u32((uint32_t*)a.alpha, M, 0u, s);
+    if (rc) return rc;
+  }
+  if (l.counter_bytes) {
+    int rc = fill_u32(a.counters, (int64_t)(l.counter_bytes / 4), 0u, s);
+    if (rc) return rc;
+  }
+  int rc = launch_gemm_w8(a, s);
+  if (rc) return rc;
+  if (taps && K > 0) {
+    if (taps->q1) MSD_HIP_CHECK(hipMemcpyAsync(taps->q1, a.q1, (size_t)M * K, hipMemcpyDeviceToDevice, s));
+    if (taps->q2) MSD_HIP_CHECK(hipMemcpyAsync(taps->q2, a.q2, (size_t)M * K, hipMemcpyDeviceToDevice, s));
+    if (taps->scale)
+      MSD_HIP_CHECK(hipMemcpyAsync(taps->scale, a.alpha, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
+  }
+  return MSD_OK;
+}
+
+size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+  if (M <= 0 || K <= 0 || N <= 0) return 256;
+  return w4_layout(M, K, N).total + 256;
+}
+
+int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
+                   const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                   size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (K % 32 != 0 || K > (1 << 20)) return MSD_ERR_SHAPE;
+  if (M == 0 || N == 0) return MSD_OK;
+  if (!y || (K > 0 && (!x_bf16 || !W_fp4 || !W_e8m0))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W_fp4, 16) || !aligned_to(x_bf16, 2) || !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
+    return MSD_ERR_INVALID_ARG;
+  const W4Layout l = w4_layout(M, K, N);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  GemmW4Args a{};
+  a.q1 = (uint32_t*)(ws + l.q1);
+  a.q2 = (uint32_t*)(ws + l.q2);
+  a.e8m0 = (uint8_t*)(ws + l.e8m0);
+  a.W = W_fp4;
+  a.We = W_e8m0;
+  a.y = y;
+  a.out_bf16 = out_dtype == MSD_BF16;
+  a.ldy = ldy;
+  a.M = M; a.K = K; a.N = N;
+  if (K > 0) {
+    uint8_t* t1 = taps ? (uint8_t*)taps->q1 : nullptr;
+    uint8_t* t2 = taps ? (uint8_t*)taps->q2 : nullptr;
+    uint8_t* te = taps ? (uint8_t*)taps->scale : nullptr;
+    if (!(t1 && t2 && te)) t1 = t2 = te = nullptr;  // the ABI-format taps come as a set
+    if (t1 && (!aligned_to(t1, 16) || !aligned_to(t2, 16))) return MSD_ERR_INVALID_ARG;
+    int rc = launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, t1, t2, te, (uint32_t*)a.q1,
+                                    (uint32_t*)a.q2, (uint8_t*)a.e8m0, s);
+    if (rc) return rc;
+  }
+  return launch_gemm_w4(a, s);
+}
+
+size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L) {
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || L < 0) return 256;
+  return attn_workspace_bytes(B, Hq, Hkv, d, L) + 256;
+}
+
+int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
+                           const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
+                           const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                           size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (scale_mode != MSD_PER_TOKEN && scale_mode != MSD_PER_CHANNEL) return MSD_ERR_INVALID_ARG;
+  if (B < 0 || Hq <= 0 || Hkv <= 0 || L < 0) return MSD_ERR_SHAPE;
+  if (d != 128 || Hq % Hkv != 0 || Hq / Hkv > 8 || L > (1 << 24)) return MSD_ERR_SHAPE;
+  if (B == 0) return MSD_OK;
+  if (!q_bf16 || !out || (L > 0 && (!K || !V || !k_scale || !v_scale))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(K, 16) || !aligned_to(V, 16) || !aligned_to(q_bf16, 16) || !aligned_to(out, 16))
+    return MSD_ERR_INVALID_ARG;
+  const size_t need = attn_workspace_bytes(B, Hq, Hkv, d, L);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < need) return MSD_ERR_WORKSPACE;
+  AttnArgs a{};
+  a.q = (const uint16_t*)q_bf16;
+  a.K = K; a.V = V;
+  a.k_scale = k_scale; a.v_scale = v_scale;
+  a.scale_mode = scale_mode;
+  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.d = d;
+  a.kv_len = kv_len;
+  a.L = L;
+  a.out = out;
+  a.out_bf16 = out_dtype == MSD_BF16;
+  a.workspace = workspace;
+  a.workspace_bytes = workspace_bytes;
+  a.taps = taps;
+  return launch_attn_decode(a, (hipStream_t)stream);
+}
+
+int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                           const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                           void* /*workspace*/, size_t /*workspace_bytes*/, const msd_debug_taps* /*taps*/,
+                           void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (K % 16 != 0) return MSD_ERR_SHAPE;
+  if (M == 0 || N == 0) return MSD_OK;
+  if (!y || !w_scale || (K > 0 && (!x_bf16 || !W))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W, 16) || !aligned_to(x_bf16, 16) || ldx % 8 != 0) return MSD_ERR_INVALID_ARG;
+  return launch_dequant_gemm_w8((const uint16_t*)x_bf16, M, K, ldx, W, w_scale, N, y,
+                                out_dtype == MSD_BF16, ldy, (hipStream_t)stream);
+}
+
+int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
+                           const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
+                           void* /*workspace*/, size_t /*workspace_bytes*/, const msd_debug_taps* /*taps*/,
+                           void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (K % 32 != 0) return MSD_ERR_SHAPE;
+  if (M == 0 || N == 0) return MSD_OK;
+  if (!y || (K > 0 && (!x_bf16 || !W_fp4 || !W_e8m0))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W_fp4, 16) || !aligned_to(x_bf16, 16) || ldx % 8 != 0) return MSD_ERR_INVALID_ARG;
+  return launch_dequant_gemm_w4((const uint16_t*)x_bf16, M, K, ldx, W_fp4, W_e8m0, N, y,
+                                out_dtype == MSD_BF16, ldy, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Shared device/host helpers of the gfx950 MSD library (not shared with the CPU oracle).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "msd.h"
+
+namespace msd {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int kWave = 64;
+
+// error bookkeeping (host)
+extern thread_local int g_last_hip_error;
+inline int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return MSD_ERR_HIP;
+}
+#define MSD_HIP_CHECK(expr)                          \
+  do {                                               \
+    hipError_t e__ = (expr);                         \
+    if (e__ != hipSuccess) return msd::hip_fail(e__); \
+  } while (0)
+#define MSD_LAUNCH_CHECK() MSD_HIP_CHECK(hipGetLastError())
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- device helpers ------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// fp32 -> BF16 bits, round-to-nearest-even (finite inputs)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// One step of the two-pass INT8 decomposition (paper Sec. 3.2): given alpha, beta (already
+// rounded fp32 quotients) produce the two codes of x.  Correctly rounded division,
+// round-half-to-even, fused residual.
+__device__ __forceinline__ void int8_codes(float x, float alpha, float beta, int& c1, int& c2) {
+  float t = __fdiv_rn(x, alpha);
+  float q = fminf(fmaxf(rintf(t), -128.f), 127.f);
+  float r = __fmaf_rn(-alpha, q, x);
+  float u = __fdiv_rn(r, beta);
+  float p = fminf(fmaxf(rintf(u), -128.f), 127.f);
+  c1 = (int)q;
+  c2 = (int)p;
+}
+
+}  // namespace msd

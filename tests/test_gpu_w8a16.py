@@ -1,0 +1,118 @@
+"""GPU parity: msd_decompose (INT8) and msd_gemm_w8a16 against the CPU oracle, through the C ABI.
+
+Bar: INT8 codes, alpha bits and both int32 partial products bit-exact; fp32 output within
+relative L2 1e-3 of the oracle (the stated bar) and, tighter, 1e-6 (the epilogue differs from
+the oracle's fp64 merge only by a handful of fp32 roundings); Theorem-1 output bound against
+the fp64 truth."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13915_amd import synth
+from gpu_util import bf16_to_dev, to_dev, rel_l2, bf16_dev_to_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def msd():
+    from paper_2605_13915_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("M,K", [(1, 4096), (16, 1024), (5, 48), (3, 16400), (33, 8192), (7, 70000)])
+def test_decompose_int8_bit_exact(msd, M, K):
+    K = K - K % 16
+    x = synth.activations(synth.seed_for(0, M), M, K, outliers=K >= 1024)
+    x[M // 2, :] = 0 if M > 2 else x[M // 2, :]          # an all-zero row
+    q1, q2, al, be = oracle.decompose_int8(x)
+    d1, d2, da = msd.msd_decompose(msd.MSD_INT8, bf16_to_dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(d1.cpu().numpy(), q1)
+    assert np.array_equal(d2.cpu().numpy(), q2)
+    assert np.array_equal(da.cpu().numpy().view(np.uint32), al.view(np.uint32))
+
+
+def test_decompose_strided_rows(msd):
+    x = synth.activations(3, 6, 512)
+    big = torch.zeros((6, 520), dtype=torch.bfloat16, device="cuda")
+    big[:, :512] = bf16_to_dev(x)
+    d1, d2, da = msd.msd_decompose(msd.MSD_INT8, big[:, :512])      # ldx = 520 (16-byte aligned rows)
+    odd = torch.zeros((6, 515), dtype=torch.bfloat16, device="cuda")
+    odd[:, :512] = bf16_to_dev(x)
+    e1, e2, ea = msd.msd_decompose(msd.MSD_INT8, odd[:, :512])      # ldx = 515: unaligned path
+    q1, q2, al, _ = oracle.decompose_int8(x)
+    for a, b in ((d1, q1), (d2, q2), (e1, q1), (e2, q2)):
+        assert np.array_equal(a.cpu().numpy(), b)
+    assert np.array_equal(da.cpu().numpy(), al) and np.array_equal(ea.cpu().numpy(), al)
+
+
+SHAPES = [
+    (16, 1024, 1024, 0),       # config 0
+    (1, 4096, 4096, 1), (8, 4096, 4096, 1),   # decode, skinny kernel
+    (32, 4096, 4096, 1),       # decode, split-K tiled kernel
+    (3, 208, 50, 0),           # ragged everything, K not a multiple of 64
+    (40, 1040, 200, 1),        # ragged tiled, several M tiles
+    (130, 512, 300, 1),        # larger-tile kernel with ragged tails
+    (128, 4096, 1024, 1),
+]
+
+
+@pytest.mark.parametrize("M,K,N,outl", SHAPES)
+def test_gemm_w8a16_parity(msd, M, K, N, outl):
+    seed = synth.seed_for(1, M * 7 + N)
+    x = synth.activations(seed, M, K, outliers=bool(outl))
+    W, s = synth.int8_weights(seed, N, K)
+    y_ref, t = oracle.gemm_w8a16(x, W, s, taps=True)
+    y, g = msd.msd_gemm_w8a16(bf16_to_dev(x), to_dev(W), to_dev(s), taps=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(g["q1"].cpu().numpy(), t["q1"])
+    assert np.array_equal(g["q2"].cpu().numpy(), t["q2"])
+    assert np.array_equal(g["scale"].cpu().numpy().view(np.uint32), t["alpha"].view(np.uint32))
+    assert np.array_equal(g["acc1"].cpu().numpy(), t["acc1"])
+    assert np.array_equal(g["acc2"].cpu().numpy(), t["acc2"])
+    yh = y.cpu().numpy()
+    assert rel_l2(yh, y_ref) <= 1e-3
+    assert rel_l2(yh, y_ref) <= 1e-6
+    # accuracy bound against the fp64 truth (Theorem 1 pushed through the dot product)
+    truth = oracle.truth_gemm_w8(x, W, s)
+    xf = synth.bf16_bits_to_f32(x).astype(np.float64)
+    bound = s.astype(np.float64)[None] * np.abs(W.astype(np.float64)).sum(1)[None] * np.abs(xf).max(1)[:, None] / 64516.0
+    assert np.all(np.abs(yh - truth) <= bound * (1 + 1e-4) + np.abs(truth) * 2.0 ** -21 + 1e-30)
+
+
+def test_gemm_w8a16_bf16_output_and_determinism(msd):
+    M, K, N = 8, 1024, 512
+    x = synth.activations(77, M, K)
+    W, s = synth.int8_weights(77, N, K)
+    ref = oracle.gemm_w8a16(x, W, s, out_bf16=True)
+    xd, Wd, sd = bf16_to_dev(x), to_dev(W), to_dev(s)
+    y = msd.msd_gemm_w8a16(xd, Wd, sd, out_dtype=torch.bfloat16)
+    y2 = msd.msd_gemm_w8a16(xd, Wd, sd, out_dtype=torch.bfloat16)
+    bits = bf16_dev_to_bits(y)
+    assert np.array_equal(bits, bf16_dev_to_bits(y2))
+    a = synth.bf16_bits_to_f32(bits)
+    b = synth.bf16_bits_to_f32(ref)
+    assert rel_l2(a, b) <= 1e-3
+    # BF16 rounding of nearly equal fp32 values: at most one ulp apart, and only rarely
+    assert np.mean(bits != ref) < 0.01
+
+
+def test_gemm_w8a16_error_codes(msd):
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((8, 64), dtype=torch.int8, device="cuda")
+    s = torch.ones(8, device="cuda")
+    tiny = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_gemm_w8a16(x, W, s, ws=tiny)
+    assert e.value.code == -3
+    x2 = torch.zeros((4, 24), dtype=torch.bfloat16, device="cuda")
+    W2 = torch.zeros((8, 24), dtype=torch.int8, device="cuda")
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_gemm_w8a16(x2, W2, s)
+    assert e.value.code == -2
+    # empty problems are successful no-ops
+    y = msd.msd_gemm_w8a16(x[:0], W, s)
+    assert y.shape == (0, 8)
