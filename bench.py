@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the MSD hot path on one MI355X.
+
+Headline workload (``config.workload``): the W8A16 decode shapes, M in {1,8,32,128}, K=4096,
+N in {4096,14336}.  One step = the whole hot path (decomposition, dual INT8 GEMM, dual-scale
+epilogue) once for each of the eight shapes.  Weights are replicated so that the working set a
+step cycles through exceeds twice the 256 MB last-level cache: every weight byte comes from HBM.
+Inputs are resident in HBM before the timed region.  ``value`` is algorithmic bytes per second.
+
+Prints ONE JSON line (rank 0).  ``--gpus`` above 1 is refused: this build is single-GPU.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+INT8_PEAK_TOPS = 5000.0
+FP4_PEAK_TFLOPS = 10100.0
+BF16_PEAK_TFLOPS = 2500.0
+LLC_BYTES = 256 << 20
+
+
+def w8_bytes(M, K, N):
+    """Algorithmic HBM bytes of one W8A16 call: W once, BF16 x, s_W, fp32 y."""
+    return K * N + 2 * M * K + 4 * N + 4 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", default="all", help="comma list of extra legs: prefill,w4,attn,cmp | all | none")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_13915_amd import binding as msd, synth
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    msd.lib()
+    stream = torch.cuda.current_stream()
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    K = 4096
+    Ms = [1, 8, 32, 128]
+    Ns = [4096, 14336]
+    # ---- inputs, resident in HBM
+    acts = {}
+    for i, M in enumerate(Ms):
+        acts[M] = dev_bf16(synth.activations(synth.seed_for(1, i), M, K, outliers=True))
+    weights = {}
+    for j, N in enumerate(Ns):
+        W, s = synth.int8_weights(synth.seed_for(1, 10 + j), N, K)
+        copies = max(2, -(-2 * LLC_BYTES // (N * K)) + 1)
+        Wd = torch.from_numpy(W).to(dev)
+        reps = [Wd] + [Wd.clone() for _ in range(copies - 1)]
+        weights[N] = (reps, torch.from_numpy(s).to(dev))
+    outs = {(M, N): torch.empty((M, N), dtype=torch.float32, device=dev) for M in Ms for N in Ns}
+    ws_bytes = max(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N) for M in Ms for N in Ns)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    shapes = [(M, N) for N in Ns for M in Ms]
+    step_bytes = sum(w8_bytes(M, K, N) for M, N in shapes)
+
+    def run_step(i):
+        for (M, N) in shapes:
+            reps, s = weights[N]
+            msd.msd_gemm_w8a16(acts[M], reps[i % len(reps)], s, y=outs[(M, N)], ws=ws)
+
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run_step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-shape device time with HIP events on the launch stream (bursts of cold-cache calls)
+    def time_calls(fn, n_calls):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(n_calls):
+            fn(i)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n_calls  # us per call
+
+    per_shape = []
+    for (M, N) in shapes:
+        reps, s = weights[N]
+        n_calls = 4 * len(reps)
+
+        def call(i, M=M, N=N, reps=reps, s=s):
+            msd.msd_gemm_w8a16(acts[M], reps[i % len(reps)], s, y=outs[(M, N)], ws=ws)
+
+        call(0)
+        us = time_calls(call, n_calls)
+        b = w8_bytes(M, K, N)
+        per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2),
+                          "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
+                          "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2)})
+    dom = max(per_shape, key=lambda r: r["us_per_call"])
+    roofline = {"bound": "hbm", "kernel": "msd_gemm_w8a16 M=%d K=%d N=%d (decompose + GEMM + epilogue per call)" %
+                (dom["M"], dom["K"], dom["N"]),
+                "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4), "traffic": None}
+
+    extras = {}
+    want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
+        {"prefill", "w4", "attn", "cmp"} if args.extras == "all" else set())
+    try:
+        import bench_extras
+        extras = bench_extras.run(want, msd, synth, time_calls, dev)
+    except ImportError:
+        extras = {}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = [(1, 4096), (8, 4096), (32, 4096)]
+        W, s = synth.int8_weights(synth.seed_for(1, 10), 4096, K)
+        xs = [synth.activations(synth.seed_for(1, i), M, K, outliers=True) for i, (M, _) in enumerate(sample)]
+        oracle.gemm_w8a16(xs[0], W[:64], s[:64])  # load the library outside the timed region
+        c0 = time.perf_counter()
+        for x, (M, N) in zip(xs, sample):
+            oracle.gemm_w8a16(x, W, s)
+        c1 = time.perf_counter()
+        cb = sum(w8_bytes(M, K, N) for M, N in sample)
+        cpu = {"value": round(cb / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": "oracle W8A16 MSD GEMM, full outputs, M in {1,8,32}, K=4096, N=4096 (%.1f s)" % (c1 - c0)}
+
+    line = {
+        "metric": "MSD W8A16 decode GEMM, algorithmic HBM GB/s (decompose + dual INT8 GEMM + epilogue)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "W8A16 MSD GEMM decode shapes: M in {1,8,32,128}, K=4096, N in {4096,14336}; "
+                               "one step = all 8 shapes, weights cycled through >512 MB of copies (cold HBM)",
+                   "bytes_per_step": step_bytes},
+        "roofline": roofline, "cpu_baseline": cpu, "shapes": per_shape, "extras": extras,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

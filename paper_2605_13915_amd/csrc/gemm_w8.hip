@@ -11,12 +11,10 @@
 // l%16, rows 4*(l/16)+r in register r.  A = stacked activation codes, B = W rows.
 //
 // Two kernels:
-//   skinny : 2M <= 16.  One 16-row A fragment carries [x1; x2].  W goes HBM -> registers in
+//   skinny : 2M <= 64.  Up to four 16-row A fragments carry [x1; x2].  W goes HBM -> registers in
 //            MFMA layout directly (each lane reads 16 contiguous bytes of one W row), the
 //            K range is split over the waves of a workgroup and reduced through LDS.
-//   tiled  : any M.  LDS-staged tiles, 4 waves, optional split-K over workgroups with
-//            per-split int32 slabs and a last-arriver epilogue (integer sums: exact and
-//            order-independent, hence deterministic).
+//   tiled  : any M.  LDS-staged tiles, 4 waves, register-local merge of the two components.
 #include "kernels.hpp"
 
 namespace msd {
@@ -45,10 +43,13 @@ __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta,
   return sw * (alpha * (float)a1 + beta * (float)a2);
 }
 
-// ------------------------------------------------------------------ skinny (2M <= 16)
-template <int WAVES, int UNROLL>
+// ------------------------------------------------------------------ skinny (2M <= 16*RT)
+// One workgroup per 16 output channels.  The stacked rows [x1; x2] fill RT A fragments; each
+// wave owns a contiguous K range, streams its 16 x (K/WAVES) slice of W from HBM straight into
+// MFMA B fragments and reads the matching A fragments from the (cache-resident) code buffers.
+template <int WAVES, int UNROLL, int RT>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_skinny_kernel(GemmW8Args a) {
-  __shared__ int s_part[WAVES][4][64];
+  __shared__ int s_part[WAVES][RT][4][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = lane & 15, g = lane >> 4;
   const int M = (int)a.M;
@@ -60,38 +61,50 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_skinny_kernel(GemmW8Args a
   const int ks1 = min(ksteps, ks0 + per);
   const int64_t wrow = min(n0 + row, N - 1);
   const int8_t* wp = a.W + wrow * K + 16 * g;
-  const int8_t* ap = nullptr;
-  if (row < M)
-    ap = a.q1 + (int64_t)row * a.ldq + 16 * g;
-  else if (row < 2 * M)
-    ap = a.q2 + (int64_t)(row - M) * a.ldq + 16 * g;
-  v4i acc = {0, 0, 0, 0};
+  const int8_t* ap[RT];
+#pragma unroll
+  for (int f = 0; f < RT; ++f) {
+    const int i = f * 16 + row;  // stacked row: [0,M) -> x1, [M,2M) -> x2
+    ap[f] = nullptr;
+    if (i < M)
+      ap[f] = a.q1 + (int64_t)i * a.ldq + 16 * g;
+    else if (i < 2 * M)
+      ap[f] = a.q2 + (int64_t)(i - M) * a.ldq + 16 * g;
+  }
   const v4i zero = {0, 0, 0, 0};
+  v4i acc[RT];
+#pragma unroll
+  for (int f = 0; f < RT; ++f) acc[f] = zero;
   for (int ks = ks0; ks < ks1; ks += UNROLL) {
-    v4i wv[UNROLL], av[UNROLL];
+    v4i wv[UNROLL], av[RT][UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t k = (int64_t)(ks + u) * 64;
       const bool ok = (ks + u < ks1) && (k + 16 * g < K);
       wv[u] = ok ? ldg16_stream(wp + k) : zero;
-      av[u] = (ok && ap) ? ldg16(ap + k) : zero;
+#pragma unroll
+      for (int f = 0; f < RT; ++f) av[f][u] = (ok && ap[f]) ? ldg16(ap[f] + k) : zero;
     }
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) acc = mfma16(av[u], wv[u], acc);
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int f = 0; f < RT; ++f) acc[f] = mfma16(av[f][u], wv[u], acc[f]);
   }
 #pragma unroll
-  for (int r = 0; r < 4; ++r) s_part[wave][r][lane] = acc[r];
+  for (int f = 0; f < RT; ++f)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s_part[wave][f][r][lane] = acc[f][r];
   __syncthreads();
-  // thread t -> (m = t/16, j = t%16): D[i][j] lives in register i%4 of lane (i/4)*16 + j
-  const int t = threadIdx.x;
-  if (t < M * 16) {
+  // thread t -> (m = t/16, j = t%16); stacked row i sits in fragment i/16, register (i%16)%4 of
+  // lane ((i%16)/4)*16 + j
+  for (int t = threadIdx.x; t < M * 16; t += WAVES * 64) {
     const int m = t >> 4, j = t & 15;
     const int i1 = m, i2 = M + m;
     int a1 = 0, a2 = 0;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-      a1 += s_part[w][i1 & 3][(i1 >> 2) * 16 + j];
-      a2 += s_part[w][i2 & 3][(i2 >> 2) * 16 + j];
+      a1 += s_part[w][i1 >> 4][i1 & 3][((i1 & 15) >> 2) * 16 + j];
+      a2 += s_part[w][i2 >> 4][i2 & 3][((i2 & 15) >> 2) * 16 + j];
     }
     const int64_t n = n0 + j;
     if (n < N) {
@@ -126,22 +139,18 @@ struct TiledCfg {
 };
 
 template <int BMH, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_w8_tiled_kernel(GemmW8Args a, int nsplit,
-                                                                      int ksteps_per_split) {
+__global__ __launch_bounds__(WM * WN * 64) void gemm_w8_tiled_kernel(GemmW8Args a) {
   using C = TiledCfg<BMH, BN, WM, WN>;
   __shared__ __attribute__((aligned(16))) int8_t sA[C::kRowsA * kLdsStride];
   __shared__ __attribute__((aligned(16))) int8_t sB[BN * kLdsStride];
-  __shared__ int s_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int row16 = lane & 15, g = lane >> 4;
   const int64_t M = a.M, K = a.K, N = a.N;
   const int64_t m0 = (int64_t)blockIdx.y * BMH;
   const int64_t n0 = (int64_t)blockIdx.x * BN;
-  const int split = blockIdx.z;
-  const int ksteps = (int)((K + kBK - 1) / kBK);
-  const int ks0 = split * ksteps_per_split;
-  const int ks1 = min(ksteps, ks0 + ksteps_per_split);
+  const int ks0 = 0;
+  const int ks1 = (int)((K + kBK - 1) / kBK);
   const v4i zero = {0, 0, 0, 0};
 
   // global -> register staging of one K step
@@ -214,51 +223,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_tiled_kernel(GemmW8Args 
       }
   }
 
-  // ---- split-K: park partial sums in this split's slab; the last workgroup of the tile sums
-  if (nsplit > 1) {
-    const int64_t slab = 2 * M * N;
-    int32_t* mine = a.part + (int64_t)split * slab;
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < C::kFragM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::kFragN; ++j)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int64_t m = m0 + wm * C::kTMH + 16 * i + 4 * g + r;
-            const int64_t n = n0 + wn * C::kTN + 16 * j + row16;
-            if (m < M && n < N) __builtin_nontemporal_store(acc[c][i][j][r], &mine[(c * M + m) * N + n]);
-          }
-    __threadfence();
-    __syncthreads();
-    const unsigned tile = blockIdx.y * gridDim.x + blockIdx.x;
-    if (tid == 0) {
-      const unsigned prev = atomicAdd(&a.counters[tile], 1u);
-      s_last = (prev == (unsigned)nsplit - 1u);
-      if (s_last) a.counters[tile] = 0;  // ready for the next call on this stream
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < C::kFragM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::kFragN; ++j)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int64_t m = m0 + wm * C::kTMH + 16 * i + 4 * g + r;
-            const int64_t n = n0 + wn * C::kTN + 16 * j + row16;
-            int s = 0;
-            if (m < M && n < N)
-              for (int sp = 0; sp < nsplit; ++sp)
-                s += __builtin_nontemporal_load(&a.part[(int64_t)sp * slab + (c * M + m) * N + n]);
-            acc[c][i][j][r] = s;
-          }
-  }
-
   // ---- dual-scale epilogue
 #pragma unroll
   for (int i = 0; i < C::kFragM; ++i)
@@ -281,57 +245,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_tiled_kernel(GemmW8Args 
 }
 
 // ------------------------------------------------------------------ dispatch
-struct TiledPlan {
-  int kind;  // 0 skinny, 1: 32x64 tiles (decode), 2: 64x128 tiles
-  int nsplit;
-  int ksteps_per_split;
-  dim3 grid;
-};
-
-static TiledPlan plan_w8(int64_t M, int64_t K, int64_t N) {
-  TiledPlan p{};
-  const int ksteps = (int)((K + kBK - 1) / kBK);
-  if (2 * M <= 16) {
-    p.kind = 0;
-    p.nsplit = 1;
-    p.grid = dim3((unsigned)cdiv(N, 16));
-    return p;
-  }
-  int bmh, bn;
-  if (M <= 32) {
-    p.kind = 1, bmh = 32, bn = 64;
-  } else {
-    p.kind = 2, bmh = 64, bn = 128;
-  }
-  const int64_t tiles = cdiv(M, bmh) * cdiv(N, bn);
-  int nsplit = 1;
-  // memory-bound shapes with too few tiles to fill 256 CUs: split K
-  while (tiles * nsplit < 512 && nsplit < 16 && ksteps / (nsplit * 2) >= 4) nsplit *= 2;
-  p.ksteps_per_split = (ksteps + nsplit - 1) / nsplit;
-  if (p.ksteps_per_split < 1) p.ksteps_per_split = 1;
-  p.nsplit = (ksteps + p.ksteps_per_split - 1) / p.ksteps_per_split;
-  if (p.nsplit < 1) p.nsplit = 1;
-  p.grid = dim3((unsigned)cdiv(N, bn), (unsigned)cdiv(M, bmh), (unsigned)p.nsplit);
-  return p;
-}
-
-void gemm_w8_scratch(int64_t M, int64_t K, int64_t N, size_t* part_bytes, size_t* counter_bytes) {
-  const TiledPlan p = plan_w8(M, K, N);
-  *part_bytes = p.nsplit > 1 ? (size_t)p.nsplit * 2 * M * N * sizeof(int32_t) : 0;
-  *counter_bytes = p.nsplit > 1 ? (size_t)p.grid.x * p.grid.y * sizeof(uint32_t) : 0;
+void gemm_w8_scratch(int64_t, int64_t, int64_t, size_t* part_bytes, size_t* counter_bytes) {
+  *part_bytes = 0;
+  *counter_bytes = 0;
 }
 
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
-  const TiledPlan p = plan_w8(a.M, a.K, a.N);
-  if (p.kind == 0) {
-    hipLaunchKernelGGL((gemm_w8_skinny_kernel<8, 8>), p.grid, dim3(512), 0, stream, a);
-  } else if (p.kind == 1) {
-    hipLaunchKernelGGL((gemm_w8_tiled_kernel<32, 64, 1, 4>), p.grid, dim3(256), 0, stream, a, p.nsplit,
-                       p.ksteps_per_split);
+  const int64_t M = a.M, N = a.N;
+  if (2 * M <= 64) {
+    const dim3 grid((unsigned)cdiv(N, 16));
+    if (2 * M <= 16)
+      hipLaunchKernelGGL((gemm_w8_skinny_kernel<8, 8, 1>), grid, dim3(512), 0, stream, a);
+    else if (2 * M <= 32)
+      hipLaunchKernelGGL((gemm_w8_skinny_kernel<8, 4, 2>), grid, dim3(512), 0, stream, a);
+    else
+      hipLaunchKernelGGL((gemm_w8_skinny_kernel<8, 4, 4>), grid, dim3(512), 0, stream, a);
+  } else if (cdiv(M, 64) * cdiv(N, 128) < 256) {
+    // few, tall tiles: narrow the N tile so that a decode-sized problem still covers the chip
+    const dim3 grid((unsigned)cdiv(N, 32), (unsigned)cdiv(M, 64));
+    hipLaunchKernelGGL((gemm_w8_tiled_kernel<64, 32, 4, 1>), grid, dim3(256), 0, stream, a);
   } else {
-    hipLaunchKernelGGL((gemm_w8_tiled_kernel<64, 128, 2, 2>), p.grid, dim3(256), 0, stream, a, p.nsplit,
-                       p.ksteps_per_split);
+    const dim3 grid((unsigned)cdiv(N, 128), (unsigned)cdiv(M, 64));
+    hipLaunchKernelGGL((gemm_w8_tiled_kernel<64, 128, 2, 2>), grid, dim3(256), 0, stream, a);
   }
   MSD_LAUNCH_CHECK();
   return MSD_OK;

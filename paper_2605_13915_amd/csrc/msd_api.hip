@@ -149,7 +149,8 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   if (K % 32 != 0 || K > (1 << 20)) return MSD_ERR_SHAPE;
   if (M == 0 || N == 0) return MSD_OK;
   if (!y || (K > 0 && (!x_bf16 || !W_fp4 || !W_e8m0))) return MSD_ERR_INVALID_ARG;
-  if (!aligned_to(W_fp4, 16) || !aligned_to(x_bf16, 2) || !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
+  if (!aligned_to(W_fp4, 16) || !aligned_to(W_e8m0, 4) || !aligned_to(x_bf16, 2) ||
+      !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
     return MSD_ERR_INVALID_ARG;
   const W4Layout l = w4_layout(M, K, N);
   if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;

@@ -1,0 +1,78 @@
+"""GPU parity: msd_decompose (MXFP4) and msd_gemm_w4a16 against the CPU oracle, through the C ABI.
+
+Bar: 4-bit component codes and E8M0 exponents bit-exact; fp32 output within relative L2 1e-3 of
+the oracle (the GPU accumulates block products in fp32 inside the matrix instruction, the oracle
+in fp64); Theorem-2 output bound against the fp64 truth."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13915_amd import synth
+from gpu_util import bf16_to_dev, to_dev, rel_l2, bf16_dev_to_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def msd():
+    from paper_2605_13915_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("M,K,scale", [(1, 8192, 1.0), (7, 96, 1e-3), (33, 4096, 300.0), (300, 544, 1.0)])
+def test_decompose_mxfp4_bit_exact(msd, M, K, scale):
+    x = synth.activations(synth.seed_for(3, M), M, K, outliers=K >= 1024, scale=scale)
+    xf = synth.bf16_bits_to_f32(x).copy()
+    xf[0, :32] = 0.0                       # all-zero block
+    xf[M - 1, 32:64] = 0.0
+    xf[M - 1, 33] = 1.859375               # equality case of the alpha rule
+    xf[M - 1, 34] = 0.125                  # tie on the code grid
+    x = synth.f32_to_bf16_bits(xf)
+    q1, q2, e = oracle.decompose_mxfp4(x)
+    d1, d2, de = msd.msd_decompose(msd.MSD_MXFP4, bf16_to_dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(de.cpu().numpy(), e)
+    assert np.array_equal(d1.cpu().numpy(), q1)
+    assert np.array_equal(d2.cpu().numpy(), q2)
+
+
+SHAPES = [(1, 8192, 512), (32, 8192, 256), (5, 96, 40), (17, 1056, 100), (70, 512, 48), (2, 2048, 4096)]
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_gemm_w4a16_parity(msd, M, K, N):
+    seed = synth.seed_for(3, M * 11 + N)
+    x = synth.activations(seed, M, K, outliers=K >= 1024)
+    codes, exps = synth.mxfp4_weights(seed, N, K)
+    y_ref, t = oracle.gemm_w4a16(x, codes, exps, taps=True)
+    y, g = msd.msd_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps), taps=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(g["scale"].cpu().numpy(), t["e8m0"])
+    assert np.array_equal(g["q1"].cpu().numpy(), t["q1"])
+    assert np.array_equal(g["q2"].cpu().numpy(), t["q2"])
+    yh = y.cpu().numpy()
+    assert rel_l2(yh, y_ref) <= 1e-3
+    assert rel_l2(yh, y_ref) <= 2e-6
+    truth = oracle.truth_gemm_w4(x, codes, exps)
+    a = np.exp2(t["e8m0"].astype(np.float64) - 127)
+    wabs = np.abs(synth.dequantize_mxfp4(codes, exps).astype(np.float64)).reshape(N, -1, 32).sum(axis=2)
+    bound = (a / 64) @ wabs.T
+    assert np.all(np.abs(yh - truth) <= bound * (1 + 1e-5) + np.abs(truth) * 2.0 ** -20 + 1e-30)
+
+
+def test_gemm_w4a16_bf16_out_and_errors(msd):
+    M, K, N = 4, 1024, 64
+    x = synth.activations(5, M, K)
+    codes, exps = synth.mxfp4_weights(5, N, K)
+    ref = oracle.gemm_w4a16(x, codes, exps, out_bf16=True)
+    y = msd.msd_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps), out_dtype=torch.bfloat16)
+    bits = bf16_dev_to_bits(y)
+    assert rel_l2(synth.bf16_bits_to_f32(bits), synth.bf16_bits_to_f32(ref)) <= 1e-3
+    assert np.mean(bits != ref) < 0.01
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_gemm_w4a16(torch.zeros((2, 48), dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros((4, 24), dtype=torch.uint8, device="cuda"),
+                           torch.zeros((4, 1), dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -2
