@@ -1,5 +1,414 @@
+// MSD attention decode over an INT8 KV cache for gfx950 (paper Sec. 4.2, Alg. 3; tiling of
+// Sec. 4.3; fused-kernel steps of Sec. 3.9 "Attention decode example").
+//
+// K and V stay INT8 from HBM to the matrix unit.  Per (batch, KV head) the G = Hq/Hkv query
+// rows are decomposed once into two INT8 components each; per 64-token tile a wave
+//   (1) loads K_t, V_t once,
+//   (2) computes S1 = Q1 K_t^T and S2 = Q2 K_t^T on v_mfma_i32_16x16x64_i8 with the rows
+//       [Q1; Q2] of all heads stacked in one A fragment,
+//   (3) merges S = (alpha_Q S1 + beta_Q S2)/sqrt(d) (times s_K[t] for per-token scales),
+//   (4) runs the online softmax in fp32 and decomposes P (times s_V[t]) with a scale that
+//       needs no reduction over P,
+//   (5) computes O1 = P1 V_t, O2 = P2 V_t on the same MFMA and rescales the running output.
+// The KV length is split over workgroups (flash-decode); a small second kernel merges the
+// (m, l, O) partials -- the only cross-workgroup step.
+//
+// Layout tricks.  A-fragment row i = 4*(lane/16)+r carries (head, component), chosen so that
+// S1 and S2 (and later O1 and O2) of one head land in registers of the same lane: the
+// merges are register-local.  The contraction index of an MFMA may be permuted freely as
+// long as both operands agree; for P.V the k slot (kg, 4*jq+tt) stands for token
+// 16*tt + 4*kg + jq of the tile, which lets P travel as one packed dword per lane and lets V
+// be brought into "token-contiguous" order by 4x4 byte transposes (v_perm_b32) in registers.
 #include "kernels.hpp"
+
 namespace msd {
-size_t attn_workspace_bytes(int, int, int, int, int64_t) { return 256; }
-int launch_attn_decode(const AttnArgs&, hipStream_t) { return MSD_ERR_UNSUPPORTED; }
+
+struct AttnParams {
+  const uint16_t* q;
+  const int8_t* K;
+  const int8_t* V;
+  const float* k_scale;
+  const float* v_scale;
+  const int32_t* kv_len;
+  int B, Hq, Hkv, G;
+  int64_t L;
+  int nsplit;
+  int64_t tokens_per_split;
+  float* part_o;  // [B*Hkv][nsplit][G][128]
+  float* part_m;  // [B*Hkv][nsplit][G]
+  float* part_l;
+  int8_t* tap_q1;
+  int8_t* tap_q2;
+  float* tap_alpha;
+  int32_t* tap_s1;
+  int32_t* tap_s2;
+};
+
+constexpr int kD = 128;
+constexpr int kTile = 64;
+constexpr int kAttnWaves = 4;
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ v4i mfma_s8(v4i a, v4i b, v4i c) {
+  return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float row16_max(float v) {  // over the 16 lanes sharing lane/16
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// 4x4 byte transpose: in[t] = 4 channel bytes of token t; out[c] = 4 token bytes of channel c
+__device__ __forceinline__ void transpose4x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d,
+                                             uint32_t (&o)[4]) {
+  const uint32_t ab_lo = __builtin_amdgcn_perm(b, a, 0x05010400u);
+  const uint32_t ab_hi = __builtin_amdgcn_perm(b, a, 0x07030602u);
+  const uint32_t cd_lo = __builtin_amdgcn_perm(d, c, 0x05010400u);
+  const uint32_t cd_hi = __builtin_amdgcn_perm(d, c, 0x07030602u);
+  o[0] = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x05040100u);
+  o[1] = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x07060302u);
+  o[2] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x05040100u);
+  o[3] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
+}
+
+// HPL = heads per lane group: 1 for G <= 4, 2 for G <= 8.
+template <int HPL, bool PER_TOKEN>
+__global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams p) {
+  constexpr int NH = 4 * HPL;  // head slots
+  __shared__ __attribute__((aligned(16))) int8_t sQ[2][NH][kD];
+  __shared__ float sAlpha[NH];
+  __shared__ __attribute__((aligned(16))) uint32_t sP[kAttnWaves][2][NH][16];
+  __shared__ float sM[kAttnWaves][NH], sL[kAttnWaves][NH];
+  __shared__ float sO[kAttnWaves][NH][kD];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;  // g: lane group = head group in D layouts; kg for operands
+  const int bk = blockIdx.x / p.nsplit, split = blockIdx.x % p.nsplit;
+  const int b = bk / p.Hkv, hk = bk % p.Hkv;
+  const int G = p.G;
+  int64_t len = p.kv_len ? (int64_t)p.kv_len[b] : p.L;
+  len = max((int64_t)0, min(len, p.L));
+  const int64_t t_begin = (int64_t)split * p.tokens_per_split;
+  const int64_t t_end = min(len, t_begin + p.tokens_per_split);
+  const int64_t kv_base = (int64_t)bk * p.L;  // token index base of this (b, kv head)
+  const int8_t* Kb = p.K + kv_base * kD;
+  const int8_t* Vb = p.V + kv_base * kD;
+
+  // ---- prologue: decompose the G query rows (Alg. 3 steps 1-2), one head per wave at a time
+  for (int h = wave; h < NH; h += kAttnWaves) {
+    uint32_t c1 = 0, c2 = 0;
+    float alpha = 0.f;
+    if (h < G) {
+      const int64_t qrow = (int64_t)b * p.Hq + hk * G + h;
+      const uint32_t w = reinterpret_cast<const uint32_t*>(p.q + qrow * kD)[lane];
+      float x0 = __uint_as_float(w << 16), x1 = __uint_as_float(w & 0xFFFF0000u);
+      if (!PER_TOKEN) {  // absorb the per-channel K scale into Q
+        x0 *= p.k_scale[hk * kD + 2 * lane];
+        x1 *= p.k_scale[hk * kD + 2 * lane + 1];
+      }
+      const float mx = wave_max(fmaxf(fabsf(x0), fabsf(x1)));
+      if (mx > 0.f) {
+        alpha = __fdiv_rn(mx, 127.0f);
+        const float beta = __fdiv_rn(alpha, 254.0f);
+        int a0, b0, a1, b1;
+        int8_codes(x0, alpha, beta, a0, b0);
+        int8_codes(x1, alpha, beta, a1, b1);
+        c1 = ((uint32_t)a0 & 0xFFu) | (((uint32_t)a1 & 0xFFu) << 8);
+        c2 = ((uint32_t)b0 & 0xFFu) | (((uint32_t)b1 & 0xFFu) << 8);
+      }
+      if (split == 0 && p.tap_q1) {
+        reinterpret_cast<uint16_t*>(p.tap_q1 + qrow * kD)[lane] = (uint16_t)c1;
+        reinterpret_cast<uint16_t*>(p.tap_q2 + qrow * kD)[lane] = (uint16_t)c2;
+        if (lane == 0) p.tap_alpha[qrow] = alpha;
+      }
+    }
+    reinterpret_cast<uint16_t*>(&sQ[0][h][0])[lane] = (uint16_t)c1;
+    reinterpret_cast<uint16_t*>(&sQ[1][h][0])[lane] = (uint16_t)c2;
+    if (lane == 0) sAlpha[h] = alpha;
+  }
+  __syncthreads();
+
+  // A-fragment row of this lane (as an operand lane: row = j, k group = g)
+  const int slot = j & 3;
+  const bool row_valid = (HPL == 2) || (slot < 2);
+  const int row_head = (j >> 2) * HPL + (HPL == 2 ? (slot >> 1) : 0);
+  const int row_comp = (HPL == 2) ? (slot & 1) : slot;
+  const v4i zero4 = {0, 0, 0, 0};
+  v4i qa[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+    qa[s] = (row_valid && row_head < G)
+                ? *reinterpret_cast<const v4i*>(&sQ[row_comp][row_head][64 * s + 16 * g])
+                : zero4;
+
+  // per-lane-group state (as a D lane: head group = g)
+  float aq[HPL], bq[HPL], m_run[HPL], l_run[HPL], o_run[HPL][8];
+#pragma unroll
+  for (int hh = 0; hh < HPL; ++hh) {
+    aq[hh] = sAlpha[g * HPL + hh];
+    bq[hh] = __fdiv_rn(aq[hh], 254.0f);
+    m_run[hh] = -INFINITY;
+    l_run[hh] = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o_run[hh][c] = 0.f;
+  }
+  const float sm_scale = kLog2e / sqrtf((float)kD);  // scores are kept in log2 units
+
+  for (int64_t t0 = t_begin + (int64_t)wave * kTile; t0 < t_end; t0 += kAttnWaves * kTile) {
+    const int64_t last = t_end - 1;
+    // ---- (1) load K_t and V_t once
+    v4i kf[4][2];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      const int64_t tok = min(t0 + 16 * tt + j, last);
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        kf[tt][s] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(Kb + tok * kD + 64 * s + 16 * g));
+    }
+    v2i vr[4][4];  // [jq][tt]: 8 channels (8j..8j+7) of token 16*tt + 4*g + jq
+#pragma unroll
+    for (int jq = 0; jq < 4; ++jq)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const int64_t tok = min(t0 + 16 * tt + 4 * g + jq, last);
+        vr[jq][tt] = __builtin_nontemporal_load(reinterpret_cast<const v2i*>(Vb + tok * kD + 8 * j));
+      }
+    float sk[4], sv[4];
+    bool live[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      const int64_t tok = t0 + 16 * tt + j;
+      live[tt] = tok < t_end;
+      sk[tt] = 1.f;
+      sv[tt] = 1.f;
+      if (PER_TOKEN) {
+        sk[tt] = p.k_scale[kv_base + min(tok, last)];
+        sv[tt] = live[tt] ? p.v_scale[kv_base + tok] : 0.f;
+      }
+    }
+    // ---- (2) S1, S2 for all heads of the group
+    v4i sd[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      sd[tt] = mfma_s8(qa[0], kf[tt][0], zero4);
+      sd[tt] = mfma_s8(qa[1], kf[tt][1], sd[tt]);
+    }
+    if (p.tap_s1) {
+#pragma unroll
+      for (int hh = 0; hh < HPL; ++hh) {
+        const int head = g * HPL + hh;
+        if (head < G) {
+          const int64_t row = ((int64_t)b * p.Hq + hk * G + head) * p.L;
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt)
+            if (live[tt]) {
+              p.tap_s1[row + t0 + 16 * tt + j] = sd[tt][2 * hh];
+              p.tap_s2[row + t0 + 16 * tt + j] = sd[tt][2 * hh + 1];
+            }
+        }
+      }
+    }
+    // scale of the P decomposition: alpha_P = top/127 with top a bound on P (or P*s_V)
+    float top = 1.f;
+    if (PER_TOKEN) top = row16_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
+    const float to_code = top > 0.f ? __fdiv_rn(127.0f, top) : 0.f;
+    const float from_code = top * (1.0f / 127.0f);
+    // ---- (3)+(4) merge, online softmax, decompose P
+    float corr[HPL];
+    uint32_t pk1[HPL], pk2[HPL];
+#pragma unroll
+    for (int hh = 0; hh < HPL; ++hh) {
+      float s[4];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const float v = (aq[hh] * (float)sd[tt][2 * hh] + bq[hh] * (float)sd[tt][2 * hh + 1]) * (sm_scale * sk[tt]);
+        s[tt] = live[tt] ? v : -INFINITY;
+        mx = fmaxf(mx, s[tt]);
+      }
+      mx = row16_max(mx);
+      const float m_new = fmaxf(m_run[hh], mx);
+      corr[hh] = __builtin_amdgcn_exp2f(m_run[hh] - m_new);
+      m_run[hh] = m_new;
+      float lsum = 0.f;
+      uint32_t w1 = 0, w2 = 0;
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const float pr = __builtin_amdgcn_exp2f(s[tt] - m_new);
+        lsum += pr;
+        const float t = pr * sv[tt] * to_code;  // P (times s_V) in units of alpha_P
+        const float c1 = fminf(rintf(t), 127.f);
+        const float c2 = fminf(fmaxf(rintf((t - c1) * 254.0f), -127.f), 127.f);
+        w1 |= ((uint32_t)(int)c1 & 0xFFu) << (8 * tt);
+        w2 |= ((uint32_t)(int)c2 & 0xFFu) << (8 * tt);
+      }
+      l_run[hh] = l_run[hh] * corr[hh] + lsum;
+      pk1[hh] = w1;
+      pk2[hh] = w2;
+    }
+    // ---- hand P to the A-fragment layout through LDS (wave-private)
+#pragma unroll
+    for (int hh = 0; hh < HPL; ++hh) {
+      sP[wave][0][g * HPL + hh][j] = pk1[hh];
+      sP[wave][1][g * HPL + hh][j] = pk2[hh];
+    }
+    __builtin_amdgcn_wave_barrier();
+    const v4i pa = row_valid ? *reinterpret_cast<const v4i*>(&sP[wave][row_comp][row_head][4 * g]) : zero4;
+    __builtin_amdgcn_wave_barrier();
+    // ---- V_t into token-contiguous B fragments: vb[c][jq] = 4 token bytes of channel 8j+c
+    uint32_t vb[8][4];
+#pragma unroll
+    for (int jq = 0; jq < 4; ++jq) {
+      uint32_t lo[4], hi[4];
+      transpose4x4((uint32_t)vr[jq][0][0], (uint32_t)vr[jq][1][0], (uint32_t)vr[jq][2][0], (uint32_t)vr[jq][3][0], lo);
+      transpose4x4((uint32_t)vr[jq][0][1], (uint32_t)vr[jq][1][1], (uint32_t)vr[jq][2][1], (uint32_t)vr[jq][3][1], hi);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        vb[c][jq] = lo[c];
+        vb[4 + c][jq] = hi[c];
+      }
+    }
+    // ---- (5) O1, O2, merge and rescale the running output
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const v4i bf = {(int)vb[c][0], (int)vb[c][1], (int)vb[c][2], (int)vb[c][3]};
+      const v4i od = mfma_s8(pa, bf, zero4);
+#pragma unroll
+      for (int hh = 0; hh < HPL; ++hh) {
+        const float ot = from_code * ((float)od[2 * hh] + (float)od[2 * hh + 1] * (1.0f / 254.0f));
+        o_run[hh][c] = o_run[hh][c] * corr[hh] + ot;
+      }
+    }
+  }
+
+  // ---- merge the waves of this workgroup, write the split's partial (m, l, O)
+#pragma unroll
+  for (int hh = 0; hh < HPL; ++hh) {
+    const float lt = row16_sum(l_run[hh]);
+    const int hs = g * HPL + hh;
+    if (j == 0) {
+      sM[wave][hs] = m_run[hh];
+      sL[wave][hs] = lt;
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) sO[wave][hs][8 * j + c] = o_run[hh][c];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * kD; idx += kAttnWaves * 64) {
+    const int h = idx / kD, c = idx % kD;
+    float ms = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) ms = fmaxf(ms, sM[w][h]);
+    float o = 0.f, l = 0.f;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) {
+      const float wgt = (sM[w][h] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sM[w][h] - ms);
+      o += sO[w][h][c] * wgt;
+      l += sL[w][h] * wgt;
+    }
+    const int64_t pr = ((int64_t)bk * p.nsplit + split) * G + h;
+    p.part_o[pr * kD + c] = o;
+    if (c == 0) {
+      p.part_m[pr] = ms;
+      p.part_l[pr] = l;
+    }
+  }
+}
+
+// Merge the split partials: out = sum_s O_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
+// (times s_V per channel in per-channel mode; Alg. 3 last two steps).
+__global__ __launch_bounds__(kD) void attn_combine_kernel(AttnParams p, void* out, int out_bf16,
+                                                          int per_channel) {
+  const int row = blockIdx.x;  // b*Hq + hq
+  const int b = row / p.Hq, hq = row % p.Hq;
+  const int hk = hq / p.G, h = hq % p.G;
+  const int c = threadIdx.x;
+  const int64_t base = ((int64_t)(b * p.Hkv + hk) * p.nsplit) * p.G + h;
+  float ms = -INFINITY;
+  for (int s = 0; s < p.nsplit; ++s) ms = fmaxf(ms, p.part_m[base + (int64_t)s * p.G]);
+  float o = 0.f, l = 0.f;
+  for (int s = 0; s < p.nsplit; ++s) {
+    const int64_t pr = base + (int64_t)s * p.G;
+    const float mv = p.part_m[pr];
+    const float wgt = (mv == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mv - ms);
+    o += p.part_o[pr * kD + c] * wgt;
+    l += p.part_l[pr] * wgt;
+  }
+  float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
+  if (per_channel) v *= p.v_scale[hk * kD + c];
+  if (out_bf16)
+    reinterpret_cast<uint16_t*>(out)[(int64_t)row * kD + c] = f32_to_bf16_bits(v);
+  else
+    reinterpret_cast<float*>(out)[(int64_t)row * kD + c] = v;
+}
+
+static int plan_nsplit(int B, int Hkv, int64_t L) {
+  const int64_t pairs = (int64_t)B * Hkv;
+  int64_t ns = cdiv(1024, pairs);
+  int64_t max_by_len = L / (kAttnWaves * kTile * 2);  // >= 2 rounds of 4 waves per split
+  if (max_by_len < 1) max_by_len = 1;
+  if (ns > max_by_len) ns = max_by_len;
+  if (ns > 64) ns = 64;
+  if (ns < 1) ns = 1;
+  return (int)ns;
+}
+
+size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L) {
+  (void)d;
+  const int ns = plan_nsplit(B, Hkv, L);
+  const size_t rows = (size_t)B * Hq * ns;
+  return align_up(rows * kD * 4, 256) + 2 * align_up(rows * 4, 256);
+}
+
+int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
+  AttnParams p{};
+  p.q = a.q; p.K = a.K; p.V = a.V;
+  p.k_scale = a.k_scale; p.v_scale = a.v_scale;
+  p.kv_len = a.kv_len;
+  p.B = a.B; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
+  p.L = a.L;
+  p.nsplit = plan_nsplit(a.B, a.Hkv, a.L);
+  int64_t tps = cdiv(a.L > 0 ? a.L : 1, p.nsplit);
+  tps = cdiv(tps, kAttnWaves * kTile) * (kAttnWaves * kTile);
+  p.tokens_per_split = tps;
+  const size_t rows = (size_t)a.B * a.Hq * p.nsplit;
+  char* ws = (char*)a.workspace;
+  p.part_o = (float*)ws;
+  p.part_m = (float*)(ws + align_up(rows * kD * 4, 256));
+  p.part_l = (float*)(ws + align_up(rows * kD * 4, 256) + align_up(rows * 4, 256));
+  if (a.taps) {
+    p.tap_q1 = (int8_t*)a.taps->q1;
+    p.tap_q2 = (int8_t*)a.taps->q2;
+    p.tap_alpha = (float*)a.taps->scale;
+    p.tap_s1 = a.taps->acc1;
+    p.tap_s2 = a.taps->acc2;
+    if (!(p.tap_q1 && p.tap_q2 && p.tap_alpha)) p.tap_q1 = p.tap_q2 = nullptr, p.tap_alpha = nullptr;
+    if (!(p.tap_s1 && p.tap_s2)) p.tap_s1 = p.tap_s2 = nullptr;
+  }
+  const dim3 grid((unsigned)((int64_t)a.B * a.Hkv * p.nsplit));
+  const bool per_token = a.scale_mode == MSD_PER_TOKEN;
+  if (p.G <= 4) {
+    if (per_token)
+      hipLaunchKernelGGL((attn_decode_kernel<1, true>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+    else
+      hipLaunchKernelGGL((attn_decode_kernel<1, false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+  } else {
+    if (per_token)
+      hipLaunchKernelGGL((attn_decode_kernel<2, true>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+    else
+      hipLaunchKernelGGL((attn_decode_kernel<2, false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+  }
+  MSD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(a.B * a.Hq)), dim3(kD), 0, stream, p, a.out,
+                     a.out_bf16, per_token ? 0 : 1);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 }  // namespace msd
