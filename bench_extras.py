@@ -1,0 +1,158 @@
+"""Secondary benchmark legs printed inside bench.py's JSON line under "extras".
+
+Each leg times one C-ABI entry point on the shapes the benchmark spec lists for it, with HIP events
+on the launch stream, inputs resident in HBM and (for memory-bound shapes) weight / KV copies
+cycled so that the working set exceeds twice the 256 MB last-level cache.  Figures: time per
+call, algorithmic GB/s or executed/effective TOP/s, and the fraction of the MI355X peak that
+bounds the leg.  The comparison kernels (dequantise-then-BF16-MFMA) run beside the MSD kernels.
+"""
+import numpy as np
+import torch
+
+HBM = 8000.0
+INT8_TOPS = 5000.0
+FP4_TFLOPS = 10100.0
+LLC = 256 << 20
+
+
+def _bf16(bits, dev):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+
+def _copies(t, nbytes):
+    n = max(2, -(-2 * LLC // max(nbytes, 1)) + 1)
+    n = min(n, 48)
+    return [t] + [t.clone() for _ in range(n - 1)]
+
+
+def _rand_i8(shape, dev, seed):
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    return torch.randint(-127, 128, shape, dtype=torch.int8, device=dev, generator=g)
+
+
+def leg_prefill(msd, synth, time_calls, dev):
+    """W8A16 prefill shapes (MFMA-bound): executed ops 4MKN against the INT8 peak."""
+    out = []
+    for (M, K, N) in [(2048, 8192, 8192), (8192, 8192, 8192), (2048, 8192, 28672), (8192, 8192, 28672)]:
+        x = _bf16(synth.activations(synth.seed_for(2, M), 64, K), dev).repeat(M // 64, 1).contiguous()
+        W = _rand_i8((N, K), dev, 5)
+        s = torch.rand(N, device=dev) * 0.009 + 0.001
+        y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+        f = lambda i: msd.msd_gemm_w8a16(x, W, s, y=y, ws=ws)
+        f(0)
+        us = time_calls(f, 3)
+        rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 1),
+               "eff_TOPS": round(2.0 * M * K * N / us / 1e6, 1),
+               "int8_mfma_frac": round(4.0 * M * K * N / us / 1e6 / INT8_TOPS, 4)}
+        try:
+            g = lambda i: msd.msd_dequant_gemm_w8a16(x, W, s, y=y, ws=ws)
+            g(0)
+            us2 = time_calls(g, 2)
+            rec["cmp_dequant_us"] = round(us2, 1)
+            rec["speedup_vs_dequant"] = round(us2 / us, 3)
+        except Exception as e:  # noqa: BLE001
+            rec["cmp_error"] = str(e)
+        out.append(rec)
+        del x, W, y, ws
+        torch.cuda.empty_cache()
+    return out
+
+
+def leg_w4(msd, synth, time_calls, dev):
+    out = []
+    K, N = 8192, 28672
+    codes, exps = synth.mxfp4_weights(synth.seed_for(3, 0), 2048, K)
+    codes = torch.from_numpy(codes).to(dev).repeat(N // 2048, 1).contiguous()
+    exps = torch.from_numpy(exps).to(dev).repeat(N // 2048, 1).contiguous()
+    wbytes = K * N // 2 + K * N // 32
+    reps = [(codes, exps)] + [(codes.clone(), exps.clone()) for _ in range(-(-2 * LLC // wbytes))]
+    for M in (1, 32, 4096):
+        x = _bf16(synth.activations(synth.seed_for(3, M), min(M, 64), K), dev)
+        if M > 64:
+            x = x.repeat(M // 64, 1).contiguous()
+        y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        ws = torch.empty(msd.lib().msd_gemm_w4a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+        f = lambda i: msd.msd_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws)
+        f(0)
+        us = time_calls(f, 2 * len(reps) if M <= 32 else 3)
+        b = wbytes + 2 * M * K + 4 * M * N
+        rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "GBps": round(b / us / 1e3, 1),
+               "hbm_frac": round(b / us / 1e3 / HBM, 4), "exec_TFLOPS": round(4.0 * M * K * N / us / 1e6, 1),
+               "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
+        try:
+            g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws)
+            g(0)
+            us2 = time_calls(g, 2 * len(reps) if M <= 32 else 2)
+            rec["cmp_dequant_us"] = round(us2, 1)
+            rec["speedup_vs_dequant"] = round(us2 / us, 3)
+        except Exception as e:  # noqa: BLE001
+            rec["cmp_error"] = str(e)
+        out.append(rec)
+    return out
+
+
+def leg_attn(msd, synth, time_calls, dev):
+    out = []
+    B, Hq, Hkv, d = 16, 32, 8, 128
+    q = _bf16(synth.queries(synth.seed_for(4, 0), B, Hq, d), dev)
+    for L in (4096, 32768):
+        kvbytes = 2 * B * Hkv * L * d
+        n = max(2, min(6, -(-2 * LLC // kvbytes) + 1)) if L <= 4096 else 2
+        sets = []
+        for r in range(n):
+            Kc = _rand_i8((B, Hkv, L, d), dev, 11 + r)
+            Vc = _rand_i8((B, Hkv, L, d), dev, 31 + r)
+            ks = torch.rand((B, Hkv, L), device=dev) * 0.02 + 0.02
+            vs = torch.rand((B, Hkv, L), device=dev) * 0.02 + 0.02
+            sets.append((Kc, Vc, ks, vs))
+        o = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
+        ws = torch.empty(msd.lib().msd_attn_decode_int8kv_workspace_bytes(B, Hq, Hkv, d, L), dtype=torch.uint8,
+                         device=dev)
+        f = lambda i: msd.msd_attn_decode_int8kv(q, *sets[i % n], msd.MSD_PER_TOKEN, out=o, ws=ws)
+        f(0)
+        us = time_calls(f, 4 * n)
+        b = kvbytes + 8 * B * Hkv * L + 2 * B * Hq * d + 4 * B * Hq * d
+        out.append({"B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "L": L, "us": round(us, 1),
+                    "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM, 4)})
+        del sets
+        torch.cuda.empty_cache()
+    return out
+
+
+def leg_cmp_decode(msd, synth, time_calls, dev):
+    """Dequant comparison kernel on the W8A16 decode shapes (same cold-cache protocol)."""
+    out = []
+    K = 4096
+    for N in (4096, 14336):
+        W = _rand_i8((N, K), dev, 3)
+        reps = _copies(W, N * K)
+        s = torch.rand(N, device=dev) * 0.009 + 0.001
+        for M in (1, 8, 32, 128):
+            x = _bf16(synth.activations(synth.seed_for(1, M), M, K), dev)
+            y = torch.empty((M, N), dtype=torch.float32, device=dev)
+            ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+            f = lambda i: msd.msd_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws)
+            g = lambda i: msd.msd_dequant_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws)
+            f(0); g(0)
+            us_msd = time_calls(f, 2 * len(reps))
+            us_cmp = time_calls(g, 2 * len(reps))
+            out.append({"M": M, "K": K, "N": N, "msd_us": round(us_msd, 2), "dequant_us": round(us_cmp, 2),
+                        "speedup_vs_dequant": round(us_cmp / us_msd, 3)})
+        del reps, W
+        torch.cuda.empty_cache()
+    return out
+
+
+def run(want, msd, synth, time_calls, dev):
+    res = {}
+    legs = {"prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode}
+    for name, fn in legs.items():
+        if name in want:
+            try:
+                res[name] = fn(msd, synth, time_calls, dev)
+            except Exception as e:  # noqa: BLE001
+                res[name] = {"error": repr(e)}
+            torch.cuda.empty_cache()
+    return res
