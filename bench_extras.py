@@ -2,7 +2,8 @@
 
 Each leg times one C-ABI entry point on the shapes the benchmark spec lists for it, with HIP events
 on the launch stream, inputs resident in HBM and (for memory-bound shapes) weight / KV copies
-cycled so that the working set exceeds twice the 256 MB last-level cache.  Figures: time per
+cycled so that the working set exceeds twice the 256 MB last-level cache.  Microsecond-scale calls
+are marshalled once and replayed as HIP graphs (time_calls); millisecond-scale ones run eagerly.  Figures: time per
 call, algorithmic GB/s or executed/effective TOP/s, and the fraction of the MI355X peak that
 bounds the leg.  The comparison kernels (dequantise-then-BF16-MFMA) run beside the MSD kernels.
 """
@@ -13,6 +14,20 @@ HBM = 8000.0
 INT8_TOPS = 5000.0
 FP4_TFLOPS = 10100.0
 LLC = 256 << 20
+
+
+def _eager_us(fn, n):
+    """HIP-event time per call of n eager calls on the current stream (for millisecond-scale kernels)."""
+    st = torch.cuda.current_stream()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(st)
+    for i in range(n):
+        fn(i)
+    e1.record(st)
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
 
 
 def _bf16(bits, dev):
@@ -42,14 +57,14 @@ def leg_prefill(msd, synth, time_calls, dev):
         ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
         f = lambda i: msd.msd_gemm_w8a16(x, W, s, y=y, ws=ws)
         f(0)
-        us = time_calls(f, 3)
+        us = _eager_us(f, 3)
         rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "eff_TOPS": round(2.0 * M * K * N / us / 1e6, 1),
                "int8_mfma_frac": round(4.0 * M * K * N / us / 1e6 / INT8_TOPS, 4)}
         try:
             g = lambda i: msd.msd_dequant_gemm_w8a16(x, W, s, y=y, ws=ws)
             g(0)
-            us2 = time_calls(g, 2)
+            us2 = _eager_us(g, 2)
             rec["cmp_dequant_us"] = round(us2, 1)
             rec["speedup_vs_dequant"] = round(us2 / us, 3)
         except Exception as e:  # noqa: BLE001
@@ -74,17 +89,23 @@ def leg_w4(msd, synth, time_calls, dev):
             x = x.repeat(M // 64, 1).contiguous()
         y = torch.empty((M, N), dtype=torch.float32, device=dev)
         ws = torch.empty(msd.lib().msd_gemm_w4a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
-        f = lambda i: msd.msd_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws)
-        f(0)
-        us = time_calls(f, 2 * len(reps) if M <= 32 else 3)
+        f = lambda i: msd.msd_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws, prepare=M <= 32)
+        if M <= 32:
+            us = time_calls(f, 2 * len(reps))
+        else:
+            f(0)
+            us = _eager_us(f, 3)
         b = wbytes + 2 * M * K + 4 * M * N
         rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "GBps": round(b / us / 1e3, 1),
                "hbm_frac": round(b / us / 1e3 / HBM, 4), "exec_TFLOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
         try:
-            g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws)
-            g(0)
-            us2 = time_calls(g, 2 * len(reps) if M <= 32 else 2)
+            g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws, prepare=M <= 32)
+            if M <= 32:
+                us2 = time_calls(g, 2 * len(reps))
+            else:
+                g(0)
+                us2 = _eager_us(g, 2)
             rec["cmp_dequant_us"] = round(us2, 1)
             rec["speedup_vs_dequant"] = round(us2 / us, 3)
         except Exception as e:  # noqa: BLE001
@@ -110,8 +131,7 @@ def leg_attn(msd, synth, time_calls, dev):
         o = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
         ws = torch.empty(msd.lib().msd_attn_decode_int8kv_workspace_bytes(B, Hq, Hkv, d, L), dtype=torch.uint8,
                          device=dev)
-        f = lambda i: msd.msd_attn_decode_int8kv(q, *sets[i % n], msd.MSD_PER_TOKEN, out=o, ws=ws)
-        f(0)
+        f = lambda i: msd.msd_attn_decode_int8kv(q, *sets[i % n], msd.MSD_PER_TOKEN, out=o, ws=ws, prepare=True)
         us = time_calls(f, 4 * n)
         b = kvbytes + 8 * B * Hkv * L + 2 * B * Hq * d + 4 * B * Hq * d
         out.append({"B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "L": L, "us": round(us, 1),
@@ -133,9 +153,8 @@ def leg_cmp_decode(msd, synth, time_calls, dev):
             x = _bf16(synth.activations(synth.seed_for(1, M), M, K), dev)
             y = torch.empty((M, N), dtype=torch.float32, device=dev)
             ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
-            f = lambda i: msd.msd_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws)
-            g = lambda i: msd.msd_dequant_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws)
-            f(0); g(0)
+            f = lambda i: msd.msd_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws, prepare=True)
+            g = lambda i: msd.msd_dequant_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws, prepare=True)
             us_msd = time_calls(f, 2 * len(reps))
             us_cmp = time_calls(g, 2 * len(reps))
             out.append({"M": M, "K": K, "N": N, "msd_us": round(us_msd, 2), "dequant_us": round(us_cmp, 2),

@@ -106,6 +106,23 @@ def _out_code(dtype):
     raise TypeError("out dtype must be float32 or bfloat16")
 
 
+class Prepared:
+    """One C-ABI call with every argument marshalled once.  ``prepared()`` enqueues it again on the
+    stream it was prepared for (a few hundred nanoseconds of Python instead of ~10 us), which is what
+    tight loops and HIP-graph capture want.  Holds references to the tensors it points into."""
+
+    __slots__ = ("fn", "args", "keep", "name", "out")
+
+    def __init__(self, fn, args, keep, name, out):
+        self.fn, self.args, self.keep, self.name, self.out = fn, args, keep, name, out
+
+    def __call__(self):
+        rc = self.fn(*self.args)
+        if rc != 0:
+            raise MsdError(rc, self.name)
+        return self.out
+
+
 def msd_decompose(fmt, x):
     """x: bf16 [M][K] (row stride may exceed K).  Returns (q1, q2, scale) device tensors."""
     _dev(x, torch.bfloat16, "x")
@@ -125,7 +142,7 @@ def msd_decompose(fmt, x):
     return q1, q2, sc
 
 
-def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws):
+def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws, prepare=False):
     L = lib()
     M, K = x.shape
     if y is None:
@@ -149,41 +166,44 @@ def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws):
                   keep["acc1"].data_ptr() if "acc1" in keep else None,
                   keep["acc2"].data_ptr() if "acc2" in keep else None)
     ldx = x.stride(0) if M > 1 else max(K, x.stride(0))
-    rc = getattr(L, fn_name)(_ptr(x), M, K, ldx, *w_args, N, _ptr(y), _out_code(y.dtype), y.stride(0),
-                             _ptr(ws), ws.numel(), C.byref(tp) if tp is not None else None, _stream())
+    args = (_ptr(x), M, K, ldx, *w_args, N, _ptr(y), _out_code(y.dtype), y.stride(0), _ptr(ws), ws.numel(),
+            C.byref(tp) if tp is not None else None, _stream())
+    if prepare:
+        return Prepared(getattr(L, fn_name), args, (x, y, ws, keep, tp), fn_name, y)
+    rc = getattr(L, fn_name)(*args)
     _check(rc, fn_name)
     return (y, keep) if taps else y
 
 
-def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, ws=None):
+def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, ws=None, prepare=False):
     _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
     assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
     return _gemm_common("msd_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
-                        W.shape[0], out_dtype, taps, y, ws)
+                        W.shape[0], out_dtype, taps, y, ws, prepare)
 
 
-def msd_dequant_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, y=None, ws=None):
+def msd_dequant_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, y=None, ws=None, prepare=False):
     _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
     assert W.is_contiguous()
     return _gemm_common("msd_dequant_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x,
-                        (_ptr(W), _ptr(w_scale)), W.shape[0], out_dtype, False, y, ws)
+                        (_ptr(W), _ptr(w_scale)), W.shape[0], out_dtype, False, y, ws, prepare)
 
 
-def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None):
+def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None, prepare=False):
     _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
     assert W_fp4.is_contiguous() and W_e8m0.is_contiguous() and W_fp4.shape[1] * 2 == x.shape[1]
     return _gemm_common("msd_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x, (_ptr(W_fp4), _ptr(W_e8m0)),
-                        W_fp4.shape[0], out_dtype, taps, y, ws)
+                        W_fp4.shape[0], out_dtype, taps, y, ws, prepare)
 
 
-def msd_dequant_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws=None):
+def msd_dequant_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws=None, prepare=False):
     _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
     return _gemm_common("msd_dequant_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x,
-                        (_ptr(W_fp4), _ptr(W_e8m0)), W_fp4.shape[0], out_dtype, False, y, ws)
+                        (_ptr(W_fp4), _ptr(W_e8m0)), W_fp4.shape[0], out_dtype, False, y, ws, prepare)
 
 
 def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,
-                           taps=False, out=None, ws=None):
+                           taps=False, out=None, ws=None, prepare=False):
     _dev(q, torch.bfloat16, "q"); _dev(K, torch.int8, "K"); _dev(V, torch.int8, "V")
     _dev(k_scale, torch.float32, "k_scale"); _dev(v_scale, torch.float32, "v_scale")
     B, Hq, d = q.shape
@@ -205,8 +225,12 @@ def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, o
         tp = Taps(*(keep[k].data_ptr() for k in ("q1", "q2", "scale", "acc1", "acc2")))
     if kv_len is not None:
         _dev(kv_len, torch.int32, "kv_len")
-    rc = L.msd_attn_decode_int8kv(_ptr(q), _ptr(K), _ptr(V), _ptr(k_scale), _ptr(v_scale), scale_mode, B, Hq,
-                                  Hkv, d, _ptr(kv_len), Lmax, _ptr(out), _out_code(out.dtype), _ptr(ws),
-                                  ws.numel(), C.byref(tp) if tp is not None else None, _stream())
+    args = (_ptr(q), _ptr(K), _ptr(V), _ptr(k_scale), _ptr(v_scale), scale_mode, B, Hq, Hkv, d, _ptr(kv_len),
+            Lmax, _ptr(out), _out_code(out.dtype), _ptr(ws), ws.numel(),
+            C.byref(tp) if tp is not None else None, _stream())
+    if prepare:
+        return Prepared(L.msd_attn_decode_int8kv, args, (q, K, V, k_scale, v_scale, kv_len, out, ws, keep, tp),
+                        "msd_attn_decode_int8kv", out)
+    rc = L.msd_attn_decode_int8kv(*args)
     _check(rc, "msd_attn_decode_int8kv")
     return (out, keep) if taps else out

@@ -6,115 +6,21 @@
 // MXFP4:  one thread per 32-element block (no cross-lane reduction: the block max is the
 //         only reduction and beta needs none).  Writes the ABI format (4-bit codes) and/or
 //         the GEMM's internal operand format (FP6-E2M3 codes, 24 B per block in a 32 B slot).
+#include "decompose_int8_dev.hpp"
 #include "kernels.hpp"
 
 namespace msd {
 
 // ---------------------------------------------------------------- INT8
 constexpr int kDecThreads = 256;
-constexpr int kDecRegChunks = 4;  // 16-element chunks cached in registers per thread
-
-struct Chunk16 {
-  uint32_t w[8];  // 16 BF16 values
-};
-
-__device__ __forceinline__ Chunk16 load_chunk16(const uint16_t* p, bool aligned) {
-  Chunk16 c;
-  if (aligned) {
-    const uint4* q = reinterpret_cast<const uint4*>(p);
-    uint4 a = q[0], b = q[1];
-    c.w[0] = a.x; c.w[1] = a.y; c.w[2] = a.z; c.w[3] = a.w;
-    c.w[4] = b.x; c.w[5] = b.y; c.w[6] = b.z; c.w[7] = b.w;
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) c.w[i] = (uint32_t)p[2 * i] | ((uint32_t)p[2 * i + 1] << 16);
-  }
-  return c;
-}
-
-__device__ __forceinline__ float chunk_absmax(const Chunk16& c) {
-  float m = 0.f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    m = fmaxf(m, fabsf(__uint_as_float(c.w[i] << 16)));
-    m = fmaxf(m, fabsf(__uint_as_float(c.w[i] & 0xFFFF0000u)));
-  }
-  return m;
-}
-
-__device__ __forceinline__ void chunk_codes(const Chunk16& c, float alpha, float beta, uint4& o1,
-                                            uint4& o2) {
-  uint32_t a[4], b[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    uint32_t pa = 0, pb = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t w = c.w[j * 2 + (e >> 1)];
-      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-      int c1, c2;
-      int8_codes(x, alpha, beta, c1, c2);
-      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
-      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
-    }
-    a[j] = pa;
-    b[j] = pb;
-  }
-  o1 = make_uint4(a[0], a[1], a[2], a[3]);
-  o2 = make_uint4(b[0], b[1], b[2], b[3]);
-}
 
 __global__ __launch_bounds__(kDecThreads) void decompose_int8_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int8_t* __restrict__ q1,
     int8_t* __restrict__ q2, int64_t ldq, float* __restrict__ alpha_out, int aligned) {
   __shared__ float s_red[kDecThreads / kWave];
   const int64_t m = blockIdx.x;
-  const uint16_t* xr = x + m * ldx;
-  const int nchunks = K / 16;
-  Chunk16 cache[kDecRegChunks];
-  float mx = 0.f;
-#pragma unroll
-  for (int i = 0; i < kDecRegChunks; ++i) {
-    const int c = threadIdx.x + i * kDecThreads;
-    if (c < nchunks) {
-      cache[i] = load_chunk16(xr + c * 16, aligned);
-      mx = fmaxf(mx, chunk_absmax(cache[i]));
-    }
-  }
-  for (int c = threadIdx.x + kDecRegChunks * kDecThreads; c < nchunks; c += kDecThreads)
-    mx = fmaxf(mx, chunk_absmax(load_chunk16(xr + c * 16, aligned)));
-  mx = wave_max(mx);
-  if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-  const float alpha = __fdiv_rn(mx, 127.0f);
-  const float beta = __fdiv_rn(alpha, 254.0f);
-  if (threadIdx.x == 0) alpha_out[m] = alpha;
-  uint4* o1 = reinterpret_cast<uint4*>(q1 + m * ldq);
-  uint4* o2 = reinterpret_cast<uint4*>(q2 + m * ldq);
-  if (mx == 0.f) {  // all-zero row: zero codes, zero scales
-    for (int c = threadIdx.x; c < nchunks; c += kDecThreads) {
-      o1[c] = make_uint4(0, 0, 0, 0);
-      o2[c] = make_uint4(0, 0, 0, 0);
-    }
-    return;
-  }
-#pragma unroll
-  for (int i = 0; i < kDecRegChunks; ++i) {
-    const int c = threadIdx.x + i * kDecThreads;
-    if (c < nchunks) {
-      uint4 a, b;
-      chunk_codes(cache[i], alpha, beta, a, b);
-      o1[c] = a;
-      o2[c] = b;
-    }
-  }
-  for (int c = threadIdx.x + kDecRegChunks * kDecThreads; c < nchunks; c += kDecThreads) {
-    uint4 a, b;
-    chunk_codes(load_chunk16(xr + c * 16, aligned), alpha, beta, a, b);
-    o1[c] = a;
-    o2[c] = b;
-  }
+  decompose_row_int8_block<kDecThreads>(x + m * ldx, K, q1 + m * ldq, q2 + m * ldq, alpha_out + m,
+                                        aligned != 0, s_red);
 }
 
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,

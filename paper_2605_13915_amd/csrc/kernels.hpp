@@ -25,13 +25,15 @@ struct GemmW8Args {
   int32_t* acc1;  // nullable taps [M][N]
   int32_t* acc2;
   int64_t M, K, N;
-  // split-K scratch (nullable when unused): int32 partial sums [2][M][N] and tile counters
-  int32_t* part;
-  uint32_t* counters;
+  // single-launch decode (x == nullptr when the decomposition ran as its own kernel):
+  const uint16_t* x;  // [M][ldx] BF16 activations
+  int64_t ldx;
+  int x_aligned;     // rows of x are 16-byte aligned
+  int export_codes;  // also write q1/q2/alpha to the workspace (observation points)
 };
+// true when launch_gemm_w8 runs the decomposition itself (single launch)
+bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);
-// scratch the GEMM wants beyond q1/q2/alpha: bytes of split-K partials and counters
-void gemm_w8_scratch(int64_t M, int64_t K, int64_t N, size_t* part_bytes, size_t* counter_bytes);
 
 // ---- W4A16 (gemm_w4.hip)
 struct GemmW4Args {

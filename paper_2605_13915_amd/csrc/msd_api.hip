@@ -20,8 +20,7 @@ static bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintp
 
 // workspace layout of msd_gemm_w8a16
 struct W8Layout {
-  size_t q1, q2, alpha, part, counters, total;
-  size_t part_bytes, counter_bytes;
+  size_t q1, q2, alpha, total;
 };
 static W8Layout w8_layout(int64_t M, int64_t K, int64_t N) {
   W8Layout l{};
@@ -29,9 +28,6 @@ static W8Layout w8_layout(int64_t M, int64_t K, int64_t N) {
   l.q1 = off; off = align_up(off + (size_t)M * K, 256);
   l.q2 = off; off = align_up(off + (size_t)M * K, 256);
   l.alpha = off; off = align_up(off + (size_t)M * sizeof(float), 256);
-  gemm_w8_scratch(M, K, N, &l.part_bytes, &l.counter_bytes);
-  l.part = off; off = align_up(off + l.part_bytes, 256);
-  l.counters = off; off = align_up(off + l.counter_bytes, 256);
   l.total = off;
   return l;
 }
@@ -111,18 +107,18 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   a.M = M; a.K = K; a.N = N;
   a.acc1 = taps ? taps->acc1 : nullptr;
   a.acc2 = taps ? taps->acc2 : nullptr;
-  a.part = l.part_bytes ? (int32_t*)(ws + l.part) : nullptr;
-  a.counters = l.counter_bytes ? (uint32_t*)(ws + l.counters) : nullptr;
-  if (K > 0) {
+  if (gemm_w8_is_fused(M, K, N)) {
+    // one launch: the GEMM kernel decomposes the rows itself, under its own weight loads
+    a.x = (const uint16_t*)x_bf16;
+    a.ldx = ldx;
+    a.x_aligned = (aligned_to(x_bf16, 16) && ldx % 8 == 0) ? 1 : 0;
+    a.export_codes = (taps && (taps->q1 || taps->q2 || taps->scale)) ? 1 : 0;
+  } else if (K > 0) {
     int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
                                    (float*)a.alpha, s);
     if (rc) return rc;
   } else {
     int rc = fill_u32((uint32_t*)a.alpha, M, 0u, s);
-    if (rc) return rc;
-  }
-  if (l.counter_bytes) {
-    int rc = fill_u32(a.counters, (int64_t)(l.counter_bytes / 4), 0u, s);
     if (rc) return rc;
   }
   int rc = launch_gemm_w8(a, s);
