@@ -10,13 +10,15 @@
 // 16 consecutive k bytes of group l/16; B holds column l%16, same k bytes; D holds column
 // l%16, rows 4*(l/16)+r in register r.  A = stacked activation codes, B = W rows.
 //
-// Two kernels:
+// Kernels:
 //   decode : 2M <= 64.  Up to four 16-row A fragments carry [x1; x2].  W goes HBM -> registers
 //            in MFMA layout directly (each lane reads 16 contiguous bytes of one W row), the K
 //            range is split over the waves of a workgroup and reduced through LDS.  For M <= 8
 //            the kernel also decomposes the activations itself, under its own weight loads:
 //            one launch per call and no code buffer in HBM.
-//   tiled  : any M.  LDS-staged tiles, 4 waves, register-local merge of the two components.
+//   large  : any M.  32x32x32 MFMA, LDS-staged tiles (swizzled), 4 waves, register-local merge
+//            of the two components; for prefill-sized problems a 256x256 tile filled by
+//            asynchronous global->LDS loads four stages deep.
 #include <cstdlib>
 
 #include "decompose_int8_dev.hpp"
@@ -258,124 +260,159 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
   }
 }
 
-// ------------------------------------------------------------------ tiled (any M)
-// Workgroup tile: BMH activation rows (both components -> 2*BMH stacked rows) x BN weight
-// rows, K step 64.  Waves are laid out WM x WN; each wave owns TMH = BMH/WM activation rows
-// (both components, so the merge is register-local) and TN = BN/WN output channels.
-constexpr int kBK = 64;
-constexpr int kLdsStride = kBK + 16;  // +16 B: consecutive rows land in distinct 16 B bank groups
+// ------------------------------------------------------------------ large tiles (prefill)
+// v_mfma_i32_32x32x32_i8 (A: row l%32, 16 k bytes of group l/32; D: column l%32, row
+// 8*(r/4) + 4*(l/32) + r%4 in register r), BK = 64, LDS double buffering with one barrier per
+// K step, global -> register -> LDS staging with the next tile's loads issued before the
+// current tile's MFMAs.  LDS rows are 64 B; the 16-byte chunk index is XOR-swizzled with
+// (row>>2)&3 so that the ds_read_b128 of sixteen consecutive rows (one 256-byte LDS pass) hit
+// sixteen distinct 16-byte bank groups (measured: (row>>1)&3 left a 2-way conflict, half of the
+// LDS cycles).
+// Each wave owns both components of its activation rows, so the merge stays in registers.
+// Workgroup ids are remapped so that each XCD (ids congruent mod 8) walks a contiguous range
+// of tiles in groups of kGroupM tile rows: neighbours in an XCD's L2 share W and A tiles.
+__device__ __forceinline__ v16i mfma32(v4i a, v4i b, v16i c) {
+  return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+
+constexpr int kGroupM = 8;
 
 template <int BMH, int BN, int WM, int WN>
-struct TiledCfg {
-  static constexpr int kThreads = WM * WN * 64;
-  static constexpr int kRowsA = 2 * BMH;
-  static constexpr int kTMH = BMH / WM;
-  static constexpr int kTN = BN / WN;
-  static constexpr int kFragM = kTMH / 16;  // per component
-  static constexpr int kFragN = kTN / 16;
-  static constexpr int kChunksA = kRowsA * (kBK / 16);
-  static constexpr int kChunksB = BN * (kBK / 16);
-  static constexpr int kLdA = (kChunksA + kThreads - 1) / kThreads;
-  static constexpr int kLdB = (kChunksB + kThreads - 1) / kThreads;
-};
-
-template <int BMH, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_w8_tiled_kernel(GemmW8Args a) {
-  using C = TiledCfg<BMH, BN, WM, WN>;
-  __shared__ __attribute__((aligned(16))) int8_t sA[C::kRowsA * kLdsStride];
-  __shared__ __attribute__((aligned(16))) int8_t sB[BN * kLdsStride];
+__global__ __launch_bounds__(WM * WN * 64) void gemm_w8_mfma32_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+  constexpr int THREADS = WM * WN * 64;
+  constexpr int ROWS_A = 2 * BMH;
+  constexpr int TMH = BMH / WM, TN = BN / WN;
+  constexpr int FM = TMH / 32, FN = TN / 32;  // fragments per component / per wave column range
+  constexpr int LA = ROWS_A * 4 / THREADS, LB = BN * 4 / THREADS;
+  static_assert(ROWS_A * 4 % THREADS == 0 && BN * 4 % THREADS == 0, "tile/threads mismatch");
+  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+  int8_t* sA = smem;                    // [2][ROWS_A][64]
+  int8_t* sB = smem + 2 * ROWS_A * 64;  // [2][BN][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int row16 = lane & 15, g = lane >> 4;
+  const int l32 = lane & 31, kg = lane >> 5;
   const int64_t M = a.M, K = a.K, N = a.N;
-  const int64_t m0 = (int64_t)blockIdx.y * BMH;
-  const int64_t n0 = (int64_t)blockIdx.x * BN;
-  const int ks0 = 0;
-  const int ks1 = (int)((K + kBK - 1) / kBK);
-  const v4i zero = {0, 0, 0, 0};
+  // ---- tile of this workgroup (XCD-contiguous, grouped along M)
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  {
+    const int per_xcd = (total + 7) / 8;
+    const int logical = (id % 8) * per_xcd + id / 8;
+    id = logical;
+  }
+  if (id >= total) return;
+  const int group = id / (kGroupM * tiles_n);
+  const int first_m = group * kGroupM;
+  const int rows_in_group = min(kGroupM, tiles_m - first_m);
+  const int in_group = id - group * kGroupM * tiles_n;
+  const int tm = first_m + in_group % rows_in_group;
+  const int tn = in_group / rows_in_group;
+  const int64_t m0 = (int64_t)tm * BMH, n0 = (int64_t)tn * BN;
+  const v4i zero4 = {0, 0, 0, 0};
 
-  // global -> register staging of one K step
-  v4i ra[C::kLdA], rb[C::kLdB];
-  auto load_tiles = [&](int ks) {
-    const int64_t k0 = (int64_t)ks * kBK;
+  const int8_t* ga[LA];
+  int oa[LA];
+  bool va[LA];
 #pragma unroll
-    for (int i = 0; i < C::kLdA; ++i) {
-      const int c = tid + i * C::kThreads;
-      const int r = c >> 2, kc = (c & 3) * 16;
-      v4i v = zero;
-      if (c < C::kChunksA) {
-        const int comp = r / BMH;
-        const int64_t m = m0 + (r - comp * BMH);
-        if (m < M && k0 + kc < K) v = ldg16((comp ? a.q2 : a.q1) + m * a.ldq + k0 + kc);
-      }
-      ra[i] = v;
-    }
+  for (int i = 0; i < LA; ++i) {
+    const int c = tid + i * THREADS, r = c >> 2, ch = c & 3;
+    const int comp = r / BMH;
+    const int64_t m = m0 + (r - comp * BMH);
+    va[i] = m < M;
+    ga[i] = (comp ? a.q2 : a.q1) + min(m, M - 1) * a.ldq + ch * 16;
+    oa[i] = r * 64 + ((ch ^ ((r >> 2) & 3)) << 4);
+  }
+  const int8_t* gb[LB];
+  int ob[LB];
+  bool vb[LB];
 #pragma unroll
-    for (int i = 0; i < C::kLdB; ++i) {
-      const int c = tid + i * C::kThreads;
-      const int r = c >> 2, kc = (c & 3) * 16;
-      v4i v = zero;
-      if (c < C::kChunksB) {
-        const int64_t n = n0 + r;
-        if (n < N && k0 + kc < K) v = ldg16_stream(a.W + n * K + k0 + kc);
-      }
-      rb[i] = v;
-    }
+  for (int i = 0; i < LB; ++i) {
+    const int c = tid + i * THREADS, r = c >> 2, ch = c & 3;
+    const int64_t n = n0 + r;
+    vb[i] = n < N;
+    gb[i] = a.W + min(n, N - 1) * K + ch * 16;
+    ob[i] = r * 64 + ((ch ^ ((r >> 2) & 3)) << 4);
+  }
+  const int kch = (tid & 3) * 16;  // k offset of this thread's chunks inside a K step
+  v4i ra[LA], rb[LB];
+  auto gload = [&](int kt) {
+    const int64_t k0 = (int64_t)kt * 64;
+    const bool kok = k0 + kch < K;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) ra[i] = (va[i] && kok) ? ldg16(ga[i] + k0) : zero4;
+#pragma unroll
+    for (int i = 0; i < LB; ++i) rb[i] = (vb[i] && kok) ? ldg16(gb[i] + k0) : zero4;
   };
-  auto store_tiles = [&]() {
+  auto sstore = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < C::kLdA; ++i) {
-      const int c = tid + i * C::kThreads;
-      if (c < C::kChunksA) *reinterpret_cast<v4i*>(&sA[(c >> 2) * kLdsStride + (c & 3) * 16]) = ra[i];
-    }
+    for (int i = 0; i < LA; ++i) *reinterpret_cast<v4i*>(sA + buf * ROWS_A * 64 + oa[i]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < C::kLdB; ++i) {
-      const int c = tid + i * C::kThreads;
-      if (c < C::kChunksB) *reinterpret_cast<v4i*>(&sB[(c >> 2) * kLdsStride + (c & 3) * 16]) = rb[i];
-    }
+    for (int i = 0; i < LB; ++i) *reinterpret_cast<v4i*>(sB + buf * BN * 64 + ob[i]) = rb[i];
   };
 
-  v4i acc[2][C::kFragM][C::kFragN];
+  v16i acc[2][FM][FN];
 #pragma unroll
   for (int c = 0; c < 2; ++c)
 #pragma unroll
-    for (int i = 0; i < C::kFragM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int j = 0; j < C::kFragN; ++j) acc[c][i][j] = zero;
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][i][j][r] = 0;
 
-  if (ks0 < ks1) load_tiles(ks0);
-  for (int ks = ks0; ks < ks1; ++ks) {
-    __syncthreads();  // previous step's LDS reads are done
-    store_tiles();
+  // fragment addresses inside a buffer (row part; the chunk part depends on the K half-step)
+  int fa_row[2][FM], fb_row[FN];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa_row[c][i] = c * BMH + wm * TMH + 32 * i + l32;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) fb_row[j] = wn * TN + 32 * j + l32;
+
+  const int KT = (int)((K + 63) / 64);
+  if (KT > 0) {
+    gload(0);
+    sstore(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) gload(kt + 1);
+    const int8_t* bA = sA + buf * ROWS_A * 64;
+    const int8_t* bB = sB + buf * BN * 64;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int chunk = 2 * s + kg;
+      v4i fb[FN];
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        fb[j] = *reinterpret_cast<const v4i*>(bB + fb_row[j] * 64 + ((chunk ^ ((fb_row[j] >> 2) & 3)) << 4));
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+          const v4i fa =
+              *reinterpret_cast<const v4i*>(bA + fa_row[c][i] * 64 + ((chunk ^ ((fa_row[c][i] >> 2) & 3)) << 4));
+#pragma unroll
+          for (int j = 0; j < FN; ++j) acc[c][i][j] = mfma32(fa, fb[j], acc[c][i][j]);
+        }
+    }
+    if (kt + 1 < KT) sstore(buf ^ 1);
     __syncthreads();
-    if (ks + 1 < ks1) load_tiles(ks + 1);
-    v4i fb[C::kFragN];
-#pragma unroll
-    for (int j = 0; j < C::kFragN; ++j)
-      fb[j] = *reinterpret_cast<const v4i*>(&sB[(wn * C::kTN + 16 * j + row16) * kLdsStride + 16 * g]);
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int i = 0; i < C::kFragM; ++i) {
-        const v4i fa = *reinterpret_cast<const v4i*>(
-            &sA[(c * BMH + wm * C::kTMH + 16 * i + row16) * kLdsStride + 16 * g]);
-#pragma unroll
-        for (int j = 0; j < C::kFragN; ++j) acc[c][i][j] = mfma16(fa, fb[j], acc[c][i][j]);
-      }
   }
 
   // ---- dual-scale epilogue
 #pragma unroll
-  for (int i = 0; i < C::kFragM; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int64_t m = m0 + wm * C::kTMH + 16 * i + 4 * g + r;
+    for (int r = 0; r < 16; ++r) {
+      const int64_t m = m0 + wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
       if (m >= M) continue;
       const float alpha = a.alpha[m];
       const float beta = __fdiv_rn(alpha, 254.0f);
 #pragma unroll
-      for (int j = 0; j < C::kFragN; ++j) {
-        const int64_t n = n0 + wn * C::kTN + 16 * j + row16;
+      for (int j = 0; j < FN; ++j) {
+        const int64_t n = n0 + wn * TN + 32 * j + l32;
         if (n >= N) continue;
         const int a1 = acc[0][i][j][r], a2 = acc[1][i][j][r];
         store_out(a.y, a.out_bf16, m * a.ldy + n, merge_scales(a.w_scale[n], alpha, beta, a1, a2));
@@ -383,6 +420,243 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_tiled_kernel(GemmW8Args 
         if (a.acc2) a.acc2[m * N + n] = a2;
       }
     }
+}
+
+// ------------------------------------------------------------------ large tiles, asynchronous LDS fill
+// Same tiling and fragment layout as gemm_w8_mfma32_kernel, but the tiles go HBM/L2 -> LDS
+// with global_load_lds_dwordx4 (no staging registers, no ds_write), NS stages deep: while the
+// MFMAs of K step t run, the loads of steps t+1 .. t+NS-2 are in flight and step t+NS-1 is
+// being issued.  One s_barrier per K step; the wait before it is an explicit
+// s_waitcnt vmcnt(8*(NS-2)): a wave issues 8 loads per step and they complete in order.
+// The loads are written as inline asm on purpose: the compiler does not see them write LDS
+// and therefore does not serialise every ds_read behind the youngest load.
+// Each load instruction fills 1 KB of LDS = 16 rows of 64 B in lane order, so a lane fetches
+// the global chunk whose swizzled position it owns.  Rows past M / N are clamped to the last
+// valid row (their results are never stored).  Requires K % 64 == 0.
+__device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm_barrier() {
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+  else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+}
+
+template <int NS>
+__global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+  constexpr int BMH = 128, BN = 256, ROWS_A = 256, TMH = 64, TN = 128, FM = 2, FN = 4;
+  constexpr int STAGE = (ROWS_A + BN) * 64;  // 32 KB
+  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, kg = lane >> 5;
+  const int64_t M = a.M, K = a.K, N = a.N;
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  {
+    const int per_xcd = (total + 7) / 8;
+    id = (id % 8) * per_xcd + id / 8;
+  }
+  if (id >= total) return;
+  const int group = id / (kGroupM * tiles_n);
+  const int first_m = group * kGroupM;
+  const int rows_in_group = min(kGroupM, tiles_m - first_m);
+  const int in_group = id - group * kGroupM * tiles_n;
+  const int tm = first_m + in_group % rows_in_group;
+  const int tn = in_group / rows_in_group;
+  const int64_t m0 = (int64_t)tm * BMH, n0 = (int64_t)tn * BN;
+
+  // ---- this wave's 8 load instructions per stage: waves 0,1 fill A (16 blocks of 16 rows), waves 2,3 fill B
+  const int rr = lane >> 2, pc = lane & 3;
+  const int lc = pc ^ ((rr >> 2) & 3);  // logical chunk this lane fetches
+  const bool fillsA = wave < 2;
+  uint32_t voff[8];
+  const int8_t* gbase[8];
+  uint32_t ldst[8];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int blk = (wave & 1) * 8 + q;
+    if (fillsA) {
+      const int comp = blk >> 3;
+      const int64_t mrow = min(m0 + (blk & 7) * 16 + rr, M - 1);
+      voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
+      gbase[q] = (comp ? a.q2 : a.q1) + m0 * a.ldq;
+      ldst[q] = lds0 + blk * 1024;
+    } else {
+      const int64_t nrow = min(n0 + blk * 16 + rr, N - 1);
+      voff[q] = (uint32_t)((nrow - n0) * K + lc * 16);
+      gbase[q] = a.W + n0 * K;
+      ldst[q] = lds0 + ROWS_A * 64 + blk * 1024;
+    }
+  }
+  auto issue = [&](int kt) {
+    const int64_t k0 = (int64_t)kt * 64;
+    const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) lds_dma16(gbase[q] + k0, voff[q], ldst[q] + sb);
+  };
+
+  v16i acc[2][FM][FN];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][i][j][r] = 0;
+
+  int fa_off[2][FM][2], fb_off[FN][2];  // byte offset inside a stage for K half-step 0 / 1
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int row = c * BMH + wm * TMH + 32 * i + l32;
+        fa_off[c][i][s] = row * 64 + (((2 * s + kg) ^ ((row >> 2) & 3)) << 4);
+      }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int row = wn * TN + 32 * j + l32;
+      fb_off[j][s] = ROWS_A * 64 + row * 64 + (((2 * s + kg) ^ ((row >> 2) & 3)) << 4);
+    }
+  }
+
+  const int KT = (int)(K / 64);
+  auto stage_ptr = [&](int kt) { return smem + (kt % NS) * STAGE; };
+  auto load_frags = [&](const int8_t* st, int s, v4i (&fa)[4], v4i (&fb)[4]) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const v4i*>(st + fb_off[j][s]);
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa[c * FM + i] = *reinterpret_cast<const v4i*>(st + fa_off[c][i][s]);
+  };
+  auto mfma_block = [&](const v4i (&fa)[4], const v4i (&fb)[4]) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[c][i][j] = mfma32(fa[c * FM + i], fb[j], acc[c][i][j]);
+  };
+  // wait until tile t has landed (its younger in-flight tiles may stay outstanding), then barrier
+  auto wait_tile = [&](int t, int newest_issued) {
+    const int younger = newest_issued - t;
+    if (younger >= 2) wait_vm_barrier<16>();
+    else if (younger == 1) wait_vm_barrier<8>();
+    else wait_vm_barrier<0>();
+  };
+  static_assert(NS == 3 || NS == 4, "stage count");
+  // Software pipeline: the fragments of K half-step (kt,1) are fetched under the MFMAs of (kt,0),
+  // those of (kt+1,0) under the MFMAs of (kt,1).  The barrier for tile kt+1 sits between the two
+  // MFMA blocks of tile kt; after it the stage of tile kt-1 is free and is refilled at once.
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < KT) issue(t);
+  v4i fa0[4], fb0[4], fa1[4], fb1[4];
+  if (KT > 0) {
+    wait_tile(0, min(KT - 1, NS - 2));
+    load_frags(stage_ptr(0), 0, fa0, fb0);
+  }
+  for (int kt = 0; kt + 1 < KT; ++kt) {
+    load_frags(stage_ptr(kt), 1, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
+    if (kt + NS - 1 < KT) issue(kt + NS - 1);
+    load_frags(stage_ptr(kt + 1), 0, fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block(fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (KT > 0) {  // last tile: nothing left to prefetch
+    load_frags(stage_ptr(KT - 1), 1, fa1, fb1);
+    mfma_block(fa0, fb0);
+    mfma_block(fa1, fb1);
+  }
+
+  // ---- dual-scale epilogue.  alpha and beta of the tile's 128 rows go through LDS (free now), the
+  // output is produced one (fragment, register) row at a time so that the compiler does not pull
+  // all 256 accumulators into VGPRs at once.
+  __syncthreads();
+  float* s_ab = reinterpret_cast<float*>(smem);  // [0..127] alpha, [128..255] beta
+  if (tid < BMH) {
+    const int64_t m = m0 + tid;
+    const float al = m < M ? a.alpha[m] : 0.f;
+    s_ab[tid] = al;
+    s_ab[BMH + tid] = __fdiv_rn(al, 254.0f);
+  }
+  __syncthreads();
+  float sw[FN];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int64_t n = n0 + wn * TN + 32 * j + l32;
+    sw[j] = n < N ? a.w_scale[n] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int lr = wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
+      const int64_t m = m0 + lr;
+      const float alpha = s_ab[lr], beta = s_ab[BMH + lr];
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int64_t n = n0 + wn * TN + 32 * j + l32;
+          if (n >= N) continue;
+          const int a1 = acc[0][i][j][r], a2 = acc[1][i][j][r];
+          store_out(a.y, a.out_bf16, m * a.ldy + n, merge_scales(sw[j], alpha, beta, a1, a2));
+          if (a.acc1) a.acc1[m * N + n] = a1;
+          if (a.acc2) a.acc2[m * N + n] = a2;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int NS>
+static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
+  const int tiles_m = (int)cdiv(a.M, 128), tiles_n = (int)cdiv(a.N, 256);
+  const int total = tiles_m * tiles_n;
+  const int grid = ((total + 7) / 8) * 8;
+  const size_t lds = (size_t)NS * 512 * 64;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<NS>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_w8_dma_kernel<NS>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+  return MSD_OK;
+}
+
+template <int BMH, int BN, int WM, int WN>
+static int launch_mfma32(const GemmW8Args& a, hipStream_t stream) {
+  const int tiles_m = (int)cdiv(a.M, BMH), tiles_n = (int)cdiv(a.N, BN);
+  const int total = tiles_m * tiles_n;
+  const int grid = ((total + 7) / 8) * 8;  // every XCD gets the same number of slots
+  const size_t lds = (size_t)2 * (2 * BMH + BN) * 64;
+  static bool attr_set = false;
+  if (!attr_set && lds > 64 * 1024) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_mfma32_kernel<BMH, BN, WM, WN>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_w8_mfma32_kernel<BMH, BN, WM, WN>), dim3(grid), dim3(WM * WN * 64), lds, stream, a,
+                     tiles_m, tiles_n);
+  return MSD_OK;
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -420,7 +694,6 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   static const int tune = getenv("MSD_TUNE_W8") ? atoi(getenv("MSD_TUNE_W8")) : 0;
   int rc = MSD_OK;
   const bool wide = cdiv(N, 16) > 512;  // many column tiles: widen the workgroup tile (measured)
-  (void)tune;
   if (a.x != nullptr) {  // the caller asked for the single-launch path (gemm_w8_is_fused)
     rc = launch_decode<4, 8, 1, 1, true>(a, stream);
   } else if (2 * M <= 16) {
@@ -429,13 +702,13 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     rc = launch_decode<8, 4, 2, 2, false>(a, stream);
   } else if (2 * M <= 64) {
     rc = wide ? launch_decode<8, 2, 4, 4, false>(a, stream) : launch_decode<8, 4, 4, 1, false>(a, stream);
-  } else if (cdiv(M, 64) * cdiv(N, 128) < 256) {
-    // few, tall tiles: narrow the N tile so that a decode-sized problem still covers the chip
-    const dim3 grid((unsigned)cdiv(N, 32), (unsigned)cdiv(M, 64));
-    hipLaunchKernelGGL((gemm_w8_tiled_kernel<64, 32, 4, 1>), grid, dim3(256), 0, stream, a);
+  } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
+    // few tiles (decode with a large batch): small tiles so that the problem covers more CUs (measured)
+    rc = launch_mfma32<64, 64, 2, 2>(a, stream);
+  } else if (a.K % 64 == 0 && a.K >= 64 && tune != 3) {
+    rc = launch_dma<4>(a, stream);
   } else {
-    const dim3 grid((unsigned)cdiv(N, 128), (unsigned)cdiv(M, 64));
-    hipLaunchKernelGGL((gemm_w8_tiled_kernel<64, 128, 2, 2>), grid, dim3(256), 0, stream, a);
+    rc = launch_mfma32<128, 256, 2, 2>(a, stream);
   }
   if (rc) return rc;
   MSD_LAUNCH_CHECK();

@@ -57,6 +57,9 @@ SHAPES = [
     (40, 1040, 200, 1),        # ragged tiled, several M tiles
     (130, 512, 300, 1),        # larger-tile kernel with ragged tails
     (128, 4096, 1024, 1),
+    (300, 1040, 520, 1),       # several large tiles, ragged in M, N and K
+    (257, 256, 777, 0),
+    (1100, 512, 4200, 1),      # >= 128 large tiles: the asynchronous-LDS-fill kernel, ragged M and N
 ]
 
 
