@@ -1,0 +1,76 @@
+// Device code of the two-pass MXFP4 block decomposition (paper Sec. 3.2.1, Alg. 2), shared by
+// the stand-alone decomposition kernel and by the single-launch W4A16 decode GEMM.
+#pragma once
+#include "msd_common.hpp"
+
+namespace msd {
+
+// Exponent e of alpha = 2^e for a block with max-abs mb: smallest e with mb <= 1.859375 * 2^e,
+// read off the fp32 fields (1.859375 has mantissa field 0x6E0000); clamped to [-123, 127].
+__device__ __forceinline__ int mx_alpha_exponent(float mb) {
+  const uint32_t u = __float_as_uint(mb);
+  int e = (int)(u >> 23) - 127;
+  if ((u & 0x7FFFFFu) > 0x6E0000u) e += 1;
+  return min(max(e, -123), 127);
+}
+
+__device__ __forceinline__ float pow2f(int e) {  // e in [-126, 127]
+  return __uint_as_float((uint32_t)(e + 127) << 23);
+}
+
+// 32 BF16 values of one block -> integer grid codes k1, k2 (value k/4) and exponent e.
+__device__ __forceinline__ int mx_block_codes(const uint32_t (&w)[16], int (&k1)[32], int (&k2)[32]) {
+  float mb = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    mb = fmaxf(mb, fabsf(__uint_as_float(w[i] << 16)));
+    mb = fmaxf(mb, fabsf(__uint_as_float(w[i] & 0xFFFF0000u)));
+  }
+  const int e = mx_alpha_exponent(mb);
+  const float up = pow2f(2 - e);    // 4/alpha
+  const float down = pow2f(e - 2);  // alpha/4
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const float x = (i & 1) ? __uint_as_float(w[i >> 1] & 0xFFFF0000u) : __uint_as_float(w[i >> 1] << 16);
+    const float a = fminf(fmaxf(rintf(x * up), -7.f), 7.f);
+    const float r = __fmaf_rn(-a, down, x);  // exact
+    const float b = fminf(fmaxf(rintf(r * up * 16.0f), -7.f), 7.f);
+    k1[i] = (int)a;
+    k2[i] = (int)b;
+  }
+  return e;
+}
+
+__device__ __forceinline__ uint32_t nibble4(int k) {  // sign-magnitude, -0 -> +0
+  return k < 0 ? (8u | (uint32_t)(-k)) : (uint32_t)k;
+}
+__device__ __forceinline__ uint32_t e2m3_code(int k) {  // value k/4 as FP6 E2M3: magnitude field 2|k|
+  return k < 0 ? (32u | (uint32_t)(-2 * k)) : (uint32_t)(2 * k);
+}
+
+// Pack 32 six-bit codes into 6 dwords, element i at bits [6i, 6i+6).
+__device__ __forceinline__ void pack_fp6(const int (&k)[32], uint32_t (&out)[6]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {  // 16 codes -> 96 bits -> 3 dwords
+    uint64_t lo = 0;             // bits 0..63
+    uint32_t hi = 0;             // bits 64..95
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint64_t c = e2m3_code(k[h * 16 + i]);
+      const int bit = 6 * i;
+      if (bit + 6 <= 64) {
+        lo |= c << bit;
+      } else if (bit >= 64) {
+        hi |= (uint32_t)c << (bit - 64);
+      } else {  // straddles bit 64 (i = 10: bits 60..65)
+        lo |= c << bit;
+        hi |= (uint32_t)(c >> (64 - bit));
+      }
+    }
+    out[h * 3 + 0] = (uint32_t)lo;
+    out[h * 3 + 1] = (uint32_t)(lo >> 32);
+    out[h * 3 + 2] = hi;
+  }
+}
+
+}  // namespace msd

@@ -12,64 +12,56 @@
 //
 // MFMA layout: lane l holds row/column l%16 and one 32-element K block; the scale byte of a
 // lane applies to that block.  Which block a lane group takes is free as long as A and B
-// agree: over a super-step of 16 blocks, lane group g = l/16 takes blocks 4g..4g+3, so each
-// lane reads 64 contiguous bytes of W and one dword of four scale bytes, and MFMA u
-// (u = 0..3) consumes block 4g+u with scale byte u selected by op_sel.
+// agree: over a super-step of 16 blocks, MFMA u (u = 0..3) gives lane group g = l/16 block
+// 4u+g, so the four lanes of a row read 64 contiguous weight bytes per load instruction
+// (measured: the transposed assignment 4g+u, 16 bytes out of every 64 per instruction, streamed
+// 30 % slower).  The 16 scale bytes of a row and super-step come as one 16-byte load; a lane
+// shifts its byte (4u+g) down to bits 7:0.
+#include <cstdlib>
+
+#include "decompose_mxfp4_dev.hpp"
 #include "kernels.hpp"
 
 namespace msd {
 
-template <int SEL>
 __device__ __forceinline__ v4f mfma_scaled(v8i a, v8i b, v4f c, int sa, int sb) {
-  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); scale byte SEL of sa / sb
-  return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 2, 4, SEL, sa, SEL, sb);
+  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); E8M0 scales in byte 0 of sa / sb
+  return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 2, 4, 0, sa, 0, sb);
 }
 
-struct ABlock4 {  // four consecutive FP6 blocks of one row (6 dwords each) and their scale bytes
-  v8i blk[4];
-  int scale;
-};
-
-// rows [m0, m0+16): lane (row = l%16, g = l/16) loads blocks [b0 + 4g, +4) of row m0+row
-__device__ __forceinline__ void load_a(const uint32_t* __restrict__ q, const uint8_t* __restrict__ e,
-                                       int64_t M, int64_t KB, int64_t m, int64_t b, bool fast,
-                                       ABlock4& out) {
-  const v8i zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-  for (int u = 0; u < 4; ++u) out.blk[u] = zero;
-  out.scale = 0x7F7F7F7F;
-  if (m >= M) return;
-  const uint32_t* p = q + (m * KB + b) * 8;
-  const uint8_t* pe = e + m * KB + b;
-  if (fast) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint4 lo = *reinterpret_cast<const uint4*>(p + 8 * u);
-      const uint2 hi = *reinterpret_cast<const uint2*>(p + 8 * u + 4);
-      out.blk[u] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
-    }
-    out.scale = *reinterpret_cast<const int*>(pe);
-  } else {
-    uint32_t sc = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      uint32_t byte = 0x7F;
-      if (b + u < KB) {
-        const uint4 lo = *reinterpret_cast<const uint4*>(p + 8 * u);
-        const uint2 hi = *reinterpret_cast<const uint2*>(p + 8 * u + 4);
-        out.blk[u] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
-        byte = pe[u];
-      }
-      sc |= byte << (8 * u);
-    }
-    out.scale = (int)sc;
-  }
+// byte 4*d+b of the 16 scale bytes sc[0..3] of a super-step, in bits 7:0
+__device__ __forceinline__ int scale_byte(const v4i& sc, int d, int b) {
+  const uint32_t w = d == 0 ? sc[0] : d == 1 ? sc[1] : d == 2 ? sc[2] : sc[3];
+  return (int)((w >> (8 * b)) & 0xFFu);
 }
 
-// One workgroup: rows [m0, m0 + 16*RT) x 16 output channels; WAVES waves split K.
-template <int WAVES, int RT>
+__device__ __forceinline__ v8i load_fp6_slot(const uint32_t* p) {  // 24 B of a 32 B slot (global)
+  const uint4 lo = *reinterpret_cast<const uint4*>(p);
+  const uint2 hi = *reinterpret_cast<const uint2*>(p + 4);
+  return v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+}
+__device__ __forceinline__ v8i load_fp6_lds(const uint8_t* p) {  // 24 B, 8-byte aligned (LDS)
+  const uint2* q = reinterpret_cast<const uint2*>(p);
+  const uint2 x0 = q[0], x1 = q[1], x2 = q[2];
+  return v8i{(int)x0.x, (int)x0.y, (int)x1.x, (int)x1.y, (int)x2.x, (int)x2.y, 0, 0};
+}
+
+// One workgroup: rows [m0, m0 + 16*RT) x 16 output channels; WAVES waves split K in super-steps
+// of 16 blocks.  Per batch of U super-steps a wave first issues all its weight loads (HBM ->
+// registers in B-operand layout), then fetches the activation operands, then runs the MFMAs.
+//
+// SELF (M <= 2, RT = 1): the kernel decomposes the activations itself (Alg. 2) -- the block
+// decomposition needs no reduction beyond the 32-element block, so each wave handles exactly the
+// blocks of its own K range, one block per lane, into wave-private LDS, under its own weight
+// loads.  One launch per call, nothing materialised in HBM.
+// FAST: K is a whole number of super-steps and the scale arrays are 16-byte aligned, so no load in
+// the main loop is predicated per lane (predicated loads do not batch: measured 25 % slower).
+// Rows past M are clamped to the last row (their results are never stored).
+template <int WAVES, int U, int RT, bool SELF, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a) {
+  constexpr bool CONTIG = true;
   __shared__ float s_part[WAVES][RT][4][64];
+  extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];  // SELF: per wave [2][M][bpw][24 B] + [M][bpw]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = lane & 15, g = lane >> 4;
   const int64_t M = a.M, N = a.N, KB = a.K / 32;
@@ -77,55 +69,131 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
   const int64_t m0 = (int64_t)blockIdx.y * 16 * RT;
   const int64_t supers = (KB + 15) / 16;  // super-steps of 16 blocks (512 k)
   const int64_t per = (supers + WAVES - 1) / WAVES;
-  const int64_t s0 = wave * per, s1 = min(supers, s0 + per);
-  const bool fast = (KB % 16) == 0;  // no ragged super-step, dword-aligned scale rows
+  const int64_t s0 = min((int64_t)wave * per, supers), s1 = min(supers, s0 + per);
+  constexpr bool fast = FAST;
   const int64_t wrow = min(n0 + row, N - 1);
   const uint8_t* wp = a.W + wrow * (KB * 16);
   const uint8_t* wep = a.We + wrow * KB;
   const v8i zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const v4i one16 = {0x7F7F7F7F, 0x7F7F7F7F, 0x7F7F7F7F, 0x7F7F7F7F};
   v4f acc[RT];
 #pragma unroll
   for (int f = 0; f < RT; ++f) acc[f] = v4f{0.f, 0.f, 0.f, 0.f};
-  for (int64_t s = s0; s < s1; ++s) {
-    const int64_t b = s * 16 + 4 * g;  // first of this lane's four blocks
-    v8i wb[4];
-    int wscale;
-    if (fast) {
+  // SELF: wave-private LDS for the blocks [s0*16, s1*16) of every row
+  const int bpw = (int)(per * 16);  // block slots per row and wave
+  uint8_t* my_q = s_dyn + (size_t)wave * ((size_t)2 * M * bpw * 24 + (size_t)M * bpw);
+  uint8_t* my_e = my_q + (size_t)2 * M * bpw * 24;
+  bool ready = !SELF;
+  for (int64_t sb = s0; sb < (SELF ? max(s1, s0 + 1) : s1); sb += U) {
+    // ---- weights of this batch: block 4u+g of super-step s for MFMA u
+    v8i wb[U][4];
+    int wsc[U][4];
+#pragma unroll
+    for (int u2 = 0; u2 < U; ++u2) {
+      const int64_t s = sb + u2;
+      v4i sc16 = one16;
+      if (s < s1 && fast) sc16 = *reinterpret_cast<const v4i*>(wep + s * 16);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + (b + u) * 16));
-        wb[u] = v8i{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
-      }
-      wscale = *reinterpret_cast<const int*>(wep + b);
-    } else {
-      uint32_t sc = 0;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        uint32_t byte = 0x7F;
-        wb[u] = zero8;
-        if (b + u < KB) {
-          const uint4 v = *reinterpret_cast<const uint4*>(wp + (b + u) * 16);
-          wb[u] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
-          byte = wep[b + u];
+        const int64_t bi = s * 16 + (CONTIG ? 4 * u + g : 4 * g + u);
+        const bool ok = s < s1 && (FAST || bi < KB);
+        wb[u2][u] = zero8;
+        if (ok) {
+          const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + bi * 16));
+          wb[u2][u] = v8i{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
         }
-        sc |= byte << (8 * u);
+        wsc[u2][u] = fast ? (CONTIG ? scale_byte(sc16, u, g) : scale_byte(sc16, g, u)) : (ok ? (int)wep[bi] : 0x7F);
       }
-      wscale = (int)sc;
     }
+    if (SELF && !ready) {
+      // decompose this wave's blocks: block c -> (row c / nb, block c % nb), one block per lane and pass
+      const int64_t b_lo = s0 * 16, b_hi = min(s1 * 16, KB);
+      const int nb = (int)max((int64_t)0, b_hi - b_lo);
+      const int total = (int)M * nb;
+      const bool al16 = a.x_aligned != 0;
+#pragma unroll 1
+      for (int c = lane; c < total; c += 64) {
+        const int m = c / nb, bb = c - m * nb;
+        const uint16_t* xb = a.x + (int64_t)m * a.ldx + (b_lo + bb) * 32;
+        uint32_t w[16];
+        if (al16) {
+          const uint4* q = reinterpret_cast<const uint4*>(xb);
 #pragma unroll
-    for (int f = 0; f < RT; ++f) {
-      ABlock4 a1, a2;
-      load_a(a.q1, a.e8m0, M, KB, m0 + 16 * f + row, b, fast, a1);
-      load_a(a.q2, a.e8m0, M, KB, m0 + 16 * f + row, b, fast, a2);
-      const int sbeta = a2.scale - 0x04040404;  // beta = alpha / 16: every E8M0 byte minus 4
-      acc[f] = mfma_scaled<0>(a1.blk[0], wb[0], acc[f], a1.scale, wscale);
-      acc[f] = mfma_scaled<1>(a1.blk[1], wb[1], acc[f], a1.scale, wscale);
-      acc[f] = mfma_scaled<2>(a1.blk[2], wb[2], acc[f], a1.scale, wscale);
-      acc[f] = mfma_scaled<3>(a1.blk[3], wb[3], acc[f], a1.scale, wscale);
-      acc[f] = mfma_scaled<0>(a2.blk[0], wb[0], acc[f], sbeta, wscale);
-      acc[f] = mfma_scaled<1>(a2.blk[1], wb[1], acc[f], sbeta, wscale);
-      acc[f] = mfma_scaled<2>(a2.blk[2], wb[2], acc[f], sbeta, wscale);
-      acc[f] = mfma_scaled<3>(a2.blk[3], wb[3], acc[f], sbeta, wscale);
+          for (int i = 0; i < 4; ++i) {
+            const uint4 v = q[i];
+            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
+        }
+        int k1[32], k2[32];
+        const int e = mx_block_codes(w, k1, k2);
+        uint32_t p1[6], p2[6];
+        pack_fp6(k1, p1);
+        pack_fp6(k2, p2);
+        uint2* d1 = reinterpret_cast<uint2*>(my_q + ((size_t)m * bpw + bb) * 24);
+        uint2* d2 = reinterpret_cast<uint2*>(my_q + ((size_t)(M + m) * bpw + bb) * 24);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+          d1[i] = make_uint2(p1[2 * i], p1[2 * i + 1]);
+          d2[i] = make_uint2(p2[2 * i], p2[2 * i + 1]);
+        }
+        my_e[(size_t)m * bpw + bb] = (uint8_t)(e + 127);
+        if (blockIdx.x == 0 && a.abi_q1) {  // observation points only: ABI-format codes
+          uint32_t c1[4], c2[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            uint32_t pa = 0, pc = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              pa |= nibble4(k1[j * 8 + i]) << (4 * i);
+              pc |= nibble4(k2[j * 8 + i]) << (4 * i);
+            }
+            c1[j] = pa;
+            c2[j] = pc;
+          }
+          const int64_t gb = (int64_t)m * KB + b_lo + bb;
+          reinterpret_cast<uint4*>(a.abi_q1 + gb * 16)[0] = make_uint4(c1[0], c1[1], c1[2], c1[3]);
+          reinterpret_cast<uint4*>(a.abi_q2 + gb * 16)[0] = make_uint4(c2[0], c2[1], c2[2], c2[3]);
+          a.abi_e8m0[gb] = (uint8_t)(e + 127);
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      ready = true;
+    }
+    // ---- activation operands and MFMAs
+#pragma unroll
+    for (int u2 = 0; u2 < U; ++u2) {
+      const int64_t s = sb + u2;
+      if (s >= s1) continue;
+#pragma unroll
+      for (int f = 0; f < RT; ++f) {
+        const int64_t m = FAST ? min(m0 + 16 * f + row, M - 1) : m0 + 16 * f + row;
+        v4i asc16 = one16;
+        if (!SELF && fast && m < M) asc16 = *reinterpret_cast<const v4i*>(a.e8m0 + m * KB + s * 16);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int64_t bi = s * 16 + (CONTIG ? 4 * u + g : 4 * g + u);
+          const bool ok = FAST || (m < M && bi < KB);
+          v8i a1 = zero8, a2 = zero8;
+          int sa = 0x7F;
+          if (ok) {
+            if (SELF) {
+              const int64_t bl = bi - s0 * 16;
+              a1 = load_fp6_lds(my_q + ((size_t)m * bpw + bl) * 24);
+              a2 = load_fp6_lds(my_q + ((size_t)(M + m) * bpw + bl) * 24);
+              sa = my_e[(size_t)m * bpw + bl];
+            } else {
+              a1 = load_fp6_slot(a.q1 + (m * KB + bi) * 8);
+              a2 = load_fp6_slot(a.q2 + (m * KB + bi) * 8);
+              sa = fast ? (CONTIG ? scale_byte(asc16, u, g) : scale_byte(asc16, g, u)) : (int)a.e8m0[m * KB + bi];
+            }
+          }
+          acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa, wsc[u2][u]);
+          acc[f] = mfma_scaled(a2, wb[u2][u], acc[f], sa - 4, wsc[u2][u]);  // beta = alpha / 16
+        }
+      }
     }
   }
 #pragma unroll
@@ -148,14 +216,45 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
   }
 }
 
+bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t) { return M <= 2 && K > 0 && K <= 32768; }
+
+template <int WAVES, int U, int RT, bool SELF>
+static int launch_w4(const GemmW4Args& a, hipStream_t stream) {
+  size_t dyn = 0;
+  if (SELF) {
+    const int64_t supers = (a.K / 32 + 15) / 16;
+    const int64_t bpw = cdiv(supers, WAVES) * 16;
+    dyn = (size_t)WAVES * (2 * a.M * bpw * 24 + a.M * bpw);
+    dyn = align_up(dyn, 16);
+  }
+  const dim3 grid((unsigned)cdiv(a.N, 16), (unsigned)cdiv(a.M, 16 * RT));
+  const bool fast = (a.K / 32) % 16 == 0 && a.scales_aligned;
+  if (fast)
+    hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, true>), grid, dim3(WAVES * 64), dyn, stream, a);
+  else
+    hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, false>), grid, dim3(WAVES * 64), dyn, stream, a);
+  return MSD_OK;
+}
+
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
-  if (a.M <= 16) {
-    hipLaunchKernelGGL((gemm_w4_skinny_kernel<8, 1>), dim3((unsigned)cdiv(a.N, 16), 1), dim3(512), 0, stream, a);
+  static const int tune = getenv("MSD_TUNE_W4") ? atoi(getenv("MSD_TUNE_W4")) : 0;
+  int rc;
+  if (a.x != nullptr) {  // single launch (gemm_w4_is_fused)
+    switch (tune) {
+      case 1: rc = launch_w4<8, 1, 1, true>(a, stream); break;
+      case 2: rc = launch_w4<4, 4, 1, true>(a, stream); break;
+      default: rc = launch_w4<4, 2, 1, true>(a, stream); break;
+    }
+  } else if (a.M <= 16) {
+    rc = launch_w4<4, 2, 1, false>(a, stream);
   } else {
-    hipLaunchKernelGGL((gemm_w4_skinny_kernel<8, 2>), dim3((unsigned)cdiv(a.N, 16), (unsigned)cdiv(a.M, 32)),
-                       dim3(512), 0, stream, a);
+    switch (tune) {
+      case 1: rc = launch_w4<8, 1, 2, false>(a, stream); break;
+      default: rc = launch_w4<4, 2, 2, false>(a, stream); break;
+    }
   }
+  if (rc) return rc;
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

@@ -109,7 +109,9 @@ __device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, 
 
 constexpr int kSelfMaxRows = 8;
 
-template <int WAVES, int UNROLL, int RT, int NT, bool SELF>
+// FAST: K % 64 == 0, so no load of the main loop is predicated per lane (predicated loads do not
+// batch); fragment rows past 2M then re-read row 0 -- their products are never looked at.
+template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a) {
   constexpr int THREADS = WAVES * 64;
   __shared__ int s_acc[RT][NT][4][64];
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
   const int8_t* ap[RT];
 #pragma unroll
   for (int f = 0; f < RT; ++f) {
-    const int i = f * 16 + row;
+    const int i = (FAST && f * 16 + row >= 2 * M) ? 0 : f * 16 + row;
     ap[f] = nullptr;
     if (SELF) {
       if (i < 2 * M) ap[f] = my_codes + (int64_t)i * kw + 16 * g - (int64_t)ks0 * 64;
@@ -159,9 +161,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t k = (int64_t)(ks + u) * 64;
-      ok[u] = (ks + u < ks1) && (k + 16 * g < K);
+      ok[u] = (ks + u < ks1) && (FAST || k + 16 * g < K);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) wv[t][u] = ok[u] ? ldg16_stream(wp[t] + k) : zero;
+      for (int t = 0; t < NT; ++t) {
+        wv[t][u] = zero;
+        if (ok[u]) wv[t][u] = ldg16_stream(wp[t] + k);
+      }
     }
     if (SELF && !ready) {
       // this wave's slice of x: rows [0,M) x columns [k_lo, k_hi), in chunks of 16 elements
@@ -220,7 +225,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t k = (int64_t)(ks + u) * 64;
 #pragma unroll
-      for (int f = 0; f < RT; ++f) av[f][u] = (ok[u] && ap[f]) ? ldg16(ap[f] + k) : zero;
+      for (int f = 0; f < RT; ++f) {
+        av[f][u] = zero;
+        if (ok[u] && (FAST || ap[f])) av[f][u] = ldg16(ap[f] + k);
+      }
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
@@ -679,12 +687,18 @@ static int launch_decode(const GemmW8Args& a, hipStream_t stream) {
     static size_t allowed = 0;  // per instantiation
     if (dyn > allowed) {
       MSD_HIP_CHECK(hipFuncSetAttribute(
-          reinterpret_cast<const void*>(&gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF>),
+          reinterpret_cast<const void*>(&gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, true>),
+          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelfMaxCodeBytes));
+      MSD_HIP_CHECK(hipFuncSetAttribute(
+          reinterpret_cast<const void*>(&gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, false>),
           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelfMaxCodeBytes));
       allowed = kSelfMaxCodeBytes;
     }
   }
-  hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF>), grid, dim3(WAVES * 64), dyn, stream, a);
+  if (a.K % 64 == 0)
+    hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, true>), grid, dim3(WAVES * 64), dyn, stream, a);
+  else
+    hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, false>), grid, dim3(WAVES * 64), dyn, stream, a);
   return MSD_OK;
 }
 

@@ -46,7 +46,16 @@ struct GemmW4Args {
   int out_bf16;
   int64_t ldy;
   int64_t M, K, N;
+  // single-launch decode (x == nullptr when the decomposition ran as its own kernel):
+  const uint16_t* x;
+  int64_t ldx;
+  int x_aligned;
+  uint8_t* abi_q1;  // observation points in ABI format (nullable, all three or none)
+  uint8_t* abi_q2;
+  uint8_t* abi_e8m0;
+  int scales_aligned;  // W_e8m0 is 16-byte aligned (16-byte scale loads allowed)
 };
+bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
 
 // ---- attention (attn.hip)

@@ -145,7 +145,7 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   if (K % 32 != 0 || K > (1 << 20)) return MSD_ERR_SHAPE;
   if (M == 0 || N == 0) return MSD_OK;
   if (!y || (K > 0 && (!x_bf16 || !W_fp4 || !W_e8m0))) return MSD_ERR_INVALID_ARG;
-  if (!aligned_to(W_fp4, 16) || !aligned_to(W_e8m0, 4) || !aligned_to(x_bf16, 2) ||
+  if (!aligned_to(W_fp4, 16) ||  !aligned_to(x_bf16, 2) ||
       !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
     return MSD_ERR_INVALID_ARG;
   const W4Layout l = w4_layout(M, K, N);
@@ -158,6 +158,7 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   a.e8m0 = (uint8_t*)(ws + l.e8m0);
   a.W = W_fp4;
   a.We = W_e8m0;
+  a.scales_aligned = aligned_to(W_e8m0, 16) ? 1 : 0;
   a.y = y;
   a.out_bf16 = out_dtype == MSD_BF16;
   a.ldy = ldy;
@@ -168,9 +169,17 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
     uint8_t* te = taps ? (uint8_t*)taps->scale : nullptr;
     if (!(t1 && t2 && te)) t1 = t2 = te = nullptr;  // the ABI-format taps come as a set
     if (t1 && (!aligned_to(t1, 16) || !aligned_to(t2, 16))) return MSD_ERR_INVALID_ARG;
-    int rc = launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, t1, t2, te, (uint32_t*)a.q1,
-                                    (uint32_t*)a.q2, (uint8_t*)a.e8m0, s);
-    if (rc) return rc;
+    if (gemm_w4_is_fused(M, K, N)) {
+      // one launch: the GEMM kernel decomposes the blocks of its own K range itself
+      a.x = (const uint16_t*)x_bf16;
+      a.ldx = ldx;
+      a.x_aligned = (aligned_to(x_bf16, 16) && ldx % 8 == 0) ? 1 : 0;
+      a.abi_q1 = t1; a.abi_q2 = t2; a.abi_e8m0 = te;
+    } else {
+      int rc = launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, t1, t2, te, (uint32_t*)a.q1,
+                                      (uint32_t*)a.q2, (uint8_t*)a.e8m0, s);
+      if (rc) return rc;
+    }
   }
   return launch_gemm_w4(a, s);
 }
