@@ -236,6 +236,220 @@ static int launch_w4(const GemmW4Args& a, hipStream_t stream) {
   return MSD_OK;
 }
 
+// ------------------------------------------------------------------ tiled (M > 16)
+// v_mfma_scale_f32_32x32x64_f8f6f4: lane l holds row/column l%32 and K block l/32 (two blocks
+// per instruction).  Workgroup tile BM x BN, K stage of 4 blocks (128 k), LDS double buffering
+// with register staging of the next stage.  LDS operand layout is [block][row][24 B] for the
+// FP6 components and [block][column][16 B] for the FP4 weights, i.e. exactly lane order, so all
+// fragment reads are linear and conflict-free.  Both components accumulate into one fp32
+// accumulator; beta's scale byte is alpha's minus 4.
+__device__ __forceinline__ v16f mfma32_scaled(v8i a, v8i b, v16f c, int sa, int sb) {
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 4, 0, sa, 0, sb);
+}
+
+constexpr int kW4GroupM = 8;
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_w4_tiled_kernel(GemmW4Args a, int tiles_m, int tiles_n) {
+  constexpr int THREADS = WM * WN * 64;
+  constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+  constexpr int A_ITEMS = BM * 4 * 2, B_ITEMS = BN * 4;
+  constexpr int LA = (A_ITEMS + THREADS - 1) / THREADS, LB = (B_ITEMS + THREADS - 1) / THREADS;
+  constexpr int SZ_A = 4 * BM * 24, SZ_B = 4 * BN * 16, SZ_AE = BM * 4, SZ_BE = BN * 4;
+  constexpr int STAGE = 2 * SZ_A + SZ_B + SZ_AE + SZ_BE;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem4[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, kb = lane >> 5;
+  const int64_t M = a.M, N = a.N, KB = a.K / 32;
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  {
+    const int per_xcd = (total + 7) / 8;
+    id = (id % 8) * per_xcd + id / 8;
+  }
+  if (id >= total) return;
+  const int group = id / (kW4GroupM * tiles_n);
+  const int first_m = group * kW4GroupM;
+  const int rows_in_group = min(kW4GroupM, tiles_m - first_m);
+  const int in_group = id - group * kW4GroupM * tiles_n;
+  const int tm = first_m + in_group % rows_in_group;
+  const int tn = in_group / rows_in_group;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const bool dword_scales = (KB % 4) == 0 && a.scales_aligned;
+  const v8i zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  // ---- staging registers for one stage
+  uint4 ra_lo[LA];
+  uint2 ra_hi[LA];
+  uint4 rb[LB];
+  uint32_t rae = 0x7F7F7F7Fu, rbe = 0x7F7F7F7Fu, rbe2 = 0x7F7F7F7Fu;
+  auto gload = [&](int kt) {
+    const int64_t b0 = (int64_t)kt * 4;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int idx = tid + i * THREADS;
+      ra_lo[i] = make_uint4(0, 0, 0, 0);
+      ra_hi[i] = make_uint2(0, 0);
+      if (idx < A_ITEMS) {
+        const int comp = idx / (BM * 4), rem = idx - comp * (BM * 4);
+        const int r = rem >> 2, blk = rem & 3;
+        const int64_t m = min(m0 + r, M - 1);
+        if (b0 + blk < KB) {
+          const uint32_t* p = (comp ? a.q2 : a.q1) + (m * KB + b0 + blk) * 8;
+          ra_lo[i] = *reinterpret_cast<const uint4*>(p);
+          ra_hi[i] = *reinterpret_cast<const uint2*>(p + 4);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int idx = tid + i * THREADS;
+      rb[i] = make_uint4(0, 0, 0, 0);
+      if (idx < B_ITEMS) {
+        const int c = idx >> 2, blk = idx & 3;
+        const int64_t n = min(n0 + c, N - 1);
+        if (b0 + blk < KB) {
+          const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(a.W + n * (KB * 16) + (b0 + blk) * 16));
+          rb[i] = make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+        }
+      }
+    }
+    rae = rbe = rbe2 = 0x7F7F7F7Fu;
+    if (tid < BM) {
+      const int64_t m = min(m0 + tid, M - 1);
+      const uint8_t* pe = a.e8m0 + m * KB + b0;
+      if (dword_scales) {
+        rae = *reinterpret_cast<const uint32_t*>(pe);
+      } else {
+        uint32_t v = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v |= (uint32_t)(b0 + u < KB ? pe[u] : 0x7F) << (8 * u);
+        rae = v;
+      }
+    }
+    for (int c = tid; c < BN; c += THREADS) {  // BN <= 2*THREADS: at most two passes, kept simple
+      const int64_t n = min(n0 + c, N - 1);
+      const uint8_t* pe = a.We + n * KB + b0;
+      uint32_t v = 0;
+      if (dword_scales) {
+        v = *reinterpret_cast<const uint32_t*>(pe);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v |= (uint32_t)(b0 + u < KB ? pe[u] : 0x7F) << (8 * u);
+      }
+      if (c == tid) rbe = v; else rbe2 = v;
+    }
+  };
+  auto sstore = [&](int buf) {
+    uint8_t* st = smem4 + buf * STAGE;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int idx = tid + i * THREADS;
+      if (idx < A_ITEMS) {
+        const int comp = idx / (BM * 4), rem = idx - comp * (BM * 4);
+        const int r = rem >> 2, blk = rem & 3;
+        uint2* d = reinterpret_cast<uint2*>(st + comp * SZ_A + (blk * BM + r) * 24);
+        d[0] = make_uint2(ra_lo[i].x, ra_lo[i].y);
+        d[1] = make_uint2(ra_lo[i].z, ra_lo[i].w);
+        d[2] = ra_hi[i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int idx = tid + i * THREADS;
+      if (idx < B_ITEMS) {
+        const int c = idx >> 2, blk = idx & 3;
+        *reinterpret_cast<uint4*>(st + 2 * SZ_A + (blk * BN + c) * 16) = rb[i];
+      }
+    }
+    if (tid < BM) *reinterpret_cast<uint32_t*>(st + 2 * SZ_A + SZ_B + tid * 4) = rae;
+    if (tid < BN) *reinterpret_cast<uint32_t*>(st + 2 * SZ_A + SZ_B + SZ_AE + tid * 4) = rbe;
+    if (tid + THREADS < BN) *reinterpret_cast<uint32_t*>(st + 2 * SZ_A + SZ_B + SZ_AE + (tid + THREADS) * 4) = rbe2;
+  };
+
+  v16f acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int KT = (int)((KB + 3) / 4);
+  if (KT > 0) {
+    gload(0);
+    sstore(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) gload(kt + 1);
+    const uint8_t* st = smem4 + buf * STAGE;
+#pragma unroll
+    for (int kp = 0; kp < 2; ++kp) {
+      const int blk = kp * 2 + kb;
+      v8i fb[FN];
+      int sb[FN];
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int c = wn * TN + 32 * j + l32;
+        const uint4 v = *reinterpret_cast<const uint4*>(st + 2 * SZ_A + (blk * BN + c) * 16);
+        fb[j] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
+        sb[j] = st[2 * SZ_A + SZ_B + SZ_AE + c * 4 + blk];
+      }
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int r = wm * TM + 32 * i + l32;
+        const v8i f1 = load_fp6_lds(st + (blk * BM + r) * 24);
+        const v8i f2 = load_fp6_lds(st + SZ_A + (blk * BM + r) * 24);
+        const int sa = st[2 * SZ_A + SZ_B + r * 4 + blk];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          acc[i][j] = mfma32_scaled(f1, fb[j], acc[i][j], sa, sb[j]);
+          acc[i][j] = mfma32_scaled(f2, fb[j], acc[i][j], sa - 4, sb[j]);
+        }
+      }
+    }
+    if (kt + 1 < KT) sstore(buf ^ 1);
+    __syncthreads();
+  }
+  (void)zero8;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t m = m0 + wm * TM + 32 * i + (r >> 2) * 8 + kb * 4 + (r & 3);
+      if (m >= M) continue;
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int64_t n = n0 + wn * TN + 32 * j + l32;
+        if (n >= N) continue;
+        if (a.out_bf16)
+          reinterpret_cast<uint16_t*>(a.y)[m * a.ldy + n] = f32_to_bf16_bits(acc[i][j][r]);
+        else
+          reinterpret_cast<float*>(a.y)[m * a.ldy + n] = acc[i][j][r];
+      }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+static int launch_w4_tiled(const GemmW4Args& a, hipStream_t stream) {
+  const int tiles_m = (int)cdiv(a.M, BM), tiles_n = (int)cdiv(a.N, BN);
+  const int total = tiles_m * tiles_n;
+  const int grid = ((total + 7) / 8) * 8;
+  const size_t lds = (size_t)2 * (2 * 4 * BM * 24 + 4 * BN * 16 + BM * 4 + BN * 4);
+  static bool attr_set = false;
+  if (!attr_set && lds > 64 * 1024) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_tiled_kernel<BM, BN, WM, WN>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_w4_tiled_kernel<BM, BN, WM, WN>), dim3(grid), dim3(WM * WN * 64), lds, stream, a, tiles_m,
+                     tiles_n);
+  return MSD_OK;
+}
+
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
   static const int tune = getenv("MSD_TUNE_W4") ? atoi(getenv("MSD_TUNE_W4")) : 0;
@@ -248,10 +462,15 @@ int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {
     }
   } else if (a.M <= 16) {
     rc = launch_w4<4, 2, 1, false>(a, stream);
+  } else if (a.M <= 32 && tune == 1) {
+    rc = launch_w4<4, 2, 2, false>(a, stream);
+  } else if (a.M <= 32) {
+    rc = launch_w4_tiled<32, 128, 1, 4>(a, stream);
   } else {
     switch (tune) {
-      case 1: rc = launch_w4<8, 1, 2, false>(a, stream); break;
-      default: rc = launch_w4<4, 2, 2, false>(a, stream); break;
+      case 2: rc = launch_w4_tiled<128, 128, 2, 2>(a, stream); break;
+      case 3: rc = launch_w4_tiled<64, 256, 1, 4>(a, stream); break;
+      default: rc = launch_w4_tiled<128, 256, 2, 2>(a, stream); break;
     }
   }
   if (rc) return rc;

@@ -38,7 +38,8 @@ def test_decompose_mxfp4_bit_exact(msd, M, K, scale):
     assert np.array_equal(d2.cpu().numpy(), q2)
 
 
-SHAPES = [(1, 8192, 512), (32, 8192, 256), (5, 96, 40), (17, 1056, 100), (70, 512, 48), (2, 2048, 4096)]
+SHAPES = [(1, 8192, 512), (32, 8192, 256), (5, 96, 40), (17, 1056, 100), (70, 512, 48), (2, 2048, 4096),
+          (200, 2048, 600), (130, 160, 300)]
 
 
 @pytest.mark.parametrize("M,K,N", SHAPES)
