@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", default="all", help="comma list of extra legs: prefill,w4,attn,cmp | all | none")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
+                         "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -74,6 +77,21 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     shapes = [(M, N) for N in Ns for M in Ms]
     step_bytes = sum(w8_bytes(M, K, N) for M, N in shapes)
+
+    if args.traffic_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # calibration: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        for (M, N) in shapes:
+            reps, s = weights[N]
+            for i in range(3):
+                msd.msd_gemm_w8a16(acts[M], reps[(5 * i + 1) % len(reps)], s, y=outs[(M, N)], ws=ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": [{"M": M, "K": K, "N": N, "calls": 3} for (M, N) in shapes],
+                          "calibration_copy_bytes": 1 << 30}))
+        return
 
     # ---- every call is marshalled once (binding.Prepared) and the timed region replays HIP graphs of
     # whole steps, so that the GPU, not the Python interpreter (~10 us per ctypes call), sets the pace

@@ -11,7 +11,7 @@
 //       needs no reduction over P,
 //   (5) computes O1 = P1 V_t, O2 = P2 V_t on the same MFMA and rescales the running output.
 // The KV length is split over workgroups (flash-decode); a small second kernel merges the
-// (m, l, O) partials -- the only cross-workgroup step.
+// (m, l, O) partials -- the only cross-workgroup step (skipped when there is one split).
 //
 // Layout tricks.  A-fragment row i = 4*(lane/16)+r carries (head, component), chosen so that
 // S1 and S2 (and later O1 and O2) of one head land in registers of the same lane: the
@@ -37,6 +37,8 @@ struct AttnParams {
   float* part_o;  // [B*Hkv][nsplit][G][128]
   float* part_m;  // [B*Hkv][nsplit][G]
   float* part_l;
+  void* out;
+  int out_bf16;
   int8_t* tap_q1;
   int8_t* tap_q2;
   float* tap_alpha;
@@ -160,38 +162,54 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
   }
   const float sm_scale = kLog2e / sqrtf((float)kD);  // scores are kept in log2 units
 
-  for (int64_t t0 = t_begin + (int64_t)wave * kTile; t0 < t_end; t0 += kAttnWaves * kTile) {
-    const int64_t last = t_end - 1;
-    // ---- (1) load K_t and V_t once
-    v4i kf[4][2];
+  // Tile loads are software-pipelined: the K/V/scale loads of the wave's next tile are issued
+  // before the current tile is processed.  Token indices are clamped to the last valid token, so
+  // every load is unconditional (a wave's look-ahead past its range re-reads that token).
+  const int64_t last = max(t_end - 1, (int64_t)0);
+  v4i kf[4][2], kfn[4][2];
+  v2i vr[4][4], vrn[4][4];  // [jq][tt]: 8 channels (8j..8j+7) of token 16*tt + 4*g + jq
+  float sk[4], sv[4], skn[4], svn[4];
+  auto load_tile = [&](int64_t t0, v4i (&kx)[4][2], v2i (&vx)[4][4], float (&skx)[4], float (&svx)[4]) {
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) {
       const int64_t tok = min(t0 + 16 * tt + j, last);
 #pragma unroll
       for (int s = 0; s < 2; ++s)
-        kf[tt][s] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(Kb + tok * kD + 64 * s + 16 * g));
+        kx[tt][s] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(Kb + tok * kD + 64 * s + 16 * g));
     }
-    v2i vr[4][4];  // [jq][tt]: 8 channels (8j..8j+7) of token 16*tt + 4*g + jq
 #pragma unroll
     for (int jq = 0; jq < 4; ++jq)
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) {
         const int64_t tok = min(t0 + 16 * tt + 4 * g + jq, last);
-        vr[jq][tt] = __builtin_nontemporal_load(reinterpret_cast<const v2i*>(Vb + tok * kD + 8 * j));
+        vx[jq][tt] = __builtin_nontemporal_load(reinterpret_cast<const v2i*>(Vb + tok * kD + 8 * j));
       }
-    float sk[4], sv[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      skx[tt] = 1.f;
+      svx[tt] = 1.f;
+      if (PER_TOKEN) {
+        const int64_t tok = min(t0 + 16 * tt + j, last);
+        skx[tt] = p.k_scale[kv_base + tok];
+        svx[tt] = p.v_scale[kv_base + tok];
+      }
+    }
+  };
+  const int64_t t_first = t_begin + (int64_t)wave * kTile;
+  if (t_first < t_end) load_tile(t_first, kfn, vrn, skn, svn);
+  for (int64_t t0 = t_first; t0 < t_end; t0 += kAttnWaves * kTile) {
     bool live[4];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) {
-      const int64_t tok = t0 + 16 * tt + j;
-      live[tt] = tok < t_end;
-      sk[tt] = 1.f;
-      sv[tt] = 1.f;
-      if (PER_TOKEN) {
-        sk[tt] = p.k_scale[kv_base + min(tok, last)];
-        sv[tt] = live[tt] ? p.v_scale[kv_base + tok] : 0.f;
-      }
+      live[tt] = t0 + 16 * tt + j < t_end;
+      sk[tt] = skn[tt];
+      sv[tt] = live[tt] ? svn[tt] : 0.f;
+#pragma unroll
+      for (int s = 0; s < 2; ++s) kf[tt][s] = kfn[tt][s];
+#pragma unroll
+      for (int jq = 0; jq < 4; ++jq) vr[jq][tt] = vrn[jq][tt];
     }
+    if (t0 + kAttnWaves * kTile < t_end) load_tile(t0 + kAttnWaves * kTile, kfn, vrn, skn, svn);
     // ---- (2) S1, S2 for all heads of the group
     v4i sd[4];
 #pragma unroll
@@ -312,19 +330,30 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
       o += sO[w][h][c] * wgt;
       l += sL[w][h] * wgt;
     }
-    const int64_t pr = ((int64_t)bk * p.nsplit + split) * G + h;
-    p.part_o[pr * kD + c] = o;
-    if (c == 0) {
-      p.part_m[pr] = ms;
-      p.part_l[pr] = l;
+    if (p.nsplit == 1) {  // no cross-workgroup step at all
+      float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
+      if (!PER_TOKEN) v *= p.v_scale[hk * kD + c];
+      const int64_t orow = (int64_t)b * p.Hq + hk * G + h;
+      if (p.out_bf16)
+        reinterpret_cast<uint16_t*>(p.out)[orow * kD + c] = f32_to_bf16_bits(v);
+      else
+        reinterpret_cast<float*>(p.out)[orow * kD + c] = v;
+    } else {
+      const int64_t pr = ((int64_t)bk * p.nsplit + split) * G + h;
+      p.part_o[pr * kD + c] = o;
+      if (c == 0) {
+        p.part_m[pr] = ms;
+        p.part_l[pr] = l;
+      }
     }
   }
 }
 
 // Merge the split partials: out = sum_s O_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
-// (times s_V per channel in per-channel mode; Alg. 3 last two steps).
-__global__ __launch_bounds__(kD) void attn_combine_kernel(AttnParams p, void* out, int out_bf16,
-                                                          int per_channel) {
+// (times s_V per channel in per-channel mode; Alg. 3 last two steps).  A second launch: a
+// release/acquire handshake inside the main kernel costs far more than the launch (every
+// workgroup's agent-scope release fence forces an L2 write-back under the KV stream).
+__global__ __launch_bounds__(kD) void attn_combine_kernel(AttnParams p, int per_channel) {
   const int row = blockIdx.x;  // b*Hq + hq
   const int b = row / p.Hq, hq = row % p.Hq;
   const int hk = hq / p.G, h = hq % p.G;
@@ -342,10 +371,10 @@ __global__ __launch_bounds__(kD) void attn_combine_kernel(AttnParams p, void* ou
   }
   float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
   if (per_channel) v *= p.v_scale[hk * kD + c];
-  if (out_bf16)
-    reinterpret_cast<uint16_t*>(out)[(int64_t)row * kD + c] = f32_to_bf16_bits(v);
+  if (p.out_bf16)
+    reinterpret_cast<uint16_t*>(p.out)[(int64_t)row * kD + c] = f32_to_bf16_bits(v);
   else
-    reinterpret_cast<float*>(out)[(int64_t)row * kD + c] = v;
+    reinterpret_cast<float*>(p.out)[(int64_t)row * kD + c] = v;
 }
 
 static int plan_nsplit(int B, int Hkv, int64_t L) {
@@ -382,6 +411,8 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
   p.part_o = (float*)ws;
   p.part_m = (float*)(ws + align_up(rows * kD * 4, 256));
   p.part_l = (float*)(ws + align_up(rows * kD * 4, 256) + align_up(rows * 4, 256));
+  p.out = a.out;
+  p.out_bf16 = a.out_bf16;
   if (a.taps) {
     p.tap_q1 = (int8_t*)a.taps->q1;
     p.tap_q2 = (int8_t*)a.taps->q2;
@@ -405,9 +436,11 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL((attn_decode_kernel<2, false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
   }
   MSD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(a.B * a.Hq)), dim3(kD), 0, stream, p, a.out,
-                     a.out_bf16, per_token ? 0 : 1);
-  MSD_LAUNCH_CHECK();
+  if (p.nsplit > 1) {
+    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(a.B * a.Hq)), dim3(kD), 0, stream, p,
+                       per_token ? 0 : 1);
+    MSD_LAUNCH_CHECK();
+  }
   return MSD_OK;
 }
 
