@@ -169,10 +169,22 @@ def main():
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
                           "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2)})
     dom = max(per_shape, key=lambda r: r["us_per_call"] )
+    # HBM bytes per call from the committed counter summary (FETCH_SIZE / WRITE_SIZE runs of
+    # `bench.py --traffic-probe`, scaled by a copy of known size); null when the file has no line for it
+    traffic = None
+    try:
+        import re
+        with open(os.path.join(ROOT, "profiles", "w8a16_decode_hbm_traffic_pmc.txt")) as fh:
+            mt = re.search(r"^traffic M=%d N=%d total_bytes=(\d+)" % (dom["M"], dom["N"]), fh.read(), re.M)
+        traffic = int(mt.group(1)) if mt else None
+    except OSError:
+        traffic = None
     roofline = {"bound": "hbm", "kernel": "msd_gemm_w8a16 M=%d K=%d N=%d (all launches of one call)" %
                 (dom["M"], dom["K"], dom["N"]),
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4), "traffic": None}
+                "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                "algorithmic_bytes": w8_bytes(dom["M"], K, dom["N"])}
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
