@@ -430,17 +430,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_mfma32_kernel(GemmW8Args
     }
 }
 
-// ------------------------------------------------------------------ large tiles, asynchronous LDS fill
-// Same tiling and fragment layout as gemm_w8_mfma32_kernel, but the tiles go HBM/L2 -> LDS
-// with global_load_lds_dwordx4 (no staging registers, no ds_write), NS stages deep: while the
-// MFMAs of K step t run, the loads of steps t+1 .. t+NS-2 are in flight and step t+NS-1 is
-// being issued.  One s_barrier per K step; the wait before it is an explicit
-// s_waitcnt vmcnt(8*(NS-2)): a wave issues 8 loads per step and they complete in order.
-// The loads are written as inline asm on purpose: the compiler does not see them write LDS
-// and therefore does not serialise every ds_read behind the youngest load.
-// Each load instruction fills 1 KB of LDS = 16 rows of 64 B in lane order, so a lane fetches
-// the global chunk whose swizzled position it owns.  Rows past M / N are clamped to the last
-// valid row (their results are never stored).  Requires K % 64 == 0.
+// ------------------------------------------------------------------ asynchronous LDS fill (prefill and batched decode)
+// Same fragment layout as gemm_w8_mfma32_kernel, but the tiles go HBM/L2 -> LDS with
+// global_load_lds_dwordx4 (no staging registers, no ds_write), NS stages deep: while the MFMAs
+// of K step t run, the loads of steps t+1 .. t+NS-2 are in flight and step t+NS-1 is being
+// issued.  One s_barrier per K step; the wait before it is an explicit s_waitcnt vmcnt(n): a
+// wave issues L loads per step and they complete in order.  The loads are written as inline asm
+// on purpose: the compiler does not see them write LDS and therefore does not serialise every
+// ds_read behind the youngest load.  Each load instruction fills 1 KB of LDS = 16 rows of 64 B in
+// lane order, so a lane fetches the global chunk whose swizzled position it owns.  Rows past M / N
+// are clamped to the last valid row (their results are never stored).  Requires K % 64 == 0.
+//
+// Two uses.  <128,256,2,2,4>: prefill, 256x256 output tile (128 activation rows x 2 components),
+// MFMA-bound.  Small tiles with many stages: batched decode (32 < M <= 128, few output tiles),
+// where the weight stream is cold and the bytes in flight per CU, i.e. the stage count, set the
+// HBM rate (Little's law), not the MFMA.
 __device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
@@ -450,20 +454,22 @@ __device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, ui
 
 template <int N>
 __device__ __forceinline__ void wait_vm_barrier() {
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-  else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int NS>
-__global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
-  constexpr int BMH = 128, BN = 256, ROWS_A = 256, TMH = 64, TN = 128, FM = 2, FN = 4;
-  constexpr int STAGE = (ROWS_A + BN) * 64;  // 32 KB
+template <int BMH, int BN, int WM, int WN, int NS>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+  constexpr int NW = WM * WN, ROWS_A = 2 * BMH, R = ROWS_A + BN;
+  constexpr int TMH = BMH / WM, TN = BN / WN, FM = TMH / 32, FN = TN / 32;
+  constexpr int L = R / (16 * NW);   // load instructions per wave and stage
+  constexpr int STAGE = R * 64;
+  static_assert(R % (16 * NW) == 0 && TMH % 32 == 0 && TN % 32 == 0, "tile shape");
+  static_assert(NS >= 3 && (NS - 2) * L < 64, "stage count");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, kg = lane >> 5;
   const int64_t M = a.M, K = a.K, N = a.N;
   const int total = tiles_m * tiles_n;
@@ -481,35 +487,34 @@ __global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tile
   const int tn = in_group / rows_in_group;
   const int64_t m0 = (int64_t)tm * BMH, n0 = (int64_t)tn * BN;
 
-  // ---- this wave's 8 load instructions per stage: waves 0,1 fill A (16 blocks of 16 rows), waves 2,3 fill B
+  // ---- this wave's L load instructions per stage: 16-row block q*NW + wave of the stage
+  // (blocks 0 .. ROWS_A/16-1 are q1 then q2 rows, the rest W rows)
   const int rr = lane >> 2, pc = lane & 3;
   const int lc = pc ^ ((rr >> 2) & 3);  // logical chunk this lane fetches
-  const bool fillsA = wave < 2;
-  uint32_t voff[8];
-  const int8_t* gbase[8];
-  uint32_t ldst[8];
+  uint32_t voff[L];
+  const int8_t* gbase[L];
+  uint32_t ldst[L];
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int blk = (wave & 1) * 8 + q;
-    if (fillsA) {
-      const int comp = blk >> 3;
-      const int64_t mrow = min(m0 + (blk & 7) * 16 + rr, M - 1);
+  for (int q = 0; q < L; ++q) {
+    const int blk = q * NW + wave;
+    if (blk < ROWS_A / 16) {
+      const int comp = blk / (BMH / 16);
+      const int64_t mrow = min(m0 + (blk % (BMH / 16)) * 16 + rr, M - 1);
       voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
       gbase[q] = (comp ? a.q2 : a.q1) + m0 * a.ldq;
-      ldst[q] = lds0 + blk * 1024;
     } else {
-      const int64_t nrow = min(n0 + blk * 16 + rr, N - 1);
+      const int64_t nrow = min(n0 + (blk - ROWS_A / 16) * 16 + rr, N - 1);
       voff[q] = (uint32_t)((nrow - n0) * K + lc * 16);
       gbase[q] = a.W + n0 * K;
-      ldst[q] = lds0 + ROWS_A * 64 + blk * 1024;
     }
+    ldst[q] = lds0 + blk * 1024;
   }
   auto issue = [&](int kt) {
     const int64_t k0 = (int64_t)kt * 64;
     const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) lds_dma16(gbase[q] + k0, voff[q], ldst[q] + sb);
+    for (int q = 0; q < L; ++q) lds_dma16(gbase[q] + k0, voff[q], ldst[q] + sb);
   };
 
   v16i acc[2][FM][FN];
@@ -541,7 +546,7 @@ __global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tile
 
   const int KT = (int)(K / 64);
   auto stage_ptr = [&](int kt) { return smem + (kt % NS) * STAGE; };
-  auto load_frags = [&](const int8_t* st, int s, v4i (&fa)[4], v4i (&fb)[4]) {
+  auto load_frags = [&](const int8_t* st, int s, v4i (&fa)[2 * FM], v4i (&fb)[FN]) {
 #pragma unroll
     for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const v4i*>(st + fb_off[j][s]);
 #pragma unroll
@@ -549,7 +554,7 @@ __global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tile
 #pragma unroll
       for (int i = 0; i < FM; ++i) fa[c * FM + i] = *reinterpret_cast<const v4i*>(st + fa_off[c][i][s]);
   };
-  auto mfma_block = [&](const v4i (&fa)[4], const v4i (&fb)[4]) {
+  auto mfma_block = [&](const v4i (&fa)[2 * FM], const v4i (&fb)[FN]) {
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -557,21 +562,22 @@ __global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tile
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[c][i][j] = mfma32(fa[c * FM + i], fb[j], acc[c][i][j]);
   };
-  // wait until tile t has landed (its younger in-flight tiles may stay outstanding), then barrier
+  // Wait until tile t has landed, then barrier.  In steady state the NS-3 tiles issued after it
+  // may stay outstanding ((NS-2) before the first tile); near the end of K fewer tiles follow and
+  // the wait simply drains everything.
   auto wait_tile = [&](int t, int newest_issued) {
     const int younger = newest_issued - t;
-    if (younger >= 2) wait_vm_barrier<16>();
-    else if (younger == 1) wait_vm_barrier<8>();
+    if (younger == NS - 2) wait_vm_barrier<(NS - 2) * L>();
+    else if (younger == NS - 3) wait_vm_barrier<(NS - 3) * L>();
     else wait_vm_barrier<0>();
   };
-  static_assert(NS == 3 || NS == 4, "stage count");
   // Software pipeline: the fragments of K half-step (kt,1) are fetched under the MFMAs of (kt,0),
   // those of (kt+1,0) under the MFMAs of (kt,1).  The barrier for tile kt+1 sits between the two
   // MFMA blocks of tile kt; after it the stage of tile kt-1 is free and is refilled at once.
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
     if (t < KT) issue(t);
-  v4i fa0[4], fb0[4], fa1[4], fb1[4];
+  v4i fa0[2 * FM], fb0[FN], fa1[2 * FM], fb1[FN];
   if (KT > 0) {
     wait_tile(0, min(KT - 1, NS - 2));
     load_frags(stage_ptr(0), 0, fa0, fb0);
@@ -594,16 +600,16 @@ __global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tile
     mfma_block(fa1, fb1);
   }
 
-  // ---- dual-scale epilogue.  alpha and beta of the tile's 128 rows go through LDS (free now), the
+  // ---- dual-scale epilogue.  alpha and beta of the tile's rows go through LDS (free now), the
   // output is produced one (fragment, register) row at a time so that the compiler does not pull
-  // all 256 accumulators into VGPRs at once.
+  // all accumulators into VGPRs at once.
   __syncthreads();
-  float* s_ab = reinterpret_cast<float*>(smem);  // [0..127] alpha, [128..255] beta
-  if (tid < BMH) {
-    const int64_t m = m0 + tid;
+  float* s_ab = reinterpret_cast<float*>(smem);  // [0..BMH-1] alpha, [BMH..2BMH-1] beta
+  for (int i = tid; i < BMH; i += NW * 64) {
+    const int64_t m = m0 + i;
     const float al = m < M ? a.alpha[m] : 0.f;
-    s_ab[tid] = al;
-    s_ab[BMH + tid] = __fdiv_rn(al, 254.0f);
+    s_ab[i] = al;
+    s_ab[BMH + i] = __fdiv_rn(al, 254.0f);
   }
   __syncthreads();
   float sw[FN];
@@ -634,19 +640,21 @@ __global__ __launch_bounds__(256) void gemm_w8_dma_kernel(GemmW8Args a, int tile
     }
 }
 
-template <int NS>
+template <int BMH, int BN, int WM, int WN, int NS>
 static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
-  const int tiles_m = (int)cdiv(a.M, 128), tiles_n = (int)cdiv(a.N, 256);
+  const int tiles_m = (int)cdiv(a.M, BMH), tiles_n = (int)cdiv(a.N, BN);
   const int total = tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  const size_t lds = (size_t)NS * 512 * 64;
+  const size_t lds = (size_t)NS * (2 * BMH + BN) * 64;
+  static_assert((size_t)NS * (2 * BMH + BN) * 64 <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<NS>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w8_dma_kernel<NS>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS>), dim3(grid), dim3(WM * WN * 64), lds, stream, a,
+                     tiles_m, tiles_n);
   return MSD_OK;
 }
 
@@ -717,10 +725,16 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   } else if (2 * M <= 64) {
     rc = wide ? launch_decode<8, 2, 4, 4, false>(a, stream) : launch_decode<8, 4, 4, 1, false>(a, stream);
   } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
-    // few tiles (decode with a large batch): small tiles so that the problem covers more CUs (measured)
-    rc = launch_mfma32<64, 64, 2, 2>(a, stream);
+    // Few output tiles (decode with a large batch).  With K a multiple of 64: asynchronous-fill
+    // kernel on the largest of three small tiles that still gives about 200 workgroups (measured:
+    // the stream rate is set by how many CUs pull, then by the activation re-reads per workgroup).
+    const auto wgs = [&](int bmh, int bn) { return cdiv(M, bmh) * cdiv(N, bn); };
+    if (a.K % 64 != 0) rc = launch_mfma32<64, 64, 2, 2>(a, stream);
+    else if (wgs(64, 128) >= 200) rc = launch_dma<64, 128, 2, 2, 8>(a, stream);
+    else if (wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
+    else rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // 64 KB of LDS: two workgroups per CU
   } else if (a.K % 64 == 0 && a.K >= 64 && tune != 3) {
-    rc = launch_dma<4>(a, stream);
+    rc = launch_dma<128, 256, 2, 2, 4>(a, stream);
   } else {
     rc = launch_mfma32<128, 256, 2, 2>(a, stream);
   }

@@ -60,6 +60,8 @@ SHAPES = [
     (300, 1040, 520, 1),       # several large tiles, ragged in M, N and K
     (257, 256, 777, 0),
     (1100, 512, 4200, 1),      # >= 128 large tiles: the asynchronous-LDS-fill kernel, ragged M and N
+    (128, 256, 12800, 1),      # batched decode, 64x128 tiles of the asynchronous-fill kernel
+    (70, 320, 6500, 1),        # batched decode, 64x64 tiles, ragged M and N
 ]
 
 
@@ -84,6 +86,24 @@ def test_gemm_w8a16_parity(msd, M, K, N, outl):
     xf = synth.bf16_bits_to_f32(x).astype(np.float64)
     bound = s.astype(np.float64)[None] * np.abs(W.astype(np.float64)).sum(1)[None] * np.abs(xf).max(1)[:, None] / 64516.0
     assert np.all(np.abs(yh - truth) <= bound * (1 + 1e-4) + np.abs(truth) * 2.0 ** -21 + 1e-30)
+
+
+@pytest.mark.parametrize("M,K,N", [(128, 4096, 1024), (100, 1024, 700), (96, 2112, 520), (65, 192, 300),
+                                   (128, 4096, 14336 // 4), (1, 4096, 1024), (2, 1040, 300), (8, 4096, 512)])
+def test_gemm_w8a16_product_path_without_taps(msd, M, K, N):
+    """The path a caller without observation points takes.  y starts as NaN."""
+    seed = synth.seed_for(1, M * 11 + N)
+    x = synth.activations(seed, M, K, outliers=True)
+    W, s = synth.int8_weights(seed, N, K)
+    y_ref = oracle.gemm_w8a16(x, W, s)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    xd, Wd, sd = bf16_to_dev(x), to_dev(W), to_dev(s)
+    for _ in range(2):      # a second call over its own previous result
+        msd.msd_gemm_w8a16(xd, Wd, sd, y=y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()
+        assert np.all(np.isfinite(yh))
+        assert rel_l2(yh, y_ref) <= 1e-6
 
 
 def test_gemm_w8a16_bf16_output_and_determinism(msd):
