@@ -510,6 +510,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     }
     ldst[q] = lds0 + blk * 1024;
   }
+  const int KT = (int)(K / 64);
   auto issue = [&](int kt) {
     const int64_t k0 = (int64_t)kt * 64;
     const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
@@ -544,7 +545,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     }
   }
 
-  const int KT = (int)(K / 64);
   auto stage_ptr = [&](int kt) { return smem + (kt % NS) * STAGE; };
   auto load_frags = [&](const int8_t* st, int s, v4i (&fa)[2 * FM], v4i (&fb)[FN]) {
 #pragma unroll
@@ -582,16 +582,35 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     wait_tile(0, min(KT - 1, NS - 2));
     load_frags(stage_ptr(0), 0, fa0, fb0);
   }
+  // The first MFMA of a block is issued before the fragment reads of the next block: the
+  // compiler's wait for the current fragments (it cannot count LDS operations across the inline
+  // asm and waits for all of them) then covers no read that was only just issued.
+  auto mfma_first = [&](const v4i (&fa)[2 * FM], const v4i (&fb)[FN]) {
+    acc[0][0][0] = mfma32(fa[0], fb[0], acc[0][0][0]);
+  };
+  auto mfma_rest = [&](const v4i (&fa)[2 * FM], const v4i (&fb)[FN]) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          if (c + i + j > 0) acc[c][i][j] = mfma32(fa[c * FM + i], fb[j], acc[c][i][j]);
+  };
   for (int kt = 0; kt + 1 < KT; ++kt) {
+    mfma_first(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
     load_frags(stage_ptr(kt), 1, fa1, fb1);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_block(fa0, fb0);
+    mfma_rest(fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
     wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
     if (kt + NS - 1 < KT) issue(kt + NS - 1);
+    mfma_first(fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
     load_frags(stage_ptr(kt + 1), 0, fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_block(fa1, fb1);
+    mfma_rest(fa1, fb1);
     __builtin_amdgcn_sched_barrier(0);
   }
   if (KT > 0) {  // last tile: nothing left to prefetch
@@ -734,7 +753,7 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     else if (wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
     else rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // 64 KB of LDS: two workgroups per CU
   } else if (a.K % 64 == 0 && a.K >= 64 && tune != 3) {
-    rc = launch_dma<128, 256, 2, 2, 4>(a, stream);
+    rc = tune == 5 ? launch_dma<128, 256, 2, 2, 5>(a, stream) : tune == 6 ? launch_dma<128, 256, 2, 2, 3>(a, stream) : launch_dma<128, 256, 2, 2, 4>(a, stream);
   } else {
     rc = launch_mfma32<128, 256, 2, 2>(a, stream);
   }
