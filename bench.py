@@ -157,6 +157,7 @@ def main():
         return best
 
     per_shape = []
+    stream_us = {}
     for (M, N) in shapes:
         reps, s = weights[N]
 
@@ -164,10 +165,17 @@ def main():
             return msd.msd_gemm_w8a16(acts[M], reps[i % len(reps)], s, y=outs[(M, N)], ws=ws, prepare=True)
 
         us = time_calls(mk, 2 * len(reps))
+        if N not in stream_us:
+            # a bare read of the same weight bytes (no arithmetic, one launch), same cold-cache protocol:
+            # what this GPU charges for the stream alone at this size
+            stream_us[N] = time_calls(lambda i, reps=reps: msd.msd_stream_read(reps[i % len(reps)], prepare=True),
+                                      2 * len(reps))
         b = w8_bytes(M, K, N)
         per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2),
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
-                          "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2)})
+                          "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2),
+                          "bare_weight_read_us": round(stream_us[N], 2),
+                          "bare_read_over_call": round(stream_us[N] / us, 3)})
     dom = max(per_shape, key=lambda r: r["us_per_call"] )
     # HBM bytes per call from the committed counter summary (FETCH_SIZE / WRITE_SIZE runs of
     # `bench.py --traffic-probe`, scaled by a copy of known size); null when the file has no line for it

@@ -156,6 +156,16 @@ int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
                            int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,
                            const msd_debug_taps* taps, void* stream);
 
+/*
+ * Measurement aid (not a step of the method; no paper passage).  Reads the row-major byte
+ * matrix src [rows][row_bytes] (device) once, in the access pattern of the decode kernels'
+ * weight stream, computes nothing and writes nothing.  bench.py times it next to the GEMM
+ * calls: it is what the same weight bytes cost on this GPU with no arithmetic, launch
+ * included.  row_bytes must be a positive multiple of 256, src 16-byte aligned; rows == 0
+ * is a no-op.  Errors: MSD_ERR_INVALID_ARG, MSD_ERR_SHAPE, MSD_ERR_HIP.
+ */
+int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

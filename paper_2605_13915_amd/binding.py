@@ -59,8 +59,9 @@ def lib():
                                              vp, vp]
         L.msd_attn_decode_int8kv_workspace_bytes.argtypes = [ci, ci, ci, ci, i64]
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
+        L.msd_stream_read.argtypes = [vp, i64, i64, vp]
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
-                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16"):
+                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -200,6 +201,14 @@ def msd_dequant_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws
     _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
     return _gemm_common("msd_dequant_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x,
                         (_ptr(W_fp4), _ptr(W_e8m0)), W_fp4.shape[0], out_dtype, False, y, ws, prepare)
+
+
+def msd_stream_read(t, prepare=False):
+    """Measurement aid: bare read of the 2-D byte tensor t (rows of a multiple of 256 bytes)."""
+    assert t.is_cuda and t.dim() == 2 and t.is_contiguous() and t.element_size() == 1
+    args = (_ptr(t), t.shape[0], t.shape[1], _stream())
+    call = Prepared(lib().msd_stream_read, args, (t,), "msd_stream_read", None)
+    return call if prepare else call()
 
 
 def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,

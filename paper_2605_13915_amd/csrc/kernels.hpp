@@ -86,4 +86,7 @@ int launch_dequant_gemm_w4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx,
                            const uint8_t* We, int64_t N, void* y, int out_bf16, int64_t ldy,
                            hipStream_t stream);
 
+// ---- measurement aid (stream_probe.hip)
+int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream);
+
 }  // namespace msd

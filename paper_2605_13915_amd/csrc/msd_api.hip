@@ -247,4 +247,12 @@ int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
                                 out_dtype == MSD_BF16, ldy, (hipStream_t)stream);
 }
 
+int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stream) {
+  if (rows < 0 || row_bytes < 0) return MSD_ERR_SHAPE;
+  if (rows == 0) return MSD_OK;
+  if (row_bytes == 0 || row_bytes % 256 != 0) return MSD_ERR_SHAPE;
+  if (!src || !aligned_to(src, 16)) return MSD_ERR_INVALID_ARG;
+  return launch_stream_read(src, rows, row_bytes, (hipStream_t)stream);
+}
+
 }  // extern "C"

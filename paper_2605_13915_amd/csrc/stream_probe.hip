@@ -1,0 +1,41 @@
+// Measurement aid, not part of the method: a bare read of a row-major byte matrix in the access
+// pattern of the decode kernels' weight stream (a workgroup owns 16 rows, its four waves split
+// the row, each wave instruction fetches 16 rows x 64 B, eight instructions in flight per lane).
+// Nothing is computed or written.  Its time is what the same bytes cost on this GPU with no
+// arithmetic at all, launch included: the floor the decode kernels are measured against.
+#include "kernels.hpp"
+
+namespace msd {
+
+__device__ int g_stream_probe_sink;
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const int8_t* __restrict__ src, int64_t rows,
+                                                          int64_t row_bytes) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = min((int64_t)blockIdx.x * 16 + (lane & 15), rows - 1);
+  const int64_t quarter = row_bytes / 4;  // row_bytes % 256 == 0 (checked on the host)
+  const int8_t* p = src + row * row_bytes + wave * quarter + 16 * (lane >> 4);
+  v4i acc = {0, 0, 0, 0};
+  for (int64_t k0 = 0; k0 < quarter; k0 += 64 * 8) {
+    v4i r[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int64_t k = min(k0 + 64 * u, quarter - 64);  // the tail re-reads the last 64-byte column
+      r[u] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p + k));
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= r[u];
+  }
+  // keeps the loads alive; the condition is practically never true and the value is never read
+  if (acc[0] == 0x5EEDBEEF && acc[1] == 0x0BADF00D && acc[2] == acc[3]) g_stream_probe_sink = acc[2];
+}
+
+int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream) {
+  if (rows == 0 || row_bytes == 0) return MSD_OK;
+  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)cdiv(rows, 16)), dim3(256), 0, stream,
+                     (const int8_t*)src, rows, row_bytes);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+}  // namespace msd

@@ -48,3 +48,7 @@ def test_workspace_queries_and_host_side_validation():
     assert lib.msd_decompose(0, None, 0, 16, 16, None, None, None, None) == 0       # empty: no-op
     assert lib.msd_decompose(1, ctypes.c_void_p(256), 1, 48, 48, ctypes.c_void_p(256), ctypes.c_void_p(256),
                              ctypes.c_void_p(256), None) == -2                      # K % 32 != 0
+    lib.msd_stream_read.argtypes = [ctypes.c_void_p, i64, i64, ctypes.c_void_p]
+    assert lib.msd_stream_read(ctypes.c_void_p(256), 16, 100, None) == -2            # row_bytes % 256 != 0
+    assert lib.msd_stream_read(None, 16, 256, None) == -1                           # null pointer
+    assert lib.msd_stream_read(None, 0, 256, None) == 0                             # empty: no-op

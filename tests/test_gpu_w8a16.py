@@ -62,6 +62,8 @@ SHAPES = [
     (1100, 512, 4200, 1),      # >= 128 large tiles: the asynchronous-LDS-fill kernel, ragged M and N
     (128, 256, 12800, 1),      # batched decode, 64x128 tiles of the asynchronous-fill kernel
     (70, 320, 6500, 1),        # batched decode, 64x64 tiles, ragged M and N
+    (30, 512, 8300, 1),        # 16 < M <= 32 with many columns: 32x64 tiles of the asynchronous-fill kernel
+    (32, 528, 8300, 0),        # same M and N, K not a multiple of 64: register-operand kernel, wide variant
 ]
 
 
