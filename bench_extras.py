@@ -61,8 +61,10 @@ def leg_prefill(msd, synth, time_calls, dev):
         rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "eff_TOPS": round(2.0 * M * K * N / us / 1e6, 1),
                "int8_mfma_frac": round(4.0 * M * K * N / us / 1e6 / INT8_TOPS, 4)}
+        ws2 = g = None
         try:
-            g = lambda i: msd.msd_dequant_gemm_w8a16(x, W, s, y=y, ws=ws)
+            ws2 = torch.empty(msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+            g = lambda i: msd.msd_dequant_gemm_w8a16(x, W, s, y=y, ws=ws2)
             g(0)
             us2 = _eager_us(g, 2)
             rec["cmp_dequant_us"] = round(us2, 1)
@@ -70,7 +72,7 @@ def leg_prefill(msd, synth, time_calls, dev):
         except Exception as e:  # noqa: BLE001
             rec["cmp_error"] = str(e)
         out.append(rec)
-        del x, W, y, ws
+        del x, W, y, ws, ws2, f, g
         torch.cuda.empty_cache()
     return out
 
@@ -100,7 +102,8 @@ def leg_w4(msd, synth, time_calls, dev):
                "hbm_frac": round(b / us / 1e3 / HBM, 4), "exec_TFLOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
         try:
-            g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws, prepare=M <= 32)
+            ws2 = torch.empty(msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+            g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws2, prepare=M <= 32)
             if M <= 32:
                 us2 = time_calls(g, 2 * len(reps))
             else:
@@ -154,7 +157,8 @@ def leg_cmp_decode(msd, synth, time_calls, dev):
             y = torch.empty((M, N), dtype=torch.float32, device=dev)
             ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
             f = lambda i: msd.msd_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws, prepare=True)
-            g = lambda i: msd.msd_dequant_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws, prepare=True)
+            ws2 = torch.empty(msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+            g = lambda i: msd.msd_dequant_gemm_w8a16(x, reps[i % len(reps)], s, y=y, ws=ws2, prepare=True)
             us_msd = time_calls(f, 2 * len(reps))
             us_cmp = time_calls(g, 2 * len(reps))
             out.append({"M": M, "K": K, "N": N, "msd_us": round(us_msd, 2), "dequant_us": round(us_cmp, 2),

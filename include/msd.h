@@ -145,8 +145,13 @@ size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int
  * Comparison kernels (the conventional path the paper argues against, Sec. 3.1 first
  * equation): weights are lifted to BF16 inside the kernel (bf16(s_W*W) for INT8, exact for
  * MXFP4) and multiplied on BF16 matrix instructions with fp32 accumulation.  Same
- * arguments as the MSD entry points; taps are ignored.
+ * arguments as the MSD entry points; taps are ignored.  With M >= 256 and a workspace of
+ * msd_dequant_gemm_workspace_bytes(M, K, N) bytes (16-byte aligned, room for a BF16 copy of
+ * W) the literal two-step form runs: one pass writes bf16(W) to the workspace, then a tiled
+ * BF16 GEMM built on the MSD prefill pipeline multiplies.  With a smaller or null workspace,
+ * or fewer rows, the weights are lifted inside a single streaming kernel.
  */
+size_t msd_dequant_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
                            const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
                            void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,

@@ -52,7 +52,8 @@ def lib():
         L.msd_dequant_gemm_w8a16.argtypes = gemm8
         L.msd_gemm_w4a16.argtypes = gemm4
         L.msd_dequant_gemm_w4a16.argtypes = gemm4
-        for f in (L.msd_gemm_w8a16_workspace_bytes, L.msd_gemm_w4a16_workspace_bytes):
+        for f in (L.msd_gemm_w8a16_workspace_bytes, L.msd_gemm_w4a16_workspace_bytes,
+                  L.msd_dequant_gemm_workspace_bytes):
             f.argtypes = [i64, i64, i64]
             f.restype = sz
         L.msd_attn_decode_int8kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, i64, vp, ci, vp, sz,
@@ -186,7 +187,7 @@ def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, w
 def msd_dequant_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, y=None, ws=None, prepare=False):
     _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
     assert W.is_contiguous()
-    return _gemm_common("msd_dequant_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x,
+    return _gemm_common("msd_dequant_gemm_w8a16", "msd_dequant_gemm_workspace_bytes", x,
                         (_ptr(W), _ptr(w_scale)), W.shape[0], out_dtype, False, y, ws, prepare)
 
 
@@ -199,7 +200,7 @@ def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None
 
 def msd_dequant_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws=None, prepare=False):
     _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
-    return _gemm_common("msd_dequant_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x,
+    return _gemm_common("msd_dequant_gemm_w4a16", "msd_dequant_gemm_workspace_bytes", x,
                         (_ptr(W_fp4), _ptr(W_e8m0)), W_fp4.shape[0], out_dtype, False, y, ws, prepare)
 
 

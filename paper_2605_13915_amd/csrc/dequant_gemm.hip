@@ -5,7 +5,8 @@
 // BF16 activations on v_mfma_f32_16x16x32_bf16 with fp32 accumulation.  Same work split as
 // the MSD skinny kernels (16 output channels per workgroup, K split over the waves), so the
 // two paths differ only in what the paper changes: per-element weight conversion on the
-// vector ALU and a BF16 instead of an INT8 / FP4 matrix instruction.
+// vector ALU and a BF16 instead of an INT8 / FP4 matrix instruction.  With 256 or more
+// activation rows (and enough workspace) the two-step form at the end of this file runs instead.
 #include "kernels.hpp"
 
 namespace msd {
@@ -160,16 +161,76 @@ static int launch_dq(const DqArgs& a, hipStream_t stream) {
   return MSD_OK;
 }
 
+// ------------------------------------------------------------------ prefill: dequantise, then GEMM
+// For many activation rows the comparison path is the literal two-step form: one pass lifts the
+// whole weight matrix to BF16 in HBM (bf16(s_W * w), or the exact MXFP4 value), then a BF16 GEMM
+// runs on the same asynchronous-fill pipeline as the MSD prefill kernel (launch_bf16_gemm_tiled),
+// so that both paths get the same engineering.  Needs 2*N*K bytes of workspace.
+constexpr int64_t kTiledMinRows = 256;
+
+__global__ __launch_bounds__(256) void dequant_w8_to_bf16_kernel(const int8_t* __restrict__ W,
+                                                                 const float* __restrict__ w_scale, int64_t N,
+                                                                 int64_t K, uint16_t* __restrict__ out) {
+  const int64_t chunks = K / 16;  // 16 weights per thread
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= N * chunks) return;
+  const int64_t n = gid / chunks;
+  const v4i w = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(W) + gid);
+  Frag8 f[2];
+  dequant_i8x16(w, w_scale[n], f);
+  uint4* o = reinterpret_cast<uint4*>(out + gid * 16);
+  o[0] = make_uint4(f[0].u[0], f[0].u[1], f[0].u[2], f[0].u[3]);
+  o[1] = make_uint4(f[1].u[0], f[1].u[1], f[1].u[2], f[1].u[3]);
+}
+
+__global__ __launch_bounds__(256) void dequant_w4_to_bf16_kernel(const uint8_t* __restrict__ W,
+                                                                 const uint8_t* __restrict__ We, int64_t blocks,
+                                                                 uint16_t* __restrict__ out) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 32-element block per thread
+  if (gid >= blocks) return;
+  const v4i w = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(W) + gid);
+  Frag8 f[4];
+  dequant_fp4x32(w, (int)We[gid], f);
+  uint4* o = reinterpret_cast<uint4*>(out + gid * 32);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = make_uint4(f[i].u[0], f[i].u[1], f[i].u[2], f[i].u[3]);
+}
+
+size_t dequant_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+  return M >= kTiledMinRows ? align_up((size_t)N * K * 2, 256) : 0;
+}
+
+static bool use_tiled(int64_t M, int64_t K, const uint16_t* x, int64_t ldx, void* ws, size_t ws_bytes, int64_t N) {
+  return M >= kTiledMinRows && K % 32 == 0 && K > 0 && ws != nullptr && ws_bytes >= (size_t)N * K * 2 &&
+         (reinterpret_cast<uintptr_t>(x) & 15) == 0 && ldx % 8 == 0 && (reinterpret_cast<uintptr_t>(ws) & 15) == 0;
+}
+
 int launch_dequant_gemm_w8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
-                           const float* w_scale, int64_t N, void* y, int out_bf16, int64_t ldy,
-                           hipStream_t stream) {
+                           const float* w_scale, int64_t N, void* y, int out_bf16, int64_t ldy, void* ws,
+                           size_t ws_bytes, hipStream_t stream) {
+  if (use_tiled(M, K, x, ldx, ws, ws_bytes, N)) {
+    uint16_t* Wb = reinterpret_cast<uint16_t*>(ws);
+    const int64_t items = N * (K / 16);
+    hipLaunchKernelGGL(dequant_w8_to_bf16_kernel, dim3((unsigned)cdiv(items, 256)), dim3(256), 0, stream, W,
+                       w_scale, N, K, Wb);
+    MSD_LAUNCH_CHECK();
+    return launch_bf16_gemm_tiled(x, M, K, ldx, Wb, N, y, out_bf16, ldy, stream);
+  }
   DqArgs a{x, ldx, (const uint8_t*)W, w_scale, nullptr, y, out_bf16, ldy, M, K, N};
   return launch_dq<8>(a, stream);
 }
 
 int launch_dequant_gemm_w4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const uint8_t* W,
-                           const uint8_t* We, int64_t N, void* y, int out_bf16, int64_t ldy,
-                           hipStream_t stream) {
+                           const uint8_t* We, int64_t N, void* y, int out_bf16, int64_t ldy, void* ws,
+                           size_t ws_bytes, hipStream_t stream) {
+  if (use_tiled(M, K, x, ldx, ws, ws_bytes, N)) {
+    uint16_t* Wb = reinterpret_cast<uint16_t*>(ws);
+    const int64_t blocks = N * (K / 32);
+    hipLaunchKernelGGL(dequant_w4_to_bf16_kernel, dim3((unsigned)cdiv(blocks, 256)), dim3(256), 0, stream, W, We,
+                       blocks, Wb);
+    MSD_LAUNCH_CHECK();
+    return launch_bf16_gemm_tiled(x, M, K, ldx, Wb, N, y, out_bf16, ldy, stream);
+  }
   DqArgs a{x, ldx, W, nullptr, We, y, out_bf16, ldy, M, K, N};
   return launch_dq<4>(a, stream);
 }

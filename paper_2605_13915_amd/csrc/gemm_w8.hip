@@ -20,6 +20,7 @@
 //            of the two components; for prefill-sized problems a 256x256 tile filled by
 //            asynchronous global->LDS loads four stages deep.
 #include <cstdlib>
+#include <type_traits>
 
 #include "decompose_int8_dev.hpp"
 #include "kernels.hpp"
@@ -283,6 +284,10 @@ __device__ __forceinline__ v16i mfma32(v4i a, v4i b, v16i c) {
   return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
+__device__ __forceinline__ v16f mfma32(v4i a, v4i b, v16f c) {  // the 16 bytes are 8 BF16 values
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+
 constexpr int kGroupM = 8;
 
 template <int BMH, int BN, int WM, int WN>
@@ -446,6 +451,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_mfma32_kernel(GemmW8Args
 // where the weight stream is cold and the bytes in flight per CU, i.e. the stage count, set the
 // HBM rate (Little's law), not the MFMA.
 __device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  // the base is wave-uniform by construction; say so, or the "s" operand may be given a VGPR pair
+  const uint64_t g = reinterpret_cast<uint64_t>(gbase);
+  const uint32_t glo = __builtin_amdgcn_readfirstlane((uint32_t)g), ghi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
+  gbase = reinterpret_cast<const int8_t*>(((uint64_t)ghi << 32) | glo);
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(voff), "s"(gbase), "s"(lds_addr)
@@ -458,8 +468,16 @@ __device__ __forceinline__ void wait_vm_barrier() {
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int BMH, int BN, int WM, int WN, int NS>
+//
+// BF16 = true turns the same pipeline into a plain BF16 GEMM for the comparison path (weights
+// already lifted to BF16 in HBM): a 64-byte row chunk is 32 BF16 values instead of 64 codes, the
+// matrix instruction is v_mfma_f32_32x32x16_bf16 (same 16 bytes per lane and K group, so the LDS
+// layout and every fragment offset are unchanged), the A rows are 2*BMH consecutive activation
+// rows instead of two components of BMH rows, and the epilogue stores the fp32 sums.  The
+// argument struct is reused with byte units: q1 = activations, ldq and K in bytes, W = BF16 weights.
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+  using AccT = std::conditional_t<BF16, v16f, v16i>;
   constexpr int NW = WM * WN, ROWS_A = 2 * BMH, R = ROWS_A + BN;
   constexpr int TMH = BMH / WM, TN = BN / WN, FM = TMH / 32, FN = TN / 32;
   constexpr int L = R / (16 * NW);   // load instructions per wave and stage
@@ -485,7 +503,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
   const int in_group = id - group * kGroupM * tiles_n;
   const int tm = first_m + in_group % rows_in_group;
   const int tn = in_group / rows_in_group;
-  const int64_t m0 = (int64_t)tm * BMH, n0 = (int64_t)tn * BN;
+  const int64_t m0 = (int64_t)tm * (BF16 ? ROWS_A : BMH), n0 = (int64_t)tn * BN;
 
   // ---- this wave's L load instructions per stage: 16-row block q*NW + wave of the stage
   // (blocks 0 .. ROWS_A/16-1 are q1 then q2 rows, the rest W rows)
@@ -500,9 +518,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     const int blk = q * NW + wave;
     if (blk < ROWS_A / 16) {
       const int comp = blk / (BMH / 16);
-      const int64_t mrow = min(m0 + (blk % (BMH / 16)) * 16 + rr, M - 1);
+      const int64_t mrow = min(m0 + (BF16 ? comp * BMH : 0) + (blk % (BMH / 16)) * 16 + rr, M - 1);
       voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
-      gbase[q] = (comp ? a.q2 : a.q1) + m0 * a.ldq;
+      gbase[q] = ((comp && !BF16) ? a.q2 : a.q1) + m0 * a.ldq;
     } else {
       const int64_t nrow = min(n0 + (blk - ROWS_A / 16) * 16 + rr, N - 1);
       voff[q] = (uint32_t)((nrow - n0) * K + lc * 16);
@@ -518,7 +536,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     for (int q = 0; q < L; ++q) lds_dma16(gbase[q] + k0, voff[q], ldst[q] + sb);
   };
 
-  v16i acc[2][FM][FN];
+  AccT acc[2][FM][FN];
 #pragma unroll
   for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -619,6 +637,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     mfma_block(fa1, fb1);
   }
 
+  if constexpr (BF16) {
+    // ---- plain epilogue of the comparison GEMM
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t m = m0 + c * BMH + wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
+          if (m < M) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+              const int64_t n = n0 + wn * TN + 32 * j + l32;
+              if (n < N) store_out(a.y, a.out_bf16, m * a.ldy + n, acc[c][i][j][r]);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+    return;
+  } else {
   // ---- dual-scale epilogue.  alpha and beta of the tile's rows go through LDS (free now), the
   // output is produced one (fragment, register) row at a time so that the compiler does not pull
   // all accumulators into VGPRs at once.
@@ -657,23 +695,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+  }
 }
 
-template <int BMH, int BN, int WM, int WN, int NS>
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false>
 static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
-  const int tiles_m = (int)cdiv(a.M, BMH), tiles_n = (int)cdiv(a.N, BN);
+  const int tiles_m = (int)cdiv(a.M, BF16 ? 2 * BMH : BMH), tiles_n = (int)cdiv(a.N, BN);
   const int total = tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
   const size_t lds = (size_t)NS * (2 * BMH + BN) * 64;
   static_assert((size_t)NS * (2 * BMH + BN) * 64 <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS>), dim3(grid), dim3(WM * WN * 64), lds, stream, a,
-                     tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16>), dim3(grid), dim3(WM * WN * 64), lds, stream,
+                     a, tiles_m, tiles_n);
   return MSD_OK;
 }
 
@@ -691,6 +730,27 @@ static int launch_mfma32(const GemmW8Args& a, hipStream_t stream) {
   }
   hipLaunchKernelGGL((gemm_w8_mfma32_kernel<BMH, BN, WM, WN>), dim3(grid), dim3(WM * WN * 64), lds, stream, a,
                      tiles_m, tiles_n);
+  return MSD_OK;
+}
+
+// Plain BF16 GEMM y = x Wb^T (fp32 accumulation) on the asynchronous-fill pipeline, for the
+// comparison path.  x [M][ldx] BF16 (rows 16-byte aligned), Wb [N][K] BF16, K % 32 == 0.
+int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const uint16_t* Wb, int64_t N,
+                           void* y, int out_bf16, int64_t ldy, hipStream_t stream) {
+  GemmW8Args a{};
+  a.q1 = reinterpret_cast<const int8_t*>(x);
+  a.q2 = a.q1;
+  a.ldq = 2 * ldx;
+  a.W = reinterpret_cast<const int8_t*>(Wb);
+  a.y = y;
+  a.out_bf16 = out_bf16;
+  a.ldy = ldy;
+  a.M = M;
+  a.K = 2 * K;
+  a.N = N;
+  const int rc = launch_dma<128, 256, 2, 2, 4, true>(a, stream);
+  if (rc) return rc;
+  MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
 

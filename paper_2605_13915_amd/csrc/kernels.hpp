@@ -79,12 +79,18 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream);
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
 
 // ---- comparison kernels (dequant_gemm.hip)
+// ws / ws_bytes: optional scratch for the BF16 copy of the weights (dequant_workspace_bytes);
+// without it the fused single-kernel form runs whatever M is
 int launch_dequant_gemm_w8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
-                           const float* w_scale, int64_t N, void* y, int out_bf16, int64_t ldy,
-                           hipStream_t stream);
+                           const float* w_scale, int64_t N, void* y, int out_bf16, int64_t ldy, void* ws,
+                           size_t ws_bytes, hipStream_t stream);
 int launch_dequant_gemm_w4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const uint8_t* W,
-                           const uint8_t* We, int64_t N, void* y, int out_bf16, int64_t ldy,
-                           hipStream_t stream);
+                           const uint8_t* We, int64_t N, void* y, int out_bf16, int64_t ldy, void* ws,
+                           size_t ws_bytes, hipStream_t stream);
+size_t dequant_workspace_bytes(int64_t M, int64_t K, int64_t N);
+// plain BF16 GEMM on the asynchronous-fill pipeline (gemm_w8.hip), used by the comparison path
+int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const uint16_t* Wb, int64_t N,
+                           void* y, int out_bf16, int64_t ldy, hipStream_t stream);
 
 // ---- measurement aid (stream_probe.hip)
 int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream);

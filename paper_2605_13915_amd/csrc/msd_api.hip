@@ -221,7 +221,7 @@ int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
 
 int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
                            const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
-                           void* /*workspace*/, size_t /*workspace_bytes*/, const msd_debug_taps* /*taps*/,
+                           void* workspace, size_t workspace_bytes, const msd_debug_taps* /*taps*/,
                            void* stream) {
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
@@ -230,12 +230,12 @@ int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
   if (!y || !w_scale || (K > 0 && (!x_bf16 || !W))) return MSD_ERR_INVALID_ARG;
   if (!aligned_to(W, 16) || !aligned_to(x_bf16, 16) || ldx % 8 != 0) return MSD_ERR_INVALID_ARG;
   return launch_dequant_gemm_w8((const uint16_t*)x_bf16, M, K, ldx, W, w_scale, N, y,
-                                out_dtype == MSD_BF16, ldy, (hipStream_t)stream);
+                                out_dtype == MSD_BF16, ldy, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
                            const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
-                           void* /*workspace*/, size_t /*workspace_bytes*/, const msd_debug_taps* /*taps*/,
+                           void* workspace, size_t workspace_bytes, const msd_debug_taps* /*taps*/,
                            void* stream) {
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
@@ -244,7 +244,12 @@ int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
   if (!y || (K > 0 && (!x_bf16 || !W_fp4 || !W_e8m0))) return MSD_ERR_INVALID_ARG;
   if (!aligned_to(W_fp4, 16) || !aligned_to(x_bf16, 16) || ldx % 8 != 0) return MSD_ERR_INVALID_ARG;
   return launch_dequant_gemm_w4((const uint16_t*)x_bf16, M, K, ldx, W_fp4, W_e8m0, N, y,
-                                out_dtype == MSD_BF16, ldy, (hipStream_t)stream);
+                                out_dtype == MSD_BF16, ldy, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t msd_dequant_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+  if (M <= 0 || K <= 0 || N <= 0) return 256;
+  return dequant_workspace_bytes(M, K, N) + 256;
 }
 
 int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stream) {

@@ -33,6 +33,33 @@ def test_dequant_w8_matches_oracle_baseline(msd, M, K, N):
     assert rel_l2(y_msd.cpu().numpy(), truth) * 2 < rel_l2(y.cpu().numpy(), truth)
 
 
+@pytest.mark.parametrize("M,K,N", [(256, 512, 300), (300, 1056, 520), (700, 256, 777)])
+def test_dequant_w8_two_step_form(msd, M, K, N):
+    """M >= 256 with the full workspace: weights are written to HBM as BF16, then a tiled BF16 GEMM runs."""
+    x = synth.activations(67 + M, M, K)
+    W, s = synth.int8_weights(67 + M, N, K)
+    ref = oracle.dequant_gemm_w8a16(x, W, s)
+    xd, Wd, sd = bf16_to_dev(x), to_dev(W), to_dev(s)
+    y = msd.msd_dequant_gemm_w8a16(xd, Wd, sd)
+    torch.cuda.synchronize()
+    assert rel_l2(y.cpu().numpy(), ref) <= 1e-5
+    # the single-kernel form (no workspace) computes the same thing
+    tiny = torch.empty(256, dtype=torch.uint8, device="cuda")
+    y1 = msd.msd_dequant_gemm_w8a16(xd, Wd, sd, ws=tiny)
+    torch.cuda.synchronize()
+    assert rel_l2(y1.cpu().numpy(), ref) <= 1e-5
+
+
+def test_dequant_w4_two_step_form(msd):
+    M, K, N = 300, 544, 200
+    x = synth.activations(73, M, K)
+    codes, exps = synth.mxfp4_weights(73, N, K)
+    truth = oracle.truth_gemm_w4(x, codes, exps)
+    y = msd.msd_dequant_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps))
+    torch.cuda.synchronize()
+    assert rel_l2(y.cpu().numpy(), truth) <= 1e-5
+
+
 @pytest.mark.parametrize("M,K,N", [(1, 8192, 256), (32, 2048, 128), (40, 544, 72)])
 def test_dequant_w4_matches_truth(msd, M, K, N):
     x = synth.activations(71 + M, M, K)
