@@ -1,0 +1,390 @@
+// W4A16 MSD GEMM, MFMA-bound regime (many activation rows): paper Sec. 3.2.1 / Alg. 2 feeding
+// Sec. 3.4.1, on v_mfma_scale_f32_32x32x64_f8f6f4 with an asynchronous global -> LDS pipeline.
+//
+// Three launches per call:
+//   (1) decompose_mxfp4_pair_kernel: Alg. 2 per 32-element block; writes the FP6-E2M3 operands of
+//       both components K-step-major and already in the GEMM's LDS order, so that the GEMM copies
+//       them with perfectly contiguous 1 KB fetches (the rate of the global -> LDS path falls with
+//       the number of cache lines an instruction touches):
+//         qop[K step][group of 32 rows][6 chunks][32 rows][16 B]
+//         chunk 3c+b = dwords 0..3 of block b of component c, chunk 3c+2 = [dwords 4,5 of block 0 | of block 1]
+//       and the alpha bytes as sa_t[K step][tile of 256 rows][512 B], byte wm*256 + b*128 + l*4 + i
+//       for row wm*128 + 32*i + l of the tile and block b: a lane's four row fragments read their
+//       scale bytes as one dword and pick the byte with the instruction's op_sel.
+//   (2) transpose_w_scales_kernel: the weights' E8M0 bytes [N][K/32] -> sw_t in the same layout
+//       over columns (the weight values themselves are consumed where they are).
+//   (3) gemm_w4_dma_kernel: 256 x 256 output tile, 4 waves of 128 x 128, one K step = 64 elements
+//       = two MX blocks = exactly one MFMA K extent (lane l: row/column l%32, block l/32).  A stage
+//       is 33 KB: 24 KB activation operands, 8 KB weights, 1 KB scale bytes, filled by 33
+//       global_load_lds_dwordx4 instructions (8 per wave, wave 0 one more for the scales), NS stages
+//       deep.  Both components accumulate into the same fp32 accumulator (scale bytes alpha and
+//       alpha - 4, i.e. beta = alpha / 16), so the 256 x 256 tile needs 256 accumulator registers.
+//
+// LDS layout of a stage (every fragment read is linear in the lane, hence conflict-free, except
+// the 8-byte tails):
+//   activations: 8 groups of 32 rows, each [6 chunks][32 rows][16 B] as in qop;
+//   weights:     8 groups of 32 columns, group = [2 blocks][32 columns][16 B] (= lane order);
+//   scales:      512 B for the rows, 512 B for the columns, layout as in sa_t.
+#include "decompose_mxfp4_dev.hpp"
+#include "kernels.hpp"
+
+namespace msd {
+
+// ------------------------------------------------------------------ (1) decomposition, K-step pairs
+__device__ __forceinline__ int scale_slot(int r, int b) {  // byte of (row or column r of a 256 tile, block b)
+  return (r >> 7) * 256 + b * 128 + (r & 31) * 4 + ((r >> 5) & 3);
+}
+
+__global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_t* __restrict__ x, int64_t ldx,
+                                                                   int64_t M, int KB2, int64_t Mpad,
+                                                                   uint32_t* __restrict__ qop,
+                                                                   uint8_t* __restrict__ sa_t, int aligned) {
+  // consecutive threads take consecutive rows of one K step: their 16-byte stores are adjacent
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= M * KB2) return;
+  const int s = (int)(gid / M);
+  const int64_t m = gid % M;
+  uint32_t p1[2][6], p2[2][6];
+  int eb[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const uint16_t* xb = x + m * ldx + ((int64_t)2 * s + b) * 32;
+    uint32_t w[16];
+    if (aligned) {
+      const uint4* q = reinterpret_cast<const uint4*>(xb);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint4 v = q[i];
+        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
+    }
+    int k1[32], k2[32];
+    const int e = mx_block_codes(w, k1, k2);
+    pack_fp6(k1, p1[b]);
+    pack_fp6(k2, p2[b]);
+    eb[b] = e + 127;
+  }
+  // group of 32 rows: [6 chunks][32 rows][4 dwords]
+  uint4* d = reinterpret_cast<uint4*>(qop) + (((int64_t)s * (Mpad / 32) + m / 32) * 6) * 32 + (m % 32);
+  d[0 * 32] = make_uint4(p1[0][0], p1[0][1], p1[0][2], p1[0][3]);
+  d[1 * 32] = make_uint4(p1[1][0], p1[1][1], p1[1][2], p1[1][3]);
+  d[2 * 32] = make_uint4(p1[0][4], p1[0][5], p1[1][4], p1[1][5]);
+  d[3 * 32] = make_uint4(p2[0][0], p2[0][1], p2[0][2], p2[0][3]);
+  d[4 * 32] = make_uint4(p2[1][0], p2[1][1], p2[1][2], p2[1][3]);
+  d[5 * 32] = make_uint4(p2[0][4], p2[0][5], p2[1][4], p2[1][5]);
+  uint8_t* sc = sa_t + ((int64_t)s * (Mpad / 256) + m / 256) * 512;
+  sc[scale_slot((int)(m % 256), 0)] = (uint8_t)eb[0];
+  sc[scale_slot((int)(m % 256), 1)] = (uint8_t)eb[1];
+}
+
+// ------------------------------------------------------------------ (2) weight scale bytes, K-step-major
+// One workgroup moves a 64 (columns) x 64 (K steps) tile of byte pairs through LDS so that both the
+// reads (along K) and the writes (along N) are contiguous.
+__global__ __launch_bounds__(256) void transpose_w_scales_kernel(const uint8_t* __restrict__ We, int64_t N,
+                                                                 int KB2, int64_t Npad,
+                                                                 uint8_t* __restrict__ sw_t) {
+  __shared__ uint16_t tile[64][65];
+  const int64_t n0 = (int64_t)blockIdx.x * 64;
+  const int s0 = blockIdx.y * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int r = i >> 6, c = i & 63;  // r: column of W within the tile, c: K step
+    const int64_t n = n0 + r;
+    const int s = s0 + c;
+    uint16_t v = 0x7F7F;
+    if (n < N && s < KB2) {
+      const uint8_t* p = We + (n * KB2 + s) * 2;
+      v = (uint16_t)p[0] | ((uint16_t)p[1] << 8);
+    }
+    tile[r][c] = v;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int c = i >> 6, r = i & 63;  // consecutive threads -> consecutive columns of W
+    const int64_t n = n0 + r;
+    const int s = s0 + c;
+    if (n < Npad && s < KB2) {
+      uint8_t* sc = sw_t + ((int64_t)s * (Npad / 256) + n / 256) * 512;
+      const uint16_t v = tile[r][c];
+      sc[scale_slot((int)(n % 256), 0)] = (uint8_t)(v & 0xFF);
+      sc[scale_slot((int)(n % 256), 1)] = (uint8_t)(v >> 8);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ (3) GEMM
+template <int SELA, int SELB>
+__device__ __forceinline__ v16f mfma64_scaled(v8i a, v8i b, v16f c, int sa, int sb) {
+  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); E8M0 scales: byte SELA of sa, byte SELB of sb
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 4, SELA, sa, SELB, sb);
+}
+
+__device__ __forceinline__ void w4_lds_dma16(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  // the base is wave-uniform by construction; say so, or the "s" operand may be given a VGPR pair
+  const uint64_t g = reinterpret_cast<uint64_t>(gbase);
+  const uint32_t glo = __builtin_amdgcn_readfirstlane((uint32_t)g), ghi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
+  gbase = reinterpret_cast<const uint8_t*>(((uint64_t)ghi << 32) | glo);
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void w4_wait_vm_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+constexpr int kW4PGroupM = 8;
+
+template <int NS>
+__global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, int tiles_m, int tiles_n) {
+  constexpr int SZ_A = 24576, SZ_W = 8192, STAGE = SZ_A + SZ_W + 1024;
+  constexpr int L = 8;  // data load instructions per wave and stage (wave 0 issues one more: scales)
+  static_assert(NS >= 3 && (NS - 2) * (L + 1) < 64, "stage count");
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem4p[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, kb = lane >> 5;
+  const int64_t M = a.M, N = a.N;
+  const int KT = (int)(a.K / 64);
+  const uint32_t step_a = (uint32_t)(a.Mpad * 96);  // bytes of qop per K step
+  const int64_t row_w = a.K / 2;           // bytes per weight row
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  {
+    const int per_xcd = (total + 7) / 8;
+    id = (id % 8) * per_xcd + id / 8;
+  }
+  if (id >= total) return;
+  const int group = id / (kW4PGroupM * tiles_n);
+  const int first_m = group * kW4PGroupM;
+  const int rows_in_group = min(kW4PGroupM, tiles_m - first_m);
+  const int in_group = id - group * kW4PGroupM * tiles_n;
+  const int tm = first_m + in_group % rows_in_group;
+  const int tn = in_group / rows_in_group;
+  const int64_t m0 = (int64_t)tm * 256, n0 = (int64_t)tn * 256;
+
+  // ---- this wave's load instructions per stage: instruction q*4 + wave of the 32 data instructions
+  // (0..23: activation group idx/3, chunk pair idx%3; 24..31: weight group idx-24)
+  uint32_t voff[L], ldst[L], kstep[L];
+  const uint8_t* gbase[L];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem4p;
+#pragma unroll
+  for (int q = 0; q < L; ++q) {
+    const int idx = q * 4 + wave;
+    if (idx < 24) {  // a contiguous kilobyte of qop: third j of row group gi
+      const int gi = idx / 3, j = idx % 3;
+      voff[q] = (uint32_t)(lane * 16);
+      gbase[q] = a.qop + ((m0 / 32 + gi) * 3 + j) * 1024;
+      ldst[q] = lds0 + gi * 3072 + j * 1024;
+      kstep[q] = step_a;
+    } else {
+      const int gj = idx - 24;
+      const int64_t nrow = min(n0 + 32 * gj + l32, N - 1);
+      voff[q] = (uint32_t)((nrow - n0) * row_w + kb * 16);
+      gbase[q] = a.W + n0 * row_w;
+      ldst[q] = lds0 + SZ_A + gj * 1024;
+      kstep[q] = 32;
+    }
+  }
+  // scale bytes of a stage: lanes 0..31 fetch the 512 bytes of sa_t[kt][tm], lanes 32..63 those of sw_t[kt][tn]
+  const uint8_t* sbase = kb ? a.sw_t : a.sa_t;                                     // per lane
+  const uint64_t s_first = (uint64_t)(sbase - a.ws) + (kb ? n0 : m0) * 2 + 16 * l32;  // byte offset from a.ws
+  const uint64_t s_inc = (uint64_t)(kb ? a.Npad : a.Mpad) * 2;                     // per K step
+  auto issue = [&](int kt) {
+    const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
+#pragma unroll
+    for (int q = 0; q < L; ++q) w4_lds_dma16(gbase[q] + (int64_t)kt * kstep[q], voff[q], ldst[q] + sb);
+    if (wave == 0) w4_lds_dma16(a.ws, (uint32_t)(s_first + (uint64_t)kt * s_inc), lds0 + sb + SZ_A + SZ_W);
+  };
+
+  v16f acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // per-lane LDS offsets inside a stage (kb*32 + l32 == lane, so the 16-byte reads are linear in the lane)
+  const uint32_t o_main = lane * 16, o_tail = l32 * 16 + 8 * kb, o_sc = kb * 128 + l32 * 4;
+  auto load_a = [&](int kt, int c, v8i (&fa)[4]) {  // component c of K step kt
+    const uint8_t* st = smem4p + (kt % NS) * STAGE + wm * (4 * 3072) + c * 1536;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 v = *reinterpret_cast<const uint4*>(st + i * 3072 + o_main);
+      const uint2 t = *reinterpret_cast<const uint2*>(st + i * 3072 + 1024 + o_tail);
+      fa[i] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, (int)t.x, (int)t.y, 0, 0};
+    }
+  };
+  // weights and scale bytes of K step kt; sa / sb: byte i = scale of row fragment i / column fragment i
+  auto load_b = [&](int kt, v8i (&fb)[4], int& sa, int& sb) {
+    const uint8_t* st = smem4p + (kt % NS) * STAGE;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint4 v = *reinterpret_cast<const uint4*>(st + SZ_A + (wn * 4 + j) * 1024 + o_main);
+      fb[j] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
+    }
+    sa = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + wm * 256 + o_sc);
+    sb = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + 512 + wn * 256 + o_sc);
+  };
+  // one component block: 16 MFMAs on 16 different accumulators; the first one is issued ahead of
+  // the LDS reads that run under the block, so that the compiler's wait for this block's
+  // operands (it cannot count LDS operations across the inline asm) covers no read just issued
+  auto mfma_first = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb) {
+    acc[0][0] = mfma64_scaled<0, 0>(fa[0], fb[0], acc[0][0], sa, sb);
+  };
+  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb) {
+#define MSD_W4_ROW(I)                                                                      \
+  if (I > 0) acc[I][0] = mfma64_scaled<I, 0>(fa[I], fb[0], acc[I][0], sa, sb);             \
+  acc[I][1] = mfma64_scaled<I, 1>(fa[I], fb[1], acc[I][1], sa, sb);                        \
+  acc[I][2] = mfma64_scaled<I, 2>(fa[I], fb[2], acc[I][2], sa, sb);                        \
+  acc[I][3] = mfma64_scaled<I, 3>(fa[I], fb[3], acc[I][3], sa, sb);
+    MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
+#undef MSD_W4_ROW
+  };
+  // wait until tile t has landed (the tiles issued after it may stay in flight), then barrier
+  auto wait_tile = [&](int t, int newest_issued) {
+    const int younger = newest_issued - t;
+    if (wave == 0) {
+      if (younger == NS - 2) w4_wait_vm_barrier<(NS - 2) * (L + 1)>();
+      else if (younger == NS - 3) w4_wait_vm_barrier<(NS - 3) * (L + 1)>();
+      else w4_wait_vm_barrier<0>();
+    } else {
+      if (younger == NS - 2) w4_wait_vm_barrier<(NS - 2) * L>();
+      else if (younger == NS - 3) w4_wait_vm_barrier<(NS - 3) * L>();
+      else w4_wait_vm_barrier<0>();
+    }
+  };
+
+  // Pipeline of K step s:  block 0 = component 1 ... the registers roll as follows.
+  //   first block  (component 0 of step s): under it the component-1 operands of step s are read;
+  //   barrier for tile s+1; the stage of tile s-1 is free now and is refilled with tile s-1+NS;
+  //   second block (component 1 of step s): under it the component-0 operands, the weights and
+  //   the scale bytes of step s+1 are read (weights and scales are double-buffered in registers,
+  //   the activation operands are not: each set is dead when its successor is fetched).
+  v8i a0[4], a1[4], b0[4], b1[4];
+  int sa0 = 0, sb0 = 0, sa1 = 0, sb1 = 0;
+  auto step = [&](int s, v8i (&bc)[4], int sac, int sbc, v8i (&bn)[4], int& san, int& sbn) {
+    mfma_first(a0, bc, sac, sbc);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(s, 1, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rest(a0, bc, sac, sbc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s + 1 < KT) {
+      wait_tile(s + 1, min(KT - 1, s + NS - 2));
+      if (s - 1 + NS < KT) issue(s - 1 + NS);
+    }
+    const int sac2 = sac - 0x04040404;  // beta = alpha / 16: every scale byte minus 4 (bytes are >= 4)
+    mfma_first(a1, bc, sac2, sbc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s + 1 < KT) {
+      load_a(s + 1, 0, a0);
+      load_b(s + 1, bn, san, sbn);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rest(a1, bc, sac2, sbc);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < KT) issue(t);
+  if (KT > 0) {
+    wait_tile(0, min(KT - 1, NS - 2));
+    load_a(0, 0, a0);
+    load_b(0, b0, sa0, sb0);
+  }
+  for (int s = 0; s < KT; s += 2) {
+    step(s, b0, sa0, sb0, b1, sa1, sb1);
+    if (s + 1 < KT) step(s + 1, b1, sa1, sb1, b0, sa0, sb0);
+  }
+
+  // ---- epilogue: the accumulators are the output (both components and all scales are in them)
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t m = m0 + wm * 128 + 32 * i + (r >> 2) * 8 + kb * 4 + (r & 3);
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t n = n0 + wn * 128 + 32 * j + l32;
+          if (n >= N) continue;
+          if (a.out_bf16)
+            reinterpret_cast<uint16_t*>(a.y)[m * a.ldy + n] = f32_to_bf16_bits(acc[i][j][r]);
+          else
+            reinterpret_cast<float*>(a.y)[m * a.ldy + n] = acc[i][j][r];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// ------------------------------------------------------------------ host side
+bool gemm_w4_prefill_applies(int64_t M, int64_t K, int64_t N) {
+  (void)N;
+  return M > 32 && K >= 64 && K % 64 == 0;
+}
+
+W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N) {
+  W4PrefillLayout l{};
+  const size_t KB2 = (size_t)K / 64;
+  l.Mpad = align_up((size_t)M, 256);
+  l.Npad = align_up((size_t)N, 256);
+  size_t off = 0;
+  l.qop = off; off = align_up(off + l.Mpad * KB2 * 96, 256);
+  l.sa_t = off; off = align_up(off + KB2 * l.Mpad * 2, 256);
+  l.sw_t = off; off = align_up(off + KB2 * l.Npad * 2, 256);
+  l.total = off;
+  return l;
+}
+
+int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
+                           int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
+                           hipStream_t stream) {
+  const W4PrefillLayout l = w4_prefill_layout(M, K, N);
+  if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace
+  const int KB2 = (int)(K / 64);
+  const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(decompose_mxfp4_pair_kernel, dim3((unsigned)cdiv(M * KB2, 256)), dim3(256), 0, stream, x, ldx,
+                     M, KB2, (int64_t)l.Mpad, reinterpret_cast<uint32_t*>(ws + l.qop), ws + l.sa_t, aligned);
+  MSD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(transpose_w_scales_kernel, dim3((unsigned)(l.Npad / 64), (unsigned)cdiv(KB2, 64)), dim3(256), 0,
+                     stream, We, N, KB2, (int64_t)l.Npad, ws + l.sw_t);
+  MSD_LAUNCH_CHECK();
+  GemmW4PrefillArgs a{};
+  a.ws = ws;
+  a.qop = ws + l.qop;
+  a.sa_t = ws + l.sa_t;
+  a.sw_t = ws + l.sw_t;
+  a.W = W;
+  a.y = y;
+  a.out_bf16 = out_bf16;
+  a.ldy = ldy;
+  a.M = M; a.K = K; a.N = N;
+  a.Mpad = (int64_t)l.Mpad;
+  a.Npad = (int64_t)l.Npad;
+  constexpr int NS = 4;
+  const int tiles_m = (int)cdiv(M, 256), tiles_n = (int)cdiv(N, 256);
+  const int total = tiles_m * tiles_n;
+  const int grid = ((total + 7) / 8) * 8;
+  const size_t lds = (size_t)NS * (24576 + 8192 + 1024);
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_dma_kernel<NS>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_w4_dma_kernel<NS>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+}  // namespace msd

@@ -58,6 +58,28 @@ struct GemmW4Args {
 bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
 
+// ---- W4A16, many rows (gemm_w4_prefill.hip): own decomposition format, asynchronous LDS fill
+struct GemmW4PrefillArgs {
+  const uint8_t* ws;    // workspace base (scale fetches use 32-bit offsets from it)
+  const uint8_t* qop;   // [M][K/64][96 B] FP6 operands of both components
+  const uint8_t* sa_t;  // [K/64][Mpad][2] activation scale bytes
+  const uint8_t* sw_t;  // [K/64][Npad][2] weight scale bytes
+  const uint8_t* W;     // [N][K/2]
+  void* y;
+  int out_bf16;
+  int64_t ldy;
+  int64_t M, K, N, Mpad, Npad;
+};
+struct W4PrefillLayout {
+  size_t qop, sa_t, sw_t, total, Mpad, Npad;
+};
+bool gemm_w4_prefill_applies(int64_t M, int64_t K, int64_t N);
+W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N);
+// decomposition + scale transposition + GEMM; ws holds w4_prefill_layout(M, K, N).total bytes
+int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
+                           int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
+                           hipStream_t stream);
+
 // ---- attention (attn.hip)
 struct AttnArgs {
   const uint16_t* q;

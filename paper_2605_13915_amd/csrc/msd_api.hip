@@ -1,4 +1,6 @@
 // C-ABI entry points: argument validation, workspace carving, kernel dispatch.
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace msd {
@@ -36,7 +38,7 @@ static W8Layout w8_layout(int64_t M, int64_t K, int64_t N) {
 struct W4Layout {
   size_t q1, q2, e8m0, abi_q1, abi_q2, abi_e, total;
 };
-static W4Layout w4_layout(int64_t M, int64_t K, int64_t /*N*/) {
+static W4Layout w4_layout(int64_t M, int64_t K, int64_t N) {
   W4Layout l{};
   const size_t KB = (size_t)K / 32;
   size_t off = 0;
@@ -44,6 +46,8 @@ static W4Layout w4_layout(int64_t M, int64_t K, int64_t /*N*/) {
   l.q2 = off; off = align_up(off + (size_t)M * KB * 32, 256);
   l.e8m0 = off; off = align_up(off + (size_t)M * KB, 256);
   l.total = off;
+  // the many-row path keeps its own operand format; the workspace is sized for whichever is larger
+  if (gemm_w4_prefill_applies(M, K, N)) l.total = std::max(l.total, w4_prefill_layout(M, K, N).total);
   return l;
 }
 }  // namespace msd
@@ -169,6 +173,12 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
     uint8_t* te = taps ? (uint8_t*)taps->scale : nullptr;
     if (!(t1 && t2 && te)) t1 = t2 = te = nullptr;  // the ABI-format taps come as a set
     if (t1 && (!aligned_to(t1, 16) || !aligned_to(t2, 16))) return MSD_ERR_INVALID_ARG;
+    if (!t1 && gemm_w4_prefill_applies(M, K, N) && w4_prefill_layout(M, K, N).total < ((size_t)1 << 31)) {
+      // many rows, no observation points: decomposition in the GEMM's own operand order,
+      // weight scales transposed once, GEMM on the asynchronous-fill pipeline
+      return launch_gemm_w4_prefill((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
+                                    (uint8_t*)ws, s);
+    }
     if (gemm_w4_is_fused(M, K, N)) {
       // one launch: the GEMM kernel decomposes the blocks of its own K range itself
       a.x = (const uint16_t*)x_bf16;

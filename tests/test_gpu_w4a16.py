@@ -63,6 +63,30 @@ def test_gemm_w4a16_parity(msd, M, K, N):
     assert np.all(np.abs(yh - truth) <= bound * (1 + 1e-5) + np.abs(truth) * 2.0 ** -20 + 1e-30)
 
 
+@pytest.mark.parametrize("M,K,N", [(256, 512, 256), (300, 2048, 600), (40, 192, 70), (700, 64, 1000), (1, 8192, 512),
+                                   (33, 4096, 300)])
+def test_gemm_w4a16_product_path_without_taps(msd, M, K, N):
+    """The path a caller without observation points takes; with more than 32 rows and K a multiple of 64
+    that is the many-row pipeline (own operand format, transposed scale bytes, 256 x 256 tiles).
+    y starts as NaN and is computed twice."""
+    seed = synth.seed_for(3, M * 13 + N)
+    x = synth.activations(seed, M, K, outliers=K >= 1024)
+    codes, exps = synth.mxfp4_weights(seed, N, K)
+    y_ref = oracle.gemm_w4a16(x, codes, exps)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    xd, cd, ed = bf16_to_dev(x), to_dev(codes), to_dev(exps)
+    for _ in range(2):
+        msd.msd_gemm_w4a16(xd, cd, ed, y=y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()
+        assert np.all(np.isfinite(yh))
+        assert rel_l2(yh, y_ref) <= 2e-6
+    # BF16 output of the same path: RNE of the fp32 value
+    yb = msd.msd_gemm_w4a16(xd, cd, ed, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert rel_l2(yb.float().cpu().numpy(), y_ref) <= 1e-2
+
+
 def test_gemm_w4a16_bf16_out_and_errors(msd):
     M, K, N = 4, 1024, 64
     x = synth.activations(5, M, K)
