@@ -535,6 +535,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
 #pragma unroll
     for (int q = 0; q < L; ++q) lds_dma16(gbase[q] + k0, voff[q], ldst[q] + sb);
   };
+  auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
+    lds_dma16(gbase[q] + (int64_t)kt * 64, voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
+  };
 
   AccT acc[2][FM][FN];
 #pragma unroll
@@ -615,6 +618,31 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
         for (int j = 0; j < FN; ++j)
           if (c + i + j > 0) acc[c][i][j] = mfma32(fa[c * FM + i], fb[j], acc[c][i][j]);
   };
+  // The same block with the L load instructions of tile kt_issue spread between the MFMAs
+  // (one every SPREAD MFMAs): issued in one burst right after the barrier they fill the address
+  // queue, the waves leave the burst at different times and the next barrier pays for the skew.
+  auto mfma_rest_issue = [&](const v4i (&fa)[2 * FM], const v4i (&fb)[FN], int kt_issue, bool do_issue) {
+    constexpr int NM = 2 * FM * FN - 1;
+    constexpr int SPREAD = (NM + 1) / L > 1 ? (NM + 1) / L : 1;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int idx = (c * FM + i) * FN + j - 1;  // 0 .. NM-1 over the MFMAs of this block
+          if (idx < 0) continue;
+          acc[c][i][j] = mfma32(fa[c * FM + i], fb[j], acc[c][i][j]);
+          if (idx % SPREAD == 0 && idx / SPREAD < L) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (do_issue) issue_one(kt_issue, idx / SPREAD);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+#pragma unroll
+    for (int q = (NM + SPREAD - 1) / SPREAD; q < L; ++q)  // loads that found no MFMA to follow
+      if (do_issue) issue_one(kt_issue, q);
+  };
   for (int kt = 0; kt + 1 < KT; ++kt) {
     mfma_first(fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
@@ -623,12 +651,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     mfma_rest(fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
     wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
-    if (kt + NS - 1 < KT) issue(kt + NS - 1);
     mfma_first(fa1, fb1);
     __builtin_amdgcn_sched_barrier(0);
     load_frags(stage_ptr(kt + 1), 0, fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(fa1, fb1);
+    mfma_rest_issue(fa1, fb1, kt + NS - 1, kt + NS - 1 < KT);
     __builtin_amdgcn_sched_barrier(0);
   }
   if (KT > 0) {  // last tile: nothing left to prefetch
