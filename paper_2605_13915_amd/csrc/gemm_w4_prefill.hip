@@ -240,14 +240,31 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   auto mfma_first = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb) {
     acc[0][0] = mfma64_scaled<0, 0>(fa[0], fb[0], acc[0][0], sa, sb);
   };
-  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb) {
+  // ISSUE: the load instructions of tile kt_issue go out between the MFMAs, one after every second
+  // MFMA (in one burst after the barrier they fill the address queue, the waves leave the burst at
+  // different times and the next barrier pays for the skew); wave 0's scale fetch goes last.
+  auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
+    w4_lds_dma16(gbase[q] + (int64_t)kt * kstep[q], voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
+  };
+  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb, int kt_issue, bool do_issue) {
+#define MSD_W4_POST(IDX)                                            \
+  if ((IDX) % 2 == 0 && (IDX) / 2 < L) {                            \
+    __builtin_amdgcn_sched_barrier(0);                              \
+    if (do_issue) issue_one(kt_issue, (IDX) / 2);                   \
+    __builtin_amdgcn_sched_barrier(0);                              \
+  }
 #define MSD_W4_ROW(I)                                                                      \
-  if (I > 0) acc[I][0] = mfma64_scaled<I, 0>(fa[I], fb[0], acc[I][0], sa, sb);             \
-  acc[I][1] = mfma64_scaled<I, 1>(fa[I], fb[1], acc[I][1], sa, sb);                        \
-  acc[I][2] = mfma64_scaled<I, 2>(fa[I], fb[2], acc[I][2], sa, sb);                        \
-  acc[I][3] = mfma64_scaled<I, 3>(fa[I], fb[3], acc[I][3], sa, sb);
+  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0>(fa[I], fb[0], acc[I][0], sa, sb); MSD_W4_POST(4 * I - 1) } \
+  acc[I][1] = mfma64_scaled<I, 1>(fa[I], fb[1], acc[I][1], sa, sb); MSD_W4_POST(4 * I)     \
+  acc[I][2] = mfma64_scaled<I, 2>(fa[I], fb[2], acc[I][2], sa, sb); MSD_W4_POST(4 * I + 1) \
+  acc[I][3] = mfma64_scaled<I, 3>(fa[I], fb[3], acc[I][3], sa, sb); MSD_W4_POST(4 * I + 2)
     MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
 #undef MSD_W4_ROW
+#undef MSD_W4_POST
+    if (do_issue && wave == 0) {
+      const uint32_t sbo = (uint32_t)((kt_issue % NS) * STAGE);
+      w4_lds_dma16(a.ws, (uint32_t)(s_first + (uint64_t)kt_issue * s_inc), lds0 + sbo + SZ_A + SZ_W);
+    }
   };
   // wait until tile t has landed (the tiles issued after it may stay in flight), then barrier
   auto wait_tile = [&](int t, int newest_issued) {
@@ -276,12 +293,9 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     __builtin_amdgcn_sched_barrier(0);
     load_a(s, 1, a1);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(a0, bc, sac, sbc);
+    mfma_rest(a0, bc, sac, sbc, 0, false);
     __builtin_amdgcn_sched_barrier(0);
-    if (s + 1 < KT) {
-      wait_tile(s + 1, min(KT - 1, s + NS - 2));
-      if (s - 1 + NS < KT) issue(s - 1 + NS);
-    }
+    if (s + 1 < KT) wait_tile(s + 1, min(KT - 1, s + NS - 2));
     const int sac2 = sac - 0x04040404;  // beta = alpha / 16: every scale byte minus 4 (bytes are >= 4)
     mfma_first(a1, bc, sac2, sbc);
     __builtin_amdgcn_sched_barrier(0);
@@ -290,7 +304,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
       load_b(s + 1, bn, san, sbn);
     }
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(a1, bc, sac2, sbc);
+    mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, s + 1 < KT && s - 1 + NS < KT);
     __builtin_amdgcn_sched_barrier(0);
   };
 #pragma unroll
