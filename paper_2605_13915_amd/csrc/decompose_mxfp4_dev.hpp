@@ -41,6 +41,53 @@ __device__ __forceinline__ int mx_block_codes(const uint32_t (&w)[16], int (&k1)
   return e;
 }
 
+// Same decomposition, packed on the fly: 32 BF16 values -> the FP6-E2M3 operands of both
+// components (6 dwords each, element i at bits [6i, 6i+6)) and the exponent e.  Keeps no
+// 32-element code arrays alive (the GEMM kernels that decompose in place are register-bound).
+__device__ __forceinline__ int mx_block_pack_fp6(const uint32_t (&w)[16], uint32_t (&p1)[6], uint32_t (&p2)[6]) {
+  float mb = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    mb = fmaxf(mb, fabsf(__uint_as_float(w[i] << 16)));
+    mb = fmaxf(mb, fabsf(__uint_as_float(w[i] & 0xFFFF0000u)));
+  }
+  const int e = mx_alpha_exponent(mb);
+  const float up = pow2f(2 - e);    // 4/alpha
+  const float down = pow2f(e - 2);  // alpha/4
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {  // 16 codes -> 96 bits -> 3 dwords per component
+    uint64_t lo1 = 0, lo2 = 0;
+    uint32_t hi1 = 0, hi2 = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int idx = h * 16 + i;
+      const float x = (idx & 1) ? __uint_as_float(w[idx >> 1] & 0xFFFF0000u) : __uint_as_float(w[idx >> 1] << 16);
+      const float a = fminf(fmaxf(rintf(x * up), -7.f), 7.f);
+      const float r = __fmaf_rn(-a, down, x);  // exact
+      const float b = fminf(fmaxf(rintf(r * up * 16.0f), -7.f), 7.f);
+      const int ka = (int)a, kb = (int)b;
+      const uint64_t c1 = ka < 0 ? (32u | (uint32_t)(-2 * ka)) : (uint32_t)(2 * ka);
+      const uint64_t c2 = kb < 0 ? (32u | (uint32_t)(-2 * kb)) : (uint32_t)(2 * kb);
+      const int bit = 6 * i;
+      if (bit + 6 <= 64) {
+        lo1 |= c1 << bit;
+        lo2 |= c2 << bit;
+      } else if (bit >= 64) {
+        hi1 |= (uint32_t)c1 << (bit - 64);
+        hi2 |= (uint32_t)c2 << (bit - 64);
+      } else {  // straddles bit 64 (i = 10: bits 60..65)
+        lo1 |= c1 << bit;
+        lo2 |= c2 << bit;
+        hi1 |= (uint32_t)(c1 >> (64 - bit));
+        hi2 |= (uint32_t)(c2 >> (64 - bit));
+      }
+    }
+    p1[h * 3 + 0] = (uint32_t)lo1; p1[h * 3 + 1] = (uint32_t)(lo1 >> 32); p1[h * 3 + 2] = hi1;
+    p2[h * 3 + 0] = (uint32_t)lo2; p2[h * 3 + 1] = (uint32_t)(lo2 >> 32); p2[h * 3 + 2] = hi2;
+  }
+  return e;
+}
+
 __device__ __forceinline__ uint32_t nibble4(int k) {  // sign-magnitude, -0 -> +0
   return k < 0 ? (8u | (uint32_t)(-k)) : (uint32_t)k;
 }

@@ -57,8 +57,16 @@ __device__ __forceinline__ v8i load_fp6_lds(const uint8_t* p) {  // 24 B, 8-byte
 // FAST: K is a whole number of super-steps and the scale arrays are 16-byte aligned, so no load in
 // the main loop is predicated per lane (predicated loads do not batch: measured 25 % slower).
 // Rows past M are clamped to the last row (their results are never stored).
-template <int WAVES, int U, int RT, bool SELF, bool FAST>
+// STACK (2M <= 16, RT = 1): the two components share one MFMA -- fragment rows [0, M) carry x1,
+// rows [M, 2M) carry x2 with the scale byte of beta (row concatenation, Sec. 3.9; the scale
+// operand is per lane, so the two halves can use different scales); the epilogue adds output rows
+// m and M + m.  Halves the matrix instructions, which at 4 bits per weight are as expensive as
+// the weight stream itself.
+// EXPORT (SELF only): workgroup 0 also writes the ABI-format codes for the observation points; a
+// separate instantiation because that path keeps 64 code registers alive.
+template <int WAVES, int U, int RT, bool SELF, bool FAST, bool STACK, bool EXPORT = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a) {
+  static_assert(!STACK || RT == 1, "stacked components use a single row fragment");
   constexpr bool CONTIG = true;
   __shared__ float s_part[WAVES][RT][4][64];
   extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];  // SELF: per wave [2][M][bpw][24 B] + [M][bpw]
@@ -127,11 +135,34 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
 #pragma unroll
           for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
         }
-        int k1[32], k2[32];
-        const int e = mx_block_codes(w, k1, k2);
         uint32_t p1[6], p2[6];
-        pack_fp6(k1, p1);
-        pack_fp6(k2, p2);
+        int e;
+        if constexpr (EXPORT) {
+          int k1[32], k2[32];
+          e = mx_block_codes(w, k1, k2);
+          pack_fp6(k1, p1);
+          pack_fp6(k2, p2);
+          if (blockIdx.x == 0 && a.abi_q1) {  // observation points only: ABI-format codes
+            uint32_t c1[4], c2[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              uint32_t pa = 0, pc = 0;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                pa |= nibble4(k1[j * 8 + i]) << (4 * i);
+                pc |= nibble4(k2[j * 8 + i]) << (4 * i);
+              }
+              c1[j] = pa;
+              c2[j] = pc;
+            }
+            const int64_t gb = (int64_t)m * KB + b_lo + bb;
+            reinterpret_cast<uint4*>(a.abi_q1 + gb * 16)[0] = make_uint4(c1[0], c1[1], c1[2], c1[3]);
+            reinterpret_cast<uint4*>(a.abi_q2 + gb * 16)[0] = make_uint4(c2[0], c2[1], c2[2], c2[3]);
+            a.abi_e8m0[gb] = (uint8_t)(e + 127);
+          }
+        } else {
+          e = mx_block_pack_fp6(w, p1, p2);
+        }
         uint2* d1 = reinterpret_cast<uint2*>(my_q + ((size_t)m * bpw + bb) * 24);
         uint2* d2 = reinterpret_cast<uint2*>(my_q + ((size_t)(M + m) * bpw + bb) * 24);
 #pragma unroll
@@ -140,24 +171,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
           d2[i] = make_uint2(p2[2 * i], p2[2 * i + 1]);
         }
         my_e[(size_t)m * bpw + bb] = (uint8_t)(e + 127);
-        if (blockIdx.x == 0 && a.abi_q1) {  // observation points only: ABI-format codes
-          uint32_t c1[4], c2[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            uint32_t pa = 0, pc = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              pa |= nibble4(k1[j * 8 + i]) << (4 * i);
-              pc |= nibble4(k2[j * 8 + i]) << (4 * i);
-            }
-            c1[j] = pa;
-            c2[j] = pc;
-          }
-          const int64_t gb = (int64_t)m * KB + b_lo + bb;
-          reinterpret_cast<uint4*>(a.abi_q1 + gb * 16)[0] = make_uint4(c1[0], c1[1], c1[2], c1[3]);
-          reinterpret_cast<uint4*>(a.abi_q2 + gb * 16)[0] = make_uint4(c2[0], c2[1], c2[2], c2[3]);
-          a.abi_e8m0[gb] = (uint8_t)(e + 127);
-        }
       }
       __builtin_amdgcn_wave_barrier();
       ready = true;
@@ -169,29 +182,50 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
       if (s >= s1) continue;
 #pragma unroll
       for (int f = 0; f < RT; ++f) {
-        const int64_t m = FAST ? min(m0 + 16 * f + row, M - 1) : m0 + 16 * f + row;
+        // source of this lane's fragment row: activation row m, component comp
+        int comp = 0;
+        int64_t m = FAST ? min(m0 + 16 * f + row, M - 1) : m0 + 16 * f + row;
+        bool row_ok = m < M;
+        if (STACK) {
+          const int r = FAST ? min(row, (int)(2 * M - 1)) : row;
+          comp = r >= M ? 1 : 0;
+          m = r - comp * M;
+          row_ok = r < 2 * M;
+        }
         v4i asc16 = one16;
-        if (!SELF && fast && m < M) asc16 = *reinterpret_cast<const v4i*>(a.e8m0 + m * KB + s * 16);
+        if (!SELF && fast && row_ok) asc16 = *reinterpret_cast<const v4i*>(a.e8m0 + m * KB + s * 16);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int64_t bi = s * 16 + (CONTIG ? 4 * u + g : 4 * g + u);
-          const bool ok = FAST || (m < M && bi < KB);
+          const bool ok = FAST || (row_ok && bi < KB);
           v8i a1 = zero8, a2 = zero8;
           int sa = 0x7F;
           if (ok) {
             if (SELF) {
               const int64_t bl = bi - s0 * 16;
-              a1 = load_fp6_lds(my_q + ((size_t)m * bpw + bl) * 24);
-              a2 = load_fp6_lds(my_q + ((size_t)(M + m) * bpw + bl) * 24);
+              if (STACK) {
+                a1 = load_fp6_lds(my_q + ((size_t)(comp * M + m) * bpw + bl) * 24);
+              } else {
+                a1 = load_fp6_lds(my_q + ((size_t)m * bpw + bl) * 24);
+                a2 = load_fp6_lds(my_q + ((size_t)(M + m) * bpw + bl) * 24);
+              }
               sa = my_e[(size_t)m * bpw + bl];
             } else {
-              a1 = load_fp6_slot(a.q1 + (m * KB + bi) * 8);
-              a2 = load_fp6_slot(a.q2 + (m * KB + bi) * 8);
+              if (STACK) {
+                a1 = load_fp6_slot((comp ? a.q2 : a.q1) + (m * KB + bi) * 8);
+              } else {
+                a1 = load_fp6_slot(a.q1 + (m * KB + bi) * 8);
+                a2 = load_fp6_slot(a.q2 + (m * KB + bi) * 8);
+              }
               sa = fast ? (CONTIG ? scale_byte(asc16, u, g) : scale_byte(asc16, g, u)) : (int)a.e8m0[m * KB + bi];
             }
           }
-          acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa, wsc[u2][u]);
-          acc[f] = mfma_scaled(a2, wb[u2][u], acc[f], sa - 4, wsc[u2][u]);  // beta = alpha / 16
+          if (STACK) {
+            acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa - 4 * comp, wsc[u2][u]);  // beta = alpha / 16
+          } else {
+            acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa, wsc[u2][u]);
+            acc[f] = mfma_scaled(a2, wb[u2][u], acc[f], sa - 4, wsc[u2][u]);  // beta = alpha / 16
+          }
         }
       }
     }
@@ -209,6 +243,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) v += s_part[w][i >> 4][i & 3][((i & 15) >> 2) * 16 + j];
+    if (STACK) {  // second component: fragment row M + i (same fp32 order for every wave)
+      const int i2 = (int)M + i;
+      float v2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) v2 += s_part[w][0][i2 & 3][(i2 >> 2) * 16 + j];
+      v += v2;
+    }
     if (a.out_bf16)
       reinterpret_cast<uint16_t*>(a.y)[m * a.ldy + n] = f32_to_bf16_bits(v);
     else
@@ -218,7 +259,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
 
 bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t) { return M <= 2 && K > 0 && K <= 32768; }
 
-template <int WAVES, int U, int RT, bool SELF>
+template <int WAVES, int U, int RT, bool SELF, bool STACK = false>
 static int launch_w4(const GemmW4Args& a, hipStream_t stream) {
   size_t dyn = 0;
   if (SELF) {
@@ -229,10 +270,16 @@ static int launch_w4(const GemmW4Args& a, hipStream_t stream) {
   }
   const dim3 grid((unsigned)cdiv(a.N, 16), (unsigned)cdiv(a.M, 16 * RT));
   const bool fast = (a.K / 32) % 16 == 0 && a.scales_aligned;
-  if (fast)
-    hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, true>), grid, dim3(WAVES * 64), dyn, stream, a);
-  else
-    hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, false>), grid, dim3(WAVES * 64), dyn, stream, a);
+  if (SELF && a.abi_q1) {  // observation points requested
+    if (fast)
+      hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, true, STACK, SELF>), grid, dim3(WAVES * 64), dyn, stream, a);
+    else
+      hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, false, STACK, SELF>), grid, dim3(WAVES * 64), dyn, stream, a);
+  } else if (fast) {
+    hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, true, STACK>), grid, dim3(WAVES * 64), dyn, stream, a);
+  } else {
+    hipLaunchKernelGGL((gemm_w4_skinny_kernel<WAVES, U, RT, SELF, false, STACK>), grid, dim3(WAVES * 64), dyn, stream, a);
+  }
   return MSD_OK;
 }
 
@@ -456,10 +503,13 @@ int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {
   int rc;
   if (a.x != nullptr) {  // single launch (gemm_w4_is_fused)
     switch (tune) {
-      case 1: rc = launch_w4<8, 1, 1, true>(a, stream); break;
-      case 2: rc = launch_w4<4, 4, 1, true>(a, stream); break;
-      default: rc = launch_w4<4, 2, 1, true>(a, stream); break;
+      case 1: rc = launch_w4<8, 1, 1, true, true>(a, stream); break;
+      case 2: rc = launch_w4<4, 4, 1, true, true>(a, stream); break;
+      case 9: rc = launch_w4<4, 2, 1, true, false>(a, stream); break;
+      default: rc = launch_w4<4, 2, 1, true, true>(a, stream); break;
     }
+  } else if (a.M <= 8 && tune != 9) {
+    rc = launch_w4<4, 2, 1, false, true>(a, stream);  // both components in one row fragment
   } else if (a.M <= 16) {
     rc = launch_w4<4, 2, 1, false>(a, stream);
   } else if (a.M <= 32 && tune == 1) {
