@@ -98,9 +98,20 @@ def leg_w4(msd, synth, time_calls, dev):
             f(0)
             us = _eager_us(f, 3)
         b = wbytes + 2 * M * K + 4 * M * N
+        if M == 1:  # bare read of the same weight bytes (codes + scale bytes), two launches, cold
+            def rd(i):
+                c, e = reps[i % len(reps)]
+                return [msd.msd_stream_read(c, prepare=True), msd.msd_stream_read(e, prepare=True)]
+            class _Both:
+                def __init__(self, ps): self.ps = ps
+                def __call__(self):
+                    for p_ in self.ps: p_()
+            bare_us = time_calls(lambda i: _Both(rd(i)), 2 * len(reps))
         rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "GBps": round(b / us / 1e3, 1),
                "hbm_frac": round(b / us / 1e3 / HBM, 4), "exec_TFLOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
+        if M <= 32:
+            rec["bare_weight_read_us"] = round(bare_us, 1)
         try:
             ws2 = torch.empty(msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
             g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws2, prepare=M <= 32)
@@ -137,8 +148,16 @@ def leg_attn(msd, synth, time_calls, dev):
         f = lambda i: msd.msd_attn_decode_int8kv(q, *sets[i % n], msd.MSD_PER_TOKEN, out=o, ws=ws, prepare=True)
         us = time_calls(f, 4 * n)
         b = kvbytes + 8 * B * Hkv * L + 2 * B * Hq * d + 4 * B * Hq * d
+        # bare read of the same K and V bytes (one launch each), same cold-cache protocol
+        class _Both:
+            def __init__(self, ps): self.ps = ps
+            def __call__(self):
+                for p_ in self.ps: p_()
+        bare_us = time_calls(lambda i: _Both([msd.msd_stream_read(sets[i % n][0].view(-1, 4096), prepare=True),
+                                              msd.msd_stream_read(sets[i % n][1].view(-1, 4096), prepare=True)]), 4 * n)
         out.append({"B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "L": L, "us": round(us, 1),
-                    "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM, 4)})
+                    "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM, 4),
+                    "bare_kv_read_us": round(bare_us, 1)})
         del sets
         torch.cuda.empty_cache()
     return out

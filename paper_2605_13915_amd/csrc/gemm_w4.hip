@@ -499,29 +499,19 @@ static int launch_w4_tiled(const GemmW4Args& a, hipStream_t stream) {
 
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
-  static const int tune = getenv("MSD_TUNE_W4") ? atoi(getenv("MSD_TUNE_W4")) : 0;
   int rc;
   if (a.x != nullptr) {  // single launch (gemm_w4_is_fused)
-    switch (tune) {
-      case 1: rc = launch_w4<8, 1, 1, true, true>(a, stream); break;
-      case 2: rc = launch_w4<4, 4, 1, true, true>(a, stream); break;
-      case 9: rc = launch_w4<4, 2, 1, true, false>(a, stream); break;
-      default: rc = launch_w4<4, 2, 1, true, true>(a, stream); break;
-    }
-  } else if (a.M <= 8 && tune != 9) {
+    rc = launch_w4<4, 2, 1, true, true>(a, stream);
+  } else if (a.M <= 8) {
     rc = launch_w4<4, 2, 1, false, true>(a, stream);  // both components in one row fragment
   } else if (a.M <= 16) {
     rc = launch_w4<4, 2, 1, false>(a, stream);
-  } else if (a.M <= 32 && tune == 1) {
-    rc = launch_w4<4, 2, 2, false>(a, stream);
   } else if (a.M <= 32) {
     rc = launch_w4_tiled<32, 128, 1, 4>(a, stream);
   } else {
-    switch (tune) {
-      case 2: rc = launch_w4_tiled<128, 128, 2, 2>(a, stream); break;
-      case 3: rc = launch_w4_tiled<64, 256, 1, 4>(a, stream); break;
-      default: rc = launch_w4_tiled<128, 256, 2, 2>(a, stream); break;
-    }
+    // more than 32 rows with K not a multiple of 64, or observation points requested (otherwise
+    // the many-row pipeline of gemm_w4_prefill.hip runs)
+    rc = launch_w4_tiled<128, 256, 2, 2>(a, stream);
   }
   if (rc) return rc;
   MSD_LAUNCH_CHECK();

@@ -819,7 +819,6 @@ static int launch_decode(const GemmW8Args& a, hipStream_t stream) {
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
   const int64_t M = a.M, N = a.N;
-  static const int tune = getenv("MSD_TUNE_W8") ? atoi(getenv("MSD_TUNE_W8")) : 0;
   int rc = MSD_OK;
   const bool wide = cdiv(N, 16) > 512;  // many column tiles: widen the workgroup tile (measured)
   if (a.x != nullptr) {  // the caller asked for the single-launch path (gemm_w8_is_fused)
@@ -841,8 +840,8 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     else if (wgs(64, 128) >= 200) rc = launch_dma<64, 128, 2, 2, 8>(a, stream);
     else if (wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
     else rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // 64 KB of LDS: two workgroups per CU
-  } else if (a.K % 64 == 0 && a.K >= 64 && tune != 3) {
-    rc = tune == 5 ? launch_dma<128, 256, 2, 2, 5>(a, stream) : tune == 6 ? launch_dma<128, 256, 2, 2, 3>(a, stream) : launch_dma<128, 256, 2, 2, 4>(a, stream);
+  } else if (a.K % 64 == 0 && a.K >= 64) {
+    rc = launch_dma<128, 256, 2, 2, 4>(a, stream);  // three or five stages measured the same
   } else {
     rc = launch_mfma32<128, 256, 2, 2>(a, stream);
   }
