@@ -331,10 +331,10 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
         for (int j = 0; j < 4; ++j) {
           const int64_t n = n0 + wn * 128 + 32 * j + l32;
           if (n >= N) continue;
-          if (a.out_bf16)
-            reinterpret_cast<uint16_t*>(a.y)[m * a.ldy + n] = f32_to_bf16_bits(acc[i][j][r]);
+          if (a.out_bf16)  // written once, not read again: streaming stores
+            __builtin_nontemporal_store(f32_to_bf16_bits(acc[i][j][r]), reinterpret_cast<uint16_t*>(a.y) + m * a.ldy + n);
           else
-            reinterpret_cast<float*>(a.y)[m * a.ldy + n] = acc[i][j][r];
+            __builtin_nontemporal_store(acc[i][j][r], reinterpret_cast<float*>(a.y) + m * a.ldy + n);
         }
       }
       __builtin_amdgcn_sched_barrier(0);

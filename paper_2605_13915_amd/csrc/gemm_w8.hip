@@ -45,6 +45,13 @@ __device__ __forceinline__ void store_out(void* y, int out_bf16, int64_t idx, fl
   else
     reinterpret_cast<float*>(y)[idx] = v;
 }
+// the same for the large-tile epilogues: the output is written once and not read again by the kernel
+__device__ __forceinline__ void store_out_stream(void* y, int out_bf16, int64_t idx, float v) {
+  if (out_bf16)
+    __builtin_nontemporal_store(f32_to_bf16_bits(v), reinterpret_cast<uint16_t*>(y) + idx);
+  else
+    __builtin_nontemporal_store(v, reinterpret_cast<float*>(y) + idx);
+}
 
 __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta, int a1, int a2) {
   // y = s_W * (alpha*acc1 + beta*acc2)   (Alg. 1 step 8)
@@ -677,7 +684,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
               const int64_t n = n0 + wn * TN + 32 * j + l32;
-              if (n < N) store_out(a.y, a.out_bf16, m * a.ldy + n, acc[c][i][j][r]);
+              if (n < N) store_out_stream(a.y, a.out_bf16, m * a.ldy + n, acc[c][i][j][r]);
             }
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -715,7 +722,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
           const int64_t n = n0 + wn * TN + 32 * j + l32;
           if (n >= N) continue;
           const int a1 = acc[0][i][j][r], a2 = acc[1][i][j][r];
-          store_out(a.y, a.out_bf16, m * a.ldy + n, merge_scales(sw[j], alpha, beta, a1, a2));
+          store_out_stream(a.y, a.out_bf16, m * a.ldy + n, merge_scales(sw[j], alpha, beta, a1, a2));
           if (a.acc1) a.acc1[m * N + n] = a1;
           if (a.acc2) a.acc2[m * N + n] = a2;
         }

@@ -87,6 +87,23 @@ def test_gemm_w4a16_product_path_without_taps(msd, M, K, N):
     assert rel_l2(yb.float().cpu().numpy(), y_ref) <= 1e-2
 
 
+@pytest.mark.parametrize("M,K,N", [(2, 1024, 256), (8, 512, 300), (100, 256, 300)])
+def test_gemm_w4a16_strided_operands(msd, M, K, N):
+    """ldx > K and ldy > N; pad columns of y stay untouched."""
+    seed = synth.seed_for(3, M * 19 + N)
+    x = synth.activations(seed, M, K)
+    codes, exps = synth.mxfp4_weights(seed, N, K)
+    y_ref = oracle.gemm_w4a16(x, codes, exps)
+    xbig = torch.zeros((M, K + 40), dtype=torch.bfloat16, device="cuda")
+    xbig[:, :K] = bf16_to_dev(x)
+    ybig = torch.full((M, N + 5), -7.0, dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w4a16(xbig[:, :K], to_dev(codes), to_dev(exps), y=ybig[:, :N])
+    torch.cuda.synchronize()
+    yh = ybig.cpu().numpy()
+    assert rel_l2(yh[:, :N], y_ref) <= 2e-6
+    assert np.all(yh[:, N:] == -7.0)
+
+
 def test_gemm_w4a16_bf16_out_and_errors(msd):
     M, K, N = 4, 1024, 64
     x = synth.activations(5, M, K)

@@ -108,6 +108,31 @@ def test_gemm_w8a16_product_path_without_taps(msd, M, K, N):
         assert rel_l2(yh, y_ref) <= 1e-6
 
 
+@pytest.mark.parametrize("M,K,N", [(2, 1024, 256), (8, 512, 300), (24, 256, 8300), (100, 256, 700), (300, 512, 600)])
+def test_gemm_w8a16_strided_operands_and_bf16_output(msd, M, K, N):
+    """Row strides larger than the row length for x and y (ldx > K, ldy > N; the pad columns of y must stay
+    untouched), on every kernel family; then BF16 output of the same call."""
+    seed = synth.seed_for(1, M * 17 + N)
+    x = synth.activations(seed, M, K, outliers=True)
+    W, s = synth.int8_weights(seed, N, K)
+    y_ref = oracle.gemm_w8a16(x, W, s)
+    xbig = torch.zeros((M, K + 24), dtype=torch.bfloat16, device="cuda")
+    xbig[:, :K] = bf16_to_dev(x)
+    ybig = torch.full((M, N + 9), -7.0, dtype=torch.float32, device="cuda")
+    Wd, sd = to_dev(W), to_dev(s)
+    msd.msd_gemm_w8a16(xbig[:, :K], Wd, sd, y=ybig[:, :N])
+    torch.cuda.synchronize()
+    yh = ybig.cpu().numpy()
+    assert rel_l2(yh[:, :N], y_ref) <= 1e-6
+    assert np.all(yh[:, N:] == -7.0)
+    yb = msd.msd_gemm_w8a16(xbig[:, :K], Wd, sd, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    ref_bits = oracle.gemm_w8a16(x, W, s, out_bf16=True)
+    bits = bf16_dev_to_bits(yb)
+    assert np.mean(bits != ref_bits) < 0.01          # equal up to rare one-ulp ties of nearly equal fp32 values
+    assert rel_l2(synth.bf16_bits_to_f32(bits), synth.bf16_bits_to_f32(ref_bits)) <= 1e-3
+
+
 def test_gemm_w8a16_bf16_output_and_determinism(msd):
     M, K, N = 8, 1024, 512
     x = synth.activations(77, M, K)
