@@ -60,13 +60,21 @@ __device__ __forceinline__ void chunk_codes(const Chunk16& c, float alpha, float
 // One workgroup of THREADS threads decomposes one row: xr[0..K) -> q1r, q2r (16-byte aligned),
 // *alpha_out.  s_red: THREADS/64 floats of LDS.  Ends with every thread's stores issued (no
 // trailing barrier).
+// With a_step != 0 the codes go to the blocked layout of the asynchronous-fill GEMM instead:
+// q1r / q2r then point at the array base and chunk c of row m lands at
+//   (c/4) * a_step + (m/16) * 1024 + (m%16) * 64 + ((c%4) ^ (((m%16)>>2)&3)) * 16.
 template <int THREADS>
 __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restrict__ xr, int K,
                                                          int8_t* __restrict__ q1r,
                                                          int8_t* __restrict__ q2r,
                                                          float* __restrict__ alpha_out, bool aligned,
-                                                         float* s_red) {
+                                                         float* s_red, int64_t a_step = 0, int64_t m = 0) {
   const int nchunks = K / 16;
+  const int64_t row_off = (m / 16) * 1024 + (m % 16) * 64;
+  const int sw = (int)(((m % 16) >> 2) & 3);
+  auto slot = [&](int c) -> int64_t {  // index of chunk c in units of 16 bytes
+    return a_step ? ((int64_t)(c >> 2) * a_step + row_off + (((c & 3) ^ sw) << 4)) >> 4 : c;
+  };
   Chunk16 cache[kDecRegChunks];
   float mx = 0.f;
 #pragma unroll
@@ -92,8 +100,8 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
   uint4* o2 = reinterpret_cast<uint4*>(q2r);
   if (mx == 0.f) {  // all-zero row: zero codes, zero scales
     for (int c = threadIdx.x; c < nchunks; c += THREADS) {
-      o1[c] = make_uint4(0, 0, 0, 0);
-      o2[c] = make_uint4(0, 0, 0, 0);
+      o1[slot(c)] = make_uint4(0, 0, 0, 0);
+      o2[slot(c)] = make_uint4(0, 0, 0, 0);
     }
     return;
   }
@@ -103,15 +111,15 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
     if (c < nchunks) {
       uint4 a, b;
       chunk_codes(cache[i], alpha, beta, a, b);
-      o1[c] = a;
-      o2[c] = b;
+      o1[slot(c)] = a;
+      o2[slot(c)] = b;
     }
   }
   for (int c = threadIdx.x + kDecRegChunks * THREADS; c < nchunks; c += THREADS) {
     uint4 a, b;
     chunk_codes(load_chunk16(xr + c * 16, aligned), alpha, beta, a, b);
-    o1[c] = a;
-    o2[c] = b;
+    o1[slot(c)] = a;
+    o2[slot(c)] = b;
   }
 }
 

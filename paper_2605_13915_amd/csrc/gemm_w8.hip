@@ -520,14 +520,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
   const int8_t* gbase[L];
   uint32_t ldst[L];
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  // Blocked activation codes (a.a_step != 0, see GemmW8Args): the 16-row block of a K step is one
+  // contiguous, already swizzled kilobyte, copied in lane order; a.a_step bytes separate K steps.
+  const bool blocked = !BF16 && a.a_step != 0;
+  int64_t kadv[L];  // bytes between consecutive K steps of this instruction's source
 #pragma unroll
   for (int q = 0; q < L; ++q) {
     const int blk = q * NW + wave;
+    kadv[q] = 64;
     if (blk < ROWS_A / 16) {
       const int comp = blk / (BMH / 16);
-      const int64_t mrow = min(m0 + (BF16 ? comp * BMH : 0) + (blk % (BMH / 16)) * 16 + rr, M - 1);
-      voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
-      gbase[q] = ((comp && !BF16) ? a.q2 : a.q1) + m0 * a.ldq;
+      if (blocked) {
+        voff[q] = (uint32_t)(lane * 16);
+        gbase[q] = (comp ? a.q2 : a.q1) + (m0 / 16 + blk % (BMH / 16)) * 1024;
+        kadv[q] = a.a_step;
+      } else {
+        const int64_t mrow = min(m0 + (BF16 ? comp * BMH : 0) + (blk % (BMH / 16)) * 16 + rr, M - 1);
+        voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
+        gbase[q] = ((comp && !BF16) ? a.q2 : a.q1) + m0 * a.ldq;
+      }
     } else {
       const int64_t nrow = min(n0 + (blk - ROWS_A / 16) * 16 + rr, N - 1);
       voff[q] = (uint32_t)((nrow - n0) * K + lc * 16);
@@ -537,13 +548,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
   }
   const int KT = (int)(K / 64);
   auto issue = [&](int kt) {
-    const int64_t k0 = (int64_t)kt * 64;
     const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
 #pragma unroll
-    for (int q = 0; q < L; ++q) lds_dma16(gbase[q] + k0, voff[q], ldst[q] + sb);
+    for (int q = 0; q < L; ++q) lds_dma16(gbase[q] + kt * kadv[q], voff[q], ldst[q] + sb);
   };
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
-    lds_dma16(gbase[q] + (int64_t)kt * 64, voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
+    lds_dma16(gbase[q] + kt * kadv[q], voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
   };
 
   AccT acc[2][FM][FN];
@@ -823,32 +833,53 @@ static int launch_decode(const GemmW8Args& a, hipStream_t stream) {
   return MSD_OK;
 }
 
+// Which kernel family serves a shape (the decomposition launch writes the layout it wants).
+enum class W8Path { kDecode, kFillSmall, kFillLarge, kStaged };
+static W8Path w8_path(int64_t M, int64_t K, int64_t N) {
+  const bool wide = cdiv(N, 16) > 512;  // many column tiles
+  const bool k64 = K % 64 == 0 && K >= 64;
+  if (2 * M <= 32) return W8Path::kDecode;
+  if (2 * M <= 64) return (wide && k64) ? W8Path::kFillSmall : W8Path::kDecode;
+  if (cdiv(M, 128) * cdiv(N, 256) < 128) return k64 ? W8Path::kFillSmall : W8Path::kStaged;
+  return k64 ? W8Path::kFillLarge : W8Path::kStaged;
+}
+
+bool gemm_w8_wants_blocked(int64_t M, int64_t K, int64_t N) {
+  if (gemm_w8_is_fused(M, K, N)) return false;
+  const W8Path p = w8_path(M, K, N);
+  return p == W8Path::kFillSmall || p == W8Path::kFillLarge;
+}
+
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
   const int64_t M = a.M, N = a.N;
   int rc = MSD_OK;
   const bool wide = cdiv(N, 16) > 512;  // many column tiles: widen the workgroup tile (measured)
+  const W8Path path = w8_path(M, a.K, N);
+  if (a.a_step != 0 && (a.x != nullptr || (path != W8Path::kFillSmall && path != W8Path::kFillLarge)))
+    return MSD_ERR_INVALID_ARG;  // only the asynchronous-fill kernels read the blocked layout
   if (a.x != nullptr) {  // the caller asked for the single-launch path (gemm_w8_is_fused)
     rc = launch_decode<4, 8, 1, 1, true>(a, stream);
-  } else if (2 * M <= 16) {
-    rc = wide ? launch_decode<4, 8, 1, 2, false>(a, stream) : launch_decode<4, 8, 1, 1, false>(a, stream);
-  } else if (2 * M <= 32) {
-    rc = launch_decode<8, 4, 2, 2, false>(a, stream);
-  } else if (2 * M <= 64) {
-    if (!wide) rc = launch_decode<8, 4, 4, 1, false>(a, stream);
-    else if (a.K % 64 == 0) rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // measured: 27 vs 31 us at N = 14336
-    else rc = launch_decode<8, 2, 4, 4, false>(a, stream);
-  } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
-    // Few output tiles (decode with a large batch).  With K a multiple of 64: asynchronous-fill
-    // kernel on the largest of three small tiles that still gives about 200 workgroups (measured:
-    // the stream rate is set by how many CUs pull, then by the activation re-reads per workgroup).
+  } else if (path == W8Path::kDecode) {
+    if (2 * M <= 16)
+      rc = wide ? launch_decode<4, 8, 1, 2, false>(a, stream) : launch_decode<4, 8, 1, 1, false>(a, stream);
+    else if (2 * M <= 32)
+      rc = launch_decode<8, 4, 2, 2, false>(a, stream);
+    else
+      rc = wide ? launch_decode<8, 2, 4, 4, false>(a, stream) : launch_decode<8, 4, 4, 1, false>(a, stream);
+  } else if (path == W8Path::kFillSmall) {
+    // Few output tiles (decode with a large batch): asynchronous-fill kernel on the largest of three
+    // small tiles that still gives about 200 workgroups (measured: the stream rate is set by how
+    // many CUs pull, then by the activation re-reads per workgroup).  16 < M <= 32 with many
+    // columns measured 27 vs 31 us on the smallest tile against the register-operand kernel.
     const auto wgs = [&](int bmh, int bn) { return cdiv(M, bmh) * cdiv(N, bn); };
-    if (a.K % 64 != 0) rc = launch_mfma32<64, 64, 2, 2>(a, stream);
-    else if (wgs(64, 128) >= 200) rc = launch_dma<64, 128, 2, 2, 8>(a, stream);
-    else if (wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
+    if (2 * M > 64 && wgs(64, 128) >= 200) rc = launch_dma<64, 128, 2, 2, 8>(a, stream);
+    else if (2 * M > 64 && wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
     else rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // 64 KB of LDS: two workgroups per CU
-  } else if (a.K % 64 == 0 && a.K >= 64) {
+  } else if (path == W8Path::kFillLarge) {
     rc = launch_dma<128, 256, 2, 2, 4>(a, stream);  // three or five stages measured the same
+  } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
+    rc = launch_mfma32<64, 64, 2, 2>(a, stream);
   } else {
     rc = launch_mfma32<128, 256, 2, 2>(a, stream);
   }

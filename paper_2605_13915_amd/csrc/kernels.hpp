@@ -5,8 +5,9 @@
 namespace msd {
 
 // ---- decomposition (decompose.hip)
+// a_step != 0: write the blocked layout of GemmW8Args instead of row-major [M][ldq]
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
-                          int8_t* q2, int64_t ldq, float* alpha, hipStream_t stream);
+                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, hipStream_t stream);
 int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
                            uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
                            uint8_t* op_e8m0, hipStream_t stream);
@@ -30,7 +31,13 @@ struct GemmW8Args {
   int64_t ldx;
   int x_aligned;     // rows of x are 16-byte aligned
   int export_codes;  // also write q1/q2/alpha to the workspace (observation points)
+  // blocked code layout for the asynchronous-fill kernels (0: q1/q2 are row-major [M][ldq]):
+  // q[K/64][ceil(M/128)*8 blocks][16 rows][64 B], the four 16-byte chunks of a row stored at
+  // chunk ^ ((row>>2)&3), i.e. exactly the LDS image; a_step = bytes between K steps
+  int64_t a_step;
 };
+// does launch_gemm_w8 take the codes in the blocked layout for this shape?
+bool gemm_w8_wants_blocked(int64_t M, int64_t K, int64_t N);
 // true when launch_gemm_w8 runs the decomposition itself (single launch)
 bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);

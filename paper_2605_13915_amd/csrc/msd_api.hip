@@ -27,8 +27,9 @@ struct W8Layout {
 static W8Layout w8_layout(int64_t M, int64_t K, int64_t N) {
   W8Layout l{};
   size_t off = 0;
-  l.q1 = off; off = align_up(off + (size_t)M * K, 256);
-  l.q2 = off; off = align_up(off + (size_t)M * K, 256);
+  const size_t Mpad = align_up((size_t)M, 128);  // the blocked code layout holds whole 128-row tiles
+  l.q1 = off; off = align_up(off + Mpad * K, 256);
+  l.q2 = off; off = align_up(off + Mpad * K, 256);
   l.alpha = off; off = align_up(off + (size_t)M * sizeof(float), 256);
   l.total = off;
   return l;
@@ -71,7 +72,7 @@ int msd_decompose(int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx
     if (K % 16 != 0) return MSD_ERR_SHAPE;
     if (!aligned_to(scale, 4)) return MSD_ERR_INVALID_ARG;
     return launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)q1, (int8_t*)q2, K,
-                                 (float*)scale, s);
+                                 (float*)scale, 0, s);
   }
   if (K % 32 != 0) return MSD_ERR_SHAPE;
   return launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, (uint8_t*)q1, (uint8_t*)q2,
@@ -118,8 +119,11 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
     a.x_aligned = (aligned_to(x_bf16, 16) && ldx % 8 == 0) ? 1 : 0;
     a.export_codes = (taps && (taps->q1 || taps->q2 || taps->scale)) ? 1 : 0;
   } else if (K > 0) {
+    // codes in the layout the GEMM kernel of this shape reads; observation points want row-major
+    const bool code_taps = taps && (taps->q1 || taps->q2);
+    if (!code_taps && gemm_w8_wants_blocked(M, K, N)) a.a_step = (int64_t)(align_up((size_t)M, 128) / 16) * 1024;
     int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
-                                   (float*)a.alpha, s);
+                                   (float*)a.alpha, a.a_step, s);
     if (rc) return rc;
   } else {
     int rc = fill_u32((uint32_t*)a.alpha, M, 0u, s);
