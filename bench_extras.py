@@ -61,6 +61,15 @@ def leg_prefill(msd, synth, time_calls, dev):
         rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "eff_TOPS": round(2.0 * M * K * N / us / 1e6, 1),
                "int8_mfma_frac": round(4.0 * M * K * N / us / 1e6 / INT8_TOPS, 4)}
+        try:  # the matrix pipe alone on the same shape and data (no fill, no barriers, no LDS traffic)
+            h = lambda i: msd.msd_probe_mfma_w8a16(x, W, s, y=y, ws=ws)
+            h(0)
+            us3 = _eager_us(h, 3)
+            rec["mfma_only_us"] = round(us3, 1)
+            rec["mfma_only_TOPS"] = round(4.0 * M * K * N / us3 / 1e6, 1)
+            rec["frac_of_mfma_only"] = round(us3 / us, 3)
+        except Exception as e:  # noqa: BLE001
+            rec["probe_error"] = str(e)
         ws2 = g = None
         try:
             ws2 = torch.empty(msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)

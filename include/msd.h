@@ -171,6 +171,21 @@ int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
  */
 int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stream);
 
+/*
+ * Measurement aid (not a step of the method; no paper passage).  Same arguments and the same
+ * launches as msd_gemm_w8a16 on its many-row kernel (decomposition, then the 256x256-tile GEMM),
+ * except that after the first K step the GEMM kernel stops fetching and keeps multiplying that
+ * step's fragments: the same matrix-instruction sequence, tile schedule and epilogue on real
+ * operand bits, with no tile fill, no barrier and no LDS traffic.  y receives meaningless
+ * values.  Its time is what the matrix pipe alone allows for this shape and data on the GPU at
+ * hand (the clock under matrix load depends on the operand bits).  Requires K % 64 == 0, fp32
+ * output, workspace of msd_gemm_w8a16_workspace_bytes(M, K, N); taps are ignored.
+ */
+int msd_probe_mfma_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                         const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                         void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                         void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,7 @@ def lib():
         gemm4 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         L.msd_gemm_w8a16.argtypes = gemm8
         L.msd_dequant_gemm_w8a16.argtypes = gemm8
+        L.msd_probe_mfma_w8a16.argtypes = gemm8
         L.msd_gemm_w4a16.argtypes = gemm4
         L.msd_dequant_gemm_w4a16.argtypes = gemm4
         for f in (L.msd_gemm_w8a16_workspace_bytes, L.msd_gemm_w4a16_workspace_bytes,
@@ -62,7 +63,7 @@ def lib():
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
-                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read"):
+                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -189,6 +190,14 @@ def msd_dequant_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, y=None, ws=No
     assert W.is_contiguous()
     return _gemm_common("msd_dequant_gemm_w8a16", "msd_dequant_gemm_workspace_bytes", x,
                         (_ptr(W), _ptr(w_scale)), W.shape[0], out_dtype, False, y, ws, prepare)
+
+
+def msd_probe_mfma_w8a16(x, W, w_scale, y=None, ws=None, prepare=False):
+    """Measurement aid: the many-row W8A16 kernel's MFMA sequence without its data movement (y is meaningless)."""
+    _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
+    assert W.is_contiguous() and W.shape[1] == x.shape[1]
+    return _gemm_common("msd_probe_mfma_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
+                        W.shape[0], torch.float32, False, y, ws, prepare)
 
 
 def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None, prepare=False):

@@ -482,8 +482,13 @@ __device__ __forceinline__ void wait_vm_barrier() {
 // layout and every fragment offset are unchanged), the A rows are 2*BMH consecutive activation
 // rows instead of two components of BMH rows, and the epilogue stores the fp32 sums.  The
 // argument struct is reused with byte units: q1 = activations, ldq and K in bytes, W = BF16 weights.
-template <int BMH, int BN, int WM, int WN, int NS, bool BF16>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+//
+// PROBE = true is a measurement aid (msd_probe_mfma_w8a16): after the first K step the kernel stops
+// fetching and keeps multiplying the fragments of that step, i.e. the same MFMA sequence, tile
+// schedule and epilogue with real operand bits but no fill, no barrier and no LDS traffic.  Its
+// time is what the matrix pipe alone allows for this shape and data on the chip at hand.
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16, bool PROBE = false>
+__global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN == 4) ? 2 : 1) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
   using AccT = std::conditional_t<BF16, v16f, v16i>;
   constexpr int NW = WM * WN, ROWS_A = 2 * BMH, R = ROWS_A + BN;
   constexpr int TMH = BMH / WM, TN = BN / WN, FM = TMH / 32, FN = TN / 32;
@@ -661,6 +666,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
       if (do_issue) issue_one(kt_issue, q);
   };
   for (int kt = 0; kt + 1 < KT; ++kt) {
+    if constexpr (PROBE) {
+      if (kt > 0) {
+        mfma_block(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_block(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        continue;
+      }
+    }
     mfma_first(fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
     load_frags(stage_ptr(kt), 1, fa1, fb1);
@@ -672,7 +686,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
     __builtin_amdgcn_sched_barrier(0);
     load_frags(stage_ptr(kt + 1), 0, fa0, fb0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest_issue(fa1, fb1, kt + NS - 1, kt + NS - 1 < KT);
+    mfma_rest_issue(fa1, fb1, kt + NS - 1, !PROBE && kt + NS - 1 < KT);
     __builtin_amdgcn_sched_barrier(0);
   }
   if (KT > 0) {  // last tile: nothing left to prefetch
@@ -742,7 +756,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_dma_kernel(GemmW8Args a,
   }
 }
 
-template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false>
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false, bool PROBE = false>
 static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
   const int tiles_m = (int)cdiv(a.M, BF16 ? 2 * BMH : BMH), tiles_n = (int)cdiv(a.N, BN);
   const int total = tiles_m * tiles_n;
@@ -751,12 +765,12 @@ static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
   static_assert((size_t)NS * (2 * BMH + BN) * 64 <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16>), dim3(grid), dim3(WM * WN * 64), lds, stream,
-                     a, tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE>), dim3(grid), dim3(WM * WN * 64), lds,
+                     stream, a, tiles_m, tiles_n);
   return MSD_OK;
 }
 
@@ -833,6 +847,16 @@ static int launch_decode(const GemmW8Args& a, hipStream_t stream) {
   return MSD_OK;
 }
 
+// Measurement aid: the prefill kernel's MFMA sequence without its data movement (PROBE above).
+int launch_gemm_w8_mfma_probe(const GemmW8Args& a, hipStream_t stream) {
+  if (a.M == 0 || a.N == 0) return MSD_OK;
+  if (a.K % 64 != 0 || a.K < 64 || a.x != nullptr) return MSD_ERR_SHAPE;
+  const int rc = launch_dma<128, 256, 2, 2, 4, false, true>(a, stream);
+  if (rc) return rc;
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 // Which kernel family serves a shape (the decomposition launch writes the layout it wants).
 enum class W8Path { kDecode, kFillSmall, kFillLarge, kStaged };
 static W8Path w8_path(int64_t M, int64_t K, int64_t N) {
@@ -877,7 +901,8 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     else if (2 * M > 64 && wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
     else rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // 64 KB of LDS: two workgroups per CU
   } else if (path == W8Path::kFillLarge) {
-    rc = launch_dma<128, 256, 2, 2, 4>(a, stream);  // three or five stages measured the same
+    // three or five stages, and half-size tiles with two workgroups per CU, all measured the same
+    rc = launch_dma<128, 256, 2, 2, 4>(a, stream);
   } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
     rc = launch_mfma32<64, 64, 2, 2>(a, stream);
   } else {

@@ -41,6 +41,9 @@ bool gemm_w8_wants_blocked(int64_t M, int64_t K, int64_t N);
 // true when launch_gemm_w8 runs the decomposition itself (single launch)
 bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);
+// measurement aid: the prefill kernel's MFMA sequence, tile schedule and epilogue without fill,
+// barriers and LDS traffic (output is meaningless); codes in the blocked layout or row-major
+int launch_gemm_w8_mfma_probe(const GemmW8Args& a, hipStream_t stream);
 
 // ---- W4A16 (gemm_w4.hip)
 struct GemmW4Args {

@@ -261,6 +261,35 @@ int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
                                 out_dtype == MSD_BF16, ldy, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+int msd_probe_mfma_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                         const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                         size_t workspace_bytes, const msd_debug_taps* /*taps*/, void* stream) {
+  if (out_dtype != MSD_F32) return MSD_ERR_INVALID_ARG;
+  if (M <= 0 || N <= 0 || K < 64 || K % 64 != 0 || K > 131072 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (!y || !w_scale || !x_bf16 || !W) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W, 16) || !aligned_to(x_bf16, 2) || !aligned_to(w_scale, 4) || !aligned_to(y, 4))
+    return MSD_ERR_INVALID_ARG;
+  const W8Layout l = w8_layout(M, K, N);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  GemmW8Args a{};
+  a.q1 = (int8_t*)(ws + l.q1);
+  a.q2 = (int8_t*)(ws + l.q2);
+  a.ldq = K;
+  a.alpha = (float*)(ws + l.alpha);
+  a.W = W;
+  a.w_scale = w_scale;
+  a.y = y;
+  a.ldy = ldy;
+  a.M = M; a.K = K; a.N = N;
+  a.a_step = (int64_t)(align_up((size_t)M, 128) / 16) * 1024;
+  int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
+                                 (float*)a.alpha, a.a_step, s);
+  if (rc) return rc;
+  return launch_gemm_w8_mfma_probe(a, s);
+}
+
 size_t msd_dequant_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N) {
   if (M <= 0 || K <= 0 || N <= 0) return 256;
   return dequant_workspace_bytes(M, K, N) + 256;

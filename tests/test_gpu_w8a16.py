@@ -166,3 +166,22 @@ def test_gemm_w8a16_error_codes(msd):
     # empty problems are successful no-ops
     y = msd.msd_gemm_w8a16(x[:0], W, s)
     assert y.shape == (0, 8)
+
+
+def test_measurement_aids_run(msd):
+    """msd_stream_read and msd_probe_mfma_w8a16 compute nothing that can be checked; they must run, leave
+    their inputs alone and reject shapes they do not support."""
+    W = torch.randint(-127, 128, (300, 512), dtype=torch.int8, device="cuda")
+    W0 = W.clone()
+    msd.msd_stream_read(W)
+    x = bf16_to_dev(synth.activations(5, 300, 512))
+    s = torch.rand(300, device="cuda")
+    y = msd.msd_probe_mfma_w8a16(x, W, s)
+    torch.cuda.synchronize()
+    assert y.shape == (300, 300) and torch.equal(W, W0)
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_probe_mfma_w8a16(x[:, :48].contiguous(), W[:, :48].contiguous(), s)
+    assert e.value.code == -2
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_stream_read(W[:, :100].contiguous())
+    assert e.value.code == -2
