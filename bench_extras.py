@@ -121,6 +121,16 @@ def leg_w4(msd, synth, time_calls, dev):
                "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
         if M <= 32:
             rec["bare_weight_read_us"] = round(bare_us, 1)
+        else:  # the matrix pipe alone on the same shape and data
+            try:
+                h = lambda i: msd.msd_probe_mfma_w4a16(x, *reps[i % len(reps)], y=y, ws=ws)
+                h(0)
+                us3 = _eager_us(h, 3)
+                rec["mfma_only_us"] = round(us3, 1)
+                rec["mfma_only_TFLOPS"] = round(4.0 * M * K * N / us3 / 1e6, 1)
+                rec["frac_of_mfma_only"] = round(us3 / us, 3)
+            except Exception as e:  # noqa: BLE001
+                rec["probe_error"] = str(e)
         try:
             ws2 = torch.empty(msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
             g = lambda i: msd.msd_dequant_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws2, prepare=M <= 32)

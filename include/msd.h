@@ -185,6 +185,12 @@ int msd_probe_mfma_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, 
                          const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
                          void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
                          void* stream);
+/* The same aid for msd_gemm_w4a16's many-row kernel (M > 32, K % 64 == 0, workspace of
+ * msd_gemm_w4a16_workspace_bytes(M, K, N)). */
+int msd_probe_mfma_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
+                         const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
+                         void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                         void* stream);
 
 #ifdef __cplusplus
 }

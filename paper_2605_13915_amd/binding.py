@@ -53,6 +53,7 @@ def lib():
         L.msd_probe_mfma_w8a16.argtypes = gemm8
         L.msd_gemm_w4a16.argtypes = gemm4
         L.msd_dequant_gemm_w4a16.argtypes = gemm4
+        L.msd_probe_mfma_w4a16.argtypes = gemm4
         for f in (L.msd_gemm_w8a16_workspace_bytes, L.msd_gemm_w4a16_workspace_bytes,
                   L.msd_dequant_gemm_workspace_bytes):
             f.argtypes = [i64, i64, i64]
@@ -63,7 +64,8 @@ def lib():
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
-                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16"):
+                     "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
+                     "msd_probe_mfma_w4a16"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -198,6 +200,13 @@ def msd_probe_mfma_w8a16(x, W, w_scale, y=None, ws=None, prepare=False):
     assert W.is_contiguous() and W.shape[1] == x.shape[1]
     return _gemm_common("msd_probe_mfma_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
                         W.shape[0], torch.float32, False, y, ws, prepare)
+
+
+def msd_probe_mfma_w4a16(x, W_fp4, W_e8m0, y=None, ws=None, prepare=False):
+    """Measurement aid: the many-row W4A16 kernel's MFMA sequence without its data movement (y is meaningless)."""
+    _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
+    return _gemm_common("msd_probe_mfma_w4a16", "msd_gemm_w4a16_workspace_bytes", x, (_ptr(W_fp4), _ptr(W_e8m0)),
+                        W_fp4.shape[0], torch.float32, False, y, ws, prepare)
 
 
 def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None, prepare=False):

@@ -141,7 +141,10 @@ __device__ __forceinline__ void w4_wait_vm_barrier() {
 
 constexpr int kW4PGroupM = 8;
 
-template <int NS>
+// PROBE = true is a measurement aid (msd_probe_mfma_w4a16): after the first K step the kernel stops
+// fetching and keeps multiplying that step's operands -- the same scaled-MFMA sequence, tile
+// schedule and epilogue on real operand bits, without fill, barriers and LDS traffic.
+template <int NS, bool PROBE = false>
 __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, int tiles_m, int tiles_n) {
   constexpr int SZ_A = 24576, SZ_W = 8192, STAGE = SZ_A + SZ_W + 1024;
   constexpr int L = 8;  // data load instructions per wave and stage (wave 0 issues one more: scales)
@@ -289,6 +292,17 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   v8i a0[4], a1[4], b0[4], b1[4];
   int sa0 = 0, sb0 = 0, sa1 = 0, sb1 = 0;
   auto step = [&](int s, v8i (&bc)[4], int sac, int sbc, v8i (&bn)[4], int& san, int& sbn) {
+    if constexpr (PROBE) {
+      if (s > 0) {  // operands of step 0 (a1: component 1 of step 0), no data movement
+        mfma_first(a0, b0, sa0, sb0);
+        mfma_rest(a0, b0, sa0, sb0, 0, false);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_first(a1, b0, sa0 - 0x04040404, sb0);
+        mfma_rest(a1, b0, sa0 - 0x04040404, sb0, 0, false);
+        __builtin_amdgcn_sched_barrier(0);
+        return;
+      }
+    }
     mfma_first(a0, bc, sac, sbc);
     __builtin_amdgcn_sched_barrier(0);
     load_a(s, 1, a1);
@@ -299,12 +313,12 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     const int sac2 = sac - 0x04040404;  // beta = alpha / 16: every scale byte minus 4 (bytes are >= 4)
     mfma_first(a1, bc, sac2, sbc);
     __builtin_amdgcn_sched_barrier(0);
-    if (s + 1 < KT) {
+    if (!PROBE && s + 1 < KT) {
       load_a(s + 1, 0, a0);
       load_b(s + 1, bn, san, sbn);
     }
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, s + 1 < KT && s - 1 + NS < KT);
+    mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, !PROBE && s + 1 < KT && s - 1 + NS < KT);
     __builtin_amdgcn_sched_barrier(0);
   };
 #pragma unroll
@@ -362,7 +376,7 @@ W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N) {
 
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
-                           hipStream_t stream) {
+                           hipStream_t stream, bool probe) {
   const W4PrefillLayout l = w4_prefill_layout(M, K, N);
   if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace
   const int KB2 = (int)(K / 64);
@@ -392,11 +406,16 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
   const size_t lds = (size_t)NS * (24576 + 8192 + 1024);
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_dma_kernel<NS>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_dma_kernel<NS, false>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_dma_kernel<NS, true>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w4_dma_kernel<NS>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+  if (probe)
+    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, true>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+  else
+    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

@@ -85,10 +85,12 @@ struct W4PrefillLayout {
 };
 bool gemm_w4_prefill_applies(int64_t M, int64_t K, int64_t N);
 W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N);
-// decomposition + scale transposition + GEMM; ws holds w4_prefill_layout(M, K, N).total bytes
+// decomposition + scale transposition + GEMM; ws holds w4_prefill_layout(M, K, N).total bytes.
+// probe: measurement aid -- the GEMM keeps multiplying the operands of its first K step (no fill,
+// barriers or LDS traffic afterwards); y is then meaningless
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
-                           hipStream_t stream);
+                           hipStream_t stream, bool probe = false);
 
 // ---- attention (attn.hip)
 struct AttnArgs {

@@ -290,6 +290,20 @@ int msd_probe_mfma_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, 
   return launch_gemm_w8_mfma_probe(a, s);
 }
 
+int msd_probe_mfma_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
+                         const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                         size_t workspace_bytes, const msd_debug_taps* /*taps*/, void* stream) {
+  if (out_dtype != MSD_F32) return MSD_ERR_INVALID_ARG;
+  if (M <= 0 || N <= 0 || K <= 0 || ldx < K || ldy < N || !gemm_w4_prefill_applies(M, K, N)) return MSD_ERR_SHAPE;
+  if (!y || !x_bf16 || !W_fp4 || !W_e8m0) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W_fp4, 16) || !aligned_to(x_bf16, 2) || !aligned_to(y, 4)) return MSD_ERR_INVALID_ARG;
+  const W4PrefillLayout l = w4_prefill_layout(M, K, N);
+  if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
+  return launch_gemm_w4_prefill((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, 0, ldy, M, K, N, (uint8_t*)workspace,
+                                (hipStream_t)stream, true);
+}
+
 size_t msd_dequant_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N) {
   if (M <= 0 || K <= 0 || N <= 0) return 256;
   return dequant_workspace_bytes(M, K, N) + 256;

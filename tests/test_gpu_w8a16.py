@@ -185,3 +185,10 @@ def test_measurement_aids_run(msd):
     with pytest.raises(msd.MsdError) as e:
         msd.msd_stream_read(W[:, :100].contiguous())
     assert e.value.code == -2
+    codes, exps = synth.mxfp4_weights(9, 300, 512)
+    y4 = msd.msd_probe_mfma_w4a16(x, to_dev(codes), to_dev(exps))
+    torch.cuda.synchronize()
+    assert y4.shape == (300, 300)
+    with pytest.raises(msd.MsdError) as e:      # 32 rows or fewer never reach the many-row kernel
+        msd.msd_probe_mfma_w4a16(x[:8], to_dev(codes), to_dev(exps))
+    assert e.value.code == -2
