@@ -170,12 +170,22 @@ def main():
             # what this GPU charges for the stream alone at this size
             stream_us[N] = time_calls(lambda i, reps=reps: msd.msd_stream_read(reps[i % len(reps)], prepare=True),
                                       2 * len(reps))
+        # the same call on one weight copy over and over (cache-resident weights), labelled warm
+        warm = time_calls(lambda i, M=M, N=N, reps=reps, s=s: msd.msd_gemm_w8a16(acts[M], reps[0], s, y=outs[(M, N)],
+                                                                             ws=ws, prepare=True), 16)
         b = w8_bytes(M, K, N)
-        per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2),
+        per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2), "warm_us_per_call": round(warm, 2),
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
                           "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2),
                           "bare_weight_read_us": round(stream_us[N], 2),
                           "bare_read_over_call": round(stream_us[N] / us, 3)})
+    # measured streaming-read rate of this GPU: a bare read of 1 GiB (four launches of 256 MiB, cold)
+    big = torch.empty((4, 65536, 4096), dtype=torch.uint8, device=dev)
+    big.fill_(1)
+    rd_us = time_calls(lambda i: msd.msd_stream_read(big[i % 4], prepare=True), 8)
+    measured_stream_GBps = (65536 * 4096) / rd_us / 1e3
+    del big
+    torch.cuda.empty_cache()
     dom = max(per_shape, key=lambda r: r["us_per_call"] )
     # HBM bytes per call from the committed counter summary (FETCH_SIZE / WRITE_SIZE runs of
     # `bench.py --traffic-probe`, scaled by a copy of known size); null when the file has no line for it
@@ -192,7 +202,9 @@ def main():
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
-                "algorithmic_bytes": w8_bytes(dom["M"], K, dom["N"])}
+                "algorithmic_bytes": w8_bytes(dom["M"], K, dom["N"]),
+                "measured_stream_read_GBps": round(measured_stream_GBps, 1),
+                "bare_weight_read_us_same_shape": dom["bare_weight_read_us"]}
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
