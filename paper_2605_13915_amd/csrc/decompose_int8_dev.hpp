@@ -60,20 +60,23 @@ __device__ __forceinline__ void chunk_codes(const Chunk16& c, float alpha, float
 // One workgroup of THREADS threads decomposes one row: xr[0..K) -> q1r, q2r (16-byte aligned),
 // *alpha_out.  s_red: THREADS/64 floats of LDS.  Ends with every thread's stores issued (no
 // trailing barrier).
-// With a_step != 0 the codes go to the blocked layout of the asynchronous-fill GEMM instead:
-// q1r / q2r then point at the array base and chunk c of row m lands at
-//   (c/4) * a_step + (m/16) * 1024 + (m%16) * 64 + ((c%4) ^ (((m%16)>>2)&3)) * 16.
+// With a_step != 0 the codes go to the blocked layout of the asynchronous-fill GEMM instead
+// (stage depth a_bk = 64 or 128 bytes of K per row): q1r / q2r then point at the array base and
+// 16-byte chunk c of row m lands in stage c / (a_bk/16), block m / (1024/a_bk), at the row's
+// place inside the block with its chunk index XOR-swizzled as in the GEMM's LDS image.
 template <int THREADS>
 __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restrict__ xr, int K,
                                                          int8_t* __restrict__ q1r,
                                                          int8_t* __restrict__ q2r,
                                                          float* __restrict__ alpha_out, bool aligned,
-                                                         float* s_red, int64_t a_step = 0, int64_t m = 0) {
+                                                         float* s_red, int64_t a_step = 0, int64_t m = 0,
+                                                         int a_bk = 64) {
   const int nchunks = K / 16;
-  const int64_t row_off = (m / 16) * 1024 + (m % 16) * 64;
-  const int sw = (int)(((m % 16) >> 2) & 3);
+  const int cpr = a_bk / 16, rpi = 1024 / a_bk;  // chunks per row, rows per 1 KB block
+  const int64_t row_off = (m / rpi) * 1024 + (m % rpi) * a_bk;
+  const int sw = a_bk == 64 ? (int)((m >> 2) & 3) : (int)((m >> 1) & 7);
   auto slot = [&](int c) -> int64_t {  // index of chunk c in units of 16 bytes
-    return a_step ? ((int64_t)(c >> 2) * a_step + row_off + (((c & 3) ^ sw) << 4)) >> 4 : c;
+    return a_step ? ((int64_t)(c / cpr) * a_step + row_off + (((c % cpr) ^ sw) << 4)) >> 4 : c;
   };
   Chunk16 cache[kDecRegChunks];
   float mx = 0.f;

@@ -487,14 +487,22 @@ __device__ __forceinline__ void wait_vm_barrier() {
 // fetching and keeps multiplying the fragments of that step, i.e. the same MFMA sequence, tile
 // schedule and epilogue with real operand bits but no fill, no barrier and no LDS traffic.  Its
 // time is what the matrix pipe alone allows for this shape and data on the chip at hand.
-template <int BMH, int BN, int WM, int WN, int NS, bool BF16, bool PROBE = false>
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16, bool PROBE = false, int BK = 64>
 __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN == 4) ? 2 : 1) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+  // BK = bytes of K per row and stage.  64: LDS rows of 64 B, chunk swizzle (row>>2)&3, a fill
+  // instruction covers 16 rows.  128 (small batched-decode tiles, K % 128 == 0): rows of 128 B =
+  // whole cache lines, swizzle (row>>1)&7, 8 rows per fill instruction, four MFMA K extents per
+  // stage -- half as many barrier rounds for the same K, which is what bounds those tiles.
   using AccT = std::conditional_t<BF16, v16f, v16i>;
   constexpr int NW = WM * WN, ROWS_A = 2 * BMH, R = ROWS_A + BN;
   constexpr int TMH = BMH / WM, TN = BN / WN, FM = TMH / 32, FN = TN / 32;
-  constexpr int L = R / (16 * NW);   // load instructions per wave and stage
-  constexpr int STAGE = R * 64;
-  static_assert(R % (16 * NW) == 0 && TMH % 32 == 0 && TN % 32 == 0, "tile shape");
+  constexpr int HS = BK / 32;       // MFMA K extents (32 bytes) per stage
+  constexpr int CPR = BK / 16;      // 16-byte chunks per row
+  constexpr int RPI = 1024 / BK;    // rows per fill instruction
+  constexpr int L = R / (RPI * NW);  // fill instructions per wave and stage
+  constexpr int STAGE = R * BK;
+  static_assert(BK == 64 || BK == 128, "stage depth");
+  static_assert(R % (RPI * NW) == 0 && TMH % 32 == 0 && TN % 32 == 0 && BMH % RPI == 0, "tile shape");
   static_assert(NS >= 3 && (NS - 2) * L < 64, "stage count");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -516,42 +524,43 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
   const int tm = first_m + in_group % rows_in_group;
   const int tn = in_group / rows_in_group;
   const int64_t m0 = (int64_t)tm * (BF16 ? ROWS_A : BMH), n0 = (int64_t)tn * BN;
+  auto swz = [](int row) { return BK == 64 ? ((row >> 2) & 3) : ((row >> 1) & 7); };
 
-  // ---- this wave's L load instructions per stage: 16-row block q*NW + wave of the stage
-  // (blocks 0 .. ROWS_A/16-1 are q1 then q2 rows, the rest W rows)
-  const int rr = lane >> 2, pc = lane & 3;
-  const int lc = pc ^ ((rr >> 2) & 3);  // logical chunk this lane fetches
+  // ---- this wave's L fill instructions per stage: block q*NW + wave of RPI rows
+  // (blocks 0 .. ROWS_A/RPI-1 are q1 then q2 rows, the rest W rows)
+  const int rr = lane / CPR, pc = lane % CPR;
   uint32_t voff[L];
   const int8_t* gbase[L];
   uint32_t ldst[L];
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-  // Blocked activation codes (a.a_step != 0, see GemmW8Args): the 16-row block of a K step is one
-  // contiguous, already swizzled kilobyte, copied in lane order; a.a_step bytes separate K steps.
+  // Blocked activation codes (a.a_step != 0, see GemmW8Args): the block of a stage is one
+  // contiguous, already swizzled kilobyte, copied in lane order; a.a_step bytes separate stages.
   const bool blocked = !BF16 && a.a_step != 0;
-  int64_t kadv[L];  // bytes between consecutive K steps of this instruction's source
+  int64_t kadv[L];  // bytes between consecutive stages of this instruction's source
 #pragma unroll
   for (int q = 0; q < L; ++q) {
     const int blk = q * NW + wave;
-    kadv[q] = 64;
-    if (blk < ROWS_A / 16) {
-      const int comp = blk / (BMH / 16);
+    const int lc = pc ^ swz(blk * RPI + rr);  // logical chunk this lane fetches
+    kadv[q] = BK;
+    if (blk < ROWS_A / RPI) {
+      const int comp = blk / (BMH / RPI);
       if (blocked) {
         voff[q] = (uint32_t)(lane * 16);
-        gbase[q] = (comp ? a.q2 : a.q1) + (m0 / 16 + blk % (BMH / 16)) * 1024;
+        gbase[q] = (comp ? a.q2 : a.q1) + (m0 / RPI + blk % (BMH / RPI)) * 1024;
         kadv[q] = a.a_step;
       } else {
-        const int64_t mrow = min(m0 + (BF16 ? comp * BMH : 0) + (blk % (BMH / 16)) * 16 + rr, M - 1);
+        const int64_t mrow = min(m0 + (BF16 ? comp * BMH : 0) + (blk % (BMH / RPI)) * RPI + rr, M - 1);
         voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
         gbase[q] = ((comp && !BF16) ? a.q2 : a.q1) + m0 * a.ldq;
       }
     } else {
-      const int64_t nrow = min(n0 + (blk - ROWS_A / 16) * 16 + rr, N - 1);
+      const int64_t nrow = min(n0 + (blk - ROWS_A / RPI) * RPI + rr, N - 1);
       voff[q] = (uint32_t)((nrow - n0) * K + lc * 16);
       gbase[q] = a.W + n0 * K;
     }
     ldst[q] = lds0 + blk * 1024;
   }
-  const int KT = (int)(K / 64);
+  const int KT = (int)(K / BK);
   auto issue = [&](int kt) {
     const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
 #pragma unroll
@@ -571,31 +580,31 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][i][j][r] = 0;
 
-  int fa_off[2][FM][2], fb_off[FN][2];  // byte offset inside a stage for K half-step 0 / 1
+  int fa_off[2][FM][HS], fb_off[FN][HS];  // byte offset inside a stage for K extent h
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
+  for (int h = 0; h < HS; ++h) {
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
         const int row = c * BMH + wm * TMH + 32 * i + l32;
-        fa_off[c][i][s] = row * 64 + (((2 * s + kg) ^ ((row >> 2) & 3)) << 4);
+        fa_off[c][i][h] = row * BK + (((2 * h + kg) ^ swz(row)) << 4);
       }
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
       const int row = wn * TN + 32 * j + l32;
-      fb_off[j][s] = ROWS_A * 64 + row * 64 + (((2 * s + kg) ^ ((row >> 2) & 3)) << 4);
+      fb_off[j][h] = ROWS_A * BK + row * BK + (((2 * h + kg) ^ swz(row)) << 4);
     }
   }
 
   auto stage_ptr = [&](int kt) { return smem + (kt % NS) * STAGE; };
-  auto load_frags = [&](const int8_t* st, int s, v4i (&fa)[2 * FM], v4i (&fb)[FN]) {
+  auto load_frags = [&](const int8_t* st, int h, v4i (&fa)[2 * FM], v4i (&fb)[FN]) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const v4i*>(st + fb_off[j][s]);
+    for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const v4i*>(st + fb_off[j][h]);
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int i = 0; i < FM; ++i) fa[c * FM + i] = *reinterpret_cast<const v4i*>(st + fa_off[c][i][s]);
+      for (int i = 0; i < FM; ++i) fa[c * FM + i] = *reinterpret_cast<const v4i*>(st + fa_off[c][i][h]);
   };
   auto mfma_block = [&](const v4i (&fa)[2 * FM], const v4i (&fb)[FN]) {
 #pragma unroll
@@ -614,17 +623,6 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
     else if (younger == NS - 3) wait_vm_barrier<(NS - 3) * L>();
     else wait_vm_barrier<0>();
   };
-  // Software pipeline: the fragments of K half-step (kt,1) are fetched under the MFMAs of (kt,0),
-  // those of (kt+1,0) under the MFMAs of (kt,1).  The barrier for tile kt+1 sits between the two
-  // MFMA blocks of tile kt; after it the stage of tile kt-1 is free and is refilled at once.
-#pragma unroll
-  for (int t = 0; t < NS - 1; ++t)
-    if (t < KT) issue(t);
-  v4i fa0[2 * FM], fb0[FN], fa1[2 * FM], fb1[FN];
-  if (KT > 0) {
-    wait_tile(0, min(KT - 1, NS - 2));
-    load_frags(stage_ptr(0), 0, fa0, fb0);
-  }
   // The first MFMA of a block is issued before the fragment reads of the next block: the
   // compiler's wait for the current fragments (it cannot count LDS operations across the inline
   // asm and waits for all of them) then covers no read that was only just issued.
@@ -640,7 +638,7 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
         for (int j = 0; j < FN; ++j)
           if (c + i + j > 0) acc[c][i][j] = mfma32(fa[c * FM + i], fb[j], acc[c][i][j]);
   };
-  // The same block with the L load instructions of tile kt_issue spread between the MFMAs
+  // The same block with the L fill instructions of tile kt_issue spread between the MFMAs
   // (one every SPREAD MFMAs): issued in one burst right after the barrier they fill the address
   // queue, the waves leave the burst at different times and the next barrier pays for the skew.
   auto mfma_rest_issue = [&](const v4i (&fa)[2 * FM], const v4i (&fb)[FN], int kt_issue, bool do_issue) {
@@ -665,34 +663,50 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
     for (int q = (NM + SPREAD - 1) / SPREAD; q < L; ++q)  // loads that found no MFMA to follow
       if (do_issue) issue_one(kt_issue, q);
   };
-  for (int kt = 0; kt + 1 < KT; ++kt) {
+
+  // Software pipeline over the K extents (kt, h): the fragments of the next extent are fetched
+  // under the MFMAs of the current one, alternating between two register sets.  The barrier for
+  // tile kt+1 sits before the last extent of tile kt; after it the stage of tile kt-1 is free and
+  // is refilled (tile kt+NS-1) under that extent's MFMAs.
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < KT) issue(t);
+  v4i fa0[2 * FM], fb0[FN], fa1[2 * FM], fb1[FN];
+  if (KT > 0) {
+    wait_tile(0, min(KT - 1, NS - 2));
+    load_frags(stage_ptr(0), 0, fa0, fb0);
+  }
+  for (int kt = 0; kt < KT; ++kt) {
     if constexpr (PROBE) {
       if (kt > 0) {
-        mfma_block(fa0, fb0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_block(fa1, fb1);
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int h = 0; h < HS; h += 2) {
+          mfma_block(fa0, fb0);
+          __builtin_amdgcn_sched_barrier(0);
+          mfma_block(fa1, fb1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
         continue;
       }
     }
-    mfma_first(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(stage_ptr(kt), 1, fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
-    mfma_first(fa1, fb1);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(stage_ptr(kt + 1), 0, fa0, fb0);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_rest_issue(fa1, fb1, kt + NS - 1, !PROBE && kt + NS - 1 < KT);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  if (KT > 0) {  // last tile: nothing left to prefetch
-    load_frags(stage_ptr(KT - 1), 1, fa1, fb1);
-    mfma_block(fa0, fb0);
-    mfma_block(fa1, fb1);
+    const bool more = kt + 1 < KT;
+#pragma unroll
+    for (int h = 0; h < HS; ++h) {
+      const bool last = h == HS - 1;
+      v4i(&fac)[2 * FM] = (h & 1) ? fa1 : fa0;
+      v4i(&fbc)[FN] = (h & 1) ? fb1 : fb0;
+      v4i(&fan)[2 * FM] = (h & 1) ? fa0 : fa1;
+      v4i(&fbn)[FN] = (h & 1) ? fb0 : fb1;
+      if (last && more) wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
+      mfma_first(fac, fbc);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!last) load_frags(stage_ptr(kt), h + 1, fan, fbn);
+      else if (more) load_frags(stage_ptr(kt + 1), 0, fan, fbn);
+      __builtin_amdgcn_sched_barrier(0);
+      if (last) mfma_rest_issue(fac, fbc, kt + NS - 1, !PROBE && more && kt + NS - 1 < KT);
+      else mfma_rest(fac, fbc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 
   if constexpr (BF16) {
@@ -756,21 +770,23 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
   }
 }
 
-template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false, bool PROBE = false>
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false, bool PROBE = false, int BK = 64>
 static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
+  if (a.K % BK != 0 || (a.a_step != 0 && a.a_bk != BK)) return MSD_ERR_INVALID_ARG;
   const int tiles_m = (int)cdiv(a.M, BF16 ? 2 * BMH : BMH), tiles_n = (int)cdiv(a.N, BN);
   const int total = tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  const size_t lds = (size_t)NS * (2 * BMH + BN) * 64;
-  static_assert((size_t)NS * (2 * BMH + BN) * 64 <= 160 * 1024, "LDS budget");
+  const size_t lds = (size_t)NS * (2 * BMH + BN) * BK;
+  static_assert((size_t)NS * (2 * BMH + BN) * BK <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    MSD_HIP_CHECK(hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE, BK>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE>), dim3(grid), dim3(WM * WN * 64), lds,
-                     stream, a, tiles_m, tiles_n);
+  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE, BK>), dim3(grid), dim3(WM * WN * 64),
+                     lds, stream, a, tiles_m, tiles_n);
   return MSD_OK;
 }
 
@@ -868,10 +884,13 @@ static W8Path w8_path(int64_t M, int64_t K, int64_t N) {
   return k64 ? W8Path::kFillLarge : W8Path::kStaged;
 }
 
-bool gemm_w8_wants_blocked(int64_t M, int64_t K, int64_t N) {
-  if (gemm_w8_is_fused(M, K, N)) return false;
+// Stage depth (bytes of K per row) of the blocked code layout this shape's GEMM reads; 0: row-major.
+int gemm_w8_blocked_bk(int64_t M, int64_t K, int64_t N) {
+  if (gemm_w8_is_fused(M, K, N)) return 0;
   const W8Path p = w8_path(M, K, N);
-  return p == W8Path::kFillSmall || p == W8Path::kFillLarge;
+  if (p == W8Path::kFillLarge) return 64;
+  if (p == W8Path::kFillSmall) return K % 128 == 0 ? 128 : 64;
+  return 0;
 }
 
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
@@ -896,10 +915,15 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     // small tiles that still gives about 200 workgroups (measured: the stream rate is set by how
     // many CUs pull, then by the activation re-reads per workgroup).  16 < M <= 32 with many
     // columns measured 27 vs 31 us on the smallest tile against the register-operand kernel.
+    // These tiles do few MFMAs per barrier round, so with K % 128 == 0 a stage holds 128 bytes of K.
     const auto wgs = [&](int bmh, int bn) { return cdiv(M, bmh) * cdiv(N, bn); };
-    if (2 * M > 64 && wgs(64, 128) >= 200) rc = launch_dma<64, 128, 2, 2, 8>(a, stream);
-    else if (2 * M > 64 && wgs(64, 64) >= 200) rc = launch_dma<64, 64, 2, 2, 6>(a, stream);
-    else rc = launch_dma<32, 64, 1, 2, 8>(a, stream);  // 64 KB of LDS: two workgroups per CU
+    const bool deep = a.K % 128 == 0 && (a.a_step == 0 || a.a_bk == 128);
+    if (2 * M > 64 && wgs(64, 128) >= 200)
+      rc = deep ? launch_dma<64, 128, 2, 2, 4, false, false, 128>(a, stream) : launch_dma<64, 128, 2, 2, 8>(a, stream);
+    else if (2 * M > 64 && wgs(64, 64) >= 200)
+      rc = deep ? launch_dma<64, 64, 2, 2, 4, false, false, 128>(a, stream) : launch_dma<64, 64, 2, 2, 6>(a, stream);
+    else  // at most 64 KB of LDS: two workgroups per CU
+      rc = deep ? launch_dma<32, 64, 1, 2, 4, false, false, 128>(a, stream) : launch_dma<32, 64, 1, 2, 8>(a, stream);
   } else if (path == W8Path::kFillLarge) {
     // three or five stages, and half-size tiles with two workgroups per CU, all measured the same
     rc = launch_dma<128, 256, 2, 2, 4>(a, stream);

@@ -5,9 +5,9 @@
 namespace msd {
 
 // ---- decomposition (decompose.hip)
-// a_step != 0: write the blocked layout of GemmW8Args instead of row-major [M][ldq]
+// a_step != 0: write the blocked layout of GemmW8Args (stage depth a_bk) instead of row-major [M][ldq]
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
-                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, hipStream_t stream);
+                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, hipStream_t stream);
 int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
                            uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
                            uint8_t* op_e8m0, hipStream_t stream);
@@ -31,13 +31,16 @@ struct GemmW8Args {
   int64_t ldx;
   int x_aligned;     // rows of x are 16-byte aligned
   int export_codes;  // also write q1/q2/alpha to the workspace (observation points)
-  // blocked code layout for the asynchronous-fill kernels (0: q1/q2 are row-major [M][ldq]):
-  // q[K/64][ceil(M/128)*8 blocks][16 rows][64 B], the four 16-byte chunks of a row stored at
-  // chunk ^ ((row>>2)&3), i.e. exactly the LDS image; a_step = bytes between K steps
+  // blocked code layout for the asynchronous-fill kernels (a_step == 0: q1/q2 are row-major
+  // [M][ldq]): q[K/a_bk stages][Mpad*a_bk/1024 blocks][1 KB], a block = 1024/a_bk rows of a_bk
+  // bytes, the 16-byte chunks of a row stored at chunk ^ swizzle(row) (a_bk = 64: (row>>2)&3,
+  // 128: (row>>1)&7), i.e. exactly the LDS image; a_step = bytes between stages, Mpad = M
+  // rounded up to 128
   int64_t a_step;
+  int a_bk;
 };
-// does launch_gemm_w8 take the codes in the blocked layout for this shape?
-bool gemm_w8_wants_blocked(int64_t M, int64_t K, int64_t N);
+// stage depth of the blocked layout launch_gemm_w8 wants for this shape (0: row-major)
+int gemm_w8_blocked_bk(int64_t M, int64_t K, int64_t N);
 // true when launch_gemm_w8 runs the decomposition itself (single launch)
 bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);

@@ -72,7 +72,7 @@ int msd_decompose(int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx
     if (K % 16 != 0) return MSD_ERR_SHAPE;
     if (!aligned_to(scale, 4)) return MSD_ERR_INVALID_ARG;
     return launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)q1, (int8_t*)q2, K,
-                                 (float*)scale, 0, s);
+                                 (float*)scale, 0, 64, s);
   }
   if (K % 32 != 0) return MSD_ERR_SHAPE;
   return launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, (uint8_t*)q1, (uint8_t*)q2,
@@ -121,9 +121,10 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   } else if (K > 0) {
     // codes in the layout the GEMM kernel of this shape reads; observation points want row-major
     const bool code_taps = taps && (taps->q1 || taps->q2);
-    if (!code_taps && gemm_w8_wants_blocked(M, K, N)) a.a_step = (int64_t)(align_up((size_t)M, 128) / 16) * 1024;
+    a.a_bk = code_taps ? 0 : gemm_w8_blocked_bk(M, K, N);
+    if (a.a_bk) a.a_step = (int64_t)align_up((size_t)M, 128) * a.a_bk;  // Mpad rows of a_bk bytes per stage
     int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
-                                   (float*)a.alpha, a.a_step, s);
+                                   (float*)a.alpha, a.a_step, a.a_bk ? a.a_bk : 64, s);
     if (rc) return rc;
   } else {
     int rc = fill_u32((uint32_t*)a.alpha, M, 0u, s);
@@ -283,9 +284,10 @@ int msd_probe_mfma_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, 
   a.y = y;
   a.ldy = ldy;
   a.M = M; a.K = K; a.N = N;
-  a.a_step = (int64_t)(align_up((size_t)M, 128) / 16) * 1024;
+  a.a_bk = 64;
+  a.a_step = (int64_t)align_up((size_t)M, 128) * 64;
   int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
-                                 (float*)a.alpha, a.a_step, s);
+                                 (float*)a.alpha, a.a_step, 64, s);
   if (rc) return rc;
   return launch_gemm_w8_mfma_probe(a, s);
 }
