@@ -173,38 +173,40 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   const int tn = in_group / rows_in_group;
   const int64_t m0 = (int64_t)tm * 256, n0 = (int64_t)tn * 256;
 
-  // ---- this wave's load instructions per stage: instruction q*4 + wave of the 32 data instructions
-  // (0..23: activation group idx/3, chunk pair idx%3; 24..31: weight group idx-24)
-  uint32_t voff[L], ldst[L], kstep[L];
-  const uint8_t* gbase[L];
+  // ---- this wave's load instructions per stage: instruction idx = q*4 + wave of the 32 data
+  // instructions.  The stage image is linear in idx (24 KB of activation operands, then 8 weight
+  // groups of 1 KB), and so is the activation source (qop holds the tile's 24 KB of a K step
+  // contiguously): instruction idx < 24 copies kilobyte idx of it.  Instructions 24..31 gather
+  // weight group idx - 24 (32 columns x 2 blocks).  All bases are wave-uniform scalars; only the
+  // two weight offsets and the scale offset are per lane.
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem4p;
+  const uint8_t* a_src = a.qop + (m0 / 32 * 3 + wave) * 1024;  // + kt * step_a + q * 4096, lane * 16
+  const uint8_t* w_src = a.W + n0 * row_w;                      // + kt * 32, lane offsets below
+  uint32_t voff_w[2];
 #pragma unroll
-  for (int q = 0; q < L; ++q) {
-    const int idx = q * 4 + wave;
-    if (idx < 24) {  // a contiguous kilobyte of qop: third j of row group gi
-      const int gi = idx / 3, j = idx % 3;
-      voff[q] = (uint32_t)(lane * 16);
-      gbase[q] = a.qop + ((m0 / 32 + gi) * 3 + j) * 1024;
-      ldst[q] = lds0 + gi * 3072 + j * 1024;
-      kstep[q] = step_a;
-    } else {
-      const int gj = idx - 24;
-      const int64_t nrow = min(n0 + 32 * gj + l32, N - 1);
-      voff[q] = (uint32_t)((nrow - n0) * row_w + kb * 16);
-      gbase[q] = a.W + n0 * row_w;
-      ldst[q] = lds0 + SZ_A + gj * 1024;
-      kstep[q] = 32;
-    }
+  for (int g = 0; g < 2; ++g) {
+    const int gj = g * 4 + wave;
+    const int64_t nrow = min(n0 + 32 * gj + l32, N - 1);
+    voff_w[g] = (uint32_t)((nrow - n0) * row_w + kb * 16);
   }
+  const uint32_t voff_a = (uint32_t)(lane * 16);
   // scale bytes of a stage: lanes 0..31 fetch the 512 bytes of sa_t[kt][tm], lanes 32..63 those of sw_t[kt][tn]
   const uint8_t* sbase = kb ? a.sw_t : a.sa_t;                                     // per lane
   const uint64_t s_first = (uint64_t)(sbase - a.ws) + (kb ? n0 : m0) * 2 + 16 * l32;  // byte offset from a.ws
   const uint64_t s_inc = (uint64_t)(kb ? a.Npad : a.Mpad) * 2;                     // per K step
+  auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
+    const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 4096);
+    if (q < 6) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 4096, voff_a, dst);
+    else w4_lds_dma16(w_src + (int64_t)kt * 32, voff_w[q - 6], dst);
+  };
+  auto issue_scales = [&](int kt) {
+    if (wave == 0)
+      w4_lds_dma16(a.ws, (uint32_t)(s_first + (uint64_t)kt * s_inc), lds0 + (uint32_t)((kt % NS) * STAGE) + SZ_A + SZ_W);
+  };
   auto issue = [&](int kt) {
-    const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
 #pragma unroll
-    for (int q = 0; q < L; ++q) w4_lds_dma16(gbase[q] + (int64_t)kt * kstep[q], voff[q], ldst[q] + sb);
-    if (wave == 0) w4_lds_dma16(a.ws, (uint32_t)(s_first + (uint64_t)kt * s_inc), lds0 + sb + SZ_A + SZ_W);
+    for (int q = 0; q < L; ++q) issue_one(kt, q);
+    issue_scales(kt);
   };
 
   v16f acc[4][4];
@@ -246,9 +248,6 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // ISSUE: the load instructions of tile kt_issue go out between the MFMAs, one after every second
   // MFMA (in one burst after the barrier they fill the address queue, the waves leave the burst at
   // different times and the next barrier pays for the skew); wave 0's scale fetch goes last.
-  auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
-    w4_lds_dma16(gbase[q] + (int64_t)kt * kstep[q], voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
-  };
   auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb, int kt_issue, bool do_issue) {
 #define MSD_W4_POST(IDX)                                            \
   if ((IDX) % 2 == 0 && (IDX) / 2 < L) {                            \
@@ -264,10 +263,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
 #undef MSD_W4_ROW
 #undef MSD_W4_POST
-    if (do_issue && wave == 0) {
-      const uint32_t sbo = (uint32_t)((kt_issue % NS) * STAGE);
-      w4_lds_dma16(a.ws, (uint32_t)(s_first + (uint64_t)kt_issue * s_inc), lds0 + sbo + SZ_A + SZ_W);
-    }
+    if (do_issue) issue_scales(kt_issue);
   };
   // wait until tile t has landed (the tiles issued after it may stay in flight), then barrier
   auto wait_tile = [&](int t, int newest_issued) {
