@@ -20,8 +20,10 @@
  * Pin status (see tests/test_oracle_*.py): every function below is pinned by the
  * paper's theorems, closed forms, brute force on tiny inputs or an independently
  * written exact-rational implementation.  msd_oracle_attn_decode in per-token scale
- * mode is pinned only through invariants and the fp64 truth ("parity unpinned"
- * beyond those, because the paper states attention for per-channel scales only).
+ * mode (a reading: the paper states attention for per-channel scales only) is pinned
+ * by reduction to the per-channel statement -- identical codes and output for uniform
+ * power-of-two scales, exact equivalence of scaling s_K[t] and scaling the INT8 row
+ * K[t] by a power of two -- next to the invariants and the fp64 truth.
  */
 #include <math.h>
 #include <stdint.h>

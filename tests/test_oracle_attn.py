@@ -142,3 +142,63 @@ def test_kv_len_and_gqa_mapping():
     q_sw = np.concatenate([q[:, 4:], q[:, :4]], axis=1)
     out_ref = oracle.attn_decode(q_sw, Kc, Vc, ks, vs, oracle.PER_TOKEN, kv_len=kv_len)
     assert np.array_equal(out_sw[:, :4], out_ref[:, 4:]) and np.array_equal(out_sw[:, 4:], out_ref[:, :4])
+
+
+def test_per_token_mode_reduces_to_the_per_channel_statement_for_uniform_scales():
+    """Pin of the per-token reading against the paper's own (per-channel) statement: with every
+    per-token scale equal to one power of two c, and every per-channel scale equal to the same c,
+    both modes describe the same dequantised K and V, and scaling by a power of two is exact in
+    every step -- so the two code paths must produce identical Q, S and P codes and the same
+    output up to the one place where they differ in rounding (alpha_P = fl(c/127) against the
+    exact constant 1/127)."""
+    B, Hq, Hkv, d, L = 2, 8, 2, 128, 300
+    rng = np.random.default_rng(5)
+    q = synth.queries(11, B, Hq, d)
+    Kc = rng.integers(-127, 128, (B, Hkv, L, d), dtype=np.int8)
+    Vc = rng.integers(-127, 128, (B, Hkv, L, d), dtype=np.int8)
+    for ck, cv in ((2.0 ** -6, 2.0 ** -5), (1.0, 1.0), (2.0 ** -3, 4.0)):
+        kt = np.full((B, Hkv, L), ck, np.float32)
+        vt = np.full((B, Hkv, L), cv, np.float32)
+        kc = np.full((Hkv, d), ck, np.float32)
+        vc = np.full((Hkv, d), cv, np.float32)
+        o_t, t_t = oracle.attn_decode(q, Kc, Vc, kt, vt, oracle.PER_TOKEN, taps=True)
+        o_c, t_c = oracle.attn_decode(q, Kc, Vc, kc, vc, oracle.PER_CHANNEL, taps=True)
+        for key in ("q1", "q2", "s1", "s2", "p1", "p2"):
+            assert np.array_equal(t_t[key], t_c[key]), key
+        assert np.array_equal(t_t["p"], t_c["p"])
+        err = np.linalg.norm(o_t.astype(np.float64) - o_c) / np.linalg.norm(o_c)
+        assert err < 1e-7
+
+
+def test_per_token_scales_are_applied_to_their_own_token():
+    """Pin of the per-token indexing: multiplying s_K[t] by 2^e_t is the same as multiplying the
+    INT8 row K[t] by 2^e_t (small codes, so the product is still INT8) -- exactly, because the
+    integer dot products scale by 2^e_t and the merge multiplies by a power of two.  The same
+    move on V changes alpha_P (it is max_t s_V[t] / 127), so there the two runs agree within the
+    decomposition error only, which still separates a right index from a wrong one by orders of
+    magnitude."""
+    B, Hq, Hkv, d, L = 2, 8, 2, 128, 300
+    rng = np.random.default_rng(7)
+    q = synth.queries(13, B, Hq, d)
+    Kc = rng.integers(-31, 32, (B, Hkv, L, d), dtype=np.int8)
+    Vc = rng.integers(-31, 32, (B, Hkv, L, d), dtype=np.int8)
+    e = rng.integers(0, 3, (B, Hkv, L))
+    f = rng.integers(0, 3, (B, Hkv, L))
+    ck, cv = 2.0 ** -6, 2.0 ** -5
+    ku = np.full((B, Hkv, L), ck, np.float32)
+    vu = np.full((B, Hkv, L), cv, np.float32)
+    ks = (ck * 2.0 ** e).astype(np.float32)
+    vs = (cv * 2.0 ** f).astype(np.float32)
+    K2 = (Kc.astype(np.int32) * (1 << e)[..., None]).astype(np.int8)
+    V2 = (Vc.astype(np.int32) * (1 << f)[..., None]).astype(np.int8)
+    o1, t1 = oracle.attn_decode(q, Kc, Vc, ks, vu, oracle.PER_TOKEN, taps=True)
+    o2, t2 = oracle.attn_decode(q, K2, Vc, ku, vu, oracle.PER_TOKEN, taps=True)
+    assert np.array_equal(o1, o2) and np.array_equal(t1["p"], t2["p"])
+    assert np.array_equal(t1["s1"] * (1 << e).repeat(Hq // Hkv, axis=1), t2["s1"])
+    o3 = oracle.attn_decode(q, Kc, Vc, ku, vs, oracle.PER_TOKEN)
+    o4 = oracle.attn_decode(q, Kc, V2, ku, vu, oracle.PER_TOKEN)
+    err = np.linalg.norm(o3.astype(np.float64) - o4) / np.linalg.norm(o4)
+    assert err < 2e-4
+    # a shifted scale index would be off by O(1)
+    o_bad = oracle.attn_decode(q, Kc, Vc, ku, np.roll(vs, 1, axis=2), oracle.PER_TOKEN)
+    assert np.linalg.norm(o_bad.astype(np.float64) - o4) / np.linalg.norm(o4) > 0.05
