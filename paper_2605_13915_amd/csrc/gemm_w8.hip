@@ -72,49 +72,7 @@ __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta,
 //       the wave quantises its slice into wave-private LDS in A-fragment order.
 //   otherwise: the codes were written to the workspace by the decomposition kernel.
 //
-// Bit-exact quantisation without a division per element.  q = rne(x/alpha) is computed as
-// rne(x * (1/alpha)); the product differs from the correctly rounded quotient by at most
-// 127*2^-22 < 3.1e-5 in absolute terms, so the two can round differently only if the product is
-// within that distance of a half-integer.  Lanes where it is within 1e-4 recompute with the
-// exact division (about 2 elements in 10^4).  Same for the residual pass.
-__device__ __forceinline__ void int8_codes_fast(float x, float alpha, float ra, float beta, float rb,
-                                                int& c1, int& c2) {
-  float t = x * ra;
-  float q = rintf(t);
-  const bool tie1 = fabsf(t - q) > 0.5f - 1e-4f;
-  if (__builtin_amdgcn_ballot_w64(tie1) != 0)  // wave-uniform branch: the division is really skipped
-    q = tie1 ? rintf(__fdiv_rn(x, alpha)) : q;
-  const float r = __fmaf_rn(-alpha, q, x);
-  float u = r * rb;
-  float p = rintf(u);
-  const bool tie2 = fabsf(u - p) > 0.5f - 1e-4f;
-  if (__builtin_amdgcn_ballot_w64(tie2) != 0) p = tie2 ? rintf(__fdiv_rn(r, beta)) : p;
-  c1 = (int)fminf(fmaxf(q, -128.f), 127.f);
-  c2 = (int)fminf(fmaxf(p, -128.f), 127.f);
-}
-
-__device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, float ra, float beta,
-                                                 float rb, uint4& o1, uint4& o2) {
-  uint32_t a[4], b[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    uint32_t pa = 0, pb = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t w = c.w[j * 2 + (e >> 1)];
-      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-      int c1, c2;
-      int8_codes_fast(x, alpha, ra, beta, rb, c1, c2);
-      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
-      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
-    }
-    a[j] = pa;
-    b[j] = pb;
-  }
-  o1 = make_uint4(a[0], a[1], a[2], a[3]);
-  o2 = make_uint4(b[0], b[1], b[2], b[3]);
-}
-
+//   (the quantiser itself, bit-exact without a division per element, is in decompose_int8_dev.hpp)
 constexpr int kSelfMaxRows = 8;
 
 // FAST: K % 64 == 0, so no load of the main loop is predicated per lane (predicated loads do not
