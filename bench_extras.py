@@ -206,9 +206,59 @@ def leg_cmp_decode(msd, synth, time_calls, dev):
     return out
 
 
+def leg_variants(msd, synth, time_calls, dev):
+    """Decomposition-constant variants (paper Sec. 3.3) on a 2048 x 2048 x 2048 GEMM: relative L2 error of
+    the GPU output against an fp64 product of the same activations and exactly dequantised weights, and
+    time per call -- the variants change constants only, so the times should agree.  The MXFP4 rows are
+    the quantities of the paper's design-evolution table (Gaussian activations, MXFP4 weights)."""
+    M = K = N = 2048
+    out = {"shape": [M, K, N]}
+
+    def rel(y, truth):
+        return float(torch.linalg.norm(y.double() - truth) / torch.linalg.norm(truth))
+
+    xb = synth.activations(synth.seed_for(7, 0), M, K, outliers=False)
+    x = _bf16(xb, dev)
+    xd = x.double()
+    # INT8 weights
+    Wn, sn = synth.int8_weights(synth.seed_for(7, 1), N, K)
+    W, sc = torch.from_numpy(Wn).to(dev), torch.from_numpy(sn).to(dev)
+    truth = (xd @ W.double().T) * sc.double()[None, :]
+    y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N),
+                         msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
+    w8 = {}
+    for name, fn in (("main", lambda i: msd.msd_gemm_w8a16(x, W, sc, y=y, ws=ws)),
+                     ("fractional", lambda i: msd.msd_gemm_w8a16_variant(msd.MSD_VARIANT_INT8_FRACTIONAL, x, W, sc,
+                                                                         y=y, ws=ws)),
+                     ("dequant_bf16", lambda i: msd.msd_dequant_gemm_w8a16(x, W, sc, y=y, ws=ws))):
+        fn(0)
+        torch.cuda.synchronize()
+        w8[name] = {"rel_l2_vs_fp64": float("%.4g" % rel(y, truth)), "us": round(_eager_us(fn, 20), 1)}
+    out["w8a16"] = w8
+    del truth, W
+    # MXFP4 weights
+    cn, en = synth.mxfp4_weights(synth.seed_for(7, 2), N, K)
+    codes, exps = torch.from_numpy(cn).to(dev), torch.from_numpy(en).to(dev)
+    truth = xd @ torch.from_numpy(synth.dequantize_mxfp4(cn, en).astype(np.float64)).to(dev).T
+    ws = torch.empty(max(msd.lib().msd_gemm_w4a16_workspace_bytes(M, K, N),
+                         msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
+    w4 = {}
+    for name, var in (("v1", msd.MSD_VARIANT_MXFP4_V1), ("v2", msd.MSD_VARIANT_MXFP4_V2),
+                      ("v3_main", msd.MSD_VARIANT_MAIN)):
+        fn = lambda i, var=var: msd.msd_gemm_w4a16_variant(var, x, codes, exps, y=y, ws=ws)
+        fn(0)
+        torch.cuda.synchronize()
+        w4[name] = {"rel_l2_vs_fp64": float("%.4g" % rel(y, truth)), "us": round(_eager_us(fn, 20), 1)}
+    out["w4a16"] = w4
+    out["paper_table_l2"] = {"v1": 0.0182, "v2": 0.0107, "v3": 0.0101}
+    return out
+
+
 def run(want, msd, synth, time_calls, dev):
     res = {}
-    legs = {"prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode}
+    legs = {"prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
+            "variants": leg_variants}
     for name, fn in legs.items():
         if name in want:
             try:

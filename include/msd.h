@@ -44,6 +44,14 @@ enum {
 enum { MSD_INT8 = 0, MSD_MXFP4 = 1 };             /* decomposition format */
 enum { MSD_F32 = 0, MSD_BF16 = 1 };               /* output dtype */
 enum { MSD_PER_TOKEN = 0, MSD_PER_CHANNEL = 1 };  /* KV-cache scale granularity */
+/* Parameterisations of the decomposition constants (paper Sec. 3.3).  MSD_VARIANT_MAIN is the
+ * method as stated (what the entry points without a variant argument compute). */
+enum {
+  MSD_VARIANT_MAIN = 0,
+  MSD_VARIANT_INT8_FRACTIONAL = 1, /* INT8: alpha = max|x| / 127.49, beta = alpha / 254.98 */
+  MSD_VARIANT_MXFP4_V1 = 2,        /* MXFP4: alpha bound 1.75, beta = alpha / 8 (no clipping) */
+  MSD_VARIANT_MXFP4_V2 = 3         /* MXFP4: alpha bound 1.75, beta = alpha / 16 */
+};
 
 /*
  * Optional observation points ("taps").  Any member may be NULL.  They exist so that the
@@ -120,6 +128,31 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
                    void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
                    void* stream);
 size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * The three entry points above with the decomposition constants of paper Sec. 3.3 selectable
+ * ("fractional scaling" paragraph for INT8; the MXFP4 design-evolution table for MXFP4).
+ * Everything else (arguments, layouts, workspace sizes, errors) is as for the entry point of the
+ * same name without the suffix, which is the call with variant = MSD_VARIANT_MAIN.
+ *   MSD_VARIANT_INT8_FRACTIONAL (msd_decompose with MSD_INT8, msd_gemm_w8a16): alpha =
+ *       max|x_row| / 127.49f, beta = alpha / 254.98f (the two constants rounded to fp32), the merge
+ *       uses the same beta; reconstruction bound max|x| / 65015 instead of / 64516.
+ *   MSD_VARIANT_MXFP4_V1 (msd_decompose with MSD_MXFP4, msd_gemm_w4a16): e is the smallest
+ *       integer with max|x_block| <= 1.75 * 2^e and beta = alpha / 8 (beta's E8M0 byte is alpha's
+ *       minus 3); the residual never saturates.
+ *   MSD_VARIANT_MXFP4_V2: bound 1.75 as v1, beta = alpha / 16 as the main variant.
+ * A variant that does not belong to the format of the call is an INVALID_ARG error.
+ */
+int msd_decompose_variant(int variant, int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                          void* q1, void* q2, void* scale, void* stream);
+int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                           const int8_t* W, const float* w_scale, int64_t N, void* y, int out_dtype,
+                           int64_t ldy, void* workspace, size_t workspace_bytes,
+                           const msd_debug_taps* taps, void* stream);
+int msd_gemm_w4a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                           const uint8_t* W_fp4, const uint8_t* W_e8m0, int64_t N, void* y,
+                           int out_dtype, int64_t ldy, void* workspace, size_t workspace_bytes,
+                           const msd_debug_taps* taps, void* stream);
 
 /*
  * One decode step of attention over an INT8 KV cache without dequantising it (paper

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libmsd.so")
 MSD_INT8, MSD_MXFP4 = 0, 1
 MSD_F32, MSD_BF16 = 0, 1
 MSD_PER_TOKEN, MSD_PER_CHANNEL = 0, 1
+MSD_VARIANT_MAIN, MSD_VARIANT_INT8_FRACTIONAL, MSD_VARIANT_MXFP4_V1, MSD_VARIANT_MXFP4_V2 = 0, 1, 2, 3
 
 _ERR = {-1: "MSD_ERR_INVALID_ARG", -2: "MSD_ERR_SHAPE", -3: "MSD_ERR_WORKSPACE", -4: "MSD_ERR_HIP",
         -5: "MSD_ERR_UNSUPPORTED"}
@@ -46,6 +47,7 @@ def lib():
         L.msd_last_hip_error.restype = ci
         L.msd_version.restype = C.c_char_p
         L.msd_decompose.argtypes = [ci, vp, i64, i64, i64, vp, vp, vp, vp]
+        L.msd_decompose_variant.argtypes = [ci] + L.msd_decompose.argtypes
         gemm8 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         gemm4 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         L.msd_gemm_w8a16.argtypes = gemm8
@@ -54,6 +56,8 @@ def lib():
         L.msd_gemm_w4a16.argtypes = gemm4
         L.msd_dequant_gemm_w4a16.argtypes = gemm4
         L.msd_probe_mfma_w4a16.argtypes = gemm4
+        L.msd_gemm_w8a16_variant.argtypes = [ci] + gemm8
+        L.msd_gemm_w4a16_variant.argtypes = [ci] + gemm4
         for f in (L.msd_gemm_w8a16_workspace_bytes, L.msd_gemm_w4a16_workspace_bytes,
                   L.msd_dequant_gemm_workspace_bytes):
             f.argtypes = [i64, i64, i64]
@@ -65,7 +69,8 @@ def lib():
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
-                     "msd_probe_mfma_w4a16"):
+                     "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
+                     "msd_gemm_w4a16_variant"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -130,6 +135,11 @@ class Prepared:
 
 def msd_decompose(fmt, x):
     """x: bf16 [M][K] (row stride may exceed K).  Returns (q1, q2, scale) device tensors."""
+    return msd_decompose_variant(None, fmt, x)
+
+
+def msd_decompose_variant(variant, fmt, x):
+    """msd_decompose with the decomposition constants of `variant` (None: the entry point without one)."""
     _dev(x, torch.bfloat16, "x")
     M, K = x.shape
     assert x.stride(1) == 1
@@ -141,13 +151,16 @@ def msd_decompose(fmt, x):
         q1 = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
         q2 = torch.empty_like(q1)
         sc = torch.empty((M, K // 32), dtype=torch.uint8, device=x.device)
-    rc = lib().msd_decompose(fmt, _ptr(x), M, K, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(q1),
-                             _ptr(q2), _ptr(sc), _stream())
-    _check(rc, "msd_decompose")
+    args = (fmt, _ptr(x), M, K, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(q1), _ptr(q2), _ptr(sc),
+            _stream())
+    if variant is None:
+        _check(lib().msd_decompose(*args), "msd_decompose")
+    else:
+        _check(lib().msd_decompose_variant(variant, *args), "msd_decompose_variant")
     return q1, q2, sc
 
 
-def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws, prepare=False):
+def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws, prepare=False, lead=()):
     L = lib()
     M, K = x.shape
     if y is None:
@@ -157,7 +170,7 @@ def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws, prepare=F
     tp = None
     keep = {}
     if taps:
-        if fn_name.endswith("w8a16"):
+        if "w8a16" in fn_name:
             keep = dict(q1=torch.empty((M, K), dtype=torch.int8, device=x.device),
                         q2=torch.empty((M, K), dtype=torch.int8, device=x.device),
                         scale=torch.empty((M,), dtype=torch.float32, device=x.device),
@@ -171,7 +184,7 @@ def _gemm_common(fn_name, ws_fn, x, w_args, N, out_dtype, taps, y, ws, prepare=F
                   keep["acc1"].data_ptr() if "acc1" in keep else None,
                   keep["acc2"].data_ptr() if "acc2" in keep else None)
     ldx = x.stride(0) if M > 1 else max(K, x.stride(0))
-    args = (_ptr(x), M, K, ldx, *w_args, N, _ptr(y), _out_code(y.dtype), y.stride(0), _ptr(ws), ws.numel(),
+    args = (*lead, _ptr(x), M, K, ldx, *w_args, N, _ptr(y), _out_code(y.dtype), y.stride(0), _ptr(ws), ws.numel(),
             C.byref(tp) if tp is not None else None, _stream())
     if prepare:
         return Prepared(getattr(L, fn_name), args, (x, y, ws, keep, tp), fn_name, y)
@@ -185,6 +198,14 @@ def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, w
     assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
     return _gemm_common("msd_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
                         W.shape[0], out_dtype, taps, y, ws, prepare)
+
+
+def msd_gemm_w8a16_variant(variant, x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, ws=None,
+                           prepare=False):
+    _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
+    assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
+    return _gemm_common("msd_gemm_w8a16_variant", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
+                        W.shape[0], out_dtype, taps, y, ws, prepare, lead=(int(variant),))
 
 
 def msd_dequant_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, y=None, ws=None, prepare=False):
@@ -214,6 +235,15 @@ def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None
     assert W_fp4.is_contiguous() and W_e8m0.is_contiguous() and W_fp4.shape[1] * 2 == x.shape[1]
     return _gemm_common("msd_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x, (_ptr(W_fp4), _ptr(W_e8m0)),
                         W_fp4.shape[0], out_dtype, taps, y, ws, prepare)
+
+
+def msd_gemm_w4a16_variant(variant, x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None,
+                           prepare=False):
+    _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
+    assert W_fp4.is_contiguous() and W_e8m0.is_contiguous() and W_fp4.shape[1] * 2 == x.shape[1]
+    return _gemm_common("msd_gemm_w4a16_variant", "msd_gemm_w4a16_workspace_bytes", x,
+                        (_ptr(W_fp4), _ptr(W_e8m0)), W_fp4.shape[0], out_dtype, taps, y, ws, prepare,
+                        lead=(int(variant),))
 
 
 def msd_dequant_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws=None, prepare=False):

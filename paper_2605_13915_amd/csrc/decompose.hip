@@ -18,23 +18,24 @@ constexpr int kDecThreads = 256;
 __global__ __launch_bounds__(kDecThreads) void decompose_int8_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int8_t* __restrict__ q1,
     int8_t* __restrict__ q2, int64_t ldq, float* __restrict__ alpha_out, int aligned, int64_t a_step,
-    int a_bk) {
+    int a_bk, float num1, float num2) {
   __shared__ float s_red[kDecThreads / kWave];
   const int64_t m = blockIdx.x;
   if (a_step)  // blocked layout for the asynchronous-fill GEMM: q1 / q2 are the array bases
-    decompose_row_int8_block<kDecThreads>(x + m * ldx, K, q1, q2, alpha_out + m, aligned != 0, s_red, a_step, m,
-                                          a_bk);
+    decompose_row_int8_block<kDecThreads>(x + m * ldx, K, q1, q2, alpha_out + m, aligned != 0, s_red, num1,
+                                          num2, a_step, m, a_bk);
   else
     decompose_row_int8_block<kDecThreads>(x + m * ldx, K, q1 + m * ldq, q2 + m * ldq, alpha_out + m,
-                                          aligned != 0, s_red);
+                                          aligned != 0, s_red, num1, num2);
 }
 
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
-                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, hipStream_t stream) {
+                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, Int8Range rg,
+                          hipStream_t stream) {
   if (M == 0 || K == 0) return MSD_OK;
   const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
   hipLaunchKernelGGL(decompose_int8_kernel, dim3((unsigned)M), dim3(kDecThreads), 0, stream, x, ldx,
-                     (int)K, q1, q2, ldq, alpha, aligned, a_step, a_bk);
+                     (int)K, q1, q2, ldq, alpha, aligned, a_step, a_bk, rg.num1, rg.num2);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
@@ -45,7 +46,7 @@ int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, 
 __global__ __launch_bounds__(256) void decompose_mxfp4_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int64_t M, int KB, uint8_t* __restrict__ abi_q1,
     uint8_t* __restrict__ abi_q2, uint8_t* __restrict__ abi_e8m0, uint32_t* __restrict__ op_q1,
-    uint32_t* __restrict__ op_q2, uint8_t* __restrict__ op_e8m0, int aligned) {
+    uint32_t* __restrict__ op_q2, uint8_t* __restrict__ op_e8m0, int aligned, MxVariant mv) {
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= M * KB) return;
   const int64_t m = gid / KB;
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_kernel(
     for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
   }
   int k1[32], k2[32];
-  const int e = mx_block_codes(w, k1, k2);
+  const int e = mx_block_codes(w, k1, k2, mv.hi_mant, mv.shift);
   const uint8_t ebyte = (uint8_t)(e + 127);
   if (abi_q1) {
     uint32_t a[4], c[4];
@@ -99,13 +100,13 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_kernel(
 
 int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
                            uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
-                           uint8_t* op_e8m0, hipStream_t stream) {
+                           uint8_t* op_e8m0, MxVariant mv, hipStream_t stream) {
   if (M == 0 || K == 0) return MSD_OK;
   const int KB = (int)(K / 32);
   const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
   const int64_t total = M * KB;
   hipLaunchKernelGGL(decompose_mxfp4_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, stream,
-                     x, ldx, M, KB, abi_q1, abi_q2, abi_e8m0, op_q1, op_q2, op_e8m0, aligned);
+                     x, ldx, M, KB, abi_q1, abi_q2, abi_e8m0, op_q1, op_q2, op_e8m0, aligned, mv);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

@@ -59,7 +59,7 @@ __device__ __forceinline__ void chunk_codes(const Chunk16& c, float alpha, float
 
 // Bit-exact quantisation without a division per element.  q = rne(x/alpha) is computed as
 // rne(x * (1/alpha)); the product differs from the correctly rounded quotient by at most
-// 127*2^-22 < 3.1e-5 in absolute terms, so the two can round differently only if the product is
+// 127.49*2^-22 < 3.1e-5 in absolute terms (|x/alpha| <= 127.49 for either pair of range constants), so the two can round differently only if the product is
 // within that distance of a half-integer.  Lanes where it is within 1e-4 recompute with the
 // exact division (about 2 elements in 10^4).  Same for the residual pass.
 __device__ __forceinline__ void int8_codes_fast(float x, float alpha, float ra, float beta, float rb,
@@ -102,7 +102,7 @@ __device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, 
 
 // One workgroup of THREADS threads decomposes one row: xr[0..K) -> q1r, q2r (16-byte aligned),
 // *alpha_out.  s_red: THREADS/64 floats of LDS.  Ends with every thread's stores issued (no
-// trailing barrier).
+// trailing barrier).  num1 / num2: the range constants (alpha = max / num1, beta = alpha / num2).
 // With a_step != 0 the codes go to the blocked layout of the asynchronous-fill GEMM instead
 // (stage depth a_bk = 64 or 128 bytes of K per row): q1r / q2r then point at the array base and
 // 16-byte chunk c of row m lands in stage c / (a_bk/16), block m / (1024/a_bk), at the row's
@@ -112,8 +112,8 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
                                                          int8_t* __restrict__ q1r,
                                                          int8_t* __restrict__ q2r,
                                                          float* __restrict__ alpha_out, bool aligned,
-                                                         float* s_red, int64_t a_step = 0, int64_t m = 0,
-                                                         int a_bk = 64) {
+                                                         float* s_red, float num1, float num2,
+                                                         int64_t a_step = 0, int64_t m = 0, int a_bk = 64) {
   const int nchunks = K / 16;
   const int cpr = a_bk / 16, rpi = 1024 / a_bk;  // chunks per row, rows per 1 KB block
   const int64_t row_off = (m / rpi) * 1024 + (m % rpi) * a_bk;
@@ -139,8 +139,8 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
   mx = s_red[0];
 #pragma unroll
   for (int w = 1; w < THREADS / 64; ++w) mx = fmaxf(mx, s_red[w]);
-  const float alpha = __fdiv_rn(mx, 127.0f);
-  const float beta = __fdiv_rn(alpha, 254.0f);
+  const float alpha = __fdiv_rn(mx, num1);
+  const float beta = __fdiv_rn(alpha, num2);
   const float ra = __fdiv_rn(1.0f, alpha), rb = __fdiv_rn(1.0f, beta);  // unused for an all-zero row
   if (threadIdx.x == 0) *alpha_out = alpha;
   uint4* o1 = reinterpret_cast<uint4*>(q1r);

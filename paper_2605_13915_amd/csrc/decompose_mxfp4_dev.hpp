@@ -5,12 +5,13 @@
 
 namespace msd {
 
-// Exponent e of alpha = 2^e for a block with max-abs mb: smallest e with mb <= 1.859375 * 2^e,
-// read off the fp32 fields (1.859375 has mantissa field 0x6E0000); clamped to [-123, 127].
-__device__ __forceinline__ int mx_alpha_exponent(float mb) {
+// Exponent e of alpha = 2^e for a block with max-abs mb: smallest e with mb <= hi * 2^e, read off
+// the fp32 fields (hi in [1, 2) given by its mantissa field: 1.859375 is 0x6E0000, 1.75 is
+// 0x600000); clamped to [-123, 127].
+__device__ __forceinline__ int mx_alpha_exponent(float mb, uint32_t hi_mant) {
   const uint32_t u = __float_as_uint(mb);
   int e = (int)(u >> 23) - 127;
-  if ((u & 0x7FFFFFu) > 0x6E0000u) e += 1;
+  if ((u & 0x7FFFFFu) > hi_mant) e += 1;
   return min(max(e, -123), 127);
 }
 
@@ -19,22 +20,25 @@ __device__ __forceinline__ float pow2f(int e) {  // e in [-126, 127]
 }
 
 // 32 BF16 values of one block -> integer grid codes k1, k2 (value k/4) and exponent e.
-__device__ __forceinline__ int mx_block_codes(const uint32_t (&w)[16], int (&k1)[32], int (&k2)[32]) {
+// beta = alpha / 2^shift (shift 4 in Alg. 2).
+__device__ __forceinline__ int mx_block_codes(const uint32_t (&w)[16], int (&k1)[32], int (&k2)[32],
+                                              uint32_t hi_mant, int shift) {
   float mb = 0.f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     mb = fmaxf(mb, fabsf(__uint_as_float(w[i] << 16)));
     mb = fmaxf(mb, fabsf(__uint_as_float(w[i] & 0xFFFF0000u)));
   }
-  const int e = mx_alpha_exponent(mb);
+  const int e = mx_alpha_exponent(mb, hi_mant);
   const float up = pow2f(2 - e);    // 4/alpha
   const float down = pow2f(e - 2);  // alpha/4
+  const float up2 = pow2f(shift);   // alpha/beta
 #pragma unroll
   for (int i = 0; i < 32; ++i) {
     const float x = (i & 1) ? __uint_as_float(w[i >> 1] & 0xFFFF0000u) : __uint_as_float(w[i >> 1] << 16);
     const float a = fminf(fmaxf(rintf(x * up), -7.f), 7.f);
     const float r = __fmaf_rn(-a, down, x);  // exact
-    const float b = fminf(fmaxf(rintf(r * up * 16.0f), -7.f), 7.f);
+    const float b = fminf(fmaxf(rintf(r * up * up2), -7.f), 7.f);
     k1[i] = (int)a;
     k2[i] = (int)b;
   }
@@ -44,16 +48,18 @@ __device__ __forceinline__ int mx_block_codes(const uint32_t (&w)[16], int (&k1)
 // Same decomposition, packed on the fly: 32 BF16 values -> the FP6-E2M3 operands of both
 // components (6 dwords each, element i at bits [6i, 6i+6)) and the exponent e.  Keeps no
 // 32-element code arrays alive (the GEMM kernels that decompose in place are register-bound).
-__device__ __forceinline__ int mx_block_pack_fp6(const uint32_t (&w)[16], uint32_t (&p1)[6], uint32_t (&p2)[6]) {
+__device__ __forceinline__ int mx_block_pack_fp6(const uint32_t (&w)[16], uint32_t (&p1)[6], uint32_t (&p2)[6],
+                                                 uint32_t hi_mant, int shift) {
   float mb = 0.f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     mb = fmaxf(mb, fabsf(__uint_as_float(w[i] << 16)));
     mb = fmaxf(mb, fabsf(__uint_as_float(w[i] & 0xFFFF0000u)));
   }
-  const int e = mx_alpha_exponent(mb);
+  const int e = mx_alpha_exponent(mb, hi_mant);
   const float up = pow2f(2 - e);    // 4/alpha
   const float down = pow2f(e - 2);  // alpha/4
+  const float up2 = pow2f(shift);   // alpha/beta
 #pragma unroll
   for (int h = 0; h < 2; ++h) {  // 16 codes -> 96 bits -> 3 dwords per component
     uint64_t lo1 = 0, lo2 = 0;
@@ -64,7 +70,7 @@ __device__ __forceinline__ int mx_block_pack_fp6(const uint32_t (&w)[16], uint32
       const float x = (idx & 1) ? __uint_as_float(w[idx >> 1] & 0xFFFF0000u) : __uint_as_float(w[idx >> 1] << 16);
       const float a = fminf(fmaxf(rintf(x * up), -7.f), 7.f);
       const float r = __fmaf_rn(-a, down, x);  // exact
-      const float b = fminf(fmaxf(rintf(r * up * 16.0f), -7.f), 7.f);
+      const float b = fminf(fmaxf(rintf(r * up * up2), -7.f), 7.f);
       const int ka = (int)a, kb = (int)b;
       const uint64_t c1 = ka < 0 ? (32u | (uint32_t)(-2 * ka)) : (uint32_t)(2 * ka);
       const uint64_t c2 = kb < 0 ? (32u | (uint32_t)(-2 * kb)) : (uint32_t)(2 * kb);

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
         int e;
         if constexpr (EXPORT) {
           int k1[32], k2[32];
-          e = mx_block_codes(w, k1, k2);
+          e = mx_block_codes(w, k1, k2, a.mv.hi_mant, a.mv.shift);
           pack_fp6(k1, p1);
           pack_fp6(k2, p2);
           if (blockIdx.x == 0 && a.abi_q1) {  // observation points only: ABI-format codes
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
             a.abi_e8m0[gb] = (uint8_t)(e + 127);
           }
         } else {
-          e = mx_block_pack_fp6(w, p1, p2);
+          e = mx_block_pack_fp6(w, p1, p2, a.mv.hi_mant, a.mv.shift);
         }
         uint2* d1 = reinterpret_cast<uint2*>(my_q + ((size_t)m * bpw + bb) * 24);
         uint2* d2 = reinterpret_cast<uint2*>(my_q + ((size_t)(M + m) * bpw + bb) * 24);
@@ -221,10 +221,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
             }
           }
           if (STACK) {
-            acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa - 4 * comp, wsc[u2][u]);  // beta = alpha / 16
+            acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa - a.mv.shift * comp, wsc[u2][u]);  // beta = alpha / 2^shift
           } else {
             acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa, wsc[u2][u]);
-            acc[f] = mfma_scaled(a2, wb[u2][u], acc[f], sa - 4, wsc[u2][u]);  // beta = alpha / 16
+            acc[f] = mfma_scaled(a2, wb[u2][u], acc[f], sa - a.mv.shift, wsc[u2][u]);  // beta = alpha / 2^shift
           }
         }
       }
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w4_tiled_kernel(GemmW4Args 
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
           acc[i][j] = mfma32_scaled(f1, fb[j], acc[i][j], sa, sb[j]);
-          acc[i][j] = mfma32_scaled(f2, fb[j], acc[i][j], sa - 4, sb[j]);
+          acc[i][j] = mfma32_scaled(f2, fb[j], acc[i][j], sa - a.mv.shift, sb[j]);
         }
       }
     }

@@ -38,7 +38,8 @@ __device__ __forceinline__ int scale_slot(int r, int b) {  // byte of (row or co
 __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                                                                    int64_t M, int KB2, int64_t Mpad,
                                                                    uint32_t* __restrict__ qop,
-                                                                   uint8_t* __restrict__ sa_t, int aligned) {
+                                                                   uint8_t* __restrict__ sa_t, int aligned,
+                                                                   MxVariant mv) {
   // consecutive threads take consecutive rows of one K step: their 16-byte stores are adjacent
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= M * KB2) return;
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
       for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
     }
     int k1[32], k2[32];
-    const int e = mx_block_codes(w, k1, k2);
+    const int e = mx_block_codes(w, k1, k2, mv.hi_mant, mv.shift);
     pack_fp6(k1, p1[b]);
     pack_fp6(k2, p2[b]);
     eb[b] = e + 127;
@@ -287,14 +288,15 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   //   the activation operands are not: each set is dead when its successor is fetched).
   v8i a0[4], a1[4], b0[4], b1[4];
   int sa0 = 0, sb0 = 0, sa1 = 0, sb1 = 0;
+  const int beta_shift = a.mv.shift * 0x01010101;
   auto step = [&](int s, v8i (&bc)[4], int sac, int sbc, v8i (&bn)[4], int& san, int& sbn) {
     if constexpr (PROBE) {
       if (s > 0) {  // operands of step 0 (a1: component 1 of step 0), no data movement
         mfma_first(a0, b0, sa0, sb0);
         mfma_rest(a0, b0, sa0, sb0, 0, false);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_first(a1, b0, sa0 - 0x04040404, sb0);
-        mfma_rest(a1, b0, sa0 - 0x04040404, sb0, 0, false);
+        mfma_first(a1, b0, sa0 - beta_shift, sb0);
+        mfma_rest(a1, b0, sa0 - beta_shift, sb0, 0, false);
         __builtin_amdgcn_sched_barrier(0);
         return;
       }
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     mfma_rest(a0, bc, sac, sbc, 0, false);
     __builtin_amdgcn_sched_barrier(0);
     if (s + 1 < KT) wait_tile(s + 1, min(KT - 1, s + NS - 2));
-    const int sac2 = sac - 0x04040404;  // beta = alpha / 16: every scale byte minus 4 (bytes are >= 4)
+    const int sac2 = sac - beta_shift;  // beta = alpha / 2^shift: every scale byte minus shift (bytes are >= 4)
     mfma_first(a1, bc, sac2, sbc);
     __builtin_amdgcn_sched_barrier(0);
     if (!PROBE && s + 1 < KT) {
@@ -372,13 +374,13 @@ W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N) {
 
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
-                           hipStream_t stream, bool probe) {
+                           MxVariant mv, hipStream_t stream, bool probe) {
   const W4PrefillLayout l = w4_prefill_layout(M, K, N);
   if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace
   const int KB2 = (int)(K / 64);
   const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
   hipLaunchKernelGGL(decompose_mxfp4_pair_kernel, dim3((unsigned)cdiv(M * KB2, 256)), dim3(256), 0, stream, x, ldx,
-                     M, KB2, (int64_t)l.Mpad, reinterpret_cast<uint32_t*>(ws + l.qop), ws + l.sa_t, aligned);
+                     M, KB2, (int64_t)l.Mpad, reinterpret_cast<uint32_t*>(ws + l.qop), ws + l.sa_t, aligned, mv);
   MSD_LAUNCH_CHECK();
   hipLaunchKernelGGL(transpose_w_scales_kernel, dim3((unsigned)(l.Npad / 64), (unsigned)cdiv(KB2, 64)), dim3(256), 0,
                      stream, We, N, KB2, (int64_t)l.Npad, ws + l.sw_t);
@@ -395,6 +397,7 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
   a.M = M; a.K = K; a.N = N;
   a.Mpad = (int64_t)l.Mpad;
   a.Npad = (int64_t)l.Npad;
+  a.mv = mv;
   constexpr int NS = 4;
   const int tiles_m = (int)cdiv(M, 256), tiles_n = (int)cdiv(N, 256);
   const int total = tiles_m * tiles_n;

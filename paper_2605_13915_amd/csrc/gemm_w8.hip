@@ -161,7 +161,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
         float v = s_red[threadIdx.x * WAVES];
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) v = fmaxf(v, s_red[threadIdx.x * WAVES + w]);
-        s_alpha[threadIdx.x] = __fdiv_rn(v, 127.0f);
+        s_alpha[threadIdx.x] = __fdiv_rn(v, a.rg.num1);
       }
       __syncthreads();
       my_alpha = s_alpha[threadIdx.x % kSelfMaxRows];
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
         const float al = s_alpha[m];
         uint4 o1 = make_uint4(0, 0, 0, 0), o2 = o1;
         if (al > 0.f) {
-          const float be = __fdiv_rn(al, 254.0f);
+          const float be = __fdiv_rn(al, a.rg.num2);
           chunk_codes_fast(load_chunk16(a.x + (int64_t)m * a.ldx + k_lo + cc * 16, al16), al,
                            __fdiv_rn(1.0f, al), be, __fdiv_rn(1.0f, be), o1, o2);
         }
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
     const int64_t n = n0 + c;
     if (n < N) {
       const float alpha = SELF ? my_alpha : a.alpha[m];
-      const float beta = __fdiv_rn(alpha, 254.0f);
+      const float beta = __fdiv_rn(alpha, a.rg.num2);
       store_out(a.y, a.out_bf16, (int64_t)m * a.ldy + n, merge_scales(a.w_scale[n], alpha, beta, a1, a2));
       if (a.acc1) a.acc1[(int64_t)m * N + n] = a1;
       if (a.acc2) a.acc2[(int64_t)m * N + n] = a2;
@@ -387,7 +387,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_mfma32_kernel(GemmW8Args
       const int64_t m = m0 + wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
       if (m >= M) continue;
       const float alpha = a.alpha[m];
-      const float beta = __fdiv_rn(alpha, 254.0f);
+      const float beta = __fdiv_rn(alpha, a.rg.num2);
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
         const int64_t n = n0 + wn * TN + 32 * j + l32;
@@ -696,7 +696,7 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
     const int64_t m = m0 + i;
     const float al = m < M ? a.alpha[m] : 0.f;
     s_ab[i] = al;
-    s_ab[BMH + i] = __fdiv_rn(al, 254.0f);
+    s_ab[BMH + i] = __fdiv_rn(al, a.rg.num2);
   }
   __syncthreads();
   float sw[FN];

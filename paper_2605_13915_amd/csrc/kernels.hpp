@@ -4,13 +4,28 @@
 
 namespace msd {
 
+// ---- variants of the decomposition constants (paper Sec. 3.3)
+// INT8: alpha = max|x| / num1, beta = alpha / num2; (127, 254) is the method as stated, (127.49, 254.98)
+// the "fractional scaling" refinement with the bound M/65015.
+struct Int8Range {
+  float num1 = 127.0f, num2 = 254.0f;
+};
+// MXFP4: alpha = 2^e with e the smallest exponent such that max|block| <= hi * 2^e, hi given by its fp32
+// mantissa field; beta = alpha / 2^shift.  (1.859375, 4) is Alg. 2; the design-evolution table's earlier
+// parameterisations are v1 = (1.75, 3) and v2 = (1.75, 4).
+struct MxVariant {
+  uint32_t hi_mant = 0x6E0000u;  // 1.859375; 1.75 is 0x600000
+  int shift = 4;
+};
+
 // ---- decomposition (decompose.hip)
 // a_step != 0: write the blocked layout of GemmW8Args (stage depth a_bk) instead of row-major [M][ldq]
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
-                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, hipStream_t stream);
+                          int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, Int8Range rg,
+                          hipStream_t stream);
 int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
                            uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
-                           uint8_t* op_e8m0, hipStream_t stream);
+                           uint8_t* op_e8m0, MxVariant mv, hipStream_t stream);
 
 // ---- W8A16 dual INT8 GEMM + dual-scale epilogue (gemm_w8.hip)
 struct GemmW8Args {
@@ -38,6 +53,7 @@ struct GemmW8Args {
   // rounded up to 128
   int64_t a_step;
   int a_bk;
+  Int8Range rg;  // range constants of the decomposition and of beta in the epilogue
 };
 // stage depth of the blocked layout launch_gemm_w8 wants for this shape (0: row-major)
 int gemm_w8_blocked_bk(int64_t M, int64_t K, int64_t N);
@@ -67,6 +83,7 @@ struct GemmW4Args {
   uint8_t* abi_q2;
   uint8_t* abi_e8m0;
   int scales_aligned;  // W_e8m0 is 16-byte aligned (16-byte scale loads allowed)
+  MxVariant mv;
 };
 bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
@@ -82,6 +99,7 @@ struct GemmW4PrefillArgs {
   int out_bf16;
   int64_t ldy;
   int64_t M, K, N, Mpad, Npad;
+  MxVariant mv;
 };
 struct W4PrefillLayout {
   size_t qop, sa_t, sw_t, total, Mpad, Npad;
@@ -93,7 +111,7 @@ W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N);
 // barriers or LDS traffic afterwards); y is then meaningless
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
-                           hipStream_t stream, bool probe = false);
+                           MxVariant mv, hipStream_t stream, bool probe = false);
 
 // ---- attention (attn.hip)
 struct AttnArgs {

@@ -55,6 +55,22 @@ static W4Layout w4_layout(int64_t M, int64_t K, int64_t N) {
 
 using namespace msd;
 
+// decomposition constants of a variant; false when the variant does not belong to the format
+static bool int8_range_of(int variant, Int8Range& rg) {
+  if (variant == MSD_VARIANT_MAIN) return true;
+  if (variant != MSD_VARIANT_INT8_FRACTIONAL) return false;
+  rg.num1 = 127.49f;
+  rg.num2 = 254.98f;
+  return true;
+}
+static bool mx_variant_of(int variant, MxVariant& mv) {
+  if (variant == MSD_VARIANT_MAIN) return true;
+  if (variant != MSD_VARIANT_MXFP4_V1 && variant != MSD_VARIANT_MXFP4_V2) return false;
+  mv.hi_mant = 0x600000u;  // 1.75
+  mv.shift = variant == MSD_VARIANT_MXFP4_V1 ? 3 : 4;
+  return true;
+}
+
 extern "C" {
 
 int msd_last_hip_error(void) { return g_last_hip_error; }
@@ -62,7 +78,15 @@ const char* msd_version(void) { return "0.1"; }
 
 int msd_decompose(int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, void* q1, void* q2,
                   void* scale, void* stream) {
+  return msd_decompose_variant(MSD_VARIANT_MAIN, fmt, x_bf16, M, K, ldx, q1, q2, scale, stream);
+}
+
+int msd_decompose_variant(int variant, int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, void* q1,
+                          void* q2, void* scale, void* stream) {
   if (fmt != MSD_INT8 && fmt != MSD_MXFP4) return MSD_ERR_INVALID_ARG;
+  Int8Range rg;
+  MxVariant mv;
+  if (!(fmt == MSD_INT8 ? int8_range_of(variant, rg) : mx_variant_of(variant, mv))) return MSD_ERR_INVALID_ARG;
   if (M < 0 || K < 0 || ldx < K) return MSD_ERR_SHAPE;
   if (M == 0 || K == 0) return MSD_OK;
   if (!x_bf16 || !q1 || !q2 || !scale) return MSD_ERR_INVALID_ARG;
@@ -72,11 +96,11 @@ int msd_decompose(int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx
     if (K % 16 != 0) return MSD_ERR_SHAPE;
     if (!aligned_to(scale, 4)) return MSD_ERR_INVALID_ARG;
     return launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)q1, (int8_t*)q2, K,
-                                 (float*)scale, 0, 64, s);
+                                 (float*)scale, 0, 64, rg, s);
   }
   if (K % 32 != 0) return MSD_ERR_SHAPE;
   return launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, (uint8_t*)q1, (uint8_t*)q2,
-                                (uint8_t*)scale, nullptr, nullptr, nullptr, s);
+                                (uint8_t*)scale, nullptr, nullptr, nullptr, mv, s);
 }
 
 size_t msd_gemm_w8a16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
@@ -87,6 +111,15 @@ size_t msd_gemm_w8a16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
 int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
                    const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
                    size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  return msd_gemm_w8a16_variant(MSD_VARIANT_MAIN, x_bf16, M, K, ldx, W, w_scale, N, y, out_dtype, ldy, workspace,
+                                workspace_bytes, taps, stream);
+}
+
+int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                           const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                           size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  Int8Range rg;
+  if (!int8_range_of(variant, rg)) return MSD_ERR_INVALID_ARG;
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
   if (K % 16 != 0 || K > 131072) return MSD_ERR_SHAPE;
@@ -112,6 +145,7 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   a.M = M; a.K = K; a.N = N;
   a.acc1 = taps ? taps->acc1 : nullptr;
   a.acc2 = taps ? taps->acc2 : nullptr;
+  a.rg = rg;
   if (gemm_w8_is_fused(M, K, N)) {
     // one launch: the GEMM kernel decomposes the rows itself, under its own weight loads
     a.x = (const uint16_t*)x_bf16;
@@ -124,7 +158,7 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
     a.a_bk = code_taps ? 0 : gemm_w8_blocked_bk(M, K, N);
     if (a.a_bk) a.a_step = (int64_t)align_up((size_t)M, 128) * a.a_bk;  // Mpad rows of a_bk bytes per stage
     int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
-                                   (float*)a.alpha, a.a_step, a.a_bk ? a.a_bk : 64, s);
+                                   (float*)a.alpha, a.a_step, a.a_bk ? a.a_bk : 64, rg, s);
     if (rc) return rc;
   } else {
     int rc = fill_u32((uint32_t*)a.alpha, M, 0u, s);
@@ -149,6 +183,16 @@ size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
 int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const uint8_t* W_fp4,
                    const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
                    size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  return msd_gemm_w4a16_variant(MSD_VARIANT_MAIN, x_bf16, M, K, ldx, W_fp4, W_e8m0, N, y, out_dtype, ldy,
+                                workspace, workspace_bytes, taps, stream);
+}
+
+int msd_gemm_w4a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
+                           const uint8_t* W_fp4, const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype,
+                           int64_t ldy, void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                           void* stream) {
+  MxVariant mv;
+  if (!mx_variant_of(variant, mv)) return MSD_ERR_INVALID_ARG;
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
   if (K % 32 != 0 || K > (1 << 20)) return MSD_ERR_SHAPE;
@@ -172,6 +216,7 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
   a.out_bf16 = out_dtype == MSD_BF16;
   a.ldy = ldy;
   a.M = M; a.K = K; a.N = N;
+  a.mv = mv;
   if (K > 0) {
     uint8_t* t1 = taps ? (uint8_t*)taps->q1 : nullptr;
     uint8_t* t2 = taps ? (uint8_t*)taps->q2 : nullptr;
@@ -182,7 +227,7 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
       // many rows, no observation points: decomposition in the GEMM's own operand order,
       // weight scales transposed once, GEMM on the asynchronous-fill pipeline
       return launch_gemm_w4_prefill((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
-                                    (uint8_t*)ws, s);
+                                    (uint8_t*)ws, mv, s);
     }
     if (gemm_w4_is_fused(M, K, N)) {
       // one launch: the GEMM kernel decomposes the blocks of its own K range itself
@@ -192,7 +237,7 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
       a.abi_q1 = t1; a.abi_q2 = t2; a.abi_e8m0 = te;
     } else {
       int rc = launch_decompose_mxfp4((const uint16_t*)x_bf16, M, K, ldx, t1, t2, te, (uint32_t*)a.q1,
-                                      (uint32_t*)a.q2, (uint8_t*)a.e8m0, s);
+                                      (uint32_t*)a.q2, (uint8_t*)a.e8m0, mv, s);
       if (rc) return rc;
     }
   }
@@ -287,7 +332,7 @@ int msd_probe_mfma_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, 
   a.a_bk = 64;
   a.a_step = (int64_t)align_up((size_t)M, 128) * 64;
   int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
-                                 (float*)a.alpha, a.a_step, 64, s);
+                                 (float*)a.alpha, a.a_step, 64, a.rg, s);
   if (rc) return rc;
   return launch_gemm_w8_mfma_probe(a, s);
 }
@@ -303,7 +348,7 @@ int msd_probe_mfma_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, 
   if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;
   if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
   return launch_gemm_w4_prefill((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, 0, ldy, M, K, N, (uint8_t*)workspace,
-                                (hipStream_t)stream, true);
+                                MxVariant{}, (hipStream_t)stream, true);
 }
 
 size_t msd_dequant_gemm_workspace_bytes(int64_t M, int64_t K, int64_t N) {

@@ -1,0 +1,77 @@
+"""GPU parity over seeded random shapes that straddle every kernel-selection boundary of the two GEMMs.
+
+Same bars as the per-shape files: codes, scales and int32 partials bit-exact where the observation
+points are requested, fp32 output within 1e-6 (W8) / 2e-6 (W4) relative L2 of the oracle, far inside
+the stated 1e-3."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13915_amd import synth
+from gpu_util import bf16_to_dev, to_dev, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+ROWS = [1, 2, 3, 5, 8, 9, 16, 17, 24, 32, 33, 40, 64, 65, 100, 128, 129, 200, 256, 257, 300]
+COLS = [1, 7, 16, 50, 64, 100, 255, 256, 257, 512, 1000, 2049, 4096, 8200, 8300, 9000]
+K_W8 = [16, 48, 64, 128, 192, 256, 320, 512, 1024, 1040, 2048, 2112]
+K_W4 = [32, 64, 96, 128, 256, 512, 544, 1024, 2048]
+
+
+@pytest.fixture(scope="module")
+def msd():
+    from paper_2605_13915_amd import binding
+    binding.lib()
+    return binding
+
+
+def _cases(seed, n, ks, budget):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M, N, K = int(rng.choice(ROWS)), int(rng.choice(COLS)), int(rng.choice(ks))
+        if M * K * N > budget:           # keep the oracle's share of the run to seconds
+            N = max(1, int(budget // (M * K)))
+        out.append((M, K, N, bool(rng.integers(2)), bool(rng.integers(2)), int(rng.integers(1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N,taps,outl,seed", _cases(11, 30, K_W8, 4e8))
+def test_w8a16_random_shape(msd, M, K, N, taps, outl, seed):
+    x = synth.activations(seed, M, K, outliers=outl)
+    if seed % 4 == 0:
+        x[seed % M] = 0                  # an all-zero row now and then
+    W, s = synth.int8_weights(seed + 1, N, K)
+    xd, Wd, sd = bf16_to_dev(x), to_dev(W), to_dev(s)
+    if taps:
+        y_ref, t = oracle.gemm_w8a16(x, W, s, taps=True)
+        y, g = msd.msd_gemm_w8a16(xd, Wd, sd, taps=True)
+        torch.cuda.synchronize()
+        for k in ("q1", "q2", "acc1", "acc2"):
+            assert np.array_equal(g[k].cpu().numpy(), t[k]), k
+        assert np.array_equal(g["scale"].cpu().numpy().view(np.uint32), t["alpha"].view(np.uint32))
+    else:
+        y_ref = oracle.gemm_w8a16(x, W, s)
+        y = msd.msd_gemm_w8a16(xd, Wd, sd)
+        torch.cuda.synchronize()
+    assert rel_l2(y.cpu().numpy(), y_ref) <= 1e-6
+
+
+@pytest.mark.parametrize("M,K,N,taps,outl,seed", _cases(12, 30, K_W4, 2e8))
+def test_w4a16_random_shape(msd, M, K, N, taps, outl, seed):
+    x = synth.activations(seed, M, K, outliers=outl, scale=float(10.0 ** (seed % 6 - 3)))
+    codes, exps = synth.mxfp4_weights(seed + 1, N, K)
+    xd, cd, ed = bf16_to_dev(x), to_dev(codes), to_dev(exps)
+    if taps:
+        y_ref, t = oracle.gemm_w4a16(x, codes, exps, taps=True)
+        y, g = msd.msd_gemm_w4a16(xd, cd, ed, taps=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(g["q1"].cpu().numpy(), t["q1"])
+        assert np.array_equal(g["q2"].cpu().numpy(), t["q2"])
+        assert np.array_equal(g["scale"].cpu().numpy(), t["e8m0"])
+    else:
+        y_ref = oracle.gemm_w4a16(x, codes, exps)
+        y = msd.msd_gemm_w4a16(xd, cd, ed)
+        torch.cuda.synchronize()
+    assert rel_l2(y.cpu().numpy(), y_ref) <= 2e-6

@@ -179,6 +179,33 @@ def test_gemm_output_bound_against_fp64_truth():
     assert np.all(np.abs(y - truth) <= bound * (1 + 1e-4) + np.abs(truth) * 2.0 ** -23)
 
 
+def test_gemm_fractional_variant_uses_its_own_constants_throughout():
+    # Sec. 3.3: the variant changes the decomposition AND the beta of the merge.  Codes and partial
+    # products must be those of the fractional decomposition, the output the exact rational merge with
+    # beta = alpha / 254.98f, and the output-level bound tightens to M/65015.
+    x = make_rows(27, 5, 256)
+    W, s = synth.int8_weights(27, 24, 256)
+    y, t = oracle.gemm_w8a16(x, W, s, fractional=True, taps=True)
+    q1, q2, al, be = oracle.decompose_int8(x, fractional=True)
+    assert np.array_equal(t["q1"], q1) and np.array_equal(t["q2"], q2)
+    assert np.array_equal(t["alpha"], al) and np.array_equal(t["beta"], be)
+    assert np.array_equal(be, (al / np.float32(254.98)).astype(np.float32))
+    assert np.array_equal(t["acc1"].astype(np.int64), q1.astype(np.int64) @ W.astype(np.int64).T)
+    assert np.array_equal(t["acc2"].astype(np.int64), q2.astype(np.int64) @ W.astype(np.int64).T)
+    for m in range(5):
+        for n in range(0, 24, 5):
+            ex = Fraction(float(s[n])) * (Fraction(float(al[m])) * int(t["acc1"][m, n]) +
+                                          Fraction(float(be[m])) * int(t["acc2"][m, n]))
+            assert abs(Fraction(float(y[m, n])) - ex) <= abs(ex) * Fraction(1, 2 ** 22) + Fraction(1, 10 ** 30)
+    xf = f32(x)
+    truth = oracle.truth_gemm_w8(x, W, s)
+    M = np.abs(xf).max(axis=1)
+    bound = s.astype(np.float64)[None, :] * np.abs(W.astype(np.float64)).sum(axis=1)[None, :] * M[:, None] / 65015.0
+    assert np.all(np.abs(y - truth) <= bound * (1 + 1e-4) + np.abs(truth) * 2.0 ** -23)
+    y_main = oracle.gemm_w8a16(x, W, s)
+    assert not np.array_equal(y, y_main)          # a different quantiser, not a relabelling
+
+
 def test_gemv_m1_identity_weights():
     # M = 1 with W = 127 * I and s_W = 1/127 must give back alpha*q1 + beta*q2 per element.
     K = 64

@@ -182,10 +182,13 @@ def _e2m1(n):
     return -mag if n & 8 else mag
 
 
-def test_w4_gemm_exact_rational_tiny():
+@pytest.mark.parametrize("variant,shift", [(3, 4), (1, 3), (2, 4)])
+def test_w4_gemm_exact_rational_tiny(variant, shift):
     x = synth.activations(41, 2, 64, outliers=False)
     codes, exps = synth.mxfp4_weights(41, 3, 64)
-    y, t = oracle.gemm_w4a16(x, codes, exps, taps=True)
+    y, t = oracle.gemm_w4a16(x, codes, exps, variant=variant, taps=True)
+    d1, d2, de = oracle.decompose_mxfp4(x, variant=variant)      # the GEMM decomposes as the variant says
+    assert np.array_equal(d1, t["q1"]) and np.array_equal(d2, t["q2"]) and np.array_equal(de, t["e8m0"])
     k1 = unpack_quarters(t["q1"])
     k2 = unpack_quarters(t["q2"])
     for m in range(2):
@@ -195,10 +198,8 @@ def test_w4_gemm_exact_rational_tiny():
                 byte = int(codes[n, k // 2])
                 w = Fraction(_e2m1((byte >> 4) if k & 1 else (byte & 15))) * Fraction(2) ** (int(exps[n, k // 32]) - 127)
                 a = Fraction(2) ** (int(t["e8m0"][m, k // 32]) - 127)
-                tot += w * (a * Fraction(int(k1[m, k]), 4) + a / 16 * Fraction(int(k2[m, k]), 4))
+                tot += w * (a * Fraction(int(k1[m, k]), 4) + a / 2 ** shift * Fraction(int(k2[m, k]), 4))
             assert abs(Fraction(float(y[m, n])) - tot) <= abs(tot) * Fraction(1, 2 ** 23)
-    q1, q2, e = oracle.decompose_mxfp4(x)
-    assert np.array_equal(q1, t["q1"]) and np.array_equal(q2, t["q2"]) and np.array_equal(e, t["e8m0"])
 
 
 def test_w4_truth_matches_numpy_and_output_bound():
