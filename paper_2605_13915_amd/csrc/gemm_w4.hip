@@ -257,7 +257,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
   }
 }
 
-bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t) { return M <= 2 && K > 0 && K <= 32768; }
+bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t) { return M <= 1 && K > 0 && K <= 32768; }
 
 template <int WAVES, int U, int RT, bool SELF, bool STACK = false>
 static int launch_w4(const GemmW4Args& a, hipStream_t stream) {

@@ -40,45 +40,37 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
                                                                    uint32_t* __restrict__ qop,
                                                                    uint8_t* __restrict__ sa_t, int aligned,
                                                                    MxVariant mv) {
-  // consecutive threads take consecutive rows of one K step: their 16-byte stores are adjacent
+  // one thread per (K step, block of the step, row), rows fastest: the 16-byte stores of
+  // consecutive threads are adjacent
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= M * KB2) return;
-  const int s = (int)(gid / M);
+  if (gid >= 2 * M * KB2) return;
   const int64_t m = gid % M;
-  uint32_t p1[2][6], p2[2][6];
-  int eb[2];
+  const int b = (int)((gid / M) & 1);
+  const int s = (int)(gid / (2 * M));
+  const uint16_t* xb = x + m * ldx + ((int64_t)2 * s + b) * 32;
+  uint32_t w[16];
+  if (aligned) {
+    const uint4* q = reinterpret_cast<const uint4*>(xb);
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const uint16_t* xb = x + m * ldx + ((int64_t)2 * s + b) * 32;
-    uint32_t w[16];
-    if (aligned) {
-      const uint4* q = reinterpret_cast<const uint4*>(xb);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const uint4 v = q[i];
-        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
+    for (int i = 0; i < 4; ++i) {
+      const uint4 v = q[i];
+      w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
     }
-    int k1[32], k2[32];
-    const int e = mx_block_codes(w, k1, k2, mv.hi_mant, mv.shift);
-    pack_fp6(k1, p1[b]);
-    pack_fp6(k2, p2[b]);
-    eb[b] = e + 127;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
   }
-  // group of 32 rows: [6 chunks][32 rows][4 dwords]
-  uint4* d = reinterpret_cast<uint4*>(qop) + (((int64_t)s * (Mpad / 32) + m / 32) * 6) * 32 + (m % 32);
-  d[0 * 32] = make_uint4(p1[0][0], p1[0][1], p1[0][2], p1[0][3]);
-  d[1 * 32] = make_uint4(p1[1][0], p1[1][1], p1[1][2], p1[1][3]);
-  d[2 * 32] = make_uint4(p1[0][4], p1[0][5], p1[1][4], p1[1][5]);
-  d[3 * 32] = make_uint4(p2[0][0], p2[0][1], p2[0][2], p2[0][3]);
-  d[4 * 32] = make_uint4(p2[1][0], p2[1][1], p2[1][2], p2[1][3]);
-  d[5 * 32] = make_uint4(p2[0][4], p2[0][5], p2[1][4], p2[1][5]);
-  uint8_t* sc = sa_t + ((int64_t)s * (Mpad / 256) + m / 256) * 512;
-  sc[scale_slot((int)(m % 256), 0)] = (uint8_t)eb[0];
-  sc[scale_slot((int)(m % 256), 1)] = (uint8_t)eb[1];
+  uint32_t p1[6], p2[6];
+  const int e = mx_block_pack_fp6(w, p1, p2, mv.hi_mant, mv.shift);
+  // group of 32 rows: [6 chunks][32 rows][16 B]; this block's dwords 0..3 fill chunk 3c + b, its
+  // dwords 4, 5 the half b of chunk 3c + 2
+  uint8_t* d = reinterpret_cast<uint8_t*>(qop) + ((((int64_t)s * (Mpad / 32) + m / 32) * 6) * 32 + (m % 32)) * 16;
+  *reinterpret_cast<uint4*>(d + (0 + b) * 512) = make_uint4(p1[0], p1[1], p1[2], p1[3]);
+  *reinterpret_cast<uint2*>(d + 2 * 512 + b * 8) = make_uint2(p1[4], p1[5]);
+  *reinterpret_cast<uint4*>(d + (3 + b) * 512) = make_uint4(p2[0], p2[1], p2[2], p2[3]);
+  *reinterpret_cast<uint2*>(d + 5 * 512 + b * 8) = make_uint2(p2[4], p2[5]);
+  uint8_t* sc = sa_t + ((int64_t)s * max(Mpad / 256, (int64_t)1) + m / 256) * 512;
+  sc[scale_slot((int)(m % 256), b)] = (uint8_t)(e + 127);
 }
 
 // ------------------------------------------------------------------ (2) weight scale bytes, K-step-major
@@ -372,16 +364,23 @@ W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N) {
   return l;
 }
 
+int launch_decompose_mxfp4_pair(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, int64_t Mpad, uint8_t* qop,
+                                uint8_t* sa_t, MxVariant mv, hipStream_t stream) {
+  const int KB2 = (int)(K / 64);
+  const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(decompose_mxfp4_pair_kernel, dim3((unsigned)cdiv(2 * M * KB2, 256)), dim3(256), 0, stream, x, ldx,
+                     M, KB2, Mpad, reinterpret_cast<uint32_t*>(qop), sa_t, aligned, mv);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
                            MxVariant mv, hipStream_t stream, bool probe) {
   const W4PrefillLayout l = w4_prefill_layout(M, K, N);
   if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace
   const int KB2 = (int)(K / 64);
-  const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
-  hipLaunchKernelGGL(decompose_mxfp4_pair_kernel, dim3((unsigned)cdiv(M * KB2, 256)), dim3(256), 0, stream, x, ldx,
-                     M, KB2, (int64_t)l.Mpad, reinterpret_cast<uint32_t*>(ws + l.qop), ws + l.sa_t, aligned, mv);
-  MSD_LAUNCH_CHECK();
+  if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, (int64_t)l.Mpad, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
   hipLaunchKernelGGL(transpose_w_scales_kernel, dim3((unsigned)(l.Npad / 64), (unsigned)cdiv(KB2, 64)), dim3(256), 0,
                      stream, We, N, KB2, (int64_t)l.Npad, ws + l.sw_t);
   MSD_LAUNCH_CHECK();

@@ -64,7 +64,10 @@ def test_gemm_w4a16_parity(msd, M, K, N):
 
 
 @pytest.mark.parametrize("M,K,N", [(256, 512, 256), (300, 2048, 600), (40, 192, 70), (700, 64, 1000), (1, 8192, 512),
-                                   (33, 4096, 300)])
+                                   (33, 4096, 300),
+                                   # 9..32 rows with K a multiple of 512: weights straight to the matrix operand,
+                                   # activation operands through LDS (one, two, three and many K batches)
+                                   (32, 512, 128), (9, 1024, 300), (17, 1536, 1000), (32, 8192, 700), (24, 2048, 8300)])
 def test_gemm_w4a16_product_path_without_taps(msd, M, K, N):
     """The path a caller without observation points takes; with more than 32 rows and K a multiple of 64
     that is the many-row pipeline (own operand format, transposed scale bytes, 256 x 256 tiles).
@@ -87,7 +90,7 @@ def test_gemm_w4a16_product_path_without_taps(msd, M, K, N):
     assert rel_l2(yb.float().cpu().numpy(), y_ref) <= 1e-2
 
 
-@pytest.mark.parametrize("M,K,N", [(2, 1024, 256), (8, 512, 300), (100, 256, 300)])
+@pytest.mark.parametrize("M,K,N", [(2, 1024, 256), (8, 512, 300), (100, 256, 300), (20, 1024, 300)])
 def test_gemm_w4a16_strided_operands(msd, M, K, N):
     """ldx > K and ldy > N; pad columns of y stay untouched."""
     seed = synth.seed_for(3, M * 19 + N)
