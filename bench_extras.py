@@ -166,6 +166,18 @@ def leg_attn(msd, synth, time_calls, dev):
                          device=dev)
         f = lambda i: msd.msd_attn_decode_int8kv(q, *sets[i % n], msd.MSD_PER_TOKEN, out=o, ws=ws, prepare=True)
         us = time_calls(f, 4 * n)
+        # the comparison kernel (K, V lifted to BF16 in registers) and the paper's per-channel scale mode
+        fc = lambda i: msd.msd_dequant_attn_decode_int8kv(q, *sets[i % n], msd.MSD_PER_TOKEN, out=o, ws=ws,
+                                                          prepare=True)
+        us_cmp = time_calls(fc, 4 * n)
+        kc = torch.rand((Hkv, d), device=dev) * 0.02 + 0.02
+        vc = torch.rand((Hkv, d), device=dev) * 0.02 + 0.02
+        fch = lambda i: msd.msd_attn_decode_int8kv(q, sets[i % n][0], sets[i % n][1], kc, vc, msd.MSD_PER_CHANNEL,
+                                                   out=o, ws=ws, prepare=True)
+        us_ch = time_calls(fch, 4 * n)
+        fcc = lambda i: msd.msd_dequant_attn_decode_int8kv(q, sets[i % n][0], sets[i % n][1], kc, vc,
+                                                           msd.MSD_PER_CHANNEL, out=o, ws=ws, prepare=True)
+        us_ch_cmp = time_calls(fcc, 4 * n)
         b = kvbytes + 8 * B * Hkv * L + 2 * B * Hq * d + 4 * B * Hq * d
         # bare read of the same K and V bytes (one launch each), same cold-cache protocol
         class _Both:
@@ -176,7 +188,11 @@ def leg_attn(msd, synth, time_calls, dev):
                                               msd.msd_stream_read(sets[i % n][1].view(-1, 4096), prepare=True)]), 4 * n)
         out.append({"B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "L": L, "us": round(us, 1),
                     "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM, 4),
-                    "bare_kv_read_us": round(bare_us, 1)})
+                    "bare_kv_read_us": round(bare_us, 1), "dequant_us": round(us_cmp, 1),
+                    "speedup_vs_dequant": round(us_cmp / us, 3),
+                    "per_channel": {"us": round(us_ch, 1), "dequant_us": round(us_ch_cmp, 1),
+                                    "GBps": round((kvbytes + 6 * B * Hq * d) / us_ch / 1e3, 1),
+                                    "speedup_vs_dequant": round(us_ch_cmp / us_ch, 3)}})
         del sets
         torch.cuda.empty_cache()
     return out

@@ -175,6 +175,21 @@ int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
 size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
 
 /*
+ * Comparison kernel for msd_attn_decode_int8kv: the conventional path of paper Sec. 4.1 (K and V
+ * lifted from INT8 to BF16 before Q K^T and P V), as one fused kernel.  Same arguments, layouts,
+ * workspace size (msd_attn_decode_int8kv_workspace_bytes) and errors; taps are ignored.  K and V
+ * bytes become BF16 exactly, Q K^T and P V run on BF16 matrix instructions with fp32
+ * accumulation, P (times s_V[t] in per-token mode) is rounded to BF16.  Per-token s_K[t]
+ * multiplies the score column in fp32; per-channel s_K is folded into Q (rounded to BF16), s_V
+ * multiplies the output.
+ */
+int msd_dequant_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
+                                   const float* k_scale, const float* v_scale, int scale_mode,
+                                   int B, int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L,
+                                   void* out, int out_dtype, void* workspace, size_t workspace_bytes,
+                                   const msd_debug_taps* taps, void* stream);
+
+/*
  * Comparison kernels (the conventional path the paper argues against, Sec. 3.1 first
  * equation): weights are lifted to BF16 inside the kernel (bf16(s_W*W) for INT8, exact for
  * MXFP4) and multiplied on BF16 matrix instructions with fp32 accumulation.  Same

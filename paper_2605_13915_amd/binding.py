@@ -64,13 +64,14 @@ def lib():
             f.restype = sz
         L.msd_attn_decode_int8kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, i64, vp, ci, vp, sz,
                                              vp, vp]
+        L.msd_dequant_attn_decode_int8kv.argtypes = L.msd_attn_decode_int8kv.argtypes
         L.msd_attn_decode_int8kv_workspace_bytes.argtypes = [ci, ci, ci, ci, i64]
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
                      "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
-                     "msd_gemm_w4a16_variant"):
+                     "msd_gemm_w4a16_variant", "msd_dequant_attn_decode_int8kv"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -261,7 +262,7 @@ def msd_stream_read(t, prepare=False):
 
 
 def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,
-                           taps=False, out=None, ws=None, prepare=False):
+                           taps=False, out=None, ws=None, prepare=False, _fn="msd_attn_decode_int8kv"):
     _dev(q, torch.bfloat16, "q"); _dev(K, torch.int8, "K"); _dev(V, torch.int8, "V")
     _dev(k_scale, torch.float32, "k_scale"); _dev(v_scale, torch.float32, "v_scale")
     B, Hq, d = q.shape
@@ -287,8 +288,14 @@ def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, o
             Lmax, _ptr(out), _out_code(out.dtype), _ptr(ws), ws.numel(),
             C.byref(tp) if tp is not None else None, _stream())
     if prepare:
-        return Prepared(L.msd_attn_decode_int8kv, args, (q, K, V, k_scale, v_scale, kv_len, out, ws, keep, tp),
-                        "msd_attn_decode_int8kv", out)
-    rc = L.msd_attn_decode_int8kv(*args)
-    _check(rc, "msd_attn_decode_int8kv")
+        return Prepared(getattr(L, _fn), args, (q, K, V, k_scale, v_scale, kv_len, out, ws, keep, tp), _fn, out)
+    rc = getattr(L, _fn)(*args)
+    _check(rc, _fn)
     return (out, keep) if taps else out
+
+
+def msd_dequant_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,
+                                   out=None, ws=None, prepare=False):
+    """Comparison kernel: K and V lifted to BF16 in registers, BF16 matrix instructions."""
+    return msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len, out_dtype, False, out, ws, prepare,
+                                  _fn="msd_dequant_attn_decode_int8kv")

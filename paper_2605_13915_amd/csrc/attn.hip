@@ -19,52 +19,9 @@
 // long as both operands agree; for P.V the k slot (kg, 4*jq+tt) stands for token
 // 16*tt + 4*kg + jq of the tile, which lets P travel as one packed dword per lane and lets V
 // be brought into "token-contiguous" order by 4x4 byte transposes (v_perm_b32) in registers.
-#include "kernels.hpp"
+#include "attn_common.hpp"
 
 namespace msd {
-
-struct AttnParams {
-  const uint16_t* q;
-  const int8_t* K;
-  const int8_t* V;
-  const float* k_scale;
-  const float* v_scale;
-  const int32_t* kv_len;
-  int B, Hq, Hkv, G;
-  int64_t L;
-  int nsplit;
-  int64_t tokens_per_split;
-  float* part_o;  // [B*Hkv][nsplit][G][128]
-  float* part_m;  // [B*Hkv][nsplit][G]
-  float* part_l;
-  void* out;
-  int out_bf16;
-  int8_t* tap_q1;
-  int8_t* tap_q2;
-  float* tap_alpha;
-  int32_t* tap_s1;
-  int32_t* tap_s2;
-};
-
-constexpr int kD = 128;
-constexpr int kTile = 64;
-constexpr int kAttnWaves = 4;
-constexpr float kLog2e = 1.4426950408889634f;
-
-__device__ __forceinline__ v4i mfma_s8(v4i a, v4i b, v4i c) {
-  return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ float row16_max(float v) {  // over the 16 lanes sharing lane/16
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
-}
-__device__ __forceinline__ float row16_sum(float v) {
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
 
 // 4x4 byte transpose: in[t] = 4 channel bytes of token t; out[c] = 4 token bytes of channel c
 __device__ __forceinline__ void transpose4x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d,
@@ -377,32 +334,20 @@ __global__ __launch_bounds__(kD) void attn_combine_kernel(AttnParams p, int per_
     reinterpret_cast<float*>(p.out)[(int64_t)row * kD + c] = v;
 }
 
-static int plan_nsplit(int B, int Hkv, int64_t L) {
-  const int64_t pairs = (int64_t)B * Hkv;
-  int64_t ns = cdiv(1024, pairs);
-  int64_t max_by_len = L / (kAttnWaves * kTile * 2);  // >= 2 rounds of 4 waves per split
-  if (max_by_len < 1) max_by_len = 1;
-  if (ns > max_by_len) ns = max_by_len;
-  if (ns > 64) ns = 64;
-  if (ns < 1) ns = 1;
-  return (int)ns;
-}
-
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L) {
   (void)d;
-  const int ns = plan_nsplit(B, Hkv, L);
+  const int ns = attn_plan_nsplit(B, Hkv, L);
   const size_t rows = (size_t)B * Hq * ns;
   return align_up(rows * kD * 4, 256) + 2 * align_up(rows * 4, 256);
 }
 
-int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
-  AttnParams p{};
+void attn_fill_params(const AttnArgs& a, AttnParams& p) {
   p.q = a.q; p.K = a.K; p.V = a.V;
   p.k_scale = a.k_scale; p.v_scale = a.v_scale;
   p.kv_len = a.kv_len;
   p.B = a.B; p.Hq = a.Hq; p.Hkv = a.Hkv; p.G = a.Hq / a.Hkv;
   p.L = a.L;
-  p.nsplit = plan_nsplit(a.B, a.Hkv, a.L);
+  p.nsplit = attn_plan_nsplit(a.B, a.Hkv, a.L);
   int64_t tps = cdiv(a.L > 0 ? a.L : 1, p.nsplit);
   tps = cdiv(tps, kAttnWaves * kTile) * (kAttnWaves * kTile);
   p.tokens_per_split = tps;
@@ -413,6 +358,17 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
   p.part_l = (float*)(ws + align_up(rows * kD * 4, 256) + align_up(rows * 4, 256));
   p.out = a.out;
   p.out_bf16 = a.out_bf16;
+}
+
+int launch_attn_combine(const AttnParams& p, int per_channel, hipStream_t stream) {
+  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(p.B * p.Hq)), dim3(kD), 0, stream, p, per_channel);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
+  AttnParams p{};
+  attn_fill_params(a, p);
   if (a.taps) {
     p.tap_q1 = (int8_t*)a.taps->q1;
     p.tap_q2 = (int8_t*)a.taps->q2;
@@ -436,11 +392,7 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL((attn_decode_kernel<2, false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
   }
   MSD_LAUNCH_CHECK();
-  if (p.nsplit > 1) {
-    hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(a.B * a.Hq)), dim3(kD), 0, stream, p,
-                       per_token ? 0 : 1);
-    MSD_LAUNCH_CHECK();
-  }
+  if (p.nsplit > 1) return launch_attn_combine(p, per_token ? 0 : 1, stream);
   return MSD_OK;
 }
 

@@ -1,0 +1,70 @@
+// Shared pieces of the two attention-decode kernels (MSD over the INT8 cache, attn.hip; the
+// dequantise-then-BF16 comparison kernel, attn_dequant.hip): launch parameters, the flash-decode
+// split plan, the 16-lane row reductions and the partial-result merge.
+#pragma once
+#include "kernels.hpp"
+
+namespace msd {
+
+struct AttnParams {
+  const uint16_t* q;
+  const int8_t* K;
+  const int8_t* V;
+  const float* k_scale;
+  const float* v_scale;
+  const int32_t* kv_len;
+  int B, Hq, Hkv, G;
+  int64_t L;
+  int nsplit;
+  int64_t tokens_per_split;
+  float* part_o;  // [B*Hkv][nsplit][G][128]
+  float* part_m;  // [B*Hkv][nsplit][G]
+  float* part_l;
+  void* out;
+  int out_bf16;
+  int8_t* tap_q1;
+  int8_t* tap_q2;
+  float* tap_alpha;
+  int32_t* tap_s1;
+  int32_t* tap_s2;
+};
+
+constexpr int kD = 128;
+constexpr int kTile = 64;
+constexpr int kAttnWaves = 4;
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ v4i mfma_s8(v4i a, v4i b, v4i c) {
+  return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float row16_max(float v) {  // over the 16 lanes sharing lane/16
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// number of KV splits per (batch, KV head): enough workgroups to fill the chip, at least two rounds
+// of the four waves per split
+inline int attn_plan_nsplit(int B, int Hkv, int64_t L) {
+  const int64_t pairs = (int64_t)B * Hkv;
+  int64_t ns = cdiv(1024, pairs);
+  int64_t max_by_len = L / (kAttnWaves * kTile * 2);
+  if (max_by_len < 1) max_by_len = 1;
+  if (ns > max_by_len) ns = max_by_len;
+  if (ns > 64) ns = 64;
+  if (ns < 1) ns = 1;
+  return (int)ns;
+}
+
+// fills the split plan, the partial-result pointers inside the workspace and the output fields of p
+void attn_fill_params(const AttnArgs& a, AttnParams& p);
+// merges the split partials into p.out (attn.hip); call only when p.nsplit > 1
+int launch_attn_combine(const AttnParams& p, int per_channel, hipStream_t stream);
+
+}  // namespace msd

@@ -147,6 +147,9 @@ struct AttnArgs {
 };
 int launch_attn_decode(const AttnArgs& a, hipStream_t stream);
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
+// comparison kernel (attn_dequant.hip): K and V lifted to BF16 in registers, BF16 matrix instructions;
+// same arguments, split plan and workspace; taps are ignored
+int launch_attn_dequant(const AttnArgs& a, hipStream_t stream);
 
 // ---- comparison kernels (dequant_gemm.hip)
 // ws / ws_bytes: optional scratch for the BF16 copy of the weights (dequant_workspace_bytes);

@@ -256,7 +256,9 @@ size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int
   return attn_workspace_bytes(B, Hq, Hkv, d, L) + 256;
 }
 
-int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
+}  // extern "C"
+
+static int attn_entry(bool dequant, const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
                            const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
                            const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
                            size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
@@ -282,8 +284,26 @@ int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
   a.out_bf16 = out_dtype == MSD_BF16;
   a.workspace = workspace;
   a.workspace_bytes = workspace_bytes;
-  a.taps = taps;
-  return launch_attn_decode(a, (hipStream_t)stream);
+  a.taps = dequant ? nullptr : taps;
+  return dequant ? launch_attn_dequant(a, (hipStream_t)stream) : launch_attn_decode(a, (hipStream_t)stream);
+}
+
+extern "C" {
+
+int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
+                           const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
+                           const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                           size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  return attn_entry(false, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, kv_len, L, out, out_dtype,
+                    workspace, workspace_bytes, taps, stream);
+}
+
+int msd_dequant_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
+                                   const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
+                                   const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                                   size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  return attn_entry(true, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, kv_len, L, out, out_dtype,
+                    workspace, workspace_bytes, taps, stream);
 }
 
 int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,

@@ -68,3 +68,50 @@ def test_dequant_w4_matches_truth(msd, M, K, N):
     y = msd.msd_dequant_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps))
     torch.cuda.synchronize()
     assert rel_l2(y.cpu().numpy(), truth) <= 1e-5
+
+
+ATTN_CASES = [
+    # B, Hq, Hkv, L, mode, kv_len
+    (2, 8, 2, 96, "token", None),
+    (1, 4, 1, 2048, "token", None),            # several KV splits
+    (3, 8, 2, 700, "token", [700, 0, 333]),     # ragged lengths incl. an empty entry
+    (2, 8, 2, 300, "channel", None),
+    (2, 8, 1, 520, "token", None),              # 8 query heads per KV head
+    (2, 8, 1, 520, "channel", None),
+    (2, 3, 3, 130, "token", None),              # no grouping
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,mode,kv_len", ATTN_CASES)
+def test_dequant_attention_against_fp64_truth(msd, B, Hq, Hkv, L, mode, kv_len):
+    """The comparison attention kernel rounds P (and, per channel, Q * s_K) to BF16 and is otherwise exact up
+    to fp32 accumulation: within 5e-3 of the fp64 attention over the dequantised cache, per head; and the MSD
+    kernel, whose P carries 16 bits, is the closer of the two."""
+    d = 128
+    seed = synth.seed_for(4, B * 1000 + L + 7)
+    q = synth.queries(seed, B, Hq, d)
+    if mode == "token":
+        Kc, ks, Vc, vs = synth.kv_cache_per_token(seed, B, Hkv, L, d)
+        omode, gmode = oracle.PER_TOKEN, msd.MSD_PER_TOKEN
+    else:
+        Kc, ks, Vc, vs = synth.kv_cache_per_channel(seed, B, Hkv, L, d)
+        omode, gmode = oracle.PER_CHANNEL, msd.MSD_PER_CHANNEL
+    kl = None if kv_len is None else np.array(kv_len, np.int32)
+    truth = oracle.truth_attn(q, Kc, Vc, ks, vs, omode, kv_len=kl)
+    args = (bf16_to_dev(q), to_dev(Kc), to_dev(Vc), to_dev(ks), to_dev(vs), gmode)
+    kld = None if kl is None else to_dev(kl)
+    out = msd.msd_dequant_attn_decode_int8kv(*args, kv_len=kld)
+    out_msd = msd.msd_attn_decode_int8kv(*args, kv_len=kld)
+    torch.cuda.synchronize()
+    o, om = out.cpu().numpy(), out_msd.cpu().numpy()
+    lens = [L] * B if kl is None else list(kl)
+    live = np.array([l > 0 for l in lens])
+    assert np.all(o[~live] == 0)
+    for b in range(B):
+        if lens[b] > 0:
+            for h in range(Hq):
+                assert rel_l2(o[b, h], truth[b, h]) <= 5e-3
+    assert rel_l2(om[live], truth[live]) < rel_l2(o[live], truth[live])
+    ob = msd.msd_dequant_attn_decode_int8kv(*args, kv_len=kld, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert rel_l2(ob.float().cpu().numpy()[live], truth[live]) <= 1e-2
