@@ -198,6 +198,38 @@ def leg_attn(msd, synth, time_calls, dev):
     return out
 
 
+def leg_nq_sweep(msd, synth, time_calls, dev):
+    """Query rows per KV head (the paper's Nq, Sec. 4.4): MSD against the dequantising comparison kernel at
+    B = 16, Hkv = 8, L = 4096, d = 128, per-channel scales (the paper's setting) and per-token scales, cold KV.
+    The paper's cost model puts the crossover N* at about 20 to 32 rows on its hardware."""
+    B, Hkv, d, L = 16, 8, 128, 4096
+    kvbytes = 2 * B * Hkv * L * d
+    n = 5
+    sets = []
+    for r in range(n):
+        sets.append((_rand_i8((B, Hkv, L, d), dev, 51 + r), _rand_i8((B, Hkv, L, d), dev, 71 + r),
+                     torch.rand((B, Hkv, L), device=dev) * 0.02 + 0.02, torch.rand((B, Hkv, L), device=dev) * 0.02 + 0.02))
+    kc = torch.rand((Hkv, d), device=dev) * 0.02 + 0.02
+    vc = torch.rand((Hkv, d), device=dev) * 0.02 + 0.02
+    rows = []
+    for G in (1, 2, 4, 8, 12, 16, 24, 32, 48):
+        Hq = Hkv * G
+        q = _bf16(synth.queries(synth.seed_for(4, G), B, Hq, d), dev)
+        o = torch.empty((B, Hq, d), dtype=torch.float32, device=dev)
+        ws = torch.empty(msd.lib().msd_attn_decode_int8kv_workspace_bytes(B, Hq, Hkv, d, L), dtype=torch.uint8,
+                         device=dev)
+        row = {"Nq": G}
+        for mode, name in ((msd.MSD_PER_CHANNEL, "per_channel"), (msd.MSD_PER_TOKEN, "per_token")):
+            def args(i):
+                K_, V_, ks_, vs_ = sets[i % n]
+                return (q, K_, V_, kc, vc, mode) if mode == msd.MSD_PER_CHANNEL else (q, K_, V_, ks_, vs_, mode)
+            us = time_calls(lambda i: msd.msd_attn_decode_int8kv(*args(i), out=o, ws=ws, prepare=True), 2 * n)
+            us_c = time_calls(lambda i: msd.msd_dequant_attn_decode_int8kv(*args(i), out=o, ws=ws, prepare=True), 2 * n)
+            row[name] = {"msd_us": round(us, 1), "dequant_us": round(us_c, 1), "speedup_vs_dequant": round(us_c / us, 3)}
+        rows.append(row)
+    return {"B": B, "Hkv": Hkv, "d": d, "L": L, "kv_bytes": kvbytes, "rows": rows}
+
+
 def leg_cmp_decode(msd, synth, time_calls, dev):
     """Dequant comparison kernel on the W8A16 decode shapes (same cold-cache protocol)."""
     out = []
@@ -274,7 +306,7 @@ def leg_variants(msd, synth, time_calls, dev):
 def run(want, msd, synth, time_calls, dev):
     res = {}
     legs = {"prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
-            "variants": leg_variants}
+            "variants": leg_variants, "nq": leg_nq_sweep}
     for name, fn in legs.items():
         if name in want:
             try:

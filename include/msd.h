@@ -165,7 +165,9 @@ int msd_gemm_w4a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
  *       column t in the merge; P_t*s_V[t] is decomposed with alpha_P = (max s_V over the KV tile)/127.
  *   kv_len : nullable int32 [B], valid tokens per batch entry (<= L); NULL means L everywhere.
  *   out    : [B][Hq][d] float or BF16.  Entries with kv_len == 0 produce zeros.
- *   d must be 128 (64 and 256 are SHAPE errors in this version); Hq % Hkv == 0; Hq/Hkv <= 8.
+ *   d must be 128 (64 and 256 are SHAPE errors in this version); Hq % Hkv == 0; Hq/Hkv <= 64.
+ *   Up to 8 query heads per KV head share one pass over the KV cache; larger groups are processed
+ *   8 heads at a time (16 in the comparison kernel), each pass re-reading the split's KV range.
  */
 int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
                            const float* k_scale, const float* v_scale, int scale_mode, int B,

@@ -42,10 +42,11 @@ __device__ __forceinline__ v4f mfma_bf(v8bf a, v8bf b, v4f c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-constexpr int kCmpHeads = 8;  // query heads per KV head the kernel holds (rows 8..15 of the fragments idle)
+constexpr int kCmpHeads = 16;  // query heads per pass over the KV range: the 16 rows of the A fragment
 constexpr int kPStride = 72;  // BF16 elements per head row of the P tile in LDS (64 + pad)
 
-template <bool PER_TOKEN>
+// MULTI (G > 16): the group is processed 16 heads at a time, one walk over the KV range each.
+template <bool PER_TOKEN, bool MULTI>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t sQ[16][kD];
   __shared__ __attribute__((aligned(16))) uint16_t sP[kAttnWaves][16][kPStride];
@@ -65,12 +66,17 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParam
   const int8_t* Kb = p.K + kv_base * kD;
   const int8_t* Vb = p.V + kv_base * kD;
 
-  // ---- prologue: the G query rows as BF16 (per-channel mode: Q * s_K rounded to BF16), zero rows above
+  const float sm_scale = kLog2e / sqrtf((float)kD);  // scores are kept in log2 units
+  const v4f zero4f = {0.f, 0.f, 0.f, 0.f};
+  const int64_t last = max(t_end - 1, (int64_t)0);
+  const int64_t t_first = t_begin + (int64_t)wave * kTile;
+  for (int h0 = 0; h0 < (MULTI ? G : 1); h0 += kCmpHeads) {  // one pass over the KV range per 16 heads
+  // ---- prologue: the query rows as BF16 (per-channel mode: Q * s_K rounded to BF16), zero rows above G
   for (int idx = tid; idx < 16 * kD; idx += kAttnWaves * 64) {
     const int h = idx / kD, c = idx % kD;
     uint16_t v = 0;
-    if (h < G) {
-      v = p.q[((int64_t)b * p.Hq + hk * G + h) * kD + c];
+    if (h0 + h < G) {
+      v = p.q[((int64_t)b * p.Hq + hk * G + h0 + h) * kD + c];
       if (!PER_TOKEN) v = f32_to_bf16_bits(__uint_as_float((uint32_t)v << 16) * p.k_scale[hk * kD + c]);
     }
     sQ[h][c] = v;
@@ -85,7 +91,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParam
       qa[s][h].u[0] = v.x; qa[s][h].u[1] = v.y; qa[s][h].u[2] = v.z; qa[s][h].u[3] = v.w;
     }
 
-  // per-lane state as a D lane: heads 4 g + r, r = 0..3
+  // per-lane state as a D lane: heads h0 + 4 g + r, r = 0..3
   float m_run[4], l_run[4], o_run[8][4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -94,11 +100,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParam
 #pragma unroll
     for (int c = 0; c < 8; ++c) o_run[c][r] = 0.f;
   }
-  const float sm_scale = kLog2e / sqrtf((float)kD);  // scores are kept in log2 units
-  const v4f zero4f = {0.f, 0.f, 0.f, 0.f};
-
   // tile loads, software-pipelined exactly as in the MSD kernel
-  const int64_t last = max(t_end - 1, (int64_t)0);
   v4i kf[4][2], kfn[4][2];
   v2i vr[4][4], vrn[4][4];  // [jq][tt]: 8 channels (8j..8j+7) of token 16*tt + 4*g + jq
   float sk[4], sv[4], skn[4], svn[4];
@@ -128,7 +130,6 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParam
       }
     }
   };
-  const int64_t t_first = t_begin + (int64_t)wave * kTile;
   if (t_first < t_end) load_tile(t_first, kfn, vrn, skn, svn);
   for (int64_t t0 = t_first; t0 < t_end; t0 += kAttnWaves * kTile) {
     bool live[4];
@@ -226,27 +227,27 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParam
   for (int r = 0; r < 4; ++r) {
     const float lt = row16_sum(l_run[r]);
     const int hs = 4 * g + r;
-    if (hs < kCmpHeads) {
-      if (j == 0) {
-        sM[wave][hs] = m_run[r];
-        sL[wave][hs] = lt;
-      }
-#pragma unroll
-      for (int c = 0; c < 8; ++c) sO[wave][hs][8 * j + c] = o_run[c][r];
+    if (j == 0) {
+      sM[wave][hs] = m_run[r];
+      sL[wave][hs] = lt;
     }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) sO[wave][hs][8 * j + c] = o_run[c][r];
   }
   __syncthreads();
-  for (int idx = tid; idx < G * kD; idx += kAttnWaves * 64) {
-    const int h = idx / kD, c = idx % kD;
+  const int nh_here = min(kCmpHeads, G - h0);
+  for (int idx = tid; idx < nh_here * kD; idx += kAttnWaves * 64) {
+    const int hl = idx / kD, c = idx % kD;
+    const int h = h0 + hl;
     float ms = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) ms = fmaxf(ms, sM[w][h]);
+    for (int w = 0; w < kAttnWaves; ++w) ms = fmaxf(ms, sM[w][hl]);
     float o = 0.f, l = 0.f;
 #pragma unroll
     for (int w = 0; w < kAttnWaves; ++w) {
-      const float wgt = (sM[w][h] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sM[w][h] - ms);
-      o += sO[w][h][c] * wgt;
-      l += sL[w][h] * wgt;
+      const float wgt = (sM[w][hl] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sM[w][hl] - ms);
+      o += sO[w][hl][c] * wgt;
+      l += sL[w][hl] * wgt;
     }
     if (p.nsplit == 1) {
       float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
@@ -265,6 +266,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_dequant_kernel(AttnParam
       }
     }
   }
+  if (MULTI && h0 + kCmpHeads < G) __syncthreads();  // sQ and the merge buffers are reused by the next head group
+  }
 }
 
 }  // namespace
@@ -274,10 +277,17 @@ int launch_attn_dequant(const AttnArgs& a, hipStream_t stream) {
   attn_fill_params(a, p);
   const dim3 grid((unsigned)((int64_t)a.B * a.Hkv * p.nsplit));
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;
-  if (per_token)
-    hipLaunchKernelGGL((attn_dequant_kernel<true>), grid, dim3(kAttnWaves * 64), 0, stream, p);
-  else
-    hipLaunchKernelGGL((attn_dequant_kernel<false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+  if (p.G <= kCmpHeads) {
+    if (per_token)
+      hipLaunchKernelGGL((attn_dequant_kernel<true, false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+    else
+      hipLaunchKernelGGL((attn_dequant_kernel<false, false>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+  } else {
+    if (per_token)
+      hipLaunchKernelGGL((attn_dequant_kernel<true, true>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+    else
+      hipLaunchKernelGGL((attn_dequant_kernel<false, true>), grid, dim3(kAttnWaves * 64), 0, stream, p);
+  }
   MSD_LAUNCH_CHECK();
   if (p.nsplit > 1) return launch_attn_combine(p, per_token ? 0 : 1, stream);
   return MSD_OK;

@@ -265,7 +265,7 @@ static int attn_entry(bool dequant, const void* q_bf16, const int8_t* K, const i
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (scale_mode != MSD_PER_TOKEN && scale_mode != MSD_PER_CHANNEL) return MSD_ERR_INVALID_ARG;
   if (B < 0 || Hq <= 0 || Hkv <= 0 || L < 0) return MSD_ERR_SHAPE;
-  if (d != 128 || Hq % Hkv != 0 || Hq / Hkv > 8 || L > (1 << 24)) return MSD_ERR_SHAPE;
+  if (d != 128 || Hq % Hkv != 0 || Hq / Hkv > 64 || L > (1 << 24)) return MSD_ERR_SHAPE;
   if (B == 0) return MSD_OK;
   if (!q_bf16 || !out || (L > 0 && (!K || !V || !k_scale || !v_scale))) return MSD_ERR_INVALID_ARG;
   if (!aligned_to(K, 16) || !aligned_to(V, 16) || !aligned_to(q_bf16, 16) || !aligned_to(out, 16))

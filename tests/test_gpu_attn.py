@@ -34,6 +34,10 @@ CASES = [
     (2, 8, 1, 520, "channel", None),
     (2, 3, 3, 130, "token", None),            # no grouping (G = 1)
     (1, 6, 2, 64, "token", None),             # G = 3
+    (1, 12, 1, 300, "token", None),           # G = 12: two passes of 8 and 4 heads over the KV range
+    (2, 32, 2, 200, "channel", None),         # G = 16
+    (1, 40, 2, 130, "channel", None),         # G = 20: ragged last head group
+    (1, 48, 1, 1100, "token", [1000]),        # G = 48, several KV splits
 ]
 
 

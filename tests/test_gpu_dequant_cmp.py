@@ -79,6 +79,9 @@ ATTN_CASES = [
     (2, 8, 1, 520, "token", None),              # 8 query heads per KV head
     (2, 8, 1, 520, "channel", None),
     (2, 3, 3, 130, "token", None),              # no grouping
+    (2, 32, 2, 200, "channel", None),           # G = 16: every row of the fragment is a head
+    (1, 24, 1, 300, "token", None),             # G = 24: a second pass with 8 heads
+    (1, 48, 1, 1100, "token", [1000]),          # G = 48, several KV splits
 ]
 
 
