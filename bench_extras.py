@@ -230,6 +230,43 @@ def leg_nq_sweep(msd, synth, time_calls, dev):
     return {"B": B, "Hkv": Hkv, "d": d, "L": L, "kv_bytes": kvbytes, "rows": rows}
 
 
+def leg_moe(msd, synth, time_calls, dev):
+    """Grouped W8A16 GEMM (paper Sec. 7.5): E = 64 experts of N = 2048, K = 4096 (537 MB of INT8 weights, beyond
+    the last-level cache), decode batches routed at random (multinomial counts); one grouped call against one
+    msd_gemm_w8a16 call per active expert.  GB/s counts the weights of the active experts only."""
+    E, N, K = 64, 2048, 4096
+    W = _rand_i8((E, N, K), dev, 91)
+    sc = torch.rand((E, N), device=dev) * 0.009 + 0.001
+    rng = np.random.default_rng(91)
+    out = []
+    for T in (16, 64, 256):
+        counts = rng.multinomial(T, np.ones(E) / E)
+        # four routings that are rotations of each other: consecutive calls touch different experts, so that
+        # the weights come from HBM even when one call's active set would fit the last-level cache
+        rolls = [np.roll(counts, 16 * r) for r in range(4)]
+        offs_np = [np.concatenate([[0], np.cumsum(c)]) for c in rolls]
+        offs = [torch.from_numpy(o.astype(np.int32)).to(dev) for o in offs_np]
+        x = _bf16(synth.activations(synth.seed_for(8, T), T, K), dev)
+        y = torch.empty((T, N), dtype=torch.float32, device=dev)
+        ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(T, K, N), dtype=torch.uint8, device=dev)
+        us = time_calls(lambda i: msd.msd_moe_gemm_w8a16(x, offs[i % 4], W, sc, y=y, ws=ws, prepare=True), 8)
+        active = [e for e in range(E) if counts[e] > 0]
+
+        class _PerExpert:
+            def __init__(self, o, c):
+                self.ps = [msd.msd_gemm_w8a16(x[o[e]:o[e + 1]], W[e], sc[e], y=y[o[e]:o[e + 1]], ws=ws, prepare=True)
+                           for e in range(E) if c[e] > 0]
+            def __call__(self):
+                for p_ in self.ps: p_()
+        us_loop = time_calls(lambda i: _PerExpert(offs_np[i % 4], rolls[i % 4]), 4)
+        wbytes = len(active) * N * K
+        out.append({"T": T, "E": E, "active_experts": len(active), "max_rows_per_expert": int(counts.max()),
+                    "K": K, "N": N, "grouped_us": round(us, 1), "per_expert_calls_us": round(us_loop, 1),
+                    "GBps_active_weights": round(wbytes / us / 1e3, 1),
+                    "hbm_frac": round(wbytes / us / 1e3 / HBM, 4)})
+    return out
+
+
 def leg_cmp_decode(msd, synth, time_calls, dev):
     """Dequant comparison kernel on the W8A16 decode shapes (same cold-cache protocol)."""
     out = []
@@ -306,7 +343,7 @@ def leg_variants(msd, synth, time_calls, dev):
 def run(want, msd, synth, time_calls, dev):
     res = {}
     legs = {"prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
-            "variants": leg_variants, "nq": leg_nq_sweep}
+            "variants": leg_variants, "nq": leg_nq_sweep, "moe": leg_moe}
     for name, fn in legs.items():
         if name in want:
             try:

@@ -155,6 +155,27 @@ int msd_gemm_w4a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
                            const msd_debug_taps* taps, void* stream);
 
 /*
+ * Grouped MSD linear layer for mixture-of-experts models (paper Sec. 7.5: the decomposition works on
+ * individual activation rows, so a grouped GEMM is msd_gemm_w8a16 per expert).  The T activation
+ * rows are sorted by expert; expert e owns rows [expert_offsets[e], expert_offsets[e+1]) and
+ * multiplies them with its own weights:
+ *   y[t][:] = w_scale[e][:] (.) (alpha_t * (x1_t W[e]^T) + beta_t * (x2_t W[e]^T))   for t in expert e.
+ *   expert_offsets : DEVICE int32 [E+1], non-decreasing, expert_offsets[0] = 0 and
+ *                    expert_offsets[E] <= T (rows past it are left unwritten).  It is read by the
+ *                    kernels; the host never looks at it, so no synchronisation is needed after routing.
+ *   W : int8 [E][N][K];  w_scale : float [E][N];  x_bf16 : [T][ldx];  y : [T][ldy].
+ *   workspace : msd_gemm_w8a16_workspace_bytes(T, K, N) bytes.
+ * One decomposition launch over all rows and one GEMM launch over (channel tiles x experts);
+ * experts without rows cost nothing but the launch of their workgroups.  Meant for decode, where
+ * an expert sees a handful of rows (the kernel walks an expert's rows 16 at a time).
+ * Errors as msd_gemm_w8a16; E > 65535 is a SHAPE error.
+ */
+int msd_moe_gemm_w8a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                       const int32_t* expert_offsets, int E, const int8_t* W, const float* w_scale,
+                       int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
  * One decode step of attention over an INT8 KV cache without dequantising it (paper
  * Sec. 4.2, Alg. 3; tiling of Sec. 4.3): Q and the softmax numerator P are decomposed into
  * two INT8 components each, Q K^T and P V run as INT8 products, softmax is fp32 and online.

@@ -83,6 +83,23 @@ def gemm_w8a16(x_bf16, W, w_scale, fractional=False, out_bf16=False, taps=False)
     return y
 
 
+def moe_gemm_w8a16(x_bf16, expert_offsets, W, w_scale, out_bf16=False):
+    """Grouped form of Alg. 1 for mixture-of-experts layers (Sec. 7.5: the decomposition is per activation
+    row, so the grouped GEMM is Alg. 1 applied per expert).  x_bf16 [T][K] sorted by expert, expert e owns
+    rows [expert_offsets[e], expert_offsets[e+1]); W [E][N][K], w_scale [E][N].  Rows past expert_offsets[E]
+    are returned as zeros."""
+    offs = np.asarray(expert_offsets, np.int64)
+    E, N, K = W.shape
+    T = x_bf16.shape[0]
+    assert offs.shape == (E + 1,) and offs[0] == 0 and np.all(np.diff(offs) >= 0) and offs[-1] <= T
+    y = np.zeros((T, N), np.uint16 if out_bf16 else np.float32)
+    for e in range(E):
+        r0, r1 = int(offs[e]), int(offs[e + 1])
+        if r1 > r0:
+            y[r0:r1] = gemm_w8a16(x_bf16[r0:r1], W[e], w_scale[e], out_bf16=out_bf16)
+    return y
+
+
 def truth_gemm_w8(x_bf16, W, w_scale):
     x = _c(x_bf16, np.uint16)
     W = _c(W, np.int8)

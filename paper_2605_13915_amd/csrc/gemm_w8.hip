@@ -78,7 +78,7 @@ constexpr int kSelfMaxRows = 8;
 // FAST: K % 64 == 0, so no load of the main loop is predicated per lane (predicated loads do not
 // batch); fragment rows past 2M then re-read row 0 -- their products are never looked at.
 template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST>
-__global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a) {
+__device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const int64_t n0) {
   constexpr int THREADS = WAVES * 64;
   __shared__ int s_acc[RT][NT][4][64];
   __shared__ float s_red[SELF ? kSelfMaxRows * WAVES : 1];
@@ -89,7 +89,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = lane & 15, g = lane >> 4;
   for (int i = threadIdx.x; i < RT * NT * 256; i += THREADS) (&s_acc[0][0][0][0])[i] = 0;
-  const int64_t n0 = (int64_t)blockIdx.x * (16 * NT);
   const int ksteps = (int)((K + 63) / 64);
   const int per = (ksteps + WAVES - 1) / WAVES;
   const int ks0 = min(wave * per, ksteps);
@@ -231,6 +230,36 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
       if (a.acc1) a.acc1[(int64_t)m * N + n] = a1;
       if (a.acc2) a.acc2[(int64_t)m * N + n] = a2;
     }
+  }
+}
+
+template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a) {
+  gemm_w8_decode_body<WAVES, UNROLL, RT, NT, SELF, FAST>(a, (int64_t)blockIdx.x * (16 * NT));
+}
+
+// Grouped form for mixture-of-experts layers (paper Sec. 7.5: the decomposition is per activation
+// row, so a grouped GEMM is the same computation per expert).  Rows are sorted by expert; expert
+// e = blockIdx.y owns rows [offs[e], offs[e+1]) and its own weight matrix and scales.  The
+// workgroup reads its expert's row range on the device (no host synchronisation), skips empty
+// experts, and runs the decode body on chunks of 8*RT rows.
+template <int WAVES, int UNROLL, int RT, int NT, bool FAST>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w8_grouped_kernel(GemmW8Args a, const int32_t* __restrict__ offs) {
+  const int e = blockIdx.y;
+  const int64_t r0 = offs[e], r1 = offs[e + 1];
+  const int64_t n0 = (int64_t)blockIdx.x * (16 * NT);
+  for (int64_t c0 = r0; c0 < r1; c0 += 8 * RT) {
+    GemmW8Args b = a;
+    b.q1 = a.q1 + c0 * a.ldq;
+    b.q2 = a.q2 + c0 * a.ldq;
+    b.alpha = a.alpha + c0;
+    b.W = a.W + (int64_t)e * a.N * a.K;
+    b.w_scale = a.w_scale + (int64_t)e * a.N;
+    b.y = a.out_bf16 ? (void*)(reinterpret_cast<uint16_t*>(a.y) + c0 * a.ldy)
+                     : (void*)(reinterpret_cast<float*>(a.y) + c0 * a.ldy);
+    b.M = min((int64_t)(8 * RT), r1 - c0);
+    gemm_w8_decode_body<WAVES, UNROLL, RT, NT, false, FAST>(b, n0);
+    __syncthreads();  // the accumulators in LDS are zeroed again by the next chunk
   }
 }
 
@@ -818,6 +847,18 @@ static int launch_decode(const GemmW8Args& a, hipStream_t stream) {
     hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, true>), grid, dim3(WAVES * 64), dyn, stream, a);
   else
     hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, false>), grid, dim3(WAVES * 64), dyn, stream, a);
+  return MSD_OK;
+}
+
+int launch_gemm_w8_grouped(const GemmW8Args& a, const int32_t* offs, int E, hipStream_t stream) {
+  if (E <= 0 || a.N == 0) return MSD_OK;
+  constexpr int NT = 2;
+  const dim3 grid((unsigned)cdiv(a.N, 16 * NT), (unsigned)E);
+  if (a.K % 64 == 0)
+    hipLaunchKernelGGL((gemm_w8_grouped_kernel<8, 4, 2, NT, true>), grid, dim3(8 * 64), 0, stream, a, offs);
+  else
+    hipLaunchKernelGGL((gemm_w8_grouped_kernel<8, 4, 2, NT, false>), grid, dim3(8 * 64), 0, stream, a, offs);
+  MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
 

@@ -60,6 +60,9 @@ int gemm_w8_blocked_bk(int64_t M, int64_t K, int64_t N);
 // true when launch_gemm_w8 runs the decomposition itself (single launch)
 bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);
+// grouped form (mixture of experts): a.q1/q2/alpha/y cover all T rows (row-major codes), a.W = [E][N][K],
+// a.w_scale = [E][N]; expert e owns rows [offs[e], offs[e+1]) (device array of E + 1 entries); a.M is unused
+int launch_gemm_w8_grouped(const GemmW8Args& a, const int32_t* offs, int E, hipStream_t stream);
 // measurement aid: the prefill kernel's MFMA sequence, tile schedule and epilogue without fill,
 // barriers and LDS traffic (output is meaningless); codes in the blocked layout or row-major
 int launch_gemm_w8_mfma_probe(const GemmW8Args& a, hipStream_t stream);

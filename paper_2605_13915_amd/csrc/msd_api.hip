@@ -176,6 +176,43 @@ int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
   return MSD_OK;
 }
 
+int msd_moe_gemm_w8a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const int32_t* expert_offsets, int E,
+                       const int8_t* W, const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (T < 0 || K < 0 || N < 0 || E < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (K % 16 != 0 || K > 131072 || E > 65535) return MSD_ERR_SHAPE;
+  if (T == 0 || N == 0 || E == 0) return MSD_OK;
+  if (!y || !w_scale || !expert_offsets || (K > 0 && (!x_bf16 || !W))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W, 16) || !aligned_to(x_bf16, 2) || !aligned_to(w_scale, 4) || !aligned_to(expert_offsets, 4) ||
+      !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
+    return MSD_ERR_INVALID_ARG;
+  const W8Layout l = w8_layout(T, K, N);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  GemmW8Args a{};
+  a.q1 = (int8_t*)(ws + l.q1);
+  a.q2 = (int8_t*)(ws + l.q2);
+  a.ldq = K;
+  a.alpha = (float*)(ws + l.alpha);
+  a.W = W;
+  a.w_scale = w_scale;
+  a.y = y;
+  a.out_bf16 = out_dtype == MSD_BF16;
+  a.ldy = ldy;
+  a.M = T; a.K = K; a.N = N;
+  if (K > 0) {
+    int rc = launch_decompose_int8((const uint16_t*)x_bf16, T, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
+                                   (float*)a.alpha, 0, 64, a.rg, s);
+    if (rc) return rc;
+  } else {
+    int rc = fill_u32((uint32_t*)a.alpha, T, 0u, s);
+    if (rc) return rc;
+  }
+  return launch_gemm_w8_grouped(a, expert_offsets, E, s);
+}
+
 size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N) {
   if (M <= 0 || K <= 0 || N <= 0) return 256;
   return w4_layout(M, K, N).total + 256;

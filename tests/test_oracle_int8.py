@@ -236,3 +236,28 @@ def test_loose_pins_from_the_papers_tables():
     e_deq = np.linalg.norm(deq - truth) / np.linalg.norm(truth)
     assert gold["msd_rel_l2"] / 4 < e_msd < gold["msd_rel_l2"] * 2.5
     assert e_deq / e_msd > 30
+
+
+# ---------------------------------------------------------------- grouped GEMM (Sec. 7.5)
+
+def test_moe_grouped_gemm_is_alg1_per_row_with_its_experts_weights():
+    # every output row depends on its own activation row and on its expert's weights only: it must equal
+    # the M = 1 product of that row, whatever the other rows and the grouping are; experts without rows
+    # contribute nothing; negating an expert's weights negates exactly its rows.
+    E, N, K, T = 5, 24, 128, 11
+    x = make_rows(31, T, K)
+    W = np.stack([synth.int8_weights(31 + e, N, K)[0] for e in range(E)])
+    s = np.stack([synth.int8_weights(31 + e, N, K)[1] for e in range(E)])
+    offs = np.array([0, 3, 3, 4, 10, 11])            # expert 1 is empty
+    y = oracle.moe_gemm_w8a16(x, offs, W, s)
+    owner = np.searchsorted(offs, np.arange(T), side="right") - 1
+    assert list(owner) == [0, 0, 0, 2, 3, 3, 3, 3, 3, 3, 4]
+    for t in range(T):
+        assert np.array_equal(y[t:t + 1], oracle.gemm_w8a16(x[t:t + 1], W[owner[t]], s[owner[t]]))
+    W2 = W.copy()
+    W2[3] = -W2[3]
+    y2 = oracle.moe_gemm_w8a16(x, offs, W2, s)
+    assert np.array_equal(y2[4:10], -y[4:10]) and np.array_equal(y2[:4], y[:4]) and np.array_equal(y2[10:], y[10:])
+    # rows not assigned to any expert stay zero
+    y3 = oracle.moe_gemm_w8a16(x, np.array([0, 3, 3, 4, 8, 9]), W, s)
+    assert np.all(y3[9:] == 0) and np.array_equal(y3[:8], y[:8])
