@@ -260,9 +260,31 @@ def leg_moe(msd, synth, time_calls, dev):
                 for p_ in self.ps: p_()
         us_loop = time_calls(lambda i: _PerExpert(offs_np[i % 4], rolls[i % 4]), 4)
         wbytes = len(active) * N * K
-        out.append({"T": T, "E": E, "active_experts": len(active), "max_rows_per_expert": int(counts.max()),
+        out.append({"fmt": "w8a16", "T": T, "E": E, "active_experts": len(active),
+                    "max_rows_per_expert": int(counts.max()),
                     "K": K, "N": N, "grouped_us": round(us, 1), "per_expert_calls_us": round(us_loop, 1),
                     "GBps_active_weights": round(wbytes / us / 1e3, 1),
+                    "hbm_frac": round(wbytes / us / 1e3 / HBM, 4)})
+    del W
+    torch.cuda.empty_cache()
+    # MXFP4 experts, twice as many so that the weights still exceed the last-level cache
+    E = 128
+    g = torch.Generator(device=dev)
+    g.manual_seed(92)
+    codes = torch.randint(0, 256, (E, N, K // 2), dtype=torch.uint8, device=dev, generator=g)
+    exps = torch.randint(118, 124, (E, N, K // 32), dtype=torch.uint8, device=dev, generator=g)
+    for T in (16, 64, 256):
+        counts = rng.multinomial(T, np.ones(E) / E)
+        rolls = [np.roll(counts, 32 * r) for r in range(4)]
+        offs = [torch.from_numpy(np.concatenate([[0], np.cumsum(c)]).astype(np.int32)).to(dev) for c in rolls]
+        x = _bf16(synth.activations(synth.seed_for(8, T + 1), T, K), dev)
+        y = torch.empty((T, N), dtype=torch.float32, device=dev)
+        ws = torch.empty(msd.lib().msd_gemm_w4a16_workspace_bytes(T, K, N), dtype=torch.uint8, device=dev)
+        us = time_calls(lambda i: msd.msd_moe_gemm_w4a16(x, offs[i % 4], codes, exps, y=y, ws=ws, prepare=True), 8)
+        n_act = int((counts > 0).sum())
+        wbytes = n_act * (N * K // 2 + N * K // 32)
+        out.append({"fmt": "w4a16", "T": T, "E": E, "active_experts": n_act, "max_rows_per_expert": int(counts.max()),
+                    "K": K, "N": N, "grouped_us": round(us, 1), "GBps_active_weights": round(wbytes / us / 1e3, 1),
                     "hbm_frac": round(wbytes / us / 1e3 / HBM, 4)})
     return out
 

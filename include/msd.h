@@ -176,6 +176,18 @@ int msd_moe_gemm_w8a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
                        size_t workspace_bytes, void* stream);
 
 /*
+ * The same for MXFP4 weights: msd_gemm_w4a16 per expert.
+ *   W_fp4 : uint8 [E][N][K/2];  W_e8m0 : uint8 [E][N][K/32];  other arguments as msd_moe_gemm_w8a16.
+ *   workspace : msd_gemm_w4a16_workspace_bytes(T, K, N) bytes.
+ * The kernel walks an expert's rows 8 at a time (both components of 8 rows fill one 16-row
+ * matrix operand).
+ */
+int msd_moe_gemm_w4a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
+                       const int32_t* expert_offsets, int E, const uint8_t* W_fp4,
+                       const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * One decode step of attention over an INT8 KV cache without dequantising it (paper
  * Sec. 4.2, Alg. 3; tiling of Sec. 4.3): Q and the softmax numerator P are decomposed into
  * two INT8 components each, Q K^T and P V run as INT8 products, softmax is fp32 and online.

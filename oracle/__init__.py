@@ -156,6 +156,21 @@ def gemm_w4a16(x_bf16, W_fp4, W_e8m0, variant=3, out_bf16=False, taps=False):
     return (y, t) if taps else y
 
 
+def moe_gemm_w4a16(x_bf16, expert_offsets, W_fp4, W_e8m0, out_bf16=False):
+    """Grouped form of the W4A16 GEMM (Sec. 7.5; Alg. 2 + Sec. 3.4.1 per expert).  W_fp4 [E][N][K/2],
+    W_e8m0 [E][N][K/32]; rows past expert_offsets[E] are returned as zeros."""
+    offs = np.asarray(expert_offsets, np.int64)
+    E, N = W_fp4.shape[:2]
+    T = x_bf16.shape[0]
+    assert offs.shape == (E + 1,) and offs[0] == 0 and np.all(np.diff(offs) >= 0) and offs[-1] <= T
+    y = np.zeros((T, N), np.uint16 if out_bf16 else np.float32)
+    for e in range(E):
+        r0, r1 = int(offs[e]), int(offs[e + 1])
+        if r1 > r0:
+            y[r0:r1] = gemm_w4a16(x_bf16[r0:r1], W_fp4[e], W_e8m0[e], out_bf16=out_bf16)
+    return y
+
+
 def truth_gemm_w4(x_bf16, W_fp4, W_e8m0):
     x = _c(x_bf16, np.uint16)
     Wq = _c(W_fp4, np.uint8)

@@ -65,6 +65,7 @@ def lib():
         L.msd_attn_decode_int8kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, i64, vp, ci, vp, sz,
                                              vp, vp]
         L.msd_moe_gemm_w8a16.argtypes = [vp, i64, i64, i64, vp, ci, vp, vp, i64, vp, ci, i64, vp, sz, vp]
+        L.msd_moe_gemm_w4a16.argtypes = L.msd_moe_gemm_w8a16.argtypes
         L.msd_dequant_attn_decode_int8kv.argtypes = L.msd_attn_decode_int8kv.argtypes
         L.msd_attn_decode_int8kv_workspace_bytes.argtypes = [ci, ci, ci, ci, i64]
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
@@ -72,7 +73,8 @@ def lib():
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
                      "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
-                     "msd_gemm_w4a16_variant", "msd_dequant_attn_decode_int8kv", "msd_moe_gemm_w8a16"):
+                     "msd_gemm_w4a16_variant", "msd_dequant_attn_decode_int8kv", "msd_moe_gemm_w8a16",
+                     "msd_moe_gemm_w4a16"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -274,6 +276,29 @@ def msd_moe_gemm_w8a16(x, expert_offsets, W, w_scale, out_dtype=torch.float32, y
     if prepare:
         return Prepared(L.msd_moe_gemm_w8a16, args, (x, expert_offsets, W, w_scale, y, ws), "msd_moe_gemm_w8a16", y)
     _check(L.msd_moe_gemm_w8a16(*args), "msd_moe_gemm_w8a16")
+    return y
+
+
+def msd_moe_gemm_w4a16(x, expert_offsets, W_fp4, W_e8m0, out_dtype=torch.float32, y=None, ws=None, prepare=False):
+    """x: bf16 [T][K], rows sorted by expert; expert_offsets: int32 device tensor [E+1]; W_fp4: uint8 [E][N][K/2];
+    W_e8m0: uint8 [E][N][K/32].  Returns y [T][N]."""
+    _dev(x, torch.bfloat16, "x"); _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
+    _dev(expert_offsets, torch.int32, "expert_offsets")
+    T, K = x.shape
+    E, N, K2 = W_fp4.shape
+    assert K2 * 2 == K and W_fp4.is_contiguous() and W_e8m0.shape == (E, N, K // 32) and W_e8m0.is_contiguous()
+    assert expert_offsets.numel() == E + 1 and expert_offsets.is_contiguous()
+    L = lib()
+    if y is None:
+        y = torch.empty((T, N), dtype=out_dtype, device=x.device)
+    if ws is None:
+        ws = workspace(L.msd_gemm_w4a16_workspace_bytes(T, K, N), x.device)
+    ldx = x.stride(0) if T > 1 else max(K, x.stride(0))
+    args = (_ptr(x), T, K, ldx, _ptr(expert_offsets), E, _ptr(W_fp4), _ptr(W_e8m0), N, _ptr(y), _out_code(y.dtype),
+            y.stride(0), _ptr(ws), ws.numel(), _stream())
+    if prepare:
+        return Prepared(L.msd_moe_gemm_w4a16, args, (x, expert_offsets, W_fp4, W_e8m0, y, ws), "msd_moe_gemm_w4a16", y)
+    _check(L.msd_moe_gemm_w4a16(*args), "msd_moe_gemm_w4a16")
     return y
 
 

@@ -65,7 +65,7 @@ __device__ __forceinline__ v8i load_fp6_lds(const uint8_t* p) {  // 24 B, 8-byte
 // EXPORT (SELF only): workgroup 0 also writes the ABI-format codes for the observation points; a
 // separate instantiation because that path keeps 64 code registers alive.
 template <int WAVES, int U, int RT, bool SELF, bool FAST, bool STACK, bool EXPORT = false>
-__global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a) {
+__device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const int64_t n0, const int64_t m0) {
   static_assert(!STACK || RT == 1, "stacked components use a single row fragment");
   constexpr bool CONTIG = true;
   __shared__ float s_part[WAVES][RT][4][64];
@@ -73,8 +73,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = lane & 15, g = lane >> 4;
   const int64_t M = a.M, N = a.N, KB = a.K / 32;
-  const int64_t n0 = (int64_t)blockIdx.x * 16;
-  const int64_t m0 = (int64_t)blockIdx.y * 16 * RT;
   const int64_t supers = (KB + 15) / 16;  // super-steps of 16 blocks (512 k)
   const int64_t per = (supers + WAVES - 1) / WAVES;
   const int64_t s0 = min((int64_t)wave * per, supers), s1 = min(supers, s0 + per);
@@ -254,6 +252,35 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
       reinterpret_cast<uint16_t*>(a.y)[m * a.ldy + n] = f32_to_bf16_bits(v);
     else
       reinterpret_cast<float*>(a.y)[m * a.ldy + n] = v;
+  }
+}
+
+template <int WAVES, int U, int RT, bool SELF, bool FAST, bool STACK, bool EXPORT = false>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a) {
+  gemm_w4_skinny_body<WAVES, U, RT, SELF, FAST, STACK, EXPORT>(a, (int64_t)blockIdx.x * 16,
+                                                               (int64_t)blockIdx.y * 16 * RT);
+}
+
+// Grouped form for mixture-of-experts layers (paper Sec. 7.5; rows sorted by expert, expert
+// e = blockIdx.y owns rows [offs[e], offs[e+1]) and its own weights and scales).  The workgroup reads
+// its expert's row range on the device and runs the stacked-component body on chunks of 8 rows.
+template <int WAVES, int U, bool FAST>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w4_grouped_kernel(GemmW4Args a, const int32_t* __restrict__ offs) {
+  const int e = blockIdx.y;
+  const int64_t r0 = offs[e], r1 = offs[e + 1];
+  const int64_t KB = a.K / 32;
+  for (int64_t c0 = r0; c0 < r1; c0 += 8) {
+    GemmW4Args b = a;
+    b.q1 = a.q1 + c0 * KB * 8;
+    b.q2 = a.q2 + c0 * KB * 8;
+    b.e8m0 = a.e8m0 + c0 * KB;
+    b.W = a.W + (int64_t)e * a.N * (KB * 16);
+    b.We = a.We + (int64_t)e * a.N * KB;
+    b.y = a.out_bf16 ? (void*)(reinterpret_cast<uint16_t*>(a.y) + c0 * a.ldy)
+                     : (void*)(reinterpret_cast<float*>(a.y) + c0 * a.ldy);
+    b.M = min((int64_t)8, r1 - c0);
+    gemm_w4_skinny_body<WAVES, U, 1, false, FAST, true>(b, (int64_t)blockIdx.x * 16, 0);
+    __syncthreads();  // the wave partials in LDS are rewritten by the next chunk
   }
 }
 
@@ -494,6 +521,18 @@ static int launch_w4_tiled(const GemmW4Args& a, hipStream_t stream) {
   }
   hipLaunchKernelGGL((gemm_w4_tiled_kernel<BM, BN, WM, WN>), dim3(grid), dim3(WM * WN * 64), lds, stream, a, tiles_m,
                      tiles_n);
+  return MSD_OK;
+}
+
+int launch_gemm_w4_grouped(const GemmW4Args& a, const int32_t* offs, int E, hipStream_t stream) {
+  if (E <= 0 || a.N == 0) return MSD_OK;
+  const dim3 grid((unsigned)cdiv(a.N, 16), (unsigned)E);
+  const bool fast = (a.K / 32) % 16 == 0 && a.scales_aligned;
+  if (fast)
+    hipLaunchKernelGGL((gemm_w4_grouped_kernel<4, 2, true>), grid, dim3(4 * 64), 0, stream, a, offs);
+  else
+    hipLaunchKernelGGL((gemm_w4_grouped_kernel<4, 2, false>), grid, dim3(4 * 64), 0, stream, a, offs);
+  MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
 

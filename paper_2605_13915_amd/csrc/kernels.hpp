@@ -89,6 +89,9 @@ struct GemmW4Args {
   MxVariant mv;
 };
 bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
+// grouped form (mixture of experts): a.q1/q2/e8m0/y cover all T rows, a.W = [E][N][K/2], a.We = [E][N][K/32];
+// expert e owns rows [offs[e], offs[e+1]) (device array of E + 1 entries); a.M is unused
+int launch_gemm_w4_grouped(const GemmW4Args& a, const int32_t* offs, int E, hipStream_t stream);
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
 
 // ---- W4A16, many rows (gemm_w4_prefill.hip): own decomposition format, asynchronous LDS fill

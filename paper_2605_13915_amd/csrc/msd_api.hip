@@ -288,6 +288,41 @@ int msd_gemm_w4a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
   return launch_gemm_w4(a, s);
 }
 
+int msd_moe_gemm_w4a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const int32_t* expert_offsets, int E,
+                       const uint8_t* W_fp4, const uint8_t* W_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (T < 0 || K < 0 || N < 0 || E < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
+  if (K % 32 != 0 || K > (1 << 20) || E > 65535) return MSD_ERR_SHAPE;
+  if (T == 0 || N == 0 || E == 0) return MSD_OK;
+  if (!y || !expert_offsets || (K > 0 && (!x_bf16 || !W_fp4 || !W_e8m0))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(W_fp4, 16) || !aligned_to(x_bf16, 2) || !aligned_to(expert_offsets, 4) ||
+      !aligned_to(y, out_dtype == MSD_F32 ? 4 : 2))
+    return MSD_ERR_INVALID_ARG;
+  const W4Layout l = w4_layout(T, K, N);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < l.total) return MSD_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  GemmW4Args a{};
+  a.q1 = (uint32_t*)(ws + l.q1);
+  a.q2 = (uint32_t*)(ws + l.q2);
+  a.e8m0 = (uint8_t*)(ws + l.e8m0);
+  a.W = W_fp4;
+  a.We = W_e8m0;
+  // every expert's scale rows must be 16-byte aligned for the 16-byte scale loads
+  a.scales_aligned = (aligned_to(W_e8m0, 16) && (N * (K / 32)) % 16 == 0) ? 1 : 0;
+  a.y = y;
+  a.out_bf16 = out_dtype == MSD_BF16;
+  a.ldy = ldy;
+  a.M = T; a.K = K; a.N = N;
+  if (K > 0) {
+    int rc = launch_decompose_mxfp4((const uint16_t*)x_bf16, T, K, ldx, nullptr, nullptr, nullptr, (uint32_t*)a.q1,
+                                    (uint32_t*)a.q2, (uint8_t*)a.e8m0, a.mv, s);
+    if (rc) return rc;
+  }
+  return launch_gemm_w4_grouped(a, expert_offsets, E, s);
+}
+
 size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L) {
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || L < 0) return 256;
   return attn_workspace_bytes(B, Hq, Hkv, d, L) + 256;

@@ -89,3 +89,32 @@ def test_moe_error_codes(msd):
     assert e.value.code == -3
     y = msd.msd_moe_gemm_w8a16(x[:0], offs, W, s)     # no rows: a successful no-op
     assert y.shape == (0, 8)
+
+
+W4_CASES = [
+    (4, 300, 512, [1, 0, 5, 2]),                 # an empty expert, ragged N
+    (8, 128, 1024, [3, 1, 1, 0, 0, 8, 16, 2]),   # one and two chunks of 8 rows
+    (3, 520, 544, [17, 9, 1]),                   # several chunks, K not a multiple of 512
+    (2, 4096, 4096, [2, 7]),                     # decode-sized matrices
+]
+
+
+@pytest.mark.parametrize("E,N,K,counts", W4_CASES)
+def test_moe_gemm_w4a16_parity(msd, E, N, K, counts):
+    seed = synth.seed_for(8, E * 100 + N + 1)
+    T = int(sum(counts))
+    x = synth.activations(seed, T, K, outliers=True)
+    packs = [synth.mxfp4_weights(seed + 1 + e, N, K) for e in range(E)]
+    codes = np.stack([p[0] for p in packs])
+    exps = np.stack([p[1] for p in packs])
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    ref = oracle.moe_gemm_w4a16(x, offs, codes, exps)
+    y = torch.full((T, N), float("nan"), dtype=torch.float32, device="cuda")
+    msd.msd_moe_gemm_w4a16(bf16_to_dev(x), to_dev(offs), to_dev(codes), to_dev(exps), y=y)
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    assert np.all(np.isfinite(yh))
+    for e in range(E):
+        r0, r1 = offs[e], offs[e + 1]
+        if r1 > r0:
+            assert rel_l2(yh[r0:r1], ref[r0:r1]) <= 2e-6

@@ -224,3 +224,22 @@ def test_w4_gemm_loose_accuracy_pin():
     l2 = np.linalg.norm(y - truth) / np.linalg.norm(truth)
     g = GOLD["mxfp4_gemm"]["normal_0.5"]["rel_l2"]
     assert abs(l2 - g) / g < 0.15
+
+
+# ------------------------------------------------------------------ grouped GEMM (Sec. 7.5)
+
+def test_moe_grouped_w4_gemm_is_the_gemm_per_row_with_its_experts_weights():
+    E, N, K, T = 4, 10, 128, 9
+    x = synth.activations(51, T, K)
+    packs = [synth.mxfp4_weights(51 + e, N, K) for e in range(E)]
+    codes = np.stack([p[0] for p in packs])
+    exps = np.stack([p[1] for p in packs])
+    offs = np.array([0, 2, 2, 8, 9])                 # expert 1 is empty
+    y = oracle.moe_gemm_w4a16(x, offs, codes, exps)
+    owner = np.searchsorted(offs, np.arange(T), side="right") - 1
+    for t in range(T):
+        assert np.array_equal(y[t:t + 1], oracle.gemm_w4a16(x[t:t + 1], codes[owner[t]], exps[owner[t]]))
+    c2 = codes.copy()
+    c2[2] ^= 0x88                                    # flip the sign bit of every weight of expert 2
+    y2 = oracle.moe_gemm_w4a16(x, offs, c2, exps)
+    assert np.array_equal(y2[2:8], -y[2:8]) and np.array_equal(y2[:2], y[:2]) and np.array_equal(y2[8:], y[8:])
