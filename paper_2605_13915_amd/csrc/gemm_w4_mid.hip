@@ -24,29 +24,43 @@ namespace msd {
 
 namespace {
 
-constexpr int kMidU = 8;  // K steps per batch (256 weight bytes per channel)
 constexpr int kMidThreads = 256;
-constexpr int kMidBN = 128;                                   // channels per workgroup
-constexpr int kMidStageA = kMidU * 3072 / 16 / kMidThreads;   // 16-byte activation-operand chunks per thread and batch
-constexpr int kMidStageW = kMidBN * kMidU * 32 / 16 / kMidThreads;  // 16-byte weight chunks per thread and batch
-constexpr int kMidRowW = kMidU * 32 + 16;                     // LDS bytes per weight row (padded)
-constexpr int kMidBufA = kMidU * (3072 + 256);                // operands, then the scale dwords
-constexpr int kMidBufW = kMidBN * kMidRowW;
-constexpr int kMidLds = 2 * (kMidBufA + kMidBufW);
-static_assert(kMidStageA * kMidThreads * 16 == kMidU * 3072 && kMidU * 16 <= kMidThreads, "batch split");
-static_assert(kMidU * 32 / 16 == 16, "a weight row of a batch is 16 chunks: 16 lanes per row");
+constexpr int kMidBN = 128;  // channels per workgroup
 
+// RG: groups of 32 activation rows held at once (M <= 32 * RG); U: K steps per batch (U * 32 weight
+// bytes per channel).  Per batch and buffer LDS holds U * (RG * 3072 + 256) bytes of activation
+// operands and scale dwords and 128 padded weight rows; (RG, U) = (1, 8), (2, 4), (4, 4) fit twice.
+template <int RG, int U>
+struct MidCfg {
+  static constexpr int kStepA = RG * 3072;                                 // operand bytes per K step
+  static constexpr int kStageA = U * kStepA / 16 / kMidThreads;            // 16-byte operand chunks per thread and batch
+  static constexpr int kChunksW = U * 2;                                   // 16-byte chunks per weight row and batch
+  static constexpr int kRowsPerPass = kMidThreads / kChunksW;              // weight rows one staging instruction covers
+  static constexpr int kStageW = kMidBN / kRowsPerPass;                    // 16-byte weight chunks per thread and batch
+  static constexpr int kRowW = U * 32 + 16;                                // LDS bytes per weight row (padded)
+  static constexpr int kBufA = U * (kStepA + 256);                         // operands, then the scale dwords
+  static constexpr int kBufW = kMidBN * kRowW;
+  static constexpr int kLds = 2 * (kBufA + kBufW);
+  static_assert(kStageA * kMidThreads * 16 == U * kStepA && U * 16 <= kMidThreads, "batch split");
+  static_assert(kRowsPerPass * kChunksW == kMidThreads && kStageW * kRowsPerPass == kMidBN, "weight staging split");
+  static_assert(U % 2 == 0 && U <= 8, "one 16-byte scale load per channel covers at most 16 blocks");
+  static_assert(kLds <= 160 * 1024, "LDS budget");
+};
+
+template <int SEL>
 __device__ __forceinline__ v16f mfma_mid(v8i a, v8i b, v16f c, int sa, int sb) {
-  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); E8M0 scales in byte 0 of sa / sb
-  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 4, 0, sa, 0, sb);
+  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); E8M0 scales: byte SEL of sa, byte 0 of sb
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 4, SEL, sa, 0, sb);
 }
 
+template <int RG, int U>
 __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t* __restrict__ qop,
                                                                   const uint8_t* __restrict__ sa_t,
                                                                   const uint8_t* __restrict__ W,
                                                                   const uint8_t* __restrict__ We, void* y,
                                                                   int out_bf16, int64_t ldy, int M, int64_t K,
                                                                   int64_t N, int shift) {
+  using C = MidCfg<RG, U>;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mid[];  // [2][A batch] then [2][W batch]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, kb = lane >> 5;
@@ -54,67 +68,89 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   const int64_t n = n0 + wave * 32 + l32;
   // channels past N repeat the last one; their results are not stored
   const uint8_t* werow = We + min(n, N - 1) * (K / 32);
-  const int NB = (int)(K / (64 * kMidU));  // batches (K is a multiple of 64 * kMidU)
-  // weight staging: chunk tid + i * 256 of the batch = (row r = chunk / 16, 16-byte column c = chunk % 16)
-  const int wr = tid >> 4, wc = tid & 15;
-  const uint8_t* wsrc[kMidStageW];
+  const int NB = (int)(K / (64 * U));  // batches (K is a multiple of 64 * U)
+  // weight staging: chunk tid + i * 256 of the batch = (row chunk / kChunksW, 16-byte column chunk % kChunksW)
+  const int wr = tid / C::kChunksW, wc = tid % C::kChunksW;
+  const uint8_t* wsrc[C::kStageW];
 #pragma unroll
-  for (int i = 0; i < kMidStageW; ++i) wsrc[i] = W + min(n0 + wr + 16 * i, N - 1) * (K / 2) + wc * 16;
+  for (int i = 0; i < C::kStageW; ++i)
+    wsrc[i] = W + min(n0 + wr + C::kRowsPerPass * i, N - 1) * (K / 2) + wc * 16;
 
   // two register stages: while batch b is multiplied out of LDS, batch b + 1 and batch b + 2 are in flight
   struct Stage {
-    v4i w[kMidStageW], a[kMidStageA], asc, wsc;  // wsc: the 16 weight scale bytes of this lane's channel
+    v4i w[C::kStageW], a[C::kStageA], asc, wsc;  // wsc: the 2 U weight scale bytes of this lane's channel
   };
   Stage st0, st1;
   st0.asc = st1.asc = v4i{0, 0, 0, 0};
+  st0.wsc = st1.wsc = v4i{0, 0, 0, 0};
   auto load_batch = [&](int b, Stage& st) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < kMidStageW; ++i)
-      st.w[i] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wsrc[i] + (int64_t)b * (kMidU * 32)));
-    st.wsc = *reinterpret_cast<const v4i*>(werow + (int64_t)b * 16);
-    const uint8_t* src = qop + (int64_t)b * (kMidU * 3072);  // the batch's operands are contiguous
+    for (int i = 0; i < C::kStageW; ++i)
+      st.w[i] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wsrc[i] + (int64_t)b * (U * 32)));
+    if (U == 8) {
+      st.wsc = *reinterpret_cast<const v4i*>(werow + (int64_t)b * 16);
+    } else {  // U == 4: 8 scale bytes
+      const v2i t = *reinterpret_cast<const v2i*>(werow + (int64_t)b * 8);
+      st.wsc[0] = t[0];
+      st.wsc[1] = t[1];
+    }
+    const uint8_t* src = qop + (int64_t)b * (U * C::kStepA);  // the batch's operands are contiguous
 #pragma unroll
-    for (int i = 0; i < kMidStageA; ++i) st.a[i] = *reinterpret_cast<const v4i*>(src + (tid + i * kMidThreads) * 16);
-    // scale dwords: 256 of each step's 512-byte record, one 16-byte chunk per thread of the first two waves
-    if (tid < kMidU * 16)
-      st.asc = *reinterpret_cast<const v4i*>(sa_t + ((int64_t)b * kMidU + (tid >> 4)) * 512 + (tid & 15) * 16);
+    for (int i = 0; i < C::kStageA; ++i) st.a[i] = *reinterpret_cast<const v4i*>(src + (tid + i * kMidThreads) * 16);
+    // scale dwords: 256 of each step's 512-byte record, one 16-byte chunk per thread
+    if (tid < U * 16)
+      st.asc = *reinterpret_cast<const v4i*>(sa_t + ((int64_t)b * U + (tid >> 4)) * 512 + (tid & 15) * 16);
   };
   auto store_batch = [&](int buf, const Stage& st) __attribute__((always_inline)) {
-    uint8_t* sa = s_mid + buf * kMidBufA;
-    uint8_t* sw = s_mid + 2 * kMidBufA + buf * kMidBufW;
+    uint8_t* sa = s_mid + buf * C::kBufA;
+    uint8_t* sw = s_mid + 2 * C::kBufA + buf * C::kBufW;
 #pragma unroll
-    for (int i = 0; i < kMidStageW; ++i) *reinterpret_cast<v4i*>(sw + (wr + 16 * i) * kMidRowW + wc * 16) = st.w[i];
+    for (int i = 0; i < C::kStageW; ++i)
+      *reinterpret_cast<v4i*>(sw + (wr + C::kRowsPerPass * i) * C::kRowW + wc * 16) = st.w[i];
 #pragma unroll
-    for (int i = 0; i < kMidStageA; ++i) *reinterpret_cast<v4i*>(sa + (tid + i * kMidThreads) * 16) = st.a[i];
-    if (tid < kMidU * 16) *reinterpret_cast<v4i*>(sa + kMidU * 3072 + tid * 16) = st.asc;
+    for (int i = 0; i < C::kStageA; ++i) *reinterpret_cast<v4i*>(sa + (tid + i * kMidThreads) * 16) = st.a[i];
+    if (tid < U * 16) *reinterpret_cast<v4i*>(sa + U * C::kStepA + tid * 16) = st.asc;
   };
-  v16f acc;
+  v16f acc[RG];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[rg][r] = 0.f;
   auto multiply = [&](int buf, const v4i& sc) __attribute__((always_inline)) {
-    const uint8_t* sa_buf = s_mid + buf * kMidBufA;
-    const uint8_t* sw_row = s_mid + 2 * kMidBufA + buf * kMidBufW + (wave * 32 + l32) * kMidRowW + kb * 16;
+    const uint8_t* sa_buf = s_mid + buf * C::kBufA;
+    const uint8_t* sw_row = s_mid + 2 * C::kBufA + buf * C::kBufW + (wave * 32 + l32) * C::kRowW + kb * 16;
 #pragma unroll
-    for (int u = 0; u < kMidU; ++u) {
-      const uint8_t* rec = sa_buf + u * 3072;
-      const int sa = *reinterpret_cast<const int*>(sa_buf + kMidU * 3072 + u * 256 + kb * 128 + l32 * 4) & 0xFF;
+    for (int u = 0; u < U; ++u) {
+      // the step's row scales: byte rg of the dword is the scale of row 32 rg + l32 (block kb)
+      const int sa = *reinterpret_cast<const int*>(sa_buf + U * C::kStepA + u * 256 + kb * 128 + l32 * 4);
+      const int sa2 = sa - shift * 0x01010101;  // beta = alpha / 2^shift (the bytes are >= 4)
       // scale byte of block 2u + kb of the batch
       const uint32_t sw = (uint32_t)(u < 2 ? sc[0] : u < 4 ? sc[1] : u < 6 ? sc[2] : sc[3]);
       const int sb = (int)((sw >> (16 * (u & 1) + 8 * kb)) & 0xFFu);
       const v4i w = *reinterpret_cast<const v4i*>(sw_row + u * 32);
       const v8i bw = {w[0], w[1], w[2], w[3], 0, 0, 0, 0};
 #pragma unroll
-      for (int comp = 0; comp < 2; ++comp) {
-        const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
-        const uint2 hi = *reinterpret_cast<const uint2*>(rec + ((3 * comp + 2) * 32 + l32) * 16 + kb * 8);
-        const v8i av = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
-        acc = mfma_mid(av, bw, acc, sa - shift * comp, sb);  // beta = alpha / 2^shift
+      for (int rg = 0; rg < RG; ++rg) {
+        const uint8_t* rec = sa_buf + u * C::kStepA + rg * 3072;
+#pragma unroll
+        for (int comp = 0; comp < 2; ++comp) {
+          const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
+          const uint2 hi = *reinterpret_cast<const uint2*>(rec + ((3 * comp + 2) * 32 + l32) * 16 + kb * 8);
+          const v8i av = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+          const int s = comp ? sa2 : sa;
+          if (rg == 0) acc[rg] = mfma_mid<0>(av, bw, acc[rg], s, sb);
+          else if (rg == 1) acc[rg] = mfma_mid<1>(av, bw, acc[rg], s, sb);
+          else if (rg == 2) acc[rg] = mfma_mid<2>(av, bw, acc[rg], s, sb);
+          else acc[rg] = mfma_mid<3>(av, bw, acc[rg], s, sb);
+        }
       }
+      // four row groups: keep the K steps apart in the schedule, or the hoisted fragment reads spill
+      if (RG == 4) __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   // LDS buffer b % 2 and register stage b % 2 belong to batch b; the scale bytes of a batch stay in
-  // its register stage until the batch after next is fetched into it, i.e. until it has been multiplied
+  // a register copy until the batch has been multiplied
   v4i sc_cur = {0, 0, 0, 0}, sc_next = {0, 0, 0, 0};
   load_batch(0, st0);
   if (NB > 1) load_batch(1, st1);
@@ -143,30 +179,50 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   // D: column l%32, row 8*(r/4) + 4*(l/32) + r%4 in register r
   if (n < N) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = 8 * (r >> 2) + 4 * kb + (r & 3);
-      if (m < M) {
-        if (out_bf16)
-          reinterpret_cast<uint16_t*>(y)[(int64_t)m * ldy + n] = f32_to_bf16_bits(acc[r]);
-        else
-          reinterpret_cast<float*>(y)[(int64_t)m * ldy + n] = acc[r];
+    for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = 32 * rg + 8 * (r >> 2) + 4 * kb + (r & 3);
+        if (m < M) {
+          if (out_bf16)
+            reinterpret_cast<uint16_t*>(y)[(int64_t)m * ldy + n] = f32_to_bf16_bits(acc[rg][r]);
+          else
+            reinterpret_cast<float*>(y)[(int64_t)m * ldy + n] = acc[rg][r];
+        }
       }
-    }
   }
+}
+
+template <int RG, int U>
+int launch_mid(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
+               int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
+  constexpr int lds = MidCfg<RG, U>::kLds;
+  const void* fn = reinterpret_cast<const void*>(&gemm_w4_mid_kernel<RG, U>);
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_w4_mid_kernel<RG, U>), dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), lds, stream,
+                     qop, sa_t, W, We, y, out_bf16, ldy, (int)M, K, N, shift);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
 }
 
 }  // namespace
 
 bool gemm_w4_mid_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned) {
-  // whole batches of K steps; 16-byte loads of the weight scale rows
-  return M > 4 && M <= 32 && N >= 1 && K >= 64 * kMidU && K % (64 * kMidU) == 0 && scales_aligned;
+  // whole batches of 8 K steps (4 would do above 32 rows; one rule keeps the layout choice simple);
+  // 16-byte loads of the weight scale rows
+  return M > 4 && M <= 128 && N >= 1 && K >= 512 && K % 512 == 0 && scales_aligned;
 }
 
-W4MidLayout w4_mid_layout(int64_t K) {
+W4MidLayout w4_mid_layout(int64_t M, int64_t K) {
   W4MidLayout l{};
   const size_t steps = (size_t)K / 64;
+  l.Mpad = M <= 32 ? 32 : M <= 64 ? 64 : 128;
   size_t off = 0;
-  l.qop = off; off = align_up(off + steps * 3072, 256);
+  l.qop = off; off = align_up(off + steps * (l.Mpad / 32) * 3072, 256);
   l.sa_t = off; off = align_up(off + steps * 512, 256);
   l.total = off;
   return l;
@@ -174,18 +230,11 @@ W4MidLayout w4_mid_layout(int64_t K) {
 
 int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
                        int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, hipStream_t stream) {
-  const W4MidLayout l = w4_mid_layout(K);
-  if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, 32, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
-  static bool attr_set = false;
-  if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_mid_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, kMidLds));
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(gemm_w4_mid_kernel, dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), kMidLds, stream,
-                     ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, (int)M, K, N, mv.shift);
-  MSD_LAUNCH_CHECK();
-  return MSD_OK;
+  const W4MidLayout l = w4_mid_layout(M, K);
+  if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, (int64_t)l.Mpad, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
+  if (l.Mpad == 32) return launch_mid<1, 8>(ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  if (l.Mpad == 64) return launch_mid<2, 4>(ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  return launch_mid<4, 4>(ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
 }
 
 }  // namespace msd

@@ -124,13 +124,14 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
 int launch_decompose_mxfp4_pair(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, int64_t Mpad, uint8_t* qop,
                                 uint8_t* sa_t, MxVariant mv, hipStream_t stream);
 
-// ---- W4A16, 32 rows or fewer with the weight stream as the bound (gemm_w4_mid.hip)
+// ---- W4A16, 128 rows or fewer with the weight stream as the bound (gemm_w4_mid.hip)
 struct W4MidLayout {
-  size_t qop, sa_t, total;
+  size_t qop, sa_t, total, Mpad;  // Mpad: rows rounded up to 32, 64 or 128
 };
 bool gemm_w4_mid_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned);
-W4MidLayout w4_mid_layout(int64_t K);
-// decomposition (K-step-major operands of one 32-row group) + GEMM; ws holds w4_mid_layout(K).total bytes
+W4MidLayout w4_mid_layout(int64_t M, int64_t K);
+// decomposition (K-step-major operands of one, two or four 32-row groups) + GEMM; ws holds
+// w4_mid_layout(M, K).total bytes
 int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
                        int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, hipStream_t stream);
 

@@ -49,7 +49,7 @@ static W4Layout w4_layout(int64_t M, int64_t K, int64_t N) {
   l.total = off;
   // the many-row path keeps its own operand format; the workspace is sized for whichever is larger
   if (gemm_w4_prefill_applies(M, K, N)) l.total = std::max(l.total, w4_prefill_layout(M, K, N).total);
-  if (gemm_w4_mid_applies(M, K, N, true)) l.total = std::max(l.total, w4_mid_layout(K).total);
+  if (gemm_w4_mid_applies(M, K, N, true)) l.total = std::max(l.total, w4_mid_layout(M, K).total);
   return l;
 }
 }  // namespace msd
@@ -261,17 +261,17 @@ int msd_gemm_w4a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
     uint8_t* te = taps ? (uint8_t*)taps->scale : nullptr;
     if (!(t1 && t2 && te)) t1 = t2 = te = nullptr;  // the ABI-format taps come as a set
     if (t1 && (!aligned_to(t1, 16) || !aligned_to(t2, 16))) return MSD_ERR_INVALID_ARG;
+    if (!t1 && gemm_w4_mid_applies(M, K, N, a.scales_aligned != 0)) {
+      // 5..128 rows, no observation points: activation operands K-step-major, weights and operands
+      // staged through LDS per 128 channels (the weight stream is the bound)
+      return launch_gemm_w4_mid((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
+                                (uint8_t*)ws, mv, s);
+    }
     if (!t1 && gemm_w4_prefill_applies(M, K, N) && w4_prefill_layout(M, K, N).total < ((size_t)1 << 31)) {
       // many rows, no observation points: decomposition in the GEMM's own operand order,
       // weight scales transposed once, GEMM on the asynchronous-fill pipeline
       return launch_gemm_w4_prefill((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
                                     (uint8_t*)ws, mv, s);
-    }
-    if (!t1 && gemm_w4_mid_applies(M, K, N, a.scales_aligned != 0)) {
-      // 9..32 rows, no observation points: activation operands K-step-major, shared through LDS,
-      // weights straight from HBM into the matrix operand
-      return launch_gemm_w4_mid((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
-                                (uint8_t*)ws, mv, s);
     }
     if (gemm_w4_is_fused(M, K, N)) {
       // one launch: the GEMM kernel decomposes the blocks of its own K range itself
