@@ -37,10 +37,13 @@ def main():
     ap.add_argument("--steps", type=int, default=48)
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", default="all", help="comma list of extra legs: prefill,w4,attn,cmp,variants,nq,moe | all | none")
+    ap.add_argument("--extras", default="all", help="comma list of extra legs: cfg0,prefill,w4,attn,cmp,variants,nq,moe | all | none")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
+    ap.add_argument("--counter-probe", default="", choices=["", "w8_prefill", "w4_prefill", "attn"],
+                    help="for rocprofv3 --pmc runs: three eager calls of one compute-heavy shape (W8A16 "
+                         "2048x8192x8192, W4A16 4096x8192x28672, attention L=32768), nothing else; no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -57,6 +60,35 @@ def main():
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    if args.counter_probe:
+        g = torch.Generator(device=dev)
+        g.manual_seed(7)
+        if args.counter_probe == "w8_prefill":
+            M, K, N = 2048, 8192, 8192
+            x = dev_bf16(synth.activations(synth.seed_for(2, 0), M, K, outliers=True))
+            W = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev, generator=g)
+            sc = torch.rand(N, device=dev) * 0.009 + 0.001
+            call = lambda: msd.msd_gemm_w8a16(x, W, sc)
+        elif args.counter_probe == "w4_prefill":
+            M, K, N = 4096, 8192, 28672
+            x = dev_bf16(synth.activations(synth.seed_for(3, 2), M, K, outliers=True))
+            codes = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device=dev, generator=g)
+            exps = torch.randint(118, 124, (N, K // 32), dtype=torch.uint8, device=dev, generator=g)
+            call = lambda: msd.msd_gemm_w4a16(x, codes, exps)
+        else:
+            B, Hq, Hkv, d, L = 16, 32, 8, 128, 32768
+            q = dev_bf16(synth.queries(synth.seed_for(4, 0), B, Hq, d))
+            Kc = torch.randint(-127, 128, (B, Hkv, L, d), dtype=torch.int8, device=dev, generator=g)
+            Vc = torch.randint(-127, 128, (B, Hkv, L, d), dtype=torch.int8, device=dev, generator=g)
+            ks = torch.rand((B, Hkv, L), device=dev) * 0.02 + 0.02
+            vs = torch.rand((B, Hkv, L), device=dev) * 0.02 + 0.02
+            call = lambda: msd.msd_attn_decode_int8kv(q, Kc, Vc, ks, vs, msd.MSD_PER_TOKEN)
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_probe": args.counter_probe, "calls": 3}))
+        return
 
     K = 4096
     Ms = [1, 8, 32, 128]
@@ -208,7 +240,7 @@ def main():
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
-        {"prefill", "w4", "attn", "cmp", "variants", "nq", "moe"} if args.extras == "all" else set())
+        {"cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe"} if args.extras == "all" else set())
     try:
         import bench_extras
         extras = bench_extras.run(want, msd, synth, time_calls, dev)

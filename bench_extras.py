@@ -289,6 +289,21 @@ def leg_moe(msd, synth, time_calls, dev):
     return out
 
 
+def leg_cfg0(msd, synth, time_calls, dev):
+    """The correctness configuration (M = 16, K = 1024, N = 1024, 1 MB of weights): launch-latency scale,
+    time only, MSD and comparison kernel."""
+    M, K, N = 16, 1024, 1024
+    x = _bf16(synth.activations(synth.seed_for(0, 0), M, K), dev)
+    W = _rand_i8((N, K), dev, 5)
+    sc = torch.rand(N, device=dev) * 0.009 + 0.001
+    y = torch.empty((M, N), dtype=torch.float32, device=dev)
+    ws = torch.empty(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+    us = time_calls(lambda i: msd.msd_gemm_w8a16(x, W, sc, y=y, ws=ws, prepare=True), 16)
+    us_c = time_calls(lambda i: msd.msd_dequant_gemm_w8a16(x, W, sc, y=y, ws=ws, prepare=True), 16)
+    return {"M": M, "K": K, "N": N, "msd_us": round(us, 2), "dequant_us": round(us_c, 2),
+            "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2)}
+
+
 def leg_cmp_decode(msd, synth, time_calls, dev):
     """Dequant comparison kernel on the W8A16 decode shapes (same cold-cache protocol)."""
     out = []
@@ -364,7 +379,7 @@ def leg_variants(msd, synth, time_calls, dev):
 
 def run(want, msd, synth, time_calls, dev):
     res = {}
-    legs = {"prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
+    legs = {"cfg0": leg_cfg0, "prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
             "variants": leg_variants, "nq": leg_nq_sweep, "moe": leg_moe}
     for name, fn in legs.items():
         if name in want:

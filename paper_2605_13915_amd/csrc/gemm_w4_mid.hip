@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
 #pragma unroll
         for (int comp = 0; comp < 2; ++comp) {
           const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
-          const uint2 hi = *reinterpret_cast<const uint2*>(rec + ((3 * comp + 2) * 32 + l32) * 16 + kb * 8);
+          const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
           const v8i av = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
           const int s = comp ? sa2 : sa;
           if (rg == 0) acc[rg] = mfma_mid<0>(av, bw, acc[rg], s, sb);

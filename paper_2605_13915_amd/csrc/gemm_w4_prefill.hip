@@ -6,8 +6,8 @@
 //       both components K-step-major and already in the GEMM's LDS order, so that the GEMM copies
 //       them with perfectly contiguous 1 KB fetches (the rate of the global -> LDS path falls with
 //       the number of cache lines an instruction touches):
-//         qop[K step][group of 32 rows][6 chunks][32 rows][16 B]
-//         chunk 3c+b = dwords 0..3 of block b of component c, chunk 3c+2 = [dwords 4,5 of block 0 | of block 1]
+//         qop[K step][group of 32 rows][6 chunks of 512 B]
+//         chunk 3c+b = [32 rows][dwords 0..3 of block b of component c], chunk 3c+2 = [block][32 rows][dwords 4,5]
 //       and the alpha bytes as sa_t[K step][tile of 256 rows][512 B], byte wm*256 + b*128 + l*4 + i
 //       for row wm*128 + 32*i + l of the tile and block b: a lane's four row fragments read their
 //       scale bytes as one dword and pick the byte with the instruction's op_sel.
@@ -20,9 +20,8 @@
 //       deep.  Both components accumulate into the same fp32 accumulator (scale bytes alpha and
 //       alpha - 4, i.e. beta = alpha / 16), so the 256 x 256 tile needs 256 accumulator registers.
 //
-// LDS layout of a stage (every fragment read is linear in the lane, hence conflict-free, except
-// the 8-byte tails):
-//   activations: 8 groups of 32 rows, each [6 chunks][32 rows][16 B] as in qop;
+// LDS layout of a stage (every fragment read is linear in the lane, hence conflict-free):
+//   activations: 8 groups of 32 rows, each 6 chunks of 512 B as in qop;
 //   weights:     8 groups of 32 columns, group = [2 blocks][32 columns][16 B] (= lane order);
 //   scales:      512 B for the rows, 512 B for the columns, layout as in sa_t.
 #include "decompose_mxfp4_dev.hpp"
@@ -62,13 +61,14 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
   }
   uint32_t p1[6], p2[6];
   const int e = mx_block_pack_fp6(w, p1, p2, mv.hi_mant, mv.shift);
-  // group of 32 rows: [6 chunks][32 rows][16 B]; this block's dwords 0..3 fill chunk 3c + b, its
-  // dwords 4, 5 the half b of chunk 3c + 2
-  uint8_t* d = reinterpret_cast<uint8_t*>(qop) + ((((int64_t)s * (Mpad / 32) + m / 32) * 6) * 32 + (m % 32)) * 16;
-  *reinterpret_cast<uint4*>(d + (0 + b) * 512) = make_uint4(p1[0], p1[1], p1[2], p1[3]);
-  *reinterpret_cast<uint2*>(d + 2 * 512 + b * 8) = make_uint2(p1[4], p1[5]);
-  *reinterpret_cast<uint4*>(d + (3 + b) * 512) = make_uint4(p2[0], p2[1], p2[2], p2[3]);
-  *reinterpret_cast<uint2*>(d + 5 * 512 + b * 8) = make_uint2(p2[4], p2[5]);
+  // group of 32 rows: 6 chunks of 512 B; this block's dwords 0..3 fill row m % 32 of chunk 3c + b
+  // ([32 rows][16 B]), its dwords 4, 5 row m % 32 of half b of chunk 3c + 2 ([2 blocks][32 rows][8 B])
+  uint8_t* g = reinterpret_cast<uint8_t*>(qop) + (((int64_t)s * (Mpad / 32) + m / 32) * 6) * 512;
+  const int r = (int)(m % 32);
+  *reinterpret_cast<uint4*>(g + (0 + b) * 512 + r * 16) = make_uint4(p1[0], p1[1], p1[2], p1[3]);
+  *reinterpret_cast<uint2*>(g + 2 * 512 + b * 256 + r * 8) = make_uint2(p1[4], p1[5]);
+  *reinterpret_cast<uint4*>(g + (3 + b) * 512 + r * 16) = make_uint4(p2[0], p2[1], p2[2], p2[3]);
+  *reinterpret_cast<uint2*>(g + 5 * 512 + b * 256 + r * 8) = make_uint2(p2[4], p2[5]);
   uint8_t* sc = sa_t + ((int64_t)s * max(Mpad / 256, (int64_t)1) + m / 256) * 512;
   sc[scale_slot((int)(m % 256), b)] = (uint8_t)(e + 127);
 }
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // per-lane LDS offsets inside a stage (kb*32 + l32 == lane, so the 16-byte reads are linear in the lane)
-  const uint32_t o_main = lane * 16, o_tail = l32 * 16 + 8 * kb, o_sc = kb * 128 + l32 * 4;
+  const uint32_t o_main = lane * 16, o_tail = lane * 8, o_sc = kb * 128 + l32 * 4;
   auto load_a = [&](int kt, int c, v8i (&fa)[4]) {  // component c of K step kt
     const uint8_t* st = smem4p + (kt % NS) * STAGE + wm * (4 * 3072) + c * 1536;
 #pragma unroll
