@@ -126,7 +126,8 @@ def dequant_gemm_w8a16(x_bf16, W, w_scale):
 
 def decompose_mxfp4(x_bf16, variant=3):
     """Alg. 2.  Returns q1, q2 (uint8 nibble-packed [M][K/2], low nibble = even k) and the
-    E8M0 byte of alpha ([M][K/32]); beta's byte is alpha's minus 4 (minus 3 for variant 1)."""
+    E8M0 byte of alpha ([M][K/32]); beta's byte is alpha's minus 4 (minus 3 for variant 1).
+    variant 4: the E2M1-grid ablation (codes are OCP E2M1 nibbles, beta's byte is alpha's minus 2)."""
     x = _c(x_bf16, np.uint16)
     M, K = x.shape
     assert K % 32 == 0

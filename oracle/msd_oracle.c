@@ -194,6 +194,8 @@ void msd_oracle_dequant_gemm_w8a16(const uint16_t* x_bf16, int64_t M, int64_t K,
  * -0 stored as +0; two per byte, low nibble = even k.  Scale byte = e + 127 (E8M0);
  * e is clamped to [-123, 127] so that beta's byte e + 127 - shift is a valid E8M0.
  * An all-zero block gets e = -123 and zero codes.
+ * variant 4 is the E2M1-grid ablation described further down (codes are then OCP E2M1 nibbles,
+ * shift = 2).
  */
 static int mx_alpha_exp(float mb, int variant) {
   if (mb == 0.0f) return -123;
@@ -201,10 +203,47 @@ static int mx_alpha_exp(float mb, int variant) {
   const float fr = frexpf(mb, &ex); /* mb = fr * 2^ex, fr in [0.5, 1) */
   const float f = 2.0f * fr;        /* in [1, 2), exact */
   const int E = ex - 1;
+  if (variant == 4) { /* E2M1 grid: smallest e with mb <= 6 * 2^e = 1.5 * 2^(e+2) */
+    const int e4 = (f <= 1.5f) ? E - 2 : E - 1;
+    return clampi(e4, -123, 127);
+  }
   const float hi = (variant == 3) ? 1.859375f : 1.75f;
   int e = (f <= hi) ? E : E + 1; /* smallest e with mb <= hi * 2^e */
   return clampi(e, -123, 127);
 }
+
+/* ---------- ablation: both components on the OCP E2M1 grid (variant 4) -------------------
+ * The paper's components live on the uniform grid {k/4}; Sec. 2.2 / Sec. 3.2.1 attribute the format to
+ * the MX specification, whose FP4 element is E2M1 with magnitudes {0, .5, 1, 1.5, 2, 3, 4, 6}.  This
+ * variant runs the same two passes on that grid, so that a native FP4 x FP4 product could consume the
+ * components:  alpha = 2^e with e the smallest exponent such that M_b <= 6 alpha;  q1 = nearest E2M1
+ * value to x/alpha (ties to the even code);  r = x - alpha q1 (exact);  beta = alpha / 4;  q2 = nearest
+ * E2M1 value to r/beta.  |r| <= alpha (half the widest gap, 2, at the top of the range), hence
+ * |r/beta| <= 4: the second pass never saturates, and its error is at most half a gap of 1 at that
+ * magnitude: |x - (alpha q1 + beta q2)| <= beta/2 = alpha/8, against alpha/64 on the uniform grid.
+ * Codes are OCP E2M1 nibbles (bit 3 sign, bits 2..1 exponent, bit 0 mantissa), -0 stored as +0.
+ */
+static const int kE2m1Halves[8] = {0, 1, 2, 3, 4, 6, 8, 12}; /* magnitude code -> value in halves */
+
+/* nearest E2M1 magnitude code to v >= 0 (v exact); ties go to the even code; saturates at 6 */
+static int e2m1_nearest_code(float v) {
+  int best = 0;
+  float bd = v; /* distance to code 0 */
+  for (int c = 1; c < 8; ++c) {
+    const float d = fabsf(v - 0.5f * (float)kE2m1Halves[c]);
+    if (d < bd || (d == bd && (c & 1) == 0)) {
+      best = c;
+      bd = d;
+    }
+  }
+  return best;
+}
+
+static uint8_t e2m1_nibble(float scaled) { /* scaled = value / scale, exact */
+  const int c = e2m1_nearest_code(fabsf(scaled));
+  return (uint8_t)(c == 0 ? 0 : ((scaled < 0.0f ? 8 : 0) | c));
+}
+static float e2m1_value(uint8_t nib) { return (nib & 8 ? -0.5f : 0.5f) * (float)kE2m1Halves[nib & 7]; }
 
 static int grid_code(float scaled) { /* scaled = 4 * value / scale, exact */
   return clampi(rne_i(scaled), -7, 7);
@@ -231,6 +270,12 @@ void msd_oracle_decompose_mxfp4(const uint16_t* x_bf16, int64_t M, int64_t K, in
         uint8_t n1[2], n2[2];
         for (int j = 0; j < 2; ++j) {
           const float xv = bf16_to_f32(xb[i + j]);
+          if (variant == 4) {
+            n1[j] = e2m1_nibble(ldexpf(xv, -e));                 /* x/alpha */
+            const float r = xv - ldexpf(e2m1_value(n1[j]), e);    /* x - alpha*q1, exact */
+            n2[j] = e2m1_nibble(ldexpf(r, 2 - e));                /* r/beta, beta = alpha/4 */
+            continue;
+          }
           const int k1 = grid_code(ldexpf(xv, 2 - e));      /* 4*x/alpha */
           const float r = xv - ldexpf((float)k1, e - 2);    /* x - alpha*k1/4, exact */
           const int k2 = grid_code(ldexpf(r, 2 - e + shift)); /* 4*r/beta */
@@ -264,7 +309,9 @@ void msd_oracle_gemm_w4a16(const uint16_t* x_bf16, int64_t M, int64_t K, int64_t
                            const uint8_t* W_fp4 /*[N][K/2]*/, const uint8_t* W_e8m0 /*[N][K/32]*/,
                            int64_t N, int variant, void* y, int out_bf16, int64_t ldy,
                            uint8_t* tap_q1, uint8_t* tap_q2, uint8_t* tap_e8m0) {
-  const int shift = (variant == 1) ? 3 : 4;
+  /* beta = alpha / 2^shift; the components are k/4 (unit 1/4) or, for the E2M1-grid ablation, h/2 */
+  const int shift = (variant == 1) ? 3 : (variant == 4) ? 2 : 4;
+  const int unit = (variant == 4) ? 2 : 3; /* block dots are integers in units of 2^-unit */
   const int64_t KB = K / 32;
 #pragma omp parallel for schedule(static)
   for (int64_t m = 0; m < M; ++m) {
@@ -278,18 +325,19 @@ void msd_oracle_gemm_w4a16(const uint16_t* x_bf16, int64_t M, int64_t K, int64_t
     for (int64_t n = 0; n < N; ++n) {
       double s = 0.0;
       for (int64_t b = 0; b < KB; ++b) {
-        int64_t d1 = 0, d2 = 0; /* in units of (1/4)*(1/2) = 1/8 */
+        int64_t d1 = 0, d2 = 0; /* in units of (1/4)*(1/2) = 1/8, or (1/2)*(1/2) = 1/4 on the E2M1 grid */
         for (int i = 0; i < 32; ++i) {
           const int64_t kk = b * 32 + i;
           const uint8_t wb = W_fp4[n * (K / 2) + kk / 2];
           const int w = e2m1_halves((kk & 1) ? (wb >> 4) : (wb & 15));
           const uint8_t a1 = q1[kk / 2], a2 = q2[kk / 2];
-          d1 += (int64_t)act_nibble_quarters((kk & 1) ? (a1 >> 4) : (a1 & 15)) * w;
-          d2 += (int64_t)act_nibble_quarters((kk & 1) ? (a2 >> 4) : (a2 & 15)) * w;
+          const uint8_t c1 = (kk & 1) ? (a1 >> 4) : (a1 & 15), c2 = (kk & 1) ? (a2 >> 4) : (a2 & 15);
+          d1 += (int64_t)(variant == 4 ? e2m1_halves(c1) : act_nibble_quarters(c1)) * w;
+          d2 += (int64_t)(variant == 4 ? e2m1_halves(c2) : act_nibble_quarters(c2)) * w;
         }
         const int ew = (int)W_e8m0[n * KB + b] - 127;
         const int e = (int)ea[b] - 127;
-        s += ldexp((double)d1, ew + e - 3) + ldexp((double)d2, ew + e - shift - 3);
+        s += ldexp((double)d1, ew + e - unit) + ldexp((double)d2, ew + e - shift - unit);
       }
       const float vf = (float)s;
       if (out_bf16)

@@ -243,3 +243,106 @@ def test_moe_grouped_w4_gemm_is_the_gemm_per_row_with_its_experts_weights():
     c2[2] ^= 0x88                                    # flip the sign bit of every weight of expert 2
     y2 = oracle.moe_gemm_w4a16(x, offs, c2, exps)
     assert np.array_equal(y2[2:8], -y[2:8]) and np.array_equal(y2[:2], y[:2]) and np.array_equal(y2[8:], y[8:])
+
+
+# ------------------------------------------------------------------ ablation: both components on the E2M1 grid
+
+E2M1_MAG = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+def unpack_e2m1(q):
+    M, K2 = q.shape
+    nib = np.empty((M, K2 * 2), np.int32)
+    nib[:, 0::2] = q & 15
+    nib[:, 1::2] = q >> 4
+    return np.where(nib & 8, -1.0, 1.0) * E2M1_MAG[nib & 7], nib
+
+
+def test_e2m1_grid_ablation_bound_and_proof_steps():
+    # Same two passes on the MX FP4 element grid: M_b/alpha in (3, 6]; pass-1 residual <= alpha (half the
+    # widest gap); |r/beta| <= 4 with beta = alpha/4, so pass 2 never saturates; error <= alpha/8.
+    x = synth.activations(61, 128, 2048, outliers=False)
+    xf = f32(x)
+    q1, q2, e = oracle.decompose_mxfp4(x, variant=4)
+    v1, n1 = unpack_e2m1(q1)
+    v2, n2 = unpack_e2m1(q2)
+    a = np.repeat(np.exp2(e.astype(np.float64) - 127), 32, axis=1)
+    Mb = np.abs(xf).reshape(128, -1, 32).max(axis=2)
+    ratio = Mb / np.exp2(e.astype(np.float64) - 127)
+    assert np.all(ratio <= 6.0) and np.all(ratio > 3.0)
+    r = xf - a * v1
+    assert np.all(np.abs(r) <= a * (1 + 1e-12))
+    assert np.all(np.abs(r / (a / 4)) <= 4.0 + 1e-12)
+    assert np.all(np.abs(v2) <= 4.0)                      # the saturating value 6 is never needed
+    err = np.abs(xf - (a * v1 + a / 4 * v2))
+    assert np.all(err <= a / 8 * (1 + 1e-12))
+    assert err.max() >= 0.95 * (a / 8).min()              # and the bound is attained, not merely satisfied
+    # -0 is stored as +0
+    assert not np.any((n1 == 8) | (n2 == 8))
+    # it is the coarser decomposition: 2-3 times the error of Alg. 2 on the paper's grid
+    q1m, q2m, em = oracle.decompose_mxfp4(x)
+    rec_m = reconstruct(q1m, q2m, em)[0]
+    l2 = lambda rec: np.linalg.norm(xf - rec) / np.linalg.norm(xf)
+    assert 1.5 < l2(a * v1 + a / 4 * v2) / l2(rec_m) < 4.0
+
+
+def test_e2m1_grid_ablation_against_exact_fractions():
+    # an independent implementation in exact rationals: exponent by search, nearest grid value by
+    # comparing distances, ties to the even code
+    rng = np.random.default_rng(62)
+    vals = rng.standard_normal((6, 64)).astype(np.float32) * np.float32(3.0)
+    vals[0, :32] = 0
+    vals[1, 0] = 6.0; vals[1, 1] = 5.0; vals[1, 2] = 2.5; vals[1, 3] = 0.25; vals[1, 4] = -1.75   # exact ties
+    vals[2, 32] = 3.0; vals[2, 33] = -1.5
+    x = synth.f32_to_bf16_bits(vals)
+    xf = synth.bf16_bits_to_f32(x)
+    q1, q2, e = oracle.decompose_mxfp4(x, variant=4)
+    grid = [Fraction(int(2 * m), 2) for m in E2M1_MAG]
+
+    def nearest(v):
+        s = -1 if v < 0 else 1
+        best, bd = 0, abs(v)
+        for c in range(1, 8):
+            d = abs(abs(v) - grid[c])
+            if d < bd or (d == bd and c % 2 == 0):
+                best, bd = c, d
+        return (0 if best == 0 else (8 if s < 0 else 0) | best), s * grid[best]
+
+    for m in range(6):
+        for b in range(2):
+            blk = [Fraction(float(v)) for v in xf[m, 32 * b:32 * b + 32]]
+            mb = max(abs(v) for v in blk)
+            if mb == 0:
+                ee = -123
+            else:
+                ee = -200
+                while mb > 6 * Fraction(2) ** ee:
+                    ee += 1
+                ee = min(max(ee, -123), 127)
+            assert int(e[m, b]) - 127 == ee
+            al = Fraction(2) ** ee
+            for i, v in enumerate(blk):
+                c1, q = nearest(v / al)
+                c2, _ = nearest((v - al * q) / (al / 4))
+                byte1, byte2 = int(q1[m, 16 * b + i // 2]), int(q2[m, 16 * b + i // 2])
+                assert ((byte1 >> 4) if i & 1 else (byte1 & 15)) == c1
+                assert ((byte2 >> 4) if i & 1 else (byte2 & 15)) == c2
+
+
+def test_e2m1_grid_ablation_gemm_exact_rational_tiny():
+    x = synth.activations(63, 2, 64, outliers=False)
+    codes, exps = synth.mxfp4_weights(63, 3, 64)
+    y, t = oracle.gemm_w4a16(x, codes, exps, variant=4, taps=True)
+    d1, d2, de = oracle.decompose_mxfp4(x, variant=4)
+    assert np.array_equal(d1, t["q1"]) and np.array_equal(d2, t["q2"]) and np.array_equal(de, t["e8m0"])
+    v1, _ = unpack_e2m1(t["q1"])
+    v2, _ = unpack_e2m1(t["q2"])
+    for m in range(2):
+        for n in range(3):
+            tot = Fraction(0)
+            for k in range(64):
+                byte = int(codes[n, k // 2])
+                w = Fraction(_e2m1((byte >> 4) if k & 1 else (byte & 15))) * Fraction(2) ** (int(exps[n, k // 32]) - 127)
+                a = Fraction(2) ** (int(t["e8m0"][m, k // 32]) - 127)
+                tot += w * (a * Fraction(float(v1[m, k])) + a / 4 * Fraction(float(v2[m, k])))
+            assert abs(Fraction(float(y[m, n])) - tot) <= abs(tot) * Fraction(1, 2 ** 23)
