@@ -367,7 +367,7 @@ def leg_variants(msd, synth, time_calls, dev):
                          msd.lib().msd_dequant_gemm_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
     w4 = {}
     for name, var in (("v1", msd.MSD_VARIANT_MXFP4_V1), ("v2", msd.MSD_VARIANT_MXFP4_V2),
-                      ("v3_main", msd.MSD_VARIANT_MAIN)):
+                      ("v3_main", msd.MSD_VARIANT_MAIN), ("e2m1_grid_ablation", msd.MSD_VARIANT_MXFP4_E2M1)):
         fn = lambda i, var=var: msd.msd_gemm_w4a16_variant(var, x, codes, exps, y=y, ws=ws)
         fn(0)
         torch.cuda.synchronize()

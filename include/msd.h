@@ -50,7 +50,8 @@ enum {
   MSD_VARIANT_MAIN = 0,
   MSD_VARIANT_INT8_FRACTIONAL = 1, /* INT8: alpha = max|x| / 127.49, beta = alpha / 254.98 */
   MSD_VARIANT_MXFP4_V1 = 2,        /* MXFP4: alpha bound 1.75, beta = alpha / 8 (no clipping) */
-  MSD_VARIANT_MXFP4_V2 = 3         /* MXFP4: alpha bound 1.75, beta = alpha / 16 */
+  MSD_VARIANT_MXFP4_V2 = 3,        /* MXFP4: alpha bound 1.75, beta = alpha / 16 */
+  MSD_VARIANT_MXFP4_E2M1 = 4       /* MXFP4 ablation: both components on the MX FP4 element grid */
 };
 
 /*
@@ -141,6 +142,13 @@ size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
  *       integer with max|x_block| <= 1.75 * 2^e and beta = alpha / 8 (beta's E8M0 byte is alpha's
  *       minus 3); the residual never saturates.
  *   MSD_VARIANT_MXFP4_V2: bound 1.75 as v1, beta = alpha / 16 as the main variant.
+ *   MSD_VARIANT_MXFP4_E2M1 (an ablation, not a parameterisation the paper prints): both components
+ *       take values on the MX FP4 element grid {0, .5, 1, 1.5, 2, 3, 4, 6} (what a native FP4 x FP4
+ *       product would consume) instead of the paper's uniform grid {k/4}: e is the smallest integer with
+ *       max|x_block| <= 6 * 2^e, q1 = nearest grid value to x/alpha (ties to the even code),
+ *       beta = alpha / 4 (byte minus 2), q2 = nearest grid value to r/beta (never saturates);
+ *       |x - (alpha q1 + beta q2)| <= alpha / 8.  q1, q2 of msd_decompose and of the observation points
+ *       are then OCP E2M1 nibbles (bit 3 sign, bits 2..1 exponent, bit 0 mantissa).
  * A variant that does not belong to the format of the call is an INVALID_ARG error.
  */
 int msd_decompose_variant(int variant, int fmt, const void* x_bf16, int64_t M, int64_t K, int64_t ldx,

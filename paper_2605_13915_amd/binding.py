@@ -16,6 +16,7 @@ MSD_INT8, MSD_MXFP4 = 0, 1
 MSD_F32, MSD_BF16 = 0, 1
 MSD_PER_TOKEN, MSD_PER_CHANNEL = 0, 1
 MSD_VARIANT_MAIN, MSD_VARIANT_INT8_FRACTIONAL, MSD_VARIANT_MXFP4_V1, MSD_VARIANT_MXFP4_V2 = 0, 1, 2, 3
+MSD_VARIANT_MXFP4_E2M1 = 4
 
 _ERR = {-1: "MSD_ERR_INVALID_ARG", -2: "MSD_ERR_SHAPE", -3: "MSD_ERR_WORKSPACE", -4: "MSD_ERR_HIP",
         -5: "MSD_ERR_UNSUPPORTED"}

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_kernel(
     for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
   }
   int k1[32], k2[32];
-  const int e = mx_block_codes(w, k1, k2, mv.hi_mant, mv.shift);
+  const int e = mx_block_codes(w, k1, k2, mv);
   const uint8_t ebyte = (uint8_t)(e + 127);
   if (abi_q1) {
     uint32_t a[4], c[4];
@@ -86,11 +86,11 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_kernel(
   }
   if (op_q1) {
     uint32_t p[6];
-    pack_fp6(k1, p);
+    pack_fp6(k1, p, mv.e2m1);
     uint32_t* d1 = op_q1 + (m * KB + b) * 8;
     reinterpret_cast<uint4*>(d1)[0] = make_uint4(p[0], p[1], p[2], p[3]);
     reinterpret_cast<uint2*>(d1)[2] = make_uint2(p[4], p[5]);
-    pack_fp6(k2, p);
+    pack_fp6(k2, p, mv.e2m1);
     uint32_t* d2 = op_q2 + (m * KB + b) * 8;
     reinterpret_cast<uint4*>(d2)[0] = make_uint4(p[0], p[1], p[2], p[3]);
     reinterpret_cast<uint2*>(d2)[2] = make_uint2(p[4], p[5]);

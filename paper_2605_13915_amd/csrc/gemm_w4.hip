@@ -137,9 +137,9 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
         int e;
         if constexpr (EXPORT) {
           int k1[32], k2[32];
-          e = mx_block_codes(w, k1, k2, a.mv.hi_mant, a.mv.shift);
-          pack_fp6(k1, p1);
-          pack_fp6(k2, p2);
+          e = mx_block_codes(w, k1, k2, a.mv);
+          pack_fp6(k1, p1, a.mv.e2m1);
+          pack_fp6(k2, p2, a.mv.e2m1);
           if (blockIdx.x == 0 && a.abi_q1) {  // observation points only: ABI-format codes
             uint32_t c1[4], c2[4];
 #pragma unroll
@@ -159,7 +159,7 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
             a.abi_e8m0[gb] = (uint8_t)(e + 127);
           }
         } else {
-          e = mx_block_pack_fp6(w, p1, p2, a.mv.hi_mant, a.mv.shift);
+          e = mx_block_pack_fp6(w, p1, p2, a.mv);
         }
         uint2* d1 = reinterpret_cast<uint2*>(my_q + ((size_t)m * bpw + bb) * 24);
         uint2* d2 = reinterpret_cast<uint2*>(my_q + ((size_t)(M + m) * bpw + bb) * 24);

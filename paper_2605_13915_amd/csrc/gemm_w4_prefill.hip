@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
     for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
   }
   uint32_t p1[6], p2[6];
-  const int e = mx_block_pack_fp6(w, p1, p2, mv.hi_mant, mv.shift);
+  const int e = mx_block_pack_fp6(w, p1, p2, mv);
   // group of 32 rows: 6 chunks of 512 B; this block's dwords 0..3 fill row m % 32 of chunk 3c + b
   // ([32 rows][16 B]), its dwords 4, 5 row m % 32 of half b of chunk 3c + 2 ([2 blocks][32 rows][8 B])
   uint8_t* g = reinterpret_cast<uint8_t*>(qop) + (((int64_t)s * (Mpad / 32) + m / 32) * 6) * 512;

@@ -10,13 +10,7 @@ namespace msd {
 struct Int8Range {
   float num1 = 127.0f, num2 = 254.0f;
 };
-// MXFP4: alpha = 2^e with e the smallest exponent such that max|block| <= hi * 2^e, hi given by its fp32
-// mantissa field; beta = alpha / 2^shift.  (1.859375, 4) is Alg. 2; the design-evolution table's earlier
-// parameterisations are v1 = (1.75, 3) and v2 = (1.75, 4).
-struct MxVariant {
-  uint32_t hi_mant = 0x6E0000u;  // 1.859375; 1.75 is 0x600000
-  int shift = 4;
-};
+// MXFP4: MxVariant (msd_common.hpp).
 
 // ---- decomposition (decompose.hip)
 // a_step != 0: write the blocked layout of GemmW8Args (stage depth a_bk) instead of row-major [M][ldq]

@@ -66,6 +66,13 @@ static bool int8_range_of(int variant, Int8Range& rg) {
 }
 static bool mx_variant_of(int variant, MxVariant& mv) {
   if (variant == MSD_VARIANT_MAIN) return true;
+  if (variant == MSD_VARIANT_MXFP4_E2M1) {  // both components on the MX FP4 element grid
+    mv.hi_mant = 0x400000u;  // max|block| <= 6 alpha = 1.5 * 2^(e + 2)
+    mv.ebias = 2;
+    mv.shift = 2;
+    mv.e2m1 = 1;
+    return true;
+  }
   if (variant != MSD_VARIANT_MXFP4_V1 && variant != MSD_VARIANT_MXFP4_V2) return false;
   mv.hi_mant = 0x600000u;  // 1.75
   mv.shift = variant == MSD_VARIANT_MXFP4_V1 ? 3 : 4;

@@ -44,6 +44,19 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Parameterisation of the two-pass MXFP4 decomposition (paper Sec. 3.3): alpha = 2^e with e the
+// smallest exponent such that max|block| <= hi * 2^(e + ebias), hi in [1, 2) given by its fp32
+// mantissa field; beta = alpha / 2^shift.  (1.859375, 4) is Alg. 2; the design-evolution table's
+// earlier parameterisations are v1 = (1.75, 3) and v2 = (1.75, 4).  e2m1 = 1 is the ablation with
+// both components on the MX FP4 element grid {0, .5, 1, 1.5, 2, 3, 4, 6} instead of the paper's
+// uniform grid {k/4}: max|block| <= 6 alpha (hi = 1.5, ebias = 2), beta = alpha / 4.
+struct MxVariant {
+  uint32_t hi_mant = 0x6E0000u;  // 1.859375; 1.75 is 0x600000, 1.5 is 0x400000
+  int shift = 4;
+  int ebias = 0;
+  int e2m1 = 0;
+};
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));

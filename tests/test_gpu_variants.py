@@ -1,5 +1,5 @@
 """GPU parity of the decomposition-constant variants (paper Sec. 3.3: fractional INT8 scaling; the MXFP4
-design-evolution table's v1 and v2) against the oracle's variants, through the C ABI, on every kernel
+design-evolution table's v1 and v2; the E2M1-grid ablation) against the oracle's variants, through the C ABI, on every kernel
 family.  Same bars as the main variant: codes, scales and int32 partials bit-exact, fp32 output within
 1e-6 / 2e-6 relative L2."""
 import numpy as np
@@ -65,13 +65,17 @@ def test_gemm_w8a16_fractional(msd, M, K, N, taps):
     assert rel_l2(y0.cpu().numpy(), oracle.gemm_w8a16(x, W, s)) <= 1e-6
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+def _mx_variant(msd, variant):
+    return {1: msd.MSD_VARIANT_MXFP4_V1, 2: msd.MSD_VARIANT_MXFP4_V2, 4: msd.MSD_VARIANT_MXFP4_E2M1}[variant]
+
+
+@pytest.mark.parametrize("variant", [1, 2, 4])
 @pytest.mark.parametrize("M,K", [(1, 4096), (7, 96), (40, 2048)])
 def test_decompose_mxfp4_variants_bit_exact(msd, variant, M, K):
     x = synth.activations(synth.seed_for(6, M), M, K, outliers=K >= 1024)
     x[0, :32] = 0
     q1, q2, e = oracle.decompose_mxfp4(x, variant=variant)
-    V = msd.MSD_VARIANT_MXFP4_V1 if variant == 1 else msd.MSD_VARIANT_MXFP4_V2
+    V = _mx_variant(msd, variant)
     d1, d2, de = msd.msd_decompose_variant(V, msd.MSD_MXFP4, bf16_to_dev(x))
     torch.cuda.synchronize()
     assert np.array_equal(d1.cpu().numpy(), q1) and np.array_equal(d2.cpu().numpy(), q2)
@@ -84,7 +88,7 @@ W4_SHAPES = [(1, 2048, 600), (2, 544, 300), (8, 1024, 520), (16, 512, 1000), (30
              (300, 544, 520)]
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("variant", [1, 2, 4])
 @pytest.mark.parametrize("M,K,N", W4_SHAPES)
 @pytest.mark.parametrize("taps", [True, False])
 def test_gemm_w4a16_variants(msd, variant, M, K, N, taps):
@@ -92,7 +96,7 @@ def test_gemm_w4a16_variants(msd, variant, M, K, N, taps):
     x = synth.activations(seed, M, K, outliers=True)
     codes, exps = synth.mxfp4_weights(seed, N, K)
     xd, cd, ed = bf16_to_dev(x), to_dev(codes), to_dev(exps)
-    V = msd.MSD_VARIANT_MXFP4_V1 if variant == 1 else msd.MSD_VARIANT_MXFP4_V2
+    V = _mx_variant(msd, variant)
     if taps:
         y_ref, t = oracle.gemm_w4a16(x, codes, exps, variant=variant, taps=True)
         y, g = msd.msd_gemm_w4a16_variant(V, xd, cd, ed, taps=True)
@@ -114,7 +118,7 @@ def test_variant_must_belong_to_the_format(msd):
     s = torch.ones(8, device="cuda")
     c = torch.zeros((8, 32), dtype=torch.uint8, device="cuda")
     e = torch.full((8, 2), 127, dtype=torch.uint8, device="cuda")
-    for bad in (msd.MSD_VARIANT_MXFP4_V1, msd.MSD_VARIANT_MXFP4_V2, 9, -1):
+    for bad in (msd.MSD_VARIANT_MXFP4_V1, msd.MSD_VARIANT_MXFP4_V2, msd.MSD_VARIANT_MXFP4_E2M1, 9, -1):
         with pytest.raises(msd.MsdError) as err:
             msd.msd_gemm_w8a16_variant(bad, x, W, s)
         assert err.value.code == -1
