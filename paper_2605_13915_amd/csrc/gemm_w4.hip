@@ -267,7 +267,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_skinny_kernel(GemmW4Args a
 template <int WAVES, int U, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w4_grouped_kernel(GemmW4Args a, const int32_t* __restrict__ offs) {
   const int e = blockIdx.y;
-  const int64_t r0 = offs[e], r1 = offs[e + 1];
+  // a.M is the total number of rows: offsets outside [0, M] (a malformed routing table) are clamped, so
+  // that no row index leaves the activation and output arrays
+  const int64_t r1 = min((int64_t)offs[e + 1], a.M), r0 = max((int64_t)offs[e], (int64_t)0);
   const int64_t KB = a.K / 32;
   for (int64_t c0 = r0; c0 < r1; c0 += 8) {
     GemmW4Args b = a;

@@ -246,7 +246,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
 template <int WAVES, int UNROLL, int RT, int NT, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_grouped_kernel(GemmW8Args a, const int32_t* __restrict__ offs) {
   const int e = blockIdx.y;
-  const int64_t r0 = offs[e], r1 = offs[e + 1];
+  // a.M is the total number of rows: offsets outside [0, M] (a malformed routing table) are clamped, so
+  // that no row index leaves the activation and output arrays
+  const int64_t r1 = min((int64_t)offs[e + 1], a.M), r0 = max((int64_t)offs[e], (int64_t)0);
   const int64_t n0 = (int64_t)blockIdx.x * (16 * NT);
   for (int64_t c0 = r0; c0 < r1; c0 += 8 * RT) {
     GemmW8Args b = a;

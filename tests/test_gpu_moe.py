@@ -118,3 +118,15 @@ def test_moe_gemm_w4a16_parity(msd, E, N, K, counts):
         r0, r1 = offs[e], offs[e + 1]
         if r1 > r0:
             assert rel_l2(yh[r0:r1], ref[r0:r1]) <= 2e-6
+
+
+def test_moe_offsets_past_the_last_row_are_clamped(msd):
+    """A routing table whose last offset exceeds the number of rows must not take any row index out of the
+    arrays: the kernels clamp it to T."""
+    E, N, K = 2, 100, 512
+    x, W, s, offs = _problem(11, E, N, K, [2, 3])
+    bad = offs.copy()
+    bad[-1] = 50
+    y = msd.msd_moe_gemm_w8a16(bf16_to_dev(x), to_dev(bad), to_dev(W), to_dev(s))
+    torch.cuda.synchronize()
+    assert rel_l2(y.cpu().numpy(), oracle.moe_gemm_w8a16(x, offs, W, s)) <= 1e-6
