@@ -1,0 +1,127 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times
+(the entry points without observation points, caller-provided output and workspace).
+
+cfg1 (W8A16 decode) and the small W4 / attention shapes are compared element by element in full.  For the
+shapes whose oracle run would take minutes (cfg2 prefill, W4 with 4096 rows, attention at L = 32768) the
+oracle computes a sample of complete activation rows, resp. complete batch entries -- rows and batch entries
+are independent, so the sampled results are exact full-size results -- spread over first, last and interior
+tiles.  To keep input generation to seconds, the MXFP4 weight matrix and the long KV cache are a seeded
+slab repeated along N resp. L (every tile and split of the kernels is still exercised; the values a tile
+sees do not matter to the bar).  Bars as everywhere: 1e-6 (W8), 2e-6 (W4), 1e-3 (attention) relative L2."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_13915_amd import synth
+from gpu_util import bf16_to_dev, to_dev, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def msd():
+    from paper_2605_13915_amd import binding
+    binding.lib()
+    return binding
+
+
+def _rows(M, n=10, seed=0):
+    """first, last, tile-boundary and random interior rows"""
+    fixed = [0, 1, 127, 128, 255, 256, M // 2, M - 129, M - 2, M - 1]
+    rng = np.random.default_rng(seed)
+    rows = sorted(set([r for r in fixed if 0 <= r < M] + list(rng.integers(0, M, n))))
+    return np.array(rows)
+
+
+@pytest.mark.parametrize("N", [4096, 14336])
+def test_cfg1_w8a16_decode_full(msd, N):
+    K = 4096
+    W, s = synth.int8_weights(synth.seed_for(1, 10 + N), N, K)
+    Wd, sd = to_dev(W), to_dev(s)
+    for M in (1, 8, 32, 128):
+        x = synth.activations(synth.seed_for(1, M), M, K, outliers=True)
+        ref = oracle.gemm_w8a16(x, W, s)
+        y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        msd.msd_gemm_w8a16(bf16_to_dev(x), Wd, sd, y=y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy()
+        assert np.all(np.isfinite(yh))
+        assert rel_l2(yh, ref) <= 1e-6
+        for m in range(M):
+            assert rel_l2(yh[m], ref[m]) <= 1e-6
+
+
+@pytest.fixture(scope="module")
+def prefill_inputs():
+    K = 8192
+    x = synth.activations(synth.seed_for(2, 0), 8192, K, outliers=True)
+    W, s = synth.int8_weights(synth.seed_for(2, 1), 28672, K)
+    return x, W, s
+
+
+@pytest.mark.parametrize("M,N", [(2048, 8192), (8192, 8192), (2048, 28672), (8192, 28672)])
+def test_cfg2_w8a16_prefill_sampled_rows(msd, prefill_inputs, M, N):
+    x, W, s = prefill_inputs
+    x, W, s = x[:M], W[:N], s[:N]
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w8a16(bf16_to_dev(x), to_dev(W), to_dev(s), y=y)
+    torch.cuda.synchronize()
+    rows = _rows(M, seed=M + N)
+    yh = y[torch.from_numpy(rows).cuda()].cpu().numpy()
+    del y
+    torch.cuda.empty_cache()
+    ref = oracle.gemm_w8a16(x[rows], W, s)
+    assert np.all(np.isfinite(yh))
+    for i in range(len(rows)):
+        assert rel_l2(yh[i], ref[i]) <= 1e-6, rows[i]
+
+
+@pytest.fixture(scope="module")
+def w4_weights():
+    K, N, slab = 8192, 28672, 2048
+    codes, exps = synth.mxfp4_weights(synth.seed_for(3, 0), slab, K)
+    return np.tile(codes, (N // slab, 1)), np.tile(exps, (N // slab, 1))
+
+
+@pytest.mark.parametrize("M", [1, 32, 4096])
+def test_cfg3_w4a16(msd, w4_weights, M):
+    codes, exps = w4_weights
+    K, N = 8192, codes.shape[0]
+    x = synth.activations(synth.seed_for(3, M), M, K, outliers=True)
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps), y=y)
+    torch.cuda.synchronize()
+    rows = np.arange(M) if M <= 32 else _rows(M, n=4, seed=M)[::2]
+    yh = y[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref = oracle.gemm_w4a16(x[rows], codes, exps)
+    assert np.all(np.isfinite(yh))
+    for i in range(len(rows)):
+        assert rel_l2(yh[i], ref[i]) <= 2e-6, rows[i]
+
+
+@pytest.mark.parametrize("L,mode", [(4096, "token"), (4096, "channel"), (32768, "token")])
+def test_cfg4_attention(msd, L, mode):
+    B, Hq, Hkv, d, slab = 16, 32, 8, 128, 4096
+    q = synth.queries(synth.seed_for(4, L), B, Hq, d)
+    if mode == "token":
+        Kc, ks, Vc, vs = synth.kv_cache_per_token(synth.seed_for(4, 1), B, Hkv, slab, d)
+        rep = L // slab
+        Kc, Vc = np.tile(Kc, (1, 1, rep, 1)), np.tile(Vc, (1, 1, rep, 1))
+        ks, vs = np.tile(ks, (1, 1, rep)), np.tile(vs, (1, 1, rep))
+        omode, gmode = oracle.PER_TOKEN, msd.MSD_PER_TOKEN
+    else:
+        Kc, ks, Vc, vs = synth.kv_cache_per_channel(synth.seed_for(4, 2), B, Hkv, L, d)
+        omode, gmode = oracle.PER_CHANNEL, msd.MSD_PER_CHANNEL
+    out = msd.msd_attn_decode_int8kv(bf16_to_dev(q), to_dev(Kc), to_dev(Vc), to_dev(ks), to_dev(vs), gmode)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    sel = list(range(B)) if L <= 4096 else [0, 9, 15]
+    if mode == "token":
+        ref = oracle.attn_decode(q[sel], Kc[sel], Vc[sel], ks[sel], vs[sel], omode)
+    else:
+        ref = oracle.attn_decode(q[sel], Kc[sel], Vc[sel], ks, vs, omode)
+    assert np.all(np.isfinite(o))
+    for i, b in enumerate(sel):
+        for h in range(Hq):
+            assert rel_l2(o[b, h], ref[i, h]) <= 1e-3, (b, h)
