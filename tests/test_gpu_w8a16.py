@@ -192,3 +192,31 @@ def test_measurement_aids_run(msd):
     with pytest.raises(msd.MsdError) as e:      # 32 rows or fewer never reach the many-row kernel
         msd.msd_probe_mfma_w4a16(x[:8], to_dev(codes), to_dev(exps))
     assert e.value.code == -2
+
+
+def test_gemm_w8a16_maximum_k_extremal_codes(msd):
+    """K = 131072, the largest accepted contraction length, with every code at +-127: the int32 partial
+    products sit 1.6 % below 2^31 and must come out exactly, on the single-launch path (M = 1), the
+    register-operand decode path (M = 3) and with observation points."""
+    K, N = 131072, 33
+    W = np.full((N, K), 127, np.int8)
+    W[1::2] = -127
+    s = np.linspace(0.5, 1.5, N).astype(np.float32)
+    for M in (1, 3):
+        vals = np.full((M, K), 3.0, np.float32)
+        vals[M - 1] = -0.75
+        x = synth.f32_to_bf16_bits(vals)
+        y_ref, t = oracle.gemm_w8a16(x, W, s, taps=True)
+        assert not t["overflow"] and abs(int(t["acc1"][0, 0])) == 127 * 127 * K
+        y, g = msd.msd_gemm_w8a16(bf16_to_dev(x), to_dev(W), to_dev(s), taps=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(g["acc1"].cpu().numpy(), t["acc1"])
+        assert np.array_equal(g["acc2"].cpu().numpy(), t["acc2"])
+        assert rel_l2(y.cpu().numpy(), y_ref) <= 1e-6
+        y2 = msd.msd_gemm_w8a16(bf16_to_dev(x), to_dev(W), to_dev(s))
+        torch.cuda.synchronize()
+        assert rel_l2(y2.cpu().numpy(), y_ref) <= 1e-6
+    with pytest.raises(msd.MsdError) as e:      # one chunk more is a shape error, not an overflow
+        msd.msd_gemm_w8a16(torch.zeros((1, K + 16), dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros((N, K + 16), dtype=torch.int8, device="cuda"), to_dev(s))
+    assert e.value.code == -2

@@ -261,3 +261,20 @@ def test_moe_grouped_gemm_is_alg1_per_row_with_its_experts_weights():
     # rows not assigned to any expert stay zero
     y3 = oracle.moe_gemm_w8a16(x, np.array([0, 3, 3, 4, 8, 9]), W, s)
     assert np.all(y3[9:] == 0) and np.array_equal(y3[:8], y[:8])
+
+
+def test_maximum_k_extremal_row_stays_inside_int32():
+    # K = 131072 is the largest contraction length the ABI accepts: with every code at +-127 on both sides
+    # the partial product is 127 * 127 * K = 2 114 060 288 < 2^31 (closed form), one more 16-element chunk of
+    # such codes would still fit, twice the length would not.
+    K = 131072
+    x = np.full((1, K), synth.f32_to_bf16_bits(np.array([3.0], np.float32))[0], np.uint16)
+    W = np.full((2, K), 127, np.int8)
+    W[1] = -127
+    s = np.array([1.0, 1.0], np.float32)
+    y, t = oracle.gemm_w8a16(x, W, s, taps=True)
+    assert not t["overflow"]
+    assert np.all(t["q1"] == 127) and np.all(t["q2"] == 0)
+    assert t["acc1"][0, 0] == 127 * 127 * K == 2114060288 and t["acc1"][0, 1] == -2114060288
+    assert 127 * 127 * K < 2 ** 31 <= 127 * 127 * 2 * K
+    assert abs(float(y[0, 0]) - 3.0 * 127 * K) <= 3.0 * 127 * K * 2.0 ** -22
