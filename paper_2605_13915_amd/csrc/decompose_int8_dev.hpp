@@ -78,8 +78,38 @@ __device__ __forceinline__ void int8_codes_fast(float x, float alpha, float ra, 
   c2 = (int)fminf(fmaxf(p, -128.f), 127.f);
 }
 
+// chunk_codes for the rare rows the reciprocal route cannot serve: same result, rolled up so that it
+// costs the kernels that inline it next to their fast path neither registers nor code size.
+__device__ __forceinline__ void chunk_codes_rare(const Chunk16& c, float alpha, float beta, uint4& o1, uint4& o2) {
+  uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0, b0 = 0, b1 = 0, b2 = 0, b3 = 0;
+#pragma unroll 1
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t w0 = j == 0 ? c.w[0] : j == 1 ? c.w[2] : j == 2 ? c.w[4] : c.w[6];
+    const uint32_t w1 = j == 0 ? c.w[1] : j == 1 ? c.w[3] : j == 2 ? c.w[5] : c.w[7];
+    uint32_t pa = 0, pb = 0;
+#pragma unroll 1
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = e < 2 ? w0 : w1;
+      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+      int c1, c2;
+      int8_codes(x, alpha, beta, c1, c2);
+      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
+      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
+    }
+    if (j == 0) { a0 = pa; b0 = pb; } else if (j == 1) { a1 = pa; b1 = pb; } else if (j == 2) { a2 = pa; b2 = pb; } else { a3 = pa; b3 = pb; }
+  }
+  o1 = make_uint4(a0, a1, a2, a3);
+  o2 = make_uint4(b0, b1, b2, b3);
+}
+
+// The reciprocal route needs beta (and with it alpha and both reciprocals) to be a normal fp32
+// number; rows whose maximum is below about 2^-113 take the plain divisions (row-uniform branch).
 __device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, float ra, float beta,
                                                  float rb, uint4& o1, uint4& o2) {
+  if (!(beta >= 1.17549435e-38f)) {
+    chunk_codes_rare(c, alpha, beta, o1, o2);
+    return;
+  }
   uint32_t a[4], b[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {

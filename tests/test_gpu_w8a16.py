@@ -220,3 +220,31 @@ def test_gemm_w8a16_maximum_k_extremal_codes(msd):
         msd.msd_gemm_w8a16(torch.zeros((1, K + 16), dtype=torch.bfloat16, device="cuda"),
                            torch.zeros((N, K + 16), dtype=torch.int8, device="cuda"), to_dev(s))
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("ex", [-130, -125, -118, -100, 100, 126])
+def test_extreme_magnitudes_stay_bit_exact(msd, ex):
+    """Rows whose scale beta (or alpha) is a denormal fp32 number, and rows near the top of the BF16 range:
+    codes and alpha must still be those of correctly rounded fp32 division (the reciprocal shortcut of the
+    quantiser does not apply there), in the stand-alone decomposition, the single-launch GEMM (M = 1) and the
+    two-launch GEMM (M = 4)."""
+    rng = np.random.default_rng(1000 + ex)
+    vals = rng.standard_normal((4, 256)).astype(np.float32) * np.float32(2.0) ** ex
+    x = synth.f32_to_bf16_bits(vals)
+    q1, q2, al, _ = oracle.decompose_int8(x)
+    d1, d2, da = msd.msd_decompose(msd.MSD_INT8, bf16_to_dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(d1.cpu().numpy(), q1) and np.array_equal(d2.cpu().numpy(), q2)
+    assert np.array_equal(da.cpu().numpy().view(np.uint32), al.view(np.uint32))
+    W, s = synth.int8_weights(7, 40, 256)
+    for M in (1, 4):
+        _, t = oracle.gemm_w8a16(x[:M], W, s, taps=True)
+        _, g = msd.msd_gemm_w8a16(bf16_to_dev(x[:M]), to_dev(W), to_dev(s), taps=True)
+        torch.cuda.synchronize()
+        for k in ("q1", "q2", "acc1", "acc2"):
+            assert np.array_equal(g[k].cpu().numpy(), t[k]), (M, k)
+    m1, m2, me = oracle.decompose_mxfp4(x)
+    g1, g2, ge = msd.msd_decompose(msd.MSD_MXFP4, bf16_to_dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(g1.cpu().numpy(), m1) and np.array_equal(g2.cpu().numpy(), m2)
+    assert np.array_equal(ge.cpu().numpy(), me)
