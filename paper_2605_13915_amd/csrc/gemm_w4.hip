@@ -17,7 +17,6 @@
 // (measured: the transposed assignment 4g+u, 16 bytes out of every 64 per instruction, streamed
 // 30 % slower).  The 16 scale bytes of a row and super-step come as one 16-byte load; a lane
 // shifts its byte (4u+g) down to bits 7:0.
-#include <cstdlib>
 
 #include "decompose_mxfp4_dev.hpp"
 #include "kernels.hpp"
@@ -50,7 +49,7 @@ __device__ __forceinline__ v8i load_fp6_lds(const uint8_t* p) {  // 24 B, 8-byte
 // of 16 blocks.  Per batch of U super-steps a wave first issues all its weight loads (HBM ->
 // registers in B-operand layout), then fetches the activation operands, then runs the MFMAs.
 //
-// SELF (M <= 2, RT = 1): the kernel decomposes the activations itself (Alg. 2) -- the block
+// SELF (M = 1, RT = 1; the kernel itself handles up to two rows): the kernel decomposes the activations itself (Alg. 2) -- the block
 // decomposition needs no reduction beyond the 32-element block, so each wave handles exactly the
 // blocks of its own K range, one block per lane, into wave-private LDS, under its own weight
 // loads.  One launch per call, nothing materialised in HBM.
@@ -312,7 +311,7 @@ static int launch_w4(const GemmW4Args& a, hipStream_t stream) {
   return MSD_OK;
 }
 
-// ------------------------------------------------------------------ tiled (M > 16)
+// ------------------------------------------------------------------ tiled (observation points, or K not a multiple of 64 / 512)
 // v_mfma_scale_f32_32x32x64_f8f6f4: lane l holds row/column l%32 and K block l/32 (two blocks
 // per instruction).  Workgroup tile BM x BN, K stage of 4 blocks (128 k), LDS double buffering
 // with register staging of the next stage.  LDS operand layout is [block][row][24 B] for the

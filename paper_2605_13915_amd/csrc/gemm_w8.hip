@@ -19,7 +19,6 @@
 //   large  : any M.  32x32x32 MFMA, LDS-staged tiles (swizzled), 4 waves, register-local merge
 //            of the two components; for prefill-sized problems a 256x256 tile filled by
 //            asynchronous global->LDS loads four stages deep.
-#include <cstdlib>
 #include <type_traits>
 
 #include "decompose_int8_dev.hpp"
