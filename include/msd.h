@@ -21,6 +21,10 @@
  *   - Return value: MSD_OK, or a negative error code; nothing is enqueued on error
  *     except for MSD_ERR_HIP, after which msd_last_hip_error() holds the hipError_t.
  *   - Results are deterministic run to run (no floating-point atomics).
+ *   - The calls enqueue kernels only (plus device-to-device copies when observation points are
+ *     requested), so they may be captured into a HIP graph.  The first call that reaches a kernel
+ *     with a large LDS footprint sets that kernel's attribute (hipFuncSetAttribute): make one
+ *     eager call of each shape class before capturing.
  */
 #ifndef MSD_H_
 #define MSD_H_
