@@ -30,9 +30,12 @@ constexpr int kMidBN = 128;  // channels per workgroup
 // RG: groups of 32 activation rows held at once (M <= 32 * RG); U: K steps per batch (U * 32 weight
 // bytes per channel).  Per batch and buffer LDS holds U * (RG * 3072 + 256) bytes of activation
 // operands and scale dwords and 128 padded weight rows; (RG, U) = (1, 8), (2, 4), (4, 4) fit twice.
-template <int RG, int U>
+// A4: the components are OCP E2M1 codes (the E2M1-grid ablation) carried as native FP4 operands: 2 KB per
+// 32-row group and K step (chunk 2c+b = [32 rows][16 B of block b of component c]) instead of 3 KB.
+template <int RG, int U, bool A4>
 struct MidCfg {
-  static constexpr int kStepA = RG * 3072;                                 // operand bytes per K step
+  static constexpr int kGroupA = A4 ? 2048 : 3072;                         // operand bytes of a 32-row group per K step
+  static constexpr int kStepA = RG * kGroupA;                              // operand bytes per K step
   static constexpr int kStageA = U * kStepA / 16 / kMidThreads;            // 16-byte operand chunks per thread and batch
   static constexpr int kChunksW = U * 2;                                   // 16-byte chunks per weight row and batch
   static constexpr int kRowsPerPass = kMidThreads / kChunksW;              // weight rows one staging instruction covers
@@ -47,20 +50,22 @@ struct MidCfg {
   static_assert(kLds <= 160 * 1024, "LDS budget");
 };
 
-template <int SEL>
+template <int SEL, int CBSZ>
 __device__ __forceinline__ v16f mfma_mid(v8i a, v8i b, v16f c, int sa, int sb) {
-  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); E8M0 scales: byte SEL of sa, byte 0 of sb
-  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 4, SEL, sa, 0, sb);
+  // A: FP6 E2M3 (cbsz = 2) or FP4 E2M1 (cbsz = 4), B: FP4 E2M1 (blgp = 4); E8M0 scales: byte SEL of sa,
+  // byte 0 of sb
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, CBSZ, 4, SEL, sa, 0, sb);
 }
 
-template <int RG, int U>
+template <int RG, int U, bool A4>
 __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t* __restrict__ qop,
                                                                   const uint8_t* __restrict__ sa_t,
                                                                   const uint8_t* __restrict__ W,
                                                                   const uint8_t* __restrict__ We, void* y,
                                                                   int out_bf16, int64_t ldy, int M, int64_t K,
                                                                   int64_t N, int shift) {
-  using C = MidCfg<RG, U>;
+  using C = MidCfg<RG, U, A4>;
+  constexpr int CBSZ = A4 ? 4 : 2;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mid[];  // [2][A batch] then [2][W batch]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, kb = lane >> 5;
@@ -131,17 +136,23 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
       const v8i bw = {w[0], w[1], w[2], w[3], 0, 0, 0, 0};
 #pragma unroll
       for (int rg = 0; rg < RG; ++rg) {
-        const uint8_t* rec = sa_buf + u * C::kStepA + rg * 3072;
+        const uint8_t* rec = sa_buf + u * C::kStepA + rg * C::kGroupA;
 #pragma unroll
         for (int comp = 0; comp < 2; ++comp) {
-          const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
-          const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
-          const v8i av = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+          v8i av;
+          if constexpr (A4) {
+            const uint4 lo = *reinterpret_cast<const uint4*>(rec + (2 * comp + kb) * 512 + l32 * 16);
+            av = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
+          } else {
+            const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
+            const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
+            av = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+          }
           const int s = comp ? sa2 : sa;
-          if (rg == 0) acc[rg] = mfma_mid<0>(av, bw, acc[rg], s, sb);
-          else if (rg == 1) acc[rg] = mfma_mid<1>(av, bw, acc[rg], s, sb);
-          else if (rg == 2) acc[rg] = mfma_mid<2>(av, bw, acc[rg], s, sb);
-          else acc[rg] = mfma_mid<3>(av, bw, acc[rg], s, sb);
+          if (rg == 0) acc[rg] = mfma_mid<0, CBSZ>(av, bw, acc[rg], s, sb);
+          else if (rg == 1) acc[rg] = mfma_mid<1, CBSZ>(av, bw, acc[rg], s, sb);
+          else if (rg == 2) acc[rg] = mfma_mid<2, CBSZ>(av, bw, acc[rg], s, sb);
+          else acc[rg] = mfma_mid<3, CBSZ>(av, bw, acc[rg], s, sb);
         }
       }
       // four row groups: keep the K steps apart in the schedule, or the hoisted fragment reads spill
@@ -193,17 +204,17 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   }
 }
 
-template <int RG, int U>
+template <int RG, int U, bool A4>
 int launch_mid(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
                int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
-  constexpr int lds = MidCfg<RG, U>::kLds;
-  const void* fn = reinterpret_cast<const void*>(&gemm_w4_mid_kernel<RG, U>);
+  constexpr int lds = MidCfg<RG, U, A4>::kLds;
+  const void* fn = reinterpret_cast<const void*>(&gemm_w4_mid_kernel<RG, U, A4>);
   static bool attr_set = false;
   if (!attr_set) {
     MSD_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w4_mid_kernel<RG, U>), dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), lds, stream,
+  hipLaunchKernelGGL((gemm_w4_mid_kernel<RG, U, A4>), dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), lds, stream,
                      qop, sa_t, W, We, y, out_bf16, ldy, (int)M, K, N, shift);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -232,9 +243,16 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
                        int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, hipStream_t stream) {
   const W4MidLayout l = w4_mid_layout(M, K);
   if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, (int64_t)l.Mpad, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
-  if (l.Mpad == 32) return launch_mid<1, 8>(ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-  if (l.Mpad == 64) return launch_mid<2, 4>(ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-  return launch_mid<4, 4>(ws + l.qop, ws + l.sa_t, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  const uint8_t* qop = ws + l.qop;
+  const uint8_t* sa = ws + l.sa_t;
+  if (mv.e2m1) {  // E2M1-grid components as native FP4 operands
+    if (l.Mpad == 32) return launch_mid<1, 8, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 64) return launch_mid<2, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    return launch_mid<4, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  }
+  if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  return launch_mid<4, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
 }
 
 }  // namespace msd

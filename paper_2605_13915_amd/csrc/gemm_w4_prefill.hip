@@ -59,6 +59,30 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
 #pragma unroll
     for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
   }
+  if (mv.e2m1) {
+    // native FP4 operands: the 32 E2M1 nibbles of the block, element i at bits [4i, 4i+4) (the ABI order),
+    // row m % 32 of chunk 2c + b of the group's four 512-byte chunks
+    int k1[32], k2[32];
+    const int e4 = mx_block_codes(w, k1, k2, mv);
+    uint32_t c1[4], c2[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t pa = 0, pc = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pa |= nibble4(k1[j * 8 + i]) << (4 * i);
+        pc |= nibble4(k2[j * 8 + i]) << (4 * i);
+      }
+      c1[j] = pa;
+      c2[j] = pc;
+    }
+    uint8_t* g4 = reinterpret_cast<uint8_t*>(qop) + (((int64_t)s * (Mpad / 32) + m / 32) * 4) * 512 + (m % 32) * 16;
+    *reinterpret_cast<uint4*>(g4 + (0 + b) * 512) = make_uint4(c1[0], c1[1], c1[2], c1[3]);
+    *reinterpret_cast<uint4*>(g4 + (2 + b) * 512) = make_uint4(c2[0], c2[1], c2[2], c2[3]);
+    uint8_t* sc4 = sa_t + ((int64_t)s * max(Mpad / 256, (int64_t)1) + m / 256) * 512;
+    sc4[scale_slot((int)(m % 256), b)] = (uint8_t)(e4 + 127);
+    return;
+  }
   uint32_t p1[6], p2[6];
   const int e = mx_block_pack_fp6(w, p1, p2, mv);
   // group of 32 rows: 6 chunks of 512 B; this block's dwords 0..3 fill row m % 32 of chunk 3c + b
@@ -108,10 +132,11 @@ __global__ __launch_bounds__(256) void transpose_w_scales_kernel(const uint8_t* 
 }
 
 // ------------------------------------------------------------------ (3) GEMM
-template <int SELA, int SELB>
+template <int SELA, int SELB, int CBSZ = 2>
 __device__ __forceinline__ v16f mfma64_scaled(v8i a, v8i b, v16f c, int sa, int sb) {
-  // A: FP6 E2M3 (cbsz = 2), B: FP4 E2M1 (blgp = 4); E8M0 scales: byte SELA of sa, byte SELB of sb
-  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 2, 4, SELA, sa, SELB, sb);
+  // A: FP6 E2M3 (cbsz = 2) or FP4 E2M1 (cbsz = 4), B: FP4 E2M1 (blgp = 4); E8M0 scales: byte SELA of sa,
+  // byte SELB of sb
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, CBSZ, 4, SELA, sa, SELB, sb);
 }
 
 __device__ __forceinline__ void w4_lds_dma16(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
@@ -137,10 +162,17 @@ constexpr int kW4PGroupM = 8;
 // PROBE = true is a measurement aid (msd_probe_mfma_w4a16): after the first K step the kernel stops
 // fetching and keeps multiplying that step's operands -- the same scaled-MFMA sequence, tile
 // schedule and epilogue on real operand bits, without fill, barriers and LDS traffic.
-template <int NS, bool PROBE = false>
+// A4 = true: the activation components are OCP E2M1 codes (the E2M1-grid ablation) and travel as native
+// FP4 operands, 16 bytes per lane and block instead of 24: a group of 32 rows is 2 KB per K step
+// (chunk 2c+b = [32 rows][16 B of block b of component c]), a stage 25 KB, 6 fill instructions per wave.
+template <int NS, bool PROBE = false, bool A4 = false>
 __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, int tiles_m, int tiles_n) {
-  constexpr int SZ_A = 24576, SZ_W = 8192, STAGE = SZ_A + SZ_W + 1024;
-  constexpr int L = 8;  // data load instructions per wave and stage (wave 0 issues one more: scales)
+  constexpr int GA = A4 ? 2048 : 3072;  // operand bytes of a 32-row group per K step
+  constexpr int CA = GA / 2;            // of one component
+  constexpr int SZ_A = 8 * GA, SZ_W = 8192, STAGE = SZ_A + SZ_W + 1024;
+  constexpr int QA = SZ_A / 4096;       // activation fill instructions per wave and stage
+  constexpr int L = QA + 2;             // data load instructions per wave and stage (wave 0 issues one more: scales)
+  constexpr int CBSZ = A4 ? 4 : 2;
   static_assert(NS >= 3 && (NS - 2) * (L + 1) < 64, "stage count");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem4p[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -149,7 +181,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   const int l32 = lane & 31, kb = lane >> 5;
   const int64_t M = a.M, N = a.N;
   const int KT = (int)(a.K / 64);
-  const uint32_t step_a = (uint32_t)(a.Mpad * 96);  // bytes of qop per K step
+  const uint32_t step_a = (uint32_t)(a.Mpad * (GA / 32));  // bytes of qop per K step
   const int64_t row_w = a.K / 2;           // bytes per weight row
   const int total = tiles_m * tiles_n;
   int id = blockIdx.x;
@@ -173,7 +205,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // weight group idx - 24 (32 columns x 2 blocks).  All bases are wave-uniform scalars; only the
   // two weight offsets and the scale offset are per lane.
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem4p;
-  const uint8_t* a_src = a.qop + (m0 / 32 * 3 + wave) * 1024;  // + kt * step_a + q * 4096, lane * 16
+  const uint8_t* a_src = a.qop + (m0 / 32 * (GA / 1024) + wave) * 1024;  // + kt * step_a + q * 4096, lane * 16
   const uint8_t* w_src = a.W + n0 * row_w;                      // + kt * 32, lane offsets below
   uint32_t voff_w[2];
 #pragma unroll
@@ -189,8 +221,8 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   const uint64_t s_inc = (uint64_t)(kb ? a.Npad : a.Mpad) * 2;                     // per K step
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
     const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 4096);
-    if (q < 6) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 4096, voff_a, dst);
-    else w4_lds_dma16(w_src + (int64_t)kt * 32, voff_w[q - 6], dst);
+    if (q < QA) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 4096, voff_a, dst);
+    else w4_lds_dma16(w_src + (int64_t)kt * 32, voff_w[q - QA], dst);
   };
   auto issue_scales = [&](int kt) {
     if (wave == 0)
@@ -213,12 +245,16 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // per-lane LDS offsets inside a stage (kb*32 + l32 == lane, so the 16-byte reads are linear in the lane)
   const uint32_t o_main = lane * 16, o_tail = lane * 8, o_sc = kb * 128 + l32 * 4;
   auto load_a = [&](int kt, int c, v8i (&fa)[4]) {  // component c of K step kt
-    const uint8_t* st = smem4p + (kt % NS) * STAGE + wm * (4 * 3072) + c * 1536;
+    const uint8_t* st = smem4p + (kt % NS) * STAGE + wm * (4 * GA) + c * CA;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 v = *reinterpret_cast<const uint4*>(st + i * 3072 + o_main);
-      const uint2 t = *reinterpret_cast<const uint2*>(st + i * 3072 + 1024 + o_tail);
-      fa[i] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, (int)t.x, (int)t.y, 0, 0};
+      const uint4 v = *reinterpret_cast<const uint4*>(st + i * GA + o_main);
+      if constexpr (A4) {
+        fa[i] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
+      } else {
+        const uint2 t = *reinterpret_cast<const uint2*>(st + i * GA + 1024 + o_tail);
+        fa[i] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, (int)t.x, (int)t.y, 0, 0};
+      }
     }
   };
   // weights and scale bytes of K step kt; sa / sb: byte i = scale of row fragment i / column fragment i
@@ -236,7 +272,7 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // the LDS reads that run under the block, so that the compiler's wait for this block's
   // operands (it cannot count LDS operations across the inline asm) covers no read just issued
   auto mfma_first = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb) {
-    acc[0][0] = mfma64_scaled<0, 0>(fa[0], fb[0], acc[0][0], sa, sb);
+    acc[0][0] = mfma64_scaled<0, 0, CBSZ>(fa[0], fb[0], acc[0][0], sa, sb);
   };
   // ISSUE: the load instructions of tile kt_issue go out between the MFMAs, one after every second
   // MFMA (in one burst after the barrier they fill the address queue, the waves leave the burst at
@@ -249,10 +285,10 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     __builtin_amdgcn_sched_barrier(0);                              \
   }
 #define MSD_W4_ROW(I)                                                                      \
-  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0>(fa[I], fb[0], acc[I][0], sa, sb); MSD_W4_POST(4 * I - 1) } \
-  acc[I][1] = mfma64_scaled<I, 1>(fa[I], fb[1], acc[I][1], sa, sb); MSD_W4_POST(4 * I)     \
-  acc[I][2] = mfma64_scaled<I, 2>(fa[I], fb[2], acc[I][2], sa, sb); MSD_W4_POST(4 * I + 1) \
-  acc[I][3] = mfma64_scaled<I, 3>(fa[I], fb[3], acc[I][3], sa, sb); MSD_W4_POST(4 * I + 2)
+  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0, CBSZ>(fa[I], fb[0], acc[I][0], sa, sb); MSD_W4_POST(4 * I - 1) } \
+  acc[I][1] = mfma64_scaled<I, 1, CBSZ>(fa[I], fb[1], acc[I][1], sa, sb); MSD_W4_POST(4 * I)     \
+  acc[I][2] = mfma64_scaled<I, 2, CBSZ>(fa[I], fb[2], acc[I][2], sa, sb); MSD_W4_POST(4 * I + 1) \
+  acc[I][3] = mfma64_scaled<I, 3, CBSZ>(fa[I], fb[3], acc[I][3], sa, sb); MSD_W4_POST(4 * I + 2)
     MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
 #undef MSD_W4_ROW
 #undef MSD_W4_POST
@@ -408,9 +444,14 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_dma_kernel<NS, true>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_dma_kernel<NS, false, true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  if (probe)
+  if (mv.e2m1)  // E2M1-grid components as native FP4 operands (the probe keeps the FP6 form)
+    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false, true>), dim3(grid), dim3(256),
+                       (size_t)NS * (16384 + 8192 + 1024), stream, a, tiles_m, tiles_n);
+  else if (probe)
     hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, true>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
   else
     hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
