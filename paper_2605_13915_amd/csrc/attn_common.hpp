@@ -49,11 +49,12 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
-// number of KV splits per (batch, KV head): enough workgroups to fill the chip, at least two rounds
+// number of KV splits per (batch, KV head): about two workgroups per CU (measured best: 256 as good, 384 and
+// 1024 worse), at least two rounds
 // of the four waves per split
 inline int attn_plan_nsplit(int B, int Hkv, int64_t L) {
   const int64_t pairs = (int64_t)B * Hkv;
-  int64_t ns = cdiv(1024, pairs);
+  int64_t ns = cdiv(512, pairs);
   int64_t max_by_len = L / (kAttnWaves * kTile * 2);
   if (max_by_len < 1) max_by_len = 1;
   if (ns > max_by_len) ns = max_by_len;
