@@ -1,23 +1,25 @@
-// W4A16 MSD GEMM for 32 activation rows or fewer when the weight stream is the bound (batched
+// W4A16 MSD GEMM for 5 to 128 activation rows, where the weight stream is the bound (batched
 // decode): paper Sec. 3.2.1 / Alg. 2 feeding Sec. 3.4.1 on v_mfma_scale_f32_32x32x64_f8f6f4.
 //
-// Two launches per call: the K-step-major decomposition of gemm_w4_prefill.hip (one group of 32
-// rows: 3 KB of FP6 operands and 64 scale bytes per K step of 64 elements), then this kernel.
+// Two launches per call: the K-step-major decomposition of gemm_w4_prefill.hip (per group of 32
+// rows 3 KB of FP6 operands per K step of 64 elements, plus one scale record per K step), then this
+// kernel.
 //
-// One workgroup = 4 waves = 128 output channels, the whole K range, all rows; a wave owns 32
-// channels (lane l: channel l%32, MX block l/32 of each K step).  K is walked in batches of U steps.
-// Per batch the workgroup stages 32 KB of weights (128 channels x 256 B, fetched 256 contiguous
-// bytes per channel and instruction) and the activation operands of the batch (U * 3 KB + scale
-// bytes, hot in L2, shared by the four waves) through LDS, double-buffered: global -> registers at
-// the start of a batch, registers -> LDS after its MFMAs, one barrier per batch.  Weight rows sit in
-// LDS with a 16-byte pad per 256 bytes, which makes both the staging stores (16 lanes per row) and
-// the fragment reads (32 rows at one K offset) conflict-free.  The weights' scale bytes (16 per
-// channel and batch) go straight to registers.  Both components accumulate into one fp32
-// accumulator of 16 registers (scale bytes alpha and alpha - shift).
+// One workgroup = 4 waves = 128 output channels, the whole K range, all rows (one, two or four
+// groups of 32); a wave owns 32 channels (lane l: channel l%32, MX block l/32 of each K step).  K is
+// walked in batches of U steps.  Per batch the workgroup stages the weights (128 channels x U*32
+// bytes, contiguous per channel and instruction) and the activation operands of the batch (hot in
+// L2, shared by the four waves) through LDS, double-buffered: global -> registers, registers -> LDS
+// one batch later (two register stages, so that two batches are in flight while a third is
+// multiplied), one barrier per batch.  Weight rows sit in LDS with a 16-byte pad, which makes both
+// the staging stores and the fragment reads (32 rows at one K offset) conflict-free.  The weights'
+// scale bytes (2U per channel and batch) go straight to registers.  Both components accumulate
+// into one fp32 accumulator of 16 registers per row group (scale bytes alpha and alpha - shift).
 // Why not weights straight into the B operand, as in the skinny kernel: with the 32 x 32 x 64
 // instruction only two lanes share a weight row, so every load instruction touches 32 rows with 32
 // bytes each -- measured 55 us (cacheable) to 68 us (non-temporal) at M = 32, N = 28672, K = 8192,
-// against the skinny kernel's re-reading of the activation operands per 16 channels at 78 us.
+// against 44 us with staging, and against 78 us for the skinny kernel, which re-reads the activation
+// operands for every 16 channels.
 #include "kernels.hpp"
 
 namespace msd {
