@@ -226,3 +226,41 @@ def truth_attn(q_bf16, Kc, Vc, k_scale, v_scale, scale_mode, kv_len=None):
                                 C.c_int(B), C.c_int(Hq), C.c_int(Hkv), C.c_int(d), _p(kl),
                                 C.c_int64(L), _p(out))
     return out
+
+
+def mla_decode(q_bf16, C_lat, scale, scale_mode, dv, sm_scale, kv_len=None, taps=False):
+    """Alg. 3 over a latent KV cache (Sec. 4.4, Sec. 7.3): q [B][Hq][dk] BF16 bits, C_lat [B][L][dk] int8 (keys =
+    whole rows, values = their first dv channels, one shared row per token for all heads), scale [B][L]
+    (per token) or [dk] (per channel), score scale sm_scale.  Returns out float32 [B][Hq][dv] (+ taps)."""
+    q = _c(q_bf16, np.uint16)
+    Cl = _c(C_lat, np.int8)
+    sc = _c(scale, np.float32)
+    B, Hq, dk = q.shape
+    _, L, ld = Cl.shape
+    assert Cl.shape[0] == B and ld >= dk and 0 < dv <= dk
+    assert sc.shape == ((B, L) if scale_mode == PER_TOKEN else (dk,))
+    kl = None if kv_len is None else _c(kv_len, np.int32)
+    out = np.empty((B, Hq, dv), np.float32)
+    t = {}
+    if taps:
+        t = dict(q1=np.empty((B, Hq, dk), np.int8), q2=np.empty((B, Hq, dk), np.int8),
+                 alpha_q=np.empty((B, Hq), np.float32), s1=np.zeros((B, Hq, L), np.int32),
+                 s2=np.zeros((B, Hq, L), np.int32))
+    lib().msd_oracle_mla_decode(_p(q), _p(Cl), C.c_int64(ld), _p(sc), C.c_int(scale_mode), C.c_int(B), C.c_int(Hq),
+                                C.c_int(dk), C.c_int(dv), C.c_double(sm_scale), _p(kl), C.c_int64(L), _p(out),
+                                _p(t.get("q1")), _p(t.get("q2")), _p(t.get("alpha_q")), _p(t.get("s1")),
+                                _p(t.get("s2")))
+    return (out, t) if taps else out
+
+
+def truth_mla(q_bf16, C_lat, scale, scale_mode, dv, sm_scale, kv_len=None):
+    q = _c(q_bf16, np.uint16)
+    Cl = _c(C_lat, np.int8)
+    sc = _c(scale, np.float32)
+    B, Hq, dk = q.shape
+    _, L, ld = Cl.shape
+    kl = None if kv_len is None else _c(kv_len, np.int32)
+    out = np.empty((B, Hq, dv), np.float64)
+    lib().msd_oracle_truth_mla(_p(q), _p(Cl), C.c_int64(ld), _p(sc), C.c_int(scale_mode), C.c_int(B), C.c_int(Hq),
+                               C.c_int(dk), C.c_int(dv), C.c_double(sm_scale), _p(kl), C.c_int64(L), _p(out))
+    return out

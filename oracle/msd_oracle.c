@@ -383,22 +383,26 @@ void msd_oracle_truth_gemm_w4(const uint16_t* x_bf16, int64_t M, int64_t K, int6
  * out: fp32 [B][Hq][d].  Taps (nullable): q codes [B][Hq][d] x2, alpha_q [B][Hq],
  * s1,s2 int32 [B][Hq][L], P float [B][Hq][L], p1,p2 int8 [B][Hq][L].
  */
-void msd_oracle_attn_decode(const uint16_t* q_bf16, const int8_t* Kc, const int8_t* Vc,
-                            const float* k_scale, const float* v_scale, int scale_mode, int B,
-                            int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, float* out,
-                            int8_t* tap_q1, int8_t* tap_q2, float* tap_alpha_q, int32_t* tap_s1,
-                            int32_t* tap_s2, float* tap_p, int8_t* tap_p1, int8_t* tap_p2) {
+/* The general form behind both entry points: query / key rows of d channels, value rows of dv
+ * channels, key row t of KV head g at Kc + ((b*Hkv + g)*L + t)*ldk (values likewise with ldv), scores
+ * multiplied by sm_scale.  Per-channel scales: k_scale [Hkv][d], v_scale [Hkv][dv]. */
+static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_t ldk, const int8_t* Vc,
+                                int64_t ldv, const float* k_scale, const float* v_scale, int scale_mode,
+                                int B, int Hq, int Hkv, int d, int dv, double sm_scale,
+                                const int32_t* kv_len, int64_t L, float* out, int8_t* tap_q1,
+                                int8_t* tap_q2, float* tap_alpha_q, int32_t* tap_s1, int32_t* tap_s2,
+                                float* tap_p, int8_t* tap_p1, int8_t* tap_p2) {
   const int G = Hq / Hkv;
-  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  const double inv_sqrt_d = sm_scale;
 #pragma omp parallel for schedule(dynamic)
   for (int bh = 0; bh < B * Hq; ++bh) {
     const int b = bh / Hq, hq = bh % Hq, g = hq / G;
     const int64_t len = kv_len ? kv_len[b] : L;
-    const int8_t* Kh = Kc + ((int64_t)(b * Hkv + g)) * L * d;
-    const int8_t* Vh = Vc + ((int64_t)(b * Hkv + g)) * L * d;
-    float* o = out + (int64_t)bh * d;
+    const int8_t* Kh = Kc + ((int64_t)(b * Hkv + g)) * L * ldk;
+    const int8_t* Vh = Vc + ((int64_t)(b * Hkv + g)) * L * ldv;
+    float* o = out + (int64_t)bh * dv;
     if (len <= 0) {
-      for (int c = 0; c < d; ++c) o[c] = 0.0f;
+      for (int c = 0; c < dv; ++c) o[c] = 0.0f;
       continue;
     }
     /* steps 1-2: absorb s_K (per-channel mode) and decompose the query row */
@@ -442,8 +446,8 @@ void msd_oracle_attn_decode(const uint16_t* q_bf16, const int8_t* Kc, const int8
     for (int64_t t = 0; t < len; ++t) {
       int64_t s1 = 0, s2 = 0;
       for (int c = 0; c < d; ++c) {
-        s1 += (int64_t)q1[c] * Kh[t * d + c];
-        s2 += (int64_t)q2[c] * Kh[t * d + c];
+        s1 += (int64_t)q1[c] * Kh[t * ldk + c];
+        s2 += (int64_t)q2[c] * Kh[t * ldk + c];
       }
       if (tap_s1) tap_s1[(int64_t)bh * L + t] = (int32_t)s1;
       if (tap_s2) tap_s2[(int64_t)bh * L + t] = (int32_t)s2;
@@ -504,33 +508,60 @@ void msd_oracle_attn_decode(const uint16_t* q_bf16, const int8_t* Kc, const int8
       if (tap_p2) tap_p2[(int64_t)bh * L + t] = p2[t];
     }
     /* steps 10-13: O1, O2 integer GEMVs, merge, V scale, normalise */
-    for (int c = 0; c < d; ++c) {
+    for (int c = 0; c < dv; ++c) {
       int64_t o1 = 0, o2 = 0;
       for (int64_t t = 0; t < len; ++t) {
-        o1 += (int64_t)p1[t] * Vh[t * d + c];
-        o2 += (int64_t)p2[t] * Vh[t * d + c];
+        o1 += (int64_t)p1[t] * Vh[t * ldv + c];
+        o2 += (int64_t)p2[t] * Vh[t * ldv + c];
       }
       double v = ap * (double)o1 + bp * (double)o2;
-      if (scale_mode == MSD_SCALE_PER_CHANNEL) v *= (double)v_scale[g * d + c];
+      if (scale_mode == MSD_SCALE_PER_CHANNEL) v *= (double)v_scale[g * dv + c];
       o[c] = (float)(v / ell);
     }
     free(qt); free(qf); free(q1); free(q2); free(S); free(P); free(p1); free(p2);
   }
 }
 
+void msd_oracle_attn_decode(const uint16_t* q_bf16, const int8_t* Kc, const int8_t* Vc,
+                            const float* k_scale, const float* v_scale, int scale_mode, int B,
+                            int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, float* out,
+                            int8_t* tap_q1, int8_t* tap_q2, float* tap_alpha_q, int32_t* tap_s1,
+                            int32_t* tap_s2, float* tap_p, int8_t* tap_p1, int8_t* tap_p2) {
+  attn_decode_general(q_bf16, Kc, d, Vc, d, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, d,
+                      1.0 / sqrt((double)d), kv_len, L, out, tap_q1, tap_q2, tap_alpha_q, tap_s1, tap_s2, tap_p,
+                      tap_p1, tap_p2);
+}
+
+/* ---------- the same for a latent KV cache (multi-head latent attention; Sec. 4.4, Sec. 7.3) ----
+ * One cached row of ld >= dk INT8 values per token serves as key (its first dk channels: the latent
+ * and the positional part) and as value (its first dv <= dk channels: the latent), shared by all Hq
+ * query heads of a batch entry: Alg. 3 with Hkv = 1, K = C, V = C[:, :dv].  q [B][Hq][dk];
+ * C [B][L][ld]; per-token scales scale[B][L] (the same scale for the key and the value reading of a
+ * row) or per-channel scales scale[dk] (its first dv entries scale the values); out [B][Hq][dv];
+ * the score scale sm_scale is the caller's (the absorbed form of such models does not use
+ * 1/sqrt(dk)).  Taps as above with d = dk. */
+void msd_oracle_mla_decode(const uint16_t* q_bf16, const int8_t* C, int64_t ld, const float* scale,
+                           int scale_mode, int B, int Hq, int dk, int dv, double sm_scale,
+                           const int32_t* kv_len, int64_t L, float* out, int8_t* tap_q1, int8_t* tap_q2,
+                           float* tap_alpha_q, int32_t* tap_s1, int32_t* tap_s2) {
+  attn_decode_general(q_bf16, C, ld, C, ld, scale, scale, scale_mode, B, Hq, 1, dk, dv, sm_scale, kv_len, L, out,
+                      tap_q1, tap_q2, tap_alpha_q, tap_s1, tap_s2, NULL, NULL, NULL);
+}
+
 /* fp64 truth: softmax(Q K_real^T / sqrt(d)) V_real with K_real, V_real the dequantised cache. */
-void msd_oracle_truth_attn(const uint16_t* q_bf16, const int8_t* Kc, const int8_t* Vc,
-                           const float* k_scale, const float* v_scale, int scale_mode, int B,
-                           int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, double* out) {
+static void truth_attn_general(const uint16_t* q_bf16, const int8_t* Kc, int64_t ldk, const int8_t* Vc,
+                               int64_t ldv, const float* k_scale, const float* v_scale, int scale_mode,
+                               int B, int Hq, int Hkv, int d, int dv, double sm_scale,
+                               const int32_t* kv_len, int64_t L, double* out) {
   const int G = Hq / Hkv;
-  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  const double inv_sqrt_d = sm_scale;
 #pragma omp parallel for schedule(dynamic)
   for (int bh = 0; bh < B * Hq; ++bh) {
     const int b = bh / Hq, hq = bh % Hq, g = hq / G;
     const int64_t len = kv_len ? kv_len[b] : L;
     const int64_t base = ((int64_t)(b * Hkv + g)) * L;
-    double* o = out + (int64_t)bh * d;
-    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    double* o = out + (int64_t)bh * dv;
+    for (int c = 0; c < dv; ++c) o[c] = 0.0;
     if (len <= 0) continue;
     double* S = (double*)malloc(sizeof(double) * (size_t)len);
     double smax = -INFINITY;
@@ -539,7 +570,7 @@ void msd_oracle_truth_attn(const uint16_t* q_bf16, const int8_t* Kc, const int8_
       for (int c = 0; c < d; ++c) {
         const double ks = scale_mode == MSD_SCALE_PER_TOKEN ? (double)k_scale[base + t]
                                                             : (double)k_scale[g * d + c];
-        s += (double)bf16_to_f32(q_bf16[(int64_t)bh * d + c]) * ks * (double)Kc[(base + t) * d + c];
+        s += (double)bf16_to_f32(q_bf16[(int64_t)bh * d + c]) * ks * (double)Kc[(base + t) * ldk + c];
       }
       S[t] = s * inv_sqrt_d;
       if (S[t] > smax) smax = S[t];
@@ -550,14 +581,28 @@ void msd_oracle_truth_attn(const uint16_t* q_bf16, const int8_t* Kc, const int8_
       ell += S[t];
     }
     for (int64_t t = 0; t < len; ++t)
-      for (int c = 0; c < d; ++c) {
+      for (int c = 0; c < dv; ++c) {
         const double vs = scale_mode == MSD_SCALE_PER_TOKEN ? (double)v_scale[base + t]
-                                                            : (double)v_scale[g * d + c];
-        o[c] += S[t] * vs * (double)Vc[(base + t) * d + c];
+                                                            : (double)v_scale[g * dv + c];
+        o[c] += S[t] * vs * (double)Vc[(base + t) * ldv + c];
       }
-    for (int c = 0; c < d; ++c) o[c] /= ell;
+    for (int c = 0; c < dv; ++c) o[c] /= ell;
     free(S);
   }
+}
+
+void msd_oracle_truth_attn(const uint16_t* q_bf16, const int8_t* Kc, const int8_t* Vc,
+                           const float* k_scale, const float* v_scale, int scale_mode, int B,
+                           int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, double* out) {
+  truth_attn_general(q_bf16, Kc, d, Vc, d, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, d,
+                     1.0 / sqrt((double)d), kv_len, L, out);
+}
+
+/* fp64 exact attention over the dequantised latent cache (see msd_oracle_mla_decode) */
+void msd_oracle_truth_mla(const uint16_t* q_bf16, const int8_t* C, int64_t ld, const float* scale,
+                          int scale_mode, int B, int Hq, int dk, int dv, double sm_scale,
+                          const int32_t* kv_len, int64_t L, double* out) {
+  truth_attn_general(q_bf16, C, ld, C, ld, scale, scale, scale_mode, B, Hq, 1, dk, dv, sm_scale, kv_len, L, out);
 }
 
 int msd_oracle_num_threads(void) {

@@ -202,3 +202,82 @@ def test_per_token_scales_are_applied_to_their_own_token():
     # a shifted scale index would be off by O(1)
     o_bad = oracle.attn_decode(q, Kc, Vc, ku, np.roll(vs, 1, axis=2), oracle.PER_TOKEN)
     assert np.linalg.norm(o_bad.astype(np.float64) - o4) / np.linalg.norm(o4) > 0.05
+
+
+# ------------------------------------------------------------------ latent KV cache (multi-head latent attention)
+
+def latent_case(seed, mode, B=2, Hq=6, L=80, dk=96, dv=64):
+    rng = np.random.default_rng(seed)
+    q = synth.queries(seed, B, Hq, dk)
+    if mode == oracle.PER_TOKEN:
+        Cl, sc, _, _ = synth.kv_cache_per_token(seed, B, 1, L, dk)
+        Cl, sc = Cl[:, 0], sc[:, 0]
+    else:
+        Cl, sc, _, _ = synth.kv_cache_per_channel(seed, B, 1, L, dk)
+        Cl, sc = Cl[:, 0], sc[0]
+    return q, Cl, sc, 1.0 / np.sqrt(48.0 + rng.integers(0, 3))
+
+
+@pytest.mark.parametrize("mode", [oracle.PER_TOKEN, oracle.PER_CHANNEL])
+def test_latent_cache_with_equal_widths_is_alg3_with_one_shared_kv_head(mode):
+    # dv = dk and sm_scale = 1/sqrt(dk): the latent form must be bit-identical to the GQA form with Hkv = 1
+    # and the cache passed as both K and V
+    q, Cl, sc, _ = latent_case(71, mode, dk=64, dv=64)
+    out, t = oracle.mla_decode(q, Cl, sc, mode, 64, 1.0 / np.sqrt(64.0), taps=True)
+    K4 = Cl[:, None]
+    s4 = sc[:, None] if mode == oracle.PER_TOKEN else sc[None]
+    ref, tr = oracle.attn_decode(q, K4, K4, s4, s4, mode, taps=True)
+    assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+    for k in ("q1", "q2", "s1", "s2"):
+        assert np.array_equal(t[k], tr[k])
+
+
+@pytest.mark.parametrize("mode", [oracle.PER_TOKEN, oracle.PER_CHANNEL])
+def test_latent_cache_scores_use_all_channels_values_the_first_dv(mode):
+    q, Cl, sc, sm = latent_case(72, mode)
+    B, Hq, dk = q.shape
+    dv = 64
+    out, t = oracle.mla_decode(q, Cl, sc, mode, dv, sm, taps=True)
+    # scores: integer dot products over all dk channels
+    for b in range(B):
+        assert np.array_equal(t["s1"][b].astype(np.int64), t["q1"][b].astype(np.int64) @ Cl[b].astype(np.int64).T)
+        assert np.array_equal(t["s2"][b].astype(np.int64), t["q2"][b].astype(np.int64) @ Cl[b].astype(np.int64).T)
+    # values: make the first dv channels of every row equal (the rest stays random): the output is that row,
+    # whatever the scores are
+    C2 = Cl.copy()
+    C2[:, :, :dv] = C2[:, :1, :dv]
+    sc2 = sc.copy()
+    if mode == oracle.PER_TOKEN:
+        sc2[:] = sc2[:, :1]
+    out2 = oracle.mla_decode(q, C2, sc2, mode, dv, sm)
+    for b in range(B):
+        row = C2[b, 0, :dv].astype(np.float64) * (sc2[b, 0] if mode == oracle.PER_TOKEN else sc2[:dv])
+        for h in range(Hq):
+            assert np.allclose(out2[b, h], row, rtol=2e-4, atol=2e-4 * np.abs(row).max())
+    # changing only the channels beyond dv changes the scores but must not enter the values
+    C3 = C2.copy()
+    C3[:, :, dv:] = -C3[:, :, dv:]
+    out3 = oracle.mla_decode(q, C3, sc2, mode, dv, sm)
+    for b in range(B):
+        row = C2[b, 0, :dv].astype(np.float64) * (sc2[b, 0] if mode == oracle.PER_TOKEN else sc2[:dv])
+        assert np.allclose(out3[b], row[None], rtol=2e-4, atol=2e-4 * np.abs(row).max())
+
+
+@pytest.mark.parametrize("mode", [oracle.PER_TOKEN, oracle.PER_CHANNEL])
+def test_latent_cache_against_numpy_softmax_and_fp64_truth(mode):
+    q, Cl, sc, sm = latent_case(73, mode, L=200)
+    B, Hq, dk = q.shape
+    dv = 64
+    kv_len = np.array([200, 131], np.int32)
+    truth = oracle.truth_mla(q, Cl, sc, mode, dv, sm, kv_len=kv_len)
+    qf = f32(q)
+    for b in range(B):
+        n = int(kv_len[b])
+        Kr = Cl[b, :n].astype(np.float64) * (sc[b, :n, None] if mode == oracle.PER_TOKEN else sc[None, :])
+        S = qf[b] @ Kr.T * sm
+        P = np.exp(S - S.max(axis=1, keepdims=True))
+        ref = (P / P.sum(axis=1, keepdims=True)) @ Kr[:, :dv]
+        assert np.allclose(truth[b], ref, rtol=1e-10, atol=1e-12)
+    out = oracle.mla_decode(q, Cl, sc, mode, dv, sm, kv_len=kv_len)
+    num = np.linalg.norm(out - truth)
+    assert num / np.linalg.norm(truth) < 1e-3
