@@ -222,6 +222,29 @@ int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
 size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
 
 /*
+ * One decode step of attention over an INT8 latent KV cache (multi-head latent attention; paper
+ * Sec. 4.2 / Alg. 3 with the shapes of Sec. 4.4 and Sec. 7.3).  One cached row per token serves
+ * every query head of a batch entry: its dk = 576 channels (512 latent + 64 positional) are the
+ * key, its first dv = 512 channels the value.
+ *   q_bf16 : [B][Hq][576] BF16 (the query in the cache's coordinates);  C : int8 [B][L][ld],
+ *            ld >= 576 and a multiple of 16, 16-byte aligned.
+ *   scale_mode MSD_PER_TOKEN : scale float [B][L], the scale of the whole cached row (it multiplies
+ *            score column t and, folded into P, value row t);  MSD_PER_CHANNEL : scale float [576],
+ *            folded into Q for the key reading, its first 512 entries multiply the output.
+ *   sm_scale : the factor on the scores before the softmax (> 0; such models do not use 1/sqrt(576)).
+ *   out    : [B][Hq][512] float or BF16.  kv_len, workspace, taps (q1, q2 int8 [B][Hq][576];
+ *            scale = alpha_Q [B][Hq]; acc1, acc2 = the integer score rows [B][Hq][L]) as for
+ *            msd_attn_decode_int8kv;  workspace of msd_mla_decode_int8kv_workspace_bytes(B, Hq, L).
+ * 8 query heads share a pass over the KV range; more heads take further passes.
+ * Errors: SHAPE (dk != 576, dv != 512, ld), INVALID_ARG, WORKSPACE.
+ */
+int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale,
+                          int scale_mode, int B, int Hq, int dk, int dv, float sm_scale,
+                          const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                          size_t workspace_bytes, const msd_debug_taps* taps, void* stream);
+size_t msd_mla_decode_int8kv_workspace_bytes(int B, int Hq, int64_t L);
+
+/*
  * Comparison kernel for msd_attn_decode_int8kv: the conventional path of paper Sec. 4.1 (K and V
  * lifted from INT8 to BF16 before Q K^T and P V), as one fused kernel.  Same arguments, layouts,
  * workspace size (msd_attn_decode_int8kv_workspace_bytes) and errors; taps are ignored.  K and V

@@ -65,6 +65,10 @@ def lib():
             f.restype = sz
         L.msd_attn_decode_int8kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, i64, vp, ci, vp, sz,
                                              vp, vp]
+        L.msd_mla_decode_int8kv.argtypes = [vp, vp, i64, vp, ci, ci, ci, ci, ci, C.c_float, vp, i64, vp, ci, vp, sz,
+                                            vp, vp]
+        L.msd_mla_decode_int8kv_workspace_bytes.argtypes = [ci, ci, i64]
+        L.msd_mla_decode_int8kv_workspace_bytes.restype = sz
         L.msd_moe_gemm_w8a16.argtypes = [vp, i64, i64, i64, vp, ci, vp, vp, i64, vp, ci, i64, vp, sz, vp]
         L.msd_moe_gemm_w4a16.argtypes = L.msd_moe_gemm_w8a16.argtypes
         L.msd_dequant_attn_decode_int8kv.argtypes = L.msd_attn_decode_int8kv.argtypes
@@ -75,7 +79,7 @@ def lib():
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
                      "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
                      "msd_gemm_w4a16_variant", "msd_dequant_attn_decode_int8kv", "msd_moe_gemm_w8a16",
-                     "msd_moe_gemm_w4a16"):
+                     "msd_moe_gemm_w4a16", "msd_mla_decode_int8kv"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -349,3 +353,37 @@ def msd_dequant_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len
     """Comparison kernel: K and V lifted to BF16 in registers, BF16 matrix instructions."""
     return msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len, out_dtype, False, out, ws, prepare,
                                   _fn="msd_dequant_attn_decode_int8kv")
+
+
+def msd_mla_decode_int8kv(q, C_lat, scale, scale_mode, sm_scale, kv_len=None, out_dtype=torch.float32, taps=False,
+                          out=None, ws=None, prepare=False):
+    """q: bf16 [B][Hq][576]; C_lat: int8 [B][L][ld] (keys = first 576 channels of a row, values = first 512);
+    scale: float [B][L] (per token) or [576] (per channel).  Returns out [B][Hq][512] (+ taps)."""
+    _dev(q, torch.bfloat16, "q"); _dev(C_lat, torch.int8, "C_lat"); _dev(scale, torch.float32, "scale")
+    B, Hq, dk = q.shape
+    _, Lmax, ld = C_lat.shape
+    assert q.is_contiguous() and C_lat.is_contiguous() and scale.is_contiguous()
+    L = lib()
+    dv = 512
+    if out is None:
+        out = torch.empty((B, Hq, dv), dtype=out_dtype, device=q.device)
+    if ws is None:
+        ws = workspace(L.msd_mla_decode_int8kv_workspace_bytes(B, Hq, Lmax), q.device)
+    tp = None
+    keep = {}
+    if taps:
+        keep = dict(q1=torch.empty((B, Hq, dk), dtype=torch.int8, device=q.device),
+                    q2=torch.empty((B, Hq, dk), dtype=torch.int8, device=q.device),
+                    scale=torch.empty((B, Hq), dtype=torch.float32, device=q.device),
+                    acc1=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device),
+                    acc2=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device))
+        tp = Taps(*(keep[k].data_ptr() for k in ("q1", "q2", "scale", "acc1", "acc2")))
+    if kv_len is not None:
+        _dev(kv_len, torch.int32, "kv_len")
+    args = (_ptr(q), _ptr(C_lat), ld, _ptr(scale), scale_mode, B, Hq, dk, dv, float(sm_scale), _ptr(kv_len), Lmax,
+            _ptr(out), _out_code(out.dtype), _ptr(ws), ws.numel(), C.byref(tp) if tp is not None else None, _stream())
+    if prepare:
+        return Prepared(L.msd_mla_decode_int8kv, args, (q, C_lat, scale, kv_len, out, ws, keep, tp),
+                        "msd_mla_decode_int8kv", out)
+    _check(L.msd_mla_decode_int8kv(*args), "msd_mla_decode_int8kv")
+    return (out, keep) if taps else out

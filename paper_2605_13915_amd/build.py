@@ -13,7 +13,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 OUT = os.path.join(HERE, "libmsd.so")
-SOURCES = ["msd_api.hip", "decompose.hip", "gemm_w8.hip", "gemm_w4.hip", "gemm_w4_prefill.hip", "gemm_w4_mid.hip", "attn.hip", "attn_dequant.hip", "dequant_gemm.hip",
+SOURCES = ["msd_api.hip", "decompose.hip", "gemm_w8.hip", "gemm_w4.hip", "gemm_w4_prefill.hip", "gemm_w4_mid.hip", "attn.hip", "attn_dequant.hip", "attn_mla.hip", "dequant_gemm.hip",
            "stream_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

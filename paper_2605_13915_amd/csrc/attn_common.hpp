@@ -49,6 +49,19 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
+// 4x4 byte transpose: in[t] = 4 channel bytes of token t; out[c] = 4 token bytes of channel c
+__device__ __forceinline__ void transpose4x4(uint32_t a, uint32_t b, uint32_t c, uint32_t d,
+                                             uint32_t (&o)[4]) {
+  const uint32_t ab_lo = __builtin_amdgcn_perm(b, a, 0x05010400u);
+  const uint32_t ab_hi = __builtin_amdgcn_perm(b, a, 0x07030602u);
+  const uint32_t cd_lo = __builtin_amdgcn_perm(d, c, 0x05010400u);
+  const uint32_t cd_hi = __builtin_amdgcn_perm(d, c, 0x07030602u);
+  o[0] = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x05040100u);
+  o[1] = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x07060302u);
+  o[2] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x05040100u);
+  o[3] = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
+}
+
 // number of KV splits per (batch, KV head): about two workgroups per CU (measured best: 256 as good, 384 and
 // 1024 worse), at least two rounds
 // of the four waves per split

@@ -152,6 +152,26 @@ size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
 // same arguments, split plan and workspace; taps are ignored
 int launch_attn_dequant(const AttnArgs& a, hipStream_t stream);
 
+// ---- attention over a latent KV cache (attn_mla.hip): keys = whole cached rows of 576 channels, values =
+// their first 512, one row per token shared by all Hq heads of a batch entry
+struct AttnMlaArgs {
+  const uint16_t* q;   // [B][Hq][576]
+  const int8_t* C;     // [B][L][ld]
+  int64_t ld;
+  const float* scale;  // per token [B][L] or per channel [576]
+  int scale_mode;
+  int B, Hq;
+  float sm_scale;
+  const int32_t* kv_len;
+  int64_t L;
+  void* out;           // [B][Hq][512]
+  int out_bf16;
+  void* workspace;
+  const msd_debug_taps* taps;
+};
+int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream);
+size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L);
+
 // ---- comparison kernels (dequant_gemm.hip)
 // ws / ws_bytes: optional scratch for the BF16 copy of the weights (dequant_workspace_bytes);
 // without it the fused single-kernel form runs whatever M is

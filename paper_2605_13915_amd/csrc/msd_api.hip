@@ -385,6 +385,43 @@ int msd_dequant_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const in
                     workspace, workspace_bytes, taps, stream);
 }
 
+size_t msd_mla_decode_int8kv_workspace_bytes(int B, int Hq, int64_t L) {
+  if (B <= 0 || Hq <= 0 || L < 0) return 256;
+  return attn_mla_workspace_bytes(B, Hq, L) + 256;
+}
+
+int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale, int scale_mode, int B,
+                          int Hq, int dk, int dv, float sm_scale, const int32_t* kv_len, int64_t L, void* out,
+                          int out_dtype, void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                          void* stream) {
+  if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
+  if (scale_mode != MSD_PER_TOKEN && scale_mode != MSD_PER_CHANNEL) return MSD_ERR_INVALID_ARG;
+  if (B < 0 || Hq <= 0 || L < 0) return MSD_ERR_SHAPE;
+  if (dk != 576 || dv != 512 || ld < dk || ld % 16 != 0 || L > (1 << 24)) return MSD_ERR_SHAPE;
+  if (!(sm_scale > 0.f)) return MSD_ERR_INVALID_ARG;
+  if (B == 0) return MSD_OK;
+  if (!q_bf16 || !out || (L > 0 && (!C || !scale))) return MSD_ERR_INVALID_ARG;
+  if (!aligned_to(C, 16) || !aligned_to(q_bf16, 2) || !aligned_to(scale, 4) || !aligned_to(out, out_dtype == MSD_F32 ? 4 : 2))
+    return MSD_ERR_INVALID_ARG;
+  const size_t need = attn_mla_workspace_bytes(B, Hq, L);
+  if (!workspace || !aligned_to(workspace, 256) || workspace_bytes < need) return MSD_ERR_WORKSPACE;
+  AttnMlaArgs a{};
+  a.q = (const uint16_t*)q_bf16;
+  a.C = C;
+  a.ld = ld;
+  a.scale = scale;
+  a.scale_mode = scale_mode;
+  a.B = B; a.Hq = Hq;
+  a.sm_scale = sm_scale;
+  a.kv_len = kv_len;
+  a.L = L;
+  a.out = out;
+  a.out_bf16 = out_dtype == MSD_BF16;
+  a.workspace = workspace;
+  a.taps = taps;
+  return launch_attn_mla(a, (hipStream_t)stream);
+}
+
 int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
                            const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
                            void* workspace, size_t workspace_bytes, const msd_debug_taps* /*taps*/,
