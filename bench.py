@@ -37,7 +37,7 @@ def main():
     ap.add_argument("--steps", type=int, default=48)
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", default="all", help="comma list of extra legs: cfg0,prefill,w4,attn,cmp,variants,nq,moe | all | none")
+    ap.add_argument("--extras", default="all", help="comma list of extra legs: cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
@@ -240,7 +240,7 @@ def main():
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
-        {"cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe"} if args.extras == "all" else set())
+        {"cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe", "mla"} if args.extras == "all" else set())
     try:
         import bench_extras
         extras = bench_extras.run(want, msd, synth, time_calls, dev)

@@ -304,6 +304,34 @@ def leg_cfg0(msd, synth, time_calls, dev):
             "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2)}
 
 
+def leg_mla(msd, synth, time_calls, dev):
+    """Attention over a latent KV cache (576-channel keys, 512-channel values from the same rows; paper Sec. 4.4 /
+    Sec. 7.3): B = 32 batch entries, Hq query heads on the one latent, per-token scales, cold cache.  Bytes = the
+    cached rows once; ops = executed INT8 multiply-adds x 2 (both components, key and value products)."""
+    B, d = 32, 576
+    out = []
+    for L in (4096, 32768):
+        n = 3 if L <= 4096 else 2
+        sets = [(_rand_i8((B, L, d), dev, 201 + r), torch.rand((B, L), device=dev) * 0.02 + 0.02) for r in range(n)]
+        for Hq in (16, 128):
+            if L > 4096 and Hq > 16:
+                continue
+            q = _bf16(synth.queries(synth.seed_for(9, Hq), B, Hq, d), dev)
+            o = torch.empty((B, Hq, 512), dtype=torch.float32, device=dev)
+            ws = torch.empty(msd.lib().msd_mla_decode_int8kv_workspace_bytes(B, Hq, L), dtype=torch.uint8, device=dev)
+            f = lambda i: msd.msd_mla_decode_int8kv(q, sets[i % n][0], sets[i % n][1], msd.MSD_PER_TOKEN,
+                                                    1.0 / 192.0 ** 0.5, out=o, ws=ws, prepare=True)
+            us = time_calls(f, 2 * n)
+            byts = B * L * d + 4 * B * L
+            ops = 2.0 * 2 * B * Hq * L * (576 + 512)
+            out.append({"B": B, "Hq": Hq, "L": L, "us": round(us, 1), "GBps": round(byts / us / 1e3, 1),
+                        "hbm_frac": round(byts / us / 1e3 / HBM, 4), "exec_TOPS": round(ops / us / 1e6, 1),
+                        "int8_mfma_frac": round(ops / us / 1e6 / INT8_TOPS, 4)})
+        del sets
+        torch.cuda.empty_cache()
+    return out
+
+
 def leg_cmp_decode(msd, synth, time_calls, dev):
     """Dequant comparison kernel on the W8A16 decode shapes (same cold-cache protocol)."""
     out = []
@@ -380,7 +408,7 @@ def leg_variants(msd, synth, time_calls, dev):
 def run(want, msd, synth, time_calls, dev):
     res = {}
     legs = {"cfg0": leg_cfg0, "prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
-            "variants": leg_variants, "nq": leg_nq_sweep, "moe": leg_moe}
+            "variants": leg_variants, "nq": leg_nq_sweep, "moe": leg_moe, "mla": leg_mla}
     for name, fn in legs.items():
         if name in want:
             try:

@@ -38,15 +38,23 @@ __device__ __forceinline__ v4i mfma_s8(v4i a, v4i b, v4i c) {
   return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float row16_max(float v) {  // over the 16 lanes sharing lane/16
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
+// The 16 lanes sharing lane/16 are one DPP row: an all-reduce over them is four rotate-and-combine
+// steps on the vector ALU (no LDS round trip).
+template <int N>
+__device__ __forceinline__ float row16_ror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, row16_ror<8>(v));
+  v = fmaxf(v, row16_ror<4>(v));
+  v = fmaxf(v, row16_ror<2>(v));
+  return fmaxf(v, row16_ror<1>(v));
 }
 __device__ __forceinline__ float row16_sum(float v) {
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
+  v += row16_ror<8>(v);
+  v += row16_ror<4>(v);
+  v += row16_ror<2>(v);
+  return v + row16_ror<1>(v);
 }
 
 // 4x4 byte transpose: in[t] = 4 channel bytes of token t; out[c] = 4 token bytes of channel c

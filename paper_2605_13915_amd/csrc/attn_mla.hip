@@ -4,24 +4,33 @@
 // its first 512 the value.  The steps are those of the grouped-query kernel (attn.hip) -- Q rows
 // decomposed once, S1 / S2 on v_mfma_i32_16x16x64_i8 with [Q1; Q2] stacked, merge, online softmax in
 // fp32, P decomposed with a scale that needs no reduction over P, O1 / O2 on the same instruction
-// with V transposed in registers -- reshaped for the wide rows:
-//   * the key product walks the 576 channels in nine 64-channel chunks, three chunks in flight;
-//   * the value product walks the 512 channels in four 128-channel slabs; the running output of the
-//     8 heads of a pass is 64 registers per lane;
-//   * the cached rows are read twice per tile (as key chunks, then as value slabs, in the two
-//     operand layouts); the second read hits L2, HBM sees each row once per pass;
-//   * 8 query heads share a pass over the KV range (one 16-row A fragment: 8 heads x 2 components);
-//     more heads are processed 8 at a time, re-decomposing their Q rows per pass.
-// The KV length is split over workgroups; a second kernel merges the split partials.
+// with V transposed in registers -- reshaped around the one thing that differs: every head reads the
+// same rows, so a tile of the cache is fetched once and shared.
+//   * A 64-token tile (36 KB) goes global -> registers -> LDS with fully coalesced 16-byte loads,
+//     fetched one tile ahead of its use; the key fragments (nine 64-channel chunks) and the value
+//     fragments (128-channel slabs, transposed 4x4 bytes at a time) are both read from that LDS copy,
+//     so HBM sees each cached row once per workgroup.
+//   * A wave owns 16 query heads (two 16-row A fragments: 8 heads x 2 components each) and keeps
+//     their running output in registers.  The four waves of a workgroup are laid out as
+//     HGW head groups x CH halves of the value channels x TS token streams (HGW*CH*TS = 4):
+//       up to 16 heads: 1 x 2 x 2 (two waves share a tile and split the value channels; two tiles in flight),
+//       up to 32 heads: 2 x 2 x 1,
+//       more:           4 x 1 x 1, 64 heads per workgroup, further heads over blockIdx.y.
+//     Waves that split the value channels both compute the (cheap) score product.
+//   * One workgroup per CU (up to 512 registers per lane); the KV length is split over workgroups
+//     and over the token streams inside one; every (split, stream) writes its own partial
+//     (m, l, O) and a second kernel merges them.
 #include "attn_common.hpp"
 
 namespace msd {
 
 namespace {
 
-constexpr int kLatK = 576;  // key channels (latent + positional)
-constexpr int kLatV = 512;  // value channels (latent)
-constexpr int kLatHeads = 8;
+constexpr int kLatK = 576;    // key channels (latent + positional)
+constexpr int kLatV = 512;    // value channels (latent)
+constexpr int kPitch = 592;   // LDS bytes per cached row: 16-byte key reads of 16 consecutive rows hit 64 distinct banks
+constexpr int kTileBytes = kTile * kPitch;
+constexpr int kPieces = kTile * (kLatK / 16);  // 16-byte pieces per tile
 
 struct MlaParams {
   const uint16_t* q;   // [B][Hq][576]
@@ -30,11 +39,12 @@ struct MlaParams {
   const int32_t* kv_len;
   int B, Hq;
   int64_t L, ld;
-  int nsplit;
+  int nsplit;  // workgroups along the KV length
+  int nparts;  // partial results per (batch, head): nsplit x token streams
   int64_t tokens_per_split;
   float sm_scale_log2;  // score scale times log2(e)
-  float* part_o;        // [B][nsplit][Hq][512]
-  float* part_m;        // [B][nsplit][Hq]
+  float* part_o;        // [B][nparts][Hq][512]
+  float* part_m;        // [B][nparts][Hq]
   float* part_l;
   void* out;
   int out_bf16;
@@ -45,25 +55,37 @@ struct MlaParams {
   int32_t* tap_s2;
 };
 
-template <bool PER_TOKEN>
+template <int HGW, int CH>
+struct MlaCfg {
+  static constexpr int kTS = kAttnWaves / (HGW * CH);  // token streams
+  static constexpr int kWS = HGW * CH;                 // waves sharing a tile
+  static constexpr int kSlabs = 4 / CH;                // 128-channel value slabs per wave
+  static constexpr int kLoads = kPieces / (64 * kWS);  // 16-byte pieces per lane per tile
+  static constexpr int kHeadsWg = 16 * HGW;
+  // tiles | sP[waves][2 frag][2 comp][8 heads][16] u32 | sAlpha[16]; the query codes of the prologue
+  // (2 x 16 x 576 bytes) alias the tiles
+  static constexpr size_t kLds = (size_t)kTS * kTileBytes + kAttnWaves * 2 * 2 * 8 * 64 + 64;
+  static_assert(kTS * kWS == kAttnWaves && kLoads * 64 * kWS == kPieces, "wave layout");
+  static_assert((size_t)kTS * kTileBytes >= 2 * 16 * kLatK, "query codes fit in the tile area");
+};
+
+template <bool PER_TOKEN, int HGW, int CH>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) {
-  constexpr int NH = kLatHeads;
-  // LDS (dynamic): sO[waves][NH][512] f32 | sQ[2][NH][576] int8 | sP[waves][2][NH][16] u32 | sAlpha[NH] |
-  // sM[waves][NH] | sL[waves][NH]
+  using Cfg = MlaCfg<HGW, CH>;
+  constexpr int TS = Cfg::kTS, WS = Cfg::kWS, NSL = Cfg::kSlabs, NLD = Cfg::kLoads;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mla[];
-  float(*sO)[NH][kLatV] = reinterpret_cast<float(*)[NH][kLatV]>(s_mla);
-  int8_t(*sQ)[NH][kLatK] = reinterpret_cast<int8_t(*)[NH][kLatK]>(s_mla + kAttnWaves * NH * kLatV * 4);
-  uint32_t(*sP)[2][NH][16] =
-      reinterpret_cast<uint32_t(*)[2][NH][16]>(s_mla + kAttnWaves * NH * kLatV * 4 + 2 * NH * kLatK);
-  float* sAlpha = reinterpret_cast<float*>(s_mla + kAttnWaves * NH * kLatV * 4 + 2 * NH * kLatK +
-                                           kAttnWaves * 2 * NH * 64);
-  float(*sM)[NH] = reinterpret_cast<float(*)[NH]>(sAlpha + NH);
-  float(*sL)[NH] = sM + kAttnWaves;
+  uint8_t* sTiles = s_mla;
+  int8_t(*sQ)[16][kLatK] = reinterpret_cast<int8_t(*)[16][kLatK]>(s_mla);
+  uint32_t(*sP)[2][2][8][16] = reinterpret_cast<uint32_t(*)[2][2][8][16]>(s_mla + TS * kTileBytes);
+  float* sAlpha = reinterpret_cast<float*>(s_mla + TS * kTileBytes + kAttnWaves * 2 * 2 * 8 * 64);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
+  const int ts = wave / WS, hg = (wave / CH) % HGW, ch = wave % CH;
   const int b = blockIdx.x / p.nsplit, split = blockIdx.x % p.nsplit;
   const int Hq = p.Hq;
+  const int hb = blockIdx.y * Cfg::kHeadsWg;  // first head of this workgroup
+  const int hw = hb + 16 * hg;                // first head of this wave
   int64_t len = p.kv_len ? (int64_t)p.kv_len[b] : p.L;
   len = max((int64_t)0, min(len, p.L));
   const int64_t t_begin = (int64_t)split * p.tokens_per_split;
@@ -71,21 +93,43 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
   const int64_t last = max(t_end - 1, (int64_t)0);
   const int8_t* Cb = p.C + (int64_t)b * p.L * p.ld;
   const float* sc_tok = p.scale + (int64_t)b * p.L;  // per-token mode only
-  const int64_t t_first = t_begin + (int64_t)wave * kTile;
   const v4i zero4 = {0, 0, 0, 0};
+  uint8_t* tile = sTiles + ts * kTileBytes;
+  const int n_iter = (int)((max(t_end - t_begin, (int64_t)0) + TS * kTile - 1) / (TS * kTile));  // same for every wave
 
   // A-fragment row of this lane: slot j&3 of head pair j>>2 = (head, component)
   const int slot = j & 3;
   const int row_head = (j >> 2) * 2 + (slot >> 1);
   const int row_comp = slot & 1;
 
-  for (int h0 = 0; h0 < Hq; h0 += NH) {  // one pass over the KV range per 8 heads
-    // ---- decompose the query rows of this pass (Alg. 3 steps 1-2), two heads per wave
-    for (int h = wave; h < NH; h += kAttnWaves) {
+  // ---- tile fetch: lane's pieces i*64*WS + (wave in stream)*64 + lane, piece = (token, 16-byte column)
+  v4i G[NLD];
+  float skn[4];
+  auto fetch = [&](int it) __attribute__((always_inline)) {
+    const int64_t t0 = t_begin + ((int64_t)it * TS + ts) * kTile;
+    if (t0 < t_end) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int piece = i * 64 * WS + (wave % WS) * 64 + lane;
+        const int tok = piece / 36, col = piece % 36;
+        G[i] = *reinterpret_cast<const v4i*>(Cb + min(t0 + tok, last) * p.ld + 16 * col);
+      }
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) skn[tt] = PER_TOKEN ? sc_tok[min(t0 + 16 * tt + j, last)] : 1.f;
+    }
+  };
+  if (n_iter > 0) fetch(0);
+
+  // ---- decompose the query rows (Alg. 3 steps 1-2): 16 heads at a time, four per wave
+  v4i qa[2][9];
+  float aq[2][2], bq[2][2];
+  for (int hgi = 0; hgi < HGW; ++hgi) {
+    for (int h = wave; h < 16; h += kAttnWaves) {
       float x[9];
       float mx = 0.f;
-      const bool live_head = h0 + h < Hq;
-      const int64_t qrow = (int64_t)b * Hq + h0 + h;
+      const int head = hb + 16 * hgi + h;
+      const bool live_head = head < Hq;
+      const int64_t qrow = (int64_t)b * Hq + head;
 #pragma unroll
       for (int i = 0; i < 9; ++i) {
         const int c = lane + 64 * i;
@@ -117,89 +161,121 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
       }
     }
     __syncthreads();
-    v4i qa[9];
+    if (hgi == hg) {
 #pragma unroll
-    for (int s = 0; s < 9; ++s) qa[s] = *reinterpret_cast<const v4i*>(&sQ[row_comp][row_head][64 * s + 16 * g]);
-    float aq[2], bq[2], m_run[2], l_run[2], o_run[4][2][8];
+      for (int mg = 0; mg < 2; ++mg) {
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      aq[hh] = sAlpha[g * 2 + hh];
-      bq[hh] = __fdiv_rn(aq[hh], 254.0f);
-      m_run[hh] = -INFINITY;
-      l_run[hh] = 0.f;
-#pragma unroll
-      for (int sl = 0; sl < 4; ++sl)
-#pragma unroll
-        for (int c = 0; c < 8; ++c) o_run[sl][hh][c] = 0.f;
-    }
-
-    for (int64_t t0 = t_first; t0 < t_end; t0 += kAttnWaves * kTile) {
-      bool live[4];
-      int64_t tokK[4];
-      float sk[4];
-#pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        live[tt] = t0 + 16 * tt + j < t_end;
-        tokK[tt] = min(t0 + 16 * tt + j, last);
-        sk[tt] = PER_TOKEN ? sc_tok[tokK[tt]] : 1.f;
-      }
-      // ---- (2) S1, S2: nine 64-channel chunks, three at a time
-      v4i sd[4] = {zero4, zero4, zero4, zero4};
-#pragma unroll
-      for (int s3 = 0; s3 < 3; ++s3) {
-        v4i kx[3][4];
-#pragma unroll
-        for (int u = 0; u < 3; ++u)
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt)
-            kx[u][tt] = __builtin_nontemporal_load(
-                reinterpret_cast<const v4i*>(Cb + tokK[tt] * p.ld + 64 * (3 * s3 + u) + 16 * g));
-#pragma unroll
-        for (int u = 0; u < 3; ++u)
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt) sd[tt] = mfma_s8(qa[3 * s3 + u], kx[u][tt], sd[tt]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (p.tap_s1) {
+        for (int s = 0; s < 9; ++s)
+          qa[mg][s] = *reinterpret_cast<const v4i*>(&sQ[row_comp][8 * mg + row_head][64 * s + 16 * g]);
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-          const int head = h0 + g * 2 + hh;
+          aq[mg][hh] = sAlpha[8 * mg + g * 2 + hh];
+          bq[mg][hh] = __fdiv_rn(aq[mg][hh], 254.0f);
+        }
+      }
+    }
+    __syncthreads();  // the codes are overwritten by the next head group, then by the first tile
+  }
+
+  float m_run[2][2], l_run[2][2], o_run[2][NSL][2][8];  // o_run[mg][slab][hh][c]: head 8 mg + 2 g + hh, channel 128 slab + 16 c + j
+  float unit = 1.f;
+#pragma unroll
+  for (int mg = 0; mg < 2; ++mg)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      m_run[mg][hh] = -INFINITY;
+      l_run[mg][hh] = 0.f;
+#pragma unroll
+      for (int sl = 0; sl < NSL; ++sl)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o_run[mg][sl][hh][c] = 0.f;
+    }
+
+  for (int it = 0; it < n_iter; ++it) {
+    const int64_t t0 = t_begin + ((int64_t)it * TS + ts) * kTile;
+    const bool tile_live = t0 < t_end;  // uniform over the waves of a stream
+    if (it > 0) __syncthreads();        // every wave is done reading the previous tile
+    float sk[4];
+    if (tile_live) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int piece = i * 64 * WS + (wave % WS) * 64 + lane;
+        *reinterpret_cast<v4i*>(tile + (piece / 36) * kPitch + 16 * (piece % 36)) = G[i];
+      }
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) sk[tt] = skn[tt];
+    }
+    __syncthreads();
+    if (it + 1 < n_iter) fetch(it + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!tile_live) continue;
+
+    bool live[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) live[tt] = t0 + 16 * tt + j < t_end;
+    // ---- (2) S1, S2 over the nine 64-channel chunks; a key fragment serves both A fragments
+    v4i sd[2][4] = {{zero4, zero4, zero4, zero4}, {zero4, zero4, zero4, zero4}};
+#pragma unroll
+    for (int s = 0; s < 9; ++s)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const v4i kf = *reinterpret_cast<const v4i*>(tile + (16 * tt + j) * kPitch + 64 * s + 16 * g);
+#pragma unroll
+        for (int mg = 0; mg < 2; ++mg) sd[mg][tt] = mfma_s8(qa[mg][s], kf, sd[mg][tt]);
+      }
+    if (p.tap_s1 && ch == 0) {
+#pragma unroll
+      for (int mg = 0; mg < 2; ++mg)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int head = hw + 8 * mg + g * 2 + hh;
           if (head < Hq) {
             const int64_t row = ((int64_t)b * Hq + head) * p.L;
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt)
               if (live[tt]) {
-                p.tap_s1[row + t0 + 16 * tt + j] = sd[tt][2 * hh];
-                p.tap_s2[row + t0 + 16 * tt + j] = sd[tt][2 * hh + 1];
+                p.tap_s1[row + t0 + 16 * tt + j] = sd[mg][tt][2 * hh];
+                p.tap_s2[row + t0 + 16 * tt + j] = sd[mg][tt][2 * hh + 1];
               }
           }
         }
-      }
-      // scale of the P decomposition: alpha_P = top/127, top a bound on P (times the value scale)
-      float sv[4];
+    }
+    // scale of the P decomposition: alpha_P = top/127, top a bound on P (times the value scale)
+    float sv[4];
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) sv[tt] = live[tt] ? sk[tt] : 0.f;
-      float top = 1.f;
-      if (PER_TOKEN) top = row16_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
-      const float to_code = top > 0.f ? __fdiv_rn(127.0f, top) : 0.f;
-      const float from_code = top * (1.0f / 127.0f);
-      // ---- (3)+(4) merge, online softmax, decompose P
-      float corr[2];
-      uint32_t pk1[2], pk2[2];
+    for (int tt = 0; tt < 4; ++tt) sv[tt] = live[tt] ? sk[tt] : 0.f;
+    float top = 1.f;
+    if (PER_TOKEN) top = row16_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
+    const float to_code = top > 0.f ? __fdiv_rn(127.0f, top) : 0.f;
+    // The running output is kept in units of `unit` = alpha_P / 254 of the latest tile, so that a tile's
+    // contribution is the integer 254 O1 + O2 itself; a change of alpha_P rescales the running output
+    // together with the softmax correction.
+    float rescale = 1.f;
+    if (top > 0.f) {
+      const float unit_new = top * (1.0f / (127.0f * 254.0f));
+      rescale = __fdiv_rn(unit, unit_new);
+      unit = unit_new;
+    }
+    // ---- (3)+(4) merge, online softmax, decompose P
+    float corr[2][2];
+#pragma unroll
+    for (int mg = 0; mg < 2; ++mg)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         float s[4];
         float mx = -INFINITY;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
-          const float v = (aq[hh] * (float)sd[tt][2 * hh] + bq[hh] * (float)sd[tt][2 * hh + 1]) * (p.sm_scale_log2 * sk[tt]);
+          const float v = (aq[mg][hh] * (float)sd[mg][tt][2 * hh] + bq[mg][hh] * (float)sd[mg][tt][2 * hh + 1]) *
+                          (p.sm_scale_log2 * sk[tt]);
           s[tt] = live[tt] ? v : -INFINITY;
           mx = fmaxf(mx, s[tt]);
         }
         mx = row16_max(mx);
-        const float m_new = fmaxf(m_run[hh], mx);
-        corr[hh] = __builtin_amdgcn_exp2f(m_run[hh] - m_new);
-        m_run[hh] = m_new;
+        const float m_new = fmaxf(m_run[mg][hh], mx);
+        const float cr = __builtin_amdgcn_exp2f(m_run[mg][hh] - m_new);
+        corr[mg][hh] = cr * rescale;
+        m_run[mg][hh] = m_new;
         float lsum = 0.f;
         uint32_t w1 = 0, w2 = 0;
 #pragma unroll
@@ -212,155 +288,193 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
           w1 |= ((uint32_t)(int)c1 & 0xFFu) << (8 * tt);
           w2 |= ((uint32_t)(int)c2 & 0xFFu) << (8 * tt);
         }
-        l_run[hh] = l_run[hh] * corr[hh] + lsum;
-        pk1[hh] = w1;
-        pk2[hh] = w2;
+        l_run[mg][hh] = l_run[mg][hh] * cr + lsum;
+        sP[wave][mg][0][g * 2 + hh][j] = w1;
+        sP[wave][mg][1][g * 2 + hh][j] = w2;
       }
+    __builtin_amdgcn_wave_barrier();
+    v4i pa[2];
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        sP[wave][0][g * 2 + hh][j] = pk1[hh];
-        sP[wave][1][g * 2 + hh][j] = pk2[hh];
-      }
-      __builtin_amdgcn_wave_barrier();
-      const v4i pa = *reinterpret_cast<const v4i*>(&sP[wave][row_comp][row_head][4 * g]);
-      __builtin_amdgcn_wave_barrier();
-      // ---- (5) O1, O2 over four 128-channel slabs of the same rows
-      int64_t tokV[4][4];
+    for (int mg = 0; mg < 2; ++mg) pa[mg] = *reinterpret_cast<const v4i*>(&sP[wave][mg][row_comp][row_head][4 * g]);
+    __builtin_amdgcn_wave_barrier();
+    // ---- (5) O1, O2 over this wave's 128-channel slabs of the same rows.  The B operand (64 tokens x 16
+    // channels) comes from two transposing LDS reads: in each 16-lane group, source lane s points at 8
+    // channel bytes of one token, and lane n receives byte n&7 of the eight source lanes 2k + (n>>3); with
+    // even source lanes on channels 0..7 and odd ones on channels 8..15 of token(k), lane n ends up with
+    // channel n of eight tokens.  token(k) follows the packing of the P codes (word 4g+i, byte t <-> token
+    // 16 t + 4 g + i).
+    const int vk = j >> 1;
+    const uint8_t* vsrc = tile + (16 * (vk & 3) + 4 * g + (vk >> 2)) * kPitch + 8 * (j & 1);
 #pragma unroll
-      for (int jq = 0; jq < 4; ++jq)
+    for (int sl = 0; sl < NSL; ++sl) {
+      const int slab = ch * NSL + sl;
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) tokV[jq][tt] = min(t0 + 16 * tt + 4 * g + jq, last) * p.ld + 8 * j;
+      for (int c = 0; c < 8; ++c) {
+        const uint8_t* src = vsrc + 128 * slab + 16 * c;
+        const v2i r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)src);
+        const v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)(src + 2 * kPitch));
+        const v4i bf = {r0[0], r0[1], r1[0], r1[1]};
 #pragma unroll
-      for (int sl = 0; sl < 4; ++sl) {
-        v2i vr[4][4];  // [jq][tt]: channels 128 sl + 8j .. +7 of token 16 tt + 4 g + jq
-#pragma unroll
-        for (int jq = 0; jq < 4; ++jq)
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt)
-            vr[jq][tt] = *reinterpret_cast<const v2i*>(Cb + tokV[jq][tt] + 128 * sl);
-        uint32_t vb[8][4];
-#pragma unroll
-        for (int jq = 0; jq < 4; ++jq) {
-          uint32_t lo[4], hi[4];
-          transpose4x4((uint32_t)vr[jq][0][0], (uint32_t)vr[jq][1][0], (uint32_t)vr[jq][2][0], (uint32_t)vr[jq][3][0], lo);
-          transpose4x4((uint32_t)vr[jq][0][1], (uint32_t)vr[jq][1][1], (uint32_t)vr[jq][2][1], (uint32_t)vr[jq][3][1], hi);
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            vb[c][jq] = lo[c];
-            vb[4 + c][jq] = hi[c];
-          }
-        }
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          const v4i bf = {(int)vb[c][0], (int)vb[c][1], (int)vb[c][2], (int)vb[c][3]};
-          const v4i od = mfma_s8(pa, bf, zero4);
+        for (int mg = 0; mg < 2; ++mg) {
+          const v4i od = mfma_s8(pa[mg], bf, zero4);
 #pragma unroll
           for (int hh = 0; hh < 2; ++hh) {
-            const float ot = from_code * ((float)od[2 * hh] + (float)od[2 * hh + 1] * (1.0f / 254.0f));
-            o_run[sl][hh][c] = o_run[sl][hh][c] * corr[hh] + ot;
+            const int merged = __mul24(od[2 * hh], 254) + od[2 * hh + 1];  // |O1| < 2^21: exact
+            o_run[mg][sl][hh][c] = o_run[mg][sl][hh][c] * corr[mg][hh] + (float)merged;
           }
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
+  }
 
-    // ---- merge the waves of this workgroup, write the split's partial (m, l, O) of these heads
+  // ---- this wave's partial (m, l, O) of its 16 heads and its value channels
+  const int part = split * TS + ts;
+#pragma unroll
+  for (int mg = 0; mg < 2; ++mg)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-      const float lt = row16_sum(l_run[hh]);
-      const int hs = g * 2 + hh;
-      if (j == 0) {
-        sM[wave][hs] = m_run[hh];
-        sL[wave][hs] = lt;
-      }
+      const float l = row16_sum(l_run[mg][hh]);
+      const int head = hw + 8 * mg + g * 2 + hh;
+      if (head >= Hq) continue;
+      if (p.nparts == 1) {
+        const int64_t orow = (int64_t)b * Hq + head;
+        const float norm = l > 0.f ? __fdiv_rn(unit, l) : 0.f;
 #pragma unroll
-      for (int sl = 0; sl < 4; ++sl)
+        for (int sl = 0; sl < NSL; ++sl)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) sO[wave][hs][128 * sl + 8 * j + c] = o_run[sl][hh][c];
-    }
-    __syncthreads();
-    const int nh_here = min(NH, Hq - h0);
-    for (int idx = tid; idx < nh_here * kLatV; idx += kAttnWaves * 64) {
-      const int hl = idx / kLatV, c = idx % kLatV;
-      const int h = h0 + hl;
-      float ms = -INFINITY;
-#pragma unroll
-      for (int w = 0; w < kAttnWaves; ++w) ms = fmaxf(ms, sM[w][hl]);
-      float o = 0.f, l = 0.f;
-#pragma unroll
-      for (int w = 0; w < kAttnWaves; ++w) {
-        const float wgt = (sM[w][hl] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sM[w][hl] - ms);
-        o += sO[w][hl][c] * wgt;
-        l += sL[w][hl] * wgt;
-      }
-      if (p.nsplit == 1) {
-        float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
-        if (!PER_TOKEN) v *= p.scale[c];
-        const int64_t orow = (int64_t)b * Hq + h;
-        if (p.out_bf16)
-          reinterpret_cast<uint16_t*>(p.out)[orow * kLatV + c] = f32_to_bf16_bits(v);
-        else
-          reinterpret_cast<float*>(p.out)[orow * kLatV + c] = v;
+          for (int c = 0; c < 8; ++c) {
+            const int col = 128 * (ch * NSL + sl) + 16 * c + j;
+            float v = o_run[mg][sl][hh][c] * norm;
+            if (!PER_TOKEN) v *= p.scale[col];
+            if (p.out_bf16)
+              reinterpret_cast<uint16_t*>(p.out)[orow * kLatV + col] = f32_to_bf16_bits(v);
+            else
+              reinterpret_cast<float*>(p.out)[orow * kLatV + col] = v;
+          }
       } else {
-        const int64_t pr = ((int64_t)b * p.nsplit + split) * Hq + h;
-        p.part_o[pr * kLatV + c] = o;
-        if (c == 0) {
-          p.part_m[pr] = ms;
+        const int64_t pr = ((int64_t)b * p.nparts + part) * Hq + head;
+#pragma unroll
+        for (int sl = 0; sl < NSL; ++sl)
+#pragma unroll
+          for (int c = 0; c < 8; ++c)
+            p.part_o[pr * kLatV + 128 * (ch * NSL + sl) + 16 * c + j] = o_run[mg][sl][hh][c] * unit;
+        if (ch == 0 && j == 0) {
+          p.part_m[pr] = m_run[mg][hh];
           p.part_l[pr] = l;
         }
       }
     }
-    __syncthreads();  // sQ and the merge buffers are rewritten by the next pass
-  }
 }
 
-// Merge the split partials (Alg. 3 last two steps; see attn.hip for why this is a launch of its own).
+// Merge the partials (Alg. 3 last two steps; see attn.hip for why this is a launch of its own).  One
+// workgroup per (batch, head): the weights of the parts are formed once in LDS, then every thread sums
+// four channels over the parts with independent 16-byte loads.
+constexpr int kMlaMaxParts = 64;
 __global__ __launch_bounds__(128) void attn_mla_combine_kernel(MlaParams p, int per_channel) {
+  __shared__ float s_w[kMlaMaxParts];
+  __shared__ float s_linv;
   const int row = blockIdx.x;  // b*Hq + h
   const int b = row / p.Hq, h = row % p.Hq;
-  const int64_t base = (int64_t)b * p.nsplit * p.Hq + h;
-  float ms = -INFINITY;
-  for (int s = 0; s < p.nsplit; ++s) ms = fmaxf(ms, p.part_m[base + (int64_t)s * p.Hq]);
-  float l = 0.f;
-  for (int s = 0; s < p.nsplit; ++s) {
-    const float mv = p.part_m[base + (int64_t)s * p.Hq];
-    if (mv != -INFINITY) l += p.part_l[base + (int64_t)s * p.Hq] * __builtin_amdgcn_exp2f(mv - ms);
+  const int64_t base = (int64_t)b * p.nparts * p.Hq + h;
+  if (threadIdx.x < 64) {
+    const int s = threadIdx.x;
+    const bool have = s < p.nparts;
+    const float m = have ? p.part_m[base + (int64_t)s * p.Hq] : -INFINITY;
+    const float lp = have ? p.part_l[base + (int64_t)s * p.Hq] : 0.f;
+    const float ms = wave_max(m);
+    const float w = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - ms);
+    float l = lp * w;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, 64);
+    s_w[s] = w;
+    if (s == 0) s_linv = l > 0.f ? __fdiv_rn(1.0f, l) : 0.f;
   }
-  for (int c = threadIdx.x; c < kLatV; c += 128) {
-    float o = 0.f;
-    for (int s = 0; s < p.nsplit; ++s) {
-      const int64_t pr = base + (int64_t)s * p.Hq;
-      const float mv = p.part_m[pr];
-      if (mv != -INFINITY) o += p.part_o[pr * kLatV + c] * __builtin_amdgcn_exp2f(mv - ms);
-    }
-    float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
-    if (per_channel) v *= p.scale[c];
+  __syncthreads();
+  const int c = 4 * threadIdx.x;
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+  for (int s = 0; s < p.nparts; ++s) {
+    const float w = s_w[s];
+    const float4 v = *reinterpret_cast<const float4*>(p.part_o + (base + (int64_t)s * p.Hq) * kLatV + c);
+    o.x += v.x * w; o.y += v.y * w; o.z += v.z * w; o.w += v.w * w;
+  }
+  const float linv = s_linv;
+  float r[4] = {o.x * linv, o.y * linv, o.z * linv, o.w * linv};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (per_channel) r[i] *= p.scale[c + i];
     if (p.out_bf16)
-      reinterpret_cast<uint16_t*>(p.out)[(int64_t)row * kLatV + c] = f32_to_bf16_bits(v);
+      reinterpret_cast<uint16_t*>(p.out)[(int64_t)row * kLatV + c + i] = f32_to_bf16_bits(r[i]);
     else
-      reinterpret_cast<float*>(p.out)[(int64_t)row * kLatV + c] = v;
+      reinterpret_cast<float*>(p.out)[(int64_t)row * kLatV + c + i] = r[i];
   }
 }
 
-int mla_nsplit(int B, int64_t L) { return attn_plan_nsplit(B, 1, L); }
+// Wave layout by head count, KV splits (about kMlaTargetWgs workgroups: one per CU holds the registers
+// and LDS of this kernel; every token stream of a split gets at least two tiles) and partial count.
+constexpr int kMlaTargetWgs = 256;
+struct MlaPlan {
+  int layout;  // 0: 1x2x2, 1: 2x2x1, 2: 4x1x1
+  int ts, heads_wg, head_blocks, nsplit, nparts;
+  int64_t tokens_per_split;
+};
+MlaPlan mla_plan(int B, int Hq, int64_t L) {
+  MlaPlan pl{};
+  pl.layout = Hq <= 16 ? 0 : (Hq <= 32 ? 1 : 2);
+  pl.ts = pl.layout == 0 ? 2 : 1;
+  pl.heads_wg = pl.layout == 0 ? 16 : (pl.layout == 1 ? 32 : 64);
+  pl.head_blocks = (Hq + pl.heads_wg - 1) / pl.heads_wg;
+  int64_t ns = cdiv((int64_t)kMlaTargetWgs, (int64_t)B * pl.head_blocks);
+  const int64_t max_by_len = max((int64_t)1, L / (2 * pl.ts * kTile));
+  ns = max((int64_t)1, min(min(ns, max_by_len), (int64_t)(64 / pl.ts)));
+  pl.nsplit = (int)ns;
+  pl.nparts = pl.nsplit * pl.ts;
+  int64_t tps = cdiv(L > 0 ? L : 1, ns);
+  pl.tokens_per_split = cdiv(tps, (int64_t)pl.ts * kTile) * (pl.ts * kTile);
+  return pl;
+}
+
+template <bool PER_TOKEN, int HGW, int CH>
+int launch_mla_layout(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
+  constexpr size_t lds = MlaCfg<HGW, CH>::kLds;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_kernel<PER_TOKEN, HGW, CH>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  const dim3 grid((unsigned)((int64_t)p.B * p.nsplit), (unsigned)pl.head_blocks);
+  hipLaunchKernelGGL((attn_mla_kernel<PER_TOKEN, HGW, CH>), grid, dim3(kAttnWaves * 64), lds, stream, p);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+template <bool PER_TOKEN>
+int launch_mla_mode(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
+  switch (pl.layout) {
+    case 0: return launch_mla_layout<PER_TOKEN, 1, 2>(p, pl, stream);
+    case 1: return launch_mla_layout<PER_TOKEN, 2, 2>(p, pl, stream);
+    default: return launch_mla_layout<PER_TOKEN, 4, 1>(p, pl, stream);
+  }
+}
 
 }  // namespace
 
 size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L) {
-  const size_t rows = (size_t)B * Hq * mla_nsplit(B, L);
+  const size_t rows = (size_t)B * Hq * mla_plan(B, Hq, L).nparts;
   return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
 }
 
 int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
+  const MlaPlan pl = mla_plan(a.B, a.Hq, a.L);
   MlaParams p{};
   p.q = a.q; p.C = a.C; p.scale = a.scale; p.kv_len = a.kv_len;
   p.B = a.B; p.Hq = a.Hq; p.L = a.L; p.ld = a.ld;
-  p.nsplit = mla_nsplit(a.B, a.L);
-  int64_t tps = cdiv(a.L > 0 ? a.L : 1, p.nsplit);
-  tps = cdiv(tps, kAttnWaves * kTile) * (kAttnWaves * kTile);
-  p.tokens_per_split = tps;
+  p.nsplit = pl.nsplit;
+  p.nparts = pl.nparts;
+  p.tokens_per_split = pl.tokens_per_split;
   p.sm_scale_log2 = a.sm_scale * kLog2e;
-  const size_t rows = (size_t)a.B * a.Hq * p.nsplit;
+  const size_t rows = (size_t)a.B * a.Hq * pl.nparts;
   char* ws = (char*)a.workspace;
   p.part_o = (float*)ws;
   p.part_m = (float*)(ws + align_up(rows * kLatV * 4, 256));
@@ -376,24 +490,10 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
     if (!(p.tap_q1 && p.tap_q2 && p.tap_alpha)) p.tap_q1 = p.tap_q2 = nullptr, p.tap_alpha = nullptr;
     if (!(p.tap_s1 && p.tap_s2)) p.tap_s1 = p.tap_s2 = nullptr;
   }
-  constexpr size_t lds = (size_t)kAttnWaves * kLatHeads * kLatV * 4 + 2 * kLatHeads * kLatK +
-                         kAttnWaves * 2 * kLatHeads * 64 + kLatHeads * 4 + 2 * kAttnWaves * kLatHeads * 4;
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;
-  static bool attr_set = false;
-  if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_kernel<true>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_kernel<false>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
-  const dim3 grid((unsigned)((int64_t)a.B * p.nsplit));
-  if (per_token)
-    hipLaunchKernelGGL((attn_mla_kernel<true>), grid, dim3(kAttnWaves * 64), lds, stream, p);
-  else
-    hipLaunchKernelGGL((attn_mla_kernel<false>), grid, dim3(kAttnWaves * 64), lds, stream, p);
-  MSD_LAUNCH_CHECK();
-  if (p.nsplit > 1) {
+  const int rc = per_token ? launch_mla_mode<true>(p, pl, stream) : launch_mla_mode<false>(p, pl, stream);
+  if (rc != MSD_OK) return rc;
+  if (p.nparts > 1) {
     hipLaunchKernelGGL(attn_mla_combine_kernel, dim3((unsigned)(a.B * a.Hq)), dim3(128), 0, stream, p,
                        per_token ? 0 : 1);
     MSD_LAUNCH_CHECK();

@@ -32,12 +32,16 @@ def _case(seed, mode, B, Hq, L, ld=576):
 CASES = [
     # B, Hq, L, mode, kv_len, ld
     (2, 8, 96, "token", None, 576),
-    (1, 16, 700, "token", None, 576),         # two passes of 8 heads
+    (1, 16, 700, "token", None, 576),          # two token streams, ragged last tile
     (3, 5, 300, "token", [300, 0, 77], 576),   # ragged lengths incl. an empty entry, partial head group
     (2, 8, 260, "channel", None, 576),
-    (1, 20, 2048, "channel", [1900], 576),     # several KV splits, three passes (8 + 8 + 4 heads)
+    (1, 16, 2300, "token", [2070], 576),       # several KV splits; the last split leaves one stream without a tile
+    (1, 20, 2048, "channel", [1900], 576),     # 32-head layout, partly filled; several KV splits
+    (2, 32, 333, "token", None, 576),          # 32-head layout, full
     (2, 4, 130, "token", None, 640),           # padded cache rows (ld > 576)
-    (1, 128, 520, "token", None, 576),         # 128 heads on one latent: 16 passes
+    (1, 40, 450, "channel", None, 576),        # 64-head layout, partly filled
+    (1, 72, 200, "token", [131], 576),         # two head blocks, the second partly filled
+    (1, 128, 520, "token", None, 576),         # 128 heads on one latent: two head blocks of 64
 ]
 
 
