@@ -206,6 +206,7 @@ int msd_moe_gemm_w4a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
  *   q_bf16 : [B][Hq][d] BF16;  K, V: int8 [B][Hkv][L][d];  query head h reads KV head h/(Hq/Hkv).
  *   scale_mode MSD_PER_CHANNEL: k_scale, v_scale float [Hkv][d]; s_K is folded into Q before
  *       the decomposition, s_V multiplies the output (Alg. 3 as printed), alpha_P = 1/127.
+ *       Both arrays are required (INVALID_ARG if NULL) even when L == 0.
  *   scale_mode MSD_PER_TOKEN : k_scale, v_scale float [B][Hkv][L]; s_K[t] multiplies score
  *       column t in the merge; P_t*s_V[t] is decomposed with alpha_P = (max s_V over the KV tile)/127.
  *   kv_len : nullable int32 [B], valid tokens per batch entry (<= L); NULL means L everywhere.
@@ -230,12 +231,15 @@ size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int
  *            ld >= 576 and a multiple of 16, 16-byte aligned.
  *   scale_mode MSD_PER_TOKEN : scale float [B][L], the scale of the whole cached row (it multiplies
  *            score column t and, folded into P, value row t);  MSD_PER_CHANNEL : scale float [576],
- *            folded into Q for the key reading, its first 512 entries multiply the output.
+ *            folded into Q for the key reading, its first 512 entries multiply the output
+ *            (required even when L == 0).
  *   sm_scale : the factor on the scores before the softmax (> 0; such models do not use 1/sqrt(576)).
  *   out    : [B][Hq][512] float or BF16.  kv_len, workspace, taps (q1, q2 int8 [B][Hq][576];
  *            scale = alpha_Q [B][Hq]; acc1, acc2 = the integer score rows [B][Hq][L]) as for
  *            msd_attn_decode_int8kv;  workspace of msd_mla_decode_int8kv_workspace_bytes(B, Hq, L).
- * 8 query heads share a pass over the KV range; more heads take further passes.
+ * Every 64-token tile of the cache is fetched once per workgroup and shared by up to 64 heads;
+ * more heads are spread over further workgroups.  Three launches: query decomposition, the
+ * main kernel, the merge of the KV splits.
  * Errors: SHAPE (dk != 576, dv != 512, ld), INVALID_ARG, WORKSPACE.
  */
 int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale,

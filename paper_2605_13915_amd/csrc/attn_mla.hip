@@ -43,6 +43,9 @@ struct MlaParams {
   int nparts;  // partial results per (batch, head): nsplit x token streams
   int64_t tokens_per_split;
   float sm_scale_log2;  // score scale times log2(e)
+  int8_t* qc1;          // [B][Hq][576] query codes, first and second component (workspace)
+  int8_t* qc2;
+  float* qalpha;        // [B][Hq]
   float* part_o;        // [B][nparts][Hq][512]
   float* part_m;        // [B][nparts][Hq]
   float* part_l;
@@ -62,12 +65,47 @@ struct MlaCfg {
   static constexpr int kSlabs = 4 / CH;                // 128-channel value slabs per wave
   static constexpr int kLoads = kPieces / (64 * kWS);  // 16-byte pieces per lane per tile
   static constexpr int kHeadsWg = 16 * HGW;
-  // tiles | sP[waves][2 frag][2 comp][8 heads][16] u32 | sAlpha[16]; the query codes of the prologue
-  // (2 x 16 x 576 bytes) alias the tiles
-  static constexpr size_t kLds = (size_t)kTS * kTileBytes + kAttnWaves * 2 * 2 * 8 * 64 + 64;
+  // tiles | sP[waves][2 frag][2 comp][8 heads][16] u32
+  static constexpr size_t kLds = (size_t)kTS * kTileBytes + kAttnWaves * 2 * 2 * 8 * 64;
   static_assert(kTS * kWS == kAttnWaves && kLoads * 64 * kWS == kPieces, "wave layout");
-  static_assert((size_t)kTS * kTileBytes >= 2 * 16 * kLatK, "query codes fit in the tile area");
 };
+
+// Alg. 3 steps 1-2 for the query rows: one wave per (batch, head) row of 576 channels; the per-channel
+// key scale, if any, is absorbed into the row first.  Codes and alpha_Q go to the workspace, where every
+// workgroup of the main kernel picks up its A fragments.
+__global__ __launch_bounds__(256) void mla_q_decompose_kernel(MlaParams p, int per_channel) {
+  const int lane = threadIdx.x & 63;
+  const int64_t qrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (qrow >= (int64_t)p.B * p.Hq) return;
+  float x[9];
+  float mx = 0.f;
+#pragma unroll
+  for (int i = 0; i < 9; ++i) {
+    const int c = lane + 64 * i;
+    x[i] = __uint_as_float((uint32_t)p.q[qrow * kLatK + c] << 16);
+    if (per_channel) x[i] *= p.scale[c];
+    mx = fmaxf(mx, fabsf(x[i]));
+  }
+  mx = wave_max(mx);
+  const float alpha = mx > 0.f ? __fdiv_rn(mx, 127.0f) : 0.f;
+  const float beta = __fdiv_rn(alpha, 254.0f);
+#pragma unroll
+  for (int i = 0; i < 9; ++i) {
+    const int c = lane + 64 * i;
+    int c1 = 0, c2 = 0;
+    if (mx > 0.f) int8_codes(x[i], alpha, beta, c1, c2);
+    p.qc1[qrow * kLatK + c] = (int8_t)c1;
+    p.qc2[qrow * kLatK + c] = (int8_t)c2;
+    if (p.tap_q1) {
+      p.tap_q1[qrow * kLatK + c] = (int8_t)c1;
+      p.tap_q2[qrow * kLatK + c] = (int8_t)c2;
+    }
+  }
+  if (lane == 0) {
+    p.qalpha[qrow] = alpha;
+    if (p.tap_q1) p.tap_alpha[qrow] = alpha;
+  }
+}
 
 template <bool PER_TOKEN, int HGW, int CH>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) {
@@ -75,9 +113,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
   constexpr int TS = Cfg::kTS, WS = Cfg::kWS, NSL = Cfg::kSlabs, NLD = Cfg::kLoads;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mla[];
   uint8_t* sTiles = s_mla;
-  int8_t(*sQ)[16][kLatK] = reinterpret_cast<int8_t(*)[16][kLatK]>(s_mla);
   uint32_t(*sP)[2][2][8][16] = reinterpret_cast<uint32_t(*)[2][2][8][16]>(s_mla + TS * kTileBytes);
-  float* sAlpha = reinterpret_cast<float*>(s_mla + TS * kTileBytes + kAttnWaves * 2 * 2 * 8 * 64);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
@@ -120,61 +156,20 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
   };
   if (n_iter > 0) fetch(0);
 
-  // ---- decompose the query rows (Alg. 3 steps 1-2): 16 heads at a time, four per wave
+  // ---- the query codes of this wave's 16 heads (decomposed by mla_q_decompose_kernel), as A fragments
   v4i qa[2][9];
   float aq[2][2], bq[2][2];
-  for (int hgi = 0; hgi < HGW; ++hgi) {
-    for (int h = wave; h < 16; h += kAttnWaves) {
-      float x[9];
-      float mx = 0.f;
-      const int head = hb + 16 * hgi + h;
-      const bool live_head = head < Hq;
-      const int64_t qrow = (int64_t)b * Hq + head;
 #pragma unroll
-      for (int i = 0; i < 9; ++i) {
-        const int c = lane + 64 * i;
-        x[i] = 0.f;
-        if (live_head) {
-          x[i] = __uint_as_float((uint32_t)p.q[qrow * kLatK + c] << 16);
-          if (!PER_TOKEN) x[i] *= p.scale[c];  // absorb the per-channel key scale into Q
-        }
-        mx = fmaxf(mx, fabsf(x[i]));
-      }
-      mx = wave_max(mx);
-      const float alpha = mx > 0.f ? __fdiv_rn(mx, 127.0f) : 0.f;
-      const float beta = __fdiv_rn(alpha, 254.0f);
+  for (int mg = 0; mg < 2; ++mg) {
+    const int64_t qrow = (int64_t)b * Hq + min(hw + 8 * mg + row_head, Hq - 1);  // rows past Hq: results unused
+    const int8_t* src = (row_comp ? p.qc2 : p.qc1) + qrow * kLatK + 16 * g;
 #pragma unroll
-      for (int i = 0; i < 9; ++i) {
-        const int c = lane + 64 * i;
-        int c1 = 0, c2 = 0;
-        if (mx > 0.f) int8_codes(x[i], alpha, beta, c1, c2);
-        sQ[0][h][c] = (int8_t)c1;
-        sQ[1][h][c] = (int8_t)c2;
-        if (live_head && split == 0 && p.tap_q1) {
-          p.tap_q1[qrow * kLatK + c] = (int8_t)c1;
-          p.tap_q2[qrow * kLatK + c] = (int8_t)c2;
-        }
-      }
-      if (lane == 0) {
-        sAlpha[h] = alpha;
-        if (live_head && split == 0 && p.tap_q1) p.tap_alpha[qrow] = alpha;
-      }
+    for (int s = 0; s < 9; ++s) qa[mg][s] = *reinterpret_cast<const v4i*>(src + 64 * s);
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      aq[mg][hh] = p.qalpha[(int64_t)b * Hq + min(hw + 8 * mg + g * 2 + hh, Hq - 1)];
+      bq[mg][hh] = __fdiv_rn(aq[mg][hh], 254.0f);
     }
-    __syncthreads();
-    if (hgi == hg) {
-#pragma unroll
-      for (int mg = 0; mg < 2; ++mg) {
-#pragma unroll
-        for (int s = 0; s < 9; ++s)
-          qa[mg][s] = *reinterpret_cast<const v4i*>(&sQ[row_comp][8 * mg + row_head][64 * s + 16 * g]);
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          aq[mg][hh] = sAlpha[8 * mg + g * 2 + hh];
-          bq[mg][hh] = __fdiv_rn(aq[mg][hh], 254.0f);
-        }
-      }
-    }
-    __syncthreads();  // the codes are overwritten by the next head group, then by the first tile
   }
 
   float m_run[2][2], l_run[2][2], o_run[2][NSL][2][8];  // o_run[mg][slab][hh][c]: head 8 mg + 2 g + hh, channel 128 slab + 16 c + j
@@ -215,14 +210,24 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
     for (int tt = 0; tt < 4; ++tt) live[tt] = t0 + 16 * tt + j < t_end;
     // ---- (2) S1, S2 over the nine 64-channel chunks; a key fragment serves both A fragments
     v4i sd[2][4] = {{zero4, zero4, zero4, zero4}, {zero4, zero4, zero4, zero4}};
+    {
+      // software pipeline over the 36 (chunk, token group) fragments: LDS reads three fragments ahead
+      constexpr int NKF = 36, DEPTH = 4;
+      v4i kf[DEPTH];
+      const uint8_t* ksrc = tile + j * kPitch + 16 * g;
+      auto kload = [&](int i) __attribute__((always_inline)) {
+        kf[i % DEPTH] = *reinterpret_cast<const v4i*>(ksrc + (16 * (i % 4)) * kPitch + 64 * (i / 4));
+      };
 #pragma unroll
-    for (int s = 0; s < 9; ++s)
+      for (int i = 0; i < DEPTH - 1; ++i) kload(i);
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        const v4i kf = *reinterpret_cast<const v4i*>(tile + (16 * tt + j) * kPitch + 64 * s + 16 * g);
+      for (int i = 0; i < NKF; ++i) {
+        if (i + DEPTH - 1 < NKF) kload(i + DEPTH - 1);
 #pragma unroll
-        for (int mg = 0; mg < 2; ++mg) sd[mg][tt] = mfma_s8(qa[mg][s], kf, sd[mg][tt]);
+        for (int mg = 0; mg < 2; ++mg) sd[mg][i % 4] = mfma_s8(qa[mg][i / 4], kf[i % DEPTH], sd[mg][i % 4]);
+        __builtin_amdgcn_sched_barrier(0);
       }
+    }
     if (p.tap_s1 && ch == 0) {
 #pragma unroll
       for (int mg = 0; mg < 2; ++mg)
@@ -305,25 +310,39 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
     // 16 t + 4 g + i).
     const int vk = j >> 1;
     const uint8_t* vsrc = tile + (16 * (vk & 3) + 4 * g + (vk >> 2)) * kPitch + 8 * (j & 1);
+    // Software pipeline over the 16-channel blocks: LDS reads two blocks ahead, the two MFMAs of a block
+    // issued one block before their results are merged on the vector ALU.
+    constexpr int NST = NSL * 8;
+    v2i rb[3][2];
+    v4i acc[2][2];
+    auto vload = [&](int st) __attribute__((always_inline)) {
+      const uint8_t* src = vsrc + 128 * (ch * NSL + st / 8) + 16 * (st % 8);
+      rb[st % 3][0] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)src);
+      rb[st % 3][1] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)(src + 2 * kPitch));
+    };
+    vload(0);
+    vload(1);
 #pragma unroll
-    for (int sl = 0; sl < NSL; ++sl) {
-      const int slab = ch * NSL + sl;
+    for (int st = 0; st <= NST; ++st) {
+      if (st + 2 < NST) vload(st + 2);
+      if (st < NST) {
+        const v4i bf = {rb[st % 3][0][0], rb[st % 3][0][1], rb[st % 3][1][0], rb[st % 3][1][1]};
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        const uint8_t* src = vsrc + 128 * slab + 16 * c;
-        const v2i r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)src);
-        const v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)(src + 2 * kPitch));
-        const v4i bf = {r0[0], r0[1], r1[0], r1[1]};
+        for (int mg = 0; mg < 2; ++mg) acc[st & 1][mg] = mfma_s8(pa[mg], bf, zero4);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // the merge below covers the latency of the MFMAs above
+      if (st >= 1) {
+        const int sl = (st - 1) / 8, c = (st - 1) % 8;
 #pragma unroll
-        for (int mg = 0; mg < 2; ++mg) {
-          const v4i od = mfma_s8(pa[mg], bf, zero4);
+        for (int mg = 0; mg < 2; ++mg)
 #pragma unroll
           for (int hh = 0; hh < 2; ++hh) {
+            const v4i od = acc[(st - 1) & 1][mg];
             const int merged = __mul24(od[2 * hh], 254) + od[2 * hh + 1];  // |O1| < 2^21: exact
-            o_run[mg][sl][hh][c] = o_run[mg][sl][hh][c] * corr[mg][hh] + (float)merged;
+            o_run[mg][sl][hh][c] = __builtin_fmaf(o_run[mg][sl][hh][c], corr[mg][hh], (float)merged);
           }
-        }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
@@ -462,7 +481,9 @@ int launch_mla_mode(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
 
 size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L) {
   const size_t rows = (size_t)B * Hq * mla_plan(B, Hq, L).nparts;
-  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
+  const size_t qrows = (size_t)B * Hq;
+  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256) + 2 * align_up(qrows * kLatK, 256) +
+         align_up(qrows * 4, 256);
 }
 
 int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
@@ -479,6 +500,11 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
   p.part_o = (float*)ws;
   p.part_m = (float*)(ws + align_up(rows * kLatV * 4, 256));
   p.part_l = (float*)(ws + align_up(rows * kLatV * 4, 256) + align_up(rows * 4, 256));
+  char* qws = ws + align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
+  const size_t qrows = (size_t)a.B * a.Hq;
+  p.qc1 = (int8_t*)qws;
+  p.qc2 = (int8_t*)(qws + align_up(qrows * kLatK, 256));
+  p.qalpha = (float*)(qws + 2 * align_up(qrows * kLatK, 256));
   p.out = a.out;
   p.out_bf16 = a.out_bf16;
   if (a.taps) {
@@ -491,6 +517,9 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
     if (!(p.tap_s1 && p.tap_s2)) p.tap_s1 = p.tap_s2 = nullptr;
   }
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;
+  hipLaunchKernelGGL(mla_q_decompose_kernel, dim3((unsigned)cdiv((int64_t)qrows, 4)), dim3(256), 0, stream, p,
+                     per_token ? 0 : 1);
+  MSD_LAUNCH_CHECK();
   const int rc = per_token ? launch_mla_mode<true>(p, pl, stream) : launch_mla_mode<false>(p, pl, stream);
   if (rc != MSD_OK) return rc;
   if (p.nparts > 1) {

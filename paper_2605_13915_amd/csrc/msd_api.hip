@@ -347,6 +347,7 @@ static int attn_entry(bool dequant, const void* q_bf16, const int8_t* K, const i
   if (d != 128 || Hq % Hkv != 0 || Hq / Hkv > 64 || L > (1 << 24)) return MSD_ERR_SHAPE;
   if (B == 0) return MSD_OK;
   if (!q_bf16 || !out || (L > 0 && (!K || !V || !k_scale || !v_scale))) return MSD_ERR_INVALID_ARG;
+  if (scale_mode == MSD_PER_CHANNEL && (!k_scale || !v_scale)) return MSD_ERR_INVALID_ARG;  // read even when L == 0
   if (!aligned_to(K, 16) || !aligned_to(V, 16) || !aligned_to(q_bf16, 16) || !aligned_to(out, 16))
     return MSD_ERR_INVALID_ARG;
   const size_t need = attn_workspace_bytes(B, Hq, Hkv, d, L);
@@ -401,6 +402,7 @@ int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const
   if (!(sm_scale > 0.f)) return MSD_ERR_INVALID_ARG;
   if (B == 0) return MSD_OK;
   if (!q_bf16 || !out || (L > 0 && (!C || !scale))) return MSD_ERR_INVALID_ARG;
+  if (scale_mode == MSD_PER_CHANNEL && !scale) return MSD_ERR_INVALID_ARG;  // read even when L == 0
   if (!aligned_to(C, 16) || !aligned_to(q_bf16, 2) || !aligned_to(scale, 4) || !aligned_to(out, out_dtype == MSD_F32 ? 4 : 2))
     return MSD_ERR_INVALID_ARG;
   const size_t need = attn_mla_workspace_bytes(B, Hq, L);
