@@ -3,23 +3,24 @@
 // One cached row per token serves every query head of a batch entry: its 576 channels are the key,
 // its first 512 the value.  The steps are those of the grouped-query kernel (attn.hip) -- Q rows
 // decomposed once, S1 / S2 on v_mfma_i32_16x16x64_i8 with [Q1; Q2] stacked, merge, online softmax in
-// fp32, P decomposed with a scale that needs no reduction over P, O1 / O2 on the same instruction
-// with V transposed in registers -- reshaped around the one thing that differs: every head reads the
-// same rows, so a tile of the cache is fetched once and shared.
+// fp32, P decomposed with a scale that needs no reduction over P, O1 / O2 on the same instruction --
+// reshaped around the one thing that differs: every head reads the same rows, so a tile of the cache
+// is fetched once and shared.
 //   * A 64-token tile (36 KB) goes global -> registers -> LDS with fully coalesced 16-byte loads,
 //     fetched one tile ahead of its use; the key fragments (nine 64-channel chunks) and the value
-//     fragments (128-channel slabs, transposed 4x4 bytes at a time) are both read from that LDS copy,
-//     so HBM sees each cached row once per workgroup.
-//   * A wave owns 16 query heads (two 16-row A fragments: 8 heads x 2 components each) and keeps
-//     their running output in registers.  The four waves of a workgroup are laid out as
-//     HGW head groups x CH halves of the value channels x TS token streams (HGW*CH*TS = 4):
-//       up to 16 heads: 1 x 2 x 2 (two waves share a tile and split the value channels; two tiles in flight),
-//       up to 32 heads: 2 x 2 x 1,
-//       more:           4 x 1 x 1, 64 heads per workgroup, further heads over blockIdx.y.
-//     Waves that split the value channels both compute the (cheap) score product.
-//   * One workgroup per CU (up to 512 registers per lane); the KV length is split over workgroups
-//     and over the token streams inside one; every (split, stream) writes its own partial
-//     (m, l, O) and a second kernel merges them.
+//     fragments (16-channel blocks, through the transposing LDS read) both come from that LDS copy,
+//     so HBM sees each cached row once per workgroup.  Both fragment streams are software-pipelined
+//     by hand (reads a few fragments ahead of the MFMAs, MFMAs one step ahead of the merge).
+//   * The query rows are decomposed once by a small kernel of their own; a wave owns 8 MG query heads
+//     (MG 16-row A fragments: 8 heads x 2 components each) and keeps their running output in
+//     registers, in units of alpha_P / 254 so that a tile contributes the exact integer 254 O1 + O2.
+//   * The NW waves of a workgroup are laid out as HGW head groups x CH parts of the value channels x
+//     TS token streams (HGW*CH*TS = NW); waves that split the value channels both compute the (cheap)
+//     score product.  In use (MG = 1, NW = 8, two waves per SIMD):
+//       up to 16 heads: 2 x 2 x 2,   up to 32 heads: 4 x 2 x 1,
+//       more:           8 x 1 x 1, 64 heads per workgroup, further heads over blockIdx.y.
+//   * One workgroup per CU; the KV length is split over workgroups and over the token streams inside
+//     one; every (split, stream) writes its own partial (m, l, O) and a last kernel merges them.
 #include "attn_common.hpp"
 
 namespace msd {
@@ -28,8 +29,13 @@ namespace {
 
 constexpr int kLatK = 576;    // key channels (latent + positional)
 constexpr int kLatV = 512;    // value channels (latent)
-constexpr int kPitch = 592;   // LDS bytes per cached row: 16-byte key reads of 16 consecutive rows hit 64 distinct banks
-constexpr int kTileBytes = kTile * kPitch;
+// LDS image of a tile: row r at r * kPitch + 16 * (r / 16).  The pitch makes the 16-byte key reads of 16
+// consecutive rows hit distinct banks; the extra 16 bytes per 16 rows do the same for the transposing
+// value reads, whose eight source rows per lane group are 16 apart (the pitch alone, a multiple of 16
+// bytes, would put them all on one bank).
+constexpr int kPitch = 592;
+constexpr int kTileBytes = kTile * kPitch + 64;
+__device__ __forceinline__ int tile_row(int r) { return r * kPitch + 16 * (r >> 4); }
 constexpr int kPieces = kTile * (kLatK / 16);  // 16-byte pieces per tile
 
 struct MlaParams {
@@ -58,16 +64,18 @@ struct MlaParams {
   int32_t* tap_s2;
 };
 
-template <int HGW, int CH>
+template <int MG, int NW, int HGW, int CH>
 struct MlaCfg {
-  static constexpr int kTS = kAttnWaves / (HGW * CH);  // token streams
+  static constexpr int kTS = NW / (HGW * CH);          // token streams
   static constexpr int kWS = HGW * CH;                 // waves sharing a tile
   static constexpr int kSlabs = 4 / CH;                // 128-channel value slabs per wave
-  static constexpr int kLoads = kPieces / (64 * kWS);  // 16-byte pieces per lane per tile
-  static constexpr int kHeadsWg = 16 * HGW;
-  // tiles | sP[waves][2 frag][2 comp][8 heads][16] u32
-  static constexpr size_t kLds = (size_t)kTS * kTileBytes + kAttnWaves * 2 * 2 * 8 * 64;
-  static_assert(kTS * kWS == kAttnWaves && kLoads * 64 * kWS == kPieces, "wave layout");
+  static constexpr int kLoads = (kPieces + 64 * kWS - 1) / (64 * kWS);  // 16-byte pieces per lane per tile
+  static constexpr int kHeadsWave = 8 * MG;
+  static constexpr int kHeadsWg = kHeadsWave * HGW;
+  // tiles | sP[waves][MG frag][2 comp][8 heads][16] u32
+  static constexpr size_t kLds = (size_t)kTS * kTileBytes + NW * MG * 2 * 8 * 64;
+  static_assert(kTS * kWS == NW && kTS >= 1, "wave layout");
+  static_assert(kLds <= 160 * 1024, "LDS");
 };
 
 // Alg. 3 steps 1-2 for the query rows: one wave per (batch, head) row of 576 channels; the per-channel
@@ -107,13 +115,13 @@ __global__ __launch_bounds__(256) void mla_q_decompose_kernel(MlaParams p, int p
   }
 }
 
-template <bool PER_TOKEN, int HGW, int CH>
-__global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) {
-  using Cfg = MlaCfg<HGW, CH>;
+template <bool PER_TOKEN, int MG, int NW, int HGW, int CH>
+__global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
+  using Cfg = MlaCfg<MG, NW, HGW, CH>;
   constexpr int TS = Cfg::kTS, WS = Cfg::kWS, NSL = Cfg::kSlabs, NLD = Cfg::kLoads;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mla[];
   uint8_t* sTiles = s_mla;
-  uint32_t(*sP)[2][2][8][16] = reinterpret_cast<uint32_t(*)[2][2][8][16]>(s_mla + TS * kTileBytes);
+  uint32_t(*sP)[MG][2][8][16] = reinterpret_cast<uint32_t(*)[MG][2][8][16]>(s_mla + TS * kTileBytes);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
@@ -121,7 +129,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
   const int b = blockIdx.x / p.nsplit, split = blockIdx.x % p.nsplit;
   const int Hq = p.Hq;
   const int hb = blockIdx.y * Cfg::kHeadsWg;  // first head of this workgroup
-  const int hw = hb + 16 * hg;                // first head of this wave
+  const int hw = hb + Cfg::kHeadsWave * hg;    // first head of this wave
   int64_t len = p.kv_len ? (int64_t)p.kv_len[b] : p.L;
   len = max((int64_t)0, min(len, p.L));
   const int64_t t_begin = (int64_t)split * p.tokens_per_split;
@@ -148,7 +156,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
       for (int i = 0; i < NLD; ++i) {
         const int piece = i * 64 * WS + (wave % WS) * 64 + lane;
         const int tok = piece / 36, col = piece % 36;
-        G[i] = *reinterpret_cast<const v4i*>(Cb + min(t0 + tok, last) * p.ld + 16 * col);
+        if (kPieces % (64 * WS) == 0 || piece < kPieces)  // uniform over a wave
+          G[i] = *reinterpret_cast<const v4i*>(Cb + min(t0 + tok, last) * p.ld + 16 * col);
       }
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) skn[tt] = PER_TOKEN ? sc_tok[min(t0 + 16 * tt + j, last)] : 1.f;
@@ -157,10 +166,10 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
   if (n_iter > 0) fetch(0);
 
   // ---- the query codes of this wave's 16 heads (decomposed by mla_q_decompose_kernel), as A fragments
-  v4i qa[2][9];
-  float aq[2][2], bq[2][2];
+  v4i qa[MG][9];
+  float aq[MG][2], bq[MG][2];
 #pragma unroll
-  for (int mg = 0; mg < 2; ++mg) {
+  for (int mg = 0; mg < MG; ++mg) {
     const int64_t qrow = (int64_t)b * Hq + min(hw + 8 * mg + row_head, Hq - 1);  // rows past Hq: results unused
     const int8_t* src = (row_comp ? p.qc2 : p.qc1) + qrow * kLatK + 16 * g;
 #pragma unroll
@@ -172,10 +181,10 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
     }
   }
 
-  float m_run[2][2], l_run[2][2], o_run[2][NSL][2][8];  // o_run[mg][slab][hh][c]: head 8 mg + 2 g + hh, channel 128 slab + 16 c + j
+  float m_run[MG][2], l_run[MG][2], o_run[MG][NSL][2][8];  // o_run[mg][slab][hh][c]: head 8 mg + 2 g + hh, channel 128 slab + 16 c + j
   float unit = 1.f;
 #pragma unroll
-  for (int mg = 0; mg < 2; ++mg)
+  for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       m_run[mg][hh] = -INFINITY;
@@ -195,7 +204,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         const int piece = i * 64 * WS + (wave % WS) * 64 + lane;
-        *reinterpret_cast<v4i*>(tile + (piece / 36) * kPitch + 16 * (piece % 36)) = G[i];
+        if (kPieces % (64 * WS) == 0 || piece < kPieces)
+          *reinterpret_cast<v4i*>(tile + tile_row(piece / 36) + 16 * (piece % 36)) = G[i];
       }
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) sk[tt] = skn[tt];
@@ -209,14 +219,18 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) live[tt] = t0 + 16 * tt + j < t_end;
     // ---- (2) S1, S2 over the nine 64-channel chunks; a key fragment serves both A fragments
-    v4i sd[2][4] = {{zero4, zero4, zero4, zero4}, {zero4, zero4, zero4, zero4}};
+    v4i sd[MG][4];
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) sd[mg][tt] = zero4;
     {
       // software pipeline over the 36 (chunk, token group) fragments: LDS reads three fragments ahead
       constexpr int NKF = 36, DEPTH = 4;
       v4i kf[DEPTH];
       const uint8_t* ksrc = tile + j * kPitch + 16 * g;
       auto kload = [&](int i) __attribute__((always_inline)) {
-        kf[i % DEPTH] = *reinterpret_cast<const v4i*>(ksrc + (16 * (i % 4)) * kPitch + 64 * (i / 4));
+        kf[i % DEPTH] = *reinterpret_cast<const v4i*>(ksrc + tile_row(16 * (i % 4)) + 64 * (i / 4));
       };
 #pragma unroll
       for (int i = 0; i < DEPTH - 1; ++i) kload(i);
@@ -224,13 +238,13 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
       for (int i = 0; i < NKF; ++i) {
         if (i + DEPTH - 1 < NKF) kload(i + DEPTH - 1);
 #pragma unroll
-        for (int mg = 0; mg < 2; ++mg) sd[mg][i % 4] = mfma_s8(qa[mg][i / 4], kf[i % DEPTH], sd[mg][i % 4]);
+        for (int mg = 0; mg < MG; ++mg) sd[mg][i % 4] = mfma_s8(qa[mg][i / 4], kf[i % DEPTH], sd[mg][i % 4]);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (p.tap_s1 && ch == 0) {
 #pragma unroll
-      for (int mg = 0; mg < 2; ++mg)
+      for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
           const int head = hw + 8 * mg + g * 2 + hh;
@@ -262,9 +276,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
       unit = unit_new;
     }
     // ---- (3)+(4) merge, online softmax, decompose P
-    float corr[2][2];
+    float corr[MG][2];
 #pragma unroll
-    for (int mg = 0; mg < 2; ++mg)
+    for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         float s[4];
@@ -298,9 +312,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
         sP[wave][mg][1][g * 2 + hh][j] = w2;
       }
     __builtin_amdgcn_wave_barrier();
-    v4i pa[2];
+    v4i pa[MG];
 #pragma unroll
-    for (int mg = 0; mg < 2; ++mg) pa[mg] = *reinterpret_cast<const v4i*>(&sP[wave][mg][row_comp][row_head][4 * g]);
+    for (int mg = 0; mg < MG; ++mg) pa[mg] = *reinterpret_cast<const v4i*>(&sP[wave][mg][row_comp][row_head][4 * g]);
     __builtin_amdgcn_wave_barrier();
     // ---- (5) O1, O2 over this wave's 128-channel slabs of the same rows.  The B operand (64 tokens x 16
     // channels) comes from two transposing LDS reads: in each 16-lane group, source lane s points at 8
@@ -309,12 +323,12 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
     // channel n of eight tokens.  token(k) follows the packing of the P codes (word 4g+i, byte t <-> token
     // 16 t + 4 g + i).
     const int vk = j >> 1;
-    const uint8_t* vsrc = tile + (16 * (vk & 3) + 4 * g + (vk >> 2)) * kPitch + 8 * (j & 1);
+    const uint8_t* vsrc = tile + tile_row(16 * (vk & 3) + 4 * g + (vk >> 2)) + 8 * (j & 1);  // 4 g + (vk >> 2) + 2 < 16
     // Software pipeline over the 16-channel blocks: LDS reads two blocks ahead, the two MFMAs of a block
     // issued one block before their results are merged on the vector ALU.
     constexpr int NST = NSL * 8;
     v2i rb[3][2];
-    v4i acc[2][2];
+    v4i acc[2][MG];
     auto vload = [&](int st) __attribute__((always_inline)) {
       const uint8_t* src = vsrc + 128 * (ch * NSL + st / 8) + 16 * (st % 8);
       rb[st % 3][0] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)src);
@@ -328,13 +342,13 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
       if (st < NST) {
         const v4i bf = {rb[st % 3][0][0], rb[st % 3][0][1], rb[st % 3][1][0], rb[st % 3][1][1]};
 #pragma unroll
-        for (int mg = 0; mg < 2; ++mg) acc[st & 1][mg] = mfma_s8(pa[mg], bf, zero4);
+        for (int mg = 0; mg < MG; ++mg) acc[st & 1][mg] = mfma_s8(pa[mg], bf, zero4);
       }
       __builtin_amdgcn_sched_barrier(0);  // the merge below covers the latency of the MFMAs above
       if (st >= 1) {
         const int sl = (st - 1) / 8, c = (st - 1) % 8;
 #pragma unroll
-        for (int mg = 0; mg < 2; ++mg)
+        for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
           for (int hh = 0; hh < 2; ++hh) {
             const v4i od = acc[(st - 1) & 1][mg];
@@ -349,7 +363,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mla_kernel(MlaParams p) 
   // ---- this wave's partial (m, l, O) of its 16 heads and its value channels
   const int part = split * TS + ts;
 #pragma unroll
-  for (int mg = 0; mg < 2; ++mg)
+  for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       const float l = row16_sum(l_run[mg][hh]);
@@ -433,19 +447,24 @@ __global__ __launch_bounds__(128) void attn_mla_combine_kernel(MlaParams p, int 
 // and LDS of this kernel; every token stream of a split gets at least two tiles) and partial count.
 constexpr int kMlaTargetWgs = 256;
 struct MlaPlan {
-  int layout;  // 0: 1x2x2, 1: 2x2x1, 2: 4x1x1
+  int layout;  // 0: up to 16 heads, 1: up to 32, 2: 64 per workgroup
   int ts, heads_wg, head_blocks, nsplit, nparts;
   int64_t tokens_per_split;
 };
+// layout -> <MG, NW, HGW, CH>
+#define MSD_MLA_LAYOUT_0 1, 8, 2, 2
+#define MSD_MLA_LAYOUT_1 1, 8, 4, 2
+#define MSD_MLA_LAYOUT_2 1, 8, 8, 1
 MlaPlan mla_plan(int B, int Hq, int64_t L) {
   MlaPlan pl{};
   pl.layout = Hq <= 16 ? 0 : (Hq <= 32 ? 1 : 2);
-  pl.ts = pl.layout == 0 ? 2 : 1;
-  pl.heads_wg = pl.layout == 0 ? 16 : (pl.layout == 1 ? 32 : 64);
+  pl.ts = pl.layout == 0 ? MlaCfg<MSD_MLA_LAYOUT_0>::kTS : (pl.layout == 1 ? MlaCfg<MSD_MLA_LAYOUT_1>::kTS : MlaCfg<MSD_MLA_LAYOUT_2>::kTS);
+  pl.heads_wg = pl.layout == 0 ? MlaCfg<MSD_MLA_LAYOUT_0>::kHeadsWg
+                               : (pl.layout == 1 ? MlaCfg<MSD_MLA_LAYOUT_1>::kHeadsWg : MlaCfg<MSD_MLA_LAYOUT_2>::kHeadsWg);
   pl.head_blocks = (Hq + pl.heads_wg - 1) / pl.heads_wg;
   int64_t ns = cdiv((int64_t)kMlaTargetWgs, (int64_t)B * pl.head_blocks);
   const int64_t max_by_len = max((int64_t)1, L / (2 * pl.ts * kTile));
-  ns = max((int64_t)1, min(min(ns, max_by_len), (int64_t)(64 / pl.ts)));
+  ns = max((int64_t)1, min(min(ns, max_by_len), (int64_t)(kMlaMaxParts / pl.ts)));
   pl.nsplit = (int)ns;
   pl.nparts = pl.nsplit * pl.ts;
   int64_t tps = cdiv(L > 0 ? L : 1, ns);
@@ -453,17 +472,17 @@ MlaPlan mla_plan(int B, int Hq, int64_t L) {
   return pl;
 }
 
-template <bool PER_TOKEN, int HGW, int CH>
+template <bool PER_TOKEN, int MG, int NW, int HGW, int CH>
 int launch_mla_layout(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
-  constexpr size_t lds = MlaCfg<HGW, CH>::kLds;
+  constexpr size_t lds = MlaCfg<MG, NW, HGW, CH>::kLds;
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_kernel<PER_TOKEN, HGW, CH>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_kernel<PER_TOKEN, MG, NW, HGW, CH>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
   const dim3 grid((unsigned)((int64_t)p.B * p.nsplit), (unsigned)pl.head_blocks);
-  hipLaunchKernelGGL((attn_mla_kernel<PER_TOKEN, HGW, CH>), grid, dim3(kAttnWaves * 64), lds, stream, p);
+  hipLaunchKernelGGL((attn_mla_kernel<PER_TOKEN, MG, NW, HGW, CH>), grid, dim3(NW * 64), lds, stream, p);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
@@ -471,9 +490,9 @@ int launch_mla_layout(const MlaParams& p, const MlaPlan& pl, hipStream_t stream)
 template <bool PER_TOKEN>
 int launch_mla_mode(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
   switch (pl.layout) {
-    case 0: return launch_mla_layout<PER_TOKEN, 1, 2>(p, pl, stream);
-    case 1: return launch_mla_layout<PER_TOKEN, 2, 2>(p, pl, stream);
-    default: return launch_mla_layout<PER_TOKEN, 4, 1>(p, pl, stream);
+    case 0: return launch_mla_layout<PER_TOKEN, MSD_MLA_LAYOUT_0>(p, pl, stream);
+    case 1: return launch_mla_layout<PER_TOKEN, MSD_MLA_LAYOUT_1>(p, pl, stream);
+    default: return launch_mla_layout<PER_TOKEN, MSD_MLA_LAYOUT_2>(p, pl, stream);
   }
 }
 
