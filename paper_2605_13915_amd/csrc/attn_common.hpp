@@ -38,12 +38,7 @@ __device__ __forceinline__ v4i mfma_s8(v4i a, v4i b, v4i c) {
   return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
 }
 
-// The 16 lanes sharing lane/16 are one DPP row: an all-reduce over them is four rotate-and-combine
-// steps on the vector ALU (no LDS round trip).
-template <int N>
-__device__ __forceinline__ float row16_ror(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
-}
+// All-reduce over the 16 lanes sharing lane/16 (one DPP row): four rotate-and-combine steps.
 __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, row16_ror<8>(v));
   v = fmaxf(v, row16_ror<4>(v));

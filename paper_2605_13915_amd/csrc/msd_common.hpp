@@ -57,15 +57,25 @@ struct MxVariant {
   int e2m1 = 0;
 };
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
+// Rotate within the 16-lane DPP row of a lane (lanes sharing lane/16): a cross-lane move on the vector
+// ALU, no LDS round trip.
+template <int N>
+__device__ __forceinline__ float row16_ror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
+// Maximum over the 64 lanes of a full wave, returned in every lane: four rotate-and-max steps inside
+// the rows, then the four row results through scalar registers.
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, row16_ror<8>(v));
+  v = fmaxf(v, row16_ror<4>(v));
+  v = fmaxf(v, row16_ror<2>(v));
+  v = fmaxf(v, row16_ror<1>(v));
+  const int b = __float_as_int(v);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(b, 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(b, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(b, 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(b, 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
 // One step of the two-pass INT8 decomposition (paper Sec. 3.2): given alpha, beta (already
