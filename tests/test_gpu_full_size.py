@@ -125,3 +125,25 @@ def test_cfg4_attention(msd, L, mode):
     for i, b in enumerate(sel):
         for h in range(Hq):
             assert rel_l2(o[b, h], ref[i, h]) <= 1e-3, (b, h)
+
+
+@pytest.mark.parametrize("Hq,L", [(16, 4096), (128, 4096), (16, 32768)])
+def test_latent_cache_attention_bench_shapes(msd, Hq, L):
+    """The three shapes of bench.py's latent-cache leg (B = 32, per-token scales): every output row of a sample
+    of batch entries (all of them are independent) against the oracle."""
+    B, slab = 32, 4096
+    q = synth.queries(synth.seed_for(9, Hq + L), B, Hq, 576)
+    Cl, sc, _, _ = synth.kv_cache_per_token(synth.seed_for(9, 3), B, 1, slab, 576)
+    Cl, sc = np.ascontiguousarray(Cl[:, 0]), np.ascontiguousarray(sc[:, 0])
+    rep = L // slab
+    Cl, sc = np.tile(Cl, (1, rep, 1)), np.tile(sc, (1, rep))
+    sm = 1.0 / np.sqrt(192.0)
+    out = msd.msd_mla_decode_int8kv(bf16_to_dev(q), to_dev(Cl), to_dev(sc), msd.MSD_PER_TOKEN, sm)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.all(np.isfinite(o))
+    sel = [0, 13, 31]
+    ref = oracle.mla_decode(q[sel], Cl[sel], sc[sel], oracle.PER_TOKEN, 512, sm)
+    for i, b in enumerate(sel):
+        for h in range(Hq):
+            assert rel_l2(o[b, h], ref[i, h]) <= 1e-3, (b, h)
