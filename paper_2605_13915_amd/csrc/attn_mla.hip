@@ -11,8 +11,9 @@
 //     fragments (16-channel blocks, through the transposing LDS read) both come from that LDS copy,
 //     so HBM sees each cached row once per workgroup.  Both fragment streams are software-pipelined
 //     by hand (reads a few fragments ahead of the MFMAs, MFMAs one step ahead of the merge).
-//   * The query rows are decomposed once by a small kernel of their own; a wave owns 8 MG query heads
-//     (MG 16-row A fragments: 8 heads x 2 components each) and keeps their running output in
+//   * The query rows of a workgroup are decomposed in its prologue, all loads of a wave in flight at once,
+//     straight into the A-fragment image in LDS (under the first tile fetches).  A wave owns 8 MG query
+//     heads (MG 16-row A fragments: 8 heads x 2 components each) and keeps their running output in
 //     registers, in units of alpha_P / 254 so that a tile contributes the exact integer 254 O1 + O2.
 //   * The NW waves of a workgroup are laid out as HGW head groups x CH parts of the value channels x
 //     TS token streams (HGW*CH*TS = NW); waves that split the value channels both compute the (cheap)
@@ -24,6 +25,7 @@
 #include <type_traits>
 
 #include "attn_common.hpp"
+#include "decompose_int8_dev.hpp"
 
 namespace msd {
 
@@ -43,7 +45,6 @@ constexpr int kPitch = 576;
 constexpr int kTileBytes = kTile * kPitch + 192;
 __device__ __forceinline__ int tile_row(int r) { return r * kPitch + 32 * ((r >> 4) & 1) + 128 * (r >> 5); }
 __device__ __forceinline__ int tile_swz(int r) { return (-(r >> 2)) & 3; }
-constexpr int kPieces = kTile * (kLatK / 16);  // 16-byte pieces per tile
 
 struct MlaParams {
   const uint16_t* q;   // [B][Hq][576]
@@ -56,9 +57,6 @@ struct MlaParams {
   int nparts;  // partial results per (batch, head): nsplit x token streams
   int64_t tokens_per_split;
   float sm_scale_log2;  // score scale times log2(e)
-  int8_t* qc1;          // [B][Hq][576] query codes, first and second component (workspace)
-  int8_t* qc2;
-  float* qalpha;        // [B][Hq]
   float* part_o;        // [B][nparts][Hq][512]
   float* part_m;        // [B][nparts][Hq]
   float* part_l;
@@ -80,48 +78,12 @@ struct MlaCfg {
   static constexpr int kLoads = (36 + kLanesRow - 1) / kLanesRow;  // 16-byte pieces per lane per tile
   static constexpr int kHeadsWave = 8 * MG;
   static constexpr int kHeadsWg = kHeadsWave * HGW;
-  // tiles | sP[waves][MG frag][2 comp][8 heads][16] u32 | sQ[HGW][MG][9 chunks][64 lanes][16 B]: the A fragments
-  static constexpr size_t kLds = (size_t)kTS * kTileBytes + NW * MG * 2 * 8 * 64 + HGW * MG * 9 * 1024;
+  // tiles | sP[waves][MG frag][2 comp][8 heads][16] u32 | sQ[HGW][MG][9 chunks][64 lanes][16 B]: the A fragments |
+  // sAlpha[heads]
+  static constexpr size_t kLds = (size_t)kTS * kTileBytes + NW * MG * 2 * 8 * 64 + HGW * MG * 9 * 1024 + kHeadsWg * 4;
   static_assert(kTS * kWS == NW && kTS >= 1, "wave layout");
   static_assert(kLds <= 160 * 1024, "LDS");
 };
-
-// Alg. 3 steps 1-2 for the query rows: one wave per (batch, head) row of 576 channels; the per-channel
-// key scale, if any, is absorbed into the row first.  Codes and alpha_Q go to the workspace, where every
-// workgroup of the main kernel picks up its A fragments.
-__global__ __launch_bounds__(256) void mla_q_decompose_kernel(MlaParams p, int per_channel) {
-  const int lane = threadIdx.x & 63;
-  const int64_t qrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (qrow >= (int64_t)p.B * p.Hq) return;
-  float x[9];
-  float mx = 0.f;
-#pragma unroll
-  for (int i = 0; i < 9; ++i) {
-    const int c = lane + 64 * i;
-    x[i] = __uint_as_float((uint32_t)p.q[qrow * kLatK + c] << 16);
-    if (per_channel) x[i] *= p.scale[c];
-    mx = fmaxf(mx, fabsf(x[i]));
-  }
-  mx = wave_max(mx);
-  const float alpha = mx > 0.f ? __fdiv_rn(mx, 127.0f) : 0.f;
-  const float beta = __fdiv_rn(alpha, 254.0f);
-#pragma unroll
-  for (int i = 0; i < 9; ++i) {
-    const int c = lane + 64 * i;
-    int c1 = 0, c2 = 0;
-    if (mx > 0.f) int8_codes(x[i], alpha, beta, c1, c2);
-    p.qc1[qrow * kLatK + c] = (int8_t)c1;
-    p.qc2[qrow * kLatK + c] = (int8_t)c2;
-    if (p.tap_q1) {
-      p.tap_q1[qrow * kLatK + c] = (int8_t)c1;
-      p.tap_q2[qrow * kLatK + c] = (int8_t)c2;
-    }
-  }
-  if (lane == 0) {
-    p.qalpha[qrow] = alpha;
-    if (p.tap_q1) p.tap_alpha[qrow] = alpha;
-  }
-}
 
 template <bool PER_TOKEN, int MG, int NW, int HGW, int CH>
 __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
@@ -131,6 +93,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
   uint8_t* sTiles = s_mla;
   uint32_t(*sP)[MG][2][8][16] = reinterpret_cast<uint32_t(*)[MG][2][8][16]>(s_mla + TS * kTileBytes);
   v4i* sQ = reinterpret_cast<v4i*>(s_mla + TS * kTileBytes + NW * MG * 2 * 8 * 64);
+  float* sAlpha = reinterpret_cast<float*>(s_mla + TS * kTileBytes + NW * MG * 2 * 8 * 64 + HGW * MG * 9 * 1024);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
@@ -178,23 +141,95 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
     fetch(Buf1{}, 1);
   }
 
-  // ---- the query codes of this wave's heads (decomposed by mla_q_decompose_kernel) as A fragments: one wave
-  // per head group parks them in LDS in fragment order, every tile reads them back chunk by chunk (registers
-  // go to the second fetch buffer instead)
+  // ---- Alg. 3 steps 1-2 for the query rows of this workgroup: a wave decomposes kHeadsWg / NW heads (all
+  // their loads in flight at once) and writes the codes straight into the A-fragment image in LDS:
+  // fragment (head group, chunk s) holds, for lane (g', j'), the 16 channels 64 s + 16 g' .. of fragment
+  // row j' = (head pair, head in pair, component).  The per-channel key scale, if any, is absorbed first.
+  {
+    constexpr int HPW = Cfg::kHeadsWg / NW;
+    static_assert(HPW * NW == Cfg::kHeadsWg, "heads per wave");
+    // a lane takes channels 4 lane .. +3 of the two 256-channel blocks and, lanes 0..15, of the last 64
+    v2i xr[HPW][3];
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+      const int head = min(hb + wave + NW * u, Hq - 1);  // rows past Hq: results unused
+      const uint16_t* qsrc16 = p.q + ((int64_t)b * Hq + head) * kLatK + 4 * lane;
+#pragma unroll
+      for (int bi = 0; bi < 3; ++bi)
+        xr[u][bi] = (bi < 2 || lane < 16) ? *reinterpret_cast<const v2i*>(qsrc16 + 256 * bi) : v2i{0, 0};
+    }
+#pragma unroll
+    for (int u = 0; u < HPW; ++u) {
+      const int hl = wave + NW * u;  // head within the workgroup
+      float x[3][4];
+      float mx = 0.f;
+#pragma unroll
+      for (int bi = 0; bi < 3; ++bi)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t w = (uint32_t)xr[u][bi][e >> 1];
+          x[bi][e] = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+          if (!PER_TOKEN) x[bi][e] *= p.scale[min(256 * bi + 4 * lane + e, kLatK - 1)];
+          mx = fmaxf(mx, fabsf(x[bi][e]));
+        }
+      mx = wave_max(mx);
+      const float alpha = mx > 0.f ? __fdiv_rn(mx, 127.0f) : 0.f;
+      const float beta = __fdiv_rn(alpha, 254.0f);
+      // reciprocal route with exact-division fallback (same codes); needs a normal beta
+      const bool fast = beta >= 1.17549435e-38f;
+      const float ra = fast ? __fdiv_rn(1.0f, alpha) : 0.f, rb = fast ? __fdiv_rn(1.0f, beta) : 0.f;
+      const int hq = hl % 8;  // head within its A fragment
+      const int jrow = 4 * (hq >> 1) + 2 * (hq & 1);
+      // channel 256 bi + 4 lane: chunk 4 bi + lane / 16, column group (lane & 15) / 4, bytes 4 (lane & 3) ..
+      uint8_t* frag = reinterpret_cast<uint8_t*>(sQ) + (size_t)(hl / 8) * 9 * 1024 + (lane >> 4) * 1024 +
+                      (((lane & 15) >> 2) * 16 + jrow) * 16 + 4 * (lane & 3);
+      const bool tap = p.tap_q1 && split == 0 && hb + hl < Hq;
+      const int64_t qrow = (int64_t)b * Hq + hb + hl;
+#pragma unroll
+      for (int bi = 0; bi < 3; ++bi) {
+        uint32_t w1 = 0, w2 = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int c1 = 0, c2 = 0;
+          if (fast)
+            int8_codes_fast(x[bi][e], alpha, ra, beta, rb, c1, c2);
+          else if (mx > 0.f)
+            int8_codes(x[bi][e], alpha, beta, c1, c2);
+          w1 |= ((uint32_t)c1 & 0xFFu) << (8 * e);
+          w2 |= ((uint32_t)c2 & 0xFFu) << (8 * e);
+        }
+        if (bi < 2 || lane < 16) {
+          *reinterpret_cast<uint32_t*>(frag + bi * 4096) = w1;
+          *reinterpret_cast<uint32_t*>(frag + bi * 4096 + 16) = w2;
+          if (tap) {
+            *reinterpret_cast<uint32_t*>(p.tap_q1 + qrow * kLatK + 256 * bi + 4 * lane) = w1;
+            *reinterpret_cast<uint32_t*>(p.tap_q2 + qrow * kLatK + 256 * bi + 4 * lane) = w2;
+          }
+        }
+      }
+      if (lane == 0) {
+        sAlpha[hl] = alpha;
+        if (tap) p.tap_alpha[qrow] = alpha;
+      }
+    }
+  }
+  __syncthreads();
   float aq[MG][2], bq[MG][2];
 #pragma unroll
-  for (int mg = 0; mg < MG; ++mg) {
-    if (ts == 0 && ch == 0) {
-      const int64_t qrow = (int64_t)b * Hq + min(hw + 8 * mg + row_head, Hq - 1);  // rows past Hq: results unused
-      const int8_t* src = (row_comp ? p.qc2 : p.qc1) + qrow * kLatK + 16 * g;
-#pragma unroll
-      for (int s = 0; s < 9; ++s) sQ[((hg * MG + mg) * 9 + s) * 64 + lane] = *reinterpret_cast<const v4i*>(src + 64 * s);
-    }
+  for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-      aq[mg][hh] = p.qalpha[(int64_t)b * Hq + min(hw + 8 * mg + g * 2 + hh, Hq - 1)];
+      aq[mg][hh] = sAlpha[Cfg::kHeadsWave * hg + 8 * mg + g * 2 + hh];
       bq[mg][hh] = __fdiv_rn(aq[mg][hh], 254.0f);
     }
+  // with registers to spare (few head groups) the fragments stay in registers instead
+  constexpr bool QREG = HGW <= 2;
+  v4i qreg[MG][QREG ? 9 : 1];
+  if (QREG) {
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+      for (int sc = 0; sc < 9; ++sc) qreg[mg][QREG ? sc : 0] = sQ[((hg * MG + mg) * 9 + sc) * 64 + lane];
   }
   const v4i* qsrc = sQ + (hg * MG * 9) * 64 + lane;  // fragment (mg, s) at qsrc[(mg * 9 + s) * 64]; first read after the
                                                      // barriers of the first tile
@@ -253,7 +288,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
       };
       auto qload = [&](int sc) __attribute__((always_inline)) {
 #pragma unroll
-        for (int mg = 0; mg < MG; ++mg) qf[sc & 1][mg] = qsrc[(mg * 9 + sc) * 64];
+        for (int mg = 0; mg < MG; ++mg) qf[sc & 1][mg] = QREG ? qreg[mg][sc] : qsrc[(mg * 9 + sc) * 64];
       };
       qload(0);
 #pragma unroll
@@ -533,9 +568,7 @@ int launch_mla_mode(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
 
 size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L) {
   const size_t rows = (size_t)B * Hq * mla_plan(B, Hq, L).nparts;
-  const size_t qrows = (size_t)B * Hq;
-  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256) + 2 * align_up(qrows * kLatK, 256) +
-         align_up(qrows * 4, 256);
+  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
 }
 
 int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
@@ -552,11 +585,6 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
   p.part_o = (float*)ws;
   p.part_m = (float*)(ws + align_up(rows * kLatV * 4, 256));
   p.part_l = (float*)(ws + align_up(rows * kLatV * 4, 256) + align_up(rows * 4, 256));
-  char* qws = ws + align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
-  const size_t qrows = (size_t)a.B * a.Hq;
-  p.qc1 = (int8_t*)qws;
-  p.qc2 = (int8_t*)(qws + align_up(qrows * kLatK, 256));
-  p.qalpha = (float*)(qws + 2 * align_up(qrows * kLatK, 256));
   p.out = a.out;
   p.out_bf16 = a.out_bf16;
   if (a.taps) {
@@ -569,9 +597,6 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
     if (!(p.tap_s1 && p.tap_s2)) p.tap_s1 = p.tap_s2 = nullptr;
   }
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;
-  hipLaunchKernelGGL(mla_q_decompose_kernel, dim3((unsigned)cdiv((int64_t)qrows, 4)), dim3(256), 0, stream, p,
-                     per_token ? 0 : 1);
-  MSD_LAUNCH_CHECK();
   const int rc = per_token ? launch_mla_mode<true>(p, pl, stream) : launch_mla_mode<false>(p, pl, stream);
   if (rc != MSD_OK) return rc;
   if (p.nparts > 1) {
