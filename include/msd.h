@@ -238,8 +238,8 @@ size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int
  *            scale = alpha_Q [B][Hq]; acc1, acc2 = the integer score rows [B][Hq][L]) as for
  *            msd_attn_decode_int8kv;  workspace of msd_mla_decode_int8kv_workspace_bytes(B, Hq, L).
  * Every 64-token tile of the cache is fetched once per workgroup and shared by up to 64 heads;
- * more heads are spread over further workgroups.  Two launches: the main kernel and the merge
- * of the KV splits.
+ * more heads are spread over further workgroups.  Launches: the main kernel and the merge of the
+ * KV splits; above 32 heads also a query-decomposition kernel.
  * Errors: SHAPE (dk != 576, dv != 512, ld), INVALID_ARG, WORKSPACE.
  */
 int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale,

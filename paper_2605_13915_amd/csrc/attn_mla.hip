@@ -12,7 +12,8 @@
 //     so HBM sees each cached row once per workgroup.  Both fragment streams are software-pipelined
 //     by hand (reads a few fragments ahead of the MFMAs, MFMAs one step ahead of the merge).
 //   * The query rows of a workgroup are decomposed in its prologue, all loads of a wave in flight at once,
-//     straight into the A-fragment image in LDS (under the first tile fetches).  A wave owns 8 MG query
+//     straight into the A-fragment image in LDS (under the first tile fetches); with 64 heads per workgroup
+//     that costs more than a launch, and a small kernel decomposes all rows once.  A wave owns 8 MG query
 //     heads (MG 16-row A fragments: 8 heads x 2 components each) and keeps their running output in
 //     registers, in units of alpha_P / 254 so that a tile contributes the exact integer 254 O1 + O2.
 //   * The NW waves of a workgroup are laid out as HGW head groups x CH parts of the value channels x
@@ -57,6 +58,9 @@ struct MlaParams {
   int nparts;  // partial results per (batch, head): nsplit x token streams
   int64_t tokens_per_split;
   float sm_scale_log2;  // score scale times log2(e)
+  int8_t* qc1;          // [B][Hq][576] query codes of both components and alpha_Q [B][Hq] (workspace; only
+  int8_t* qc2;          // used by the layout that leaves the query decomposition to its own kernel)
+  float* qalpha;
   float* part_o;        // [B][nparts][Hq][512]
   float* part_m;        // [B][nparts][Hq]
   float* part_l;
@@ -84,6 +88,44 @@ struct MlaCfg {
   static_assert(kTS * kWS == NW && kTS >= 1, "wave layout");
   static_assert(kLds <= 160 * 1024, "LDS");
 };
+
+// Alg. 3 steps 1-2 for the query rows as a kernel of its own, one wave per (batch, head) row; the per-channel
+// key scale, if any, is absorbed into the row first.  Used with the 64-heads-per-workgroup layout, where the
+// prologue version would spend more vector-ALU time per CU (8 heads per wave, every KV split again) than this
+// launch costs; codes and alpha_Q go to the workspace, where the main kernel picks up its A fragments.
+__global__ __launch_bounds__(256) void mla_q_decompose_kernel(MlaParams p, int per_channel) {
+  const int lane = threadIdx.x & 63;
+  const int64_t qrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (qrow >= (int64_t)p.B * p.Hq) return;
+  float x[9];
+  float mx = 0.f;
+#pragma unroll
+  for (int i = 0; i < 9; ++i) {
+    const int c = lane + 64 * i;
+    x[i] = __uint_as_float((uint32_t)p.q[qrow * kLatK + c] << 16);
+    if (per_channel) x[i] *= p.scale[c];
+    mx = fmaxf(mx, fabsf(x[i]));
+  }
+  mx = wave_max(mx);
+  const float alpha = mx > 0.f ? __fdiv_rn(mx, 127.0f) : 0.f;
+  const float beta = __fdiv_rn(alpha, 254.0f);
+#pragma unroll
+  for (int i = 0; i < 9; ++i) {
+    const int c = lane + 64 * i;
+    int c1 = 0, c2 = 0;
+    if (mx > 0.f) int8_codes(x[i], alpha, beta, c1, c2);
+    p.qc1[qrow * kLatK + c] = (int8_t)c1;
+    p.qc2[qrow * kLatK + c] = (int8_t)c2;
+    if (p.tap_q1) {
+      p.tap_q1[qrow * kLatK + c] = (int8_t)c1;
+      p.tap_q2[qrow * kLatK + c] = (int8_t)c2;
+    }
+  }
+  if (lane == 0) {
+    p.qalpha[qrow] = alpha;
+    if (p.tap_q1) p.tap_alpha[qrow] = alpha;
+  }
+}
 
 template <bool PER_TOKEN, int MG, int NW, int HGW, int CH>
 __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
@@ -145,7 +187,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
   // their loads in flight at once) and writes the codes straight into the A-fragment image in LDS:
   // fragment (head group, chunk s) holds, for lane (g', j'), the 16 channels 64 s + 16 g' .. of fragment
   // row j' = (head pair, head in pair, component).  The per-channel key scale, if any, is absorbed first.
-  {
+  // (Up to 32 heads per workgroup; with 64 the decomposition is a launch of its own, see mla_q_decompose_kernel.)
+  constexpr bool QFUSED = Cfg::kHeadsWg <= 32;
+  if (QFUSED) {
     constexpr int HPW = Cfg::kHeadsWg / NW;
     static_assert(HPW * NW == Cfg::kHeadsWg, "heads per wave");
     // a lane takes channels 4 lane .. +3 of the two 256-channel blocks and, lanes 0..15, of the last 64
@@ -213,6 +257,19 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
       }
     }
   }
+  if (!QFUSED) {  // codes and alpha_Q come from mla_q_decompose_kernel
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg) {
+      if (ts == 0 && ch == 0) {
+        const int64_t qrow = (int64_t)b * Hq + min(hw + 8 * mg + row_head, Hq - 1);  // rows past Hq: results unused
+        const int8_t* src = (row_comp ? p.qc2 : p.qc1) + qrow * kLatK + 16 * g;
+#pragma unroll
+        for (int sc = 0; sc < 9; ++sc)
+          sQ[((hg * MG + mg) * 9 + sc) * 64 + lane] = *reinterpret_cast<const v4i*>(src + 64 * sc);
+      }
+    }
+    if (tid < Cfg::kHeadsWg) sAlpha[tid] = p.qalpha[(int64_t)b * Hq + min(hb + tid, Hq - 1)];
+  }
   __syncthreads();
   float aq[MG][2], bq[MG][2];
 #pragma unroll
@@ -231,8 +288,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
 #pragma unroll
       for (int sc = 0; sc < 9; ++sc) qreg[mg][QREG ? sc : 0] = sQ[((hg * MG + mg) * 9 + sc) * 64 + lane];
   }
-  const v4i* qsrc = sQ + (hg * MG * 9) * 64 + lane;  // fragment (mg, s) at qsrc[(mg * 9 + s) * 64]; first read after the
-                                                     // barriers of the first tile
+  const v4i* qsrc = sQ + (hg * MG * 9) * 64 + lane;  // fragment (mg, s) at qsrc[(mg * 9 + s) * 64]
 
   float m_run[MG][2], l_run[MG][2], o_run[MG][NSL][2][8];  // o_run[mg][slab][hh][c]: head 8 mg + 2 g + hh, channel 128 slab + 16 c + j
   float unit = 1.f;
@@ -568,7 +624,9 @@ int launch_mla_mode(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
 
 size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L) {
   const size_t rows = (size_t)B * Hq * mla_plan(B, Hq, L).nparts;
-  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
+  const size_t qrows = (size_t)B * Hq;
+  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256) + 2 * align_up(qrows * kLatK, 256) +
+         align_up(qrows * 4, 256);
 }
 
 int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
@@ -585,6 +643,11 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
   p.part_o = (float*)ws;
   p.part_m = (float*)(ws + align_up(rows * kLatV * 4, 256));
   p.part_l = (float*)(ws + align_up(rows * kLatV * 4, 256) + align_up(rows * 4, 256));
+  char* qws = ws + align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256);
+  const size_t qrows = (size_t)a.B * a.Hq;
+  p.qc1 = (int8_t*)qws;
+  p.qc2 = (int8_t*)(qws + align_up(qrows * kLatK, 256));
+  p.qalpha = (float*)(qws + 2 * align_up(qrows * kLatK, 256));
   p.out = a.out;
   p.out_bf16 = a.out_bf16;
   if (a.taps) {
@@ -597,6 +660,11 @@ int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {
     if (!(p.tap_s1 && p.tap_s2)) p.tap_s1 = p.tap_s2 = nullptr;
   }
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;
+  if (pl.layout == 2) {
+    hipLaunchKernelGGL(mla_q_decompose_kernel, dim3((unsigned)cdiv((int64_t)qrows, 4)), dim3(256), 0, stream, p,
+                       per_token ? 0 : 1);
+    MSD_LAUNCH_CHECK();
+  }
   const int rc = per_token ? launch_mla_mode<true>(p, pl, stream) : launch_mla_mode<false>(p, pl, stream);
   if (rc != MSD_OK) return rc;
   if (p.nparts > 1) {
