@@ -13,16 +13,16 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 OUT = os.path.join(HERE, "libmsd.so")
-SOURCES = ["msd_api.hip", "decompose.hip", "gemm_w8.hip", "gemm_w4.hip", "gemm_w4_prefill.hip", "gemm_w4_mid.hip", "attn.hip", "attn_dequant.hip", "attn_mla.hip", "dequant_gemm.hip",
+SOURCES = ["msd_api.hip", "decompose.hip", "gemm_w8.hip", "gemm_w4.hip", "gemm_w4_prefill.hip", "gemm_w4_mid.hip", "attn.hip", "attn_wide.hip", "attn_dequant.hip", "attn_mla.hip", "dequant_gemm.hip",
            "stream_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-# Per-file additions.  attn_mla.hip: MFMA results feed vector-ALU code directly; let the compiler place
-# them in VGPRs instead of accumulation registers that would have to be copied out first.
-EXTRA_FLAGS = {"attn_mla.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+# Per-file additions.  attn_mla.hip, attn_wide.hip: MFMA results feed vector-ALU code directly; let the
+# compiler place them in VGPRs instead of accumulation registers that would have to be copied out first.
+EXTRA_FLAGS = {"attn_mla.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "attn_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src):
