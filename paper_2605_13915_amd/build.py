@@ -22,7 +22,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 # Per-file additions.  attn_mla.hip, attn_wide.hip: MFMA results feed vector-ALU code directly; let the
 # compiler place them in VGPRs instead of accumulation registers that would have to be copied out first.
-EXTRA_FLAGS = {"attn_mla.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "attn_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA_FLAGS = {"attn_mla.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"], "attn_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+               "attn_dequant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src):
