@@ -84,4 +84,16 @@ def test_attention_and_grouped_gemm_in_a_graph(msd):
     calls.append(lambda: msd.msd_moe_gemm_w8a16(*margs, y=y, prepare=True))
     outs.append(y)
     refs.append(oracle.moe_gemm_w8a16(x, offs, W, s))
+    # attention over a latent KV cache: the 16-head layout (query decomposition in the prologue) and the
+    # 64-heads-per-workgroup layout (its own decomposition launch), both with split KV and a merge launch
+    sm = 1.0 / np.sqrt(192.0)
+    for Hl in (16, 40):
+        ql = synth.queries(5 + Hl, 1, Hl, 576)
+        Cl, sc, _, _ = synth.kv_cache_per_token(5 + Hl, 1, 1, 1500, 576)
+        Cl, sc = np.ascontiguousarray(Cl[:, 0]), np.ascontiguousarray(sc[:, 0])
+        ol = torch.empty((1, Hl, 512), dtype=torch.float32, device="cuda")
+        largs = (bf16_to_dev(ql), to_dev(Cl), to_dev(sc), msd.MSD_PER_TOKEN, sm)
+        calls.append(lambda largs=largs, ol=ol: msd.msd_mla_decode_int8kv(*largs, out=ol, prepare=True))
+        outs.append(ol)
+        refs.append(oracle.mla_decode(ql, Cl, sc, oracle.PER_TOKEN, 512, sm))
     _replay_and_check(calls, outs, refs, 1e-3)
