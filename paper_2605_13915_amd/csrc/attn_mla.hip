@@ -82,9 +82,11 @@ struct MlaCfg {
   static constexpr int kLoads = (36 + kLanesRow - 1) / kLanesRow;  // 16-byte pieces per lane per tile
   static constexpr int kHeadsWave = 8 * MG;
   static constexpr int kHeadsWg = kHeadsWave * HGW;
-  // tiles | sP[waves][MG frag][2 comp][8 heads][16] u32 | sQ[HGW][MG][9 chunks][64 lanes][16 B]: the A fragments |
-  // sAlpha[heads]
-  static constexpr size_t kLds = (size_t)kTS * kTileBytes + NW * MG * 2 * 8 * 64 + HGW * MG * 9 * 1024 + kHeadsWg * 4;
+  // tiles[streams][2] | sP[waves][MG frag][2 comp][8 heads][16] u32 | sAlpha[heads] |
+  // sQ[HGW][MG][9 chunks][64 lanes][16 B]: the A fragments (over the tiles when they end up in registers)
+  static constexpr bool kQReg = HGW <= 2;  // A fragments in registers: their LDS image is only a staging area
+  static constexpr size_t kLds = (size_t)2 * kTS * kTileBytes + NW * MG * 2 * 8 * 64 + kHeadsWg * 4 +
+                                 (kQReg ? 0 : HGW * MG * 9 * 1024);
   static_assert(kTS * kWS == NW && kTS >= 1, "wave layout");
   static_assert(kLds <= 160 * 1024, "LDS");
 };
@@ -133,9 +135,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
   constexpr int TS = Cfg::kTS, WS = Cfg::kWS, NSL = Cfg::kSlabs, NLD = Cfg::kLoads;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mla[];
   uint8_t* sTiles = s_mla;
-  uint32_t(*sP)[MG][2][8][16] = reinterpret_cast<uint32_t(*)[MG][2][8][16]>(s_mla + TS * kTileBytes);
-  v4i* sQ = reinterpret_cast<v4i*>(s_mla + TS * kTileBytes + NW * MG * 2 * 8 * 64);
-  float* sAlpha = reinterpret_cast<float*>(s_mla + TS * kTileBytes + NW * MG * 2 * 8 * 64 + HGW * MG * 9 * 1024);
+  constexpr bool QREG = Cfg::kQReg;
+  uint32_t(*sP)[MG][2][8][16] = reinterpret_cast<uint32_t(*)[MG][2][8][16]>(s_mla + 2 * TS * kTileBytes);
+  float* sAlpha = reinterpret_cast<float*>(s_mla + 2 * TS * kTileBytes + NW * MG * 2 * 8 * 64);
+  v4i* sQ = reinterpret_cast<v4i*>(QREG ? s_mla : s_mla + 2 * TS * kTileBytes + NW * MG * 2 * 8 * 64 + Cfg::kHeadsWg * 4);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
@@ -152,7 +155,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
   const int8_t* Cb = p.C + (int64_t)b * p.L * p.ld;
   const float* sc_tok = p.scale + (int64_t)b * p.L;  // per-token mode only
   const v4i zero4 = {0, 0, 0, 0};
-  uint8_t* tile = sTiles + ts * kTileBytes;
+  uint8_t* tiles2 = sTiles + 2 * ts * kTileBytes;  // this stream's two tile buffers: tile k lives in buffer k & 1
   const int n_iter = (int)((max(t_end - t_begin, (int64_t)0) + TS * kTile - 1) / (TS * kTile));  // same for every wave
 
   // A-fragment row of this lane: slot j&3 of head pair j>>2 = (head, component)
@@ -280,13 +283,13 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
       bq[mg][hh] = __fdiv_rn(aq[mg][hh], 254.0f);
     }
   // with registers to spare (few head groups) the fragments stay in registers instead
-  constexpr bool QREG = HGW <= 2;
   v4i qreg[MG][QREG ? 9 : 1];
   if (QREG) {
 #pragma unroll
     for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
       for (int sc = 0; sc < 9; ++sc) qreg[mg][QREG ? sc : 0] = sQ[((hg * MG + mg) * 9 + sc) * 64 + lane];
+    __syncthreads();  // the staging area is tile memory from here on
   }
   const v4i* qsrc = sQ + (hg * MG * 9) * 64 + lane;  // fragment (mg, s) at qsrc[(mg * 9 + s) * 64]
 
@@ -304,23 +307,28 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
         for (int c = 0; c < 8; ++c) o_run[mg][sl][hh][c] = 0.f;
     }
 
-  auto step = [&](auto bufc, int it) __attribute__((always_inline)) {
+  // LDS holds two tiles per stream, so a step needs one workgroup barrier: after it tile `it` is visible and
+  // nobody reads tile it - 1 any more, whose buffer then takes tile it + 1 from the registers while the loads
+  // of tiles it + 2 and it + 3 are in flight.
+  auto stage = [&](auto bufc, int k) __attribute__((always_inline)) {  // registers of tile k -> LDS buffer k & 1
     constexpr int BUF = decltype(bufc)::value;
+    uint8_t* dst = tiles2 + BUF * kTileBytes + tile_row(frow) + 16 * (fcol ^ tile_swz(frow));  // LPR is a multiple of 4
+#pragma unroll
+    for (int i = 0; i < NLD; ++i)
+      if (36 % LPR == 0 || fcol + LPR * i < 36) *reinterpret_cast<v4i*>(dst + 16 * LPR * i) = G[BUF][i];
+    fetch(bufc, k + 2);
+  };
+  auto step = [&](auto bufc, int it) __attribute__((always_inline)) {  // bufc: buffer of tile it + 1
+    constexpr int BUF = decltype(bufc)::value;
+    const uint8_t* tile = tiles2 + (1 - BUF) * kTileBytes;
     const int64_t t0 = t_begin + ((int64_t)it * TS + ts) * kTile;
     const bool tile_live = t0 < t_end;  // uniform over the waves of a stream
-    if (it > 0) __syncthreads();        // every wave is done reading the previous tile
-    {
-      uint8_t* dst = tile + tile_row(frow) + 16 * (fcol ^ tile_swz(frow));  // LPR is a multiple of 4
-#pragma unroll
-      for (int i = 0; i < NLD; ++i)
-        if (36 % LPR == 0 || fcol + LPR * i < 36) *reinterpret_cast<v4i*>(dst + 16 * LPR * i) = G[BUF][i];
-    }
     __syncthreads();
     // the token scales of this tile: issued ahead of the next fetch, first used after the score product
     float sk[4];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) sk[tt] = PER_TOKEN ? sc_tok[min(t0 + 16 * tt + j, last)] : 1.f;
-    fetch(bufc, it + 2);
+    stage(bufc, it + 1);
     __builtin_amdgcn_sched_barrier(0);
     if (!tile_live) return;
 
@@ -479,9 +487,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  if (n_iter > 0) stage(Buf0{}, 0);
   for (int it = 0; it < n_iter; it += 2) {  // an odd count is padded with a tile past the end
-    step(Buf0{}, it);
-    step(Buf1{}, it + 1);
+    step(Buf1{}, it);
+    step(Buf0{}, it + 1);
   }
 
   // ---- this wave's partial (m, l, O) of its 16 heads and its value channels
