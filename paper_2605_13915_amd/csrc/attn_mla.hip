@@ -99,28 +99,48 @@ __global__ __launch_bounds__(256) void mla_q_decompose_kernel(MlaParams p, int p
   const int lane = threadIdx.x & 63;
   const int64_t qrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (qrow >= (int64_t)p.B * p.Hq) return;
-  float x[9];
+  // a lane takes channels 4 lane .. +3 of the two 256-channel blocks and, lanes 0..15, of the last 64
+  const uint16_t* src = p.q + qrow * kLatK + 4 * lane;
+  float x[3][4];
   float mx = 0.f;
 #pragma unroll
-  for (int i = 0; i < 9; ++i) {
-    const int c = lane + 64 * i;
-    x[i] = __uint_as_float((uint32_t)p.q[qrow * kLatK + c] << 16);
-    if (per_channel) x[i] *= p.scale[c];
-    mx = fmaxf(mx, fabsf(x[i]));
+  for (int bi = 0; bi < 3; ++bi) {
+    const v2i w2 = (bi < 2 || lane < 16) ? *reinterpret_cast<const v2i*>(src + 256 * bi) : v2i{0, 0};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = (uint32_t)w2[e >> 1];
+      x[bi][e] = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+      if (per_channel) x[bi][e] *= p.scale[min(256 * bi + 4 * lane + e, kLatK - 1)];
+      mx = fmaxf(mx, fabsf(x[bi][e]));
+    }
   }
   mx = wave_max(mx);
   const float alpha = mx > 0.f ? __fdiv_rn(mx, 127.0f) : 0.f;
   const float beta = __fdiv_rn(alpha, 254.0f);
+  // reciprocal route with exact-division fallback (same codes); needs a normal beta
+  const bool fast = beta >= 1.17549435e-38f;
+  const float ra = fast ? __fdiv_rn(1.0f, alpha) : 0.f, rb = fast ? __fdiv_rn(1.0f, beta) : 0.f;
 #pragma unroll
-  for (int i = 0; i < 9; ++i) {
-    const int c = lane + 64 * i;
-    int c1 = 0, c2 = 0;
-    if (mx > 0.f) int8_codes(x[i], alpha, beta, c1, c2);
-    p.qc1[qrow * kLatK + c] = (int8_t)c1;
-    p.qc2[qrow * kLatK + c] = (int8_t)c2;
-    if (p.tap_q1) {
-      p.tap_q1[qrow * kLatK + c] = (int8_t)c1;
-      p.tap_q2[qrow * kLatK + c] = (int8_t)c2;
+  for (int bi = 0; bi < 3; ++bi) {
+    uint32_t w1 = 0, w2 = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      int c1 = 0, c2 = 0;
+      if (fast)
+        int8_codes_fast(x[bi][e], alpha, ra, beta, rb, c1, c2);
+      else if (mx > 0.f)
+        int8_codes(x[bi][e], alpha, beta, c1, c2);
+      w1 |= ((uint32_t)c1 & 0xFFu) << (8 * e);
+      w2 |= ((uint32_t)c2 & 0xFFu) << (8 * e);
+    }
+    if (bi < 2 || lane < 16) {
+      const int64_t at = qrow * kLatK + 256 * bi + 4 * lane;
+      *reinterpret_cast<uint32_t*>(p.qc1 + at) = w1;
+      *reinterpret_cast<uint32_t*>(p.qc2 + at) = w2;
+      if (p.tap_q1) {
+        *reinterpret_cast<uint32_t*>(p.tap_q1 + at) = w1;
+        *reinterpret_cast<uint32_t*>(p.tap_q2 + at) = w2;
+      }
     }
   }
   if (lane == 0) {
