@@ -184,7 +184,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
   const int row_comp = slot & 1;
 
   // ---- tile fetch, two tiles ahead of their use (two register sets).  The 64 WS lanes of a stream take one
-  // cached row per WS lanes: a lane fetches the 16-byte pieces lr, lr + WS, ... of its row, so the loads of a
+  // cached row per WS lanes: a lane fetches the 16-byte pieces fcol, fcol + WS, ... of its row, so the loads of a
   // lane share one base address and the LDS image needs no index arithmetic.  Fetches and LDS writes are
   // unconditional (rows past the end repeat the last valid one): straight-line code lets the compiler count
   // the loads in flight exactly, so the wait before an LDS write covers its own tile only.
