@@ -15,7 +15,8 @@ OBJ = os.path.join(ROOT, "_build")
 OUT = os.path.join(HERE, "libmsd.so")
 SOURCES = ["msd_api.hip", "decompose.hip", "gemm_w8.hip", "gemm_w4.hip", "gemm_w4_prefill.hip", "gemm_w4_mid.hip", "attn.hip", "attn_wide.hip", "attn_dequant.hip", "attn_mla.hip", "dequant_gemm.hip",
            "stream_probe.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+# -Wno-inline-asm: the LDS-fill asm statements write m0 and list it as clobbered on purpose
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
@@ -30,7 +31,9 @@ def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    # the host pass does not know the packed-fp32 feature and says so: harmless, dropped
+    quiet = ("packed-fp32-ops", "warnings generated", "warning generated")
+    err = "\n".join(l for l in r.stderr.splitlines() if not any(q in l for q in quiet))
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))
     if err.strip():
