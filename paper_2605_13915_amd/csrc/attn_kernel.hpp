@@ -158,8 +158,9 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
     // scale of the P decomposition: alpha_P = top/127 with top a bound on P (or P*s_V)
     float top = 1.f;
     if (PER_TOKEN) top = row16_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
-    const float to_code = top > 0.f ? __fdiv_rn(127.0f, top) : 0.f;
-    const float from_code = top * (1.0f / 127.0f);
+    const bool coded = top > 1e-30f;  // below that every code of the tile is zero (and 127 / top would overflow)
+    const float to_code = coded ? __fdiv_rn(127.0f, top) : 0.f;
+    const float from_code = coded ? top * (1.0f / 127.0f) : 0.f;
     uint32_t vb[8][4];  // filled by the first fragment of the tile
 #pragma unroll
     for (int f = 0; f < NF; ++f) {

@@ -314,7 +314,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
   const v4i* qsrc = sQ + (hg * MG * 9) * 64 + lane;  // fragment (mg, s) at qsrc[(mg * 9 + s) * 64]
 
   float m_run[MG][2], l_run[MG][2], o_run[MG][NSL][2][8];  // o_run[mg][slab][hh][c]: head 8 mg + 2 g + hh, channel 128 slab + 16 c + j
-  float unit = 1.f;
+  float unit = 0.f;                   // 0: no coded tile yet
+  float top = PER_TOKEN ? 0.f : 1.f;  // bound on P (times the value scale) behind alpha_P
 #pragma unroll
   for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
@@ -403,20 +404,22 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
           }
         }
     }
-    // scale of the P decomposition: alpha_P = top/127, top a bound on P (times the value scale)
+    // scale of the P decomposition: alpha_P = top/127, top a bound on P (times the value scale): the largest
+    // value scale this wave has met so far (the untiled algorithm takes the largest of all tokens; a running
+    // maximum is never coarser than that and, being monotone, only ever shrinks the running output below)
     float sv[4];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) sv[tt] = live[tt] ? sk[tt] : 0.f;
-    float top = 1.f;
-    if (PER_TOKEN) top = row16_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])));
-    const float to_code = top > 0.f ? __fdiv_rn(127.0f, top) : 0.f;
-    // The running output is kept in units of `unit` = alpha_P / 254 of the latest tile, so that a tile's
-    // contribution is the integer 254 O1 + O2 itself; a change of alpha_P rescales the running output
-    // together with the softmax correction.
+    if (PER_TOKEN) top = fmaxf(top, row16_max(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]))));
+    const bool coded = top > 1e-30f;  // below that every code of the tile is zero
+    const float to_code = coded ? __fdiv_rn(127.0f, top) : 0.f;
+    // The running output is kept in units of `unit` = alpha_P / 254, so that a tile's contribution is the
+    // integer 254 O1 + O2 itself; a growing alpha_P rescales the running output (by a factor <= 1) together
+    // with the softmax correction.
     float rescale = 1.f;
-    if (top > 0.f) {
+    if (coded) {
       const float unit_new = top * (1.0f / (127.0f * 254.0f));
-      rescale = __fdiv_rn(unit, unit_new);
+      rescale = unit > 0.f ? __fdiv_rn(unit, unit_new) : 0.f;  // nothing accumulated before the first coded tile
       unit = unit_new;
     }
     // ---- (3)+(4) merge, online softmax, decompose P

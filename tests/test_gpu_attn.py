@@ -96,3 +96,30 @@ def test_attn_bf16_output_and_errors(msd):
                                    torch.ones((1, 2, 8), device="cuda"), torch.ones((1, 2, 8), device="cuda"),
                                    msd.MSD_PER_TOKEN)
     assert e.value.code == -2
+
+
+def test_attn_extreme_value_scales(msd):
+    """Per-token value scales spanning sixty orders of magnitude, a stretch of zero scales and an entry whose
+    value scales are all zero: finite outputs that match the oracle and the fp64 truth, zeros for that entry."""
+    B, Hq, Hkv, L, d = 3, 8, 2, 1500, 128
+    q = synth.queries(41, B, Hq, d)
+    Kc, ks, Vc, vs = synth.kv_cache_per_token(41, B, Hkv, L, d)
+    vs = vs.copy()
+    vs[0, :, :200] = 0.0
+    vs[0, :, 200:500] *= 1e-3
+    vs[0, :, 500:700] = 1e-35
+    vs[0, :, 700:900] *= 1e2
+    vs[1, :, :] = np.float32(1e-30) * (1 + np.arange(L, dtype=np.float32) / L)
+    vs[1, :, 640:704] *= np.float32(1e25)
+    vs[2, :, :] = 0.0
+    ref = oracle.attn_decode(q, Kc, Vc, ks, vs, oracle.PER_TOKEN)
+    truth = oracle.truth_attn(q, Kc, Vc, ks, vs, oracle.PER_TOKEN)
+    out = msd.msd_attn_decode_int8kv(bf16_to_dev(q), to_dev(Kc), to_dev(Vc), to_dev(ks), to_dev(vs), msd.MSD_PER_TOKEN)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.all(np.isfinite(o))
+    assert np.all(o[2] == 0) and np.all(ref[2] == 0)
+    for b in range(2):
+        for h in range(Hq):
+            assert rel_l2(o[b, h], truth[b, h]) <= 1e-3, (b, h)
+            assert rel_l2(o[b, h], ref[b, h]) <= 1e-3, (b, h)

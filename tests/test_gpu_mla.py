@@ -128,3 +128,32 @@ def test_mla_decode_random_shapes(msd, B, Hq, L, mode, ld, ragged, seed):
             continue
         for h in range(Hq):
             assert rel_l2(o[b, h], ref[b, h]) <= 1e-3, (b, h)
+
+
+def test_mla_extreme_token_scales(msd):
+    """Per-token scales spanning sixty orders of magnitude inside one KV split, a stretch of zero scales at the
+    start and an entry whose scales are all zero: outputs stay finite, match the oracle and the fp64 truth,
+    and the all-zero entry gives zeros."""
+    B, Hq, L = 3, 16, 1400
+    q, Cl, sc = _case(31, "token", B, Hq, L)
+    sc = sc.copy()
+    sc[0, :200] = 0.0
+    sc[0, 200:500] *= 1e-3
+    sc[0, 500:700] = 1e-35
+    sc[0, 700:900] *= 1e2
+    sc[0, 900:] *= 1e-4
+    sc[1, :] = np.float32(1e-30) * (1 + np.arange(L, dtype=np.float32) / L)
+    sc[1, 640:704] *= np.float32(1e25)
+    sc[2, :] = 0.0
+    sm = 1.0 / np.sqrt(192.0)
+    ref = oracle.mla_decode(q, Cl, sc, oracle.PER_TOKEN, 512, sm)
+    truth = oracle.truth_mla(q, Cl, sc, oracle.PER_TOKEN, 512, sm)
+    out = msd.msd_mla_decode_int8kv(bf16_to_dev(q), to_dev(Cl), to_dev(sc), msd.MSD_PER_TOKEN, sm)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.all(np.isfinite(o))
+    assert np.all(o[2] == 0) and np.all(ref[2] == 0)
+    for b in range(2):
+        for h in range(Hq):
+            assert rel_l2(o[b, h], truth[b, h]) <= 1e-3, (b, h)
+            assert rel_l2(o[b, h], ref[b, h]) <= 1e-3, (b, h)
