@@ -178,6 +178,34 @@ def leg_attn(msd, synth, time_calls, dev):
         fcc = lambda i: msd.msd_dequant_attn_decode_int8kv(q, sets[i % n][0], sets[i % n][1], kc, vc,
                                                            msd.MSD_PER_CHANNEL, out=o, ws=ws, prepare=True)
         us_ch_cmp = time_calls(fcc, 4 * n)
+        # accuracy of both kernels against an fp64 attention over the exactly dequantised cache (two batch
+        # entries; the quantity of the paper's flash-attention error table, Sec. 6.4, on this workload)
+        acc = None
+        if L <= 4096:
+            def truth(Kc, Vc, sk_, sv_, per_token, nb=2):
+                Kd, Vd = Kc[:nb].double(), Vc[:nb].double()
+                if per_token:
+                    Kd, Vd = Kd * sk_[:nb, :, :, None].double(), Vd * sv_[:nb, :, :, None].double()
+                else:
+                    Kd, Vd = Kd * sk_[None, :, None, :].double(), Vd * sv_[None, :, None, :].double()
+                qg = q[:nb].double().view(nb, Hkv, Hq // Hkv, d)
+                P = torch.softmax(torch.einsum("bhgd,bhld->bhgl", qg, Kd) / d ** 0.5, dim=-1)
+                return torch.einsum("bhgl,bhld->bhgd", P, Vd).reshape(nb, Hq, d)
+
+            def rel(t):
+                return float(((o[:2].double() - t).norm() / t.norm()).item())
+
+            Kc0, Vc0, ks0, vs0 = sets[0]
+            acc = {}
+            t_tok, t_ch = truth(Kc0, Vc0, ks0, vs0, True), truth(Kc0, Vc0, kc, vc, False)
+            for name, fn, args_, t in (("msd_per_token", msd.msd_attn_decode_int8kv, (ks0, vs0, msd.MSD_PER_TOKEN), t_tok),
+                                       ("dequant_per_token", msd.msd_dequant_attn_decode_int8kv, (ks0, vs0, msd.MSD_PER_TOKEN), t_tok),
+                                       ("msd_per_channel", msd.msd_attn_decode_int8kv, (kc, vc, msd.MSD_PER_CHANNEL), t_ch),
+                                       ("dequant_per_channel", msd.msd_dequant_attn_decode_int8kv, (kc, vc, msd.MSD_PER_CHANNEL), t_ch)):
+                fn(q, Kc0, Vc0, *args_, out=o, ws=ws)
+                torch.cuda.synchronize()
+                acc[name] = float("%.3g" % rel(t))
+            del t_tok, t_ch
         b = kvbytes + 8 * B * Hkv * L + 2 * B * Hq * d + 4 * B * Hq * d
         # bare read of the same K and V bytes (one launch each), same cold-cache protocol
         class _Both:
@@ -193,6 +221,8 @@ def leg_attn(msd, synth, time_calls, dev):
                     "per_channel": {"us": round(us_ch, 1), "dequant_us": round(us_ch_cmp, 1),
                                     "GBps": round((kvbytes + 6 * B * Hq * d) / us_ch / 1e3, 1),
                                     "speedup_vs_dequant": round(us_ch_cmp / us_ch, 3)}})
+        if acc is not None:
+            out[-1]["rel_l2_vs_fp64"] = acc
         del sets
         torch.cuda.empty_cache()
     return out
