@@ -357,6 +357,15 @@ def leg_mla(msd, synth, time_calls, dev):
             out.append({"B": B, "Hq": Hq, "L": L, "us": round(us, 1), "GBps": round(byts / us / 1e3, 1),
                         "hbm_frac": round(byts / us / 1e3 / HBM, 4), "exec_TOPS": round(ops / us / 1e6, 1),
                         "int8_mfma_frac": round(ops / us / 1e6 / INT8_TOPS, 4)})
+            if L <= 4096:  # accuracy against an fp64 attention over the dequantised rows (two batch entries)
+                C0, s0 = sets[0]
+                msd.msd_mla_decode_int8kv(q, C0, s0, msd.MSD_PER_TOKEN, 1.0 / 192.0 ** 0.5, out=o, ws=ws)
+                torch.cuda.synchronize()
+                Cd = C0[:2].double() * s0[:2, :, None].double()
+                P = torch.softmax(torch.einsum("bhd,bld->bhl", q[:2].double(), Cd) / 192.0 ** 0.5, dim=-1)
+                t = torch.einsum("bhl,bld->bhd", P, Cd[:, :, :512])
+                out[-1]["rel_l2_vs_fp64"] = float("%.3g" % ((o[:2].double() - t).norm() / t.norm()).item())
+                del Cd, P, t
         del sets
         torch.cuda.empty_cache()
     return out
