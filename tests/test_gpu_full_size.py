@@ -1,7 +1,8 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times
 (the entry points without observation points, caller-provided output and workspace).
 
-cfg1 (W8A16 decode) and the small W4 / attention shapes are compared element by element in full.  For the
+cfg1 (W8A16 decode) and the small W4 / attention shapes are compared element by element in full; so are the
+latent-cache and grouped-GEMM shapes of the bench legs (sampled batch entries; every routed row).  For the
 shapes whose oracle run would take minutes (cfg2 prefill, W4 with 4096 rows, attention at L = 32768) the
 oracle computes a sample of complete activation rows, resp. complete batch entries -- rows and batch entries
 are independent, so the sampled results are exact full-size results -- spread over first, last and interior
@@ -147,3 +148,50 @@ def test_latent_cache_attention_bench_shapes(msd, Hq, L):
     for i, b in enumerate(sel):
         for h in range(Hq):
             assert rel_l2(o[b, h], ref[i, h]) <= 1e-3, (b, h)
+
+
+@pytest.mark.parametrize("T", [16, 256])
+def test_grouped_gemm_bench_shapes(msd, T):
+    """The grouped (mixture-of-experts) GEMMs at the sizes of bench.py's leg: 64 INT8 experts and 128 MXFP4
+    experts of N = 2048, K = 4096, multinomial routing.  The experts are one seeded matrix with a sign per
+    expert (enough to tell them apart; the bytes a kernel sees do not matter to the bar); every routed row is
+    compared with the oracle's product of that row with its expert."""
+    N, K = 2048, 4096
+    rng = np.random.default_rng(91 + T)
+    x = synth.activations(synth.seed_for(8, T), T, K, outliers=True)
+    xd = bf16_to_dev(x)
+    # W8A16
+    E = 64
+    W0, s0 = synth.int8_weights(synth.seed_for(8, 1), N, K)
+    sign = np.where(rng.integers(0, 2, E) == 1, 1, -1).astype(np.int8)
+    W = W0[None] * sign[:, None, None]
+    s = np.repeat(s0[None], E, 0) * (1.0 + np.arange(E, dtype=np.float32)[:, None] / E)
+    counts = rng.multinomial(T, np.ones(E) / E)
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    y = torch.full((T, N), float("nan"), dtype=torch.float32, device="cuda")
+    msd.msd_moe_gemm_w8a16(xd, to_dev(offs), to_dev(W), to_dev(s), y=y)
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    for e in range(E):
+        r0, r1 = int(offs[e]), int(offs[e + 1])
+        if r1 > r0:
+            ref = oracle.gemm_w8a16(x[r0:r1], W[e], s[e])
+            assert rel_l2(yh[r0:r1], ref) <= 1e-6, e
+    del W, y
+    # W4A16
+    E = 128
+    codes0, exps0 = synth.mxfp4_weights(synth.seed_for(8, 2), N, K)
+    flip = (rng.integers(0, 2, E) == 1)
+    codes = np.where(flip[:, None, None], codes0[None] ^ np.uint8(0x88), codes0[None])
+    exps = np.repeat(exps0[None], E, 0)
+    counts = rng.multinomial(T, np.ones(E) / E)
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    y = torch.full((T, N), float("nan"), dtype=torch.float32, device="cuda")
+    msd.msd_moe_gemm_w4a16(xd, to_dev(offs), to_dev(codes), to_dev(exps), y=y)
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    for e in range(E):
+        r0, r1 = int(offs[e]), int(offs[e + 1])
+        if r1 > r0:
+            ref = oracle.gemm_w4a16(x[r0:r1], codes[e], exps[e])
+            assert rel_l2(yh[r0:r1], ref) <= 2e-6, e
