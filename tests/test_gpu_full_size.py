@@ -195,3 +195,30 @@ def test_grouped_gemm_bench_shapes(msd, T):
         if r1 > r0:
             ref = oracle.gemm_w4a16(x[r0:r1], codes[e], exps[e])
             assert rel_l2(yh[r0:r1], ref) <= 2e-6, e
+
+
+@pytest.mark.parametrize("G,mode", [(16, "channel"), (48, "token")])
+def test_attention_many_query_rows_bench_shape(msd, G, mode):
+    """The query-row sweep of bench.py at its size (B = 16, 8 KV heads, L = 4096) for the kernels that hold 16
+    heads per pass: sampled batch entries against the oracle, per head."""
+    B, Hkv, L, d = 16, 8, 4096, 128
+    Hq = Hkv * G
+    q = synth.queries(synth.seed_for(4, 100 + G), B, Hq, d)
+    if mode == "token":
+        Kc, ks, Vc, vs = synth.kv_cache_per_token(synth.seed_for(4, 7), B, Hkv, L, d)
+        omode, gmode = oracle.PER_TOKEN, msd.MSD_PER_TOKEN
+    else:
+        Kc, ks, Vc, vs = synth.kv_cache_per_channel(synth.seed_for(4, 8), B, Hkv, L, d)
+        omode, gmode = oracle.PER_CHANNEL, msd.MSD_PER_CHANNEL
+    out = msd.msd_attn_decode_int8kv(bf16_to_dev(q), to_dev(Kc), to_dev(Vc), to_dev(ks), to_dev(vs), gmode)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.all(np.isfinite(o))
+    sel = [0, 15]
+    if mode == "token":
+        ref = oracle.attn_decode(q[sel], Kc[sel], Vc[sel], ks[sel], vs[sel], omode)
+    else:
+        ref = oracle.attn_decode(q[sel], Kc[sel], Vc[sel], ks, vs, omode)
+    for i, b in enumerate(sel):
+        for h in range(Hq):
+            assert rel_l2(o[b, h], ref[i, h]) <= 1e-3, (b, h)
