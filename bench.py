@@ -41,9 +41,10 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
-    ap.add_argument("--counter-probe", default="", choices=["", "w8_prefill", "w4_prefill", "attn"],
+    ap.add_argument("--counter-probe", default="", choices=["", "w8_prefill", "w4_prefill", "attn", "mla16", "mla128"],
                     help="for rocprofv3 --pmc runs: three eager calls of one compute-heavy shape (W8A16 "
-                         "2048x8192x8192, W4A16 4096x8192x28672, attention L=32768), nothing else; no timing")
+                         "2048x8192x8192, W4A16 4096x8192x28672, attention L=32768, latent-cache attention with 16 heads "
+                         "at L=32768 or 128 heads at L=4096), nothing else; no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -76,6 +77,12 @@ def main():
             codes = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device=dev, generator=g)
             exps = torch.randint(118, 124, (N, K // 32), dtype=torch.uint8, device=dev, generator=g)
             call = lambda: msd.msd_gemm_w4a16(x, codes, exps)
+        elif args.counter_probe in ("mla16", "mla128"):
+            B, Hq, L = (32, 16, 32768) if args.counter_probe == "mla16" else (32, 128, 4096)
+            q = dev_bf16(synth.queries(synth.seed_for(9, Hq), B, Hq, 576))
+            Cl = torch.randint(-127, 128, (B, L, 576), dtype=torch.int8, device=dev, generator=g)
+            sl = torch.rand((B, L), device=dev) * 0.02 + 0.02
+            call = lambda: msd.msd_mla_decode_int8kv(q, Cl, sl, msd.MSD_PER_TOKEN, 1.0 / 192.0 ** 0.5)
         else:
             B, Hq, Hkv, d, L = 16, 32, 8, 128, 32768
             q = dev_bf16(synth.queries(synth.seed_for(4, 0), B, Hq, d))
