@@ -42,7 +42,8 @@ enum {
   MSD_ERR_SHAPE = -2,       /* unsupported or inconsistent sizes */
   MSD_ERR_WORKSPACE = -3,   /* workspace null or too small */
   MSD_ERR_HIP = -4,         /* a HIP call failed; see msd_last_hip_error() */
-  MSD_ERR_UNSUPPORTED = -5  /* valid request that this build has no kernel for */
+  MSD_ERR_UNSUPPORTED = -5, /* valid request that this build has no kernel for */
+  MSD_ERR_STATIC_SCRATCH = -6 /* msd_gemm_w8a16_static: the shape needs more scratch than the built-in buffer */
 };
 
 enum { MSD_INT8 = 0, MSD_MXFP4 = 1 };             /* decomposition format */
@@ -118,6 +119,28 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
                    void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
                    void* stream);
 size_t msd_gemm_w8a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * msd_gemm_w8a16 for callers that cannot allocate device memory or carry a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, kernels and
+ * results as msd_gemm_w8a16 without observation points; the activation codes and row scales live in a
+ * buffer built into the library (device memory of msd_gemm_w8a16_static_scratch_bytes() = 2 MiB + 4 KiB
+ * per GPU, held until the process ends) instead of a caller's workspace.  The call allocates and frees
+ * nothing and synchronises nothing.
+ *   Limit: msd_gemm_w8a16_workspace_bytes(M, K, N) - 256 must not exceed the buffer, i.e.
+ *   2 * roundup(M, 128) * K + 4 * M (each term rounded up to 256) <= 2 MiB + 4 KiB: up to 128 rows at
+ *   K <= 8192, 256 rows at K <= 4096.  Larger shapes return MSD_ERR_STATIC_SCRATCH and enqueue nothing.
+ *   Every call on a GPU shares that GPU's buffer: calls must be ordered on one stream (or otherwise not
+ *   overlap), concurrent calls on one GPU race.  The buffer keeps the previous call's contents; the
+ *   kernels overwrite everything they later read, so nothing needs clearing.
+ *   The first call on each device also resolves the buffer's device address (hipGetSymbolAddress) and,
+ *   like msd_gemm_w8a16, may set a kernel attribute: make one eager call per shape class before capturing.
+ * Other errors as msd_gemm_w8a16.
+ */
+int msd_gemm_w8a16_static(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                          const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                          void* stream);
+size_t msd_gemm_w8a16_static_scratch_bytes(void);
 
 /*
  * MSD linear layer with MXFP4 weights (paper Sec. 3.2.1, Alg. 2, Sec. 3.4.1): the two

@@ -19,7 +19,7 @@ MSD_VARIANT_MAIN, MSD_VARIANT_INT8_FRACTIONAL, MSD_VARIANT_MXFP4_V1, MSD_VARIANT
 MSD_VARIANT_MXFP4_E2M1 = 4
 
 _ERR = {-1: "MSD_ERR_INVALID_ARG", -2: "MSD_ERR_SHAPE", -3: "MSD_ERR_WORKSPACE", -4: "MSD_ERR_HIP",
-        -5: "MSD_ERR_UNSUPPORTED"}
+        -5: "MSD_ERR_UNSUPPORTED", -6: "MSD_ERR_STATIC_SCRATCH"}
 
 
 class MsdError(RuntimeError):
@@ -52,6 +52,10 @@ def lib():
         gemm8 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         gemm4 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         L.msd_gemm_w8a16.argtypes = gemm8
+        L.msd_gemm_w8a16_static.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp]
+        L.msd_gemm_w8a16_static.restype = ci
+        L.msd_gemm_w8a16_static_scratch_bytes.argtypes = []
+        L.msd_gemm_w8a16_static_scratch_bytes.restype = sz
         L.msd_dequant_gemm_w8a16.argtypes = gemm8
         L.msd_probe_mfma_w8a16.argtypes = gemm8
         L.msd_gemm_w4a16.argtypes = gemm4
@@ -207,6 +211,22 @@ def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, w
     assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
     return _gemm_common("msd_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
                         W.shape[0], out_dtype, taps, y, ws, prepare)
+
+
+def msd_gemm_w8a16_static(x, W, w_scale, y, prepare=False):
+    """msd_gemm_w8a16 on the library's built-in scratch buffer; y is the caller's (nothing is allocated)."""
+    _dev(x, torch.bfloat16, "x"); _dev(W, torch.int8, "W"); _dev(w_scale, torch.float32, "w_scale")
+    assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
+    assert isinstance(y, torch.Tensor) and y.is_cuda and y.shape == (x.shape[0], W.shape[0])
+    M, K = x.shape
+    ldx = x.stride(0) if M > 1 else max(K, x.stride(0))
+    args = (_ptr(x), M, K, ldx, _ptr(W), _ptr(w_scale), W.shape[0], _ptr(y), _out_code(y.dtype), y.stride(0),
+            _stream())
+    fn = lib().msd_gemm_w8a16_static
+    if prepare:
+        return Prepared(fn, args, (x, W, w_scale, y), "msd_gemm_w8a16_static", y)
+    _check(fn(*args), "msd_gemm_w8a16_static")
+    return y
 
 
 def msd_gemm_w8a16_variant(variant, x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, ws=None,

@@ -1,10 +1,37 @@
 // C-ABI entry points: argument validation, workspace carving, kernel dispatch.
 #include <algorithm>
+#include <mutex>
 
 #include "kernels.hpp"
 
 namespace msd {
 thread_local int g_last_hip_error = 0;
+
+// Built-in scratch of msd_gemm_w8a16_static: the activation codes and row scales that the other entry
+// points keep in the caller's workspace.  One copy per GPU, held until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels and copies get the address that
+// call returns on the device at hand.
+constexpr size_t kStaticScratchBytes = (2u << 20) + 4096;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device, resolved once per device
+static int static_scratch_ptr(void** out) {
+  int dev = -1;
+  MSD_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return MSD_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    MSD_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return MSD_ERR_UNSUPPORTED;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MSD_OK;
+}
 
 __global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -181,6 +208,22 @@ int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
       MSD_HIP_CHECK(hipMemcpyAsync(taps->scale, a.alpha, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
   }
   return MSD_OK;
+}
+
+size_t msd_gemm_w8a16_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int msd_gemm_w8a16_static(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                          const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* stream) {
+  if (M < 0 || K < 0 || N < 0) return MSD_ERR_SHAPE;
+  if (M > 0 && N > 0 && w8_layout(M, K, N).total > kStaticScratchBytes) return MSD_ERR_STATIC_SCRATCH;
+  void* ptr = nullptr;
+  const int rc = static_scratch_ptr(&ptr);
+  if (rc) return rc;
+  // Same kernels as msd_gemm_w8a16, with the built-in array in the workspace's place.  Nothing in it has
+  // to start at zero: the decomposition launch writes every code and scale the GEMM launch looks at (rows
+  // of a padded tile that it does not write only feed products that are never stored).
+  return msd_gemm_w8a16_variant(MSD_VARIANT_MAIN, x_bf16, M, K, ldx, W, w_scale, N, y, out_dtype, ldy, ptr,
+                                kStaticScratchBytes, nullptr, stream);
 }
 
 int msd_moe_gemm_w8a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const int32_t* expert_offsets, int E,
