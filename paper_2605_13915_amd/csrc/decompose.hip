@@ -18,10 +18,13 @@ constexpr int kDecThreads = 256;
 __global__ __launch_bounds__(kDecThreads) void decompose_int8_kernel(
     const uint16_t* __restrict__ x, int64_t ldx, int K, int8_t* __restrict__ q1,
     int8_t* __restrict__ q2, int64_t ldq, float* __restrict__ alpha_out, int aligned, int64_t a_step,
-    int a_bk, float num1, float num2) {
+    int a_bk, float num1, float num2, int frag_rt, int M) {
   __shared__ float s_red[kDecThreads / kWave];
   const int64_t m = blockIdx.x;
-  if (a_step)  // blocked layout for the asynchronous-fill GEMM: q1 / q2 are the array bases
+  if (frag_rt)  // fragment-major layout for the register-operand GEMM: q1 is the array base
+    decompose_row_int8_block<kDecThreads>(x + m * ldx, K, q1, q2, alpha_out + m, aligned != 0, s_red, num1,
+                                          num2, 0, m, 64, frag_rt, M);
+  else if (a_step)  // blocked layout for the asynchronous-fill GEMM: q1 / q2 are the array bases
     decompose_row_int8_block<kDecThreads>(x + m * ldx, K, q1, q2, alpha_out + m, aligned != 0, s_red, num1,
                                           num2, a_step, m, a_bk);
   else
@@ -31,11 +34,11 @@ __global__ __launch_bounds__(kDecThreads) void decompose_int8_kernel(
 
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
                           int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, Int8Range rg,
-                          hipStream_t stream) {
+                          hipStream_t stream, int frag_rt) {
   if (M == 0 || K == 0) return MSD_OK;
   const int aligned = ((reinterpret_cast<uintptr_t>(x) & 15) == 0 && (ldx % 8) == 0) ? 1 : 0;
   hipLaunchKernelGGL(decompose_int8_kernel, dim3((unsigned)M), dim3(kDecThreads), 0, stream, x, ldx,
-                     (int)K, q1, q2, ldq, alpha, aligned, a_step, a_bk, rg.num1, rg.num2);
+                     (int)K, q1, q2, ldq, alpha, aligned, a_step, a_bk, rg.num1, rg.num2, frag_rt, (int)M);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

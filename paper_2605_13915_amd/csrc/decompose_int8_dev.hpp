@@ -5,7 +5,7 @@
 
 namespace msd {
 
-constexpr int kDecRegChunks = 4;  // 16-element chunks cached in registers per thread
+constexpr int kDecRegChunks = 1;  // 16-element chunks cached in registers per thread (the rest is re-read from L2)
 
 struct Chunk16 {
   uint32_t w[8];  // 16 BF16 values
@@ -78,56 +78,73 @@ __device__ __forceinline__ void int8_codes_fast(float x, float alpha, float ra, 
   c2 = (int)fminf(fmaxf(p, -128.f), 127.f);
 }
 
-// chunk_codes for the rare rows the reciprocal route cannot serve: same result, rolled up so that it
-// costs the kernels that inline it next to their fast path neither registers nor code size.
-__device__ __forceinline__ void chunk_codes_rare(const Chunk16& c, float alpha, float beta, uint4& o1, uint4& o2) {
-  uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0, b0 = 0, b1 = 0, b2 = 0, b3 = 0;
+// Four elements at a time, branch-free (the quantiser of every kernel that decomposes whole rows).
+// q = rne(x * (1/alpha)) can differ from rne(x / alpha) (the correctly rounded quotient, which is what defines
+// the codes) only if x/alpha lies within 127.49 * 2^-23 < 1.6e-5 of a half-integer; then the residual
+// r = x - alpha*q, which the second pass needs anyway, has |r| >= alpha * (0.5 - 1.6e-5).  Likewise for the
+// residual pass with u = r * (1/beta): p = rne(u) is safe unless |u - p| >= 0.5 - 1.6e-5.  Both tests use the
+// margin 3e-5 (thr1 = alpha * 0.49997f).  The return value says whether this lane's four elements need the
+// divisions (about one group in 2000).  No clamp is needed on this route: |x/alpha| <= 127.49 and
+// |r/beta| <= 127.49 * (1 + 2^-22) round to at most 127.
+constexpr float kTieMargin = 0.49997f;
+
+__device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
+  return ((uint32_t)a & 0xFFu) | (((uint32_t)b & 0xFFu) << 8) | (((uint32_t)c & 0xFFu) << 16) | ((uint32_t)d << 24);
+}
+
+__device__ __forceinline__ bool quad_codes_try(uint32_t w0, uint32_t w1, float alpha, float ra, float rb, float thr1,
+                                               uint32_t& o1, uint32_t& o2) {
+  const float x0 = __uint_as_float(w0 << 16), x1 = __uint_as_float(w0 & 0xFFFF0000u);
+  const float x2 = __uint_as_float(w1 << 16), x3 = __uint_as_float(w1 & 0xFFFF0000u);
+  const float q0 = rintf(x0 * ra), q1 = rintf(x1 * ra), q2 = rintf(x2 * ra), q3 = rintf(x3 * ra);
+  const float r0 = __fmaf_rn(-alpha, q0, x0), r1 = __fmaf_rn(-alpha, q1, x1);
+  const float r2 = __fmaf_rn(-alpha, q2, x2), r3 = __fmaf_rn(-alpha, q3, x3);
+  const float u0 = r0 * rb, u1 = r1 * rb, u2 = r2 * rb, u3 = r3 * rb;
+  const float p0 = rintf(u0), p1 = rintf(u1), p2 = rintf(u2), p3 = rintf(u3);
+  const float m1 = fmaxf(fmaxf(fabsf(r0), fabsf(r1)), fmaxf(fabsf(r2), fabsf(r3)));
+  const float m2 = fmaxf(fmaxf(fabsf(u0 - p0), fabsf(u1 - p1)), fmaxf(fabsf(u2 - p2), fabsf(u3 - p3)));
+  o1 = pack4((int)q0, (int)q1, (int)q2, (int)q3);
+  o2 = pack4((int)p0, (int)p1, (int)p2, (int)p3);
+  return (m1 > thr1) | (m2 > kTieMargin);
+}
+
+// 16 elements.  The four groups go the division-free way; groups that failed its test in some lane of the wave
+// are then redone with the correctly rounded divisions by the lanes concerned (one rolled block per call site,
+// entered only when the wave has such a lane).  The reciprocal route needs beta (and with it alpha and both
+// reciprocals) to be a normal fp32 number: rows whose maximum is below about 2^-113 redo every group.
+__device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, float ra, float beta,
+                                                 float rb, uint4& o1, uint4& o2) {
+  const float thr1 = alpha * kTieMargin;
+  uint32_t a0, a1, a2, a3, b0, b1, b2, b3;
+  uint32_t redo = quad_codes_try(c.w[0], c.w[1], alpha, ra, rb, thr1, a0, b0) ? 1u : 0u;
+  redo |= quad_codes_try(c.w[2], c.w[3], alpha, ra, rb, thr1, a1, b1) ? 2u : 0u;
+  redo |= quad_codes_try(c.w[4], c.w[5], alpha, ra, rb, thr1, a2, b2) ? 4u : 0u;
+  redo |= quad_codes_try(c.w[6], c.w[7], alpha, ra, rb, thr1, a3, b3) ? 8u : 0u;
+  if (!(beta >= 1.17549435e-38f)) redo = 15u;
+  if (__builtin_amdgcn_ballot_w64(redo != 0) != 0) {
 #pragma unroll 1
-  for (int j = 0; j < 4; ++j) {
-    const uint32_t w0 = j == 0 ? c.w[0] : j == 1 ? c.w[2] : j == 2 ? c.w[4] : c.w[6];
-    const uint32_t w1 = j == 0 ? c.w[1] : j == 1 ? c.w[3] : j == 2 ? c.w[5] : c.w[7];
-    uint32_t pa = 0, pb = 0;
+    for (int j = 0; j < 4; ++j) {
+      const bool mine = (redo >> j) & 1u;
+      if (__builtin_amdgcn_ballot_w64(mine) == 0) continue;
+      const uint32_t w0 = j == 0 ? c.w[0] : j == 1 ? c.w[2] : j == 2 ? c.w[4] : c.w[6];
+      const uint32_t w1 = j == 0 ? c.w[1] : j == 1 ? c.w[3] : j == 2 ? c.w[5] : c.w[7];
+      uint32_t pa = 0, pb = 0;
 #pragma unroll 1
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t w = e < 2 ? w0 : w1;
-      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-      int c1, c2;
-      int8_codes(x, alpha, beta, c1, c2);
-      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
-      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t w = e < 2 ? w0 : w1;
+        const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+        int c1, c2;
+        int8_codes(x, alpha, beta, c1, c2);
+        pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
+        pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
+      }
+      if (mine) {
+        if (j == 0) { a0 = pa; b0 = pb; } else if (j == 1) { a1 = pa; b1 = pb; } else if (j == 2) { a2 = pa; b2 = pb; } else { a3 = pa; b3 = pb; }
+      }
     }
-    if (j == 0) { a0 = pa; b0 = pb; } else if (j == 1) { a1 = pa; b1 = pb; } else if (j == 2) { a2 = pa; b2 = pb; } else { a3 = pa; b3 = pb; }
   }
   o1 = make_uint4(a0, a1, a2, a3);
   o2 = make_uint4(b0, b1, b2, b3);
-}
-
-// The reciprocal route needs beta (and with it alpha and both reciprocals) to be a normal fp32
-// number; rows whose maximum is below about 2^-113 take the plain divisions (row-uniform branch).
-__device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, float ra, float beta,
-                                                 float rb, uint4& o1, uint4& o2) {
-  if (!(beta >= 1.17549435e-38f)) {
-    chunk_codes_rare(c, alpha, beta, o1, o2);
-    return;
-  }
-  uint32_t a[4], b[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    uint32_t pa = 0, pb = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t w = c.w[j * 2 + (e >> 1)];
-      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-      int c1, c2;
-      int8_codes_fast(x, alpha, ra, beta, rb, c1, c2);
-      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
-      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
-    }
-    a[j] = pa;
-    b[j] = pb;
-  }
-  o1 = make_uint4(a[0], a[1], a[2], a[3]);
-  o2 = make_uint4(b[0], b[1], b[2], b[3]);
 }
 
 // One workgroup of THREADS threads decomposes one row: xr[0..K) -> q1r, q2r (16-byte aligned),
@@ -143,13 +160,25 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
                                                          int8_t* __restrict__ q2r,
                                                          float* __restrict__ alpha_out, bool aligned,
                                                          float* s_red, float num1, float num2,
-                                                         int64_t a_step = 0, int64_t m = 0, int a_bk = 64) {
+                                                         int64_t a_step = 0, int64_t m = 0, int a_bk = 64,
+                                                         int frag_rt = 0, int64_t frag_m2 = 0) {
+  // frag_rt != 0: the fragment-major layout of the register-operand GEMM kernels (GemmW8Args::a_frag): both
+  // components in one array, stacked row i = m (first component) or frag_m2 + m (residual component), the 16
+  // bytes of K step s, group g of stacked row i at ((s * frag_rt + i/16) * 64 + g * 16 + i%16) * 16 -- one
+  // contiguous kilobyte per (K step, 16-row fragment), in the lane order of the matrix instruction's operand.
+  // q1r is the array base; q2r is unused.
   const int nchunks = K / 16;
   const int cpr = a_bk / 16, rpi = 1024 / a_bk;  // chunks per row, rows per 1 KB block
   const int64_t row_off = (m / rpi) * 1024 + (m % rpi) * a_bk;
   const int sw = a_bk == 64 ? (int)((m >> 2) & 3) : (int)((m >> 1) & 7);
+  const int64_t i2 = frag_m2 + m;
   auto slot = [&](int c) -> int64_t {  // index of chunk c in units of 16 bytes
+    if (frag_rt) return ((int64_t)(c >> 2) * frag_rt + (m >> 4)) * 64 + (c & 3) * 16 + (m & 15);
     return a_step ? ((int64_t)(c / cpr) * a_step + row_off + (((c % cpr) ^ sw) << 4)) >> 4 : c;
+  };
+  auto slot2 = [&](int c) -> int64_t {  // the same for the residual component
+    if (frag_rt) return ((int64_t)(c >> 2) * frag_rt + (i2 >> 4)) * 64 + (c & 3) * 16 + (i2 & 15);
+    return slot(c);
   };
   Chunk16 cache[kDecRegChunks];
   float mx = 0.f;
@@ -161,6 +190,7 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
       mx = fmaxf(mx, chunk_absmax(cache[i]));
     }
   }
+#pragma unroll 1
   for (int c = threadIdx.x + kDecRegChunks * THREADS; c < nchunks; c += THREADS)
     mx = fmaxf(mx, chunk_absmax(load_chunk16(xr + c * 16, aligned)));
   mx = wave_max(mx);
@@ -174,11 +204,11 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
   const float ra = __fdiv_rn(1.0f, alpha), rb = __fdiv_rn(1.0f, beta);  // unused for an all-zero row
   if (threadIdx.x == 0) *alpha_out = alpha;
   uint4* o1 = reinterpret_cast<uint4*>(q1r);
-  uint4* o2 = reinterpret_cast<uint4*>(q2r);
+  uint4* o2 = reinterpret_cast<uint4*>(frag_rt ? q1r : q2r);
   if (mx == 0.f) {  // all-zero row: zero codes, zero scales
     for (int c = threadIdx.x; c < nchunks; c += THREADS) {
       o1[slot(c)] = make_uint4(0, 0, 0, 0);
-      o2[slot(c)] = make_uint4(0, 0, 0, 0);
+      o2[slot2(c)] = make_uint4(0, 0, 0, 0);
     }
     return;
   }
@@ -189,14 +219,15 @@ __device__ __forceinline__ void decompose_row_int8_block(const uint16_t* __restr
       uint4 a, b;
       chunk_codes_fast(cache[i], alpha, ra, beta, rb, a, b);
       o1[slot(c)] = a;
-      o2[slot(c)] = b;
+      o2[slot2(c)] = b;
     }
   }
+#pragma unroll 1
   for (int c = threadIdx.x + kDecRegChunks * THREADS; c < nchunks; c += THREADS) {
     uint4 a, b;
     chunk_codes_fast(load_chunk16(xr + c * 16, aligned), alpha, ra, beta, rb, a, b);
     o1[slot(c)] = a;
-    o2[slot(c)] = b;
+    o2[slot2(c)] = b;
   }
 }
 

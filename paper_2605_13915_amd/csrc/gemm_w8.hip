@@ -13,8 +13,11 @@
 // Kernels:
 //   decode : 2M <= 64.  Up to four 16-row A fragments carry [x1; x2].  W goes HBM -> registers
 //            in MFMA layout directly (each lane reads 16 contiguous bytes of one W row), the K
-//            range is split over the waves of a workgroup and reduced through LDS.  For M <= 8
-//            the kernel also decomposes the activations itself, under its own weight loads:
+//            range is split over the waves of a workgroup and reduced through LDS.  The codes come
+//            from the decomposition launch in fragment-major order (one contiguous kilobyte per
+//            operand load).
+//   fused  : a handful of rows (M*K <= 16384).  The kernel also decomposes the activations itself,
+//            under its own weight loads, all of which are in flight before any arithmetic starts:
 //            one launch per call and no code buffer in HBM.
 //   large  : any M.  32x32x32 MFMA, LDS-staged tiles (swizzled), 4 waves, register-local merge
 //            of the two components; for prefill-sized problems a 256x256 tile filled by
@@ -73,6 +76,9 @@ __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta,
 //
 //   (the quantiser itself, bit-exact without a division per element, is in decompose_int8_dev.hpp)
 constexpr int kSelfMaxRows = 8;
+constexpr int kFusedMaxRows = 16;                   // rows the single-launch kernel accepts
+constexpr int64_t kFusedMaxElems = 16384;           // ... and activation elements (M*K): beyond, a launch is cheaper
+constexpr int64_t kSelfMaxCodeBytes = 136 * 1024;  // LDS budget for the self-decomposed codes
 
 // FAST: K % 64 == 0, so no load of the main loop is predicated per lane (predicated loads do not
 // batch); fragment rows past 2M then re-read row 0 -- their products are never looked at.
@@ -105,12 +111,16 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
     ap[f] = nullptr;
     if (SELF) {
       if (i < 2 * M) ap[f] = my_codes + (int64_t)i * kw + 16 * g - (int64_t)ks0 * 64;
+    } else if (a.a_frag) {
+      ap[f] = a.q1 + f * 1024 + lane * 16;  // rows past 2M hold whatever was there: their products are never read
     } else if (i < M) {
       ap[f] = a.q1 + (int64_t)i * a.ldq + 16 * g;
     } else if (i < 2 * M) {
       ap[f] = a.q2 + (int64_t)(i - M) * a.ldq + 16 * g;
     }
   }
+  // bytes between the K steps of an A fragment (fragment-major codes: RT kilobyte blocks per step)
+  const int64_t astep = (!SELF && a.a_frag) ? (int64_t)RT * 1024 : 64;
   const v4i zero = {0, 0, 0, 0};
   v4i acc[RT][NT];
 #pragma unroll
@@ -187,11 +197,10 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      const int64_t k = (int64_t)(ks + u) * 64;
 #pragma unroll
       for (int f = 0; f < RT; ++f) {
         av[f][u] = zero;
-        if (ok[u] && (FAST || ap[f])) av[f][u] = ldg16(ap[f] + k);
+        if (ok[u] && (FAST || ap[f])) av[f][u] = ldg16(ap[f] + (ks + u) * astep);
       }
     }
 #pragma unroll
@@ -281,6 +290,152 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_rowsplit_kernel(GemmW8Args
   if (a.acc2) b.acc2 = a.acc2 + c0 * a.N;
   b.M = min((int64_t)(8 * RT), a.M - c0);
   gemm_w8_decode_body<WAVES, UNROLL, RT, NT, false, FAST>(b, n0);
+}
+
+// ------------------------------------------------------------------ single launch, everything in flight at once
+// For a handful of rows (M <= MR, M*K <= kFusedMaxElems) and K = WAVES * STEPS * 64: a workgroup owns 16*NT
+// output channels, wave w the K range [w, w+1) * STEPS * 64.  Each wave first requests its slice of x (all rows;
+// it comes from L2), then its whole slice of W (STEPS * NT 16-byte loads per lane, HBM -> registers in MFMA B
+// layout), so that every weight byte of the call is in flight before any arithmetic starts -- at these sizes the
+// weight matrix is only a few times the bytes the memory system must have outstanding to run at its rate.
+// Under those loads the workgroup decomposes the rows (Alg. 1 steps 1-5; the "online activation decomposition"
+// of Sec. 3.9): row maxima over the waves through LDS, then each wave quantises its own slice into wave-private
+// LDS (row pitch KW + 16 B: the 16 rows of an A fragment fall into 16 different 16-byte bank groups).  The
+// MFMAs then take A from LDS and B from the registers the loads filled; wave partials meet in LDS integer
+// atomics (exact).  Every workgroup repeats the decomposition, which is why the row count is bounded by work:
+// at 16384 elements it costs about as much as the launch it saves.
+// MR: compile-time bound on the rows (chunks of x held per lane: MR * STEPS / 16, at most 4).
+template <int WAVES, int STEPS, int NT, int MR>
+__global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a) {
+  constexpr int THREADS = WAVES * 64, KW = STEPS * 64, CPR = KW / 16, PITCH = KW + 16;
+  constexpr int XC = (MR * CPR + 63) / 64;
+  constexpr int RT = (2 * MR + 15) / 16;
+  static_assert(MR <= kFusedMaxRows && (CPR & (CPR - 1)) == 0 && XC <= 4, "rows / K range");
+  __shared__ int s_acc[RT][NT][4][64];
+  __shared__ float s_red[kFusedMaxRows][WAVES];
+  __shared__ float s_par[kFusedMaxRows][4];  // alpha, 1/alpha, beta, 1/beta of each row
+  extern __shared__ __attribute__((aligned(16))) int8_t s_codes[];  // per wave [2M][PITCH]
+  const int M = (int)a.M;
+  const int64_t K = a.K, N = a.N;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = lane & 15, g = lane >> 4;
+  const int64_t n0 = (int64_t)blockIdx.x * (16 * NT);
+  const int k_lo = wave * KW;
+  // ---- x first (its loads are the oldest, so waiting for them does not wait for W)
+  Chunk16 xc[XC];
+  const bool al16 = a.x_aligned != 0;
+  const int nch = M * CPR;
+#pragma unroll
+  for (int i = 0; i < XC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      xc[i] = load_chunk16(a.x + (int64_t)(c / CPR) * a.ldx + k_lo + (c % CPR) * 16, al16);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) xc[i].w[j] = 0;
+    }
+  }
+  // ---- then the whole W slice of this wave
+  v4i wv[NT][STEPS];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int8_t* wp = a.W + min(n0 + 16 * t + row, N - 1) * K + k_lo + 16 * g;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) wv[t][s] = ldg16_stream(wp + s * 64);
+  }
+  for (int i = threadIdx.x; i < RT * NT * 256; i += THREADS) (&s_acc[0][0][0][0])[i] = 0;
+  // ---- row maxima: over the chunks of a lane, the lanes of a wave, the waves
+  float cm[XC];
+#pragma unroll
+  for (int i = 0; i < XC; ++i) cm[i] = chunk_absmax(xc[i]);
+#pragma unroll
+  for (int m = 0; m < MR; ++m) {
+    if (m < M) {
+      float v = 0.f;
+#pragma unroll
+      for (int i = 0; i < XC; ++i) v = ((lane + 64 * i) / CPR == m) ? fmaxf(v, cm[i]) : v;
+      v = wave_max(v);
+      if (lane == 0) s_red[m][wave] = v;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < M) {
+    float v = s_red[threadIdx.x][0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) v = fmaxf(v, s_red[threadIdx.x][w]);
+    const float al = __fdiv_rn(v, a.rg.num1), be = __fdiv_rn(al, a.rg.num2);
+    s_par[threadIdx.x][0] = al;
+    s_par[threadIdx.x][1] = __fdiv_rn(1.0f, al);  // unused for an all-zero row
+    s_par[threadIdx.x][2] = be;
+    s_par[threadIdx.x][3] = __fdiv_rn(1.0f, be);
+  }
+  __syncthreads();
+  // ---- quantise this wave's slice into its own LDS region
+  int8_t* my_codes = s_codes + (int64_t)wave * 2 * M * PITCH;
+  const bool exporter = blockIdx.x == 0 && a.export_codes;
+#pragma unroll
+  for (int i = 0; i < XC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      const int m = c / CPR, cc = c % CPR;
+      const float al = s_par[m][0];
+      uint4 o1 = make_uint4(0, 0, 0, 0), o2 = o1;
+      if (al > 0.f) chunk_codes_fast(xc[i], al, s_par[m][1], s_par[m][2], s_par[m][3], o1, o2);
+      *reinterpret_cast<uint4*>(my_codes + m * PITCH + cc * 16) = o1;
+      *reinterpret_cast<uint4*>(my_codes + (M + m) * PITCH + cc * 16) = o2;
+      if (exporter) {  // observation points only
+        *reinterpret_cast<uint4*>(const_cast<int8_t*>(a.q1) + (int64_t)m * a.ldq + k_lo + cc * 16) = o1;
+        *reinterpret_cast<uint4*>(const_cast<int8_t*>(a.q2) + (int64_t)m * a.ldq + k_lo + cc * 16) = o2;
+      }
+    }
+  }
+  if (exporter && threadIdx.x < M) const_cast<float*>(a.alpha)[threadIdx.x] = s_par[threadIdx.x][0];
+  __builtin_amdgcn_wave_barrier();  // the codes are wave-private: no workgroup barrier needed
+  // ---- MFMAs: stacked row i of the A operand is x1 row i for i < M, x2 row i - M for i < 2M; rows past
+  // that repeat row 0 (their products are never read)
+  const v4i zero = {0, 0, 0, 0};
+  v4i acc[RT][NT];
+  const int8_t* afrag[RT];
+#pragma unroll
+  for (int f = 0; f < RT; ++f) {
+    const int i = f * 16 + row;
+    afrag[f] = my_codes + (i < 2 * M ? i : 0) * PITCH + 16 * g;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[f][t] = zero;
+  }
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+#pragma unroll
+    for (int f = 0; f < RT; ++f) {
+      const v4i av = *reinterpret_cast<const v4i*>(afrag[f] + s * 64);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[f][t] = mfma16(av, wv[t][s], acc[f][t]);
+    }
+  }
+#pragma unroll
+  for (int f = 0; f < RT; ++f)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) atomicAdd(&s_acc[f][t][r][lane], acc[f][t][r]);
+  __syncthreads();
+  // thread e -> (column c, row m) with m fastest; stacked row i sits in fragment i/16, register (i%16)%4 of
+  // lane ((i%16)/4)*16 + j
+  for (int e = threadIdx.x; e < M * 16 * NT; e += THREADS) {
+    const int m = e % M, c = e / M;
+    const int t = c >> 4, j = c & 15;
+    const int i1 = m, i2 = M + m;
+    const int a1 = s_acc[i1 >> 4][t][i1 & 3][((i1 & 15) >> 2) * 16 + j];
+    const int a2 = s_acc[i2 >> 4][t][i2 & 3][((i2 & 15) >> 2) * 16 + j];
+    const int64_t n = n0 + c;
+    if (n < N) {
+      const float alpha = s_par[m][0];
+      const float beta = __fdiv_rn(alpha, a.rg.num2);
+      store_out(a.y, a.out_bf16, (int64_t)m * a.ldy + n, merge_scales(a.w_scale[n], alpha, beta, a1, a2));
+      if (a.acc1) a.acc1[(int64_t)m * N + n] = a1;
+      if (a.acc2) a.acc2[(int64_t)m * N + n] = a2;
+    }
+  }
 }
 
 // ------------------------------------------------------------------ large tiles (prefill)
@@ -836,12 +991,57 @@ int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx,
 }
 
 // ------------------------------------------------------------------ dispatch
-constexpr int64_t kSelfMaxCodeBytes = 128 * 1024;  // LDS budget for the self-decomposed codes
+// Which instance of the everything-in-flight single-launch kernel serves (K, N): 0 = none.
+//   K = 1024 / 2048 / 4096 / 8192 as 4 x 4, 4 x 8, 4 x 16 (or 8 x 8), 8 x 16 (waves x K steps per wave); with many
+//   column tiles two or four tiles per workgroup.
+enum { kFusedNone = 0, kFused4x4, kFused4x8, kFused4x16, kFused4x16x2, kFused8x8x4, kFused8x16, kFused8x16x2 };
+static int fused_instance(int64_t M, int64_t K, int64_t N) {
+  if (M < 1 || M > kFusedMaxRows || M * K > kFusedMaxElems) return kFusedNone;
+  const bool wide = cdiv(N, 16) > 512;
+  if (K == 1024) return kFused4x4;
+  if (K == 2048) return kFused4x8;
+  if (K == 4096) return !wide ? kFused4x16 : M <= 2 ? kFused4x16x2 : kFused8x8x4;
+  if (K == 8192) return wide ? kFused8x16x2 : kFused8x16;
+  return kFusedNone;
+}
 
-// Single launch (the GEMM kernel decomposes the activations itself)?
-bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t) {
-  // measured: beyond two rows the redundant per-workgroup decomposition costs more than a launch
+// Single launch (the GEMM kernel decomposes the activations itself)?  The general form (any K) pays beyond two
+// rows more for the repeated decomposition than for a launch (measured); the everything-in-flight form up to
+// kFusedMaxElems activation elements.
+bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N) {
+  if (fused_instance(M, K, N) != kFusedNone) return true;
   return M <= 2 && K > 0 && 2 * M * (K + 1024) <= kSelfMaxCodeBytes;
+}
+
+template <int WAVES, int STEPS, int NT, int MR>
+static int launch_fused_mr(const GemmW8Args& a, hipStream_t stream) {
+  const dim3 grid((unsigned)cdiv(a.N, 16 * NT));
+  const size_t dyn = (size_t)WAVES * 2 * a.M * (STEPS * 64 + 16);
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_fused_kernel<WAVES, STEPS, NT, MR>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelfMaxCodeBytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_w8_fused_kernel<WAVES, STEPS, NT, MR>), grid, dim3(WAVES * 64), dyn, stream, a);
+  return MSD_OK;
+}
+
+// picks the row bound: M * K <= kFusedMaxElems leaves at most 16384 / (WAVES * STEPS * 64) rows
+template <int WAVES, int STEPS, int NT>
+static int launch_fused(const GemmW8Args& a, hipStream_t stream) {
+  constexpr int MAXR = (int)(kFusedMaxElems / (WAVES * STEPS * 64));
+  if (a.K != (int64_t)WAVES * STEPS * 64 || a.M > MAXR) return MSD_ERR_INVALID_ARG;
+  if (a.M <= 1) return launch_fused_mr<WAVES, STEPS, NT, 1>(a, stream);
+  if (a.M <= 2) return launch_fused_mr<WAVES, STEPS, NT, 2>(a, stream);
+  if constexpr (MAXR >= 4) {
+    if (a.M <= 4) return launch_fused_mr<WAVES, STEPS, NT, 4>(a, stream);
+  }
+  if constexpr (MAXR >= 8) {
+    if (a.M <= 8) return launch_fused_mr<WAVES, STEPS, NT, 8>(a, stream);
+  }
+  if constexpr (MAXR >= 16) return launch_fused_mr<WAVES, STEPS, NT, 16>(a, stream);
+  return MSD_ERR_INVALID_ARG;
 }
 
 template <int WAVES, int UNROLL, int RT, int NT, bool SELF>
@@ -913,6 +1113,13 @@ static W8Path w8_path(int64_t M, int64_t K, int64_t N) {
   return k64 ? W8Path::kFillLarge : W8Path::kStaged;
 }
 
+// Fragments of the fragment-major code layout this shape's GEMM reads (the register-operand kernels); 0: not used.
+int gemm_w8_frag_rt(int64_t M, int64_t K, int64_t N) {
+  if (gemm_w8_is_fused(M, K, N) || K % 64 != 0 || K < 64) return 0;
+  if (w8_path(M, K, N) != W8Path::kDecode) return 0;
+  return 2 * M <= 16 ? 1 : 2 * M <= 32 ? 2 : 4;
+}
+
 // Stage depth (bytes of K per row) of the blocked code layout this shape's GEMM reads; 0: row-major.
 int gemm_w8_blocked_bk(int64_t M, int64_t K, int64_t N) {
   if (gemm_w8_is_fused(M, K, N)) return 0;
@@ -930,8 +1137,28 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   const W8Path path = w8_path(M, a.K, N);
   if (a.a_step != 0 && (a.x != nullptr || (path != W8Path::kFillSmall && path != W8Path::kFillLarge)))
     return MSD_ERR_INVALID_ARG;  // only the asynchronous-fill kernels read the blocked layout
+  if ((a.a_step != 0 || a.x != nullptr) && a.a_frag != 0) return MSD_ERR_INVALID_ARG;
   if (a.x != nullptr) {  // the caller asked for the single-launch path (gemm_w8_is_fused)
-    rc = launch_decode<4, 8, 1, 1, true>(a, stream);
+    switch (fused_instance(M, a.K, N)) {
+      case kFused4x4: rc = launch_fused<4, 4, 1>(a, stream); break;
+      case kFused4x8: rc = launch_fused<4, 8, 1>(a, stream); break;
+      case kFused4x16: rc = launch_fused<4, 16, 1>(a, stream); break;
+      case kFused4x16x2: rc = launch_fused<4, 16, 2>(a, stream); break;
+      case kFused8x8x4: rc = launch_fused<8, 8, 4>(a, stream); break;
+      case kFused8x16: rc = launch_fused<8, 16, 1>(a, stream); break;
+      case kFused8x16x2: rc = launch_fused<8, 16, 2>(a, stream); break;
+      default: rc = launch_decode<4, 8, 1, 1, true>(a, stream);
+    }
+  } else if (a.a_frag != 0) {
+    // fragment-major codes (gemm_w8_frag_rt): the register-operand kernel, with the whole K range of a wave in
+    // one batch of loads where the registers allow it (measured against the instances below at K = 4096)
+    if (path != W8Path::kDecode || a.a_frag != (2 * M <= 16 ? 1 : 2 * M <= 32 ? 2 : 4)) return MSD_ERR_INVALID_ARG;
+    if (a.a_frag == 1)
+      rc = wide ? launch_decode<4, 8, 1, 2, false>(a, stream) : launch_decode<4, 16, 1, 1, false>(a, stream);
+    else if (a.a_frag == 2)
+      rc = wide ? launch_decode<8, 4, 2, 2, false>(a, stream) : launch_decode<4, 16, 2, 1, false>(a, stream);
+    else
+      rc = wide ? launch_decode<8, 2, 4, 4, false>(a, stream) : launch_decode<8, 4, 4, 1, false>(a, stream);
   } else if (path == W8Path::kDecode) {
     if (2 * M <= 16)
       rc = wide ? launch_decode<4, 8, 1, 2, false>(a, stream) : launch_decode<4, 8, 1, 1, false>(a, stream);

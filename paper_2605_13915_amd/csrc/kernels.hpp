@@ -14,9 +14,10 @@ struct Int8Range {
 
 // ---- decomposition (decompose.hip)
 // a_step != 0: write the blocked layout of GemmW8Args (stage depth a_bk) instead of row-major [M][ldq]
+// frag_rt != 0: write the fragment-major layout (GemmW8Args::a_frag) with frag_rt fragments of 16 stacked rows
 int launch_decompose_int8(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, int8_t* q1,
                           int8_t* q2, int64_t ldq, float* alpha, int64_t a_step, int a_bk, Int8Range rg,
-                          hipStream_t stream);
+                          hipStream_t stream, int frag_rt = 0);
 int launch_decompose_mxfp4(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, uint8_t* abi_q1,
                            uint8_t* abi_q2, uint8_t* abi_e8m0, uint32_t* op_q1, uint32_t* op_q2,
                            uint8_t* op_e8m0, MxVariant mv, hipStream_t stream);
@@ -47,10 +48,17 @@ struct GemmW8Args {
   // rounded up to 128
   int64_t a_step;
   int a_bk;
+  // fragment-major code layout for the register-operand kernels (a_frag = number of 16-row fragments RT, 0: off):
+  // q1 holds both components, stacked row i = m or M + m; the 16 bytes of K step s, byte group g of stacked row
+  // i sit at ((s * RT + i/16) * 64 + g * 16 + i%16) * 16, so that a wave's operand load is one contiguous
+  // kilobyte (a load whose 64 lanes touch 16 different rows runs at a third of that rate)
+  int a_frag;
   Int8Range rg;  // range constants of the decomposition and of beta in the epilogue
 };
 // stage depth of the blocked layout launch_gemm_w8 wants for this shape (0: row-major)
 int gemm_w8_blocked_bk(int64_t M, int64_t K, int64_t N);
+// number of 16-row fragments of the fragment-major layout launch_gemm_w8 wants for this shape (0: not used)
+int gemm_w8_frag_rt(int64_t M, int64_t K, int64_t N);
 // true when launch_gemm_w8 runs the decomposition itself (single launch)
 bool gemm_w8_is_fused(int64_t M, int64_t K, int64_t N);
 int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream);

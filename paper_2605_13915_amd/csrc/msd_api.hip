@@ -190,10 +190,11 @@ int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
   } else if (K > 0) {
     // codes in the layout the GEMM kernel of this shape reads; observation points want row-major
     const bool code_taps = taps && (taps->q1 || taps->q2);
-    a.a_bk = code_taps ? 0 : gemm_w8_blocked_bk(M, K, N);
+    a.a_frag = code_taps ? 0 : gemm_w8_frag_rt(M, K, N);
+    a.a_bk = (code_taps || a.a_frag) ? 0 : gemm_w8_blocked_bk(M, K, N);
     if (a.a_bk) a.a_step = (int64_t)align_up((size_t)M, 128) * a.a_bk;  // Mpad rows of a_bk bytes per stage
     int rc = launch_decompose_int8((const uint16_t*)x_bf16, M, K, ldx, (int8_t*)a.q1, (int8_t*)a.q2, K,
-                                   (float*)a.alpha, a.a_step, a.a_bk ? a.a_bk : 64, rg, s);
+                                   (float*)a.alpha, a.a_step, a.a_bk ? a.a_bk : 64, rg, s, a.a_frag);
     if (rc) return rc;
   } else {
     int rc = fill_u32((uint32_t*)a.alpha, M, 0u, s);

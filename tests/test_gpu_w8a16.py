@@ -64,6 +64,13 @@ SHAPES = [
     (70, 320, 6500, 1),        # batched decode, 64x64 tiles, ragged M and N
     (30, 512, 8300, 1),        # 16 < M <= 32 with many columns: 32x64 tiles of the asynchronous-fill kernel
     (32, 528, 8300, 0),        # same M and N, K not a multiple of 64: register-operand kernel, wide variant
+    # the single-launch kernel with every load in flight at once (M*K <= 16384), one case per instance
+    (4, 4096, 4096, 1), (3, 4096, 1000, 1),   # 4 waves x 16 K steps
+    (2, 4096, 8300, 1),        # many column tiles, two per workgroup
+    (4, 4096, 8300, 1),        # many column tiles, 8 waves x 8 steps, four tiles per workgroup
+    (8, 2048, 530, 1), (5, 2048, 8300, 0),   # 4 x 8
+    (13, 1024, 90, 1),         # 4 x 4, 16-row bound, two A fragments
+    (2, 8192, 300, 1), (1, 8192, 8300, 1),   # 8 x 16, one and two tiles per workgroup
 ]
 
 
@@ -91,11 +98,20 @@ def test_gemm_w8a16_parity(msd, M, K, N, outl):
 
 
 @pytest.mark.parametrize("M,K,N", [(128, 4096, 1024), (100, 1024, 700), (96, 2112, 520), (65, 192, 300),
-                                   (128, 4096, 14336 // 4), (1, 4096, 1024), (2, 1040, 300), (8, 4096, 512)])
+                                   (128, 4096, 14336 // 4), (1, 4096, 1024), (2, 1040, 300), (8, 4096, 512),
+                                   # fragment-major codes (register-operand kernels): 1, 2 and 4 fragments, few and
+                                   # many column tiles, K with a partial last batch of steps, ragged N
+                                   (5, 4096, 8300), (8, 4096, 4096), (16, 4096, 4100), (12, 2112, 700),
+                                   (32, 4096, 4096), (27, 4096, 1000), (9, 64, 20), (15, 8192, 8300),
+                                   (20, 1088, 333), (6, 16384, 520),
+                                   # single-launch kernel without observation points
+                                   (4, 4096, 4096), (16, 1024, 1024), (7, 2048, 8300), (2, 8192, 4000)])
 def test_gemm_w8a16_product_path_without_taps(msd, M, K, N):
     """The path a caller without observation points takes.  y starts as NaN."""
     seed = synth.seed_for(1, M * 11 + N)
     x = synth.activations(seed, M, K, outliers=True)
+    if M >= 3:
+        x[1, :] = 0      # an all-zero row between the others
     W, s = synth.int8_weights(seed, N, K)
     y_ref = oracle.gemm_w8a16(x, W, s)
     y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
