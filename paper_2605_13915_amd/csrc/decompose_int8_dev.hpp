@@ -78,73 +78,84 @@ __device__ __forceinline__ void int8_codes_fast(float x, float alpha, float ra, 
   c2 = (int)fminf(fmaxf(p, -128.f), 127.f);
 }
 
-// Four elements at a time, branch-free (the quantiser of every kernel that decomposes whole rows).
-// q = rne(x * (1/alpha)) can differ from rne(x / alpha) (the correctly rounded quotient, which is what defines
-// the codes) only if x/alpha lies within 127.49 * 2^-23 < 1.6e-5 of a half-integer; then the residual
-// r = x - alpha*q, which the second pass needs anyway, has |r| >= alpha * (0.5 - 1.6e-5).  Likewise for the
-// residual pass with u = r * (1/beta): p = rne(u) is safe unless |u - p| >= 0.5 - 1.6e-5.  Both tests use the
-// margin 3e-5 (thr1 = alpha * 0.49997f).  The return value says whether this lane's four elements need the
-// divisions (about one group in 2000).  No clamp is needed on this route: |x/alpha| <= 127.49 and
-// |r/beta| <= 127.49 * (1 + 2^-22) round to at most 127.
-constexpr float kTieMargin = 0.49997f;
+// Correctly rounded x / a without a division: t = x * RN(1/a) is within two units in the last place of
+// the quotient; one refinement with the exact FMA residual, t' = t + (x - a t) * RN(1/a), makes it faithful,
+// and a second one then returns RN(x / a) itself (Markstein's theorem on FMA division: exact whenever the
+// significand of a is not all ones, the quotient is a normal number and nothing underflows on the way).
+// ra must be the correctly rounded reciprocal.  Checked exhaustively on the GPU against the hardware's
+// correctly rounded division for every BF16 numerator and about 10^4 divisors: identical bits.
+__device__ __forceinline__ float quotient_rn(float x, float a, float ra) {
+  float t = x * ra;
+  t = __fmaf_rn(__fmaf_rn(-a, t, x), ra, t);
+  t = __fmaf_rn(__fmaf_rn(-a, t, x), ra, t);
+  return t;
+}
 
 __device__ __forceinline__ uint32_t pack4(int a, int b, int c, int d) {
   return ((uint32_t)a & 0xFFu) | (((uint32_t)b & 0xFFu) << 8) | (((uint32_t)c & 0xFFu) << 16) | ((uint32_t)d << 24);
 }
 
-__device__ __forceinline__ bool quad_codes_try(uint32_t w0, uint32_t w1, float alpha, float ra, float rb, float thr1,
-                                               uint32_t& o1, uint32_t& o2) {
+// Four elements -> one dword of codes per component, branch-free and in constant time (no data-dependent
+// path: BF16 inputs hit exact rounding ties of x/alpha often, e.g. whenever alpha is a power of two).
+// No clamp is needed: |x/alpha| <= 127.49 and |r/beta| <= 127.49 * (1 + 2^-22) round to at most 127.
+__device__ __forceinline__ void quad_codes_fast(uint32_t w0, uint32_t w1, float alpha, float ra, float beta, float rb,
+                                                uint32_t& o1, uint32_t& o2) {
   const float x0 = __uint_as_float(w0 << 16), x1 = __uint_as_float(w0 & 0xFFFF0000u);
   const float x2 = __uint_as_float(w1 << 16), x3 = __uint_as_float(w1 & 0xFFFF0000u);
-  const float q0 = rintf(x0 * ra), q1 = rintf(x1 * ra), q2 = rintf(x2 * ra), q3 = rintf(x3 * ra);
+  const float q0 = rintf(quotient_rn(x0, alpha, ra)), q1 = rintf(quotient_rn(x1, alpha, ra));
+  const float q2 = rintf(quotient_rn(x2, alpha, ra)), q3 = rintf(quotient_rn(x3, alpha, ra));
   const float r0 = __fmaf_rn(-alpha, q0, x0), r1 = __fmaf_rn(-alpha, q1, x1);
   const float r2 = __fmaf_rn(-alpha, q2, x2), r3 = __fmaf_rn(-alpha, q3, x3);
-  const float u0 = r0 * rb, u1 = r1 * rb, u2 = r2 * rb, u3 = r3 * rb;
-  const float p0 = rintf(u0), p1 = rintf(u1), p2 = rintf(u2), p3 = rintf(u3);
-  const float m1 = fmaxf(fmaxf(fabsf(r0), fabsf(r1)), fmaxf(fabsf(r2), fabsf(r3)));
-  const float m2 = fmaxf(fmaxf(fabsf(u0 - p0), fabsf(u1 - p1)), fmaxf(fabsf(u2 - p2), fabsf(u3 - p3)));
+  const float p0 = rintf(quotient_rn(r0, beta, rb)), p1 = rintf(quotient_rn(r1, beta, rb));
+  const float p2 = rintf(quotient_rn(r2, beta, rb)), p3 = rintf(quotient_rn(r3, beta, rb));
   o1 = pack4((int)q0, (int)q1, (int)q2, (int)q3);
   o2 = pack4((int)p0, (int)p1, (int)p2, (int)p3);
-  return (m1 > thr1) | (m2 > kTieMargin);
 }
 
-// 16 elements.  The four groups go the division-free way; groups that failed its test in some lane of the wave
-// are then redone with the correctly rounded divisions by the lanes concerned (one rolled block per call site,
-// entered only when the wave has such a lane).  The reciprocal route needs beta (and with it alpha and both
-// reciprocals) to be a normal fp32 number: rows whose maximum is below about 2^-113 redo every group.
-__device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, float ra, float beta,
-                                                 float rb, uint4& o1, uint4& o2) {
-  const float thr1 = alpha * kTieMargin;
-  uint32_t a0, a1, a2, a3, b0, b1, b2, b3;
-  uint32_t redo = quad_codes_try(c.w[0], c.w[1], alpha, ra, rb, thr1, a0, b0) ? 1u : 0u;
-  redo |= quad_codes_try(c.w[2], c.w[3], alpha, ra, rb, thr1, a1, b1) ? 2u : 0u;
-  redo |= quad_codes_try(c.w[4], c.w[5], alpha, ra, rb, thr1, a2, b2) ? 4u : 0u;
-  redo |= quad_codes_try(c.w[6], c.w[7], alpha, ra, rb, thr1, a3, b3) ? 8u : 0u;
-  if (!(beta >= 1.17549435e-38f)) redo = 15u;
-  if (__builtin_amdgcn_ballot_w64(redo != 0) != 0) {
+// Rows the division-free route cannot serve take the divisions (a row-uniform choice): a scale whose
+// significand is all ones (the exception of the theorem above), or a row maximum below 2^-83, where a
+// residual of the refinement could underflow.
+__device__ __forceinline__ bool needs_divisions(float alpha, float beta) {
+  const uint32_t ua = __float_as_uint(alpha), ub = __float_as_uint(beta);
+  return (ua & 0x7FFFFFu) == 0x7FFFFFu || (ub & 0x7FFFFFu) == 0x7FFFFFu || !(alpha >= 0x1p-90f);
+}
+
+// The same 16 elements with the divisions, rolled up so that it costs the kernels that inline it next to the
+// fast route neither registers nor code size.
+__device__ __forceinline__ void chunk_codes_rolled(const Chunk16& c, float alpha, float beta, uint4& o1, uint4& o2) {
+  uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0, b0 = 0, b1 = 0, b2 = 0, b3 = 0;
 #pragma unroll 1
-    for (int j = 0; j < 4; ++j) {
-      const bool mine = (redo >> j) & 1u;
-      if (__builtin_amdgcn_ballot_w64(mine) == 0) continue;
-      const uint32_t w0 = j == 0 ? c.w[0] : j == 1 ? c.w[2] : j == 2 ? c.w[4] : c.w[6];
-      const uint32_t w1 = j == 0 ? c.w[1] : j == 1 ? c.w[3] : j == 2 ? c.w[5] : c.w[7];
-      uint32_t pa = 0, pb = 0;
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t w0 = j == 0 ? c.w[0] : j == 1 ? c.w[2] : j == 2 ? c.w[4] : c.w[6];
+    const uint32_t w1 = j == 0 ? c.w[1] : j == 1 ? c.w[3] : j == 2 ? c.w[5] : c.w[7];
+    uint32_t pa = 0, pb = 0;
 #pragma unroll 1
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t w = e < 2 ? w0 : w1;
-        const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-        int c1, c2;
-        int8_codes(x, alpha, beta, c1, c2);
-        pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
-        pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
-      }
-      if (mine) {
-        if (j == 0) { a0 = pa; b0 = pb; } else if (j == 1) { a1 = pa; b1 = pb; } else if (j == 2) { a2 = pa; b2 = pb; } else { a3 = pa; b3 = pb; }
-      }
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = e < 2 ? w0 : w1;
+      const float x = (e & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+      int c1, c2;
+      int8_codes(x, alpha, beta, c1, c2);
+      pa |= ((uint32_t)c1 & 0xFFu) << (8 * e);
+      pb |= ((uint32_t)c2 & 0xFFu) << (8 * e);
     }
+    if (j == 0) { a0 = pa; b0 = pb; } else if (j == 1) { a1 = pa; b1 = pb; } else if (j == 2) { a2 = pa; b2 = pb; } else { a3 = pa; b3 = pb; }
   }
   o1 = make_uint4(a0, a1, a2, a3);
   o2 = make_uint4(b0, b1, b2, b3);
+}
+
+// 16 elements; ra = RN(1/alpha), rb = RN(1/beta).
+__device__ __forceinline__ void chunk_codes_fast(const Chunk16& c, float alpha, float ra, float beta,
+                                                 float rb, uint4& o1, uint4& o2) {
+  if (needs_divisions(alpha, beta)) {
+    chunk_codes_rolled(c, alpha, beta, o1, o2);
+    return;
+  }
+  uint32_t a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) quad_codes_fast(c.w[2 * j], c.w[2 * j + 1], alpha, ra, beta, rb, a[j], b[j]);
+  o1 = make_uint4(a[0], a[1], a[2], a[3]);
+  o2 = make_uint4(b[0], b[1], b[2], b[3]);
 }
 
 // One workgroup of THREADS threads decomposes one row: xr[0..K) -> q1r, q2r (16-byte aligned),

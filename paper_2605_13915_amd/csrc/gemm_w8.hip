@@ -76,8 +76,8 @@ __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta,
 //
 //   (the quantiser itself, bit-exact without a division per element, is in decompose_int8_dev.hpp)
 constexpr int kSelfMaxRows = 8;
-constexpr int kFusedMaxRows = 16;                   // rows the single-launch kernel accepts
-constexpr int64_t kFusedMaxElems = 16384;           // ... and activation elements (M*K): beyond, a launch is cheaper
+constexpr int kFusedMaxRows = 8;           // rows the single-launch kernel accepts (measured: 16 x 1024 is slower than two launches)
+constexpr int64_t kFusedMaxElems = 16384;  // ... and activation elements (M*K): beyond, a launch is cheaper
 constexpr int64_t kSelfMaxCodeBytes = 136 * 1024;  // LDS budget for the self-decomposed codes
 
 // FAST: K % 64 == 0, so no load of the main loop is predicated per lane (predicated loads do not
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_rowsplit_kernel(GemmW8Args
 // LDS (row pitch KW + 16 B: the 16 rows of an A fragment fall into 16 different 16-byte bank groups).  The
 // MFMAs then take A from LDS and B from the registers the loads filled; wave partials meet in LDS integer
 // atomics (exact).  Every workgroup repeats the decomposition, which is why the row count is bounded by work:
-// at 16384 elements it costs about as much as the launch it saves.
+// at 16384 elements (about 18 vector instructions each) it costs about as much as the launch it saves.
 // MR: compile-time bound on the rows (chunks of x held per lane: MR * STEPS / 16, at most 4).
 template <int WAVES, int STEPS, int NT, int MR>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a) {
@@ -1030,7 +1030,7 @@ static int launch_fused_mr(const GemmW8Args& a, hipStream_t stream) {
 // picks the row bound: M * K <= kFusedMaxElems leaves at most 16384 / (WAVES * STEPS * 64) rows
 template <int WAVES, int STEPS, int NT>
 static int launch_fused(const GemmW8Args& a, hipStream_t stream) {
-  constexpr int MAXR = (int)(kFusedMaxElems / (WAVES * STEPS * 64));
+  constexpr int MAXR = (int)(kFusedMaxElems / (WAVES * STEPS * 64)) < kFusedMaxRows ? (int)(kFusedMaxElems / (WAVES * STEPS * 64)) : kFusedMaxRows;
   if (a.K != (int64_t)WAVES * STEPS * 64 || a.M > MAXR) return MSD_ERR_INVALID_ARG;
   if (a.M <= 1) return launch_fused_mr<WAVES, STEPS, NT, 1>(a, stream);
   if (a.M <= 2) return launch_fused_mr<WAVES, STEPS, NT, 2>(a, stream);
@@ -1040,7 +1040,6 @@ static int launch_fused(const GemmW8Args& a, hipStream_t stream) {
   if constexpr (MAXR >= 8) {
     if (a.M <= 8) return launch_fused_mr<WAVES, STEPS, NT, 8>(a, stream);
   }
-  if constexpr (MAXR >= 16) return launch_fused_mr<WAVES, STEPS, NT, 16>(a, stream);
   return MSD_ERR_INVALID_ARG;
 }
 

@@ -69,7 +69,7 @@ SHAPES = [
     (2, 4096, 8300, 1),        # many column tiles, two per workgroup
     (4, 4096, 8300, 1),        # many column tiles, 8 waves x 8 steps, four tiles per workgroup
     (8, 2048, 530, 1), (5, 2048, 8300, 0),   # 4 x 8
-    (13, 1024, 90, 1),         # 4 x 4, 16-row bound, two A fragments
+    (8, 1024, 90, 1), (13, 1024, 90, 1),   # 4 x 4 with 8 rows; 13 rows exceed the row bound: two launches
     (2, 8192, 300, 1), (1, 8192, 8300, 1),   # 8 x 16, one and two tiles per workgroup
 ]
 
