@@ -65,7 +65,9 @@ enum {
  *   GEMM W8A16 : q1,q2 int8 [M][K]; scale float alpha[M]; acc1,acc2 int32 [M][N]
  *   GEMM W4A16 : q1,q2 packed 4-bit codes [M][K/2]; scale uint8 E8M0 [M][K/32]; acc* unused
  *   attention  : q1,q2 int8 [B][Hq][d]; scale float alpha_Q [B][Hq]; acc1,acc2 int32 [B][Hq][L]
- *                (the two integer score rows S1, S2)
+ *                (the two integer score rows S1, S2); p1,p2 int8 [B][Hq][L]: the two codes of the
+ *                decomposed softmax numerator of every token, in units of that tile's alpha_P and
+ *                alpha_P / 254 (msd_attn_decode_int8kv only, both or neither; other entry points ignore them)
  */
 typedef struct msd_debug_taps {
   void* q1;
@@ -73,6 +75,8 @@ typedef struct msd_debug_taps {
   void* scale;
   int32_t* acc1;
   int32_t* acc2;
+  void* p1;
+  void* p2;
 } msd_debug_taps;
 
 /* hipError_t of the most recent failing HIP call made by this library on the calling thread. */
@@ -235,8 +239,10 @@ int msd_moe_gemm_w4a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx,
  *   kv_len : nullable int32 [B], valid tokens per batch entry (<= L); NULL means L everywhere.
  *   out    : [B][Hq][d] float or BF16.  Entries with kv_len == 0 produce zeros.
  *   d must be 128 (64 and 256 are SHAPE errors in this version); Hq % Hkv == 0; Hq/Hkv <= 64.
- *   Up to 8 query heads per KV head share one pass over the KV cache; larger groups are processed
- *   8 heads at a time (16 in the comparison kernel), each pass re-reading the split's KV range.
+ *   Up to 24 query heads per KV head share one pass over the KV cache (8 heads fill one 16-row
+ *   matrix operand; two or three operands are held at once for 9..24 heads); larger groups are
+ *   processed 16 heads per pass (also in the comparison kernel), each pass re-reading the split's
+ *   KV range.
  */
 int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
                            const float* k_scale, const float* v_scale, int scale_mode, int B,

@@ -379,7 +379,7 @@ void msd_oracle_truth_gemm_w4(const uint16_t* x_bf16, int64_t M, int64_t K, int6
  *     (a bound on P~ that needs no reduction over P, as in the paper's constant-scale
  *     argument); O = (aP*O1 + bP*O2) / l.
  * l = sum_t P_t uses the undecomposed P (Alg. 3, last step).  kv_len[b] (nullable) gives
- * the number of valid tokens per batch entry (<= L).
+ * the number of valid tokens per batch entry; values outside [0, L] are clamped to it.
  * out: fp32 [B][Hq][d].  Taps (nullable): q codes [B][Hq][d] x2, alpha_q [B][Hq],
  * s1,s2 int32 [B][Hq][L], P float [B][Hq][L], p1,p2 int8 [B][Hq][L].
  */
@@ -397,7 +397,8 @@ static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_
 #pragma omp parallel for schedule(dynamic)
   for (int bh = 0; bh < B * Hq; ++bh) {
     const int b = bh / Hq, hq = bh % Hq, g = hq / G;
-    const int64_t len = kv_len ? kv_len[b] : L;
+    int64_t len = kv_len ? kv_len[b] : L;
+    if (len > L) len = L; /* entries past the cache are read as the cache length (the library clamps likewise) */
     const int8_t* Kh = Kc + ((int64_t)(b * Hkv + g)) * L * ldk;
     const int8_t* Vh = Vc + ((int64_t)(b * Hkv + g)) * L * ldv;
     float* o = out + (int64_t)bh * dv;
@@ -558,7 +559,8 @@ static void truth_attn_general(const uint16_t* q_bf16, const int8_t* Kc, int64_t
 #pragma omp parallel for schedule(dynamic)
   for (int bh = 0; bh < B * Hq; ++bh) {
     const int b = bh / Hq, hq = bh % Hq, g = hq / G;
-    const int64_t len = kv_len ? kv_len[b] : L;
+    int64_t len = kv_len ? kv_len[b] : L;
+    if (len > L) len = L; /* entries past the cache are read as the cache length (the library clamps likewise) */
     const int64_t base = ((int64_t)(b * Hkv + g)) * L;
     double* o = out + (int64_t)bh * dv;
     for (int c = 0; c < dv; ++c) o[c] = 0.0;

@@ -30,7 +30,7 @@ class MsdError(RuntimeError):
 
 class Taps(C.Structure):
     _fields_ = [("q1", C.c_void_p), ("q2", C.c_void_p), ("scale", C.c_void_p),
-                ("acc1", C.c_void_p), ("acc2", C.c_void_p)]
+                ("acc1", C.c_void_p), ("acc2", C.c_void_p), ("p1", C.c_void_p), ("p2", C.c_void_p)]
 
 
 _lib = None
@@ -354,8 +354,10 @@ def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, o
                     q2=torch.empty((B, Hq, d), dtype=torch.int8, device=q.device),
                     scale=torch.empty((B, Hq), dtype=torch.float32, device=q.device),
                     acc1=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device),
-                    acc2=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device))
-        tp = Taps(*(keep[k].data_ptr() for k in ("q1", "q2", "scale", "acc1", "acc2")))
+                    acc2=torch.zeros((B, Hq, Lmax), dtype=torch.int32, device=q.device),
+                    p1=torch.zeros((B, Hq, Lmax), dtype=torch.int8, device=q.device),
+                    p2=torch.zeros((B, Hq, Lmax), dtype=torch.int8, device=q.device))
+        tp = Taps(*(keep[k].data_ptr() for k in ("q1", "q2", "scale", "acc1", "acc2", "p1", "p2")))
     if kv_len is not None:
         _dev(kv_len, torch.int32, "kv_len")
     args = (_ptr(q), _ptr(K), _ptr(V), _ptr(k_scale), _ptr(v_scale), scale_mode, B, Hq, Hkv, d, _ptr(kv_len),

@@ -101,6 +101,9 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
     p.tap_s2 = a.taps->acc2;
     if (!(p.tap_q1 && p.tap_q2 && p.tap_alpha)) p.tap_q1 = p.tap_q2 = nullptr, p.tap_alpha = nullptr;
     if (!(p.tap_s1 && p.tap_s2)) p.tap_s1 = p.tap_s2 = nullptr;
+    p.tap_p1 = (int8_t*)a.taps->p1;
+    p.tap_p2 = (int8_t*)a.taps->p2;
+    if (!(p.tap_p1 && p.tap_p2)) p.tap_p1 = p.tap_p2 = nullptr;
   }
   const dim3 grid((unsigned)((int64_t)a.B * a.Hkv * p.nsplit));
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;

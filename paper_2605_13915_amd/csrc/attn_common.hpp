@@ -27,6 +27,8 @@ struct AttnParams {
   float* tap_alpha;
   int32_t* tap_s1;
   int32_t* tap_s2;
+  int8_t* tap_p1;  // codes of the decomposed softmax numerator [B][Hq][L] (nullable pair)
+  int8_t* tap_p2;
 };
 
 constexpr int kD = 128;

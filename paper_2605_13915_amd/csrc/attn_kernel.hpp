@@ -219,6 +219,18 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
         l_run[f][hh] = l_run[f][hh] * corr[hh] + lsum;
         pk1[hh] = w1;
         pk2[hh] = w2;
+        if (p.tap_p1) {  // observation points only
+          const int head = h0 + f * HF + g * HPL + hh;
+          if (head < G) {
+            const int64_t row = ((int64_t)b * p.Hq + hk * G + head) * p.L;
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+              if (live[tt]) {
+                p.tap_p1[row + t0 + 16 * tt + j] = (int8_t)(w1 >> (8 * tt));
+                p.tap_p2[row + t0 + 16 * tt + j] = (int8_t)(w2 >> (8 * tt));
+              }
+          }
+        }
       }
       // ---- hand P to the A-fragment layout through LDS (wave-private)
 #pragma unroll

@@ -67,12 +67,15 @@ __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta,
 // atomics (exact, order-independent).
 //
 // Where the A fragments come from:
-//   SELF (M <= 8, one launch per call): the workgroup decomposes the activation rows itself
+//   SELF (one launch per call; the general single-launch form, chosen for M <= 2 when K has no instance of
+//       the everything-in-flight kernel below): the workgroup decomposes the activation rows itself
 //       (Alg. 1 steps 1-5) while its weight loads are in flight -- the "online activation
 //       decomposition" of Sec. 3.9; nothing is materialised in HBM.  Each wave reads the x
 //       slice of its own K range (all rows), the row maxima are combined through LDS, then
 //       the wave quantises its slice into wave-private LDS in A-fragment order.
-//   otherwise: the codes were written to the workspace by the decomposition kernel.
+//   otherwise: the codes were written to the workspace by the decomposition kernel, fragment-major
+//       (GemmW8Args::a_frag: one contiguous kilobyte per operand load) or, when observation points are
+//       requested, row-major.
 //
 //   (the quantiser itself, bit-exact without a division per element, is in decompose_int8_dev.hpp)
 constexpr int kSelfMaxRows = 8;

@@ -1,9 +1,16 @@
 """GPU parity: msd_attn_decode_int8kv against the CPU oracle, through the C ABI.
 
 Bar: Q component codes, alpha_Q bits and the two integer score rows S1, S2 bit-exact; the
-fp32 output within relative L2 1e-3 of the oracle (P codes are not compared: they depend on
-the exp implementation and, for per-token scales, on the tile the scale bound is taken over)
-and of the fp64 truth."""
+fp32 output within relative L2 1e-3 of the oracle and of the fp64 truth.  The kernel is tiled
+(Sec. 4.3): it decomposes P = exp(S - running max) tile by tile (and, with per-token scales, takes
+alpha_P per 64-token tile), the oracle decomposes exp(S - row max) once; both are the method, and
+their outputs differ by the decomposition error itself (up to a few 1e-4 here), so 1e-3 is the
+bar whenever a row spans several tiles.  When the whole row is ONE tile (L <= 64) the two compute
+the same thing up to the rounding of exp, and the bar is tight: the combined P code
+254*P1 + P2 of every token within 2 units of the oracle's and the output within 1e-4 per head
+(measured 1e-7 to 3e-5: a single code that falls the other way at a rounding tie moves a short row by 3e-5) --
+a slip in alpha_P, beta_P, a clamp or the 254*O1 + O2 merge would not pass that.  The measured
+distances are printed (pytest -s shows them)."""
 import numpy as np
 import pytest
 import torch
@@ -38,6 +45,10 @@ CASES = [
     (2, 32, 2, 200, "channel", None),         # G = 16
     (1, 40, 2, 130, "channel", None),         # G = 20: ragged last head group
     (1, 48, 1, 1100, "token", [1000]),        # G = 48, several KV splits
+    # single-tile rows: the tight bar on the P path (every head-group layout, both scale modes)
+    (2, 8, 2, 64, "channel", None), (2, 8, 2, 64, "token", None),
+    (1, 4, 1, 37, "channel", None), (3, 8, 1, 50, "token", [50, 1, 33]),
+    (2, 32, 2, 64, "channel", None), (1, 24, 1, 45, "token", None), (1, 40, 1, 64, "channel", None),
 ]
 
 
@@ -73,10 +84,29 @@ def test_attn_decode_parity(msd, B, Hq, Hkv, L, mode, kv_len):
     assert rel_l2(o[live], ref[live]) <= 1e-3
     assert rel_l2(o[live], truth[live]) <= 1e-3
     # per head, not only in aggregate
+    worst = 0.0
+    one_tile = max(lens) <= 64
+    tol = 1e-4 if one_tile else 1e-3   # one unit of alpha_P/254 on one of a few dozen tokens is ~3e-5
     for b in range(B):
         if lens[b] > 0:
             for h in range(Hq):
-                assert rel_l2(o[b, h], ref[b, h]) <= 1e-3
+                dist = rel_l2(o[b, h], ref[b, h])
+                worst = max(worst, dist)
+                assert dist <= tol, (b, h, dist)
+    print("attention parity %s B%d Hq%d Hkv%d L%d: worst per-head rel-L2 vs oracle %.2e, vs fp64 truth %.2e"
+          % (mode, B, Hq, Hkv, L, worst, rel_l2(o[live], truth[live])))
+    if one_tile:
+        # the P decomposition itself (Alg. 3 steps 8-9): combined fixed-point code 254*P1 + P2 per token
+        zg = 254 * g["p1"].cpu().numpy().astype(np.int32) + g["p2"].cpu().numpy().astype(np.int32)
+        zr = 254 * t["p1"].astype(np.int32) + t["p2"].astype(np.int32)
+        nbad, ntot = 0, 0
+        for b in range(B):
+            dz = np.abs(zg[b, :, :lens[b]] - zr[b, :, :lens[b]])
+            assert dz.max(initial=0) <= 2, (b, int(dz.max()))
+            nbad += int((dz > 0).sum())
+            ntot += dz.size
+        assert nbad <= 0.02 * ntot, (nbad, ntot)
+        print("  P codes: %d of %d tokens differ from the oracle (by at most 2 units of alpha_P/254)" % (nbad, ntot))
 
 
 def test_attn_bf16_output_and_errors(msd):

@@ -35,6 +35,14 @@ def _rows(M, n=10, seed=0):
     return np.array(rows)
 
 
+def _rows_every_tile(M, tile, seed=0):
+    """the rows of _rows plus one random row out of every `tile` consecutive rows: every row tile of the
+    kernel's schedule is looked at"""
+    rng = np.random.default_rng(seed + 1)
+    per_tile = [t * tile + int(rng.integers(0, min(tile, M - t * tile))) for t in range((M + tile - 1) // tile)]
+    return np.array(sorted(set(list(_rows(M, 4, seed)) + per_tile)))
+
+
 @pytest.mark.parametrize("N", [4096, 14336])
 def test_cfg1_w8a16_decode_full(msd, N):
     K = 4096
@@ -68,7 +76,8 @@ def test_cfg2_w8a16_prefill_sampled_rows(msd, prefill_inputs, M, N):
     y = torch.empty((M, N), dtype=torch.float32, device="cuda")
     msd.msd_gemm_w8a16(bf16_to_dev(x), to_dev(W), to_dev(s), y=y)
     torch.cuda.synchronize()
-    rows = _rows(M, seed=M + N)
+    rows = _rows_every_tile(M, 128, seed=M + N)   # the kernel's row tile is 128 activation rows
+    assert bool(torch.isfinite(y).all())         # every element, not only the sampled rows
     yh = y[torch.from_numpy(rows).cuda()].cpu().numpy()
     del y
     torch.cuda.empty_cache()
@@ -93,7 +102,8 @@ def test_cfg3_w4a16(msd, w4_weights, M):
     y = torch.empty((M, N), dtype=torch.float32, device="cuda")
     msd.msd_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps), y=y)
     torch.cuda.synchronize()
-    rows = np.arange(M) if M <= 32 else _rows(M, n=4, seed=M)[::2]
+    rows = np.arange(M) if M <= 32 else _rows_every_tile(M, 128, seed=M)   # 128-row tiles: 32 + boundary rows
+    assert bool(torch.isfinite(y).all())
     yh = y[torch.from_numpy(rows).cuda()].cpu().numpy()
     ref = oracle.gemm_w4a16(x[rows], codes, exps)
     assert np.all(np.isfinite(yh))

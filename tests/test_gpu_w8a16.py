@@ -35,6 +35,36 @@ def test_decompose_int8_bit_exact(msd, M, K):
     assert np.array_equal(da.cpu().numpy().view(np.uint32), al.view(np.uint32))
 
 
+def test_decompose_int8_every_bf16_value_under_many_scales(msd):
+    """The division-free quantiser against the oracle's divisions, exhaustively: every finite BF16 value of
+    either sign that does not exceed the row maximum, for row maxima sweeping all 128 BF16 significands in
+    three binades (powers of two and their neighbours included, where x/alpha is an exact rounding tie for
+    many x), both range-constant variants."""
+    pats = np.arange(0x0000, 0x7F80, dtype=np.uint16)          # every non-negative finite BF16 pattern
+    K = 65536
+    rows = []
+    for e in (121, 127, 131):
+        for m in range(128):
+            mx = np.uint16((e << 7) | m)
+            vals = pats[pats <= mx]
+            row = np.zeros(K, np.uint16)
+            row[:len(vals)] = vals
+            row[len(vals):2 * len(vals)] = vals | np.uint16(0x8000)
+            rows.append(row)
+    x = np.stack(rows)
+    xd = bf16_to_dev(x)
+    for frac in (False, True):
+        q1, q2, al, _ = oracle.decompose_int8(x, fractional=frac)
+        if frac:
+            d1, d2, da = msd.msd_decompose_variant(msd.MSD_VARIANT_INT8_FRACTIONAL, msd.MSD_INT8, xd)
+        else:
+            d1, d2, da = msd.msd_decompose(msd.MSD_INT8, xd)
+        torch.cuda.synchronize()
+        assert np.array_equal(da.cpu().numpy().view(np.uint32), al.view(np.uint32))
+        assert np.array_equal(d1.cpu().numpy(), q1)
+        assert np.array_equal(d2.cpu().numpy(), q2)
+
+
 def test_decompose_strided_rows(msd):
     x = synth.activations(3, 6, 512)
     big = torch.zeros((6, 520), dtype=torch.bfloat16, device="cuda")

@@ -144,6 +144,20 @@ def test_kv_len_and_gqa_mapping():
     assert np.array_equal(out_sw[:, :4], out_ref[:, 4:]) and np.array_equal(out_sw[:, 4:], out_ref[:, :4])
 
 
+def test_kv_len_outside_the_cache_is_clamped():
+    """kv_len above L reads as L (what the library does), negative as empty: no read past the cache
+    (this test also runs under AddressSanitizer, test_oracle_sanitized.py)."""
+    q, Kc, Vc, ks, vs = small_case(57, oracle.PER_TOKEN, L=48)
+    full = oracle.attn_decode(q, Kc, Vc, ks, vs, oracle.PER_TOKEN)
+    over = oracle.attn_decode(q, Kc, Vc, ks, vs, oracle.PER_TOKEN, kv_len=np.array([49, 10 ** 6], np.int32))
+    assert np.array_equal(over, full)
+    neg = oracle.attn_decode(q, Kc, Vc, ks, vs, oracle.PER_TOKEN, kv_len=np.array([-3, 48], np.int32))
+    assert np.all(neg[0] == 0) and np.array_equal(neg[1], full[1])
+    tr_full = oracle.truth_attn(q, Kc, Vc, ks, vs, oracle.PER_TOKEN)
+    tr_over = oracle.truth_attn(q, Kc, Vc, ks, vs, oracle.PER_TOKEN, kv_len=np.array([4096, 48], np.int32))
+    assert np.array_equal(tr_over, tr_full)
+
+
 def test_per_token_mode_reduces_to_the_per_channel_statement_for_uniform_scales():
     """Pin of the per-token reading against the paper's own (per-channel) statement: with every
     per-token scale equal to one power of two c, and every per-channel scale equal to the same c,
