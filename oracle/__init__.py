@@ -197,8 +197,9 @@ def _attn_args(q_bf16, Kc, Vc, k_scale, v_scale, kv_len):
     return q, Kc, Vc, ks, vs, kl, B, Hq, Hkv, d, L
 
 
-def attn_decode(q_bf16, Kc, Vc, k_scale, v_scale, scale_mode, kv_len=None, taps=False):
-    """Alg. 3 (untiled).  Returns out float32 [B][Hq][d] (+ taps dict)."""
+def attn_decode(q_bf16, Kc, Vc, k_scale, v_scale, scale_mode, kv_len=None, taps=False, lowprec=False):
+    """Alg. 3 (untiled).  Returns out float32 [B][Hq][d] (+ taps dict).  lowprec: the low-precision arithmetic
+    of Sec. 4.4 ("optimisation opportunities"): integer S merge, FP16 decomposition of P."""
     q, Kc, Vc, ks, vs, kl, B, Hq, Hkv, d, L = _attn_args(q_bf16, Kc, Vc, k_scale, v_scale, kv_len)
     if scale_mode == PER_TOKEN:
         assert ks.shape == (B, Hkv, L) and vs.shape == (B, Hkv, L)
@@ -211,7 +212,8 @@ def attn_decode(q_bf16, Kc, Vc, k_scale, v_scale, scale_mode, kv_len=None, taps=
                  alpha_q=np.empty((B, Hq), np.float32), s1=np.zeros((B, Hq, L), np.int32),
                  s2=np.zeros((B, Hq, L), np.int32), p=np.zeros((B, Hq, L), np.float32),
                  p1=np.zeros((B, Hq, L), np.int8), p2=np.zeros((B, Hq, L), np.int8))
-    lib().msd_oracle_attn_decode(_p(q), _p(Kc), _p(Vc), _p(ks), _p(vs), C.c_int(scale_mode),
+    fn = lib().msd_oracle_attn_decode_lowprec if lowprec else lib().msd_oracle_attn_decode
+    fn(_p(q), _p(Kc), _p(Vc), _p(ks), _p(vs), C.c_int(scale_mode),
                                  C.c_int(B), C.c_int(Hq), C.c_int(Hkv), C.c_int(d), _p(kl),
                                  C.c_int64(L), _p(out), _p(t.get("q1")), _p(t.get("q2")),
                                  _p(t.get("alpha_q")), _p(t.get("s1")), _p(t.get("s2")),

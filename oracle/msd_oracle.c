@@ -386,9 +386,41 @@ void msd_oracle_truth_gemm_w4(const uint16_t* x_bf16, int64_t M, int64_t K, int6
 /* The general form behind both entry points: query / key rows of d channels, value rows of dv
  * channels, key row t of KV head g at Kc + ((b*Hkv + g)*L + t)*ldk (values likewise with ldv), scores
  * multiplied by sm_scale.  Per-channel scales: k_scale [Hkv][d], v_scale [Hkv][dv]. */
+/* Nearest binary16 (FP16) value of x, ties to even, returned as a float; |x| < 65520.  binary16 keeps 11
+ * significant bits down to 2^-14 and a fixed quantum of 2^-24 below.  A sum, difference or product of two
+ * binary16 values computed in fp32 and rounded with this function is the correctly rounded binary16 result
+ * (fp32 carries 24 >= 2*11 + 2 bits, so the intermediate rounding is harmless). */
+static float f16_rne(float x) {
+  if (x == 0.0f || !isfinite(x)) return x;
+  int e;
+  (void)frexpf(fabsf(x), &e); /* |x| = m * 2^e with m in [0.5, 1) */
+  int q = e - 11;             /* exponent of the last kept bit */
+  if (q < -24) q = -24;
+  return copysignf(ldexpf(rintf(ldexpf(fabsf(x), -q)), q), x);
+}
+
+/* Low-precision variant of the attention arithmetic (Sec. 4.4, "optimisation opportunities": the decomposition
+ * (round, clamp) and the S / O merging (scale, add) "in FP16 or even INT16 instead of FP32").  The paper gives
+ * one sentence; the reading taken here (lowprec != 0):
+ *   S merge    : alpha_Q S1 + beta_Q S2 = beta_Q (254 S1 + S2) exactly, so the merge is the exact integer
+ *                z = 254 S1 + S2 (|z| < 2^30), ONE conversion to fp32 and ONE fp32 multiply by
+ *                c_t = (beta_Q * sm_scale) * s_K[t] (both products in fp32).  Integer arithmetic replaces the
+ *                scale-and-add; FP16 cannot hold S1 (up to 127*127*d).
+ *   P codes    : v = P~ / alpha_P (in [0, 127]) is formed in fp32 as before, rounded ONCE to FP16 (ties to
+ *                even), and both passes run in FP16: q1 = rne(v_h) via (v_h + 1536) - 1536 (FP16 quantum at
+ *                1536 is 1), r = v_h - q1 (exact), u = RN16(254 r), q2 = rne(u) the same way.  No clamp can
+ *                fire: v_h <= 127 and |r| <= 1/2 give |u| <= 127.
+ *   O merge    : alpha_P O1 + beta_P O2 = beta_P (254 O1 + O2), the same identity (exact in this oracle, which
+ *                carries O in fp64 either way).
+ * Error of the decomposition, in units of alpha_P, for v in [0, 127]:
+ *   |v - (q1 + q2/254)| <= |v - v_h| + |r - q2/254| <= 2^-11 v + (1/2 + 2^-5) / 254,
+ * the first term from the one FP16 rounding (relative 2^-11), the second from rne(u) (1/2) plus the FP16
+ * rounding of u < 128 (half a quantum of 2^-4).  Against the fp32 form's 1/508 this is (1 + 2^-4)/508 plus a
+ * RELATIVE 2^-11: 32 times larger for the largest probabilities, equal for small ones.  q1, r and the two
+ * magic-number roundings are exact FP16 operations. */
 static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_t ldk, const int8_t* Vc,
                                 int64_t ldv, const float* k_scale, const float* v_scale, int scale_mode,
-                                int B, int Hq, int Hkv, int d, int dv, double sm_scale,
+                                int B, int Hq, int Hkv, int d, int dv, double sm_scale, int lowprec,
                                 const int32_t* kv_len, int64_t L, float* out, int8_t* tap_q1,
                                 int8_t* tap_q2, float* tap_alpha_q, int32_t* tap_s1, int32_t* tap_s2,
                                 float* tap_p, int8_t* tap_p1, int8_t* tap_p2) {
@@ -452,8 +484,16 @@ static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_
       }
       if (tap_s1) tap_s1[(int64_t)bh * L + t] = (int32_t)s1;
       if (tap_s2) tap_s2[(int64_t)bh * L + t] = (int32_t)s2;
-      double s = ((double)aq * (double)s1 + (double)bq * (double)s2) * inv_sqrt_d;
-      if (scale_mode == MSD_SCALE_PER_TOKEN) s *= (double)k_scale[((int64_t)(b * Hkv + g)) * L + t];
+      double s;
+      if (lowprec) { /* integer merge, one conversion, one fp32 multiply */
+        const float zf = (float)(254 * s1 + s2);
+        float c = bq * (float)inv_sqrt_d;
+        if (scale_mode == MSD_SCALE_PER_TOKEN) c = c * k_scale[((int64_t)(b * Hkv + g)) * L + t];
+        s = (double)(zf * c);
+      } else {
+        s = ((double)aq * (double)s1 + (double)bq * (double)s2) * inv_sqrt_d;
+        if (scale_mode == MSD_SCALE_PER_TOKEN) s *= (double)k_scale[((int64_t)(b * Hkv + g)) * L + t];
+      }
       S[t] = s;
       if (s > smax) smax = s;
     }
@@ -477,7 +517,31 @@ static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_
     int8_t* p1 = (int8_t*)malloc((size_t)len);
     int8_t* p2 = (int8_t*)malloc((size_t)len);
     double ap, bp;
-    if (scale_mode == MSD_SCALE_PER_TOKEN) {
+    if (lowprec) {
+      float to_code; /* 1 / alpha_P */
+      if (scale_mode == MSD_SCALE_PER_TOKEN) {
+        const float apf = ap_num / 127.0f;
+        ap = apf;
+        bp = apf / 254.0f;
+        to_code = ap_num > 0.0f ? 127.0f / ap_num : 0.0f;
+      } else {
+        ap = 1.0 / 127.0;
+        bp = 1.0 / (127.0 * 254.0);
+        to_code = 127.0f;
+      }
+      for (int64_t t = 0; t < len; ++t) {
+        float v = P[t];
+        if (scale_mode == MSD_SCALE_PER_TOKEN) v = v * v_scale[((int64_t)(b * Hkv + g)) * L + t];
+        v = v * to_code;                               /* fp32, in [0, 127] */
+        const float vh = f16_rne(v);                   /* the one rounding to FP16 */
+        const float c1 = f16_rne(f16_rne(vh + 1536.0f) - 1536.0f);
+        const float r = f16_rne(vh - c1);              /* exact */
+        const float u = f16_rne(r * 254.0f);
+        const float c2 = f16_rne(f16_rne(u + 1536.0f) - 1536.0f);
+        p1[t] = (int8_t)c1;
+        p2[t] = (int8_t)c2;
+      }
+    } else if (scale_mode == MSD_SCALE_PER_TOKEN) {
       const float apf = ap_num / 127.0f, bpf = apf / 254.0f;
       ap = apf;
       bp = bpf;
@@ -529,7 +593,18 @@ void msd_oracle_attn_decode(const uint16_t* q_bf16, const int8_t* Kc, const int8
                             int8_t* tap_q1, int8_t* tap_q2, float* tap_alpha_q, int32_t* tap_s1,
                             int32_t* tap_s2, float* tap_p, int8_t* tap_p1, int8_t* tap_p2) {
   attn_decode_general(q_bf16, Kc, d, Vc, d, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, d,
-                      1.0 / sqrt((double)d), kv_len, L, out, tap_q1, tap_q2, tap_alpha_q, tap_s1, tap_s2, tap_p,
+                      1.0 / sqrt((double)d), 0, kv_len, L, out, tap_q1, tap_q2, tap_alpha_q, tap_s1, tap_s2, tap_p,
+                      tap_p1, tap_p2);
+}
+
+/* The same with the low-precision arithmetic described above attn_decode_general. */
+void msd_oracle_attn_decode_lowprec(const uint16_t* q_bf16, const int8_t* Kc, const int8_t* Vc,
+                                    const float* k_scale, const float* v_scale, int scale_mode, int B,
+                                    int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, float* out,
+                                    int8_t* tap_q1, int8_t* tap_q2, float* tap_alpha_q, int32_t* tap_s1,
+                                    int32_t* tap_s2, float* tap_p, int8_t* tap_p1, int8_t* tap_p2) {
+  attn_decode_general(q_bf16, Kc, d, Vc, d, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, d,
+                      1.0 / sqrt((double)d), 1, kv_len, L, out, tap_q1, tap_q2, tap_alpha_q, tap_s1, tap_s2, tap_p,
                       tap_p1, tap_p2);
 }
 
@@ -545,7 +620,7 @@ void msd_oracle_mla_decode(const uint16_t* q_bf16, const int8_t* C, int64_t ld, 
                            int scale_mode, int B, int Hq, int dk, int dv, double sm_scale,
                            const int32_t* kv_len, int64_t L, float* out, int8_t* tap_q1, int8_t* tap_q2,
                            float* tap_alpha_q, int32_t* tap_s1, int32_t* tap_s2) {
-  attn_decode_general(q_bf16, C, ld, C, ld, scale, scale, scale_mode, B, Hq, 1, dk, dv, sm_scale, kv_len, L, out,
+  attn_decode_general(q_bf16, C, ld, C, ld, scale, scale, scale_mode, B, Hq, 1, dk, dv, sm_scale, 0, kv_len, L, out,
                       tap_q1, tap_q2, tap_alpha_q, tap_s1, tap_s2, NULL, NULL, NULL);
 }
 

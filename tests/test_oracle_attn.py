@@ -295,3 +295,88 @@ def test_latent_cache_against_numpy_softmax_and_fp64_truth(mode):
     out = oracle.mla_decode(q, Cl, sc, mode, dv, sm, kv_len=kv_len)
     num = np.linalg.norm(out - truth)
     assert num / np.linalg.norm(truth) < 1e-3
+
+
+# ---------------------------------------------------------------- low-precision variant (Sec. 4.4, optimisation opportunities)
+def _lowprec_case(seed, mode, L=200, B=2, Hq=8, Hkv=2):
+    q, Kc, Vc, ks, vs = small_case(seed, mode, L=L, B=B, Hq=Hq, Hkv=Hkv)
+    out, t = oracle.attn_decode(q, Kc, Vc, ks, vs, mode, taps=True, lowprec=True)
+    return (q, Kc, Vc, ks, vs), out, t
+
+
+@pytest.mark.parametrize("mode", [oracle.PER_CHANNEL, oracle.PER_TOKEN])
+def test_lowprec_p_codes_equal_an_independent_float16_implementation(mode):
+    """The FP16 steps written a second time with numpy's float16 type (correctly rounded +, -, *):
+    q1 = rne(v_h), r = v_h - q1, q2 = rne(RN16(254 r)), from the oracle's own P row.  Bit for bit."""
+    (q, Kc, Vc, ks, vs), out, t = _lowprec_case(71, mode)
+    B, Hq, L = t["p"].shape
+    G = Hq // Kc.shape[1]
+    for b in range(B):
+        for h in range(Hq):
+            P = t["p"][b, h]
+            if mode == oracle.PER_TOKEN:
+                sv = vs[b, h // G]
+                v = (P * sv).astype(np.float32) * (np.float32(127.0) / sv.max())
+            else:
+                v = np.float32(127.0) * P
+            vh = v.astype(np.float32).astype(np.float16)
+            c1 = np.rint(vh.astype(np.float64))                       # round-half-even of an FP16 value, exact
+            r = (vh - c1.astype(np.float16)).astype(np.float16)
+            assert np.array_equal(r.astype(np.float64), vh.astype(np.float64) - c1)   # the residual is exact
+            u = (r * np.float16(254.0)).astype(np.float16)
+            c2 = np.rint(u.astype(np.float64))
+            assert np.array_equal(t["p1"][b, h], c1.astype(np.int8)), (b, h)
+            assert np.array_equal(t["p2"][b, h], c2.astype(np.int8)), (b, h)
+            assert c1.min() >= 0 and c1.max() <= 127 and np.abs(c2).max() <= 127
+
+
+def test_lowprec_decomposition_bound_and_closed_forms():
+    """|v - (q1 + q2/254)| <= 2^-11 v + (1/2 + 2^-5)/254 in units of alpha_P (derived in the oracle's header),
+    and it is attained to within a factor of two (the bound is not slack by an order of magnitude)."""
+    (q, Kc, Vc, ks, vs), out, t = _lowprec_case(72, oracle.PER_CHANNEL, L=4000, B=1, Hq=4, Hkv=1)
+    v = 127.0 * t["p"].astype(np.float64)
+    rec = t["p1"].astype(np.float64) + t["p2"].astype(np.float64) / 254.0
+    err = np.abs(v - rec)
+    bound = 2.0 ** -11 * v + (0.5 + 2.0 ** -5) / 254.0
+    assert np.all(err <= bound * (1 + 1e-6) + 127.0 * 2.0 ** -24)
+    assert (err / bound).max() > 0.5
+    # the largest probability of every row is exp(0) = 1: codes (127, 0), reconstructed exactly
+    imax = t["p"].argmax(axis=2)
+    for h in range(4):
+        assert t["p"][0, h, imax[0, h]] == 1.0
+        assert t["p1"][0, h, imax[0, h]] == 127 and t["p2"][0, h, imax[0, h]] == 0
+
+
+def test_lowprec_half_probability_ties_to_even():
+    """Two identical keys with scores S and S - ln 2 are not constructible exactly; instead feed the FP16 steps
+    through a row where P is exactly 1/2: L = 2 identical keys give P = (1, 1); scaled value scales make
+    P~ = (s, s/2).  127 * 1/2 = 63.5 is an exact tie: q1 = 64 (even), r = -1/2, q2 = -127, reconstruction exact."""
+    B, Hq, Hkv, d, L = 1, 1, 1, 128, 2
+    rng = np.random.default_rng(5)
+    q = synth.queries(5, B, Hq, d)
+    Kc = np.repeat(rng.integers(-127, 128, (B, Hkv, 1, d), dtype=np.int8), L, axis=2)
+    Vc = rng.integers(-127, 128, (B, Hkv, L, d), dtype=np.int8)
+    ks = np.ones((B, Hkv, L), np.float32)
+    vs = np.array([[[0.25, 0.125]]], np.float32)
+    out, t = oracle.attn_decode(q, Kc, Vc, ks, vs, oracle.PER_TOKEN, taps=True, lowprec=True)
+    assert np.array_equal(t["p"][0, 0], [1.0, 1.0])
+    assert list(t["p1"][0, 0]) == [127, 64] and list(t["p2"][0, 0]) == [0, -127]
+    ref = (0.25 * Vc[0, 0, 0].astype(np.float64) + 0.125 * Vc[0, 0, 1].astype(np.float64)) / 2.0
+    assert np.allclose(out[0, 0], ref, rtol=1e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("mode", [oracle.PER_CHANNEL, oracle.PER_TOKEN])
+def test_lowprec_integer_merge_and_accuracy_ordering(mode):
+    """The integer S merge changes nothing that is defined exactly: Q codes, S1, S2 equal the main variant's,
+    P differs by fp32 roundings only.  Accuracy against the fp64 truth: still well below 1e-3, and worse than
+    the fp32 arithmetic (the FP16 rounding of the large probabilities), as the bound says."""
+    (q, Kc, Vc, ks, vs), out, t = _lowprec_case(73, mode, L=700)
+    main, tm = oracle.attn_decode(q, Kc, Vc, ks, vs, mode, taps=True)
+    for k in ("q1", "q2", "s1", "s2"):
+        assert np.array_equal(t[k], tm[k])
+    assert np.allclose(t["p"], tm["p"], rtol=2e-5, atol=1e-9)
+    truth = oracle.truth_attn(q, Kc, Vc, ks, vs, mode)
+    e_low = np.linalg.norm(out - truth) / np.linalg.norm(truth)
+    e_main = np.linalg.norm(main - truth) / np.linalg.norm(truth)
+    assert e_low < 1e-3
+    assert e_main < e_low < 8 * e_main + 1e-5
