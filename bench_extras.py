@@ -178,6 +178,8 @@ def leg_attn(msd, synth, time_calls, dev):
         fcc = lambda i: msd.msd_dequant_attn_decode_int8kv(q, sets[i % n][0], sets[i % n][1], kc, vc,
                                                            msd.MSD_PER_CHANNEL, out=o, ws=ws, prepare=True)
         us_ch_cmp = time_calls(fcc, 4 * n)
+        us_low = time_calls(lambda i: msd.msd_attn_decode_int8kv_variant(msd.MSD_VARIANT_ATTN_LOWPREC, q, *sets[i % n],
+                                                                         msd.MSD_PER_TOKEN, out=o, ws=ws, prepare=True), 4 * n)
         # accuracy of both kernels against an fp64 attention over the exactly dequantised cache (two batch
         # entries; the quantity of the paper's flash-attention error table, Sec. 6.4, on this workload)
         acc = None
@@ -198,7 +200,10 @@ def leg_attn(msd, synth, time_calls, dev):
             Kc0, Vc0, ks0, vs0 = sets[0]
             acc = {}
             t_tok, t_ch = truth(Kc0, Vc0, ks0, vs0, True), truth(Kc0, Vc0, kc, vc, False)
+            low = lambda *a_, **k_: msd.msd_attn_decode_int8kv_variant(msd.MSD_VARIANT_ATTN_LOWPREC, *a_, **k_)
             for name, fn, args_, t in (("msd_per_token", msd.msd_attn_decode_int8kv, (ks0, vs0, msd.MSD_PER_TOKEN), t_tok),
+                                       ("msd_lowprec_per_token", low, (ks0, vs0, msd.MSD_PER_TOKEN), t_tok),
+                                       ("msd_lowprec_per_channel", low, (kc, vc, msd.MSD_PER_CHANNEL), t_ch),
                                        ("dequant_per_token", msd.msd_dequant_attn_decode_int8kv, (ks0, vs0, msd.MSD_PER_TOKEN), t_tok),
                                        ("msd_per_channel", msd.msd_attn_decode_int8kv, (kc, vc, msd.MSD_PER_CHANNEL), t_ch),
                                        ("dequant_per_channel", msd.msd_dequant_attn_decode_int8kv, (kc, vc, msd.MSD_PER_CHANNEL), t_ch)):
@@ -217,7 +222,7 @@ def leg_attn(msd, synth, time_calls, dev):
         out.append({"B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "L": L, "us": round(us, 1),
                     "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM, 4),
                     "bare_kv_read_us": round(bare_us, 1), "dequant_us": round(us_cmp, 1),
-                    "speedup_vs_dequant": round(us_cmp / us, 3),
+                    "speedup_vs_dequant": round(us_cmp / us, 3), "lowprec_us": round(us_low, 1),
                     "per_channel": {"us": round(us_ch, 1), "dequant_us": round(us_ch_cmp, 1),
                                     "GBps": round((kvbytes + 6 * B * Hq * d) / us_ch / 1e3, 1),
                                     "speedup_vs_dequant": round(us_ch_cmp / us_ch, 3)}})
@@ -255,7 +260,11 @@ def leg_nq_sweep(msd, synth, time_calls, dev):
                 return (q, K_, V_, kc, vc, mode) if mode == msd.MSD_PER_CHANNEL else (q, K_, V_, ks_, vs_, mode)
             us = time_calls(lambda i: msd.msd_attn_decode_int8kv(*args(i), out=o, ws=ws, prepare=True), 2 * n)
             us_c = time_calls(lambda i: msd.msd_dequant_attn_decode_int8kv(*args(i), out=o, ws=ws, prepare=True), 2 * n)
-            row[name] = {"msd_us": round(us, 1), "dequant_us": round(us_c, 1), "speedup_vs_dequant": round(us_c / us, 3)}
+            # the low-precision arithmetic of Sec. 4.4 (integer S / O merge, FP16 decomposition of P)
+            us_l = time_calls(lambda i: msd.msd_attn_decode_int8kv_variant(msd.MSD_VARIANT_ATTN_LOWPREC, *args(i), out=o,
+                                                                           ws=ws, prepare=True), 2 * n)
+            row[name] = {"msd_us": round(us, 1), "dequant_us": round(us_c, 1), "speedup_vs_dequant": round(us_c / us, 3),
+                         "msd_lowprec_us": round(us_l, 1), "lowprec_speedup_vs_dequant": round(us_c / us_l, 3)}
         rows.append(row)
     return {"B": B, "Hkv": Hkv, "d": d, "L": L, "kv_bytes": kvbytes, "rows": rows}
 

@@ -56,7 +56,8 @@ enum {
   MSD_VARIANT_INT8_FRACTIONAL = 1, /* INT8: alpha = max|x| / 127.49, beta = alpha / 254.98 */
   MSD_VARIANT_MXFP4_V1 = 2,        /* MXFP4: alpha bound 1.75, beta = alpha / 8 (no clipping) */
   MSD_VARIANT_MXFP4_V2 = 3,        /* MXFP4: alpha bound 1.75, beta = alpha / 16 */
-  MSD_VARIANT_MXFP4_E2M1 = 4       /* MXFP4 ablation: both components on the MX FP4 element grid */
+  MSD_VARIANT_MXFP4_E2M1 = 4,      /* MXFP4 ablation: both components on the MX FP4 element grid */
+  MSD_VARIANT_ATTN_LOWPREC = 5     /* attention: integer S / O merge, FP16 decomposition of P (Sec. 4.4) */
 };
 
 /*
@@ -250,6 +251,26 @@ int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
                            int out_dtype, void* workspace, size_t workspace_bytes,
                            const msd_debug_taps* taps, void* stream);
 size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);
+
+/*
+ * msd_attn_decode_int8kv with the low-precision arithmetic the paper lists among its optimisation
+ * opportunities (Sec. 4.4: the decomposition and the S / O merging "in FP16 or even INT16 instead of FP32") for
+ * variant = MSD_VARIANT_ATTN_LOWPREC; variant = MSD_VARIANT_MAIN is msd_attn_decode_int8kv itself.  What changes:
+ *   - S = beta_Q * (254 S1 + S2) / sqrt(d) (times s_K[t]): the merge as one exact integer multiply-add, one
+ *     conversion, one fp32 multiply (alpha_Q S1 + beta_Q S2 = beta_Q (254 S1 + S2) exactly);
+ *   - P (times s_V[t]) / alpha_P, a number in [0, 127], is rounded once to FP16 (ties to even) and decomposed in
+ *     FP16: P1 = rne(v), r = v - P1 (exact), P2 = rne(254 r); no clamp can fire.  Per element
+ *     |v - (P1 + P2/254)| <= 2^-11 v + 1/508 in units of alpha_P, against 1/508 for the fp32 arithmetic;
+ *   - O = beta_P * (254 O1 + O2) per tile, the same identity.
+ * Q codes, alpha_Q and the integer score rows are unchanged (and bit-exact); outputs stay within 1e-3 of the
+ * fp64 attention.  Arguments, workspace, observation points and errors as msd_attn_decode_int8kv; any other
+ * variant is an INVALID_ARG error.
+ */
+int msd_attn_decode_int8kv_variant(int variant, const void* q_bf16, const int8_t* K, const int8_t* V,
+                                   const float* k_scale, const float* v_scale, int scale_mode, int B,
+                                   int Hq, int Hkv, int d, const int32_t* kv_len, int64_t L, void* out,
+                                   int out_dtype, void* workspace, size_t workspace_bytes,
+                                   const msd_debug_taps* taps, void* stream);
 
 /*
  * One decode step of attention over an INT8 latent KV cache (multi-head latent attention; paper

@@ -408,16 +408,16 @@ static float f16_rne(float x) {
  *                scale-and-add; FP16 cannot hold S1 (up to 127*127*d).
  *   P codes    : v = P~ / alpha_P (in [0, 127]) is formed in fp32 as before, rounded ONCE to FP16 (ties to
  *                even), and both passes run in FP16: q1 = rne(v_h) via (v_h + 1536) - 1536 (FP16 quantum at
- *                1536 is 1), r = v_h - q1 (exact), u = RN16(254 r), q2 = rne(u) the same way.  No clamp can
- *                fire: v_h <= 127 and |r| <= 1/2 give |u| <= 127.
+ *                1536 is 1), r = v_h - q1 (exact), q2 = rne(254 r) via the fused (254 r + 1536) - 1536: the
+ *                product is exact inside the fused operation, so q2 is the round-half-even of the exact 254 r.
+ *                No clamp can fire: v_h <= 127 and |r| <= 1/2 give |254 r| <= 127.
  *   O merge    : alpha_P O1 + beta_P O2 = beta_P (254 O1 + O2), the same identity (exact in this oracle, which
  *                carries O in fp64 either way).
  * Error of the decomposition, in units of alpha_P, for v in [0, 127]:
- *   |v - (q1 + q2/254)| <= |v - v_h| + |r - q2/254| <= 2^-11 v + (1/2 + 2^-5) / 254,
- * the first term from the one FP16 rounding (relative 2^-11), the second from rne(u) (1/2) plus the FP16
- * rounding of u < 128 (half a quantum of 2^-4).  Against the fp32 form's 1/508 this is (1 + 2^-4)/508 plus a
- * RELATIVE 2^-11: 32 times larger for the largest probabilities, equal for small ones.  q1, r and the two
- * magic-number roundings are exact FP16 operations. */
+ *   |v - (q1 + q2/254)| <= |v - v_h| + |r - q2/254| <= 2^-11 v + 1/508,
+ * the first term from the one FP16 rounding (relative 2^-11), the second from rne(254 r).  Against the fp32
+ * form's 1/508 this adds a RELATIVE 2^-11: 32 times larger for the largest probabilities, equal for small
+ * ones.  q1, r and q2 are exact functions of v_h. */
 static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_t ldk, const int8_t* Vc,
                                 int64_t ldv, const float* k_scale, const float* v_scale, int scale_mode,
                                 int B, int Hq, int Hkv, int d, int dv, double sm_scale, int lowprec,
@@ -536,8 +536,7 @@ static void attn_decode_general(const uint16_t* q_bf16, const int8_t* Kc, int64_
         const float vh = f16_rne(v);                   /* the one rounding to FP16 */
         const float c1 = f16_rne(f16_rne(vh + 1536.0f) - 1536.0f);
         const float r = f16_rne(vh - c1);              /* exact */
-        const float u = f16_rne(r * 254.0f);
-        const float c2 = f16_rne(f16_rne(u + 1536.0f) - 1536.0f);
+        const float c2 = f16_rne(f16_rne(r * 254.0f + 1536.0f) - 1536.0f); /* r * 254 is exact in fp32: the fused form */
         p1[t] = (int8_t)c1;
         p2[t] = (int8_t)c2;
       }

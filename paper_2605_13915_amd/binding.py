@@ -17,6 +17,7 @@ MSD_F32, MSD_BF16 = 0, 1
 MSD_PER_TOKEN, MSD_PER_CHANNEL = 0, 1
 MSD_VARIANT_MAIN, MSD_VARIANT_INT8_FRACTIONAL, MSD_VARIANT_MXFP4_V1, MSD_VARIANT_MXFP4_V2 = 0, 1, 2, 3
 MSD_VARIANT_MXFP4_E2M1 = 4
+MSD_VARIANT_ATTN_LOWPREC = 5
 
 _ERR = {-1: "MSD_ERR_INVALID_ARG", -2: "MSD_ERR_SHAPE", -3: "MSD_ERR_WORKSPACE", -4: "MSD_ERR_HIP",
         -5: "MSD_ERR_UNSUPPORTED", -6: "MSD_ERR_STATIC_SCRATCH"}
@@ -76,6 +77,8 @@ def lib():
         L.msd_moe_gemm_w8a16.argtypes = [vp, i64, i64, i64, vp, ci, vp, vp, i64, vp, ci, i64, vp, sz, vp]
         L.msd_moe_gemm_w4a16.argtypes = L.msd_moe_gemm_w8a16.argtypes
         L.msd_dequant_attn_decode_int8kv.argtypes = L.msd_attn_decode_int8kv.argtypes
+        L.msd_attn_decode_int8kv_variant.argtypes = [ci] + L.msd_attn_decode_int8kv.argtypes
+        L.msd_attn_decode_int8kv_variant.restype = ci
         L.msd_attn_decode_int8kv_workspace_bytes.argtypes = [ci, ci, ci, ci, i64]
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
@@ -336,7 +339,7 @@ def msd_stream_read(t, prepare=False):
 
 
 def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,
-                           taps=False, out=None, ws=None, prepare=False, _fn="msd_attn_decode_int8kv"):
+                           taps=False, out=None, ws=None, prepare=False, _fn="msd_attn_decode_int8kv", variant=None):
     _dev(q, torch.bfloat16, "q"); _dev(K, torch.int8, "K"); _dev(V, torch.int8, "V")
     _dev(k_scale, torch.float32, "k_scale"); _dev(v_scale, torch.float32, "v_scale")
     B, Hq, d = q.shape
@@ -363,11 +366,18 @@ def msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, o
     args = (_ptr(q), _ptr(K), _ptr(V), _ptr(k_scale), _ptr(v_scale), scale_mode, B, Hq, Hkv, d, _ptr(kv_len),
             Lmax, _ptr(out), _out_code(out.dtype), _ptr(ws), ws.numel(),
             C.byref(tp) if tp is not None else None, _stream())
+    if variant is not None:
+        _fn, args = "msd_attn_decode_int8kv_variant", (int(variant),) + args
     if prepare:
         return Prepared(getattr(L, _fn), args, (q, K, V, k_scale, v_scale, kv_len, out, ws, keep, tp), _fn, out)
     rc = getattr(L, _fn)(*args)
     _check(rc, _fn)
     return (out, keep) if taps else out
+
+
+def msd_attn_decode_int8kv_variant(variant, q, K, V, k_scale, v_scale, scale_mode, **kw):
+    """msd_attn_decode_int8kv with the arithmetic of `variant` (MSD_VARIANT_ATTN_LOWPREC)."""
+    return msd_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, variant=variant, **kw)
 
 
 def msd_dequant_attn_decode_int8kv(q, K, V, k_scale, v_scale, scale_mode, kv_len=None, out_dtype=torch.float32,

@@ -23,11 +23,11 @@
 
 namespace msd {
 
-template <bool PER_TOKEN>
+template <bool PER_TOKEN, bool LOWP>
 static int launch_attn_for_group(const AttnParams& p, dim3 grid, hipStream_t stream) {
-  if (p.G <= 4) return launch_attn_variant<1, PER_TOKEN, false, 1>(p, grid, stream);
-  if (p.G <= 8) return launch_attn_variant<2, PER_TOKEN, false, 1>(p, grid, stream);
-  return launch_attn_wide(p, grid, PER_TOKEN, stream);
+  if (p.G <= 4) return launch_attn_variant<1, PER_TOKEN, false, 1, LOWP>(p, grid, stream);
+  if (p.G <= 8) return launch_attn_variant<2, PER_TOKEN, false, 1, LOWP>(p, grid, stream);
+  return launch_attn_wide(p, grid, PER_TOKEN, LOWP, stream);
 }
 
 // Merge the split partials: out = sum_s O_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
@@ -107,8 +107,12 @@ int launch_attn_decode(const AttnArgs& a, hipStream_t stream) {
   }
   const dim3 grid((unsigned)((int64_t)a.B * a.Hkv * p.nsplit));
   const bool per_token = a.scale_mode == MSD_PER_TOKEN;
-  if (int rc = per_token ? launch_attn_for_group<true>(p, grid, stream) : launch_attn_for_group<false>(p, grid, stream))
-    return rc;
+  int rc;
+  if (a.lowprec)
+    rc = per_token ? launch_attn_for_group<true, true>(p, grid, stream) : launch_attn_for_group<false, true>(p, grid, stream);
+  else
+    rc = per_token ? launch_attn_for_group<true, false>(p, grid, stream) : launch_attn_for_group<false, false>(p, grid, stream);
+  if (rc) return rc;
   if (p.nsplit > 1) return launch_attn_combine(p, per_token ? 0 : 1, stream);
   return MSD_OK;
 }

@@ -84,7 +84,7 @@ inline int attn_plan_nsplit(int B, int Hkv, int64_t L) {
 // fills the split plan, the partial-result pointers inside the workspace and the output fields of p
 void attn_fill_params(const AttnArgs& a, AttnParams& p);
 // launches the kernel instances for more than 8 query heads per KV head (attn_wide.hip)
-int launch_attn_wide(const AttnParams& p, dim3 grid, bool per_token, hipStream_t stream);
+int launch_attn_wide(const AttnParams& p, dim3 grid, bool per_token, bool lowprec, hipStream_t stream);
 // merges the split partials into p.out (attn.hip); call only when p.nsplit > 1
 int launch_attn_combine(const AttnParams& p, int per_channel, hipStream_t stream);
 

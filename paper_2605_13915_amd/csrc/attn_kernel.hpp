@@ -15,7 +15,23 @@ namespace msd {
 // registers, i.e. one wave per SIMD).  MULTI: groups with more heads than that are processed 8*NF
 // heads at a time, one walk over the workgroup's KV range each; without it the head loop has a
 // single trip and disappears.
-template <int HPL, bool PER_TOKEN, bool MULTI, int NF>
+//
+// LOWP: the low-precision arithmetic of Sec. 4.4 ("optimisation opportunities": decomposition and S / O
+// merging in FP16 or integers instead of FP32) for the part of the kernel that runs on the vector ALU per
+// (head, token):
+//   S merge : alpha_Q S1 + beta_Q S2 = beta_Q (254 S1 + S2): one 24-bit integer multiply-add, one conversion,
+//             one fp32 multiply (FP16 cannot hold S1, which reaches 127*127*128);
+//   P codes : v = P~/alpha_P in [0, 127] is rounded once to FP16 and both passes run on packed FP16 pairs:
+//             q1 = rne(v) as (v + 1536) - 1536 (the FP16 quantum at 1536 is 1), r = v - q1 (exact),
+//             q2 = rne(254 r) as the fused 254 r + 1536 (the product is exact inside the FMA); the low byte of
+//             the FP16 pattern of x + 1536 is the INT8 code of rne(x), so packing four codes is one byte
+//             permute.  No clamp can fire (|254 r| <= 127).
+//   O merge : alpha_P O1 + beta_P O2 = beta_P (254 O1 + O2), again one integer multiply-add and one conversion.
+// Per element of P that is |v - (q1 + q2/254)| <= 2^-11 v + 1/508 in units of alpha_P instead of 1/508: the
+// same for small probabilities, a relative 2^-11 for the largest ones.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+template <int HPL, bool PER_TOKEN, bool MULTI, int NF, bool LOWP = false>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams p, int nh_total) {
   constexpr int HF = 4 * HPL;  // heads per fragment
   constexpr int NH = HF * NF;  // head slots of one pass
@@ -195,8 +211,11 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
         float mx = -INFINITY;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
-          const float v =
-              (aq[f][hh] * (float)sd[tt][2 * hh] + bq[f][hh] * (float)sd[tt][2 * hh + 1]) * (sm_scale * sk[tt]);
+          float v;
+          if (LOWP)  // |S1| < 2^21: the 24-bit multiply is exact
+            v = (float)(__mul24(sd[tt][2 * hh], 254) + sd[tt][2 * hh + 1]) * (bq[f][hh] * (sm_scale * sk[tt]));
+          else
+            v = (aq[f][hh] * (float)sd[tt][2 * hh] + bq[f][hh] * (float)sd[tt][2 * hh + 1]) * (sm_scale * sk[tt]);
           s[tt] = live[tt] ? v : -INFINITY;
           mx = fmaxf(mx, s[tt]);
         }
@@ -206,6 +225,29 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
         m_run[f][hh] = m_new;
         float lsum = 0.f;
         uint32_t w1 = 0, w2 = 0;
+        if (LOWP) {
+          float t[4];
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) {
+            const float pr = __builtin_amdgcn_exp2f(s[tt] - m_new);
+            lsum += pr;
+            t[tt] = pr * sv[tt] * to_code;  // P (times s_V) in units of alpha_P, in [0, 127]
+          }
+          const half2_t magic = {(_Float16)1536.0f, (_Float16)1536.0f}, k254 = {(_Float16)254.0f, (_Float16)254.0f};
+          uint32_t m1[2], m2[2];
+#pragma unroll
+          for (int pr2 = 0; pr2 < 2; ++pr2) {
+            const half2_t vh = {(_Float16)t[2 * pr2], (_Float16)t[2 * pr2 + 1]};  // the one rounding to FP16
+            const half2_t a1 = vh + magic;      // integer part in the low mantissa bits
+            const half2_t c1 = a1 - magic;      // rne(vh), exact
+            const half2_t a2 = __builtin_elementwise_fma(vh - c1, k254, magic);  // one rounding: rne(254 r) exactly
+            m1[pr2] = __builtin_bit_cast(uint32_t, a1);
+            m2[pr2] = __builtin_bit_cast(uint32_t, a2);
+          }
+          // byte 0 of each half: codes of tokens tt = 0..3 in bytes 0..3
+          w1 = __builtin_amdgcn_perm(m1[1], m1[0], 0x06040200u);
+          w2 = __builtin_amdgcn_perm(m2[1], m2[0], 0x06040200u);
+        } else {
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
           const float pr = __builtin_amdgcn_exp2f(s[tt] - m_new);
@@ -215,6 +257,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
           const float c2 = fminf(fmaxf(rintf((t - c1) * 254.0f), -127.f), 127.f);
           w1 |= ((uint32_t)(int)c1 & 0xFFu) << (8 * tt);
           w2 |= ((uint32_t)(int)c2 & 0xFFu) << (8 * tt);
+        }
         }
         l_run[f][hh] = l_run[f][hh] * corr[hh] + lsum;
         pk1[hh] = w1;
@@ -262,7 +305,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
         const v4i od = mfma_s8(pa, bf, zero4);
 #pragma unroll
         for (int hh = 0; hh < HPL; ++hh) {
-          const float ot = from_code * ((float)od[2 * hh] + (float)od[2 * hh + 1] * (1.0f / 254.0f));
+          const float ot = LOWP ? (from_code * (1.0f / 254.0f)) * (float)(__mul24(od[2 * hh], 254) + od[2 * hh + 1])
+                                : from_code * ((float)od[2 * hh] + (float)od[2 * hh + 1] * (1.0f / 254.0f));
           o_run[f][hh][c] = o_run[f][hh][c] * corr[hh] + ot;
         }
       }
@@ -321,7 +365,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
   }
 }
 
-template <int HPL, bool PER_TOKEN, bool MULTI, int NF>
+template <int HPL, bool PER_TOKEN, bool MULTI, int NF, bool LOWP = false>
 int launch_attn_variant(const AttnParams& p, dim3 grid, hipStream_t stream) {
   constexpr int HF = 4 * HPL, NH = HF * NF;
   const int nh_total = (int)cdiv(p.G, NH) * NH;
@@ -329,11 +373,11 @@ int launch_attn_variant(const AttnParams& p, dim3 grid, hipStream_t stream) {
                      (size_t)nh_total * 4 + (size_t)2 * nh_total * kD;
   static size_t attr_bytes = 64 * 1024;
   if (lds > attr_bytes) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<HPL, PER_TOKEN, MULTI, NF>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_decode_kernel<HPL, PER_TOKEN, MULTI, NF, LOWP>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_bytes = lds;
   }
-  hipLaunchKernelGGL((attn_decode_kernel<HPL, PER_TOKEN, MULTI, NF>), grid, dim3(kAttnWaves * 64), lds, stream, p, nh_total);
+  hipLaunchKernelGGL((attn_decode_kernel<HPL, PER_TOKEN, MULTI, NF, LOWP>), grid, dim3(kAttnWaves * 64), lds, stream, p, nh_total);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

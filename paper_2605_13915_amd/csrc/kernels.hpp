@@ -153,6 +153,7 @@ struct AttnArgs {
   void* workspace;
   size_t workspace_bytes;
   const msd_debug_taps* taps;
+  int lowprec;  // low-precision arithmetic of the softmax phase (Sec. 4.4, optimisation opportunities)
 };
 int launch_attn_decode(const AttnArgs& a, hipStream_t stream);
 size_t attn_workspace_bytes(int B, int Hq, int Hkv, int d, int64_t L);

@@ -381,7 +381,7 @@ size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int
 
 }  // extern "C"
 
-static int attn_entry(bool dequant, const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
+static int attn_entry(bool dequant, bool lowprec, const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
                            const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
                            const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
                            size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
@@ -409,6 +409,7 @@ static int attn_entry(bool dequant, const void* q_bf16, const int8_t* K, const i
   a.workspace = workspace;
   a.workspace_bytes = workspace_bytes;
   a.taps = dequant ? nullptr : taps;
+  a.lowprec = lowprec ? 1 : 0;
   return dequant ? launch_attn_dequant(a, (hipStream_t)stream) : launch_attn_decode(a, (hipStream_t)stream);
 }
 
@@ -418,15 +419,24 @@ int msd_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V,
                            const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
                            const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
                            size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
-  return attn_entry(false, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, kv_len, L, out, out_dtype,
+  return attn_entry(false, false, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, kv_len, L, out, out_dtype,
                     workspace, workspace_bytes, taps, stream);
+}
+
+int msd_attn_decode_int8kv_variant(int variant, const void* q_bf16, const int8_t* K, const int8_t* V,
+                                   const float* k_scale, const float* v_scale, int scale_mode, int B, int Hq, int Hkv,
+                                   int d, const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                                   size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  if (variant != MSD_VARIANT_MAIN && variant != MSD_VARIANT_ATTN_LOWPREC) return MSD_ERR_INVALID_ARG;
+  return attn_entry(false, variant == MSD_VARIANT_ATTN_LOWPREC, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv,
+                    d, kv_len, L, out, out_dtype, workspace, workspace_bytes, taps, stream);
 }
 
 int msd_dequant_attn_decode_int8kv(const void* q_bf16, const int8_t* K, const int8_t* V, const float* k_scale,
                                    const float* v_scale, int scale_mode, int B, int Hq, int Hkv, int d,
                                    const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
                                    size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
-  return attn_entry(true, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, kv_len, L, out, out_dtype,
+  return attn_entry(true, false, q_bf16, K, V, k_scale, v_scale, scale_mode, B, Hq, Hkv, d, kv_len, L, out, out_dtype,
                     workspace, workspace_bytes, taps, stream);
 }
 

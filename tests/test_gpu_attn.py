@@ -109,6 +109,83 @@ def test_attn_decode_parity(msd, B, Hq, Hkv, L, mode, kv_len):
         print("  P codes: %d of %d tokens differ from the oracle (by at most 2 units of alpha_P/254)" % (nbad, ntot))
 
 
+LOWPREC_CASES = [
+    (2, 8, 2, 64, "channel", None), (2, 8, 2, 64, "token", None), (1, 4, 1, 37, "token", None),   # one tile
+    (1, 24, 1, 45, "channel", None), (2, 32, 2, 64, "token", None),
+    (2, 8, 2, 1000, "token", None), (1, 4, 1, 3000, "channel", [2500]), (3, 8, 1, 700, "token", [700, 0, 333]),
+    (1, 12, 1, 300, "channel", None), (2, 32, 2, 200, "token", None), (1, 48, 1, 1100, "token", [1000]),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,mode,kv_len", LOWPREC_CASES)
+def test_attn_decode_lowprec_parity(msd, B, Hq, Hkv, L, mode, kv_len):
+    """MSD_VARIANT_ATTN_LOWPREC (integer S / O merge, FP16 decomposition of P) against the oracle's lowprec
+    variant.  Q codes, alpha_Q, S1, S2 bit-exact as ever; outputs within 1e-3 of that oracle and of the fp64
+    truth.  Rows of one tile: outputs within 2e-4 and the combined P code within 17 units -- when the two sides'
+    P differ in the last fp32 bit, the one rounding to FP16 can fall the other way, and one FP16 quantum at the
+    top of the range is 2^-4 of alpha_P, i.e. 16 units of alpha_P/254 -- for at most 1 % of the tokens."""
+    d = 128
+    seed = synth.seed_for(4, B * 1000 + L + 7)
+    q = synth.queries(seed, B, Hq, d)
+    if mode == "token":
+        Kc, ks, Vc, vs = synth.kv_cache_per_token(seed, B, Hkv, L, d)
+        omode, gmode = oracle.PER_TOKEN, msd.MSD_PER_TOKEN
+    else:
+        Kc, ks, Vc, vs = synth.kv_cache_per_channel(seed, B, Hkv, L, d)
+        omode, gmode = oracle.PER_CHANNEL, msd.MSD_PER_CHANNEL
+    kl = None if kv_len is None else np.array(kv_len, np.int32)
+    ref, t = oracle.attn_decode(q, Kc, Vc, ks, vs, omode, kv_len=kl, taps=True, lowprec=True)
+    truth = oracle.truth_attn(q, Kc, Vc, ks, vs, omode, kv_len=kl)
+    out, g = msd.msd_attn_decode_int8kv_variant(msd.MSD_VARIANT_ATTN_LOWPREC, bf16_to_dev(q), to_dev(Kc), to_dev(Vc),
+                                                to_dev(ks), to_dev(vs), gmode,
+                                                kv_len=None if kl is None else to_dev(kl), taps=True)
+    torch.cuda.synchronize()
+    lens = [L] * B if kl is None else list(kl)
+    live = np.array([l > 0 for l in lens])
+    assert np.array_equal(g["q1"].cpu().numpy()[live], t["q1"][live])
+    assert np.array_equal(g["q2"].cpu().numpy()[live], t["q2"][live])
+    assert np.array_equal(g["scale"].cpu().numpy().view(np.uint32)[live], t["alpha_q"].view(np.uint32)[live])
+    s1, s2 = g["acc1"].cpu().numpy(), g["acc2"].cpu().numpy()
+    for b in range(B):
+        assert np.array_equal(s1[b, :, :lens[b]], t["s1"][b, :, :lens[b]])
+        assert np.array_equal(s2[b, :, :lens[b]], t["s2"][b, :, :lens[b]])
+    o = out.cpu().numpy()
+    assert np.all(np.isfinite(o)) and np.all(o[~live] == 0)
+    one_tile = max(lens) <= 64
+    tol = 2e-4 if one_tile else 1e-3
+    worst = 0.0
+    for b in range(B):
+        if lens[b] > 0:
+            for h in range(Hq):
+                dist = rel_l2(o[b, h], ref[b, h])
+                worst = max(worst, dist)
+                assert dist <= tol, (b, h, dist)
+                assert rel_l2(o[b, h], truth[b, h]) <= 1e-3, (b, h)
+    print("lowprec attention parity %s B%d Hq%d Hkv%d L%d: worst per-head rel-L2 vs oracle %.2e, vs fp64 truth %.2e"
+          % (mode, B, Hq, Hkv, L, worst, rel_l2(o[live], truth[live])))
+    if one_tile:
+        zg = 254 * g["p1"].cpu().numpy().astype(np.int32) + g["p2"].cpu().numpy().astype(np.int32)
+        zr = 254 * t["p1"].astype(np.int32) + t["p2"].astype(np.int32)
+        nbad, ntot = 0, 0
+        for b in range(B):
+            dz = np.abs(zg[b, :, :lens[b]] - zr[b, :, :lens[b]])
+            assert dz.max(initial=0) <= 17, (b, int(dz.max()))
+            nbad += int((dz > 0).sum())
+            ntot += dz.size
+        assert nbad <= 0.01 * ntot, (nbad, ntot)
+        print("  lowprec P codes: %d of %d tokens differ from the oracle" % (nbad, ntot))
+
+
+def test_attn_variant_rejects_unknown_variant(msd):
+    B, Hq, Hkv, L, d = 1, 4, 1, 64, 128
+    q = synth.queries(3, B, Hq, d)
+    Kc, ks, Vc, vs = synth.kv_cache_per_token(3, B, Hkv, L, d)
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_attn_decode_int8kv_variant(msd.MSD_VARIANT_INT8_FRACTIONAL, bf16_to_dev(q), to_dev(Kc), to_dev(Vc),
+                                           to_dev(ks), to_dev(vs), msd.MSD_PER_TOKEN)
+    assert e.value.code == -1
+
+
 def test_attn_bf16_output_and_errors(msd):
     B, Hq, Hkv, L, d = 1, 4, 1, 256, 128
     q = synth.queries(9, B, Hq, d)
