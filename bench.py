@@ -26,9 +26,78 @@ BF16_PEAK_TFLOPS = 2500.0
 LLC_BYTES = 256 << 20
 
 
+def kernel_sources_sha():
+    """sha256 over the HIP sources of the library: the counter summaries under profiles/ carry the value they
+    were measured at, and a summary taken at other sources is not reported as this build's traffic."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2605_13915_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            with open(os.path.join(d, name), "rb") as fh:
+                h.update(name.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
 def w8_bytes(M, K, N):
     """Algorithmic HBM bytes of one W8A16 call: W once, BF16 x, s_W, fp32 y."""
     return K * N + 2 * M * K + 4 * N + 4 * M * N
+
+
+def cpu_other_configs(oracle, synth, np):
+    """Oracle time for the configurations besides the headline one, on the host cores: full outputs where that
+    takes about a second, otherwise a sample of complete activation rows / batch entries (rows and batch entries
+    are independent, so the time scales linearly) extrapolated to the full shape and labelled so.  About 15 s."""
+    out = {}
+
+    def clock(fn):
+        t0 = time.perf_counter()
+        fn()
+        return time.perf_counter() - t0
+
+    rng = np.random.default_rng(7)
+    # cfg0: full
+    x = synth.activations(synth.seed_for(0), 16, 1024, outliers=False)
+    W, s = synth.int8_weights(synth.seed_for(0), 1024, 1024)
+    out["cfg0"] = {"oracle_s": round(clock(lambda: oracle.gemm_w8a16(x, W, s)), 5), "extrapolated": False, "sample": "full output"}
+    # cfg2: 8 complete activation rows against the full weight matrix
+    K = 8192
+    Wb = rng.integers(-127, 128, (28672, K), dtype=np.int8)
+    sb = rng.random(28672, dtype=np.float32) * 0.009 + 0.001
+    xr = synth.activations(synth.seed_for(2, 0), 8, K, outliers=True)
+    rows = {}
+    for N in (8192, 28672):
+        t8 = clock(lambda: oracle.gemm_w8a16(xr, Wb[:N], sb[:N]))
+        for M in (2048, 8192):
+            rows["M%d_N%d" % (M, N)] = {"oracle_s": round(t8 * M / 8, 2), "extrapolated": True,
+                                        "sample": "8 complete rows, %.3f s" % t8}
+    out["cfg2"] = rows
+    del Wb
+    # cfg3: MXFP4 weights (one 2048-channel slab repeated along N, as in the GPU leg)
+    codes, exps = synth.mxfp4_weights(synth.seed_for(3, 0), 2048, K)
+    codes, exps = np.tile(codes, (14, 1)), np.tile(exps, (14, 1))
+    x1 = synth.activations(synth.seed_for(3, 1), 1, K, outliers=True)
+    x4 = synth.activations(synth.seed_for(3, 32), 4, K, outliers=True)
+    t1 = clock(lambda: oracle.gemm_w4a16(x1, codes, exps))
+    t4 = clock(lambda: oracle.gemm_w4a16(x4, codes, exps))
+    # the oracle decodes the weight matrix once per call: time = a + b*M, fitted to the two samples
+    b_row = max(t4 - t1, 0.0) / 3.0
+    a_call = max(t1 - b_row, 0.0)
+    fit = "a + b*M fitted to M=1 (%.3f s) and M=4 (%.3f s)" % (t1, t4)
+    out["cfg3"] = {"M1": {"oracle_s": round(t1, 3), "extrapolated": False, "sample": "full output"},
+                   "M32": {"oracle_s": round(a_call + 32 * b_row, 2), "extrapolated": True, "sample": fit},
+                   "M4096": {"oracle_s": round(a_call + 4096 * b_row, 1), "extrapolated": True, "sample": fit}}
+    del codes, exps
+    # cfg4: one batch entry (32 query heads on 8 KV heads) of 16
+    for L in (4096, 32768):
+        q = synth.queries(synth.seed_for(4, L), 1, 32, 128)
+        Kc, ks, Vc, vs = synth.kv_cache_per_token(synth.seed_for(4, 1), 1, 8, 4096, 128)
+        rep = L // 4096
+        Kc, Vc, ks, vs = np.tile(Kc, (1, 1, rep, 1)), np.tile(Vc, (1, 1, rep, 1)), np.tile(ks, (1, 1, rep)), np.tile(vs, (1, 1, rep))
+        tb = clock(lambda: oracle.attn_decode(q, Kc, Vc, ks, vs, oracle.PER_TOKEN))
+        out.setdefault("cfg4", {})["L%d" % L] = {"oracle_s": round(tb * 16, 3), "extrapolated": True,
+                                                 "sample": "1 of 16 batch entries, %.3f s" % tb}
+    return out
 
 
 def main():
@@ -138,10 +207,12 @@ def main():
     CH = 12  # steps per graph; consecutive steps use different weight copies (cold HBM)
 
     def step_calls(i):
+        # every call reads a weight copy that no call of the last 500 MB of traffic has touched: the copies of
+        # one N are walked round-robin across steps AND across the four M of a step
         calls = []
-        for (M, N) in shapes:
+        for pos, (M, N) in enumerate(shapes):
             reps, s = weights[N]
-            idx = (i * 3) % len(reps) if N == 4096 else i % len(reps)
+            idx = (i * len(Ms) + pos % len(Ms)) % len(reps)
             calls.append(msd.msd_gemm_w8a16(acts[M], reps[idx], s, y=outs[(M, N)], ws=ws, prepare=True))
         return calls
 
@@ -175,8 +246,10 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-shape device time: HIP events on the launch stream around graph replays of cold-cache calls
-    def time_calls(make_call, n_calls, replays=3):
-        """make_call(i) -> binding.Prepared for call i; returns microseconds per call."""
+    def time_calls(make_call, n_calls, replays=10):
+        """make_call(i) -> binding.Prepared for call i.  Captures the n_calls calls into one HIP graph and replays
+        it `replays` times; returns the MEDIAN microseconds per call (HIP events on the launch stream) and leaves
+        {"median", "min"} in time_calls.last."""
         with torch.cuda.stream(side):
             calls = [make_call(i) for i in range(n_calls)]
             calls[0]()
@@ -184,7 +257,7 @@ def main():
             g = capture(calls)
             g.replay()
             torch.cuda.synchronize()
-            best = float("inf")
+            ts = []
             for _ in range(replays):
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
@@ -192,8 +265,10 @@ def main():
                 g.replay()
                 e1.record(side)
                 e1.synchronize()
-                best = min(best, e0.elapsed_time(e1) * 1e3 / n_calls)
-        return best
+                ts.append(e0.elapsed_time(e1) * 1e3 / n_calls)
+        ts.sort()
+        time_calls.last = {"median": ts[len(ts) // 2], "min": ts[0]}
+        return ts[len(ts) // 2]
 
     per_shape = []
     stream_us = {}
@@ -204,6 +279,7 @@ def main():
             return msd.msd_gemm_w8a16(acts[M], reps[i % len(reps)], s, y=outs[(M, N)], ws=ws, prepare=True)
 
         us = time_calls(mk, 2 * len(reps))
+        us_min = time_calls.last["min"]
         if N not in stream_us:
             # a bare read of the same weight bytes (no arithmetic, one launch), same cold-cache protocol:
             # what this GPU charges for the stream alone at this size
@@ -213,7 +289,8 @@ def main():
         warm = time_calls(lambda i, M=M, N=N, reps=reps, s=s: msd.msd_gemm_w8a16(acts[M], reps[0], s, y=outs[(M, N)],
                                                                              ws=ws, prepare=True), 16)
         b = w8_bytes(M, K, N)
-        per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2), "warm_us_per_call": round(warm, 2),
+        per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2), "us_per_call_min": round(us_min, 2),
+                          "warm_us_per_call": round(warm, 2),
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
                           "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2),
                           "bare_weight_read_us": round(stream_us[N], 2),
@@ -229,11 +306,18 @@ def main():
     # HBM bytes per call from the committed counter summary (FETCH_SIZE / WRITE_SIZE runs of
     # `bench.py --traffic-probe`, scaled by a copy of known size); null when the file has no line for it
     traffic = None
+    traffic_note = "no counter summary"
     try:
         import re
         with open(os.path.join(ROOT, "profiles", "w8a16_decode_hbm_traffic_pmc.txt")) as fh:
-            mt = re.search(r"^traffic M=%d N=%d total_bytes=(\d+)" % (dom["M"], dom["N"]), fh.read(), re.M)
-        traffic = int(mt.group(1)) if mt else None
+            txt = fh.read()
+        ms = re.search(r"^kernel_sources_sha256_16=([0-9a-f]+)", txt, re.M)
+        mt = re.search(r"^traffic M=%d N=%d total_bytes=(\d+)" % (dom["M"], dom["N"]), txt, re.M)
+        if ms and ms.group(1) == kernel_sources_sha() and mt:
+            traffic = int(mt.group(1))
+            traffic_note = "profiles/w8a16_decode_hbm_traffic_pmc.txt, taken at these kernel sources"
+        else:
+            traffic_note = "profiles/w8a16_decode_hbm_traffic_pmc.txt was taken at other kernel sources: not reported"
     except OSError:
         traffic = None
     roofline = {"bound": "hbm", "kernel": "msd_gemm_w8a16 M=%d K=%d N=%d (all launches of one call)" %
@@ -241,6 +325,7 @@ def main():
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                "traffic_source": traffic_note,
                 "algorithmic_bytes": w8_bytes(dom["M"], K, dom["N"]),
                 "measured_stream_read_GBps": round(measured_stream_GBps, 1),
                 "bare_weight_read_us_same_shape": dom["bare_weight_read_us"]}
@@ -253,6 +338,57 @@ def main():
         extras = bench_extras.run(want, msd, synth, time_calls, dev)
     except ImportError:
         extras = {}
+
+    # ---- decomposition kernels alone (a1 / a4): 2*M*K bytes in, 2*M*K + 4*M out (INT8); HBM/L2-bound
+    dec = []
+    for (Md, Kd) in [(128, 4096), (8192, 8192)]:
+        xg = torch.randn((Md, Kd), device=dev).to(torch.bfloat16)
+        q1 = torch.empty((Md, Kd), dtype=torch.int8, device=dev)
+        q2 = torch.empty_like(q1)
+        al = torch.empty((Md,), dtype=torch.float32, device=dev)
+        L_ = msd.lib()
+        import ctypes as C_
+        argsd = (msd.MSD_INT8, C_.c_void_p(xg.data_ptr()), Md, Kd, Kd, C_.c_void_p(q1.data_ptr()), C_.c_void_p(q2.data_ptr()),
+                 C_.c_void_p(al.data_ptr()), C_.c_void_p(side.cuda_stream))
+        us_d = time_calls(lambda i: msd.Prepared(L_.msd_decompose, argsd, (xg, q1, q2, al), "msd_decompose", None), 8)
+        bd = 4 * Md * Kd + 4 * Md
+        dec.append({"M": Md, "K": Kd, "us": round(us_d, 2), "us_min": round(time_calls.last["min"], 2),
+                    "GBps": round(bd / us_d / 1e3, 1), "hbm_frac": round(bd / us_d / 1e3 / HBM_PEAK_GBS, 4)})
+        del xg, q1, q2, al
+    torch.cuda.empty_cache()
+
+    # ---- every configuration in one compact table (kept inside `roofline` so that it travels with the line)
+    def _r(v, n=3):
+        return None if v is None else round(v, n)
+    per_config = {"cfg1_w8a16_decode": [
+        {"M": r["M"], "N": r["N"], "us": r["us_per_call"], "us_min": r["us_per_call_min"], "bound": "hbm",
+         "frac": r["hbm_frac"], "vs_bare_read": r["bare_read_over_call"]} for r in per_shape],
+        "decomposition_alone": dec}
+    ex = extras if isinstance(extras, dict) else {}
+    if isinstance(ex.get("cmp"), list):
+        cm = {(c["M"], c["N"]): c for c in ex["cmp"]}
+        for e_ in per_config["cfg1_w8a16_decode"]:
+            c = cm.get((e_["M"], e_["N"]))
+            if c:
+                e_["vs_dequant"] = c["speedup_vs_dequant"]
+    if isinstance(ex.get("cfg0"), dict) and "msd_us" in ex["cfg0"]:
+        per_config["cfg0_w8a16_16x1024x1024"] = {"us": ex["cfg0"]["msd_us"], "bound": "launch latency",
+                                                 "vs_dequant": _r(ex["cfg0"]["dequant_us"] / ex["cfg0"]["msd_us"])}
+    if isinstance(ex.get("prefill"), list):
+        per_config["cfg2_w8a16_prefill"] = [
+            {"M": r["M"], "N": r["N"], "us": r["us"], "bound": "mfma_int8", "frac": r["int8_mfma_frac"],
+             "exec_TOPS": r["exec_TOPS"], "vs_dequant": r.get("speedup_vs_dequant"),
+             "frac_of_mfma_only_probe": r.get("frac_of_mfma_only")} for r in ex["prefill"]]
+    if isinstance(ex.get("w4"), list):
+        per_config["cfg3_w4a16"] = [
+            {"M": r["M"], "us": r["us"], "bound": "hbm" if r["M"] <= 32 else "mfma_fp4",
+             "frac": r["hbm_frac"] if r["M"] <= 32 else r["fp4_mfma_frac"], "vs_dequant": r.get("speedup_vs_dequant")}
+            for r in ex["w4"]]
+    if isinstance(ex.get("attn"), list):
+        per_config["cfg4_attention"] = [
+            {"L": r["L"], "us": r["us"], "bound": "hbm", "frac": r["hbm_frac"], "vs_dequant": r["speedup_vs_dequant"],
+             "per_channel_us": r["per_channel"]["us"], "lowprec_us": r.get("lowprec_us")} for r in ex["attn"]]
+    roofline["per_config"] = per_config
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -270,13 +406,14 @@ def main():
             for x, W, s, M, N in data:
                 oracle.gemm_w8a16(x, W, s)
             reps += 1
-            if time.perf_counter() - c0 > 10.0 or reps >= 20:
+            if time.perf_counter() - c0 > 6.0 or reps >= 20:
                 break
         c1 = time.perf_counter()
         cpu = {"value": round(reps * step_bytes / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
                "kind": "oracle",
                "sample": "oracle W8A16 MSD GEMM (Alg. 1), full outputs of all 8 decode shapes, %d pass(es), %.1f s"
                          % (reps, c1 - c0)}
+        cpu["per_config"] = cpu_other_configs(oracle, synth, np)
 
     line = {
         "metric": "MSD W8A16 decode GEMM, algorithmic HBM GB/s (decompose + dual INT8 GEMM + epilogue)",
