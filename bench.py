@@ -110,10 +110,16 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
-    ap.add_argument("--counter-probe", default="", choices=["", "w8_prefill", "w4_prefill", "attn", "mla16", "mla128"],
-                    help="for rocprofv3 --pmc runs: three eager calls of one compute-heavy shape (W8A16 "
-                         "2048x8192x8192, W4A16 4096x8192x28672, attention L=32768, latent-cache attention with 16 heads "
-                         "at L=32768 or 128 heads at L=4096), nothing else; no timing")
+    ap.add_argument("--counter-probe", default="",
+                    choices=["", "w8_prefill", "w4_prefill", "attn", "attn4k", "mla16", "mla128", "w4_m1", "w4_m32",
+                             "probe_w8", "probe_w8_const", "probe_w4"],
+                    help="for rocprofv3 --pmc runs: three eager calls of one shape (W8A16 2048x8192x8192, W4A16 "
+                         "4096 / 1 / 32 x 8192 x 28672, attention L=32768 / 4096, latent-cache attention with 16 heads "
+                         "at L=32768 or 128 heads at L=4096, the MFMA-only probes of the two prefill kernels with random "
+                         "or constant operands), nothing else; no timing")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="with --counter-probe: first one 1 GiB device copy, the calibration kernel of the "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -134,18 +140,36 @@ def main():
     if args.counter_probe:
         g = torch.Generator(device=dev)
         g.manual_seed(7)
-        if args.counter_probe == "w8_prefill":
+        if args.with_copy:
+            src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+            dst = torch.empty_like(src)
+            torch.cuda.synchronize()
+            dst.copy_(src)  # calibration: reads 1 GiB, writes 1 GiB
+            torch.cuda.synchronize()
+            del src, dst
+            torch.cuda.empty_cache()
+        if args.counter_probe in ("w8_prefill", "probe_w8", "probe_w8_const"):
             M, K, N = 2048, 8192, 8192
             x = dev_bf16(synth.activations(synth.seed_for(2, 0), M, K, outliers=True))
             W = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev, generator=g)
             sc = torch.rand(N, device=dev) * 0.009 + 0.001
-            call = lambda: msd.msd_gemm_w8a16(x, W, sc)
-        elif args.counter_probe == "w4_prefill":
-            M, K, N = 4096, 8192, 28672
+            if args.counter_probe == "probe_w8_const":   # the same instruction stream on constant operand bits
+                x = torch.ones_like(x)
+                W = torch.ones_like(W)
+            if args.counter_probe == "w8_prefill":
+                call = lambda: msd.msd_gemm_w8a16(x, W, sc)
+            else:
+                call = lambda: msd.msd_probe_mfma_w8a16(x, W, sc)
+        elif args.counter_probe in ("w4_prefill", "w4_m1", "w4_m32", "probe_w4"):
+            M = {"w4_m1": 1, "w4_m32": 32}.get(args.counter_probe, 4096)
+            K, N = 8192, 28672
             x = dev_bf16(synth.activations(synth.seed_for(3, 2), M, K, outliers=True))
             codes = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device=dev, generator=g)
             exps = torch.randint(118, 124, (N, K // 32), dtype=torch.uint8, device=dev, generator=g)
-            call = lambda: msd.msd_gemm_w4a16(x, codes, exps)
+            if args.counter_probe == "probe_w4":
+                call = lambda: msd.msd_probe_mfma_w4a16(x, codes, exps)
+            else:
+                call = lambda: msd.msd_gemm_w4a16(x, codes, exps)
         elif args.counter_probe in ("mla16", "mla128"):
             B, Hq, L = (32, 16, 32768) if args.counter_probe == "mla16" else (32, 128, 4096)
             q = dev_bf16(synth.queries(synth.seed_for(9, Hq), B, Hq, 576))
@@ -153,7 +177,7 @@ def main():
             sl = torch.rand((B, L), device=dev) * 0.02 + 0.02
             call = lambda: msd.msd_mla_decode_int8kv(q, Cl, sl, msd.MSD_PER_TOKEN, 1.0 / 192.0 ** 0.5)
         else:
-            B, Hq, Hkv, d, L = 16, 32, 8, 128, 32768
+            B, Hq, Hkv, d, L = 16, 32, 8, 128, (4096 if args.counter_probe == "attn4k" else 32768)
             q = dev_bf16(synth.queries(synth.seed_for(4, 0), B, Hq, d))
             Kc = torch.randint(-127, 128, (B, Hkv, L, d), dtype=torch.int8, device=dev, generator=g)
             Vc = torch.randint(-127, 128, (B, Hkv, L, d), dtype=torch.int8, device=dev, generator=g)
