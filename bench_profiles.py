@@ -206,7 +206,8 @@ WORKLOADS = ["w8_prefill", "probe_w8", "probe_w8_const", "w4_prefill", "probe_w4
              "mla128"]
 
 
-def do_counters():
+def do_counters(workloads=None):
+    workloads = workloads or WORKLOADS
     out = ["Compute-heavy kernels and the MFMA-only probes: rocprofv3 hardware counters\n",
            "===========================================================================\n",
            "Command (from the repository root, on one MI355X):  python3 bench_profiles.py counters\n",
@@ -226,7 +227,7 @@ def do_counters():
            "cycles); waiting = SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES; L2 hit = TCC_HIT / (TCC_HIT + TCC_MISS); LDS conflict share =\n",
            "SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE; MFMA cycles per instruction = SQ_VALU_MFMA_BUSY_CYCLES / SQ_INSTS_MFMA\n",
            "(per-wave instruction count; what the counter charges one instruction).\n\n"]
-    for w in WORKLOADS:
+    for w in workloads:
         vals = {}
         for i, ctrs in enumerate(PASSES, 1):
             d = run_pass("pmcx_%s_%d" % (w, i), ["--pmc", *ctrs], ["--counter-probe", w])
@@ -265,4 +266,5 @@ if __name__ == "__main__":
     if what in ("traffic", "all"):
         do_traffic()
     if what in ("counters", "all"):
-        do_counters()
+        # an optional comma list restricts the workloads (the summary file then holds only those)
+        do_counters(sys.argv[2].split(",") if len(sys.argv) > 2 else None)

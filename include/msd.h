@@ -126,6 +126,28 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
 size_t msd_gemm_w8a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*
+ * Pre-packed INT8 weights (optional, one time, offline; the weights stay INT8 and keep their size up to
+ * padding).  The paper's kernels read the weights in the matrix unit's native tile format (Sec. 3.9: "resident
+ * weight tile"); on gfx950 that is the lane order of the 16x16x64 integer matrix instruction's operand:
+ *   packed[K/64][ceil(N/16)][1024]:  byte (g*16 + r)*16 + b of the kilobyte (ks, nb) = W[16*nb + r][64*ks + 16*g + b],
+ *   zero for channels past N.
+ * A load of one operand, or one fill instruction of an LDS tile, is then one contiguous kilobyte, which this
+ * GPU serves at about three times the rate of 16 separate 64-byte row pieces.
+ *   msd_packed_weights_w8_bytes(N, K) : size of the packed array (0 for empty shapes).
+ *   msd_pack_weights_w8(W, N, K, packed, stream) : W int8 [N][K] (device) -> packed (device, 16-byte aligned).
+ *       K must be a multiple of 64 (SHAPE error otherwise: such layers use msd_gemm_w8a16).
+ *   msd_gemm_w8a16_packed(...) : msd_gemm_w8a16 with W_packed in place of W; every other argument, the
+ *       workspace size (msd_gemm_w8a16_workspace_bytes), observation points, results (bit-identical integer
+ *       partial products, the same fp32 epilogue) and errors as msd_gemm_w8a16, plus SHAPE for K % 64 != 0.
+ */
+size_t msd_packed_weights_w8_bytes(int64_t N, int64_t K);
+int msd_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, void* packed, void* stream);
+int msd_gemm_w8a16_packed(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const void* W_packed,
+                          const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy,
+                          void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                          void* stream);
+
+/*
  * msd_gemm_w8a16 for callers that cannot allocate device memory or carry a workspace (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, kernels and
  * results as msd_gemm_w8a16 without observation points; the activation codes and row scales live in a

@@ -53,6 +53,12 @@ def lib():
         gemm8 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         gemm4 = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp, sz, vp, vp]
         L.msd_gemm_w8a16.argtypes = gemm8
+        L.msd_gemm_w8a16_packed.argtypes = gemm8
+        L.msd_gemm_w8a16_packed.restype = ci
+        L.msd_packed_weights_w8_bytes.argtypes = [i64, i64]
+        L.msd_packed_weights_w8_bytes.restype = sz
+        L.msd_pack_weights_w8.argtypes = [vp, i64, i64, vp, vp]
+        L.msd_pack_weights_w8.restype = ci
         L.msd_gemm_w8a16_static.argtypes = [vp, i64, i64, i64, vp, vp, i64, vp, ci, i64, vp]
         L.msd_gemm_w8a16_static.restype = ci
         L.msd_gemm_w8a16_static_scratch_bytes.argtypes = []
@@ -214,6 +220,25 @@ def msd_gemm_w8a16(x, W, w_scale, out_dtype=torch.float32, taps=False, y=None, w
     assert W.is_contiguous() and W.shape[1] == x.shape[1] and w_scale.shape[0] == W.shape[0]
     return _gemm_common("msd_gemm_w8a16", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W), _ptr(w_scale)),
                         W.shape[0], out_dtype, taps, y, ws, prepare)
+
+
+def msd_pack_weights_w8(W):
+    """W int8 [N][K] (K % 64 == 0) -> the packed array msd_gemm_w8a16_packed reads (one-time, offline)."""
+    _dev(W, torch.int8, "W")
+    assert W.is_contiguous()
+    N, K = W.shape
+    packed = torch.empty(lib().msd_packed_weights_w8_bytes(N, K), dtype=torch.int8, device=W.device)
+    _check(lib().msd_pack_weights_w8(_ptr(W), N, K, _ptr(packed), _stream()), "msd_pack_weights_w8")
+    return packed
+
+
+def msd_gemm_w8a16_packed(x, W_packed, w_scale, out_dtype=torch.float32, taps=False, y=None, ws=None, prepare=False):
+    """msd_gemm_w8a16 on weights packed by msd_pack_weights_w8; N is taken from w_scale."""
+    _dev(x, torch.bfloat16, "x"); _dev(W_packed, torch.int8, "W_packed"); _dev(w_scale, torch.float32, "w_scale")
+    N, K = w_scale.shape[0], x.shape[1]
+    assert W_packed.numel() == lib().msd_packed_weights_w8_bytes(N, K)
+    return _gemm_common("msd_gemm_w8a16_packed", "msd_gemm_w8a16_workspace_bytes", x, (_ptr(W_packed), _ptr(w_scale)),
+                        N, out_dtype, taps, y, ws, prepare)
 
 
 def msd_gemm_w8a16_static(x, W, w_scale, y, prepare=False):

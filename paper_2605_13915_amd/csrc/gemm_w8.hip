@@ -103,8 +103,13 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
   const int ks1 = min(ksteps, ks0 + per);
   const int kw = per * 64;  // K range a wave can own (its LDS stride)
   const int8_t* wp[NT];
+  // packed weights: channel tile nb, K step ks at ((ks * tiles) + nb) kilobytes, the lane's 16 bytes at lane*16
+  const int64_t wtiles = (N + 15) / 16;
+  const int64_t wstep = a.w_packed ? wtiles * 1024 : 64;  // bytes between K steps of this lane's weight stream
 #pragma unroll
-  for (int t = 0; t < NT; ++t) wp[t] = a.W + min(n0 + 16 * t + row, N - 1) * K + 16 * g;
+  for (int t = 0; t < NT; ++t)
+    wp[t] = a.w_packed ? a.W + min(n0 / 16 + t, wtiles - 1) * 1024 + lane * 16
+                       : a.W + min(n0 + 16 * t + row, N - 1) * K + 16 * g;
   // A-fragment source of this lane: stacked row i = f*16 + row; [0,M) -> x1, [M,2M) -> x2
   int8_t* my_codes = s_codes + (int64_t)wave * 2 * M * kw;
   const int8_t* ap[RT];
@@ -142,7 +147,7 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         wv[t][u] = zero;
-        if (ok[u]) wv[t][u] = ldg16_stream(wp[t] + k);
+        if (ok[u]) wv[t][u] = ldg16_stream(wp[t] + (ks + u) * wstep);
       }
     }
     if (SELF && !ready) {
@@ -342,9 +347,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a)
   v4i wv[NT][STEPS];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    const int8_t* wp = a.W + min(n0 + 16 * t + row, N - 1) * K + k_lo + 16 * g;
+    const int64_t wtiles = (N + 15) / 16;
+    const int8_t* wp = a.w_packed ? a.W + ((int64_t)wave * STEPS * wtiles + min(n0 / 16 + t, wtiles - 1)) * 1024 + lane * 16
+                                  : a.W + min(n0 + 16 * t + row, N - 1) * K + k_lo + 16 * g;
+    const int64_t wstep = a.w_packed ? wtiles * 1024 : 64;
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) wv[t][s] = ldg16_stream(wp + s * 64);
+    for (int s = 0; s < STEPS; ++s) wv[t][s] = ldg16_stream(wp + s * wstep);
   }
   for (int i = threadIdx.x; i < RT * NT * 256; i += THREADS) (&s_acc[0][0][0][0])[i] = 0;
   // ---- row maxima: over the chunks of a lane, the lanes of a wave, the waves
@@ -718,6 +726,14 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
         voff[q] = (uint32_t)((mrow - m0) * a.ldq + lc * 16);
         gbase[q] = ((comp && !BF16) ? a.q2 : a.q1) + m0 * a.ldq;
       }
+    } else if (!BF16 && a.w_packed) {
+      // packed weights: the stage's weight region is (BK/64) K steps x (BN/16) channel tiles of one kilobyte,
+      // each copied verbatim (lane order); block wb = kk * (BN/16) + nb
+      const int wb = blk - ROWS_A / RPI, kk = wb / (BN / 16), nb = wb % (BN / 16);
+      const int64_t wtiles = (N + 15) / 16;
+      voff[q] = (uint32_t)(lane * 16);
+      gbase[q] = a.W + ((int64_t)kk * wtiles + min(n0 / 16 + nb, wtiles - 1)) * 1024;
+      kadv[q] = (int64_t)(BK / 64) * wtiles * 1024;
     } else {
       const int64_t nrow = min(n0 + (blk - ROWS_A / RPI) * RPI + rr, N - 1);
       voff[q] = (uint32_t)((nrow - n0) * K + lc * 16);
@@ -758,7 +774,10 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
       const int row = wn * TN + 32 * j + l32;
-      fb_off[j][h] = ROWS_A * BK + row * BK + (((2 * h + kg) ^ swz(row)) << 4);
+      if (!BF16 && a.w_packed)  // kilobyte (K step h/2, tile row/16), inside it byte group 2*(h%2)+kg, channel row%16
+        fb_off[j][h] = ROWS_A * BK + (((h >> 1) * (BN / 16) + (row >> 4)) << 10) + (((2 * (h & 1) + kg) * 16 + (row & 15)) << 4);
+      else
+        fb_off[j][h] = ROWS_A * BK + row * BK + (((2 * h + kg) ^ swz(row)) << 4);
     }
   }
 
@@ -989,6 +1008,29 @@ int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx,
   a.N = N;
   const int rc = launch_dma<128, 256, 2, 2, 4, true>(a, stream);
   if (rc) return rc;
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+// ------------------------------------------------------------------ one-time weight packing
+// W [N][K] (K % 64 == 0) -> Wp[K/64][ceil(N/16)][1 KB] (GemmW8Args::w_packed).  One thread per 16 bytes.
+__global__ __launch_bounds__(256) void pack_weights_w8_kernel(const int8_t* __restrict__ W, int64_t N, int64_t K,
+                                                              int8_t* __restrict__ P) {
+  const int64_t tiles = (N + 15) / 16;
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;  // 16-byte piece of the packed array
+  if (id >= (K / 64) * tiles * 64) return;
+  const int l = (int)(id & 63);
+  const int64_t blk = id >> 6, ks = blk / tiles, nb = blk % tiles;
+  const int64_t n = nb * 16 + (l & 15);
+  v4i v = {0, 0, 0, 0};
+  if (n < N) v = ldg16(W + n * K + ks * 64 + 16 * (l >> 4));
+  *reinterpret_cast<v4i*>(P + id * 16) = v;
+}
+
+int launch_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, int8_t* packed, hipStream_t stream) {
+  const int64_t pieces = (K / 64) * ((N + 15) / 16) * 64;
+  if (pieces == 0) return MSD_OK;
+  hipLaunchKernelGGL(pack_weights_w8_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, stream, W, N, K, packed);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

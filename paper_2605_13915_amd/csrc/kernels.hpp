@@ -53,6 +53,11 @@ struct GemmW8Args {
   // i sit at ((s * RT + i/16) * 64 + g * 16 + i%16) * 16, so that a wave's operand load is one contiguous
   // kilobyte (a load whose 64 lanes touch 16 different rows runs at a third of that rate)
   int a_frag;
+  // packed weights (msd_pack_weights_w8): W points at Wp[K/64][Npad/16][1 KB], Npad = N rounded up to 16; the
+  // kilobyte of K step ks and channel tile nb holds, at (g*16 + r)*16 + b, byte 64*ks + 16*g + b of channel
+  // 16*nb + r (channels past N are zero) -- the lane order of the 16x16x64 matrix instruction's operand, so
+  // a register-operand load and an LDS fill are one contiguous kilobyte each.  Requires K % 64 == 0.
+  int w_packed;
   Int8Range rg;  // range constants of the decomposition and of beta in the epilogue
 };
 // stage depth of the blocked layout launch_gemm_w8 wants for this shape (0: row-major)
@@ -194,6 +199,9 @@ size_t dequant_workspace_bytes(int64_t M, int64_t K, int64_t N);
 // plain BF16 GEMM on the asynchronous-fill pipeline (gemm_w8.hip), used by the comparison path
 int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx, const uint16_t* Wb, int64_t N,
                            void* y, int out_bf16, int64_t ldy, hipStream_t stream);
+
+// ---- one-time weight packing (gemm_w8.hip): W [N][K] -> the packed layout of GemmW8Args::w_packed
+int launch_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, int8_t* packed, hipStream_t stream);
 
 // ---- measurement aid (stream_probe.hip)
 int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream);

@@ -150,7 +150,10 @@ int msd_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
                                 workspace_bytes, taps, stream);
 }
 
-int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+}  // extern "C"
+
+// the W8A16 entry points: canonical [N][K] weights, or the packed layout of msd_pack_weights_w8
+static int gemm_w8a16_impl(int variant, bool packed, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
                            const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
                            size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
   Int8Range rg;
@@ -158,6 +161,7 @@ int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (M < 0 || K < 0 || N < 0 || ldx < K || ldy < N) return MSD_ERR_SHAPE;
   if (K % 16 != 0 || K > 131072) return MSD_ERR_SHAPE;
+  if (packed && (K % 64 != 0 || K < 64)) return MSD_ERR_SHAPE;
   if (M == 0 || N == 0) return MSD_OK;
   if (!y || !w_scale || (K > 0 && (!x_bf16 || !W))) return MSD_ERR_INVALID_ARG;
   if (!aligned_to(W, 16) || !aligned_to(x_bf16, 2) || !aligned_to(w_scale, 4) ||
@@ -168,6 +172,7 @@ int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
   GemmW8Args a{};
+  a.w_packed = packed ? 1 : 0;
   a.q1 = (int8_t*)(ws + l.q1);
   a.q2 = (int8_t*)(ws + l.q2);
   a.ldq = K;
@@ -225,6 +230,34 @@ int msd_gemm_w8a16_static(const void* x_bf16, int64_t M, int64_t K, int64_t ldx,
   // of a padded tile that it does not write only feed products that are never stored).
   return msd_gemm_w8a16_variant(MSD_VARIANT_MAIN, x_bf16, M, K, ldx, W, w_scale, N, y, out_dtype, ldy, ptr,
                                 kStaticScratchBytes, nullptr, stream);
+}
+
+extern "C" {
+
+int msd_gemm_w8a16_variant(int variant, const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,
+                           const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                           size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  return gemm_w8a16_impl(variant, false, x_bf16, M, K, ldx, W, w_scale, N, y, out_dtype, ldy, workspace, workspace_bytes,
+                         taps, stream);
+}
+
+size_t msd_packed_weights_w8_bytes(int64_t N, int64_t K) {
+  if (N <= 0 || K <= 0) return 0;
+  return (size_t)((K + 63) / 64) * (size_t)((N + 15) / 16) * 1024;
+}
+
+int msd_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, void* packed, void* stream) {
+  if (N < 0 || K < 0 || K % 64 != 0 || K > 131072) return MSD_ERR_SHAPE;
+  if (N == 0 || K == 0) return MSD_OK;
+  if (!W || !packed || !aligned_to(W, 16) || !aligned_to(packed, 16)) return MSD_ERR_INVALID_ARG;
+  return launch_pack_weights_w8(W, N, K, (int8_t*)packed, (hipStream_t)stream);
+}
+
+int msd_gemm_w8a16_packed(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const void* W_packed,
+                          const float* w_scale, int64_t N, void* y, int out_dtype, int64_t ldy, void* workspace,
+                          size_t workspace_bytes, const msd_debug_taps* taps, void* stream) {
+  return gemm_w8a16_impl(MSD_VARIANT_MAIN, true, x_bf16, M, K, ldx, (const int8_t*)W_packed, w_scale, N, y, out_dtype,
+                         ldy, workspace, workspace_bytes, taps, stream);
 }
 
 int msd_moe_gemm_w8a16(const void* x_bf16, int64_t T, int64_t K, int64_t ldx, const int32_t* expert_offsets, int E,

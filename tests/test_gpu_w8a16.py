@@ -294,3 +294,57 @@ def test_extreme_magnitudes_stay_bit_exact(msd, ex):
     torch.cuda.synchronize()
     assert np.array_equal(g1.cpu().numpy(), m1) and np.array_equal(g2.cpu().numpy(), m2)
     assert np.array_equal(ge.cpu().numpy(), me)
+
+
+# ---------------------------------------------------------------- packed weights (msd_pack_weights_w8)
+PACKED_SHAPES = [
+    (1, 4096, 4096), (2, 4096, 8300), (4, 2048, 530), (8, 1024, 90), (3, 8192, 300),        # single-launch kernel
+    (8, 4096, 4096), (5, 4096, 8300), (16, 4096, 4100), (12, 2112, 700), (32, 4096, 1000),  # register-operand kernels
+    (15, 8192, 8300), (9, 64, 20),
+    (30, 512, 8300), (70, 320, 6500), (128, 256, 12800), (128, 4096, 1024), (100, 1024, 700),   # small LDS tiles
+    (65, 192, 300), (96, 2112, 520),
+    (1100, 512, 4200), (300, 1088, 520), (257, 256, 777),                                    # large LDS tiles
+]
+
+
+@pytest.mark.parametrize("M,K,N", PACKED_SHAPES)
+def test_gemm_w8a16_packed_weights(msd, M, K, N):
+    """msd_gemm_w8a16_packed against the oracle (which reads the canonical layout), with and without
+    observation points: integer partial products bit-exact, outputs within 1e-6, and bit-identical to
+    msd_gemm_w8a16 on the canonical weights (same kernels, same arithmetic, another address map)."""
+    seed = synth.seed_for(1, M * 13 + N)
+    x = synth.activations(seed, M, K, outliers=True)
+    if M >= 3:
+        x[1, :] = 0
+    W, s = synth.int8_weights(seed, N, K)
+    y_ref, t = oracle.gemm_w8a16(x, W, s, taps=True)
+    xd, Wd, sd = bf16_to_dev(x), to_dev(W), to_dev(s)
+    Wp = msd.msd_pack_weights_w8(Wd)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w8a16_packed(xd, Wp, sd, y=y)
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    assert np.all(np.isfinite(yh))
+    assert rel_l2(yh, y_ref) <= 1e-6
+    for m in range(M):
+        assert rel_l2(yh[m], y_ref[m]) <= 1e-6 or not np.any(y_ref[m]), m
+    assert torch.equal(y, msd.msd_gemm_w8a16(xd, Wd, sd))
+    y2, g = msd.msd_gemm_w8a16_packed(xd, Wp, sd, taps=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(g["q1"].cpu().numpy(), t["q1"]) and np.array_equal(g["q2"].cpu().numpy(), t["q2"])
+    assert np.array_equal(g["acc1"].cpu().numpy(), t["acc1"]) and np.array_equal(g["acc2"].cpu().numpy(), t["acc2"])
+    assert rel_l2(y2.cpu().numpy(), y_ref) <= 1e-6
+
+
+def test_pack_weights_layout_and_errors(msd):
+    """The packed array is exactly the documented permutation of W (zero padding past N); K % 64 != 0 is refused."""
+    N, K = 37, 192
+    W = torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda")
+    P = msd.msd_pack_weights_w8(W).cpu().numpy().reshape(K // 64, (N + 15) // 16, 4, 16, 16)
+    Wn = np.zeros(((N + 15) // 16 * 16, K), np.int8)
+    Wn[:N] = W.cpu().numpy()
+    ref = Wn.reshape((N + 15) // 16, 16, K // 64, 4, 16).transpose(2, 0, 3, 1, 4)   # [ks][nb][g][r][b]
+    assert np.array_equal(P, ref)
+    with pytest.raises(msd.MsdError) as e:
+        msd.msd_pack_weights_w8(torch.zeros((16, 48), dtype=torch.int8, device="cuda"))
+    assert e.value.code == -2
