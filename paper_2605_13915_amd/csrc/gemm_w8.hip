@@ -626,8 +626,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_mfma32_kernel(GemmW8Args
 // lane order, so a lane fetches the global chunk whose swizzled position it owns.  Rows past M / N
 // are clamped to the last valid row (their results are never stored).  Requires K % 64 == 0.
 //
-// Two uses.  <128,256,2,2,4>: prefill, 256x256 output tile (128 activation rows x 2 components),
-// MFMA-bound.  Small tiles with many stages: batched decode (32 < M <= 128, few output tiles),
+// Two uses.  <128,256,2,4,4>: prefill, 256x256 output tile (128 activation rows x 2 components)
+// on eight waves.  Small tiles with many stages: batched decode (32 < M <= 128, few output tiles),
 // where the weight stream is cold and the bytes in flight per CU, i.e. the stage count, set the
 // HBM rate (Little's law), not the MFMA.
 __device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, uint32_t lds_addr) {
@@ -640,6 +640,20 @@ __device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, ui
                :
                : "v"(voff), "s"(gbase), "s"(lds_addr)
                : "memory", "m0");
+}
+
+// Moves one accumulator register to a vector register at this point of the program.  Left to the
+// register allocator, an epilogue over 256 accumulators copies all of them out up front, spills, and
+// every reload of a spilled value then waits for the stores issued before it.
+__device__ __forceinline__ int acc_read(int v) {
+  int r;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+  return r;
+}
+__device__ __forceinline__ float acc_read(float v) {
+  float r;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+  return r;
 }
 
 template <int N>
@@ -906,7 +920,7 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
               const int64_t n = n0 + wn * TN + 32 * j + l32;
-              if (n < N) store_out_stream(a.y, a.out_bf16, m * a.ldy + n, acc[c][i][j][r]);
+              if (n < N) store_out_stream(a.y, a.out_bf16, m * a.ldy + n, acc_read(acc[c][i][j][r]));
             }
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -925,32 +939,51 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
     s_ab[BMH + i] = __fdiv_rn(al, a.rg.num2);
   }
   __syncthreads();
+  // The weight scales are fetched unconditionally (clamped column) and pinned in registers before the
+  // store loops: a load still pending inside the conditional store code makes the compiler wait for
+  // ALL vector-memory operations before each use, i.e. for the previous store's completion, and the
+  // epilogue then runs at one store round trip per row.
   float sw[FN];
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int64_t n = n0 + wn * TN + 32 * j + l32;
-    sw[j] = n < N ? a.w_scale[n] : 0.f;
-  }
+  for (int j = 0; j < FN; ++j) sw[j] = a.w_scale[min(n0 + wn * TN + 32 * j + l32, N - 1)];
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+  for (int j = 0; j < FN; ++j) asm volatile("" : "+v"(sw[j]));
+  // one pass per kind of output, each under a single uniform branch
+  auto for_rows = [&](auto&& emit) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int lr = wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
-      const int64_t m = m0 + lr;
-      const float alpha = s_ab[lr], beta = s_ab[BMH + lr];
-      if (m < M) {
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          const int64_t n = n0 + wn * TN + 32 * j + l32;
-          if (n >= N) continue;
-          const int a1 = acc[0][i][j][r], a2 = acc[1][i][j][r];
-          store_out_stream(a.y, a.out_bf16, m * a.ldy + n, merge_scales(sw[j], alpha, beta, a1, a2));
-          if (a.acc1) a.acc1[m * N + n] = a1;
-          if (a.acc2) a.acc2[m * N + n] = a2;
+      for (int r = 0; r < 16; ++r) {
+        const int lr = wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
+        const int64_t m = m0 + lr;
+        const float alpha = s_ab[lr], beta = s_ab[BMH + lr];
+        if (m < M) {
+#pragma unroll
+          for (int j = 0; j < FN; ++j) {
+            const int64_t n = n0 + wn * TN + 32 * j + l32;
+            if (n < N) emit(m, n, sw[j], alpha, beta, acc_read(acc[0][i][j][r]), acc_read(acc[1][i][j][r]));
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
+  };
+  if (a.out_bf16) {
+    uint16_t* y = reinterpret_cast<uint16_t*>(a.y);
+    for_rows([&](int64_t m, int64_t n, float s, float alpha, float beta, int a1, int a2) {
+      __builtin_nontemporal_store(f32_to_bf16_bits(merge_scales(s, alpha, beta, a1, a2)), y + m * a.ldy + n);
+    });
+  } else {
+    float* y = reinterpret_cast<float*>(a.y);
+    for_rows([&](int64_t m, int64_t n, float s, float alpha, float beta, int a1, int a2) {
+      __builtin_nontemporal_store(merge_scales(s, alpha, beta, a1, a2), y + m * a.ldy + n);
+    });
+  }
+  if (a.acc1 || a.acc2) {  // observation points for the parity tests
+    for_rows([&](int64_t m, int64_t n, float, float, float, int a1, int a2) {
+      if (a.acc1) a.acc1[m * N + n] = a1;
+      if (a.acc2) a.acc2[m * N + n] = a2;
+    });
+  }
   }
 }
 
@@ -1006,7 +1039,7 @@ int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx,
   a.M = M;
   a.K = 2 * K;
   a.N = N;
-  const int rc = launch_dma<128, 256, 2, 2, 4, true>(a, stream);
+  const int rc = launch_dma<128, 256, 2, 4, 4, true>(a, stream);
   if (rc) return rc;
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -1225,8 +1258,10 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     else  // at most 64 KB of LDS: two workgroups per CU
       rc = deep ? launch_dma<32, 64, 1, 2, 4, false, false, 128>(a, stream) : launch_dma<32, 64, 1, 2, 8>(a, stream);
   } else if (path == W8Path::kFillLarge) {
-    // three or five stages, and half-size tiles with two workgroups per CU, all measured the same
-    rc = launch_dma<128, 256, 2, 2, 4>(a, stream);
+    // Eight waves (two per SIMD, 128x64 wave tiles): measured 6-10% faster than four waves with 128x128 wave
+    // tiles -- twice as many waves issue fill instructions and a SIMD always has a second wave to issue from
+    // while one waits.  Three or five stages and half-size tiles (two workgroups per CU) measured no better.
+    rc = launch_dma<128, 256, 2, 4, 4>(a, stream);
   } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
     rc = launch_mfma32<64, 64, 2, 2>(a, stream);
   } else {
