@@ -674,16 +674,22 @@ __device__ __forceinline__ void wait_vm_barrier() {
 // fetching and keeps multiplying the fragments of that step, i.e. the same MFMA sequence, tile
 // schedule and epilogue with real operand bits but no fill, no barrier and no LDS traffic.  Its
 // time is what the matrix pipe alone allows for this shape and data on the chip at hand.
-template <int BMH, int BN, int WM, int WN, int NS, bool BF16, bool PROBE = false, int BK = 64>
-__global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN == 4) ? 2 : 1) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
+//
+// KS > 1 (batched decode, where the fill rate of a CU grows with the number of waves that issue loads and the
+// tiles are too small to employ many waves): KS groups of WM x WN waves share the tile; every wave takes part
+// in the fill, group g multiplies the K extents h = g (mod KS) of every stage, and the groups' integer
+// partial sums meet in LDS before the epilogue, whose rows are dealt out over the groups.
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16, bool PROBE = false, int BK = 64, int KS = 1>
+__global__ __launch_bounds__(WM * WN * KS * 64, (2 * BMH * BN <= 128 * 256 && WM * WN * KS == 4) ? 2 : 1) void gemm_w8_dma_kernel(GemmW8Args a, int tiles_m, int tiles_n) {
   // BK = bytes of K per row and stage.  64: LDS rows of 64 B, chunk swizzle (row>>2)&3, a fill
   // instruction covers 16 rows.  128 (small batched-decode tiles, K % 128 == 0): rows of 128 B =
   // whole cache lines, swizzle (row>>1)&7, 8 rows per fill instruction, four MFMA K extents per
   // stage -- half as many barrier rounds for the same K, which is what bounds those tiles.
   using AccT = std::conditional_t<BF16, v16f, v16i>;
-  constexpr int NW = WM * WN, ROWS_A = 2 * BMH, R = ROWS_A + BN;
+  constexpr int NWT = WM * WN;      // waves that tile the output
+  constexpr int NW = NWT * KS, ROWS_A = 2 * BMH, R = ROWS_A + BN;
   constexpr int TMH = BMH / WM, TN = BN / WN, FM = TMH / 32, FN = TN / 32;
-  constexpr int HS = BK / 32;       // MFMA K extents (32 bytes) per stage
+  constexpr int HS = BK / 32 / KS;  // MFMA K extents (32 bytes) per stage and wave
   constexpr int CPR = BK / 16;      // 16-byte chunks per row
   constexpr int RPI = 1024 / BK;    // rows per fill instruction
   constexpr int L = R / (RPI * NW);  // fill instructions per wave and stage
@@ -691,10 +697,12 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
   static_assert(BK == 64 || BK == 128, "stage depth");
   static_assert(R % (RPI * NW) == 0 && TMH % 32 == 0 && TN % 32 == 0 && BMH % RPI == 0, "tile shape");
   static_assert(NS >= 3 && (NS - 2) * L < 64, "stage count");
+  static_assert((BK / 32) % KS == 0 && (KS == 1 || (!BF16 && !PROBE && 16 % KS == 0)), "K groups");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WN, wn = wave % WN;
+  const int kgrp = wave / NWT, wsub = wave % NWT;
+  const int wm = wsub / WN, wn = wsub % WN;
   const int l32 = lane & 31, kg = lane >> 5;
   const int64_t M = a.M, K = a.K, N = a.N;
   const int total = tiles_m * tiles_n;
@@ -775,23 +783,24 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][i][j][r] = 0;
 
-  int fa_off[2][FM][HS], fb_off[FN][HS];  // byte offset inside a stage for K extent h
+  int fa_off[2][FM][HS], fb_off[FN][HS];  // byte offset inside a stage for this wave's K extent number hh
 #pragma unroll
-  for (int h = 0; h < HS; ++h) {
+  for (int hh = 0; hh < HS; ++hh) {
+    const int h = hh * KS + kgrp;  // extent of the stage
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int i = 0; i < FM; ++i) {
         const int row = c * BMH + wm * TMH + 32 * i + l32;
-        fa_off[c][i][h] = row * BK + (((2 * h + kg) ^ swz(row)) << 4);
+        fa_off[c][i][hh] = row * BK + (((2 * h + kg) ^ swz(row)) << 4);
       }
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
       const int row = wn * TN + 32 * j + l32;
       if (!BF16 && a.w_packed)  // kilobyte (K step h/2, tile row/16), inside it byte group 2*(h%2)+kg, channel row%16
-        fb_off[j][h] = ROWS_A * BK + (((h >> 1) * (BN / 16) + (row >> 4)) << 10) + (((2 * (h & 1) + kg) * 16 + (row & 15)) << 4);
+        fb_off[j][hh] = ROWS_A * BK + (((h >> 1) * (BN / 16) + (row >> 4)) << 10) + (((2 * (h & 1) + kg) * 16 + (row & 15)) << 4);
       else
-        fb_off[j][h] = ROWS_A * BK + row * BK + (((2 * h + kg) ^ swz(row)) << 4);
+        fb_off[j][hh] = ROWS_A * BK + row * BK + (((2 * h + kg) ^ swz(row)) << 4);
     }
   }
 
@@ -870,6 +879,20 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
   for (int t = 0; t < NS - 1; ++t)
     if (t < KT) issue(t);
   v4i fa0[2 * FM], fb0[FN], fa1[2 * FM], fb1[FN];
+  if constexpr (KS > 1) {
+    // K groups: few MFMAs per wave and stage and two waves per SIMD, so no fragment pipeline -- wait for the
+    // tile, refill the stage every wave has left (all of them passed this barrier after their reads of it),
+    // multiply this group's extents.
+    for (int kt = 0; kt < KT; ++kt) {
+      wait_tile(kt, min(KT - 1, kt + NS - 2));
+      if (kt + NS - 1 < KT) issue(kt + NS - 1);
+#pragma unroll
+      for (int hh = 0; hh < HS; ++hh) {
+        load_frags(stage_ptr(kt), hh, fa0, fb0);
+        mfma_block(fa0, fb0);
+      }
+    }
+  } else {
   if (KT > 0) {
     wait_tile(0, min(KT - 1, NS - 2));
     load_frags(stage_ptr(0), 0, fa0, fb0);
@@ -906,6 +929,7 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  }
 
   if constexpr (BF16) {
     // ---- plain epilogue of the comparison GEMM
@@ -931,7 +955,21 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
   // output is produced one (fragment, register) row at a time so that the compiler does not pull
   // all accumulators into VGPRs at once.
   __syncthreads();
-  float* s_ab = reinterpret_cast<float*>(smem);  // [0..BMH-1] alpha, [BMH..2BMH-1] beta
+  constexpr int NACC = 2 * FM * FN * 16;                  // accumulator registers per lane
+  constexpr int RED_BYTES = KS > 1 ? NW * NACC * 256 : 0;  // K groups: every wave's partial sums, [wave][register][lane]
+  int* red = reinterpret_cast<int*>(smem);
+  if constexpr (KS > 1) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            red[(wave * NACC + ((c * FM + i) * FN + j) * 16 + r) * 64 + lane] = acc[c][i][j][r];
+  }
+  float* s_ab = reinterpret_cast<float*>(smem + RED_BYTES);  // [0..BMH-1] alpha, [BMH..2BMH-1] beta
   for (int i = tid; i < BMH; i += NW * 64) {
     const int64_t m = m0 + i;
     const float al = m < M ? a.alpha[m] : 0.f;
@@ -954,6 +992,7 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
     for (int i = 0; i < FM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
+        if (KS > 1 && r % KS != kgrp) continue;  // this row belongs to another K group (wave-uniform)
         const int lr = wm * TMH + 32 * i + (r >> 2) * 8 + kg * 4 + (r & 3);
         const int64_t m = m0 + lr;
         const float alpha = s_ab[lr], beta = s_ab[BMH + lr];
@@ -961,7 +1000,19 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
 #pragma unroll
           for (int j = 0; j < FN; ++j) {
             const int64_t n = n0 + wn * TN + 32 * j + l32;
-            if (n < N) emit(m, n, sw[j], alpha, beta, acc_read(acc[0][i][j][r]), acc_read(acc[1][i][j][r]));
+            if (n >= N) continue;
+            if constexpr (KS > 1) {
+              int a1 = 0, a2 = 0;
+#pragma unroll
+              for (int g = 0; g < KS; ++g) {
+                const int* rw = red + (((g * NWT + wsub) * NACC + (i * FN + j) * 16 + r) * 64 + lane);
+                a1 += rw[0];
+                a2 += rw[FM * FN * 16 * 64];
+              }
+              emit(m, n, sw[j], alpha, beta, a1, a2);
+            } else {
+              emit(m, n, sw[j], alpha, beta, acc_read(acc[0][i][j][r]), acc_read(acc[1][i][j][r]));
+            }
           }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -987,22 +1038,25 @@ __global__ __launch_bounds__(WM * WN * 64, (2 * BMH * BN <= 128 * 256 && WM * WN
   }
 }
 
-template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false, bool PROBE = false, int BK = 64>
+template <int BMH, int BN, int WM, int WN, int NS, bool BF16 = false, bool PROBE = false, int BK = 64, int KS = 1>
 static int launch_dma(const GemmW8Args& a, hipStream_t stream) {
   if (a.K % BK != 0 || (a.a_step != 0 && a.a_bk != BK)) return MSD_ERR_INVALID_ARG;
   const int tiles_m = (int)cdiv(a.M, BF16 ? 2 * BMH : BMH), tiles_n = (int)cdiv(a.N, BN);
   const int total = tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  const size_t lds = (size_t)NS * (2 * BMH + BN) * BK;
-  static_assert((size_t)NS * (2 * BMH + BN) * BK <= 160 * 1024, "LDS budget");
+  // the stages; with K groups the partial sums of all waves (256 B per accumulator register) plus the row scales
+  constexpr size_t kStages = (size_t)NS * (2 * BMH + BN) * BK;
+  constexpr size_t kReduce = KS > 1 ? (size_t)WM * WN * KS * (2 * (BMH / WM / 32) * (BN / WN / 32) * 16) * 256 + 2 * BMH * 4 : 0;
+  constexpr size_t lds = kStages > kReduce ? kStages : kReduce;
+  static_assert(lds <= 160 * 1024, "LDS budget");
   static bool attr_set = false;
   if (!attr_set) {
     MSD_HIP_CHECK(hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE, BK>),
+        reinterpret_cast<const void*>(&gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE, BK, KS>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE, BK>), dim3(grid), dim3(WM * WN * 64),
+  hipLaunchKernelGGL((gemm_w8_dma_kernel<BMH, BN, WM, WN, NS, BF16, PROBE, BK, KS>), dim3(grid), dim3(WM * WN * KS * 64),
                      lds, stream, a, tiles_m, tiles_n);
   return MSD_OK;
 }
@@ -1173,7 +1227,7 @@ int launch_gemm_w8_grouped(const GemmW8Args& a, const int32_t* offs, int E, hipS
 int launch_gemm_w8_mfma_probe(const GemmW8Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
   if (a.K % 64 != 0 || a.K < 64 || a.x != nullptr) return MSD_ERR_SHAPE;
-  const int rc = launch_dma<128, 256, 2, 2, 4, false, true>(a, stream);
+  const int rc = launch_dma<128, 256, 2, 4, 4, false, true>(a, stream);
   if (rc) return rc;
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -1251,8 +1305,13 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     // These tiles do few MFMAs per barrier round, so with K % 128 == 0 a stage holds 128 bytes of K.
     const auto wgs = [&](int bmh, int bn) { return cdiv(M, bmh) * cdiv(N, bn); };
     const bool deep = a.K % 128 == 0 && (a.a_step == 0 || a.a_bk == 128);
-    if (2 * M > 64 && wgs(64, 128) >= 200)
-      rc = deep ? launch_dma<64, 128, 2, 2, 4, false, false, 128>(a, stream) : launch_dma<64, 128, 2, 2, 8>(a, stream);
+    // Up to one workgroup per CU of the smallest tile: eight waves as four K groups (measured 16.5 vs 20.5 us at
+    // 128 x 4096 x 4096, 19 vs 22 us at 32 x 4096 x 14336; with more tiles than CUs the larger tiles win again).
+    if (deep && wgs(32, 64) <= 256)
+      rc = launch_dma<32, 64, 1, 2, 4, false, false, 128, 4>(a, stream);
+    else
+    if (2 * M > 64 && wgs(64, 128) >= 200)  // eight waves measured 30 vs 31.6 us at 128 x 4096 x 14336
+      rc = deep ? launch_dma<64, 128, 2, 4, 4, false, false, 128>(a, stream) : launch_dma<64, 128, 2, 2, 8>(a, stream);
     else if (2 * M > 64 && wgs(64, 64) >= 200)
       rc = deep ? launch_dma<64, 64, 2, 2, 4, false, false, 128>(a, stream) : launch_dma<64, 64, 2, 2, 6>(a, stream);
     else  // at most 64 KB of LDS: two workgroups per CU

@@ -94,6 +94,9 @@ SHAPES = [
     (70, 320, 6500, 1),        # batched decode, 64x64 tiles, ragged M and N
     (30, 512, 8300, 1),        # 16 < M <= 32 with many columns: 32x64 tiles of the asynchronous-fill kernel
     (32, 528, 8300, 0),        # same M and N, K not a multiple of 64: register-operand kernel, wide variant
+    # 32x64 tiles on eight waves in four K groups (at most 256 tiles, K % 128 == 0): ragged M and N, fewer K
+    # stages than the pipeline is deep, one stage more than that
+    (64, 1024, 4100, 1), (100, 256, 1000, 1), (33, 640, 2000, 0),
     # the single-launch kernel with every load in flight at once (M*K <= 16384), one case per instance
     (4, 4096, 4096, 1), (3, 4096, 1000, 1),   # 4 waves x 16 K steps
     (2, 4096, 8300, 1),        # many column tiles, two per workgroup
@@ -302,7 +305,7 @@ PACKED_SHAPES = [
     (8, 4096, 4096), (5, 4096, 8300), (16, 4096, 4100), (12, 2112, 700), (32, 4096, 1000),  # register-operand kernels
     (15, 8192, 8300), (9, 64, 20),
     (30, 512, 8300), (70, 320, 6500), (128, 256, 12800), (128, 4096, 1024), (100, 1024, 700),   # small LDS tiles
-    (65, 192, 300), (96, 2112, 520),
+    (65, 192, 300), (96, 2112, 520), (64, 1024, 4100), (100, 256, 1000), (33, 640, 2000), (128, 128, 640),
     (1100, 512, 4200), (300, 1088, 520), (257, 256, 777),                                    # large LDS tiles
 ]
 
