@@ -13,12 +13,12 @@
 //       scale bytes as one dword and pick the byte with the instruction's op_sel.
 //   (2) transpose_w_scales_kernel: the weights' E8M0 bytes [N][K/32] -> sw_t in the same layout
 //       over columns (the weight values themselves are consumed where they are).
-//   (3) gemm_w4_dma_kernel: 256 x 256 output tile, 4 waves of 128 x 128, one K step = 64 elements
+//   (3) gemm_w4_dma_kernel: 256 x 256 output tile, 8 waves of 128 x 64, one K step = 64 elements
 //       = two MX blocks = exactly one MFMA K extent (lane l: row/column l%32, block l/32).  A stage
 //       is 33 KB: 24 KB activation operands, 8 KB weights, 1 KB scale bytes, filled by 33
-//       global_load_lds_dwordx4 instructions (8 per wave, wave 0 one more for the scales), NS stages
+//       global_load_lds_dwordx4 instructions (4 per wave, wave 0 one more for the scales), NS stages
 //       deep.  Both components accumulate into the same fp32 accumulator (scale bytes alpha and
-//       alpha - 4, i.e. beta = alpha / 16), so the 256 x 256 tile needs 256 accumulator registers.
+//       alpha - 4, i.e. beta = alpha / 16), so the 256 x 256 tile needs 128 accumulator registers per lane.
 //
 // LDS layout of a stage (every fragment read is linear in the lane, hence conflict-free):
 //   activations: 8 groups of 32 rows, each 6 chunks of 512 B as in qop;
@@ -164,20 +164,20 @@ constexpr int kW4PGroupM = 8;
 // schedule and epilogue on real operand bits, without fill, barriers and LDS traffic.
 // A4 = true: the activation components are OCP E2M1 codes (the E2M1-grid ablation) and travel as native
 // FP4 operands, 16 bytes per lane and block instead of 24: a group of 32 rows is 2 KB per K step
-// (chunk 2c+b = [32 rows][16 B of block b of component c]), a stage 25 KB, 6 fill instructions per wave.
+// (chunk 2c+b = [32 rows][16 B of block b of component c]), a stage 25 KB, 3 fill instructions per wave.
 template <int NS, bool PROBE = false, bool A4 = false>
-__global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, int tiles_m, int tiles_n) {
   constexpr int GA = A4 ? 2048 : 3072;  // operand bytes of a 32-row group per K step
   constexpr int CA = GA / 2;            // of one component
   constexpr int SZ_A = 8 * GA, SZ_W = 8192, STAGE = SZ_A + SZ_W + 1024;
-  constexpr int QA = SZ_A / 4096;       // activation fill instructions per wave and stage
-  constexpr int L = QA + 2;             // data load instructions per wave and stage (wave 0 issues one more: scales)
+  constexpr int QA = SZ_A / 8192;       // activation fill instructions per wave and stage
+  constexpr int L = QA + 1;             // data load instructions per wave and stage (wave 0 issues one more: scales)
   constexpr int CBSZ = A4 ? 4 : 2;
   static_assert(NS >= 3 && (NS - 2) * (L + 1) < 64, "stage count");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem4p[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;  // eight waves: 128 rows x 64 columns each
   const int l32 = lane & 31, kb = lane >> 5;
   const int64_t M = a.M, N = a.N;
   const int KT = (int)(a.K / 64);
@@ -198,31 +198,25 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   const int tn = in_group / rows_in_group;
   const int64_t m0 = (int64_t)tm * 256, n0 = (int64_t)tn * 256;
 
-  // ---- this wave's load instructions per stage: instruction idx = q*4 + wave of the 32 data
+  // ---- this wave's load instructions per stage: instruction idx = q*8 + wave of the 32 data
   // instructions.  The stage image is linear in idx (24 KB of activation operands, then 8 weight
   // groups of 1 KB), and so is the activation source (qop holds the tile's 24 KB of a K step
-  // contiguously): instruction idx < 24 copies kilobyte idx of it.  Instructions 24..31 gather
-  // weight group idx - 24 (32 columns x 2 blocks).  All bases are wave-uniform scalars; only the
-  // two weight offsets and the scale offset are per lane.
+  // contiguously): instruction idx < 24 (q < QA) copies kilobyte idx of it.  Instructions 24..31
+  // (q = QA) gather weight group idx - 24 = wave (32 columns x 2 blocks).  All bases are wave-uniform
+  // scalars; only the weight offset and the scale offset are per lane.
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem4p;
-  const uint8_t* a_src = a.qop + (m0 / 32 * (GA / 1024) + wave) * 1024;  // + kt * step_a + q * 4096, lane * 16
+  const uint8_t* a_src = a.qop + (m0 / 32 * (GA / 1024) + wave) * 1024;  // + kt * step_a + q * 8192, lane * 16
   const uint8_t* w_src = a.W + n0 * row_w;                      // + kt * 32, lane offsets below
-  uint32_t voff_w[2];
-#pragma unroll
-  for (int g = 0; g < 2; ++g) {
-    const int gj = g * 4 + wave;
-    const int64_t nrow = min(n0 + 32 * gj + l32, N - 1);
-    voff_w[g] = (uint32_t)((nrow - n0) * row_w + kb * 16);
-  }
+  const uint32_t voff_w = (uint32_t)((min(n0 + 32 * wave + l32, N - 1) - n0) * row_w + kb * 16);
   const uint32_t voff_a = (uint32_t)(lane * 16);
   // scale bytes of a stage: lanes 0..31 fetch the 512 bytes of sa_t[kt][tm], lanes 32..63 those of sw_t[kt][tn]
   const uint8_t* sbase = kb ? a.sw_t : a.sa_t;                                     // per lane
   const uint64_t s_first = (uint64_t)(sbase - a.ws) + (kb ? n0 : m0) * 2 + 16 * l32;  // byte offset from a.ws
   const uint64_t s_inc = (uint64_t)(kb ? a.Npad : a.Mpad) * 2;                     // per K step
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
-    const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 4096);
-    if (q < QA) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 4096, voff_a, dst);
-    else w4_lds_dma16(w_src + (int64_t)kt * 32, voff_w[q - QA], dst);
+    const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 8192);
+    if (q < QA) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 8192, voff_a, dst);
+    else w4_lds_dma16(w_src + (int64_t)kt * 32, voff_w, dst);
   };
   auto issue_scales = [&](int kt) {
     if (wave == 0)
@@ -234,11 +228,11 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     issue_scales(kt);
   };
 
-  v16f acc[4][4];
+  v16f acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -258,26 +252,27 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     }
   };
   // weights and scale bytes of K step kt; sa / sb: byte i = scale of row fragment i / column fragment i
-  auto load_b = [&](int kt, v8i (&fb)[4], int& sa, int& sb) {
+  // (the column dword holds the four fragments of a 128-column half: this wave's two are moved to bytes 0, 1)
+  auto load_b = [&](int kt, v8i (&fb)[2], int& sa, int& sb) {
     const uint8_t* st = smem4p + (kt % NS) * STAGE;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint4 v = *reinterpret_cast<const uint4*>(st + SZ_A + (wn * 4 + j) * 1024 + o_main);
+    for (int j = 0; j < 2; ++j) {
+      const uint4 v = *reinterpret_cast<const uint4*>(st + SZ_A + (wn * 2 + j) * 1024 + o_main);
       fb[j] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
     }
     sa = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + wm * 256 + o_sc);
-    sb = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + 512 + wn * 256 + o_sc);
+    sb = (int)(*reinterpret_cast<const uint32_t*>(st + SZ_A + SZ_W + 512 + (wn >> 1) * 256 + o_sc) >> ((wn & 1) * 16));
   };
-  // one component block: 16 MFMAs on 16 different accumulators; the first one is issued ahead of
+  // one component block: 8 MFMAs on 8 different accumulators; the first one is issued ahead of
   // the LDS reads that run under the block, so that the compiler's wait for this block's
   // operands (it cannot count LDS operations across the inline asm) covers no read just issued
-  auto mfma_first = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb) {
+  auto mfma_first = [&](const v8i (&fa)[4], const v8i (&fb)[2], int sa, int sb) {
     acc[0][0] = mfma64_scaled<0, 0, CBSZ>(fa[0], fb[0], acc[0][0], sa, sb);
   };
   // ISSUE: the load instructions of tile kt_issue go out between the MFMAs, one after every second
   // MFMA (in one burst after the barrier they fill the address queue, the waves leave the burst at
   // different times and the next barrier pays for the skew); wave 0's scale fetch goes last.
-  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[4], int sa, int sb, int kt_issue, bool do_issue) {
+  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[2], int sa, int sb, int kt_issue, bool do_issue) {
 #define MSD_W4_POST(IDX)                                            \
   if ((IDX) % 2 == 0 && (IDX) / 2 < L) {                            \
     __builtin_amdgcn_sched_barrier(0);                              \
@@ -285,10 +280,8 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     __builtin_amdgcn_sched_barrier(0);                              \
   }
 #define MSD_W4_ROW(I)                                                                      \
-  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0, CBSZ>(fa[I], fb[0], acc[I][0], sa, sb); MSD_W4_POST(4 * I - 1) } \
-  acc[I][1] = mfma64_scaled<I, 1, CBSZ>(fa[I], fb[1], acc[I][1], sa, sb); MSD_W4_POST(4 * I)     \
-  acc[I][2] = mfma64_scaled<I, 2, CBSZ>(fa[I], fb[2], acc[I][2], sa, sb); MSD_W4_POST(4 * I + 1) \
-  acc[I][3] = mfma64_scaled<I, 3, CBSZ>(fa[I], fb[3], acc[I][3], sa, sb); MSD_W4_POST(4 * I + 2)
+  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0, CBSZ>(fa[I], fb[0], acc[I][0], sa, sb); MSD_W4_POST(2 * I - 1) } \
+  acc[I][1] = mfma64_scaled<I, 1, CBSZ>(fa[I], fb[1], acc[I][1], sa, sb); MSD_W4_POST(2 * I)
     MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
 #undef MSD_W4_ROW
 #undef MSD_W4_POST
@@ -314,10 +307,10 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   //   second block (component 1 of step s): under it the component-0 operands, the weights and
   //   the scale bytes of step s+1 are read (weights and scales are double-buffered in registers,
   //   the activation operands are not: each set is dead when its successor is fetched).
-  v8i a0[4], a1[4], b0[4], b1[4];
+  v8i a0[4], a1[4], b0[2], b1[2];
   int sa0 = 0, sb0 = 0, sa1 = 0, sb1 = 0;
   const int beta_shift = a.mv.shift * 0x01010101;
-  auto step = [&](int s, v8i (&bc)[4], int sac, int sbc, v8i (&bn)[4], int& san, int& sbn) {
+  auto step = [&](int s, v8i (&bc)[2], int sac, int sbc, v8i (&bn)[2], int& san, int& sbn) {
     if constexpr (PROBE) {
       if (s > 0) {  // operands of step 0 (a1: component 1 of step 0), no data movement
         mfma_first(a0, b0, sa0, sb0);
@@ -368,13 +361,14 @@ __global__ __launch_bounds__(256) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
       const int64_t m = m0 + wm * 128 + 32 * i + (r >> 2) * 8 + kb * 4 + (r & 3);
       if (m < M) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int64_t n = n0 + wn * 128 + 32 * j + l32;
+        for (int j = 0; j < 2; ++j) {
+          const int64_t n = n0 + wn * 64 + 32 * j + l32;
           if (n >= N) continue;
+          const float v = acc[i][j][r];
           if (a.out_bf16)  // written once, not read again: streaming stores
-            __builtin_nontemporal_store(f32_to_bf16_bits(acc[i][j][r]), reinterpret_cast<uint16_t*>(a.y) + m * a.ldy + n);
+            __builtin_nontemporal_store(f32_to_bf16_bits(v), reinterpret_cast<uint16_t*>(a.y) + m * a.ldy + n);
           else
-            __builtin_nontemporal_store(acc[i][j][r], reinterpret_cast<float*>(a.y) + m * a.ldy + n);
+            __builtin_nontemporal_store(v, reinterpret_cast<float*>(a.y) + m * a.ldy + n);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -449,12 +443,12 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
     attr_set = true;
   }
   if (mv.e2m1)  // E2M1-grid components as native FP4 operands (the probe keeps the FP6 form)
-    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false, true>), dim3(grid), dim3(256),
+    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false, true>), dim3(grid), dim3(512),
                        (size_t)NS * (16384 + 8192 + 1024), stream, a, tiles_m, tiles_n);
   else if (probe)
-    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, true>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, true>), dim3(grid), dim3(512), lds, stream, a, tiles_m, tiles_n);
   else
-    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false>), dim3(grid), dim3(256), lds, stream, a, tiles_m, tiles_n);
+    hipLaunchKernelGGL((gemm_w4_dma_kernel<NS, false>), dim3(grid), dim3(512), lds, stream, a, tiles_m, tiles_n);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
