@@ -764,13 +764,26 @@ __global__ __launch_bounds__(WM * WN * KS * 64, (2 * BMH * BN <= 128 * 256 && WM
     ldst[q] = lds0 + blk * 1024;
   }
   const int KT = (int)(K / BK);
-  auto issue = [&](int kt) {
-    const uint32_t sb = (uint32_t)((kt % NS) * STAGE);
-#pragma unroll
-    for (int q = 0; q < L; ++q) lds_dma16(gbase[q] + kt * kadv[q], voff[q], ldst[q] + sb);
+  // Tiles are issued in increasing order, each once: the source of instruction q is a running wave-uniform
+  // pointer that advances by its stride after every issue.
+  auto uniform64 = [](uint64_t v) {
+    // (the builtin returns int: without the casts a low word with bit 31 set would sign-extend over the high word)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
   };
+#pragma unroll
+  for (int q = 0; q < L; ++q) {
+    gbase[q] = reinterpret_cast<const int8_t*>(uniform64(reinterpret_cast<uint64_t>(gbase[q])));
+    kadv[q] = (int64_t)uniform64((uint64_t)kadv[q]);
+  }
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
-    lds_dma16(gbase[q] + kt * kadv[q], voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
+    lds_dma16(gbase[q], voff[q], ldst[q] + (uint32_t)((kt % NS) * STAGE));
+    gbase[q] += kadv[q];
+  };
+  auto issue = [&](int kt) {
+#pragma unroll
+    for (int q = 0; q < L; ++q) issue_one(kt, q);
   };
 
   AccT acc[2][FM][FN];
@@ -897,7 +910,10 @@ __global__ __launch_bounds__(WM * WN * KS * 64, (2 * BMH * BN <= 128 * 256 && WM
     wait_tile(0, min(KT - 1, NS - 2));
     load_frags(stage_ptr(0), 0, fa0, fb0);
   }
-  for (int kt = 0; kt < KT; ++kt) {
+  // One K stage.  STEADY (a compile-time tag): another tile follows, a tile is issued and the tiles in flight
+  // are at their steady count, so the stage is straight-line code; the last NS-1 stages take the general form.
+  auto stage = [&](int kt, auto steady_tag) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
     if constexpr (PROBE) {
       if (kt > 0) {
 #pragma unroll
@@ -907,10 +923,10 @@ __global__ __launch_bounds__(WM * WN * KS * 64, (2 * BMH * BN <= 128 * 256 && WM
           mfma_block(fa1, fb1);
           __builtin_amdgcn_sched_barrier(0);
         }
-        continue;
+        return;
       }
     }
-    const bool more = kt + 1 < KT;
+    const bool more = STEADY || kt + 1 < KT;
 #pragma unroll
     for (int h = 0; h < HS; ++h) {
       const bool last = h == HS - 1;
@@ -918,17 +934,24 @@ __global__ __launch_bounds__(WM * WN * KS * 64, (2 * BMH * BN <= 128 * 256 && WM
       v4i(&fbc)[FN] = (h & 1) ? fb1 : fb0;
       v4i(&fan)[2 * FM] = (h & 1) ? fa0 : fa1;
       v4i(&fbn)[FN] = (h & 1) ? fb0 : fb1;
-      if (last && more) wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
+      if (last && more) {
+        if constexpr (STEADY) wait_vm_barrier<(NS - 3) * L>();
+        else wait_tile(kt + 1, min(KT - 1, kt + NS - 2));
+      }
       mfma_first(fac, fbc);
       __builtin_amdgcn_sched_barrier(0);
       if (!last) load_frags(stage_ptr(kt), h + 1, fan, fbn);
       else if (more) load_frags(stage_ptr(kt + 1), 0, fan, fbn);
       __builtin_amdgcn_sched_barrier(0);
-      if (last) mfma_rest_issue(fac, fbc, kt + NS - 1, !PROBE && more && kt + NS - 1 < KT);
+      if (last) mfma_rest_issue(fac, fbc, kt + NS - 1, STEADY || (!PROBE && more && kt + NS - 1 < KT));
       else mfma_rest(fac, fbc);
       __builtin_amdgcn_sched_barrier(0);
     }
-  }
+  };
+  int kt = 0;
+  if constexpr (!PROBE)
+    for (; kt + NS - 1 < KT; ++kt) stage(kt, std::true_type{});
+  for (; kt < KT; ++kt) stage(kt, std::false_type{});
   }
 
   if constexpr (BF16) {
