@@ -106,6 +106,10 @@ def main():
     ap.add_argument("--steps", type=int, default=48)
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--weights", default="packed", choices=["packed", "canonical"],
+                    help="weight layout of the timed decode step: packed once by msd_pack_weights_w8 before the "
+                         "timed region (default), or the canonical row-major [N][K] array; the per-shape table "
+                         "reports both")
     ap.add_argument("--extras", default="all", help="comma list of extra legs: cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
@@ -198,17 +202,26 @@ def main():
     for i, M in enumerate(Ms):
         acts[M] = dev_bf16(synth.activations(synth.seed_for(1, i), M, K, outliers=True))
     weights = {}
+    packed = {}
     for j, N in enumerate(Ns):
         W, s = synth.int8_weights(synth.seed_for(1, 10 + j), N, K)
         copies = max(2, -(-2 * LLC_BYTES // (N * K)) + 1)
         Wd = torch.from_numpy(W).to(dev)
         reps = [Wd] + [Wd.clone() for _ in range(copies - 1)]
         weights[N] = (reps, torch.from_numpy(s).to(dev))
+        packed[N] = [msd.msd_pack_weights_w8(w) for w in reps]  # one-time repack, outside every timed region
     outs = {(M, N): torch.empty((M, N), dtype=torch.float32, device=dev) for M in Ms for N in Ns}
     ws_bytes = max(msd.lib().msd_gemm_w8a16_workspace_bytes(M, K, N) for M in Ms for N in Ns)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     shapes = [(M, N) for N in Ns for M in Ms]
     step_bytes = sum(w8_bytes(M, K, N) for M, N in shapes)
+
+    def gemm(M, N, idx, layout=None, prepare=True):
+        """The decode call of shape (M, N) on weight copy idx in the given layout (default: --weights)."""
+        reps, s = weights[N]
+        if (layout or args.weights) == "packed":
+            return msd.msd_gemm_w8a16_packed(acts[M], packed[N][idx % len(reps)], s, y=outs[(M, N)], ws=ws, prepare=prepare)
+        return msd.msd_gemm_w8a16(acts[M], reps[idx % len(reps)], s, y=outs[(M, N)], ws=ws, prepare=prepare)
 
     if args.traffic_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -219,9 +232,10 @@ def main():
         for (M, N) in shapes:
             reps, s = weights[N]
             for i in range(3):
-                msd.msd_gemm_w8a16(acts[M], reps[(5 * i + 1) % len(reps)], s, y=outs[(M, N)], ws=ws)
+                gemm(M, N, 5 * i + 1, prepare=False)
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": [{"M": M, "K": K, "N": N, "calls": 3} for (M, N) in shapes],
+                          "weights": args.weights,
                           "calibration_copy_bytes": 1 << 30}))
         return
 
@@ -237,7 +251,7 @@ def main():
         for pos, (M, N) in enumerate(shapes):
             reps, s = weights[N]
             idx = (i * len(Ms) + pos % len(Ms)) % len(reps)
-            calls.append(msd.msd_gemm_w8a16(acts[M], reps[idx], s, y=outs[(M, N)], ws=ws, prepare=True))
+            calls.append(gemm(M, N, idx))
         return calls
 
     def capture(call_list):
@@ -299,22 +313,21 @@ def main():
     for (M, N) in shapes:
         reps, s = weights[N]
 
-        def mk(i, M=M, N=N, reps=reps, s=s):
-            return msd.msd_gemm_w8a16(acts[M], reps[i % len(reps)], s, y=outs[(M, N)], ws=ws, prepare=True)
-
-        us = time_calls(mk, 2 * len(reps))
+        us = time_calls(lambda i, M=M, N=N: gemm(M, N, i), 2 * len(reps))
         us_min = time_calls.last["min"]
+        other = "canonical" if args.weights == "packed" else "packed"
+        us_other = time_calls(lambda i, M=M, N=N: gemm(M, N, i, layout=other), 2 * len(reps))
         if N not in stream_us:
             # a bare read of the same weight bytes (no arithmetic, one launch), same cold-cache protocol:
             # what this GPU charges for the stream alone at this size
             stream_us[N] = time_calls(lambda i, reps=reps: msd.msd_stream_read(reps[i % len(reps)], prepare=True),
                                       2 * len(reps))
         # the same call on one weight copy over and over (cache-resident weights), labelled warm
-        warm = time_calls(lambda i, M=M, N=N, reps=reps, s=s: msd.msd_gemm_w8a16(acts[M], reps[0], s, y=outs[(M, N)],
-                                                                             ws=ws, prepare=True), 16)
+        warm = time_calls(lambda i, M=M, N=N: gemm(M, N, 0), 16)
         b = w8_bytes(M, K, N)
         per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2), "us_per_call_min": round(us_min, 2),
-                          "warm_us_per_call": round(warm, 2),
+                          "warm_us_per_call": round(warm, 2), "weights": args.weights,
+                          other + "_weights_us_per_call": round(us_other, 2),
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
                           "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2),
                           "bare_weight_read_us": round(stream_us[N], 2),
@@ -344,8 +357,8 @@ def main():
             traffic_note = "profiles/w8a16_decode_hbm_traffic_pmc.txt was taken at other kernel sources: not reported"
     except OSError:
         traffic = None
-    roofline = {"bound": "hbm", "kernel": "msd_gemm_w8a16 M=%d K=%d N=%d (all launches of one call)" %
-                (dom["M"], dom["K"], dom["N"]),
+    roofline = {"bound": "hbm", "kernel": "%s M=%d K=%d N=%d (all launches of one call)" %
+                ("msd_gemm_w8a16_packed" if args.weights == "packed" else "msd_gemm_w8a16", dom["M"], dom["K"], dom["N"]),
                 "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
@@ -385,7 +398,9 @@ def main():
     def _r(v, n=3):
         return None if v is None else round(v, n)
     per_config = {"cfg1_w8a16_decode": [
-        {"M": r["M"], "N": r["N"], "us": r["us_per_call"], "us_min": r["us_per_call_min"], "bound": "hbm",
+        {"M": r["M"], "N": r["N"], "us": r["us_per_call"], "us_min": r["us_per_call_min"],
+         ("canonical" if args.weights == "packed" else "packed") + "_weights_us":
+             r[("canonical" if args.weights == "packed" else "packed") + "_weights_us_per_call"], "bound": "hbm",
          "frac": r["hbm_frac"], "vs_bare_read": r["bare_read_over_call"]} for r in per_shape],
         "decomposition_alone": dec}
     ex = extras if isinstance(extras, dict) else {}
@@ -445,7 +460,10 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "W8A16 MSD GEMM decode shapes: M in {1,8,32,128}, K=4096, N in {4096,14336}; "
-                               "one step = all 8 shapes, weights cycled through >512 MB of copies (cold HBM)",
+                               "one step = all 8 shapes, weights cycled through >512 MB of copies (cold HBM); "
+                               + ("weights repacked once by msd_pack_weights_w8 before the timed region"
+                                  if args.weights == "packed" else "weights in the canonical [N][K] layout"),
+                   "weights": args.weights,
                    "bytes_per_step": step_bytes},
         "roofline": roofline, "cpu_baseline": cpu, "shapes": per_shape, "extras": extras,
     }
