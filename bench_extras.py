@@ -106,18 +106,23 @@ def leg_w4(msd, synth, time_calls, dev):
     exps = torch.from_numpy(exps).to(dev).repeat(N // 2048, 1).contiguous()
     wbytes = K * N // 2 + K * N // 32
     reps = [(codes, exps)] + [(codes.clone(), exps.clone()) for _ in range(-(-2 * LLC // wbytes))]
+    preps = [msd.msd_pack_weights_w4(c, e) for (c, e) in reps]  # one-time repack, not timed
     for M in (1, 32, 4096):
         x = _bf16(synth.activations(synth.seed_for(3, M), min(M, 64), K), dev)
         if M > 64:
             x = x.repeat(M // 64, 1).contiguous()
         y = torch.empty((M, N), dtype=torch.float32, device=dev)
         ws = torch.empty(msd.lib().msd_gemm_w4a16_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
-        f = lambda i: msd.msd_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws, prepare=M <= 32)
+        f = lambda i: msd.msd_gemm_w4a16_packed(x, *preps[i % len(reps)], N, y=y, ws=ws, prepare=M <= 32)
+        fc = lambda i: msd.msd_gemm_w4a16(x, *reps[i % len(reps)], y=y, ws=ws, prepare=M <= 32)
         if M <= 32:
             us = time_calls(f, 2 * len(reps))
+            us_canon = time_calls(fc, 2 * len(reps))
         else:
             f(0)
             us = _eager_us(f, 3)
+            fc(0)
+            us_canon = _eager_us(fc, 3)
         b = wbytes + 2 * M * K + 4 * M * N
         if M == 1:  # bare read of the same weight bytes (codes + scale bytes), two launches, cold
             def rd(i):
@@ -128,7 +133,8 @@ def leg_w4(msd, synth, time_calls, dev):
                 def __call__(self):
                     for p_ in self.ps: p_()
             bare_us = time_calls(lambda i: _Both(rd(i)), 2 * len(reps))
-        rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "GBps": round(b / us / 1e3, 1),
+        rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "weights": "packed", "canonical_weights_us": round(us_canon, 1),
+               "GBps": round(b / us / 1e3, 1),
                "hbm_frac": round(b / us / 1e3 / HBM, 4), "exec_TFLOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
         if M <= 32:
@@ -153,6 +159,7 @@ def leg_w4(msd, synth, time_calls, dev):
                 us2 = _eager_us(g, 2)
             rec["cmp_dequant_us"] = round(us2, 1)
             rec["speedup_vs_dequant"] = round(us2 / us, 3)
+            rec["canonical_speedup_vs_dequant"] = round(us2 / us_canon, 3)
         except Exception as e:  # noqa: BLE001
             rec["cmp_error"] = str(e)
         out.append(rec)

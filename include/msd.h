@@ -185,6 +185,31 @@ int msd_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const 
 size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*
+ * Pre-packed MXFP4 weights (optional, one time, offline; same bits, regrouped -- the counterpart of
+ * msd_pack_weights_w8 for the block-scaled matrix instructions, whose operand is 16 channels x 4 MX blocks):
+ *   packed_fp4 [K/128][ceil(N/16)][1024]: byte ((g*16 + r)*16 + b) of the kilobyte (q, nb) =
+ *       byte b of MX block 4q + g of channel 16*nb + r (W_fp4[16*nb + r][(4q + g)*16 + b]); zero past N.
+ *   packed_e8m0 [K/512][ceil(N/16)][256]: byte (r*16 + i) of the record (s, nb) = W_e8m0[16*nb + r][16*s + i];
+ *       0x7F past N.
+ * One operand load is then one contiguous kilobyte instead of 16 pieces of 64 bytes, and the 16 scale bytes of
+ * 16 channels one 256-byte run.
+ *   msd_packed_weights_w4_bytes / msd_packed_scales_w4_bytes (N, K): sizes of the two arrays (0 for empty shapes).
+ *   msd_pack_weights_w4(W_fp4, W_e8m0, N, K, packed_fp4, packed_e8m0, stream): device arrays, the packed ones
+ *       16-byte aligned.  K must be a multiple of 512 (SHAPE error otherwise: such layers use msd_gemm_w4a16).
+ *   msd_gemm_w4a16_packed(...): msd_gemm_w4a16 on the packed arrays; other arguments, workspace size, observation
+ *       points, results (bit-identical: same instructions on the same operands) and errors as msd_gemm_w4a16,
+ *       plus SHAPE for K % 512 != 0 and UNSUPPORTED for row counts whose kernel does not read the packed layout.
+ */
+size_t msd_packed_weights_w4_bytes(int64_t N, int64_t K);
+size_t msd_packed_scales_w4_bytes(int64_t N, int64_t K);
+int msd_pack_weights_w4(const uint8_t* W_fp4, const uint8_t* W_e8m0, int64_t N, int64_t K, void* packed_fp4,
+                        void* packed_e8m0, void* stream);
+int msd_gemm_w4a16_packed(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const void* packed_fp4,
+                          const void* packed_e8m0, int64_t N, void* y, int out_dtype, int64_t ldy,
+                          void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                          void* stream);
+
+/*
  * The three entry points above with the decomposition constants of paper Sec. 3.3 selectable
  * ("fractional scaling" paragraph for INT8; the MXFP4 design-evolution table for MXFP4).
  * Everything else (arguments, layouts, workspace sizes, errors) is as for the entry point of the

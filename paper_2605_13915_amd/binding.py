@@ -66,6 +66,14 @@ def lib():
         L.msd_dequant_gemm_w8a16.argtypes = gemm8
         L.msd_probe_mfma_w8a16.argtypes = gemm8
         L.msd_gemm_w4a16.argtypes = gemm4
+        L.msd_gemm_w4a16_packed.argtypes = gemm4
+        L.msd_gemm_w4a16_packed.restype = ci
+        L.msd_packed_weights_w4_bytes.argtypes = [i64, i64]
+        L.msd_packed_weights_w4_bytes.restype = sz
+        L.msd_packed_scales_w4_bytes.argtypes = [i64, i64]
+        L.msd_packed_scales_w4_bytes.restype = sz
+        L.msd_pack_weights_w4.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+        L.msd_pack_weights_w4.restype = ci
         L.msd_dequant_gemm_w4a16.argtypes = gemm4
         L.msd_probe_mfma_w4a16.argtypes = gemm4
         L.msd_gemm_w8a16_variant.argtypes = [ci] + gemm8
@@ -292,6 +300,30 @@ def msd_gemm_w4a16(x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None
     assert W_fp4.is_contiguous() and W_e8m0.is_contiguous() and W_fp4.shape[1] * 2 == x.shape[1]
     return _gemm_common("msd_gemm_w4a16", "msd_gemm_w4a16_workspace_bytes", x, (_ptr(W_fp4), _ptr(W_e8m0)),
                         W_fp4.shape[0], out_dtype, taps, y, ws, prepare)
+
+
+def msd_pack_weights_w4(W_fp4, W_e8m0):
+    """W_fp4 uint8 [N][K/2], W_e8m0 uint8 [N][K/32] (K % 512 == 0) -> (packed_fp4, packed_e8m0), the arrays
+    msd_gemm_w4a16_packed reads (one-time, offline)."""
+    _dev(W_fp4, torch.uint8, "W_fp4"); _dev(W_e8m0, torch.uint8, "W_e8m0")
+    assert W_fp4.is_contiguous() and W_e8m0.is_contiguous()
+    N, K = W_fp4.shape[0], W_fp4.shape[1] * 2
+    Wp = torch.empty(lib().msd_packed_weights_w4_bytes(N, K), dtype=torch.uint8, device=W_fp4.device)
+    Ep = torch.empty(lib().msd_packed_scales_w4_bytes(N, K), dtype=torch.uint8, device=W_fp4.device)
+    _check(lib().msd_pack_weights_w4(_ptr(W_fp4), _ptr(W_e8m0), N, K, _ptr(Wp), _ptr(Ep), _stream()),
+           "msd_pack_weights_w4")
+    return Wp, Ep
+
+
+def msd_gemm_w4a16_packed(x, packed_fp4, packed_e8m0, N, out_dtype=torch.float32, taps=False, y=None, ws=None,
+                          prepare=False):
+    """msd_gemm_w4a16 on the arrays of msd_pack_weights_w4; N (output channels) cannot be read off them."""
+    _dev(x, torch.bfloat16, "x"); _dev(packed_fp4, torch.uint8, "packed_fp4"); _dev(packed_e8m0, torch.uint8, "packed_e8m0")
+    K = x.shape[1]
+    assert packed_fp4.numel() == lib().msd_packed_weights_w4_bytes(N, K)
+    assert packed_e8m0.numel() == lib().msd_packed_scales_w4_bytes(N, K)
+    return _gemm_common("msd_gemm_w4a16_packed", "msd_gemm_w4a16_workspace_bytes", x, (_ptr(packed_fp4), _ptr(packed_e8m0)),
+                        N, out_dtype, taps, y, ws, prepare)
 
 
 def msd_gemm_w4a16_variant(variant, x, W_fp4, W_e8m0, out_dtype=torch.float32, taps=False, y=None, ws=None,

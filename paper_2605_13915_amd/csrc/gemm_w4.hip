@@ -77,8 +77,13 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
   const int64_t s0 = min((int64_t)wave * per, supers), s1 = min(supers, s0 + per);
   constexpr bool fast = FAST;
   const int64_t wrow = min(n0 + row, N - 1);
-  const uint8_t* wp = a.W + wrow * (KB * 16);
-  const uint8_t* wep = a.We + wrow * KB;
+  // Packed weights (FAST only; layout in msd.h): the 16 channels x 4 blocks that one MFMA of this workgroup
+  // multiplies are one kilobyte in lane order, the 16 x 16 scale bytes of a super-step 256 contiguous bytes.
+  const bool packed = FAST && a.w_packed != 0;
+  const int64_t wtiles = (N + 15) / 16;
+  const uint8_t* wp = packed ? a.W + (n0 / 16) * 1024 + lane * 16 : a.W + wrow * (KB * 16);
+  const uint8_t* wep = packed ? a.We + (n0 / 16) * 256 + row * 16 : a.We + wrow * KB;
+  const int64_t wq = wtiles * 1024, weq = wtiles * 256;  // packed: bytes between K units / super-steps
   const v8i zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   const v4i one16 = {0x7F7F7F7F, 0x7F7F7F7F, 0x7F7F7F7F, 0x7F7F7F7F};
   v4f acc[RT];
@@ -97,14 +102,14 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
     for (int u2 = 0; u2 < U; ++u2) {
       const int64_t s = sb + u2;
       v4i sc16 = one16;
-      if (s < s1 && fast) sc16 = *reinterpret_cast<const v4i*>(wep + s * 16);
+      if (s < s1 && fast) sc16 = *reinterpret_cast<const v4i*>(wep + (packed ? s * weq : s * 16));
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int64_t bi = s * 16 + (CONTIG ? 4 * u + g : 4 * g + u);
         const bool ok = s < s1 && (FAST || bi < KB);
         wb[u2][u] = zero8;
         if (ok) {
-          const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + bi * 16));
+          const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + (packed ? (4 * s + u) * wq : bi * 16)));
           wb[u2][u] = v8i{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
         }
         wsc[u2][u] = fast ? (CONTIG ? scale_byte(sc16, u, g) : scale_byte(sc16, g, u)) : (ok ? (int)wep[bi] : 0x7F);
@@ -537,8 +542,48 @@ int launch_gemm_w4_grouped(const GemmW4Args& a, const int32_t* offs, int E, hipS
   return MSD_OK;
 }
 
+// ------------------------------------------------------------------ one-time weight repack (msd_pack_weights_w4)
+// codes: one thread per 16-byte block of a channel; scales: one thread per (super-step, channel)
+__global__ __launch_bounds__(256) void pack_weights_w4_kernel(const uint8_t* __restrict__ W, const uint8_t* __restrict__ We,
+                                                              int64_t N, int64_t KB, uint8_t* __restrict__ Wp,
+                                                              uint8_t* __restrict__ Ep) {
+  const int64_t tiles = (N + 15) / 16;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t pieces = (KB / 4) * tiles * 64;
+  if (gid < pieces) {
+    const int lane = (int)(gid & 63), r = lane & 15, g = lane >> 4;
+    const int64_t tile = (gid >> 6) % tiles, q = (gid >> 6) / tiles;
+    const int64_t n = tile * 16 + r;
+    v4i v = {0, 0, 0, 0};
+    if (n < N) v = *reinterpret_cast<const v4i*>(W + (n * KB + 4 * q + g) * 16);
+    *reinterpret_cast<v4i*>(Wp + gid * 16) = v;
+  }
+  const int64_t recs = (KB / 16) * tiles * 16;
+  if (gid < recs) {
+    const int r = (int)(gid & 15);
+    const int64_t tile = (gid >> 4) % tiles, s = (gid >> 4) / tiles;
+    const int64_t n = tile * 16 + r;
+    uint8_t b[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) b[i] = n < N ? We[n * KB + s * 16 + i] : (uint8_t)0x7F;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) Ep[gid * 16 + i] = b[i];
+  }
+}
+
+int launch_pack_weights_w4(const uint8_t* W, const uint8_t* We, int64_t N, int64_t K, uint8_t* Wp, uint8_t* Ep,
+                           hipStream_t stream) {
+  const int64_t KB = K / 32, tiles = (N + 15) / 16;
+  const int64_t pieces = (KB / 4) * tiles * 64;
+  hipLaunchKernelGGL(pack_weights_w4_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, stream, W, We, N, KB, Wp, Ep);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
+  // packed weights: the register-operand kernel in its unpredicated form only
+  if (a.w_packed && (a.M > 16 || (a.K / 32) % 16 != 0)) return MSD_ERR_UNSUPPORTED;
   int rc;
   if (a.x != nullptr) {  // single launch (gemm_w4_is_fused)
     rc = launch_w4<4, 2, 1, true, true>(a, stream);

@@ -6,7 +6,8 @@
 // kernel.
 //
 // One workgroup = 4 waves = 128 output channels, the whole K range, all rows (one, two or four
-// groups of 32); a wave owns 32 channels (lane l: channel l%32, MX block l/32 of each K step).  K is
+// groups of 32); a wave owns 32 channels (lane l: channel l%32, MX block l/32 of each K step).  (Eight waves in
+// two K groups measured no better at 32 rows and worse at 128, where the registers no longer suffice.)  K is
 // walked in batches of U steps.  Per batch the workgroup stages the weights (128 channels x U*32
 // bytes, contiguous per channel and instruction) and the activation operands of the batch (hot in
 // L2, shared by the four waves) through LDS, double-buffered: global -> registers, registers -> LDS
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
                                                                   const uint8_t* __restrict__ W,
                                                                   const uint8_t* __restrict__ We, void* y,
                                                                   int out_bf16, int64_t ldy, int M, int64_t K,
-                                                                  int64_t N, int shift) {
+                                                                  int64_t N, int shift, int w_packed) {
   using C = MidCfg<RG, U, A4>;
   constexpr int CBSZ = A4 ? 4 : 2;
   extern __shared__ __attribute__((aligned(16))) uint8_t s_mid[];  // [2][A batch] then [2][W batch]
@@ -74,14 +75,30 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   const int64_t n0 = (int64_t)blockIdx.x * kMidBN;
   const int64_t n = n0 + wave * 32 + l32;
   // channels past N repeat the last one; their results are not stored
-  const uint8_t* werow = We + min(n, N - 1) * (K / 32);
+  // Packed weights (msd_pack_weights_w4): W is [K/128][tiles][1 KB], kilobyte = 16 channels x 4 MX blocks in the
+  // order (block g, channel r); We is [K/512][tiles][16 channels][16 bytes].
+  const int64_t wtiles = (N + 15) / 16;
+  const int64_t nc = min(n, N - 1);
+  const uint8_t* werow = w_packed ? We + (nc / 16) * 256 + (nc % 16) * 16 : We + nc * (K / 32);
   const int NB = (int)(K / (64 * U));  // batches (K is a multiple of 64 * U)
-  // weight staging: chunk tid + i * 256 of the batch = (row chunk / kChunksW, 16-byte column chunk % kChunksW)
+  // weight staging, canonical layout: chunk tid + i * 256 of the batch = (row chunk / kChunksW, 16-byte column
+  // chunk % kChunksW).  Packed layout: pass i of wave w copies kilobyte 4 i + w of the batch's U/2 x 8 kilobytes
+  // (K unit (4 i + w) / 8, channel tile (4 i + w) % 8), lane (g, r) to row 16 tile + r, byte 64 unit + 16 g.
   const int wr = tid / C::kChunksW, wc = tid % C::kChunksW;
   const uint8_t* wsrc[C::kStageW];
+  int wdst[C::kStageW];
 #pragma unroll
-  for (int i = 0; i < C::kStageW; ++i)
-    wsrc[i] = W + min(n0 + wr + C::kRowsPerPass * i, N - 1) * (K / 2) + wc * 16;
+  for (int i = 0; i < C::kStageW; ++i) {
+    if (w_packed) {
+      const int kb_i = 4 * i + wave, unit = kb_i >> 3, tile = kb_i & 7;
+      wsrc[i] = W + ((int64_t)unit * wtiles + min(n0 / 16 + tile, wtiles - 1)) * 1024 + lane * 16;
+      wdst[i] = (tile * 16 + (lane & 15)) * C::kRowW + unit * 64 + (lane >> 4) * 16;
+    } else {
+      wsrc[i] = W + min(n0 + wr + C::kRowsPerPass * i, N - 1) * (K / 2) + wc * 16;
+      wdst[i] = (wr + C::kRowsPerPass * i) * C::kRowW + wc * 16;
+    }
+  }
+  const int64_t wstep = w_packed ? (int64_t)(U / 2) * wtiles * 1024 : U * 32;  // weight bytes between batches
 
   // two register stages: while batch b is multiplied out of LDS, batch b + 1 and batch b + 2 are in flight
   struct Stage {
@@ -93,11 +110,12 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   auto load_batch = [&](int b, Stage& st) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < C::kStageW; ++i)
-      st.w[i] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wsrc[i] + (int64_t)b * (U * 32)));
+      st.w[i] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wsrc[i] + (int64_t)b * wstep));
     if (U == 8) {
-      st.wsc = *reinterpret_cast<const v4i*>(werow + (int64_t)b * 16);
+      st.wsc = *reinterpret_cast<const v4i*>(werow + (int64_t)b * (w_packed ? wtiles * 256 : 16));
     } else {  // U == 4: 8 scale bytes
-      const v2i t = *reinterpret_cast<const v2i*>(werow + (int64_t)b * 8);
+      const v2i t = *reinterpret_cast<const v2i*>(werow + (w_packed ? (int64_t)(b >> 1) * wtiles * 256 + (b & 1) * 8
+                                                                     : (int64_t)b * 8));
       st.wsc[0] = t[0];
       st.wsc[1] = t[1];
     }
@@ -113,7 +131,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
     uint8_t* sw = s_mid + 2 * C::kBufA + buf * C::kBufW;
 #pragma unroll
     for (int i = 0; i < C::kStageW; ++i)
-      *reinterpret_cast<v4i*>(sw + (wr + C::kRowsPerPass * i) * C::kRowW + wc * 16) = st.w[i];
+      *reinterpret_cast<v4i*>(sw + wdst[i]) = st.w[i];
 #pragma unroll
     for (int i = 0; i < C::kStageA; ++i) *reinterpret_cast<v4i*>(sa + (tid + i * kMidThreads) * 16) = st.a[i];
     if (tid < U * 16) *reinterpret_cast<v4i*>(sa + U * C::kStepA + tid * 16) = st.asc;
@@ -208,7 +226,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
 
 template <int RG, int U, bool A4>
 int launch_mid(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
-               int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
+               int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, int w_packed, hipStream_t stream) {
   constexpr int lds = MidCfg<RG, U, A4>::kLds;
   const void* fn = reinterpret_cast<const void*>(&gemm_w4_mid_kernel<RG, U, A4>);
   static bool attr_set = false;
@@ -217,7 +235,7 @@ int launch_mid(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W, const 
     attr_set = true;
   }
   hipLaunchKernelGGL((gemm_w4_mid_kernel<RG, U, A4>), dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), lds, stream,
-                     qop, sa_t, W, We, y, out_bf16, ldy, (int)M, K, N, shift);
+                     qop, sa_t, W, We, y, out_bf16, ldy, (int)M, K, N, shift, w_packed);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
@@ -242,19 +260,20 @@ W4MidLayout w4_mid_layout(int64_t M, int64_t K) {
 }
 
 int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
-                       int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, hipStream_t stream) {
+                       int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, int w_packed,
+                       hipStream_t stream) {
   const W4MidLayout l = w4_mid_layout(M, K);
   if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, (int64_t)l.Mpad, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
   const uint8_t* qop = ws + l.qop;
   const uint8_t* sa = ws + l.sa_t;
   if (mv.e2m1) {  // E2M1-grid components as native FP4 operands
-    if (l.Mpad == 32) return launch_mid<1, 8, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-    if (l.Mpad == 64) return launch_mid<2, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-    return launch_mid<4, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 32) return launch_mid<1, 8, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
+    if (l.Mpad == 64) return launch_mid<2, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
+    return launch_mid<4, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   }
-  if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-  if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-  return launch_mid<4, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
+  if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
+  return launch_mid<4, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
 }
 
 }  // namespace msd

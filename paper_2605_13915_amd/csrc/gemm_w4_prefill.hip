@@ -100,9 +100,10 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
 // ------------------------------------------------------------------ (2) weight scale bytes, K-step-major
 // One workgroup moves a 64 (columns) x 64 (K steps) tile of byte pairs through LDS so that both the
 // reads (along K) and the writes (along N) are contiguous.
+// packed: We is the scale array of msd_pack_weights_w4, [K/512][ceil(N/16)][16 channels][16 bytes].
 __global__ __launch_bounds__(256) void transpose_w_scales_kernel(const uint8_t* __restrict__ We, int64_t N,
                                                                  int KB2, int64_t Npad,
-                                                                 uint8_t* __restrict__ sw_t) {
+                                                                 uint8_t* __restrict__ sw_t, int packed) {
   __shared__ uint16_t tile[64][65];
   const int64_t n0 = (int64_t)blockIdx.x * 64;
   const int s0 = blockIdx.y * 64;
@@ -112,7 +113,8 @@ __global__ __launch_bounds__(256) void transpose_w_scales_kernel(const uint8_t* 
     const int s = s0 + c;
     uint16_t v = 0x7F7F;
     if (n < N && s < KB2) {
-      const uint8_t* p = We + (n * KB2 + s) * 2;
+      const uint8_t* p = packed ? We + ((int64_t)(s >> 3) * ((N + 15) / 16) + n / 16) * 256 + (n & 15) * 16 + ((2 * s) & 15)
+                                : We + (n * KB2 + s) * 2;
       v = (uint16_t)p[0] | ((uint16_t)p[1] << 8);
     }
     tile[r][c] = v;
@@ -206,8 +208,13 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // scalars; only the weight offset and the scale offset are per lane.
   const uint32_t lds0 = (uint32_t)(uintptr_t)smem4p;
   const uint8_t* a_src = a.qop + (m0 / 32 * (GA / 1024) + wave) * 1024;  // + kt * step_a + q * 8192, lane * 16
-  const uint8_t* w_src = a.W + n0 * row_w;                      // + kt * 32, lane offsets below
-  const uint32_t voff_w = (uint32_t)((min(n0 + 32 * wave + l32, N - 1) - n0) * row_w + kb * 16);
+  // packed weights (msd_pack_weights_w4): the 32 columns x 2 blocks of a wave and K step are two 512-byte halves
+  // of the kilobytes of two adjacent channel tiles
+  const int64_t wtiles = (N + 15) / 16, wq = wtiles * 1024;
+  const uint8_t* w_src = a.w_packed ? a.W + (n0 / 16) * 1024 : a.W + n0 * row_w;  // + K step, lane offsets below
+  const uint32_t voff_w =
+      a.w_packed ? (uint32_t)((min(n0 / 16 + 2 * wave + (l32 >> 4), wtiles - 1) - n0 / 16) * 1024 + (kb * 16 + (l32 & 15)) * 16)
+                 : (uint32_t)((min(n0 + 32 * wave + l32, N - 1) - n0) * row_w + kb * 16);
   const uint32_t voff_a = (uint32_t)(lane * 16);
   // scale bytes of a stage: lanes 0..31 fetch the 512 bytes of sa_t[kt][tm], lanes 32..63 those of sw_t[kt][tn]
   const uint8_t* sbase = kb ? a.sw_t : a.sa_t;                                     // per lane
@@ -216,7 +223,7 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
     const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 8192);
     if (q < QA) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 8192, voff_a, dst);
-    else w4_lds_dma16(w_src + (int64_t)kt * 32, voff_w, dst);
+    else w4_lds_dma16(a.w_packed ? w_src + (int64_t)(kt >> 1) * wq + (kt & 1) * 512 : w_src + (int64_t)kt * 32, voff_w, dst);
   };
   auto issue_scales = [&](int kt) {
     if (wave == 0)
@@ -406,13 +413,13 @@ int launch_decompose_mxfp4_pair(const uint16_t* x, int64_t ldx, int64_t M, int64
 
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
-                           MxVariant mv, hipStream_t stream, bool probe) {
+                           MxVariant mv, hipStream_t stream, bool probe, int w_packed) {
   const W4PrefillLayout l = w4_prefill_layout(M, K, N);
   if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace
   const int KB2 = (int)(K / 64);
   if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, (int64_t)l.Mpad, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
   hipLaunchKernelGGL(transpose_w_scales_kernel, dim3((unsigned)(l.Npad / 64), (unsigned)cdiv(KB2, 64)), dim3(256), 0,
-                     stream, We, N, KB2, (int64_t)l.Npad, ws + l.sw_t);
+                     stream, We, N, KB2, (int64_t)l.Npad, ws + l.sw_t, w_packed);
   MSD_LAUNCH_CHECK();
   GemmW4PrefillArgs a{};
   a.ws = ws;
@@ -420,6 +427,7 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
   a.sa_t = ws + l.sa_t;
   a.sw_t = ws + l.sw_t;
   a.W = W;
+  a.w_packed = w_packed;
   a.y = y;
   a.out_bf16 = out_bf16;
   a.ldy = ldy;

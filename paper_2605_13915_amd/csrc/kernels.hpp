@@ -93,6 +93,7 @@ struct GemmW4Args {
   uint8_t* abi_q2;
   uint8_t* abi_e8m0;
   int scales_aligned;  // W_e8m0 is 16-byte aligned (16-byte scale loads allowed)
+  int w_packed;        // W and We are the packed arrays of msd_pack_weights_w4 (needs K % 512 == 0)
   MxVariant mv;
 };
 bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
@@ -100,6 +101,9 @@ bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
 // expert e owns rows [offs[e], offs[e+1]) (device array of E + 1 entries); a.M is unused
 int launch_gemm_w4_grouped(const GemmW4Args& a, const int32_t* offs, int E, hipStream_t stream);
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
+// W [N][K/2], We [N][K/32] -> the packed arrays of msd_pack_weights_w4 (K % 512 == 0)
+int launch_pack_weights_w4(const uint8_t* W, const uint8_t* We, int64_t N, int64_t K, uint8_t* Wp, uint8_t* Ep,
+                           hipStream_t stream);
 
 // ---- W4A16, many rows (gemm_w4_prefill.hip): own decomposition format, asynchronous LDS fill
 struct GemmW4PrefillArgs {
@@ -107,7 +111,8 @@ struct GemmW4PrefillArgs {
   const uint8_t* qop;   // [M][K/64][96 B] FP6 operands of both components
   const uint8_t* sa_t;  // [K/64][Mpad][2] activation scale bytes
   const uint8_t* sw_t;  // [K/64][Npad][2] weight scale bytes
-  const uint8_t* W;     // [N][K/2]
+  const uint8_t* W;     // [N][K/2], or the packed array of msd_pack_weights_w4
+  int w_packed;
   void* y;
   int out_bf16;
   int64_t ldy;
@@ -124,7 +129,7 @@ W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N);
 // barriers or LDS traffic afterwards); y is then meaningless
 int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y,
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
-                           MxVariant mv, hipStream_t stream, bool probe = false);
+                           MxVariant mv, hipStream_t stream, bool probe = false, int w_packed = 0);
 
 // decomposition alone, in the K-step-major operand order described in gemm_w4_prefill.hip: qop holds
 // (K/64) * (Mpad/32) * 3072 bytes, sa_t (K/64) * max(Mpad/256, 1) * 512 bytes; Mpad a multiple of 32
@@ -140,7 +145,8 @@ W4MidLayout w4_mid_layout(int64_t M, int64_t K);
 // decomposition (K-step-major operands of one, two or four 32-row groups) + GEMM; ws holds
 // w4_mid_layout(M, K).total bytes
 int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
-                       int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, hipStream_t stream);
+                       int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws, MxVariant mv, int w_packed,
+                       hipStream_t stream);
 
 // ---- attention (attn.hip)
 struct AttnArgs {

@@ -124,3 +124,61 @@ def test_gemm_w4a16_bf16_out_and_errors(msd):
                            torch.zeros((4, 24), dtype=torch.uint8, device="cuda"),
                            torch.zeros((4, 1), dtype=torch.uint8, device="cuda"))
     assert e.value.code == -2
+
+
+PACKED_SHAPES = [
+    (1, 8192, 512), (1, 512, 40), (2, 2048, 4096), (3, 1024, 300), (4, 512, 8300),          # register-operand kernel
+    (9, 1024, 300), (32, 8192, 700), (24, 2048, 8300), (64, 1024, 300), (128, 1536, 4200),  # LDS-staged weight stream
+    (256, 512, 256), (300, 2048, 600), (700, 512, 1000),                                     # many-row pipeline
+]
+
+
+@pytest.mark.parametrize("M,K,N", PACKED_SHAPES)
+def test_gemm_w4a16_packed_weights(msd, M, K, N):
+    """msd_gemm_w4a16_packed against the oracle (which reads the canonical layout) and bit-identical to
+    msd_gemm_w4a16 on the canonical arrays (same instructions on the same operands, another address map)."""
+    seed = synth.seed_for(3, M * 17 + N)
+    x = synth.activations(seed, M, K, outliers=K >= 1024)
+    codes, exps = synth.mxfp4_weights(seed, N, K)
+    y_ref = oracle.gemm_w4a16(x, codes, exps)
+    xd, cd, ed = bf16_to_dev(x), to_dev(codes), to_dev(exps)
+    Wp, Ep = msd.msd_pack_weights_w4(cd, ed)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w4a16_packed(xd, Wp, Ep, N, y=y)
+    torch.cuda.synchronize()
+    yh = y.cpu().numpy()
+    assert np.all(np.isfinite(yh))
+    assert rel_l2(yh, y_ref) <= 2e-6
+    assert torch.equal(y, msd.msd_gemm_w4a16(xd, cd, ed))
+    if M <= 16:  # observation points ride on the register-operand kernel
+        y2, g = msd.msd_gemm_w4a16_packed(xd, Wp, Ep, N, taps=True)
+        torch.cuda.synchronize()
+        _, t = oracle.gemm_w4a16(x, codes, exps, taps=True)
+        assert np.array_equal(g["q1"].cpu().numpy(), t["q1"]) and np.array_equal(g["q2"].cpu().numpy(), t["q2"])
+        assert np.array_equal(g["scale"].cpu().numpy(), t["e8m0"])
+        assert rel_l2(y2.cpu().numpy(), y_ref) <= 2e-6
+
+
+def test_pack_weights_w4_layout_and_errors(msd):
+    """The packed arrays are exactly the documented permutations (zero / 0x7F padding past N); K % 512 != 0 is refused."""
+    N, K = 40, 1024
+    codes, exps = synth.mxfp4_weights(synth.seed_for(3, 99), N, K)
+    Wp, Ep = msd.msd_pack_weights_w4(to_dev(codes), to_dev(exps))
+    torch.cuda.synchronize()
+    tiles = (N + 15) // 16
+    want = np.zeros((K // 128, tiles, 4, 16, 16), dtype=np.uint8)       # [q][nb][g][r][b]
+    cp = np.zeros((tiles * 16, K // 32, 16), dtype=np.uint8)
+    cp[:N] = codes.reshape(N, K // 32, 16)
+    for q in range(K // 128):
+        for g in range(4):
+            want[q, :, g] = cp[:, 4 * q + g].reshape(tiles, 16, 16)
+    assert np.array_equal(Wp.cpu().numpy(), want.reshape(-1))
+    ep = np.full((tiles * 16, K // 32), 0x7F, dtype=np.uint8)
+    ep[:N] = exps
+    want_e = ep.reshape(tiles, 16, K // 512, 16).transpose(2, 0, 1, 3)   # [s][nb][r][i]
+    assert np.array_equal(Ep.cpu().numpy(), want_e.reshape(-1))
+    L = msd.lib()
+    assert L.msd_packed_weights_w4_bytes(N, K) == want.size and L.msd_packed_scales_w4_bytes(N, K) == want_e.size
+    assert L.msd_packed_weights_w4_bytes(0, K) == 0
+    bad = L.msd_pack_weights_w4(Wp.data_ptr(), Ep.data_ptr(), N, 544, Wp.data_ptr(), Ep.data_ptr(), None)
+    assert bad == -2  # MSD_ERR_SHAPE
