@@ -58,48 +58,6 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
   const int8_t* Kb = p.K + kv_base * kD;
   const int8_t* Vb = p.V + kv_base * kD;
 
-  // ---- prologue: decompose the G query rows (Alg. 3 steps 1-2), one head per wave at a time
-  for (int h = wave; h < nh_total; h += kAttnWaves) {
-    uint32_t c1 = 0, c2 = 0;
-    float alpha = 0.f;
-    if (h < G) {
-      const int64_t qrow = (int64_t)b * p.Hq + hk * G + h;
-      const uint32_t w = reinterpret_cast<const uint32_t*>(p.q + qrow * kD)[lane];
-      float x0 = __uint_as_float(w << 16), x1 = __uint_as_float(w & 0xFFFF0000u);
-      if (!PER_TOKEN) {  // absorb the per-channel K scale into Q
-        x0 *= p.k_scale[hk * kD + 2 * lane];
-        x1 *= p.k_scale[hk * kD + 2 * lane + 1];
-      }
-      const float mx = wave_max(fmaxf(fabsf(x0), fabsf(x1)));
-      if (mx > 0.f) {
-        alpha = __fdiv_rn(mx, 127.0f);
-        const float beta = __fdiv_rn(alpha, 254.0f);
-        int a0, b0, a1, b1;
-        int8_codes(x0, alpha, beta, a0, b0);
-        int8_codes(x1, alpha, beta, a1, b1);
-        c1 = ((uint32_t)a0 & 0xFFu) | (((uint32_t)a1 & 0xFFu) << 8);
-        c2 = ((uint32_t)b0 & 0xFFu) | (((uint32_t)b1 & 0xFFu) << 8);
-      }
-      if (split == 0 && p.tap_q1) {
-        reinterpret_cast<uint16_t*>(p.tap_q1 + qrow * kD)[lane] = (uint16_t)c1;
-        reinterpret_cast<uint16_t*>(p.tap_q2 + qrow * kD)[lane] = (uint16_t)c2;
-        if (lane == 0) p.tap_alpha[qrow] = alpha;
-      }
-    }
-    reinterpret_cast<uint16_t*>(sQ + (int64_t)h * kD)[lane] = (uint16_t)c1;
-    reinterpret_cast<uint16_t*>(sQ + (int64_t)(nh_total + h) * kD)[lane] = (uint16_t)c2;
-    if (lane == 0) sAlpha[h] = alpha;
-  }
-  __syncthreads();
-
-  // A-fragment row of this lane (as an operand lane: row = j, k group = g)
-  const int slot = j & 3;
-  const bool row_valid = (HPL == 2) || (slot < 2);
-  const int row_head = (j >> 2) * HPL + (HPL == 2 ? (slot >> 1) : 0);  // head within the fragment
-  const int row_comp = (HPL == 2) ? (slot & 1) : slot;
-  const v4i zero4 = {0, 0, 0, 0};
-  const float sm_scale = kLog2e / sqrtf((float)kD);  // scores are kept in log2 units
-
   // Tile loads are software-pipelined: the K/V/scale loads of the wave's next tile are issued
   // before the current tile is processed.  Token indices are clamped to the last valid token, so
   // every load is unconditional (a wave's look-ahead past its range re-reads that token).
@@ -134,6 +92,64 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
     }
   };
   const int64_t t_first = t_begin + (int64_t)wave * kTile;
+  // The first tile's loads go out before the query rows are decomposed: they do not depend on them, and a
+  // split of a short cache is over after a few tiles, so the prologue's latency would otherwise show in full.
+  // The loads of this wave's first query row are issued ahead of them (loads complete in order: the prologue
+  // then waits for the query row only, not for the tile).
+  uint32_t q_first = 0;
+  float ks_first0 = 1.f, ks_first1 = 1.f;
+  if (wave < G) {
+    q_first = reinterpret_cast<const uint32_t*>(p.q + ((int64_t)b * p.Hq + hk * G + wave) * kD)[lane];
+    if (!PER_TOKEN) {
+      ks_first0 = p.k_scale[hk * kD + 2 * lane];
+      ks_first1 = p.k_scale[hk * kD + 2 * lane + 1];
+    }
+  }
+  if (t_first < t_end) load_tile(t_first, kfn, vrn, skn, svn);
+
+  // ---- prologue: decompose the G query rows (Alg. 3 steps 1-2), one head per wave at a time
+  for (int h = wave; h < nh_total; h += kAttnWaves) {
+    uint32_t c1 = 0, c2 = 0;
+    float alpha = 0.f;
+    if (h < G) {
+      const int64_t qrow = (int64_t)b * p.Hq + hk * G + h;
+      const bool first = h == wave;  // loaded above
+      const uint32_t w = first ? q_first : reinterpret_cast<const uint32_t*>(p.q + qrow * kD)[lane];
+      float x0 = __uint_as_float(w << 16), x1 = __uint_as_float(w & 0xFFFF0000u);
+      if (!PER_TOKEN) {  // absorb the per-channel K scale into Q
+        x0 *= first ? ks_first0 : p.k_scale[hk * kD + 2 * lane];
+        x1 *= first ? ks_first1 : p.k_scale[hk * kD + 2 * lane + 1];
+      }
+      const float mx = wave_max(fmaxf(fabsf(x0), fabsf(x1)));
+      if (mx > 0.f) {
+        alpha = __fdiv_rn(mx, 127.0f);
+        const float beta = __fdiv_rn(alpha, 254.0f);
+        int a0, b0, a1, b1;
+        int8_codes(x0, alpha, beta, a0, b0);
+        int8_codes(x1, alpha, beta, a1, b1);
+        c1 = ((uint32_t)a0 & 0xFFu) | (((uint32_t)a1 & 0xFFu) << 8);
+        c2 = ((uint32_t)b0 & 0xFFu) | (((uint32_t)b1 & 0xFFu) << 8);
+      }
+      if (split == 0 && p.tap_q1) {
+        reinterpret_cast<uint16_t*>(p.tap_q1 + qrow * kD)[lane] = (uint16_t)c1;
+        reinterpret_cast<uint16_t*>(p.tap_q2 + qrow * kD)[lane] = (uint16_t)c2;
+        if (lane == 0) p.tap_alpha[qrow] = alpha;
+      }
+    }
+    reinterpret_cast<uint16_t*>(sQ + (int64_t)h * kD)[lane] = (uint16_t)c1;
+    reinterpret_cast<uint16_t*>(sQ + (int64_t)(nh_total + h) * kD)[lane] = (uint16_t)c2;
+    if (lane == 0) sAlpha[h] = alpha;
+  }
+  __syncthreads();
+
+  // A-fragment row of this lane (as an operand lane: row = j, k group = g)
+  const int slot = j & 3;
+  const bool row_valid = (HPL == 2) || (slot < 2);
+  const int row_head = (j >> 2) * HPL + (HPL == 2 ? (slot >> 1) : 0);  // head within the fragment
+  const int row_comp = (HPL == 2) ? (slot & 1) : slot;
+  const v4i zero4 = {0, 0, 0, 0};
+  const float sm_scale = kLog2e / sqrtf((float)kD);  // scores are kept in log2 units
+
   for (int h0 = 0; h0 < (MULTI ? G : 1); h0 += NH) {  // one pass over the KV range per NH heads
   v4i qa[NF][2];
 #pragma unroll
@@ -157,7 +173,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_decode_kernel(AttnParams
 #pragma unroll
       for (int c = 0; c < 8; ++c) o_run[f][hh][c] = 0.f;
     }
-  if (t_first < t_end) load_tile(t_first, kfn, vrn, skn, svn);
+  if (h0 > 0 && t_first < t_end) load_tile(t_first, kfn, vrn, skn, svn);  // (the first pass: before the prologue)
   for (int64_t t0 = t_first; t0 < t_end; t0 += kAttnWaves * kTile) {
     bool live[4];
 #pragma unroll
