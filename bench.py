@@ -118,7 +118,7 @@ def main():
                     choices=["", "w8_prefill", "w4_prefill", "attn", "attn4k", "mla16", "mla128", "w4_m1", "w4_m32",
                              "probe_w8", "probe_w8_const", "probe_w4"],
                     help="for rocprofv3 --pmc runs: three eager calls of one shape (W8A16 2048x8192x8192, W4A16 "
-                         "4096 / 1 / 32 x 8192 x 28672, attention L=32768 / 4096, latent-cache attention with 16 heads "
+                         "4096 / 1 / 32 x 8192 x 28672 (both on packed weights), attention L=32768 / 4096, latent-cache attention with 16 heads "
                          "at L=32768 or 128 heads at L=4096, the MFMA-only probes of the two prefill kernels with random "
                          "or constant operands), nothing else; no timing")
     ap.add_argument("--with-copy", action="store_true",
@@ -161,7 +161,8 @@ def main():
                 x = torch.ones_like(x)
                 W = torch.ones_like(W)
             if args.counter_probe == "w8_prefill":
-                call = lambda: msd.msd_gemm_w8a16(x, W, sc)
+                Wp = msd.msd_pack_weights_w8(W)  # the layout the timed runs use
+                call = lambda: msd.msd_gemm_w8a16_packed(x, Wp, sc)
             else:
                 call = lambda: msd.msd_probe_mfma_w8a16(x, W, sc)
         elif args.counter_probe in ("w4_prefill", "w4_m1", "w4_m32", "probe_w4"):
@@ -173,7 +174,8 @@ def main():
             if args.counter_probe == "probe_w4":
                 call = lambda: msd.msd_probe_mfma_w4a16(x, codes, exps)
             else:
-                call = lambda: msd.msd_gemm_w4a16(x, codes, exps)
+                Wp4, Ep4 = msd.msd_pack_weights_w4(codes, exps)  # the layout the timed runs use
+                call = lambda: msd.msd_gemm_w4a16_packed(x, Wp4, Ep4, N)
         elif args.counter_probe in ("mla16", "mla128"):
             B, Hq, L = (32, 16, 32768) if args.counter_probe == "mla16" else (32, 128, 4096)
             q = dev_bf16(synth.queries(synth.seed_for(9, Hq), B, Hq, 576))
@@ -310,6 +312,7 @@ def main():
 
     per_shape = []
     stream_us = {}
+    linear_us = {}
     for (M, N) in shapes:
         reps, s = weights[N]
 
@@ -322,6 +325,10 @@ def main():
             # what this GPU charges for the stream alone at this size
             stream_us[N] = time_calls(lambda i, reps=reps: msd.msd_stream_read(reps[i % len(reps)], prepare=True),
                                       2 * len(reps))
+            # and as one linear array (contiguous kilobytes per wave instruction, 16 in flight per lane): the
+            # pattern the packed layout is read in
+            linear_us[N] = time_calls(lambda i, reps=reps: msd.msd_stream_read_linear(reps[i % len(reps)], prepare=True),
+                                      2 * len(reps))
         # the same call on one weight copy over and over (cache-resident weights), labelled warm
         warm = time_calls(lambda i, M=M, N=N: gemm(M, N, 0), 16)
         b = w8_bytes(M, K, N)
@@ -331,7 +338,8 @@ def main():
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
                           "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2),
                           "bare_weight_read_us": round(stream_us[N], 2),
-                          "bare_read_over_call": round(stream_us[N] / us, 3)})
+                          "bare_linear_read_us": round(linear_us[N], 2),
+                          "bare_read_over_call": round(min(stream_us[N], linear_us[N]) / us, 3)})
     # measured streaming-read rate of this GPU: a bare read of 1 GiB (four launches of 256 MiB, cold)
     big = torch.empty((4, 65536, 4096), dtype=torch.uint8, device=dev)
     big.fill_(1)
@@ -365,7 +373,8 @@ def main():
                 "traffic_source": traffic_note,
                 "algorithmic_bytes": w8_bytes(dom["M"], K, dom["N"]),
                 "measured_stream_read_GBps": round(measured_stream_GBps, 1),
-                "bare_weight_read_us_same_shape": dom["bare_weight_read_us"]}
+                "bare_weight_read_us_same_shape": dom["bare_weight_read_us"],
+                "bare_linear_read_us_same_shape": dom["bare_linear_read_us"]}
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (

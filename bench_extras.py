@@ -133,12 +133,17 @@ def leg_w4(msd, synth, time_calls, dev):
                 def __call__(self):
                     for p_ in self.ps: p_()
             bare_us = time_calls(lambda i: _Both(rd(i)), 2 * len(reps))
+            # the same number of bytes as one linear array in one launch (cold copies of a plain buffer)
+            lin = [torch.empty(wbytes, dtype=torch.uint8, device=dev).fill_(i_) for i_ in range(len(reps))]
+            bare_lin_us = time_calls(lambda i: msd.msd_stream_read_linear(lin[i % len(lin)], prepare=True), 2 * len(lin))
+            del lin
         rec = {"M": M, "K": K, "N": N, "us": round(us, 1), "weights": "packed", "canonical_weights_us": round(us_canon, 1),
                "GBps": round(b / us / 1e3, 1),
                "hbm_frac": round(b / us / 1e3 / HBM, 4), "exec_TFLOPS": round(4.0 * M * K * N / us / 1e6, 1),
                "fp4_mfma_frac": round(4.0 * M * K * N / us / 1e6 / FP4_TFLOPS, 4)}
         if M <= 32:
             rec["bare_weight_read_us"] = round(bare_us, 1)
+            rec["bare_linear_read_us"] = round(bare_lin_us, 1)
         else:  # the matrix pipe alone on the same shape and data
             try:
                 h = lambda i: msd.msd_probe_mfma_w4a16(x, *reps[i % len(reps)], y=y, ws=ws)

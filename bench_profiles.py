@@ -80,7 +80,7 @@ def do_trace():
     rows = list(csv.DictReader(open(find_csv(d, "kernel_trace.csv"))))
     g = collections.defaultdict(list)
     for r in rows:
-        if "msd::" not in r["Kernel_Name"]:
+        if "msd::" not in r["Kernel_Name"] or "pack_weights" in r["Kernel_Name"]:
             continue
         g[(short(r["Kernel_Name"]), int(r["Grid_Size_X"]) * int(r.get("Grid_Size_Y", 1) or 1), r["Workgroup_Size_X"],
            r["VGPR_Count"], r["LDS_Block_Size"], r["Scratch_Size"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
@@ -113,7 +113,8 @@ def do_trace():
 
 # ------------------------------------------------------------------ HBM traffic
 def counter_rows(d):
-    return list(csv.DictReader(open(find_csv(d, "counter_collection.csv"))))
+    """dispatches of the counter run, without the one-time weight repack kernels of the set-up"""
+    return [r for r in csv.DictReader(open(find_csv(d, "counter_collection.csv"))) if "pack_weights" not in r["Kernel_Name"]]
 
 
 def calib(rows):
@@ -132,7 +133,8 @@ def do_traffic():
          "      rocprofv3 --pmc C -d gpurun_out/pmc_C_W -o p --output-format csv -- python3 bench.py --traffic-probe\n",
          "      rocprofv3 --pmc C ... -- python3 bench.py --counter-probe W --with-copy   (W = w4_m1, w4_m32, w8_prefill, w4_prefill, attn4k, attn)\n",
          stamp(),
-         "Every probe first runs one 1 GiB device-to-device copy: the counters read in KiB per dispatch up to a constant\n",
+         "The decode shapes and the W8 / W4 probes run on weights packed once at set-up (msd_pack_weights_w8 / _w4; those\n",
+         "dispatches are left out).  Every probe first runs one 1 GiB device-to-device copy: the counters read in KiB per dispatch up to a constant\n",
          "factor that the copy (1048576 KiB read, 1048576 KiB written) fixes.  Then three eager calls of each shape; values\n",
          "are the median over the three dispatches of a kernel, scaled to bytes.\n\n"]
     F = counter_rows(run_pass("pmc_fetch_decode", ["--pmc", "FETCH_SIZE"], ["--traffic-probe"]))
@@ -215,10 +217,10 @@ def do_counters(workloads=None):
            "    four passes each (8 SQ counters | 8 SQ counters | TCC_HIT_sum TCC_MISS_sum | GRBM_GUI_ACTIVE GRBM_COUNT):\n",
            "      rocprofv3 --pmc <counters> -d gpurun_out/pmcx_W_i -o p --output-format csv -- python3 bench.py --counter-probe W\n",
            stamp(),
-           "bench.py --counter-probe W runs three eager calls of one shape: w8_prefill = msd_gemm_w8a16 2048x8192x8192;\n",
+           "bench.py --counter-probe W runs three eager calls of one shape: w8_prefill = msd_gemm_w8a16_packed 2048x8192x8192;\n",
            "probe_w8 / probe_w8_const = msd_probe_mfma_w8a16 on the same shape (the prefill kernel's MFMA sequence, tile schedule\n",
            "and epilogue with no tile fill, no barrier, no LDS traffic after the first K step) with the benchmark's random operands\n",
-           "resp. all-ones operands; w4_prefill = msd_gemm_w4a16 4096x8192x28672, probe_w4 its MFMA-only probe; w4_m1 / w4_m32 the\n",
+           "resp. all-ones operands; w4_prefill = msd_gemm_w4a16_packed 4096x8192x28672, probe_w4 its MFMA-only probe; w4_m1 / w4_m32 the\n",
            "same weights with 1 / 32 rows; attn / attn4k = msd_attn_decode_int8kv B=16, 32/8 heads, d=128, L=32768 / 4096;\n",
            "mla16 / mla128 = msd_mla_decode_int8kv B=32 with 16 heads at L=32768 / 128 heads at L=4096.\n",
            "Values are the median over the three dispatches of a kernel.  Derived: kernel cycles = GRBM_GUI_ACTIVE / 8 (the\n",

@@ -391,6 +391,14 @@ int msd_dequant_gemm_w4a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx
 int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stream);
 
 /*
+ * Measurement aid (not a step of the method; no paper passage).  Reads `bytes` bytes at src (device, 16-byte
+ * aligned, bytes a multiple of 16) once as a linear array -- every wave instruction one contiguous kilobyte, the
+ * pattern of the packed weight layouts, sixteen instructions in flight per lane -- and computes and writes nothing.
+ * bench.py times it next to the calls on packed weights.  Errors: MSD_ERR_INVALID_ARG, MSD_ERR_SHAPE, MSD_ERR_HIP.
+ */
+int msd_stream_read_linear(const void* src, int64_t bytes, void* stream);
+
+/*
  * Measurement aid (not a step of the method; no paper passage).  Same arguments and the same
  * launches as msd_gemm_w8a16 on its many-row kernel (decomposition, then the 256x256-tile GEMM),
  * except that after the first K step the GEMM kernel stops fetching and keeps multiplying that

@@ -96,6 +96,8 @@ def lib():
         L.msd_attn_decode_int8kv_workspace_bytes.argtypes = [ci, ci, ci, ci, i64]
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
+        L.msd_stream_read_linear.argtypes = [vp, i64, vp]
+        L.msd_stream_read_linear.restype = ci
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
                      "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
@@ -392,6 +394,14 @@ def msd_stream_read(t, prepare=False):
     assert t.is_cuda and t.dim() == 2 and t.is_contiguous() and t.element_size() == 1
     args = (_ptr(t), t.shape[0], t.shape[1], _stream())
     call = Prepared(lib().msd_stream_read, args, (t,), "msd_stream_read", None)
+    return call if prepare else call()
+
+
+def msd_stream_read_linear(t, prepare=False):
+    """Measurement aid: bare linear read of the contiguous byte tensor t (a multiple of 16 bytes)."""
+    assert t.is_cuda and t.is_contiguous() and t.element_size() == 1
+    args = (_ptr(t), t.numel(), _stream())
+    call = Prepared(lib().msd_stream_read_linear, args, (t,), "msd_stream_read_linear", None)
     return call if prepare else call()
 
 

@@ -211,5 +211,6 @@ int launch_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, int8_t* packed
 
 // ---- measurement aid (stream_probe.hip)
 int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream);
+int launch_stream_read_linear(const void* src, int64_t bytes, hipStream_t stream);
 
 }  // namespace msd

@@ -647,4 +647,11 @@ int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stre
   return launch_stream_read(src, rows, row_bytes, (hipStream_t)stream);
 }
 
+int msd_stream_read_linear(const void* src, int64_t bytes, void* stream) {
+  if (bytes < 0 || bytes % 16 != 0 || bytes >= ((int64_t)1 << 46)) return MSD_ERR_SHAPE;
+  if (bytes == 0) return MSD_OK;
+  if (!src || !aligned_to(src, 16)) return MSD_ERR_INVALID_ARG;
+  return launch_stream_read_linear(src, bytes, (hipStream_t)stream);
+}
+
 }  // extern "C"
