@@ -223,6 +223,9 @@ def test_measurement_aids_run(msd):
     W = torch.randint(-127, 128, (300, 512), dtype=torch.int8, device="cuda")
     W0 = W.clone()
     msd.msd_stream_read(W)
+    msd.msd_stream_read_linear(W)                        # 153600 bytes: two workgroups and a ragged tail
+    msd.msd_stream_read_linear(W.view(-1)[:48])
+    assert msd.lib().msd_stream_read_linear(W.data_ptr(), 40, None) == -2   # not a multiple of 16
     x = bf16_to_dev(synth.activations(5, 300, 512))
     s = torch.rand(300, device="cuda")
     y = msd.msd_probe_mfma_w8a16(x, W, s)
