@@ -301,7 +301,7 @@ size_t msd_attn_decode_int8kv_workspace_bytes(int B, int Hq, int Hkv, int d, int
 
 /*
  * msd_attn_decode_int8kv with the low-precision arithmetic the paper lists among its optimisation
- * opportunities (Sec. 4.4: the decomposition and the S / O merging "in FP16 or even INT16 instead of FP32") for
+ * opportunities (Sec. 4.4: the decomposition and the S / O merging in 16-bit arithmetic in place of fp32) for
  * variant = MSD_VARIANT_ATTN_LOWPREC; variant = MSD_VARIANT_MAIN is msd_attn_decode_int8kv itself.  What changes:
  *   - S = beta_Q * (254 S1 + S2) / sqrt(d) (times s_K[t]): the merge as one exact integer multiply-add, one
  *     conversion, one fp32 multiply (alpha_Q S1 + beta_Q S2 = beta_Q (254 S1 + S2) exactly);

@@ -400,8 +400,8 @@ static float f16_rne(float x) {
 }
 
 /* Low-precision variant of the attention arithmetic (Sec. 4.4, "optimisation opportunities": the decomposition
- * (round, clamp) and the S / O merging (scale, add) "in FP16 or even INT16 instead of FP32").  The paper gives
- * one sentence; the reading taken here (lowprec != 0):
+ * (round, clamp) and the S / O merging (scale, add) in 16-bit floating-point or integer arithmetic in place of
+ * fp32).  The paper gives one sentence; the reading taken here (lowprec != 0):
  *   S merge    : alpha_Q S1 + beta_Q S2 = beta_Q (254 S1 + S2) exactly, so the merge is the exact integer
  *                z = 254 S1 + S2 (|z| < 2^30), ONE conversion to fp32 and ONE fp32 multiply by
  *                c_t = (beta_Q * sm_scale) * s_K[t] (both products in fp32).  Integer arithmetic replaces the
