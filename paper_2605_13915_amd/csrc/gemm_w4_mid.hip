@@ -21,6 +21,8 @@
 // bytes each -- measured 55 us (cacheable) to 68 us (non-temporal) at M = 32, N = 28672, K = 8192,
 // against 44 us with staging, and against 78 us for the skinny kernel, which re-reads the activation
 // operands for every 16 channels.
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace msd {
@@ -224,6 +226,155 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   }
 }
 
+// ------------------------------------------------------------------ up to 32 rows on packed weights
+// The packed layout (msd_pack_weights_w4) holds the B operand of the 32x32x64 instruction as two contiguous
+// 512-byte runs per wave and K step (the halves of the kilobytes of two adjacent channel tiles), so the weights go
+// HBM -> registers in operand order with no LDS stage: a wave keeps three batches of eight K steps (24 KB) in
+// flight in four rotating register sets while it multiplies the fourth.  The activation operands (shared by the
+// four waves, hot in L2) still go through LDS, double-buffered, one barrier per batch.
+constexpr int kMidpU = 8;          // K steps per batch
+constexpr int kMidpSets = 4;       // weight register sets (batches b .. b+3)
+constexpr int kMidpStepA = 3072;   // operand bytes of the 32-row group per K step
+constexpr int kMidpBufA = kMidpU * (kMidpStepA + 256);
+constexpr int kMidpStageA = kMidpU * kMidpStepA / 16 / kMidThreads;  // 16-byte operand chunks per thread and batch
+static_assert(kMidpStageA * kMidThreads * 16 == kMidpU * kMidpStepA, "operand staging split");
+
+__global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t* __restrict__ qop,
+                                                                   const uint8_t* __restrict__ sa_t,
+                                                                   const uint8_t* __restrict__ Wp,
+                                                                   const uint8_t* __restrict__ Ep, void* y,
+                                                                   int out_bf16, int64_t ldy, int M, int64_t K,
+                                                                   int64_t N, int shift) {
+  constexpr int U = kMidpU;
+  extern __shared__ __attribute__((aligned(16))) uint8_t s_midp[];  // [2][A batch]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, kb = lane >> 5;
+  const int64_t n0 = (int64_t)blockIdx.x * kMidBN;
+  const int64_t n = n0 + wave * 32 + l32;
+  const int64_t wtiles = (N + 15) / 16, wq = wtiles * 1024;
+  const int64_t nc = min(n, N - 1);  // channels past N repeat the last one; their results are not stored
+  // this lane's 16 bytes of K step ks: unit ks / 2, half ks % 2 of the kilobyte of its channel tile
+  const uint8_t* wl = Wp + (nc / 16) * 1024 + (kb * 16 + (nc & 15)) * 16;
+  const uint8_t* el = Ep + (nc / 16) * 256 + (nc & 15) * 16;  // + batch * wtiles * 256: the 16 scale bytes of the batch
+  const int NB = (int)(K / (64 * U));
+  struct WSet {
+    v4i w[U], sc;
+  };
+  struct ASet {
+    v4i a[kMidpStageA], asc;
+  };
+  WSet w0, w1, w2, w3;
+  ASet as;  // one staging set: batch b + 1 is fetched at the start of phase b and written to LDS at its end
+  as.asc = v4i{0, 0, 0, 0};
+  auto load_w = [&](int b, WSet& ws) __attribute__((always_inline)) {
+    const uint8_t* src = wl + (int64_t)b * (U / 2) * wq;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      ws.w[u] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(src + (int64_t)(u >> 1) * wq + (u & 1) * 512));
+    ws.sc = *reinterpret_cast<const v4i*>(el + (int64_t)b * wtiles * 256);
+  };
+  auto load_a = [&](int b) __attribute__((always_inline)) {
+    const uint8_t* src = qop + (int64_t)b * (U * kMidpStepA);  // the batch's operands are contiguous
+#pragma unroll
+    for (int i = 0; i < kMidpStageA; ++i) as.a[i] = *reinterpret_cast<const v4i*>(src + (tid + i * kMidThreads) * 16);
+    if (tid < U * 16)
+      as.asc = *reinterpret_cast<const v4i*>(sa_t + ((int64_t)b * U + (tid >> 4)) * 512 + (tid & 15) * 16);
+  };
+  auto store_a = [&](int buf) __attribute__((always_inline)) {
+    uint8_t* sa = s_midp + buf * kMidpBufA;
+#pragma unroll
+    for (int i = 0; i < kMidpStageA; ++i) *reinterpret_cast<v4i*>(sa + (tid + i * kMidThreads) * 16) = as.a[i];
+    if (tid < U * 16) *reinterpret_cast<v4i*>(sa + U * kMidpStepA + tid * 16) = as.asc;
+  };
+  v16f acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  // One wave per SIMD: nothing hides an LDS read but the wave's own MFMAs, so the fragments of K step u + 2 are
+  // requested before the MFMAs of step u (three rotating fragment sets); left alone the compiler requests all 32
+  // reads of a batch up front, and the 96 registers that takes push the weight sets out of the VGPRs.
+  struct Frag {
+    v8i av[2];
+    int sa;
+  };
+  auto multiply = [&](int buf, const WSet& ws) __attribute__((always_inline)) {
+    const uint8_t* sa_buf = s_midp + buf * kMidpBufA;
+    auto read_frag = [&](int u, Frag& f) __attribute__((always_inline)) {
+      const uint8_t* rec = sa_buf + u * kMidpStepA;
+#pragma unroll
+      for (int comp = 0; comp < 2; ++comp) {
+        const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
+        const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
+        f.av[comp] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      }
+      // the step's row scales: byte 0 of the dword is the scale of row l32 (block kb)
+      f.sa = *reinterpret_cast<const int*>(sa_buf + U * kMidpStepA + u * 256 + kb * 128 + l32 * 4);
+    };
+    Frag f[3];
+    read_frag(0, f[0]);
+    read_frag(1, f[1]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (u + 2 < U) read_frag(u + 2, f[(u + 2) % 3]);
+      __builtin_amdgcn_sched_barrier(0);
+      const Frag& c = f[u % 3];
+      const int sa2 = c.sa - shift * 0x01010101;  // beta = alpha / 2^shift (the bytes are >= 4)
+      const uint32_t sw = (uint32_t)(u < 2 ? ws.sc[0] : u < 4 ? ws.sc[1] : u < 6 ? ws.sc[2] : ws.sc[3]);
+      const int sb = (int)((sw >> (16 * (u & 1) + 8 * kb)) & 0xFFu);  // scale byte of block 2u + kb of the batch
+      const v8i bw = {ws.w[u][0], ws.w[u][1], ws.w[u][2], ws.w[u][3], 0, 0, 0, 0};
+      acc = mfma_mid<0, 2>(c.av[0], bw, acc, c.sa, sb);
+      acc = mfma_mid<0, 2>(c.av[1], bw, acc, sa2, sb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // batch b: weights in register set b % 4, operands in LDS buffer b % 2
+  load_a(0);
+  load_w(0, w0);
+  if (NB > 1) load_w(1, w1);
+  if (NB > 2) load_w(2, w2);
+  store_a(0);
+  __syncthreads();
+  // (The load conditions stay in: a steady-state loop peeled into straight-line code made the compiler hoist a
+  // whole batch of loads and spill 1.2 KB per lane.)
+  auto phase = [&](int b, WSet& cur, WSet& far, int buf) __attribute__((always_inline)) {
+    // operands first: loads complete in order, and the operands are needed at the end of this phase, the weights
+    // three phases from now
+    if (b + 1 < NB) load_a(b + 1);
+    if (b + 3 < NB) load_w(b + 3, far);  // the set of batch b - 1, multiplied in the previous phase
+    multiply(buf, cur);
+    if (b + 1 < NB) store_a(buf ^ 1);    // everyone left that buffer at the last barrier
+    __syncthreads();
+  };
+  for (int b = 0; b < NB; b += 4) {
+    phase(b, w0, w3, 0);
+    if (b + 1 < NB) phase(b + 1, w1, w0, 1);
+    if (b + 2 < NB) phase(b + 2, w2, w1, 0);
+    if (b + 3 < NB) phase(b + 3, w3, w2, 1);
+  }
+  // D: column l%32, row 8*(r/4) + 4*(l/32) + r%4 in register r
+  if (n < N) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = 8 * (r >> 2) + 4 * kb + (r & 3);
+      if (m < M) {
+        if (out_bf16)
+          reinterpret_cast<uint16_t*>(y)[(int64_t)m * ldy + n] = f32_to_bf16_bits(acc[r]);
+        else
+          reinterpret_cast<float*>(y)[(int64_t)m * ldy + n] = acc[r];
+      }
+    }
+  }
+}
+
+static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* Wp, const uint8_t* Ep, void* y,
+                       int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
+  constexpr int lds = 2 * kMidpBufA;
+  hipLaunchKernelGGL(gemm_w4_midp_kernel, dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), lds, stream, qop, sa_t,
+                     Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 template <int RG, int U, bool A4>
 int launch_mid(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W, const uint8_t* We, void* y, int out_bf16,
                int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, int w_packed, hipStream_t stream) {
@@ -271,6 +422,7 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
     if (l.Mpad == 64) return launch_mid<2, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
     return launch_mid<4, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   }
+  if (l.Mpad == 32 && w_packed) return launch_midp(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
   if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   return launch_mid<4, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);

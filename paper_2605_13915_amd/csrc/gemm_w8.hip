@@ -1342,7 +1342,9 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   } else if (path == W8Path::kFillLarge) {
     // Eight waves (two per SIMD, 128x64 wave tiles): measured 6-10% faster than four waves with 128x128 wave
     // tiles -- twice as many waves issue fill instructions and a SIMD always has a second wave to issue from
-    // while one waits.  Three or five stages and half-size tiles (two workgroups per CU) measured no better.
+    // while one waits.  Three or five stages, half-size tiles (two workgroups per CU) and 128 bytes of K per
+    // barrier on 64x256 or 128x128 tiles (a 256x256 tile of 128-byte stages does not fit LDS three deep) measured
+    // no better.
     rc = launch_dma<128, 256, 2, 4, 4>(a, stream);
   } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
     rc = launch_mfma32<64, 64, 2, 2>(a, stream);
