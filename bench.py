@@ -111,6 +111,9 @@ def main():
                          "timed region (default), or the canonical row-major [N][K] array; the per-shape table "
                          "reports both")
     ap.add_argument("--extras", default="all", help="comma list of extra legs: cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
+    ap.add_argument("--one-layout", action="store_true",
+                    help="time the --weights layout only (kernel traces then hold one layout per kernel name); the "
+                         "other layout's fields are null")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (the calibration kernel), then "
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
@@ -319,7 +322,7 @@ def main():
         us = time_calls(lambda i, M=M, N=N: gemm(M, N, i), 2 * len(reps))
         us_min = time_calls.last["min"]
         other = "canonical" if args.weights == "packed" else "packed"
-        us_other = time_calls(lambda i, M=M, N=N: gemm(M, N, i, layout=other), 2 * len(reps))
+        us_other = None if args.one_layout else time_calls(lambda i, M=M, N=N: gemm(M, N, i, layout=other), 2 * len(reps))
         if N not in stream_us:
             # a bare read of the same weight bytes (no arithmetic, one launch), same cold-cache protocol:
             # what this GPU charges for the stream alone at this size
@@ -334,7 +337,7 @@ def main():
         b = w8_bytes(M, K, N)
         per_shape.append({"M": M, "K": K, "N": N, "us_per_call": round(us, 2), "us_per_call_min": round(us_min, 2),
                           "warm_us_per_call": round(warm, 2), "weights": args.weights,
-                          other + "_weights_us_per_call": round(us_other, 2),
+                          other + "_weights_us_per_call": None if us_other is None else round(us_other, 2),
                           "GBps": round(b / us / 1e3, 1), "hbm_frac": round(b / us / 1e3 / HBM_PEAK_GBS, 3),
                           "exec_TOPS": round(4.0 * M * K * N / us / 1e6, 2),
                           "bare_weight_read_us": round(stream_us[N], 2),

@@ -59,9 +59,18 @@ def stamp():
     return "kernel_sources_sha256_16=%s\n" % kernel_sources_sha()
 
 
+def write_summary(name, text):
+    """profiles/<name>, and a copy under gpurun_out/profiles/ (the scratch folder is the one that travels back from
+    a remote GPU machine)"""
+    for d in (PROF, os.path.join(OUT, "profiles")):
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, name), "w") as fh:
+            fh.write(text)
+
+
 # ------------------------------------------------------------------ kernel trace of the headline run
 def do_trace():
-    d = run_pass("prof_bench", ["--kernel-trace", "--stats"], ["--extras", "none", "--no-cpu-baseline"], limit=400)
+    d = run_pass("prof_bench", ["--kernel-trace", "--stats"], ["--extras", "none", "--no-cpu-baseline", "--one-layout"], limit=400)
     line = None
     with open(os.path.join(OUT, "prof_bench.log")) as fh:
         for ln in fh:
@@ -71,10 +80,11 @@ def do_trace():
            "===================================================\n",
            "Command (from the repository root, on one MI355X):  python3 bench_profiles.py trace\n",
            "  = rocprofv3 --kernel-trace --stats -d gpurun_out/prof_bench -o p --output-format csv -- \\\n",
-           "        python3 bench.py --extras none --no-cpu-baseline        (cwd /tmp, TMPDIR=/tmp)\n", stamp(),
+           "        python3 bench.py --extras none --no-cpu-baseline --one-layout        (cwd /tmp, TMPDIR=/tmp)\n", stamp(),
            "Workload: bench.py's headline step (8 W8A16 decode shapes, M in {1,8,32,128}, K=4096, N in {4096,14336}),\n",
            "warm-up + timed steps replayed from HIP graphs, then the per-shape timing graphs (cold and warm weights,\n",
-           "bare weight reads, decomposition alone).  The trace records the kernels inside graph replays.\n\n",
+           "bare weight reads, decomposition alone), all on weights packed once at set-up (the repack dispatches are left\n",
+           "out).  The trace records the kernels inside graph replays.\n\n",
            "Per kernel and grid size (one template instantiation serves several shapes); columns: kernel, grid threads,\n",
            "workgroup, VGPRs, LDS bytes (static), scratch, dispatches, avg / min / median / max us:\n"]
     rows = list(csv.DictReader(open(find_csv(d, "kernel_trace.csv"))))
@@ -106,8 +116,7 @@ def do_trace():
         if dk:
             out.append("Its decomposition launch (grid %d) averages %.2f us in the trace; add the GEMM kernel of that shape from the\n"
                        "table above to compare with the event time per call.\n" % (m * 256, dk[0]))
-    with open(os.path.join(PROF, "w8a16_decode_bench_kernel_stats.txt"), "w") as fh:
-        fh.write("".join(out))
+    write_summary("w8a16_decode_bench_kernel_stats.txt", "".join(out))
     print("".join(out))
 
 
@@ -192,8 +201,7 @@ def do_traffic():
             tot += f_ + w_
             o.append("  %-10s %-52s fetch %11.0f B  write %11.0f B\n" % (w, nm, f_, w_))
         o.append("traffic %s total_bytes=%d alg_bytes=%d ratio=%.3f\n" % (w, tot, alg_of[w], tot / alg_of[w]))
-    with open(os.path.join(PROF, "w8a16_decode_hbm_traffic_pmc.txt"), "w") as fh:
-        fh.write("".join(o))
+    write_summary("w8a16_decode_hbm_traffic_pmc.txt", "".join(o))
     print("".join(o))
 
 
@@ -255,8 +263,7 @@ def do_counters(workloads=None):
                           c["TCC_HIT_sum"] / max(c["TCC_HIT_sum"] + c["TCC_MISS_sum"], 1),
                           c["SQ_LDS_BANK_CONFLICT"] / max(c["SQ_LDS_IDX_ACTIVE"], 1)))
         out.append("\n")
-        with open(os.path.join(PROF, "prefill_attn_counters_pmc.txt"), "w") as fh:  # written as it grows
-            fh.write("".join(out))
+        write_summary("prefill_attn_counters_pmc.txt", "".join(out))  # written as it grows
     print("".join(out))
 
 
