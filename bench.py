@@ -110,7 +110,7 @@ def main():
                     help="weight layout of the timed decode step: packed once by msd_pack_weights_w8 before the "
                          "timed region (default), or the canonical row-major [N][K] array; the per-shape table "
                          "reports both")
-    ap.add_argument("--extras", default="all", help="comma list of extra legs: cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
+    ap.add_argument("--extras", default="all", help="comma list of extra legs: mfma_rate,cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
     ap.add_argument("--one-layout", action="store_true",
                     help="time the --weights layout only (kernel traces then hold one layout per kernel name); the "
                          "other layout's fields are null")
@@ -119,11 +119,12 @@ def main():
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
     ap.add_argument("--counter-probe", default="",
                     choices=["", "w8_prefill", "w4_prefill", "attn", "attn4k", "mla16", "mla128", "w4_m1", "w4_m32",
-                             "probe_w8", "probe_w8_const", "probe_w4"],
+                             "probe_w8", "probe_w8_const", "probe_w4", "rate_w8", "rate_w8_const", "rate_w4", "rate_w4_const"],
                     help="for rocprofv3 --pmc runs: three eager calls of one shape (W8A16 2048x8192x8192, W4A16 "
                          "4096 / 1 / 32 x 8192 x 28672 (both on packed weights), attention L=32768 / 4096, latent-cache attention with 16 heads "
                          "at L=32768 or 128 heads at L=4096, the MFMA-only probes of the two prefill kernels with random "
-                         "or constant operands), nothing else; no timing")
+                         "or constant operands, the matrix-instruction-only kernel msd_probe_mfma_rate on random or constant "
+                         "bits), nothing else; no timing")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --counter-probe: first one 1 GiB device copy, the calibration kernel of the "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -155,7 +156,15 @@ def main():
             torch.cuda.synchronize()
             del src, dst
             torch.cuda.empty_cache()
-        if args.counter_probe in ("w8_prefill", "probe_w8", "probe_w8_const"):
+        if args.counter_probe.startswith("rate_"):
+            # the matrix pipe alone (msd_probe_mfma_rate) on random or constant operand bits
+            if args.counter_probe.endswith("_const"):
+                buf = torch.full((16384,), 0x01010101, dtype=torch.int32, device=dev)
+            else:
+                buf = torch.randint(-2 ** 31, 2 ** 31 - 1, (16384,), dtype=torch.int32, device=dev, generator=g)
+            fmt = msd.MSD_MXFP4 if "w4" in args.counter_probe else msd.MSD_INT8
+            call = lambda: msd.msd_probe_mfma_rate(fmt, buf, 4000)
+        elif args.counter_probe in ("w8_prefill", "probe_w8", "probe_w8_const"):
             M, K, N = 2048, 8192, 8192
             x = dev_bf16(synth.activations(synth.seed_for(2, 0), M, K, outliers=True))
             W = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev, generator=g)
@@ -381,7 +390,7 @@ def main():
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
-        {"cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe", "mla"} if args.extras == "all" else set())
+        {"mfma_rate", "cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe", "mla"} if args.extras == "all" else set())
     try:
         import bench_extras
         extras = bench_extras.run(want, msd, synth, time_calls, dev)
@@ -439,6 +448,13 @@ def main():
         per_config["cfg4_attention"] = [
             {"L": r["L"], "us": r["us"], "bound": "hbm", "frac": r["hbm_frac"], "vs_dequant": r["speedup_vs_dequant"],
              "per_channel_us": r["per_channel"]["us"], "lowprec_us": r.get("lowprec_us")} for r in ex["attn"]]
+    if isinstance(ex.get("mfma_rate"), dict) and "error" not in ex["mfma_rate"]:
+        # the matrix pipe alone on random and on constant operand bits (msd_probe_mfma_rate): the ceiling of the
+        # MFMA-bound rows on this machine is the random-bits figure, not the datasheet peak
+        per_config["matrix_pipe_alone"] = {k: {"random_bits_Tops": v["random_bits"]["Tops"],
+                                               "constant_bits_Tops": v["constant_bits"]["Tops"],
+                                               "random_bits_frac_of_datasheet": v["random_bits"]["frac_of_datasheet"]}
+                                           for k, v in ex["mfma_rate"].items()}
     roofline["per_config"] = per_config
 
     cpu = None

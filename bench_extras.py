@@ -352,6 +352,36 @@ def leg_moe(msd, synth, time_calls, dev):
     return out
 
 
+def leg_mfma_rate(msd, synth, time_calls, dev):
+    """The matrix pipe alone (msd_probe_mfma_rate: nothing but matrix instructions, operands read once) on random
+    operand bits, the benchmark's kind of data, and on constant ones: same instruction stream, same cycles per
+    instruction; what differs is the clock the chip sustains.  The random-bits figure is the ceiling of any GEMM
+    kernel on this machine for such data."""
+    out = {}
+    g = torch.Generator(device=dev)
+    g.manual_seed(11)
+    rnd = torch.randint(-2 ** 31, 2 ** 31 - 1, (16384,), dtype=torch.int32, device=dev, generator=g)
+    ones = torch.full((16384,), 0x01010101, dtype=torch.int32, device=dev)
+    for name, fmt, peak, iters in (("int8_32x32x32", msd.MSD_INT8, INT8_TOPS, 20000), ("fp6xfp4_32x32x64", msd.MSD_MXFP4, FP4_TFLOPS, 20000)):
+        rec = {}
+        for label, buf in (("random_bits", rnd), ("constant_bits", ones)):
+            msd.msd_probe_mfma_rate(fmt, buf, 100)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(3):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ops = msd.msd_probe_mfma_rate(fmt, buf, iters)
+                e1.record()
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e-3)
+            t = sorted(ts)[1]
+            rec[label] = {"ms": round(t * 1e3, 3), "Tops": round(ops / t / 1e12, 1), "frac_of_datasheet": round(ops / t / 1e12 / peak, 3)}
+        out[name] = rec
+    return out
+
+
 def leg_cfg0(msd, synth, time_calls, dev):
     """The correctness configuration (M = 16, K = 1024, N = 1024, 1 MB of weights): launch-latency scale,
     time only, MSD and comparison kernel."""
@@ -484,7 +514,7 @@ def leg_variants(msd, synth, time_calls, dev):
 
 def run(want, msd, synth, time_calls, dev):
     res = {}
-    legs = {"cfg0": leg_cfg0, "prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
+    legs = {"mfma_rate": leg_mfma_rate, "cfg0": leg_cfg0, "prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
             "variants": leg_variants, "nq": leg_nq_sweep, "moe": leg_moe, "mla": leg_mla}
     for name, fn in legs.items():
         if name in want:

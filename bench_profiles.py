@@ -212,8 +212,8 @@ PASSES = [["SQ_WAVE_CYCLES", "SQ_BUSY_CYCLES", "SQ_WAIT_INST_ANY", "SQ_WAIT_ANY"
            "SQ_ACTIVE_INST_SCA", "SQ_INSTS_VMEM_RD"],
           ["TCC_HIT_sum", "TCC_MISS_sum"],
           ["GRBM_GUI_ACTIVE", "GRBM_COUNT"]]
-WORKLOADS = ["w8_prefill", "probe_w8", "probe_w8_const", "w4_prefill", "probe_w4", "w4_m1", "w4_m32", "attn", "attn4k", "mla16",
-             "mla128"]
+WORKLOADS = ["rate_w8", "rate_w8_const", "rate_w4", "rate_w4_const", "w8_prefill", "probe_w8", "probe_w8_const", "w4_prefill",
+             "probe_w4", "w4_m1", "w4_m32", "attn", "attn4k", "mla16", "mla128"]
 
 
 def do_counters(workloads=None):
@@ -225,6 +225,9 @@ def do_counters(workloads=None):
            "    four passes each (8 SQ counters | 8 SQ counters | TCC_HIT_sum TCC_MISS_sum | GRBM_GUI_ACTIVE GRBM_COUNT):\n",
            "      rocprofv3 --pmc <counters> -d gpurun_out/pmcx_W_i -o p --output-format csv -- python3 bench.py --counter-probe W\n",
            stamp(),
+           "rate_w8 / rate_w8_const / rate_w4 / rate_w4_const = msd_probe_mfma_rate, 2048 waves x 32000 matrix instructions\n",
+           "(INT8 32x32x32 resp. FP6 x FP4 32x32x64) on random resp. constant operand bits and nothing else: equal cycle\n",
+           "counts, while bench.py's mfma_rate leg times the random-bits run 1.4x longer -- the clock under load differs.\n",
            "bench.py --counter-probe W runs three eager calls of one shape: w8_prefill = msd_gemm_w8a16_packed 2048x8192x8192;\n",
            "probe_w8 / probe_w8_const = msd_probe_mfma_w8a16 on the same shape (the prefill kernel's MFMA sequence, tile schedule\n",
            "and epilogue with no tile fill, no barrier, no LDS traffic after the first K step) with the benchmark's random operands\n",

@@ -399,6 +399,17 @@ int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stre
 int msd_stream_read_linear(const void* src, int64_t bytes, void* stream);
 
 /*
+ * Measurement aid (not a step of the method; no paper passage).  The rate of the matrix pipe on given operand
+ * bits, with no data movement: 2048 waves (eight per CU) each read six operand fragments once from `operands`
+ * (device, 64 KB, 16-byte aligned) and issue 8 * iters matrix instructions on them into eight accumulators --
+ * fmt = MSD_INT8: v_mfma_i32_32x32x32_i8 (2 * 32768 operations each), fmt = MSD_MXFP4: the FP6 x FP4
+ * block-scaled 32x32x64 instruction (2 * 65536 each), the instructions of the many-row GEMM kernels.  Timed by
+ * bench.py with random and with constant buffers: the instruction rate in cycles is the same, the clock the chip
+ * sustains under the load is not.  iters in [0, 2^22].  Errors: MSD_ERR_INVALID_ARG, MSD_ERR_SHAPE, MSD_ERR_HIP.
+ */
+int msd_probe_mfma_rate(int fmt, const void* operands, int iters, void* stream);
+
+/*
  * Measurement aid (not a step of the method; no paper passage).  Same arguments and the same
  * launches as msd_gemm_w8a16 on its many-row kernel (decomposition, then the 256x256-tile GEMM),
  * except that after the first K step the GEMM kernel stops fetching and keeps multiplying that

@@ -97,6 +97,8 @@ def lib():
         L.msd_attn_decode_int8kv_workspace_bytes.restype = sz
         L.msd_stream_read.argtypes = [vp, i64, i64, vp]
         L.msd_stream_read_linear.argtypes = [vp, i64, vp]
+        L.msd_probe_mfma_rate.argtypes = [ci, vp, ci, vp]
+        L.msd_probe_mfma_rate.restype = ci
         L.msd_stream_read_linear.restype = ci
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
@@ -395,6 +397,14 @@ def msd_stream_read(t, prepare=False):
     args = (_ptr(t), t.shape[0], t.shape[1], _stream())
     call = Prepared(lib().msd_stream_read, args, (t,), "msd_stream_read", None)
     return call if prepare else call()
+
+
+def msd_probe_mfma_rate(fmt, operands, iters):
+    """Measurement aid: 2048 waves x 8 * iters matrix instructions on the operand bits in the 64 KB tensor `operands`;
+    returns the number of scalar operations issued (2 per multiply-add)."""
+    assert operands.is_cuda and operands.is_contiguous() and operands.numel() * operands.element_size() >= 65536
+    _check(lib().msd_probe_mfma_rate(int(fmt), _ptr(operands), int(iters), _stream()), "msd_probe_mfma_rate")
+    return 2048 * 8 * int(iters) * 2 * (65536 if fmt == MSD_MXFP4 else 32768)
 
 
 def msd_stream_read_linear(t, prepare=False):

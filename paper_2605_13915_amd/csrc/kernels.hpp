@@ -212,5 +212,7 @@ int launch_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, int8_t* packed
 // ---- measurement aid (stream_probe.hip)
 int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream);
 int launch_stream_read_linear(const void* src, int64_t bytes, hipStream_t stream);
+// 1024 workgroups of two waves, each issuing 8 * iters matrix instructions on operands read once from a 64 KB buffer
+int launch_mfma_rate(int fp4, const void* operands, int iters, hipStream_t stream);
 
 }  // namespace msd

@@ -647,6 +647,13 @@ int msd_stream_read(const void* src, int64_t rows, int64_t row_bytes, void* stre
   return launch_stream_read(src, rows, row_bytes, (hipStream_t)stream);
 }
 
+int msd_probe_mfma_rate(int fmt, const void* operands, int iters, void* stream) {
+  if (fmt != MSD_INT8 && fmt != MSD_MXFP4) return MSD_ERR_INVALID_ARG;
+  if (iters < 0 || iters > (1 << 22)) return MSD_ERR_SHAPE;
+  if (!operands || !aligned_to(operands, 16)) return MSD_ERR_INVALID_ARG;
+  return launch_mfma_rate(fmt == MSD_MXFP4, operands, iters, (hipStream_t)stream);
+}
+
 int msd_stream_read_linear(const void* src, int64_t bytes, void* stream) {
   if (bytes < 0 || bytes % 16 != 0 || bytes >= ((int64_t)1 << 46)) return MSD_ERR_SHAPE;
   if (bytes == 0) return MSD_OK;

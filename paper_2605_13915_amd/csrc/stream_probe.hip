@@ -54,6 +54,74 @@ int launch_stream_read_linear(const void* src, int64_t bytes, hipStream_t stream
   return MSD_OK;
 }
 
+// ------------------------------------------------------------------ matrix-pipe rate
+// Nothing but matrix instructions: every wave loads four A and two B operand fragments (16 bytes per lane each; 24
+// bytes for the FP6 A fragments) from `operands` once and then issues `iters` rounds of the eight products
+// A_i x B_j into eight independent accumulators -- the instruction pattern of the many-row GEMM kernels with no
+// data movement at all.  What it measures is how fast the matrix pipe runs ON THESE OPERAND BITS: the
+// instruction rate in cycles is fixed, the clock the chip sustains under the load is not.
+typedef int v16i_probe __attribute__((ext_vector_type(16)));
+typedef float v16f_probe __attribute__((ext_vector_type(16)));
+template <bool FP4>
+__global__ __launch_bounds__(128) void mfma_rate_kernel(const int* __restrict__ operands, int iters) {
+  const v4i* src = reinterpret_cast<const v4i*>(operands);
+  v4i A[4], A2[4], B[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    A[i] = src[(threadIdx.x * 10 + i) & 4095];
+    A2[i] = src[(threadIdx.x * 10 + 6 + i) & 4095];
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) B[j] = src[(threadIdx.x * 10 + 4 + j) & 4095];
+  int sink = 0;
+  if constexpr (FP4) {
+    v16f_probe acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const v8i a8 = {A[i][0], A[i][1], A[i][2], A[i][3], A2[i][0], A2[i][1], 0, 0};
+          const v8i b8 = {B[j][0], B[j][1], B[j][2], B[j][3], 0, 0, 0, 0};
+          // FP6 x FP4, scale bytes 2^0 (every bit pattern of both element formats is a finite number)
+          acc[i * 2 + j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc[i * 2 + j], 2, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sink += (int)acc[i][0];
+  } else {
+    v16i_probe acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i * 2 + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[i], B[j], acc[i * 2 + j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sink += acc[i][0];
+  }
+  if (sink == 0x5EEDBEEF && iters < 0) g_stream_probe_sink = sink;  // keeps the products alive; never true
+}
+
+int launch_mfma_rate(int fp4, const void* operands, int iters, hipStream_t stream) {
+  const dim3 grid(1024), block(128);  // eight waves per CU, two per SIMD
+  if (fp4)
+    hipLaunchKernelGGL(mfma_rate_kernel<true>, grid, block, 0, stream, (const int*)operands, iters);
+  else
+    hipLaunchKernelGGL(mfma_rate_kernel<false>, grid, block, 0, stream, (const int*)operands, iters);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream) {
   if (rows == 0 || row_bytes == 0) return MSD_OK;
   hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)cdiv(rows, 16)), dim3(256), 0, stream,

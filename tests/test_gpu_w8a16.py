@@ -226,6 +226,10 @@ def test_measurement_aids_run(msd):
     msd.msd_stream_read_linear(W)                        # 153600 bytes: two workgroups and a ragged tail
     msd.msd_stream_read_linear(W.view(-1)[:48])
     assert msd.lib().msd_stream_read_linear(W.data_ptr(), 40, None) == -2   # not a multiple of 16
+    ops = torch.randint(-2 ** 31, 2 ** 31 - 1, (16384,), dtype=torch.int32, device="cuda")
+    assert msd.msd_probe_mfma_rate(msd.MSD_INT8, ops, 3) == 2048 * 8 * 3 * 65536
+    assert msd.msd_probe_mfma_rate(msd.MSD_MXFP4, ops, 0) == 0
+    assert msd.lib().msd_probe_mfma_rate(7, ops.data_ptr(), 1, None) == -1
     x = bf16_to_dev(synth.activations(5, 300, 512))
     s = torch.rand(300, device="cuda")
     y = msd.msd_probe_mfma_w8a16(x, W, s)
