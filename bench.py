@@ -110,7 +110,7 @@ def main():
                     help="weight layout of the timed decode step: packed once by msd_pack_weights_w8 before the "
                          "timed region (default), or the canonical row-major [N][K] array; the per-shape table "
                          "reports both")
-    ap.add_argument("--extras", default="all", help="comma list of extra legs: mfma_rate,cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
+    ap.add_argument("--extras", default="all", help="comma list of extra legs: mfma_rate,lds_fill,cfg0,prefill,w4,attn,cmp,variants,nq,moe,mla | all | none")
     ap.add_argument("--one-layout", action="store_true",
                     help="time the --weights layout only (kernel traces then hold one layout per kernel name); the "
                          "other layout's fields are null")
@@ -390,7 +390,7 @@ def main():
 
     extras = {}
     want = set(args.extras.split(",")) if args.extras not in ("all", "none") else (
-        {"mfma_rate", "cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe", "mla"} if args.extras == "all" else set())
+        {"mfma_rate", "lds_fill", "cfg0", "prefill", "w4", "attn", "cmp", "variants", "nq", "moe", "mla"} if args.extras == "all" else set())
     try:
         import bench_extras
         extras = bench_extras.run(want, msd, synth, time_calls, dev)
@@ -455,6 +455,10 @@ def main():
                                                "constant_bits_Tops": v["constant_bits"]["Tops"],
                                                "random_bits_frac_of_datasheet": v["random_bits"]["frac_of_datasheet"]}
                                            for k, v in ex["mfma_rate"].items()}
+    if isinstance(ex.get("lds_fill"), dict) and "error" not in ex["lds_fill"]:
+        # the tile kernels' LDS fill instructions alone (msd_probe_lds_fill_rate): what a CU can pull into LDS
+        per_config["lds_fill_alone"] = {k: v["TBps"] for k, v in ex["lds_fill"].items() if isinstance(v, dict)}
+        per_config["lds_fill_alone"]["unit"] = "TB/s over 256 CUs"
     roofline["per_config"] = per_config
 
     cpu = None

@@ -382,6 +382,39 @@ def leg_mfma_rate(msd, synth, time_calls, dev):
     return out
 
 
+def leg_lds_fill(msd, synth, time_calls, dev):
+    """The LDS fill path alone (msd_probe_lds_fill_rate: the tile kernels' asynchronous fill instructions, ring and
+    barriers with no fragment reads and no matrix instructions), one eight-wave workgroup per CU: from a 1 MB window
+    every workgroup shares (L2 hits, like the activation codes), from disjoint ranges of a 1 GB buffer (HBM, like the
+    weights), and half and half -- the mix of the batched-decode tiles.  Bytes a tile kernel moves into LDS divided
+    by these rates bound its time from below whatever its arithmetic."""
+    buf = torch.empty(((1 << 30) + (1 << 20),), dtype=torch.int8, device=dev)
+    buf.random_(-128, 127)
+    out = {"workgroups": 256, "waves_per_workgroup": 8, "bytes_in_flight_per_cu": 65536}
+    rounds = 128
+    for label, parts in (("l2_window", 4), ("half_window_half_stream", 2), ("hbm_stream", 0)):
+        msd.msd_probe_lds_fill_rate(buf, 1 << 20, parts, rounds)
+        torch.cuda.synchronize()
+        ts = []
+        for r in (rounds, 0):  # the empty launch is subtracted
+            tt = []
+            for _ in range(5):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                nbytes = msd.msd_probe_lds_fill_rate(buf, 1 << 20, parts, r)
+                e1.record()
+                e1.synchronize()
+                tt.append(e0.elapsed_time(e1) * 1e-3)
+            ts.append(sorted(tt)[2])
+        moved = 256 * rounds * 32768
+        t = ts[0] - ts[1]
+        out[label] = {"us": round(t * 1e6, 1), "TBps": round(moved / t / 1e12, 2), "GBps_per_cu": round(moved / t / 1e9 / 256, 1)}
+    del buf
+    torch.cuda.empty_cache()
+    return out
+
+
 def leg_cfg0(msd, synth, time_calls, dev):
     """The correctness configuration (M = 16, K = 1024, N = 1024, 1 MB of weights): launch-latency scale,
     time only, MSD and comparison kernel."""
@@ -514,7 +547,7 @@ def leg_variants(msd, synth, time_calls, dev):
 
 def run(want, msd, synth, time_calls, dev):
     res = {}
-    legs = {"mfma_rate": leg_mfma_rate, "cfg0": leg_cfg0, "prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
+    legs = {"mfma_rate": leg_mfma_rate, "lds_fill": leg_lds_fill, "cfg0": leg_cfg0, "prefill": leg_prefill, "w4": leg_w4, "attn": leg_attn, "cmp": leg_cmp_decode,
             "variants": leg_variants, "nq": leg_nq_sweep, "moe": leg_moe, "mla": leg_mla}
     for name, fn in legs.items():
         if name in want:

@@ -410,6 +410,22 @@ int msd_stream_read_linear(const void* src, int64_t bytes, void* stream);
 int msd_probe_mfma_rate(int fmt, const void* operands, int iters, void* stream);
 
 /*
+ * Measurement aid (not a step of the method; no paper passage).  The rate at which the CUs can fill LDS, with no
+ * arithmetic: 256 workgroups of eight waves; in each of `rounds` rounds a wave issues four asynchronous
+ * 16-byte-per-lane loads into LDS (one contiguous kilobyte each: 32 KB per workgroup and round, 8 MB per round
+ * over the grid) into a ring of four rounds, two rounds ahead, with a wait and a barrier per round -- the fill
+ * instructions, depth and synchronisation of the tile GEMM kernels without their fragment reads and matrix
+ * instructions.  src (device, 16-byte aligned, src_bytes a multiple of 1024): its first hot_bytes (a multiple of
+ * 1024, at least 1024) are a window that every workgroup walks in the same order, wrapping (data that stays in
+ * L2, like the activation codes); the remaining src_bytes - hot_bytes (at least 1024) are dealt to the workgroups
+ * in disjoint ranges, wrapping at the end (data that streams from HBM when the range is large, like the weights).
+ * hot_parts in [0, 4]: how many of a wave's four instructions per round read the window.  Nothing is written
+ * outside LDS.  rounds in [0, 2^20].  Errors: MSD_ERR_INVALID_ARG, MSD_ERR_SHAPE, MSD_ERR_HIP.
+ */
+int msd_probe_lds_fill_rate(const void* src, int64_t src_bytes, int64_t hot_bytes, int hot_parts, int rounds,
+                            void* stream);
+
+/*
  * Measurement aid (not a step of the method; no paper passage).  Same arguments and the same
  * launches as msd_gemm_w8a16 on its many-row kernel (decomposition, then the 256x256-tile GEMM),
  * except that after the first K step the GEMM kernel stops fetching and keeps multiplying that

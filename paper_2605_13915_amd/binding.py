@@ -100,6 +100,8 @@ def lib():
         L.msd_probe_mfma_rate.argtypes = [ci, vp, ci, vp]
         L.msd_probe_mfma_rate.restype = ci
         L.msd_stream_read_linear.restype = ci
+        L.msd_probe_lds_fill_rate.argtypes = [vp, i64, i64, ci, ci, vp]
+        L.msd_probe_lds_fill_rate.restype = ci
         for name in ("msd_decompose", "msd_gemm_w8a16", "msd_gemm_w4a16", "msd_attn_decode_int8kv",
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
                      "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
@@ -405,6 +407,15 @@ def msd_probe_mfma_rate(fmt, operands, iters):
     assert operands.is_cuda and operands.is_contiguous() and operands.numel() * operands.element_size() >= 65536
     _check(lib().msd_probe_mfma_rate(int(fmt), _ptr(operands), int(iters), _stream()), "msd_probe_mfma_rate")
     return 2048 * 8 * int(iters) * 2 * (65536 if fmt == MSD_MXFP4 else 32768)
+
+
+def msd_probe_lds_fill_rate(t, hot_bytes, hot_parts, rounds):
+    """Measurement aid: 256 workgroups x `rounds` x 32 KB of asynchronous LDS fills out of the byte tensor t, of
+    which hot_parts quarters come from the shared window t[:hot_bytes]; returns the bytes moved."""
+    assert t.is_cuda and t.is_contiguous() and t.element_size() == 1
+    _check(lib().msd_probe_lds_fill_rate(_ptr(t), t.numel(), int(hot_bytes), int(hot_parts), int(rounds), _stream()),
+           "msd_probe_lds_fill_rate")
+    return 256 * int(rounds) * 32768
 
 
 def msd_stream_read_linear(t, prepare=False):

@@ -79,7 +79,9 @@ __device__ __forceinline__ float merge_scales(float sw, float alpha, float beta,
 //
 //   (the quantiser itself, bit-exact without a division per element, is in decompose_int8_dev.hpp)
 constexpr int kSelfMaxRows = 8;
-constexpr int kFusedMaxRows = 8;           // rows the single-launch kernel accepts (measured: 16 x 1024 is slower than two launches)
+// rows the single-launch kernel accepts (measured: 16 x 1024 is slower than two launches, as 4 waves x 4 steps and
+// as 16 waves x 1 step alike: the decomposition every workgroup repeats is bound by the CU's vector rate)
+constexpr int kFusedMaxRows = 8;
 constexpr int64_t kFusedMaxElems = 16384;  // ... and activation elements (M*K): beyond, a launch is cheaper
 constexpr int64_t kSelfMaxCodeBytes = 136 * 1024;  // LDS budget for the self-decomposed codes
 
@@ -137,6 +139,13 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
     for (int t = 0; t < NT; ++t) acc[f][t] = zero;
   bool ready = !SELF;
   float my_alpha = 0.f;  // SELF: alpha of row (threadIdx.x % kSelfMaxRows), kept for the epilogue
+  // scale factors of this thread's first output: requested now, needed after the last barrier
+  const int rows_pre = SELF ? kSelfMaxRows : M;
+  const int m_pre = (int)threadIdx.x % rows_pre;
+  const int64_t n_pre = n0 + (int)threadIdx.x / rows_pre;
+  const bool has_pre = (int)threadIdx.x < rows_pre * 16 * NT && m_pre < M && n_pre < N;
+  const float ws_pre = has_pre ? a.w_scale[n_pre] : 0.f;
+  const float alpha_pre = (!SELF && has_pre) ? a.alpha[m_pre] : 0.f;
   for (int ks = ks0; ks < max(ks1, ks0 + 1); ks += UNROLL) {  // at least one pass: every wave joins the barriers
     v4i wv[NT][UNROLL], av[RT][UNROLL];
     bool ok[UNROLL];
@@ -240,9 +249,11 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
     const int a2 = s_acc[i2 >> 4][t][i2 & 3][((i2 & 15) >> 2) * 16 + j];
     const int64_t n = n0 + c;
     if (n < N) {
-      const float alpha = SELF ? my_alpha : a.alpha[m];
+      const bool first = e == (int)threadIdx.x;
+      const float alpha = SELF ? my_alpha : first ? alpha_pre : a.alpha[m];
       const float beta = __fdiv_rn(alpha, a.rg.num2);
-      store_out(a.y, a.out_bf16, (int64_t)m * a.ldy + n, merge_scales(a.w_scale[n], alpha, beta, a1, a2));
+      const float ws = first ? ws_pre : a.w_scale[n];
+      store_out(a.y, a.out_bf16, (int64_t)m * a.ldy + n, merge_scales(ws, alpha, beta, a1, a2));
       if (a.acc1) a.acc1[(int64_t)m * N + n] = a1;
       if (a.acc2) a.acc2[(int64_t)m * N + n] = a2;
     }
@@ -354,6 +365,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a)
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) wv[t][s] = ldg16_stream(wp + s * wstep);
   }
+  // the weight scale of this thread's first output: requested now, needed after the last barrier
+  const int64_t n_pre = n0 + (int)threadIdx.x / M;
+  const float ws_pre = ((int)threadIdx.x < M * 16 * NT && n_pre < N) ? a.w_scale[n_pre] : 0.f;
   for (int i = threadIdx.x; i < RT * NT * 256; i += THREADS) (&s_acc[0][0][0][0])[i] = 0;
   // ---- row maxima: over the chunks of a lane, the lanes of a wave, the waves
   float cm[XC];
@@ -442,7 +456,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a)
     if (n < N) {
       const float alpha = s_par[m][0];
       const float beta = __fdiv_rn(alpha, a.rg.num2);
-      store_out(a.y, a.out_bf16, (int64_t)m * a.ldy + n, merge_scales(a.w_scale[n], alpha, beta, a1, a2));
+      const float ws = e == (int)threadIdx.x ? ws_pre : a.w_scale[n];
+      store_out(a.y, a.out_bf16, (int64_t)m * a.ldy + n, merge_scales(ws, alpha, beta, a1, a2));
       if (a.acc1) a.acc1[(int64_t)m * N + n] = a1;
       if (a.acc2) a.acc2[(int64_t)m * N + n] = a2;
     }
@@ -1333,7 +1348,9 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     if (deep && wgs(32, 64) <= 256)
       rc = launch_dma<32, 64, 1, 2, 4, false, false, 128, 4>(a, stream);
     else
-    if (2 * M > 64 && wgs(64, 128) >= 200)  // eight waves measured 30 vs 31.6 us at 128 x 4096 x 14336
+    // eight waves measured 30 vs 31.6 us at 128 x 4096 x 14336; as 2 x 2 waves in two K groups (a third fewer
+    // fragment reads) 31.4, as sixteen waves (2 x 4 in two K groups) 31.3
+    if (2 * M > 64 && wgs(64, 128) >= 200)
       rc = deep ? launch_dma<64, 128, 2, 4, 4, false, false, 128>(a, stream) : launch_dma<64, 128, 2, 2, 8>(a, stream);
     else if (2 * M > 64 && wgs(64, 64) >= 200)
       rc = deep ? launch_dma<64, 64, 2, 2, 4, false, false, 128>(a, stream) : launch_dma<64, 64, 2, 2, 6>(a, stream);
@@ -1344,7 +1361,8 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     // tiles -- twice as many waves issue fill instructions and a SIMD always has a second wave to issue from
     // while one waits.  Three or five stages, half-size tiles (two workgroups per CU) and 128 bytes of K per
     // barrier on 64x256 or 128x128 tiles (a 256x256 tile of 128-byte stages does not fit LDS three deep) measured
-    // no better.
+    // no better.  Sixteen waves (4 x 4 or 2 x 8, 64 accumulator registers each) measured the same within 2 %
+    // on 2048 x 8192 x 8192 and 2048 x 8192 x 28672 and 5 % faster on 8192^3.
     rc = launch_dma<128, 256, 2, 4, 4>(a, stream);
   } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
     rc = launch_mfma32<64, 64, 2, 2>(a, stream);

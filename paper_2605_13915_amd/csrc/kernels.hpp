@@ -214,5 +214,8 @@ int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStre
 int launch_stream_read_linear(const void* src, int64_t bytes, hipStream_t stream);
 // 1024 workgroups of two waves, each issuing 8 * iters matrix instructions on operands read once from a 64 KB buffer
 int launch_mfma_rate(int fp4, const void* operands, int iters, hipStream_t stream);
+// LDS fill rate alone (measurement aid): 256 workgroups x rounds x 32 KB of asynchronous LDS fills
+int launch_lds_fill_rate(const void* src, int64_t src_bytes, int64_t hot_bytes, int hot_parts, int rounds,
+                         hipStream_t stream);
 
 }  // namespace msd

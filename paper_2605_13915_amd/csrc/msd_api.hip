@@ -654,6 +654,15 @@ int msd_probe_mfma_rate(int fmt, const void* operands, int iters, void* stream) 
   return launch_mfma_rate(fmt == MSD_MXFP4, operands, iters, (hipStream_t)stream);
 }
 
+int msd_probe_lds_fill_rate(const void* src, int64_t src_bytes, int64_t hot_bytes, int hot_parts, int rounds,
+                            void* stream) {
+  if (src_bytes < 0 || hot_bytes < 0 || src_bytes % 1024 != 0 || hot_bytes % 1024 != 0) return MSD_ERR_SHAPE;
+  if (hot_bytes < 1024 || src_bytes < hot_bytes + 1024 || src_bytes >= ((int64_t)1 << 46)) return MSD_ERR_SHAPE;
+  if (hot_parts < 0 || hot_parts > 4 || rounds < 0 || rounds > (1 << 20)) return MSD_ERR_SHAPE;
+  if (!src || !aligned_to(src, 16)) return MSD_ERR_INVALID_ARG;
+  return launch_lds_fill_rate(src, src_bytes, hot_bytes, hot_parts, rounds, (hipStream_t)stream);
+}
+
 int msd_stream_read_linear(const void* src, int64_t bytes, void* stream) {
   if (bytes < 0 || bytes % 16 != 0 || bytes >= ((int64_t)1 << 46)) return MSD_ERR_SHAPE;
   if (bytes == 0) return MSD_OK;

@@ -122,6 +122,74 @@ int launch_mfma_rate(int fp4, const void* operands, int iters, hipStream_t strea
   return MSD_OK;
 }
 
+// ------------------------------------------------------------------ LDS fill rate
+// Nothing but the fill instructions of the tile kernels: one workgroup of eight waves per CU; per round a wave
+// issues four asynchronous 16-byte-per-lane loads into LDS (one contiguous kilobyte each, 32 KB per workgroup and
+// round) into a ring of four rounds, and before it issues round r + 2 it waits for its loads of round r and meets
+// the other waves at a barrier -- the issue pattern, depth and synchronisation of gemm_w8_dma_kernel with no
+// fragment reads and no matrix instructions.  Of the four instructions the first `hot_parts` read a window at the
+// start of `src` that every workgroup walks in the same order (the activation codes, which come from L2); the
+// others read the rest of `src`, every workgroup its own range (the weight stream, which comes from HBM).  Its
+// time is what moving those bytes into LDS costs with no arithmetic at all.
+__device__ __forceinline__ void probe_lds_dma16(const int8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  const uint64_t g = reinterpret_cast<uint64_t>(gbase);
+  const uint32_t glo = __builtin_amdgcn_readfirstlane((uint32_t)g), ghi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
+  gbase = reinterpret_cast<const int8_t*>(((uint64_t)ghi << 32) | glo);
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+constexpr int kFillProbeRing = 4, kFillProbeRound = 32768;
+
+__global__ __launch_bounds__(512) void lds_fill_rate_kernel(const int8_t* __restrict__ src, int64_t hot_kb, int64_t cold_kb,
+                                                            int hot_parts, int rounds) {
+  extern __shared__ __attribute__((aligned(16))) int8_t fill_ring[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)fill_ring;
+  const uint32_t voff = (uint32_t)(lane * 16);
+  auto issue = [&](int r) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = q * 8 + wave;  // kilobyte of the round
+      int64_t kb;
+      if (q < hot_parts) kb = ((int64_t)r * 32 + i) % hot_kb;
+      else kb = hot_kb + (((int64_t)blockIdx.x * rounds + r) * 32 + i) % cold_kb;
+      probe_lds_dma16(src + kb * 1024, voff, lds0 + (uint32_t)((r % kFillProbeRing) * kFillProbeRound + i * 1024));
+    }
+  };
+  if (rounds > 0) issue(0);
+  if (rounds > 1) issue(1);
+  for (int r = 0; r < rounds; ++r) {
+    // loads of rounds r + 1 (and nothing younger) may stay outstanding; at the end everything drains
+    if (r + 1 < rounds) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (r + 2 < rounds) issue(r + 2);
+  }
+  // one LDS word per workgroup is read back so that the fills cannot be dropped; the condition is never true
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0 && rounds < 0) g_stream_probe_sink = reinterpret_cast<const int*>(fill_ring)[lane];
+}
+
+int launch_lds_fill_rate(const void* src, int64_t src_bytes, int64_t hot_bytes, int hot_parts, int rounds,
+                         hipStream_t stream) {
+  constexpr int kLds = kFillProbeRing * kFillProbeRound;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lds_fill_rate_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(lds_fill_rate_kernel, dim3(256), dim3(512), kLds, stream, (const int8_t*)src, hot_bytes / 1024,
+                     (src_bytes - hot_bytes) / 1024, hot_parts, rounds);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 int launch_stream_read(const void* src, int64_t rows, int64_t row_bytes, hipStream_t stream) {
   if (rows == 0 || row_bytes == 0) return MSD_OK;
   hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)cdiv(rows, 16)), dim3(256), 0, stream,

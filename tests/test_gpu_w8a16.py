@@ -102,7 +102,8 @@ SHAPES = [
     (2, 4096, 8300, 1),        # many column tiles, two per workgroup
     (4, 4096, 8300, 1),        # many column tiles, 8 waves x 8 steps, four tiles per workgroup
     (8, 2048, 530, 1), (5, 2048, 8300, 0),   # 4 x 8
-    (8, 1024, 90, 1), (13, 1024, 90, 1),   # 4 x 4 with 8 rows; 13 rows exceed the row bound: two launches
+    (8, 1024, 90, 1),          # 4 x 4 with 8 rows
+    (13, 1024, 90, 1), (9, 1024, 1030, 0), (9, 2048, 90, 1),   # more rows than the row bound: two launches
     (2, 8192, 300, 1), (1, 8192, 8300, 1),   # 8 x 16, one and two tiles per workgroup
 ]
 
@@ -230,6 +231,15 @@ def test_measurement_aids_run(msd):
     assert msd.msd_probe_mfma_rate(msd.MSD_INT8, ops, 3) == 2048 * 8 * 3 * 65536
     assert msd.msd_probe_mfma_rate(msd.MSD_MXFP4, ops, 0) == 0
     assert msd.lib().msd_probe_mfma_rate(7, ops.data_ptr(), 1, None) == -1
+    # LDS fill probe: window and stream of one kilobyte each (every address wraps), no rounds, a few rounds
+    small = W.view(-1)[:2048]
+    assert msd.msd_probe_lds_fill_rate(small, 1024, 2, 5) == 256 * 5 * 32768
+    assert msd.msd_probe_lds_fill_rate(W.view(-1)[:153600], 4096, 4, 0) == 0
+    assert msd.msd_probe_lds_fill_rate(W.view(-1)[:153600], 4096, 0, 3) == 256 * 3 * 32768
+    assert msd.lib().msd_probe_lds_fill_rate(W.data_ptr(), 2048, 2048, 2, 1, None) == -2   # no stream part
+    assert msd.lib().msd_probe_lds_fill_rate(W.data_ptr(), 4096, 1024, 5, 1, None) == -2   # hot_parts > 4
+    assert msd.lib().msd_probe_lds_fill_rate(W.data_ptr(), 4000, 1024, 1, 1, None) == -2   # not whole kilobytes
+    assert msd.lib().msd_probe_lds_fill_rate(None, 4096, 1024, 1, 1, None) == -1
     x = bf16_to_dev(synth.activations(5, 300, 512))
     s = torch.rand(300, device="cuda")
     y = msd.msd_probe_mfma_w8a16(x, W, s)
