@@ -26,6 +26,7 @@
 //   scales:      512 B for the rows, 512 B for the columns, layout as in sa_t.
 #include "decompose_mxfp4_dev.hpp"
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace msd {
 
@@ -153,6 +154,21 @@ __device__ __forceinline__ void w4_lds_dma16(const uint8_t* gbase, uint32_t voff
                : "memory", "m0");
 }
 
+// The same instruction issued by lanes 0..7 only (128 bytes): the other lanes are switched off inside the
+// statement, so the caller's code stays free of branches.
+__device__ __forceinline__ void w4_lds_dma16_lanes8(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  const uint64_t g = reinterpret_cast<uint64_t>(gbase);
+  const uint32_t glo = __builtin_amdgcn_readfirstlane((uint32_t)g), ghi = __builtin_amdgcn_readfirstlane((uint32_t)(g >> 32));
+  gbase = reinterpret_cast<const uint8_t*>(((uint64_t)ghi << 32) | glo);
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  uint64_t saved;
+  asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0"
+               : "=&s"(saved)
+               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
 template <int N>
 __device__ __forceinline__ void w4_wait_vm_barrier() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
@@ -173,9 +189,9 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   constexpr int CA = GA / 2;            // of one component
   constexpr int SZ_A = 8 * GA, SZ_W = 8192, STAGE = SZ_A + SZ_W + 1024;
   constexpr int QA = SZ_A / 8192;       // activation fill instructions per wave and stage
-  constexpr int L = QA + 1;             // data load instructions per wave and stage (wave 0 issues one more: scales)
+  constexpr int L = QA + 2;             // load instructions per wave and stage: QA activation, 1 weight, 1 scale piece
   constexpr int CBSZ = A4 ? 4 : 2;
-  static_assert(NS >= 3 && (NS - 2) * (L + 1) < 64, "stage count");
+  static_assert(NS >= 3 && (NS - 2) * L < 64, "stage count");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem4p[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -215,24 +231,30 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   const uint32_t voff_w =
       a.w_packed ? (uint32_t)((min(n0 / 16 + 2 * wave + (l32 >> 4), wtiles - 1) - n0 / 16) * 1024 + (kb * 16 + (l32 & 15)) * 16)
                  : (uint32_t)((min(n0 + 32 * wave + l32, N - 1) - n0) * row_w + kb * 16);
+  // bytes from one pair of K steps to the next, and from the even to the odd step of a pair (no branch on the layout
+  // inside the K loop)
+  const int64_t w_pair = a.w_packed ? wq : 64;
+  const int w_odd = a.w_packed ? 512 : 32;
   const uint32_t voff_a = (uint32_t)(lane * 16);
-  // scale bytes of a stage: lanes 0..31 fetch the 512 bytes of sa_t[kt][tm], lanes 32..63 those of sw_t[kt][tn]
-  const uint8_t* sbase = kb ? a.sw_t : a.sa_t;                                     // per lane
-  const uint64_t s_first = (uint64_t)(sbase - a.ws) + (kb ? n0 : m0) * 2 + 16 * l32;  // byte offset from a.ws
-  const uint64_t s_inc = (uint64_t)(kb ? a.Npad : a.Mpad) * 2;                     // per K step
+  // scale bytes of a stage: one kilobyte, the 512 bytes of sa_t[kt][tm] then those of sw_t[kt][tn], in 64 pieces
+  // of 16 bytes; wave w fetches pieces 8w .. 8w+7 with its lanes 0..7 (waves 0..3 activation scales, 4..7 weight
+  // scales), so that every wave issues the same number of loads per stage and waits on the same count
+  const int sp = wave * 8 + (lane & 7), skb = sp >> 5, sl = sp & 31;
+  const uint8_t* sbase = skb ? a.sw_t : a.sa_t;
+  const uint64_t s_first = (uint64_t)(sbase - a.ws) + (skb ? n0 : m0) * 2 + 16 * sl;  // byte offset from a.ws
+  const uint64_t s_inc = (uint64_t)(skb ? a.Npad : a.Mpad) * 2;                    // per K step
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
     const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 8192);
     if (q < QA) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 8192, voff_a, dst);
-    else w4_lds_dma16(a.w_packed ? w_src + (int64_t)(kt >> 1) * wq + (kt & 1) * 512 : w_src + (int64_t)kt * 32, voff_w, dst);
-  };
-  auto issue_scales = [&](int kt) {
-    if (wave == 0)
-      w4_lds_dma16(a.ws, (uint32_t)(s_first + (uint64_t)kt * s_inc), lds0 + (uint32_t)((kt % NS) * STAGE) + SZ_A + SZ_W);
+    else if (q == QA)
+      w4_lds_dma16(w_src + (int64_t)(kt >> 1) * w_pair + (kt & 1) * w_odd, voff_w, dst);
+    else
+      w4_lds_dma16_lanes8(a.ws, (uint32_t)(s_first + (uint64_t)kt * s_inc),
+                          lds0 + (uint32_t)((kt % NS) * STAGE) + SZ_A + SZ_W + (uint32_t)(wave * 128));
   };
   auto issue = [&](int kt) {
 #pragma unroll
     for (int q = 0; q < L; ++q) issue_one(kt, q);
-    issue_scales(kt);
   };
 
   v16f acc[4][2];
@@ -278,34 +300,37 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   };
   // ISSUE: the load instructions of tile kt_issue go out between the MFMAs, one after every second
   // MFMA (in one burst after the barrier they fill the address queue, the waves leave the burst at
-  // different times and the next barrier pays for the skew); wave 0's scale fetch goes last.
-  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[2], int sa, int sb, int kt_issue, bool do_issue) {
-#define MSD_W4_POST(IDX)                                            \
-  if ((IDX) % 2 == 0 && (IDX) / 2 < L) {                            \
-    __builtin_amdgcn_sched_barrier(0);                              \
-    if (do_issue) issue_one(kt_issue, (IDX) / 2);                   \
-    __builtin_amdgcn_sched_barrier(0);                              \
-  }
+  // different times and the next barrier pays for the skew); the scale piece goes last.
+  // do_issue: a bool, or std::true_type where the loads are unconditional (the steady state of the K loop, which
+  // must stay one basic block: across a branch the compiler sinks the MFMAs below the fragment reads, the barrier
+  // and the loads, and nothing overlaps any more).  Loads 0..3 follow MFMAs 1, 3, 5, 7, load 4 follows MFMA 6.
+  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[2], int sa, int sb, int kt_issue, auto do_issue) {
+    auto post = [&](auto idx) {
+      constexpr int IDX = decltype(idx)::value;
+      constexpr int q = (IDX % 2 == 0) ? IDX / 2 : (IDX == 5 ? 4 : -1);
+      if constexpr (q >= 0 && q < L) {
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (std::is_same_v<decltype(do_issue), std::true_type>) {
+          issue_one(kt_issue, q);
+        } else {
+          if (do_issue) issue_one(kt_issue, q);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
 #define MSD_W4_ROW(I)                                                                      \
-  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0, CBSZ>(fa[I], fb[0], acc[I][0], sa, sb); MSD_W4_POST(2 * I - 1) } \
-  acc[I][1] = mfma64_scaled<I, 1, CBSZ>(fa[I], fb[1], acc[I][1], sa, sb); MSD_W4_POST(2 * I)
+  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0, CBSZ>(fa[I], fb[0], acc[I][0], sa, sb); post(std::integral_constant<int, 2 * I - 1>{}); } \
+  acc[I][1] = mfma64_scaled<I, 1, CBSZ>(fa[I], fb[1], acc[I][1], sa, sb); post(std::integral_constant<int, 2 * I>{});
     MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
 #undef MSD_W4_ROW
-#undef MSD_W4_POST
-    if (do_issue) issue_scales(kt_issue);
+    static_assert(L <= 5, "load slots between the eight MFMAs of a block");
   };
   // wait until tile t has landed (the tiles issued after it may stay in flight), then barrier
   auto wait_tile = [&](int t, int newest_issued) {
     const int younger = newest_issued - t;
-    if (wave == 0) {
-      if (younger == NS - 2) w4_wait_vm_barrier<(NS - 2) * (L + 1)>();
-      else if (younger == NS - 3) w4_wait_vm_barrier<(NS - 3) * (L + 1)>();
-      else w4_wait_vm_barrier<0>();
-    } else {
-      if (younger == NS - 2) w4_wait_vm_barrier<(NS - 2) * L>();
-      else if (younger == NS - 3) w4_wait_vm_barrier<(NS - 3) * L>();
-      else w4_wait_vm_barrier<0>();
-    }
+    if (younger == NS - 2) w4_wait_vm_barrier<(NS - 2) * L>();
+    else if (younger == NS - 3) w4_wait_vm_barrier<(NS - 3) * L>();
+    else w4_wait_vm_barrier<0>();
   };
 
   // Pipeline of K step s:  block 0 = component 1 ... the registers roll as follows.
@@ -317,7 +342,8 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   v8i a0[4], a1[4], b0[2], b1[2];
   int sa0 = 0, sb0 = 0, sa1 = 0, sb1 = 0;
   const int beta_shift = a.mv.shift * 0x01010101;
-  auto step = [&](int s, v8i (&bc)[2], int sac, int sbc, v8i (&bn)[2], int& san, int& sbn) {
+  auto step = [&](auto steady, int s, v8i (&bc)[2], int sac, int sbc, v8i (&bn)[2], int& san, int& sbn) {
+    constexpr bool STEADY = decltype(steady)::value;  // s + NS - 1 < KT: every condition below holds
     if constexpr (PROBE) {
       if (s > 0) {  // operands of step 0 (a1: component 1 of step 0), no data movement
         mfma_first(a0, b0, sa0, sb0);
@@ -335,16 +361,21 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     __builtin_amdgcn_sched_barrier(0);
     mfma_rest(a0, bc, sac, sbc, 0, false);
     __builtin_amdgcn_sched_barrier(0);
-    if (s + 1 < KT) wait_tile(s + 1, min(KT - 1, s + NS - 2));
+    if constexpr (STEADY) {
+      w4_wait_vm_barrier<(NS - 3) * L>();
+    } else {
+      if (s + 1 < KT) wait_tile(s + 1, min(KT - 1, s + NS - 2));
+    }
     const int sac2 = sac - beta_shift;  // beta = alpha / 2^shift: every scale byte minus shift (bytes are >= 4)
     mfma_first(a1, bc, sac2, sbc);
     __builtin_amdgcn_sched_barrier(0);
-    if (!PROBE && s + 1 < KT) {
+    if (STEADY || (!PROBE && s + 1 < KT)) {
       load_a(s + 1, 0, a0);
       load_b(s + 1, bn, san, sbn);
     }
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, !PROBE && s + 1 < KT && s - 1 + NS < KT);
+    if constexpr (STEADY) mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, std::true_type{});
+    else mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, !PROBE && s + 1 < KT && s - 1 + NS < KT);
     __builtin_amdgcn_sched_barrier(0);
   };
 #pragma unroll
@@ -355,9 +386,16 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     load_a(0, 0, a0);
     load_b(0, b0, sa0, sb0);
   }
-  for (int s = 0; s < KT; s += 2) {
-    step(s, b0, sa0, sb0, b1, sa1, sb1);
-    if (s + 1 < KT) step(s + 1, b1, sa1, sb1, b0, sa0, sb0);
+  int s = 0;
+  if constexpr (!PROBE) {
+    for (; s + NS < KT; s += 2) {  // both steps of the pair are in the steady state
+      step(std::true_type{}, s, b0, sa0, sb0, b1, sa1, sb1);
+      step(std::true_type{}, s + 1, b1, sa1, sb1, b0, sa0, sb0);
+    }
+  }
+  for (; s < KT; s += 2) {
+    step(std::false_type{}, s, b0, sa0, sb0, b1, sa1, sb1);
+    if (s + 1 < KT) step(std::false_type{}, s + 1, b1, sa1, sb1, b0, sa0, sb0);
   }
 
   // ---- epilogue: the accumulators are the output (both components and all scales are in them)
