@@ -281,16 +281,18 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     }
   };
   // weights and scale bytes of K step kt; sa / sb: byte i = scale of row fragment i / column fragment i
-  // (the column dword holds the four fragments of a 128-column half: this wave's two are moved to bytes 0, 1)
+  // (the column dword holds the four fragments of a 128-column half: this wave reads the half with its two)
   auto load_b = [&](int kt, v8i (&fb)[2], int& sa, int& sb) {
     const uint8_t* st = smem4p + (kt % NS) * STAGE;
+    // the scale bytes first and without arithmetic on them (this wave's two column bytes are one 16-bit read):
+    // whatever waits for them then waits for nothing issued after them
+    sa = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + wm * 256 + o_sc);
+    sb = (int)*reinterpret_cast<const uint16_t*>(st + SZ_A + SZ_W + 512 + (wn >> 1) * 256 + (wn & 1) * 2 + o_sc);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const uint4 v = *reinterpret_cast<const uint4*>(st + SZ_A + (wn * 2 + j) * 1024 + o_main);
       fb[j] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
     }
-    sa = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + wm * 256 + o_sc);
-    sb = (int)(*reinterpret_cast<const uint32_t*>(st + SZ_A + SZ_W + 512 + (wn >> 1) * 256 + o_sc) >> ((wn & 1) * 16));
   };
   // one component block: 8 MFMAs on 8 different accumulators; the first one is issued ahead of
   // the LDS reads that run under the block, so that the compiler's wait for this block's
@@ -370,8 +372,8 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     mfma_first(a1, bc, sac2, sbc);
     __builtin_amdgcn_sched_barrier(0);
     if (STEADY || (!PROBE && s + 1 < KT)) {
-      load_a(s + 1, 0, a0);
       load_b(s + 1, bn, san, sbn);
+      load_a(s + 1, 0, a0);
     }
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (STEADY) mfma_rest(a1, bc, sac2, sbc, s - 1 + NS, std::true_type{});
