@@ -8,16 +8,16 @@
 //       the number of cache lines an instruction touches):
 //         qop[K step][group of 32 rows][6 chunks of 512 B]
 //         chunk 3c+b = [32 rows][dwords 0..3 of block b of component c], chunk 3c+2 = [block][32 rows][dwords 4,5]
-//       and the alpha bytes as sa_t[K step][tile of 256 rows][512 B], byte wm*256 + b*128 + l*4 + i
-//       for row wm*128 + 32*i + l of the tile and block b: a lane's four row fragments read their
-//       scale bytes as one dword and pick the byte with the instruction's op_sel.
+//       and the alpha bytes as sa_t[K step][tile of 256 rows][512 B], byte h*256 + b*128 + l*4 + i
+//       for row h*128 + 32*i + l of the tile and block b: the four row fragments of a 128-row half share a
+//       dword per lane; a wave reads the bytes of its fragments and picks one with the instruction's op_sel.
 //   (2) transpose_w_scales_kernel: the weights' E8M0 bytes [N][K/32] -> sw_t in the same layout
 //       over columns (the weight values themselves are consumed where they are).
-//   (3) gemm_w4_dma_kernel: 256 x 256 output tile, 8 waves of 128 x 64, one K step = 64 elements
+//   (3) gemm_w4_dma_kernel: 256 x 256 output tile, 8 waves of 64 x 128, one K step = 64 elements
 //       = two MX blocks = exactly one MFMA K extent (lane l: row/column l%32, block l/32).  A stage
-//       is 33 KB: 24 KB activation operands, 8 KB weights, 1 KB scale bytes, filled by 33
-//       global_load_lds_dwordx4 instructions (4 per wave, wave 0 one more for the scales), NS stages
-//       deep.  Both components accumulate into the same fp32 accumulator (scale bytes alpha and
+//       is 33 KB: 24 KB activation operands, 8 KB weights, 1 KB scale bytes, filled by 40
+//       global_load_lds_dwordx4 instructions (5 per wave: three activation kilobytes, one weight kilobyte,
+//       128 bytes of the scales), NS stages deep.  Both components accumulate into the same fp32 accumulator (scale bytes alpha and
 //       alpha - 4, i.e. beta = alpha / 16), so the 256 x 256 tile needs 128 accumulator registers per lane.
 //
 // LDS layout of a stage (every fragment read is linear in the lane, hence conflict-free):
@@ -195,7 +195,10 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   extern __shared__ __attribute__((aligned(16))) uint8_t smem4p[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3;  // eight waves: 128 rows x 64 columns each
+  // eight waves, 64 rows x 128 columns each: of the shapes with 128 accumulator registers the one that reads the
+  // fewest operand bytes from LDS per K step (10 KB per wave; 128 x 64 reads 14 KB -- the 6-bit activation
+  // operands of two components are three times the bytes of the 4-bit weights)
+  const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, kb = lane >> 5;
   const int64_t M = a.M, N = a.N;
   const int KT = (int)(a.K / 64);
@@ -257,20 +260,21 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     for (int q = 0; q < L; ++q) issue_one(kt, q);
   };
 
-  v16f acc[4][2];
+  constexpr int FI = 2, FJ = 4;  // row / column fragments of a wave
+  v16f acc[FI][FJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < FI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < FJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // per-lane LDS offsets inside a stage (kb*32 + l32 == lane, so the 16-byte reads are linear in the lane)
   const uint32_t o_main = lane * 16, o_tail = lane * 8, o_sc = kb * 128 + l32 * 4;
-  auto load_a = [&](int kt, int c, v8i (&fa)[4]) {  // component c of K step kt
-    const uint8_t* st = smem4p + (kt % NS) * STAGE + wm * (4 * GA) + c * CA;
+  auto load_a = [&](int kt, int c, v8i (&fa)[FI]) {  // component c of K step kt
+    const uint8_t* st = smem4p + (kt % NS) * STAGE + wm * (FI * GA) + c * CA;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < FI; ++i) {
       const uint4 v = *reinterpret_cast<const uint4*>(st + i * GA + o_main);
       if constexpr (A4) {
         fa[i] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
@@ -281,23 +285,24 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
     }
   };
   // weights and scale bytes of K step kt; sa / sb: byte i = scale of row fragment i / column fragment i
-  // (the column dword holds the four fragments of a 128-column half: this wave reads the half with its two)
-  auto load_b = [&](int kt, v8i (&fb)[2], int& sa, int& sb) {
+  // (a scale dword holds the four fragments of a 128-row or 128-column half: the wave's two row fragments are
+  // one 16-bit read, its four column fragments the whole dword)
+  auto load_b = [&](int kt, v8i (&fb)[FJ], int& sa, int& sb) {
     const uint8_t* st = smem4p + (kt % NS) * STAGE;
     // the scale bytes first and without arithmetic on them (this wave's two column bytes are one 16-bit read):
     // whatever waits for them then waits for nothing issued after them
-    sa = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + wm * 256 + o_sc);
-    sb = (int)*reinterpret_cast<const uint16_t*>(st + SZ_A + SZ_W + 512 + (wn >> 1) * 256 + (wn & 1) * 2 + o_sc);
+    sa = (int)*reinterpret_cast<const uint16_t*>(st + SZ_A + SZ_W + (wm >> 1) * 256 + (wm & 1) * 2 + o_sc);
+    sb = *reinterpret_cast<const int*>(st + SZ_A + SZ_W + 512 + wn * 256 + o_sc);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint4 v = *reinterpret_cast<const uint4*>(st + SZ_A + (wn * 2 + j) * 1024 + o_main);
+    for (int j = 0; j < FJ; ++j) {
+      const uint4 v = *reinterpret_cast<const uint4*>(st + SZ_A + (wn * FJ + j) * 1024 + o_main);
       fb[j] = v8i{(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};
     }
   };
   // one component block: 8 MFMAs on 8 different accumulators; the first one is issued ahead of
   // the LDS reads that run under the block, so that the compiler's wait for this block's
   // operands (it cannot count LDS operations across the inline asm) covers no read just issued
-  auto mfma_first = [&](const v8i (&fa)[4], const v8i (&fb)[2], int sa, int sb) {
+  auto mfma_first = [&](const v8i (&fa)[FI], const v8i (&fb)[FJ], int sa, int sb) {
     acc[0][0] = mfma64_scaled<0, 0, CBSZ>(fa[0], fb[0], acc[0][0], sa, sb);
   };
   // ISSUE: the load instructions of tile kt_issue go out between the MFMAs, one after every second
@@ -306,7 +311,7 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // do_issue: a bool, or std::true_type where the loads are unconditional (the steady state of the K loop, which
   // must stay one basic block: across a branch the compiler sinks the MFMAs below the fragment reads, the barrier
   // and the loads, and nothing overlaps any more).  Loads 0..3 follow MFMAs 1, 3, 5, 7, load 4 follows MFMA 6.
-  auto mfma_rest = [&](const v8i (&fa)[4], const v8i (&fb)[2], int sa, int sb, int kt_issue, auto do_issue) {
+  auto mfma_rest = [&](const v8i (&fa)[FI], const v8i (&fb)[FJ], int sa, int sb, int kt_issue, auto do_issue) {
     auto post = [&](auto idx) {
       constexpr int IDX = decltype(idx)::value;
       constexpr int q = (IDX % 2 == 0) ? IDX / 2 : (IDX == 5 ? 4 : -1);
@@ -320,11 +325,12 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
         __builtin_amdgcn_sched_barrier(0);
       }
     };
-#define MSD_W4_ROW(I)                                                                      \
-  if (I > 0) { acc[I][0] = mfma64_scaled<I, 0, CBSZ>(fa[I], fb[0], acc[I][0], sa, sb); post(std::integral_constant<int, 2 * I - 1>{}); } \
-  acc[I][1] = mfma64_scaled<I, 1, CBSZ>(fa[I], fb[1], acc[I][1], sa, sb); post(std::integral_constant<int, 2 * I>{});
-    MSD_W4_ROW(0) MSD_W4_ROW(1) MSD_W4_ROW(2) MSD_W4_ROW(3)
-#undef MSD_W4_ROW
+    // MFMA number I * FJ + J multiplies row fragment I by column fragment J; number 0 is mfma_first
+#define MSD_W4_MM(I, J)                                                                  \
+  acc[I][J] = mfma64_scaled<I, J, CBSZ>(fa[I], fb[J], acc[I][J], sa, sb);                \
+  post(std::integral_constant<int, (I) * FJ + (J) - 1>{});
+    MSD_W4_MM(0, 1) MSD_W4_MM(0, 2) MSD_W4_MM(0, 3) MSD_W4_MM(1, 0) MSD_W4_MM(1, 1) MSD_W4_MM(1, 2) MSD_W4_MM(1, 3)
+#undef MSD_W4_MM
     static_assert(L <= 5, "load slots between the eight MFMAs of a block");
   };
   // wait until tile t has landed (the tiles issued after it may stay in flight), then barrier
@@ -341,10 +347,10 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   //   second block (component 1 of step s): under it the component-0 operands, the weights and
   //   the scale bytes of step s+1 are read (weights and scales are double-buffered in registers,
   //   the activation operands are not: each set is dead when its successor is fetched).
-  v8i a0[4], a1[4], b0[2], b1[2];
+  v8i a0[FI], a1[FI], b0[FJ], b1[FJ];
   int sa0 = 0, sb0 = 0, sa1 = 0, sb1 = 0;
   const int beta_shift = a.mv.shift * 0x01010101;
-  auto step = [&](auto steady, int s, v8i (&bc)[2], int sac, int sbc, v8i (&bn)[2], int& san, int& sbn) {
+  auto step = [&](auto steady, int s, v8i (&bc)[FJ], int sac, int sbc, v8i (&bn)[FJ], int& san, int& sbn) {
     constexpr bool STEADY = decltype(steady)::value;  // s + NS - 1 < KT: every condition below holds
     if constexpr (PROBE) {
       if (s > 0) {  // operands of step 0 (a1: component 1 of step 0), no data movement
@@ -402,14 +408,14 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
 
   // ---- epilogue: the accumulators are the output (both components and all scales are in them)
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < FI; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int64_t m = m0 + wm * 128 + 32 * i + (r >> 2) * 8 + kb * 4 + (r & 3);
+      const int64_t m = m0 + wm * 64 + 32 * i + (r >> 2) * 8 + kb * 4 + (r & 3);
       if (m < M) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int64_t n = n0 + wn * 64 + 32 * j + l32;
+        for (int j = 0; j < FJ; ++j) {
+          const int64_t n = n0 + wn * 128 + 32 * j + l32;
           if (n >= N) continue;
           const float v = acc[i][j][r];
           if (a.out_bf16)  // written once, not read again: streaming stores
