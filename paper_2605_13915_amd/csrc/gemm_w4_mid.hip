@@ -229,69 +229,119 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
 // ------------------------------------------------------------------ up to 32 rows on packed weights
 // The packed layout (msd_pack_weights_w4) holds the B operand of the 32x32x64 instruction as two contiguous
 // 512-byte runs per wave and K step (the halves of the kilobytes of two adjacent channel tiles), so the weights go
-// HBM -> registers in operand order with no LDS stage: a wave keeps three batches of eight K steps (24 KB) in
-// flight in four rotating register sets while it multiplies the fourth.  The activation operands (shared by the
-// four waves, hot in L2) still go through LDS, double-buffered, one barrier per batch.
+// HBM -> registers in operand order with no LDS stage, in batches of eight K steps (8 KB per wave).  The activation
+// operands (shared by the four waves, hot in L2) go through LDS.  One wave per SIMD: nothing hides an LDS read but
+// the wave's own MFMAs, so the fragments of K step u + 2 are requested before the MFMAs of step u (three rotating
+// fragment sets); left alone the compiler requests all 32 reads of a batch up front.
 constexpr int kMidpU = 8;          // K steps per batch
-constexpr int kMidpSets = 4;       // weight register sets (batches b .. b+3)
 constexpr int kMidpStepA = 3072;   // operand bytes of the 32-row group per K step
 constexpr int kMidpBufA = kMidpU * (kMidpStepA + 256);
-constexpr int kMidpStageA = kMidpU * kMidpStepA / 16 / kMidThreads;  // 16-byte operand chunks per thread and batch
-static_assert(kMidpStageA * kMidThreads * 16 == kMidpU * kMidpStepA, "operand staging split");
+constexpr int kMidpStageA = kMidpU * kMidpStepA / 1024 / (kMidThreads / 64);  // operand kilobytes per wave and batch
+constexpr int kMidpDepth = 2;      // batches in flight behind the current one (3 and 4 measured 4 % and 7 % slower)
 
+// Every vector-memory load is an asm statement and the waits are written by hand, as in the tile kernels: written
+// as plain loads with conditions on the batch number, the compiler lost count of the loads in flight at every join
+// and waited for all of them before each batch's MFMAs -- the batch requested a moment earlier included, so each
+// batch paid a memory latency (37 against 32 us at 32 x 8192 x 28672).
+//   D batches ahead of the MFMAs a wave requests the weights of a batch (nine loads into the register set the
+//   batch before the current one has left) and then its share of the batch's operands (seven LDS fills: six
+//   operand kilobytes, 512 of the 2048 scale bytes with its first 32 lanes) into one of D + 1 LDS buffers.  The
+//   issue order is W0 A0 W1 A1 ... from the first instruction on, so when phase b starts the loads younger than
+//   the operands of batch b are the D - 1 batches after it: "vmcnt((D - 1) * 16)" means weights and operands of
+//   batch b have landed; the barrier after it publishes the fills of all waves and says that every wave has left
+//   the buffer that batch b + D goes into (batch b - 1's).  Batch numbers past the end repeat the last batch (what
+//   they fetch is never used), so the count holds to the end; the kernel drains everything before its epilogue.
+__device__ __forceinline__ void midp_fill16(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ void midp_fill16_lanes32(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+  uint64_t saved;
+  asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffffffff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0"
+               : "=&s"(saved)
+               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ v4i midp_load16(const uint8_t* gbase, uint32_t voff) {
+  v4i r;
+  asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(r) : "v"(voff), "s"(gbase) : "memory");
+  return r;
+}
+__device__ __forceinline__ v4i midp_load16_512(const uint8_t* gbase, uint32_t voff) {
+  v4i r;
+  asm volatile("global_load_dwordx4 %0, %1, %2 offset:512 nt" : "=v"(r) : "v"(voff), "s"(gbase) : "memory");
+  return r;
+}
+__device__ __forceinline__ uint64_t midp_uniform(uint64_t v) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+template <int D>
 __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t* __restrict__ qop,
                                                                    const uint8_t* __restrict__ sa_t,
                                                                    const uint8_t* __restrict__ Wp,
                                                                    const uint8_t* __restrict__ Ep, void* y,
                                                                    int out_bf16, int64_t ldy, int M, int64_t K,
-                                                                   int64_t N, int shift) {
+                                                                   int64_t N, int shift, int bn) {
+  // bn: channels per workgroup, a multiple of 16, at most kMidBN (the host picks it so that the grid fills the CUs
+  // evenly); a wave still multiplies 32 channels, those past bn or N repeat the workgroup's last one
   constexpr int U = kMidpU;
-  extern __shared__ __attribute__((aligned(16))) uint8_t s_midp[];  // [2][A batch]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int NSETS = D + 1;  // register sets and LDS buffers: the current batch and D in flight
+  extern __shared__ __attribute__((aligned(16))) uint8_t s_midp[];  // [NSETS][A batch]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, kb = lane >> 5;
-  const int64_t n0 = (int64_t)blockIdx.x * kMidBN;
-  const int64_t n = n0 + wave * 32 + l32;
+  const int64_t n0 = (int64_t)blockIdx.x * bn;
+  const int64_t n_end = min(n0 + bn, N);  // this workgroup's channels are [n0, n_end)
+  const int64_t n_raw = n0 + wave * 32 + l32;
+  const int64_t n = n_raw < n_end ? n_raw : N;  // N: not stored
   const int64_t wtiles = (N + 15) / 16, wq = wtiles * 1024;
-  const int64_t nc = min(n, N - 1);  // channels past N repeat the last one; their results are not stored
+  const int64_t nc = min(n_raw, n_end - 1);  // their loads repeat an address the workgroup reads anyway
   // this lane's 16 bytes of K step ks: unit ks / 2, half ks % 2 of the kilobyte of its channel tile
-  const uint8_t* wl = Wp + (nc / 16) * 1024 + (kb * 16 + (nc & 15)) * 16;
-  const uint8_t* el = Ep + (nc / 16) * 256 + (nc & 15) * 16;  // + batch * wtiles * 256: the 16 scale bytes of the batch
+  const uint32_t w_off = (uint32_t)((nc / 16) * 1024 + (kb * 16 + (nc & 15)) * 16);
+  const uint32_t e_off = (uint32_t)((nc / 16) * 256 + (nc & 15) * 16);
   const int NB = (int)(K / (64 * U));
+  const uint32_t lds0 = (uint32_t)(uintptr_t)s_midp;
   struct WSet {
     v4i w[U], sc;
   };
-  struct ASet {
-    v4i a[kMidpStageA], asc;
-  };
-  WSet w0, w1, w2, w3;
-  ASet as;  // one staging set: batch b + 1 is fetched at the start of phase b and written to LDS at its end
-  as.asc = v4i{0, 0, 0, 0};
+  WSet w[NSETS];
   auto load_w = [&](int b, WSet& ws) __attribute__((always_inline)) {
-    const uint8_t* src = wl + (int64_t)b * (U / 2) * wq;
+    b = min(b, NB - 1);
+    const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Wp + (int64_t)b * (U / 2) * wq)));
+    const uint64_t step = midp_uniform((uint64_t)wq);
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      ws.w[u] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(src + (int64_t)(u >> 1) * wq + (u & 1) * 512));
-    ws.sc = *reinterpret_cast<const v4i*>(el + (int64_t)b * wtiles * 256);
+    for (int u = 0; u < U; u += 2) {
+      ws.w[u] = midp_load16(src + (u >> 1) * step, w_off);
+      ws.w[u + 1] = midp_load16_512(src + (u >> 1) * step, w_off);
+    }
+    ws.sc = midp_load16(reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Ep + (int64_t)b * wtiles * 256))), e_off);
   };
-  auto load_a = [&](int b) __attribute__((always_inline)) {
-    const uint8_t* src = qop + (int64_t)b * (U * kMidpStepA);  // the batch's operands are contiguous
+  // the batch's operands are contiguous in qop: fill f copies kilobyte f (wave w: f = w, w + 4, ...); the scale
+  // bytes are 256 per K step at 512-byte intervals: lane l < 32 of wave w copies piece l % 16 of step 2w + l / 16
+  const uint32_t a_off = (uint32_t)(lane * 16);
+  const uint32_t s_off = (uint32_t)((2 * wave + ((lane >> 4) & 1)) * 512 + (lane & 15) * 16);
+  auto fill_a = [&](int b) __attribute__((always_inline)) {
+    const int bb = min(b, NB - 1);
+    const uint32_t dst = lds0 + (uint32_t)((b % NSETS) * kMidpBufA);
+    const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * kMidpStepA) + wave * 1024)));
 #pragma unroll
-    for (int i = 0; i < kMidpStageA; ++i) as.a[i] = *reinterpret_cast<const v4i*>(src + (tid + i * kMidThreads) * 16);
-    if (tid < U * 16)
-      as.asc = *reinterpret_cast<const v4i*>(sa_t + ((int64_t)b * U + (tid >> 4)) * 512 + (tid & 15) * 16);
+    for (int i = 0; i < kMidpStageA; ++i) midp_fill16(src + i * 4096, a_off, dst + (uint32_t)(wave * 1024 + i * 4096));
+    midp_fill16_lanes32(reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(sa_t + (int64_t)bb * U * 512))), s_off,
+                        dst + (uint32_t)(U * kMidpStepA + wave * 512));
   };
-  auto store_a = [&](int buf) __attribute__((always_inline)) {
-    uint8_t* sa = s_midp + buf * kMidpBufA;
-#pragma unroll
-    for (int i = 0; i < kMidpStageA; ++i) *reinterpret_cast<v4i*>(sa + (tid + i * kMidThreads) * 16) = as.a[i];
-    if (tid < U * 16) *reinterpret_cast<v4i*>(sa + U * kMidpStepA + tid * 16) = as.asc;
-  };
+  constexpr int kLoadsA = kMidpStageA + 1, kLoadsW = U + 1;
+  static_assert(kMidpStageA * (kMidThreads / 64) * 1024 == U * kMidpStepA, "operand kilobytes per wave");
+  constexpr int kYounger = (D - 1) * (kLoadsW + kLoadsA);
+  static_assert(D >= 1 && kYounger < 64, "vmcnt is a 6-bit field");
   v16f acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  // One wave per SIMD: nothing hides an LDS read but the wave's own MFMAs, so the fragments of K step u + 2 are
-  // requested before the MFMAs of step u (three rotating fragment sets); left alone the compiler requests all 32
-  // reads of a batch up front, and the 96 registers that takes push the weight sets out of the VGPRs.
   struct Frag {
     v8i av[2];
     int sa;
@@ -306,7 +356,6 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
         const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
         f.av[comp] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
       }
-      // the step's row scales: byte 0 of the dword is the scale of row l32 (block kb)
       f.sa = *reinterpret_cast<const int*>(sa_buf + U * kMidpStepA + u * 256 + kb * 128 + l32 * 4);
     };
     Frag f[3];
@@ -327,30 +376,34 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  // batch b: weights in register set b % 4, operands in LDS buffer b % 2
-  load_a(0);
-  load_w(0, w0);
-  if (NB > 1) load_w(1, w1);
-  if (NB > 2) load_w(2, w2);
-  store_a(0);
-  __syncthreads();
-  // (The load conditions stay in: a steady-state loop peeled into straight-line code made the compiler hoist a
-  // whole batch of loads and spill 1.2 KB per lane.)
-  auto phase = [&](int b, WSet& cur, WSet& far, int buf) __attribute__((always_inline)) {
-    // operands first: loads complete in order, and the operands are needed at the end of this phase, the weights
-    // three phases from now
-    if (b + 1 < NB) load_a(b + 1);
-    if (b + 3 < NB) load_w(b + 3, far);  // the set of batch b - 1, multiplied in the previous phase
-    multiply(buf, cur);
-    if (b + 1 < NB) store_a(buf ^ 1);    // everyone left that buffer at the last barrier
-    __syncthreads();
+  // the registers of `cur` pass through the wait statement, so that nothing that reads them can be placed above it
+  auto wait_batch = [&](WSet& cur) __attribute__((always_inline)) {
+    asm volatile("s_waitcnt vmcnt(%9)\n\ts_barrier"
+                 : "+v"(cur.w[0]), "+v"(cur.w[1]), "+v"(cur.w[2]), "+v"(cur.w[3]), "+v"(cur.w[4]), "+v"(cur.w[5]),
+                   "+v"(cur.w[6]), "+v"(cur.w[7]), "+v"(cur.sc)
+                 : "n"(kYounger)
+                 : "memory");
   };
-  for (int b = 0; b < NB; b += 4) {
-    phase(b, w0, w3, 0);
-    if (b + 1 < NB) phase(b + 1, w1, w0, 1);
-    if (b + 2 < NB) phase(b + 2, w2, w1, 0);
-    if (b + 3 < NB) phase(b + 3, w3, w2, 1);
+  auto phase = [&](int b, WSet& cur, WSet& far) __attribute__((always_inline)) {
+    wait_batch(cur);
+    load_w(b + D, far);
+    fill_a(b + D);
+    multiply(b % NSETS, cur);
+  };
+#pragma unroll
+  for (int j = 0; j < D; ++j) {
+    load_w(j, w[j]);
+    fill_a(j);
   }
+  for (int b = 0; b < NB; b += NSETS) {
+#pragma unroll
+    for (int j = 0; j < NSETS; ++j)
+      if (j == 0 || b + j < NB) phase(b + j, w[j], w[(j + D) % NSETS]);
+  }
+  // everything this wave requested has to land before its LDS and registers are given up
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int j = 0; j < NSETS; ++j) asm volatile("" : "+v"(w[j].sc));
   // D: column l%32, row 8*(r/4) + 4*(l/32) + r%4 in register r
   if (n < N) {
 #pragma unroll
@@ -368,9 +421,21 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
 
 static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* Wp, const uint8_t* Ep, void* y,
                        int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
-  constexpr int lds = 2 * kMidpBufA;
-  hipLaunchKernelGGL(gemm_w4_midp_kernel, dim3((unsigned)cdiv(N, kMidBN)), dim3(kMidThreads), lds, stream, qop, sa_t,
-                     Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift);
+  constexpr int lds = (kMidpDepth + 1) * kMidpBufA;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  // Channels per workgroup: 128, or the multiple of 16 (at least 80) that deals the 16-channel tiles evenly to
+  // 256 CUs per round -- 28672 channels: 256 workgroups of 112 instead of 224 of 128 (measured 31.8 against 32.5 us).
+  const int64_t tiles = cdiv(N, 16);
+  const int64_t rounds = cdiv(tiles, 8 * 256);
+  const int64_t tpw = cdiv(tiles, 256 * rounds);
+  const int bn = tpw >= 5 ? (int)tpw * 16 : kMidBN;
+  hipLaunchKernelGGL(gemm_w4_midp_kernel<kMidpDepth>, dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads), lds, stream, qop,
+                     sa_t, Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift, bn);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
