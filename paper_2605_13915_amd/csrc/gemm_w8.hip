@@ -1166,8 +1166,10 @@ int launch_pack_weights_w8(const int8_t* W, int64_t N, int64_t K, int8_t* packed
 //   column tiles two or four tiles per workgroup.
 enum { kFusedNone = 0, kFused4x4, kFused4x8, kFused4x16, kFused4x16x2, kFused8x8x4, kFused8x16, kFused8x16x2 };
 static int fused_instance(int64_t M, int64_t K, int64_t N) {
-  if (M < 1 || M > kFusedMaxRows || M * K > kFusedMaxElems) return kFusedNone;
   const bool wide = cdiv(N, 16) > 512;
+  // (Twice as many elements measured slower inside a graph, where a dependent launch costs 2 us: 10.3 against 9.5 us
+  // at 8 x 4096 x 4096 -- and faster when every launch also costs host time, which is not what is timed here.)
+  if (M < 1 || M > kFusedMaxRows || M * K > kFusedMaxElems) return kFusedNone;
   if (K == 1024) return kFused4x4;
   if (K == 2048) return kFused4x8;
   if (K == 4096) return !wide ? kFused4x16 : M <= 2 ? kFused4x16x2 : kFused8x8x4;
@@ -1197,10 +1199,12 @@ static int launch_fused_mr(const GemmW8Args& a, hipStream_t stream) {
   return MSD_OK;
 }
 
-// picks the row bound: M * K <= kFusedMaxElems leaves at most 16384 / (WAVES * STEPS * 64) rows
+// picks the row bound: M * K <= kFusedMaxElems, at most four 16-element chunks of x per lane
 template <int WAVES, int STEPS, int NT>
 static int launch_fused(const GemmW8Args& a, hipStream_t stream) {
-  constexpr int MAXR = (int)(kFusedMaxElems / (WAVES * STEPS * 64)) < kFusedMaxRows ? (int)(kFusedMaxElems / (WAVES * STEPS * 64)) : kFusedMaxRows;
+  constexpr int kByElems = (int)(kFusedMaxElems / (WAVES * STEPS * 64)), kByChunks = 64 / STEPS;  // XC <= 4
+  constexpr int MAXR = kByElems < kByChunks ? (kByElems < kFusedMaxRows ? kByElems : kFusedMaxRows)
+                                            : (kByChunks < kFusedMaxRows ? kByChunks : kFusedMaxRows);
   if (a.K != (int64_t)WAVES * STEPS * 64 || a.M > MAXR) return MSD_ERR_INVALID_ARG;
   if (a.M <= 1) return launch_fused_mr<WAVES, STEPS, NT, 1>(a, stream);
   if (a.M <= 2) return launch_fused_mr<WAVES, STEPS, NT, 2>(a, stream);

@@ -81,7 +81,8 @@ def test_decompose_strided_rows(msd):
 
 SHAPES = [
     (16, 1024, 1024, 0),       # config 0
-    (1, 4096, 4096, 1), (8, 4096, 4096, 1),   # decode, skinny kernel
+    (1, 4096, 4096, 1), (8, 4096, 4096, 1), (8, 4096, 8300, 1),   # decode: single launch; two launches, skinny kernel
+    (5, 4096, 1000, 0), (4, 8192, 520, 1),   # just above the single-launch bound
     (32, 4096, 4096, 1),       # decode, split-K tiled kernel
     (3, 208, 50, 0),           # ragged everything, K not a multiple of 64
     (40, 1040, 200, 1),        # ragged tiled, several M tiles
