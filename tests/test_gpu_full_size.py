@@ -1,5 +1,7 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times
-(the entry points without observation points, caller-provided output and workspace).
+(the entry points without observation points, caller-provided output and workspace; the GEMMs on the canonical
+weight arrays against the oracle and, bit for bit against that result, on the packed arrays bench.py times by
+default).
 
 cfg1 (W8A16 decode) and the small W4 / attention shapes are compared element by element in full; so are the
 latent-cache and grouped-GEMM shapes of the bench legs (sampled batch entries; every routed row).  For the
@@ -48,6 +50,7 @@ def test_cfg1_w8a16_decode_full(msd, N):
     K = 4096
     W, s = synth.int8_weights(synth.seed_for(1, 10 + N), N, K)
     Wd, sd = to_dev(W), to_dev(s)
+    Wp = msd.msd_pack_weights_w8(Wd)
     for M in (1, 8, 32, 128):
         x = synth.activations(synth.seed_for(1, M), M, K, outliers=True)
         ref = oracle.gemm_w8a16(x, W, s)
@@ -59,6 +62,10 @@ def test_cfg1_w8a16_decode_full(msd, N):
         assert rel_l2(yh, ref) <= 1e-6
         for m in range(M):
             assert rel_l2(yh[m], ref[m]) <= 1e-6
+        yp = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        msd.msd_gemm_w8a16_packed(bf16_to_dev(x), Wp, sd, y=yp)
+        torch.cuda.synchronize()
+        assert torch.equal(y, yp)
 
 
 @pytest.fixture(scope="module")
@@ -74,10 +81,18 @@ def test_cfg2_w8a16_prefill_sampled_rows(msd, prefill_inputs, M, N):
     x, W, s = prefill_inputs
     x, W, s = x[:M], W[:N], s[:N]
     y = torch.empty((M, N), dtype=torch.float32, device="cuda")
-    msd.msd_gemm_w8a16(bf16_to_dev(x), to_dev(W), to_dev(s), y=y)
+    xd, Wd, sd = bf16_to_dev(x), to_dev(W), to_dev(s)
+    msd.msd_gemm_w8a16(xd, Wd, sd, y=y)
     torch.cuda.synchronize()
     rows = _rows_every_tile(M, 128, seed=M + N)   # the kernel's row tile is 128 activation rows
     assert bool(torch.isfinite(y).all())         # every element, not only the sampled rows
+    Wp = msd.msd_pack_weights_w8(Wd)
+    del Wd
+    yp = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w8a16_packed(xd, Wp, sd, y=yp)
+    torch.cuda.synchronize()
+    assert torch.equal(y, yp)
+    del yp, Wp
     yh = y[torch.from_numpy(rows).cuda()].cpu().numpy()
     del y
     torch.cuda.empty_cache()
@@ -100,10 +115,17 @@ def test_cfg3_w4a16(msd, w4_weights, M):
     K, N = 8192, codes.shape[0]
     x = synth.activations(synth.seed_for(3, M), M, K, outliers=True)
     y = torch.empty((M, N), dtype=torch.float32, device="cuda")
-    msd.msd_gemm_w4a16(bf16_to_dev(x), to_dev(codes), to_dev(exps), y=y)
+    xd, cd, ed = bf16_to_dev(x), to_dev(codes), to_dev(exps)
+    msd.msd_gemm_w4a16(xd, cd, ed, y=y)
     torch.cuda.synchronize()
     rows = np.arange(M) if M <= 32 else _rows_every_tile(M, 128, seed=M)   # 128-row tiles: 32 + boundary rows
     assert bool(torch.isfinite(y).all())
+    Wp, Ep = msd.msd_pack_weights_w4(cd, ed)
+    yp = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w4a16_packed(xd, Wp, Ep, N, y=yp)
+    torch.cuda.synchronize()
+    assert torch.equal(y, yp)
+    del yp, Wp, Ep
     yh = y[torch.from_numpy(rows).cuda()].cpu().numpy()
     ref = oracle.gemm_w4a16(x[rows], codes, exps)
     assert np.all(np.isfinite(yh))
