@@ -189,8 +189,11 @@ size_t msd_gemm_w4a16_workspace_bytes(int64_t M, int64_t K, int64_t N);
  * msd_pack_weights_w8 for the block-scaled matrix instructions, whose operand is 16 channels x 4 MX blocks):
  *   packed_fp4 [K/128][ceil(N/16)][1024]: byte ((g*16 + r)*16 + b) of the kilobyte (q, nb) =
  *       byte b of MX block 4q + g of channel 16*nb + r (W_fp4[16*nb + r][(4q + g)*16 + b]); zero past N.
- *   packed_e8m0 [K/512][ceil(N/16)][256]: byte (r*16 + i) of the record (s, nb) = W_e8m0[16*nb + r][16*s + i];
- *       0x7F past N.
+ *   packed_e8m0, first part [K/512][ceil(N/16)][256]: byte (r*16 + i) of the record (s, nb) =
+ *       W_e8m0[16*nb + r][16*s + i]; 0x7F past N.  Second part, at the next multiple of 256 bytes,
+ *       [K/64][ceil(N/256)][512]: the same bytes in the order the many-row kernel stages them -- byte
+ *       (r/128)*256 + b*128 + (r%32)*4 + (r/32)%4 of the record (t, nt) = W_e8m0[256*nt + r][2*t + b]; 0x7F past N
+ *       -- so that no call has to rearrange them.
  * One operand load is then one contiguous kilobyte instead of 16 pieces of 64 bytes, and the 16 scale bytes of
  * 16 channels one 256-byte run.
  *   msd_packed_weights_w4_bytes / msd_packed_scales_w4_bytes (N, K): sizes of the two arrays (0 for empty shapes).

@@ -577,7 +577,9 @@ int launch_pack_weights_w4(const uint8_t* W, const uint8_t* We, int64_t N, int64
   const int64_t pieces = (KB / 4) * tiles * 64;
   hipLaunchKernelGGL(pack_weights_w4_kernel, dim3((unsigned)cdiv(pieces, 256)), dim3(256), 0, stream, W, We, N, KB, Wp, Ep);
   MSD_LAUNCH_CHECK();
-  return MSD_OK;
+  // second part of the scale array: the same bytes in the stage order of the many-row kernel, so that no call has to
+  // rearrange them
+  return launch_transpose_w_scales(We, N, K, Ep + w4_packed_scales_decode_bytes(N, K), stream);
 }
 
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream) {

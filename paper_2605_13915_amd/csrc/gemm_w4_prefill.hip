@@ -101,10 +101,9 @@ __global__ __launch_bounds__(256) void decompose_mxfp4_pair_kernel(const uint16_
 // ------------------------------------------------------------------ (2) weight scale bytes, K-step-major
 // One workgroup moves a 64 (columns) x 64 (K steps) tile of byte pairs through LDS so that both the
 // reads (along K) and the writes (along N) are contiguous.
-// packed: We is the scale array of msd_pack_weights_w4, [K/512][ceil(N/16)][16 channels][16 bytes].
 __global__ __launch_bounds__(256) void transpose_w_scales_kernel(const uint8_t* __restrict__ We, int64_t N,
                                                                  int KB2, int64_t Npad,
-                                                                 uint8_t* __restrict__ sw_t, int packed) {
+                                                                 uint8_t* __restrict__ sw_t) {
   __shared__ uint16_t tile[64][65];
   const int64_t n0 = (int64_t)blockIdx.x * 64;
   const int s0 = blockIdx.y * 64;
@@ -114,8 +113,7 @@ __global__ __launch_bounds__(256) void transpose_w_scales_kernel(const uint8_t* 
     const int s = s0 + c;
     uint16_t v = 0x7F7F;
     if (n < N && s < KB2) {
-      const uint8_t* p = packed ? We + ((int64_t)(s >> 3) * ((N + 15) / 16) + n / 16) * 256 + (n & 15) * 16 + ((2 * s) & 15)
-                                : We + (n * KB2 + s) * 2;
+      const uint8_t* p = We + (n * KB2 + s) * 2;
       v = (uint16_t)p[0] | ((uint16_t)p[1] << 8);
     }
     tile[r][c] = v;
@@ -243,16 +241,16 @@ __global__ __launch_bounds__(512) void gemm_w4_dma_kernel(GemmW4PrefillArgs a, i
   // of 16 bytes; wave w fetches pieces 8w .. 8w+7 with its lanes 0..7 (waves 0..3 activation scales, 4..7 weight
   // scales), so that every wave issues the same number of loads per stage and waits on the same count
   const int sp = wave * 8 + (lane & 7), skb = sp >> 5, sl = sp & 31;
-  const uint8_t* sbase = skb ? a.sw_t : a.sa_t;
-  const uint64_t s_first = (uint64_t)(sbase - a.ws) + (skb ? n0 : m0) * 2 + 16 * sl;  // byte offset from a.ws
-  const uint64_t s_inc = (uint64_t)(skb ? a.Npad : a.Mpad) * 2;                    // per K step
+  const uint8_t* sbase = skb ? a.sw_t : a.sa_t;  // wave-uniform
+  const uint64_t s_first = (uint64_t)(skb ? n0 : m0) * 2 + 16 * sl;  // byte offset from sbase (below 2^32: host check)
+  const uint64_t s_inc = (uint64_t)(skb ? a.Npad : a.Mpad) * 2;      // per K step
   auto issue_one = [&](int kt, int q) {  // q is a compile-time constant at every call site
     const uint32_t dst = lds0 + (uint32_t)((kt % NS) * STAGE) + (uint32_t)(wave * 1024 + q * 8192);
     if (q < QA) w4_lds_dma16(a_src + (int64_t)kt * step_a + q * 8192, voff_a, dst);
     else if (q == QA)
       w4_lds_dma16(w_src + (int64_t)(kt >> 1) * w_pair + (kt & 1) * w_odd, voff_w, dst);
     else
-      w4_lds_dma16_lanes8(a.ws, (uint32_t)(s_first + (uint64_t)kt * s_inc),
+      w4_lds_dma16_lanes8(sbase, (uint32_t)(s_first + (uint64_t)kt * s_inc),
                           lds0 + (uint32_t)((kt % NS) * STAGE) + SZ_A + SZ_W + (uint32_t)(wave * 128));
   };
   auto issue = [&](int kt) {
@@ -447,6 +445,24 @@ W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N) {
   return l;
 }
 
+size_t w4_packed_scales_decode_bytes(int64_t N, int64_t K) {
+  return align_up((size_t)((K + 511) / 512) * (size_t)((N + 15) / 16) * 256, 256);
+}
+
+size_t w4_packed_scales_bytes(int64_t N, int64_t K) {
+  return w4_packed_scales_decode_bytes(N, K) + (size_t)(K / 64) * align_up((size_t)N, 256) * 2;
+}
+
+// canonical E8M0 bytes [N][K/32] -> the stage order of the many-row kernel (sw_t above)
+int launch_transpose_w_scales(const uint8_t* We, int64_t N, int64_t K, uint8_t* sw_t, hipStream_t stream) {
+  const int KB2 = (int)(K / 64);
+  const int64_t Npad = (int64_t)align_up((size_t)N, 256);
+  hipLaunchKernelGGL(transpose_w_scales_kernel, dim3((unsigned)(Npad / 64), (unsigned)cdiv(KB2, 64)), dim3(256), 0,
+                     stream, We, N, KB2, Npad, sw_t);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
 int launch_decompose_mxfp4_pair(const uint16_t* x, int64_t ldx, int64_t M, int64_t K, int64_t Mpad, uint8_t* qop,
                                 uint8_t* sa_t, MxVariant mv, hipStream_t stream) {
   const int KB2 = (int)(K / 64);
@@ -461,17 +477,17 @@ int launch_gemm_w4_prefill(const uint16_t* x, int64_t ldx, const uint8_t* W, con
                            int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, uint8_t* ws,
                            MxVariant mv, hipStream_t stream, bool probe, int w_packed) {
   const W4PrefillLayout l = w4_prefill_layout(M, K, N);
-  if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace
-  const int KB2 = (int)(K / 64);
+  if (l.total >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // 32-bit offsets inside the workspace ...
   if (int rc = launch_decompose_mxfp4_pair(x, ldx, M, K, (int64_t)l.Mpad, ws + l.qop, ws + l.sa_t, mv, stream)) return rc;
-  hipLaunchKernelGGL(transpose_w_scales_kernel, dim3((unsigned)(l.Npad / 64), (unsigned)cdiv(KB2, 64)), dim3(256), 0,
-                     stream, We, N, KB2, (int64_t)l.Npad, ws + l.sw_t, w_packed);
-  MSD_LAUNCH_CHECK();
+  // packed weights carry their scale bytes in this kernel's order already (second part of the packed array)
+  if ((size_t)(K / 64) * l.Npad * 2 >= ((size_t)1 << 31)) return MSD_ERR_UNSUPPORTED;  // ... and the scale arrays
+  const uint8_t* sw_t = w_packed ? We + w4_packed_scales_decode_bytes(N, K) : ws + l.sw_t;
+  if (!w_packed)
+    if (int rc = launch_transpose_w_scales(We, N, K, ws + l.sw_t, stream)) return rc;
   GemmW4PrefillArgs a{};
-  a.ws = ws;
   a.qop = ws + l.qop;
   a.sa_t = ws + l.sa_t;
-  a.sw_t = ws + l.sw_t;
+  a.sw_t = sw_t;
   a.W = W;
   a.w_packed = w_packed;
   a.y = y;

@@ -107,10 +107,9 @@ int launch_pack_weights_w4(const uint8_t* W, const uint8_t* We, int64_t N, int64
 
 // ---- W4A16, many rows (gemm_w4_prefill.hip): own decomposition format, asynchronous LDS fill
 struct GemmW4PrefillArgs {
-  const uint8_t* ws;    // workspace base (scale fetches use 32-bit offsets from it)
   const uint8_t* qop;   // [M][K/64][96 B] FP6 operands of both components
-  const uint8_t* sa_t;  // [K/64][Mpad][2] activation scale bytes
-  const uint8_t* sw_t;  // [K/64][Npad][2] weight scale bytes
+  const uint8_t* sa_t;  // [K/64][Mpad][2] activation scale bytes (fetched with 32-bit offsets from this base)
+  const uint8_t* sw_t;  // [K/64][Npad][2] weight scale bytes (likewise; workspace, or the packed array's second part)
   const uint8_t* W;     // [N][K/2], or the packed array of msd_pack_weights_w4
   int w_packed;
   void* y;
@@ -124,6 +123,11 @@ struct W4PrefillLayout {
 };
 bool gemm_w4_prefill_applies(int64_t M, int64_t K, int64_t N);
 W4PrefillLayout w4_prefill_layout(int64_t M, int64_t K, int64_t N);
+// packed scale array of msd_pack_weights_w4: the decode-order records, then (256-byte aligned) the same bytes in the
+// order of the many-row kernel's stages, [K/64][N rounded up to 256][2] with scale_slot inside a 256-column tile
+size_t w4_packed_scales_decode_bytes(int64_t N, int64_t K);
+size_t w4_packed_scales_bytes(int64_t N, int64_t K);
+int launch_transpose_w_scales(const uint8_t* We, int64_t N, int64_t K, uint8_t* sw_t, hipStream_t stream);
 // decomposition + scale transposition + GEMM; ws holds w4_prefill_layout(M, K, N).total bytes.
 // probe: measurement aid -- the GEMM keeps multiplying the operands of its first K step (no fill,
 // barriers or LDS traffic afterwards); y is then meaningless

@@ -328,7 +328,7 @@ size_t msd_packed_weights_w4_bytes(int64_t N, int64_t K) {
 
 size_t msd_packed_scales_w4_bytes(int64_t N, int64_t K) {
   if (N <= 0 || K <= 0) return 0;
-  return (size_t)((K + 511) / 512) * (size_t)((N + 15) / 16) * 256;
+  return w4_packed_scales_bytes(N, K);
 }
 
 int msd_pack_weights_w4(const uint8_t* W_fp4, const uint8_t* W_e8m0, int64_t N, int64_t K, void* packed_fp4,

@@ -177,9 +177,22 @@ def test_pack_weights_w4_layout_and_errors(msd):
     ep = np.full((tiles * 16, K // 32), 0x7F, dtype=np.uint8)
     ep[:N] = exps
     want_e = ep.reshape(tiles, 16, K // 512, 16).transpose(2, 0, 1, 3)   # [s][nb][r][i]
-    assert np.array_equal(Ep.cpu().numpy(), want_e.reshape(-1))
+    Eh = Ep.cpu().numpy()
+    assert np.array_equal(Eh[:want_e.size], want_e.reshape(-1))
+    # second part (256-byte aligned): the same bytes per K step of 64 and tile of 256 channels, channel r of the
+    # tile and block b of the step at (r // 128) * 256 + b * 128 + (r % 32) * 4 + (r // 32) % 4; 0x7F past N
+    first = (want_e.size + 255) // 256 * 256
+    npad = (N + 255) // 256 * 256
+    e2 = np.full((npad, K // 32), 0x7F, dtype=np.uint8)
+    e2[:N] = exps
+    want_t = np.zeros((K // 64, npad // 256, 512), dtype=np.uint8)
+    r = np.arange(256)
+    for b in range(2):
+        slot = (r // 128) * 256 + b * 128 + (r % 32) * 4 + (r // 32) % 4
+        want_t[:, :, slot] = e2[:, b::2].reshape(npad // 256, 256, K // 64).transpose(2, 0, 1)
+    assert np.array_equal(Eh[first:], want_t.reshape(-1))
     L = msd.lib()
-    assert L.msd_packed_weights_w4_bytes(N, K) == want.size and L.msd_packed_scales_w4_bytes(N, K) == want_e.size
+    assert L.msd_packed_weights_w4_bytes(N, K) == want.size and L.msd_packed_scales_w4_bytes(N, K) == first + want_t.size
     assert L.msd_packed_weights_w4_bytes(0, K) == 0
     bad = L.msd_pack_weights_w4(Wp.data_ptr(), Ep.data_ptr(), N, 544, Wp.data_ptr(), Ep.data_ptr(), None)
     assert bad == -2  # MSD_ERR_SHAPE
