@@ -641,8 +641,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_w8_mfma32_kernel(GemmW8Args
 // lane order, so a lane fetches the global chunk whose swizzled position it owns.  Rows past M / N
 // are clamped to the last valid row (their results are never stored).  Requires K % 64 == 0.
 //
-// Two uses.  <128,256,2,4,4>: prefill, 256x256 output tile (128 activation rows x 2 components)
-// on eight waves.  Small tiles with many stages: batched decode (32 < M <= 128, few output tiles),
+// Two uses.  <128,256,4,4,4>: prefill, 256x256 output tile (128 activation rows x 2 components)
+// on sixteen waves.  Small tiles with many stages: batched decode (32 < M <= 128, few output tiles),
 // where the weight stream is cold and the bytes in flight per CU, i.e. the stage count, set the
 // HBM rate (Little's law), not the MFMA.
 __device__ __forceinline__ void lds_dma16(const int8_t* gbase, uint32_t voff, uint32_t lds_addr) {
@@ -1131,7 +1131,7 @@ int launch_bf16_gemm_tiled(const uint16_t* x, int64_t M, int64_t K, int64_t ldx,
   a.M = M;
   a.K = 2 * K;
   a.N = N;
-  const int rc = launch_dma<128, 256, 2, 4, 4, true>(a, stream);
+  const int rc = launch_dma<128, 256, 4, 4, 4, true>(a, stream);
   if (rc) return rc;
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -1269,7 +1269,7 @@ int launch_gemm_w8_grouped(const GemmW8Args& a, const int32_t* offs, int E, hipS
 int launch_gemm_w8_mfma_probe(const GemmW8Args& a, hipStream_t stream) {
   if (a.M == 0 || a.N == 0) return MSD_OK;
   if (a.K % 64 != 0 || a.K < 64 || a.x != nullptr) return MSD_ERR_SHAPE;
-  const int rc = launch_dma<128, 256, 2, 4, 4, false, true>(a, stream);
+  const int rc = launch_dma<128, 256, 4, 4, 4, false, true>(a, stream);
   if (rc) return rc;
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -1363,13 +1363,13 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     else  // at most 64 KB of LDS: two workgroups per CU
       rc = deep ? launch_dma<32, 64, 1, 2, 4, false, false, 128>(a, stream) : launch_dma<32, 64, 1, 2, 8>(a, stream);
   } else if (path == W8Path::kFillLarge) {
-    // Eight waves (two per SIMD, 128x64 wave tiles): measured 6-10% faster than four waves with 128x128 wave
-    // tiles -- twice as many waves issue fill instructions and a SIMD always has a second wave to issue from
-    // while one waits.  Three or five stages, half-size tiles (two workgroups per CU) and 128 bytes of K per
-    // barrier on 64x256 or 128x128 tiles (a 256x256 tile of 128-byte stages does not fit LDS three deep) measured
-    // no better.  Sixteen waves (4 x 4 or 2 x 8, 64 accumulator registers each) measured the same within 2 %
-    // on 2048 x 8192 x 8192 and 2048 x 8192 x 28672 and 5 % faster on 8192^3.
-    rc = launch_dma<128, 256, 2, 4, 4>(a, stream);
+    // Sixteen waves (four per SIMD, 64x64 wave tiles of 64 accumulator registers): 0.5-5 % faster over the four
+    // benchmark shapes than eight waves with 128x64 wave tiles (280 against 294 us at 2048 x 8192 x 8192), which in
+    // turn measured 6-10 % faster than four waves with 128x128 wave tiles -- more waves issue fill instructions and
+    // a SIMD always has another wave to issue from while one waits.  Three or five stages, half-size tiles (two
+    // workgroups per CU) and 128 bytes of K per barrier on 64x256 or 128x128 tiles (a 256x256 tile of 128-byte
+    // stages does not fit LDS three deep) measured no better.
+    rc = launch_dma<128, 256, 4, 4, 4>(a, stream);
   } else if (cdiv(M, 128) * cdiv(N, 256) < 128) {
     rc = launch_mfma32<64, 64, 2, 2>(a, stream);
   } else {
