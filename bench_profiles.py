@@ -122,8 +122,10 @@ def do_trace():
 
 # ------------------------------------------------------------------ HBM traffic
 def counter_rows(d):
-    """dispatches of the counter run, without the one-time weight repack kernels of the set-up"""
-    return [r for r in csv.DictReader(open(find_csv(d, "counter_collection.csv"))) if "pack_weights" not in r["Kernel_Name"]]
+    """dispatches of the counter run, without the one-time weight repack kernels of the set-up (the probes run on
+    packed weights, whose repack includes the rearrangement of the MXFP4 scale bytes)"""
+    return [r for r in csv.DictReader(open(find_csv(d, "counter_collection.csv")))
+            if "pack_weights" not in r["Kernel_Name"] and "transpose_w_scales" not in r["Kernel_Name"]]
 
 
 def calib(rows):
