@@ -1,4 +1,5 @@
-"""GPU parity over seeded random shapes that straddle every kernel-selection boundary of the two GEMMs.
+"""GPU parity over seeded random shapes that straddle every kernel-selection boundary of the two GEMMs, on the
+canonical weight arrays against the oracle and, where K allows, bit for bit on the packed arrays.
 
 Same bars as the per-shape files: codes, scales and int32 partials bit-exact where the observation
 points are requested, fp32 output within 1e-6 (W8) / 2e-6 (W4) relative L2 of the oracle, far inside
@@ -56,6 +57,10 @@ def test_w8a16_random_shape(msd, M, K, N, taps, outl, seed):
         y = msd.msd_gemm_w8a16(xd, Wd, sd)
         torch.cuda.synchronize()
     assert rel_l2(y.cpu().numpy(), y_ref) <= 1e-6
+    if K % 64 == 0 and not taps:         # the packed layout gives the same bits as the same entry point
+        yp = msd.msd_gemm_w8a16_packed(xd, msd.msd_pack_weights_w8(Wd), sd)
+        torch.cuda.synchronize()
+        assert torch.equal(y, yp)
 
 
 @pytest.mark.parametrize("M,K,N,taps,outl,seed", _cases(12, 30, K_W4, 2e8))
@@ -75,3 +80,8 @@ def test_w4a16_random_shape(msd, M, K, N, taps, outl, seed):
         y = msd.msd_gemm_w4a16(xd, cd, ed)
         torch.cuda.synchronize()
     assert rel_l2(y.cpu().numpy(), y_ref) <= 2e-6
+    if K % 512 == 0 and not taps:        # the packed layout gives the same bits as the same entry point
+        Wp, Ep = msd.msd_pack_weights_w4(cd, ed)
+        yp = msd.msd_gemm_w4a16_packed(xd, Wp, Ep, N)
+        torch.cuda.synchronize()
+        assert torch.equal(y, yp)
