@@ -119,12 +119,14 @@ def main():
                          "three cold-cache eager calls of each decode shape in the order of 'shapes'; no timing")
     ap.add_argument("--counter-probe", default="",
                     choices=["", "w8_prefill", "w4_prefill", "attn", "attn4k", "mla16", "mla128", "w4_m1", "w4_m32",
-                             "probe_w8", "probe_w8_const", "probe_w4", "rate_w8", "rate_w8_const", "rate_w4", "rate_w4_const"],
+                             "probe_w8", "probe_w8_const", "probe_w4", "rate_w8", "rate_w8_const", "rate_w4", "rate_w4_const",
+                             "fill_l2", "fill_mix", "fill_hbm"],
                     help="for rocprofv3 --pmc runs: three eager calls of one shape (W8A16 2048x8192x8192, W4A16 "
                          "4096 / 1 / 32 x 8192 x 28672 (both on packed weights), attention L=32768 / 4096, latent-cache attention with 16 heads "
                          "at L=32768 or 128 heads at L=4096, the MFMA-only probes of the two prefill kernels with random "
                          "or constant operands, the matrix-instruction-only kernel msd_probe_mfma_rate on random or constant "
-                         "bits), nothing else; no timing")
+                         "bits, the fill-instruction-only kernel msd_probe_lds_fill_rate on an L2-resident window, "
+                         "half and half, or streamed ranges), nothing else; no timing")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --counter-probe: first one 1 GiB device copy, the calibration kernel of the "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -164,6 +166,13 @@ def main():
                 buf = torch.randint(-2 ** 31, 2 ** 31 - 1, (16384,), dtype=torch.int32, device=dev, generator=g)
             fmt = msd.MSD_MXFP4 if "w4" in args.counter_probe else msd.MSD_INT8
             call = lambda: msd.msd_probe_mfma_rate(fmt, buf, 4000)
+        elif args.counter_probe.startswith("fill_"):
+            # the tile kernels' LDS fill instructions alone (msd_probe_lds_fill_rate): from a 1 MB window every
+            # workgroup shares, half and half, or from disjoint ranges of a 1 GiB buffer
+            buf = torch.empty(((1 << 30) + (1 << 20),), dtype=torch.int8, device=dev)
+            buf.random_(-128, 127)
+            parts = {"fill_l2": 4, "fill_mix": 2, "fill_hbm": 0}[args.counter_probe]
+            call = lambda: msd.msd_probe_lds_fill_rate(buf, 1 << 20, parts, 128)
         elif args.counter_probe in ("w8_prefill", "probe_w8", "probe_w8_const"):
             M, K, N = 2048, 8192, 8192
             x = dev_bf16(synth.activations(synth.seed_for(2, 0), M, K, outliers=True))

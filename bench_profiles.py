@@ -214,7 +214,7 @@ PASSES = [["SQ_WAVE_CYCLES", "SQ_BUSY_CYCLES", "SQ_WAIT_INST_ANY", "SQ_WAIT_ANY"
            "SQ_ACTIVE_INST_SCA", "SQ_INSTS_VMEM_RD"],
           ["TCC_HIT_sum", "TCC_MISS_sum"],
           ["GRBM_GUI_ACTIVE", "GRBM_COUNT"]]
-WORKLOADS = ["rate_w8", "rate_w8_const", "rate_w4", "rate_w4_const", "w8_prefill", "probe_w8", "probe_w8_const", "w4_prefill",
+WORKLOADS = ["rate_w8", "rate_w8_const", "rate_w4", "rate_w4_const", "fill_l2", "fill_mix", "fill_hbm", "w8_prefill", "probe_w8", "probe_w8_const", "w4_prefill",
              "probe_w4", "w4_m1", "w4_m32", "attn", "attn4k", "mla16", "mla128"]
 
 
@@ -230,6 +230,9 @@ def do_counters(workloads=None):
            "rate_w8 / rate_w8_const / rate_w4 / rate_w4_const = msd_probe_mfma_rate, 2048 waves x 32000 matrix instructions\n",
            "(INT8 32x32x32 resp. FP6 x FP4 32x32x64) on random resp. constant operand bits and nothing else: equal cycle\n",
            "counts, while bench.py's mfma_rate leg times the random-bits run 1.4x longer -- the clock under load differs.\n",
+           "fill_l2 / fill_mix / fill_hbm = msd_probe_lds_fill_rate, 256 workgroups x 128 rounds x 32 KB of LDS fills and nothing\n",
+           "else, from a 1 MB window every workgroup shares / half from the window, half from disjoint ranges of 1 GiB / all\n",
+           "from those ranges (the L2 hit rates say which is which).\n",
            "bench.py --counter-probe W runs three eager calls of one shape: w8_prefill = msd_gemm_w8a16_packed 2048x8192x8192;\n",
            "probe_w8 / probe_w8_const = msd_probe_mfma_w8a16 on the same shape (the prefill kernel's MFMA sequence, tile schedule\n",
            "and epilogue with no tile fill, no barrier, no LDS traffic after the first K step) with the benchmark's random operands\n",
