@@ -233,11 +233,19 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
 // operands (shared by the four waves, hot in L2) go through LDS.  One wave per SIMD: nothing hides an LDS read but
 // the wave's own MFMAs, so the fragments of K step u + 2 are requested before the MFMAs of step u (three rotating
 // fragment sets); left alone the compiler requests all 32 reads of a batch up front.
-constexpr int kMidpU = 8;          // K steps per batch
-constexpr int kMidpStepA = 3072;   // operand bytes of the 32-row group per K step
-constexpr int kMidpBufA = kMidpU * (kMidpStepA + 256);
-constexpr int kMidpStageA = kMidpU * kMidpStepA / 1024 / (kMidThreads / 64);  // operand kilobytes per wave and batch
+constexpr int kMidpGroupA = 3072;  // operand bytes of a 32-row group per K step
 constexpr int kMidpDepth = 2;      // batches in flight behind the current one (3 and 4 measured 4 % and 7 % slower)
+// RG groups of 32 rows, U K steps per batch: 8 steps for one or two groups, 4 for four (three LDS buffers of a
+// batch's operands have to fit)
+template <int RG, int U>
+struct MidpCfg {
+  static constexpr int kStepA = RG * kMidpGroupA;        // operand bytes per K step
+  static constexpr int kBufA = U * (kStepA + 256);       // a batch: operands, then 256 scale bytes per step
+  static constexpr int kStageA = U * kStepA / 1024 / (kMidThreads / 64);  // operand kilobytes per wave and batch
+  static constexpr int kScaleLanes = U * 256 / 16 / (kMidThreads / 64);   // lanes of a wave that copy scale bytes
+  static constexpr int kLds = (kMidpDepth + 1) * kBufA;
+  static_assert(kStageA * (kMidThreads / 64) * 1024 == U * kStepA && kScaleLanes <= 32 && kLds <= 160 * 1024, "batch split");
+};
 
 // Every vector-memory load is an asm statement and the waits are written by hand, as in the tile kernels: written
 // as plain loads with conditions on the batch number, the compiler lost count of the loads in flight at every join
@@ -257,12 +265,14 @@ __device__ __forceinline__ void midp_fill16(const uint8_t* gbase, uint32_t voff,
                : "v"(voff), "s"(gbase), "s"(lds_addr)
                : "memory", "m0");
 }
-__device__ __forceinline__ void midp_fill16_lanes32(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
+// the same issued by the lanes of `mask` (a subset of lanes 0..31) only, the others switched off inside the statement
+template <uint32_t MASK>
+__device__ __forceinline__ void midp_fill16_lanes(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
   uint64_t saved;
-  asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffffffff\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+  asm volatile("s_mov_b64 %0, exec\n\ts_mov_b32 exec_lo, %4\n\ts_mov_b32 exec_hi, 0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
                "global_load_lds_dwordx4 %1, %2\n\ts_mov_b64 exec, %0"
                : "=&s"(saved)
-               : "v"(voff), "s"(gbase), "s"(lds_addr)
+               : "v"(voff), "s"(gbase), "s"(lds_addr), "n"(MASK)
                : "memory", "m0");
 }
 __device__ __forceinline__ v4i midp_load16(const uint8_t* gbase, uint32_t voff) {
@@ -281,7 +291,7 @@ __device__ __forceinline__ uint64_t midp_uniform(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-template <int D>
+template <int D, int RG, int U>
 __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t* __restrict__ qop,
                                                                    const uint8_t* __restrict__ sa_t,
                                                                    const uint8_t* __restrict__ Wp,
@@ -290,8 +300,9 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
                                                                    int64_t N, int shift, int bn) {
   // bn: channels per workgroup, a multiple of 16, at most kMidBN (the host picks it so that the grid fills the CUs
   // evenly); a wave still multiplies 32 channels, those past bn or N repeat the workgroup's last one
-  constexpr int U = kMidpU;
+  using C = MidpCfg<RG, U>;
   constexpr int NSETS = D + 1;  // register sets and LDS buffers: the current batch and D in flight
+  static_assert(U == 8 || U == 4, "a batch is a whole or half a 16-block scale record");
   extern __shared__ __attribute__((aligned(16))) uint8_t s_midp[];  // [NSETS][A batch]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -320,44 +331,57 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
       ws.w[u] = midp_load16(src + (u >> 1) * step, w_off);
       ws.w[u + 1] = midp_load16_512(src + (u >> 1) * step, w_off);
     }
-    ws.sc = midp_load16(reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Ep + (int64_t)b * wtiles * 256))), e_off);
+    // the scale record covers eight K steps: with four steps per batch two batches share it
+    ws.sc = midp_load16(reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Ep + (int64_t)(b * U / 8) * wtiles * 256))), e_off);
   };
   // the batch's operands are contiguous in qop: fill f copies kilobyte f (wave w: f = w, w + 4, ...); the scale
-  // bytes are 256 per K step at 512-byte intervals: lane l < 32 of wave w copies piece l % 16 of step 2w + l / 16
+  // bytes are 256 per K step at 512-byte intervals: piece p = w * kScaleLanes + l of the batch (lane l < kScaleLanes of
+  // wave w) is piece p % 16 of step p / 16
   const uint32_t a_off = (uint32_t)(lane * 16);
-  const uint32_t s_off = (uint32_t)((2 * wave + ((lane >> 4) & 1)) * 512 + (lane & 15) * 16);
+  const int sp = wave * C::kScaleLanes + (lane & (C::kScaleLanes - 1));
+  const uint32_t s_off = (uint32_t)((sp >> 4) * 512 + (sp & 15) * 16);
   auto fill_a = [&](int b) __attribute__((always_inline)) {
     const int bb = min(b, NB - 1);
-    const uint32_t dst = lds0 + (uint32_t)((b % NSETS) * kMidpBufA);
-    const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * kMidpStepA) + wave * 1024)));
+    const uint32_t dst = lds0 + (uint32_t)((b % NSETS) * C::kBufA);
+    const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * C::kStepA) + wave * 1024)));
 #pragma unroll
-    for (int i = 0; i < kMidpStageA; ++i) midp_fill16(src + i * 4096, a_off, dst + (uint32_t)(wave * 1024 + i * 4096));
-    midp_fill16_lanes32(reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(sa_t + (int64_t)bb * U * 512))), s_off,
-                        dst + (uint32_t)(U * kMidpStepA + wave * 512));
+    for (int i = 0; i < C::kStageA; ++i) midp_fill16(src + i * 4096, a_off, dst + (uint32_t)(wave * 1024 + i * 4096));
+    midp_fill16_lanes<(uint32_t)((1ull << C::kScaleLanes) - 1)>(
+        reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(sa_t + (int64_t)bb * U * 512))), s_off,
+        dst + (uint32_t)(U * C::kStepA + wave * C::kScaleLanes * 16));
   };
-  constexpr int kLoadsA = kMidpStageA + 1, kLoadsW = U + 1;
-  static_assert(kMidpStageA * (kMidThreads / 64) * 1024 == U * kMidpStepA, "operand kilobytes per wave");
+  constexpr int kLoadsA = C::kStageA + 1, kLoadsW = U + 1;
   constexpr int kYounger = (D - 1) * (kLoadsW + kLoadsA);
   static_assert(D >= 1 && kYounger < 64, "vmcnt is a 6-bit field");
-  v16f acc;
+  v16f acc[RG];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[rg][r] = 0.f;
   struct Frag {
-    v8i av[2];
+    v8i av[RG][2];
     int sa;
   };
-  auto multiply = [&](int buf, const WSet& ws) __attribute__((always_inline)) {
-    const uint8_t* sa_buf = s_midp + buf * kMidpBufA;
+  auto multiply = [&](int buf, int b, const WSet& ws) __attribute__((always_inline)) {
+    const uint8_t* sa_buf = s_midp + buf * C::kBufA;
     auto read_frag = [&](int u, Frag& f) __attribute__((always_inline)) {
-      const uint8_t* rec = sa_buf + u * kMidpStepA;
 #pragma unroll
-      for (int comp = 0; comp < 2; ++comp) {
-        const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
-        const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
-        f.av[comp] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      for (int rg = 0; rg < RG; ++rg) {
+        const uint8_t* rec = sa_buf + u * C::kStepA + rg * kMidpGroupA;
+#pragma unroll
+        for (int comp = 0; comp < 2; ++comp) {
+          const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
+          const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
+          f.av[rg][comp] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+        }
       }
-      f.sa = *reinterpret_cast<const int*>(sa_buf + U * kMidpStepA + u * 256 + kb * 128 + l32 * 4);
+      // the step's row scales: byte rg of the dword is the scale of row 32 rg + l32 (block kb)
+      f.sa = *reinterpret_cast<const int*>(sa_buf + U * C::kStepA + u * 256 + kb * 128 + l32 * 4);
     };
+    // the batch's scale dwords: blocks 4 i .. 4 i + 3 of the record in dword i; with four steps per batch the odd
+    // batches take the record's second half
+    const bool second = U == 4 && (b & 1);
+    const uint32_t sd0 = (uint32_t)(second ? ws.sc[2] : ws.sc[0]), sd1 = (uint32_t)(second ? ws.sc[3] : ws.sc[1]);
     Frag f[3];
     read_frag(0, f[0]);
     read_frag(1, f[1]);
@@ -368,27 +392,42 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
       __builtin_amdgcn_sched_barrier(0);
       const Frag& c = f[u % 3];
       const int sa2 = c.sa - shift * 0x01010101;  // beta = alpha / 2^shift (the bytes are >= 4)
-      const uint32_t sw = (uint32_t)(u < 2 ? ws.sc[0] : u < 4 ? ws.sc[1] : u < 6 ? ws.sc[2] : ws.sc[3]);
+      const uint32_t sw = u < 2 ? sd0 : u < 4 ? sd1 : (uint32_t)(u < 6 ? ws.sc[2] : ws.sc[3]);
       const int sb = (int)((sw >> (16 * (u & 1) + 8 * kb)) & 0xFFu);  // scale byte of block 2u + kb of the batch
       const v8i bw = {ws.w[u][0], ws.w[u][1], ws.w[u][2], ws.w[u][3], 0, 0, 0, 0};
-      acc = mfma_mid<0, 2>(c.av[0], bw, acc, c.sa, sb);
-      acc = mfma_mid<0, 2>(c.av[1], bw, acc, sa2, sb);
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg) {
+#pragma unroll
+        for (int comp = 0; comp < 2; ++comp) {
+          const int sx = comp ? sa2 : c.sa;
+          if (rg == 0) acc[rg] = mfma_mid<0, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
+          else if (rg == 1) acc[rg] = mfma_mid<1, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
+          else if (rg == 2) acc[rg] = mfma_mid<2, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
+          else acc[rg] = mfma_mid<3, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
+        }
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
   };
   // the registers of `cur` pass through the wait statement, so that nothing that reads them can be placed above it
   auto wait_batch = [&](WSet& cur) __attribute__((always_inline)) {
-    asm volatile("s_waitcnt vmcnt(%9)\n\ts_barrier"
-                 : "+v"(cur.w[0]), "+v"(cur.w[1]), "+v"(cur.w[2]), "+v"(cur.w[3]), "+v"(cur.w[4]), "+v"(cur.w[5]),
-                   "+v"(cur.w[6]), "+v"(cur.w[7]), "+v"(cur.sc)
-                 : "n"(kYounger)
-                 : "memory");
+    if constexpr (U == 8)
+      asm volatile("s_waitcnt vmcnt(%9)\n\ts_barrier"
+                   : "+v"(cur.w[0]), "+v"(cur.w[1]), "+v"(cur.w[2]), "+v"(cur.w[3]), "+v"(cur.w[4]), "+v"(cur.w[5]),
+                     "+v"(cur.w[6]), "+v"(cur.w[7]), "+v"(cur.sc)
+                   : "n"(kYounger)
+                   : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(%5)\n\ts_barrier"
+                   : "+v"(cur.w[0]), "+v"(cur.w[1]), "+v"(cur.w[2]), "+v"(cur.w[3]), "+v"(cur.sc)
+                   : "n"(kYounger)
+                   : "memory");
   };
   auto phase = [&](int b, WSet& cur, WSet& far) __attribute__((always_inline)) {
     wait_batch(cur);
     load_w(b + D, far);
     fill_a(b + D);
-    multiply(b % NSETS, cur);
+    multiply(b % NSETS, b, cur);
   };
 #pragma unroll
   for (int j = 0; j < D; ++j) {
@@ -407,24 +446,27 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_midp_kernel(const uint8_t
   // D: column l%32, row 8*(r/4) + 4*(l/32) + r%4 in register r
   if (n < N) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = 8 * (r >> 2) + 4 * kb + (r & 3);
-      if (m < M) {
-        if (out_bf16)
-          reinterpret_cast<uint16_t*>(y)[(int64_t)m * ldy + n] = f32_to_bf16_bits(acc[r]);
-        else
-          reinterpret_cast<float*>(y)[(int64_t)m * ldy + n] = acc[r];
+    for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = 32 * rg + 8 * (r >> 2) + 4 * kb + (r & 3);
+        if (m < M) {
+          if (out_bf16)
+            reinterpret_cast<uint16_t*>(y)[(int64_t)m * ldy + n] = f32_to_bf16_bits(acc[rg][r]);
+          else
+            reinterpret_cast<float*>(y)[(int64_t)m * ldy + n] = acc[rg][r];
+        }
       }
-    }
   }
 }
 
+template <int RG, int U>
 static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* Wp, const uint8_t* Ep, void* y,
                        int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
-  constexpr int lds = (kMidpDepth + 1) * kMidpBufA;
-  static bool attr_set = false;
+  constexpr int lds = MidpCfg<RG, U>::kLds;
+  static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth, RG, U>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
@@ -434,8 +476,8 @@ static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W
   const int64_t rounds = cdiv(tiles, 8 * 256);
   const int64_t tpw = cdiv(tiles, 256 * rounds);
   const int bn = tpw >= 5 ? (int)tpw * 16 : kMidBN;
-  hipLaunchKernelGGL(gemm_w4_midp_kernel<kMidpDepth>, dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads), lds, stream, qop,
-                     sa_t, Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift, bn);
+  hipLaunchKernelGGL((gemm_w4_midp_kernel<kMidpDepth, RG, U>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads), lds,
+                     stream, qop, sa_t, Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift, bn);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }
@@ -487,7 +529,11 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
     if (l.Mpad == 64) return launch_mid<2, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
     return launch_mid<4, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   }
-  if (l.Mpad == 32 && w_packed) return launch_midp(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  if (w_packed) {  // weights straight into operand registers, hand-counted loads
+    if (l.Mpad == 32) return launch_midp<1, 8>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 64) return launch_midp<2, 8>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    return launch_midp<4, 4>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  }
   if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   return launch_mid<4, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);

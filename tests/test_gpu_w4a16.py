@@ -130,6 +130,7 @@ PACKED_SHAPES = [
     (1, 8192, 512), (1, 512, 40), (2, 2048, 4096), (3, 1024, 300), (4, 512, 8300),          # register-operand kernel
     (9, 1024, 300), (32, 8192, 700), (24, 2048, 8300), (64, 1024, 300), (128, 1536, 4200),  # LDS-staged weight stream
     (24, 512, 17590), (32, 1024, 28672),   # up to 32 rows, many channels (more workgroups than CUs)
+    (40, 512, 700), (64, 8192, 300), (100, 1024, 17590), (128, 512, 40),   # 33..128 rows: two and four row groups
     (256, 512, 256), (300, 2048, 600), (700, 512, 1000),                                     # many-row pipeline
 ]
 
