@@ -226,13 +226,14 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   }
 }
 
-// ------------------------------------------------------------------ up to 32 rows on packed weights
+// ------------------------------------------------------------------ 5..128 rows on packed weights
 // The packed layout (msd_pack_weights_w4) holds the B operand of the 32x32x64 instruction as two contiguous
 // 512-byte runs per wave and K step (the halves of the kilobytes of two adjacent channel tiles), so the weights go
 // HBM -> registers in operand order with no LDS stage, in batches of eight K steps (8 KB per wave).  The activation
-// operands (shared by the four waves, hot in L2) go through LDS.  One wave per SIMD: nothing hides an LDS read but
-// the wave's own MFMAs, so the fragments of K step u + 2 are requested before the MFMAs of step u (three rotating
-// fragment sets); left alone the compiler requests all 32 reads of a batch up front.
+// operands (shared by the four multiplying waves, hot in L2) go through LDS, filled by four loader waves.  Left
+// alone the compiler requests all LDS reads of a batch up front; here the operands of MFMA t + 4 are requested before
+// MFMA t (a rotating window of five six-register operands), which also keeps every instance under 256 registers so
+// that the loader waves fit beside the multiplying ones.
 constexpr int kMidpGroupA = 3072;  // operand bytes of a 32-row group per K step
 constexpr int kMidpDepth = 2;      // batches in flight behind the current one (3 and 4 measured 4 % and 7 % slower)
 // RG groups of 32 rows, U K steps per batch: 8 steps for one or two groups, 4 for four (three LDS buffers of a
@@ -291,7 +292,7 @@ __device__ __forceinline__ uint64_t midp_uniform(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-template <int D, int RG, int U, int LW>
+template <int D, int RG, int U, int LW, int WN>
 __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(const uint8_t* __restrict__ qop,
                                                                    const uint8_t* __restrict__ sa_t,
                                                                    const uint8_t* __restrict__ Wp,
@@ -305,8 +306,8 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   static_assert(U == 8 || U == 4, "a batch is a whole or half a 16-block scale record");
   extern __shared__ __attribute__((aligned(16))) uint8_t s_midp[];  // [NSETS][A batch]
   // LW = 4: four further waves issue the operand fills (wave 4 + i those of wave i) and do nothing else: the rate at
-  // which a CU pulls data grows with the number of waves that issue loads, and the registers allow a second wave per
-  // SIMD only with one row group.
+  // which a CU pulls data grows with the number of waves that issue loads (8192 x 28672: 37.2 -> 30.6 us at 32 rows,
+  // 47.8 -> 36.6 at 64, 70.3 -> 50.2 at 128).  A second wave per SIMD needs the kernel under 256 registers.
   static_assert(LW == 0 || LW == kMidThreads / 64, "one loader wave per multiplying wave, or none");
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -379,54 +380,45 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   for (int rg = 0; rg < RG; ++rg)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[rg][r] = 0.f;
-  struct Frag {
-    v8i av[RG][2];
-    int sa;
-  };
   auto multiply = [&](int buf, int b, const WSet& ws) __attribute__((always_inline)) {
     const uint8_t* sa_buf = s_midp + buf * C::kBufA;
-    auto read_frag = [&](int u, Frag& f) __attribute__((always_inline)) {
-#pragma unroll
-      for (int rg = 0; rg < RG; ++rg) {
-        const uint8_t* rec = sa_buf + u * C::kStepA + rg * kMidpGroupA;
-#pragma unroll
-        for (int comp = 0; comp < 2; ++comp) {
-          const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
-          const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
-          f.av[rg][comp] = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
-        }
-      }
-      // the step's row scales: byte rg of the dword is the scale of row 32 rg + l32 (block kb)
-      f.sa = *reinterpret_cast<const int*>(sa_buf + U * C::kStepA + u * 256 + kb * 128 + l32 * 4);
-    };
     // the batch's scale dwords: blocks 4 i .. 4 i + 3 of the record in dword i; with four steps per batch the odd
     // batches take the record's second half
     const bool second = U == 4 && (b & 1);
     const uint32_t sd0 = (uint32_t)(second ? ws.sc[2] : ws.sc[0]), sd1 = (uint32_t)(second ? ws.sc[3] : ws.sc[1]);
-    Frag f[3];
-    read_frag(0, f[0]);
-    read_frag(1, f[1]);
+    // The operands of one MFMA (a row group's component of a K step: six registers) are the unit of the read-ahead:
+    // a window of WN units rotates, unit t + WN - 1 is requested before the MFMA of unit t.
+    constexpr int UPS = RG * 2, T = U * UPS;  // units per K step and per batch
+    v8i win[WN];
+    constexpr int SV = (WN - 1 + UPS - 1) / UPS + 1;  // K steps whose row scales are live at once
+    int sav[SV];
+    auto read_unit = [&](int t, v8i& d) __attribute__((always_inline)) {
+      const int u = t / UPS, rg = (t / 2) % RG, comp = t & 1;
+      const uint8_t* rec = sa_buf + u * C::kStepA + rg * kMidpGroupA;
+      const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
+      const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
+      d = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+      // the step's row scales come with its first unit: byte rg of the dword is the scale of row 32 rg + l32 (block kb)
+      if (t % UPS == 0) sav[u % SV] = *reinterpret_cast<const int*>(sa_buf + U * C::kStepA + u * 256 + kb * 128 + l32 * 4);
+    };
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int t = 0; t < WN - 1; ++t) read_unit(t, win[t]);
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
       __builtin_amdgcn_sched_barrier(0);
-      if (u + 2 < U) read_frag(u + 2, f[(u + 2) % 3]);
+      if (t + WN - 1 < T) read_unit(t + WN - 1, win[(t + WN - 1) % WN]);
       __builtin_amdgcn_sched_barrier(0);
-      const Frag& c = f[u % 3];
-      const int sa2 = c.sa - shift * 0x01010101;  // beta = alpha / 2^shift (the bytes are >= 4)
+      const int u = t / UPS, rg = (t / 2) % RG, comp = t & 1;
+      const int sa1 = sav[u % SV];
+      const int sx = comp ? sa1 - shift * 0x01010101 : sa1;  // beta = alpha / 2^shift (the bytes are >= 4)
       const uint32_t sw = u < 2 ? sd0 : u < 4 ? sd1 : (uint32_t)(u < 6 ? ws.sc[2] : ws.sc[3]);
       const int sb = (int)((sw >> (16 * (u & 1) + 8 * kb)) & 0xFFu);  // scale byte of block 2u + kb of the batch
       const v8i bw = {ws.w[u][0], ws.w[u][1], ws.w[u][2], ws.w[u][3], 0, 0, 0, 0};
-#pragma unroll
-      for (int rg = 0; rg < RG; ++rg) {
-#pragma unroll
-        for (int comp = 0; comp < 2; ++comp) {
-          const int sx = comp ? sa2 : c.sa;
-          if (rg == 0) acc[rg] = mfma_mid<0, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
-          else if (rg == 1) acc[rg] = mfma_mid<1, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
-          else if (rg == 2) acc[rg] = mfma_mid<2, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
-          else acc[rg] = mfma_mid<3, 2>(c.av[rg][comp], bw, acc[rg], sx, sb);
-        }
-      }
+      const v8i& av = win[t % WN];
+      if (rg == 0) acc[rg] = mfma_mid<0, 2>(av, bw, acc[rg], sx, sb);
+      else if (rg == 1) acc[rg] = mfma_mid<1, 2>(av, bw, acc[rg], sx, sb);
+      else if (rg == 2) acc[rg] = mfma_mid<2, 2>(av, bw, acc[rg], sx, sb);
+      else acc[rg] = mfma_mid<3, 2>(av, bw, acc[rg], sx, sb);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -481,13 +473,13 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   }
 }
 
-template <int RG, int U, int LW>
+template <int RG, int U, int LW, int WN>
 static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* Wp, const uint8_t* Ep, void* y,
                        int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
   constexpr int lds = MidpCfg<RG, U>::kLds;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth, RG, U, LW>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
@@ -497,7 +489,7 @@ static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W
   const int64_t rounds = cdiv(tiles, 8 * 256);
   const int64_t tpw = cdiv(tiles, 256 * rounds);
   const int bn = tpw >= 5 ? (int)tpw * 16 : kMidBN;
-  hipLaunchKernelGGL((gemm_w4_midp_kernel<kMidpDepth, RG, U, LW>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads + LW * 64), lds,
+  hipLaunchKernelGGL((gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads + LW * 64), lds,
                      stream, qop, sa_t, Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift, bn);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -552,9 +544,9 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
   }
   if (w_packed) {  // weights straight into operand registers, hand-counted loads
     // (one row group: loader waves measured 30.6 against 31.7 us at 32 rows, 28.9 against 30.6 at 8)
-    if (l.Mpad == 32) return launch_midp<1, 8, 4>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-    if (l.Mpad == 64) return launch_midp<2, 8, 0>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
-    return launch_midp<4, 4, 0>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 32) return launch_midp<1, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 64) return launch_midp<2, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    return launch_midp<4, 4, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
   }
   if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);

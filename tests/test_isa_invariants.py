@@ -57,7 +57,7 @@ def mid_isa(tmp_path_factory):
 
 
 # <depth, row groups, steps per batch, loader waves>
-@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4E", "ILi2ELi2ELi8ELi0E", "ILi2ELi4ELi4ELi0E"])
+@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5E", "ILi2ELi2ELi8ELi4ELi5E", "ILi2ELi4ELi4ELi4ELi5E"])
 def test_midp_loads_are_not_touched_before_their_wait(mid_isa, inst):
     txt = mid_isa
     name, body = _kernel_body(txt, "gemm_w4_midp_kernel" + inst)
