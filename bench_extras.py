@@ -448,11 +448,15 @@ def leg_mla(msd, synth, time_calls, dev):
             f = lambda i: msd.msd_mla_decode_int8kv(q, sets[i % n][0], sets[i % n][1], msd.MSD_PER_TOKEN,
                                                     1.0 / 192.0 ** 0.5, out=o, ws=ws, prepare=True)
             us = time_calls(f, 2 * n)
+            fc = lambda i: msd.msd_dequant_mla_decode_int8kv(q, sets[i % n][0], sets[i % n][1], msd.MSD_PER_TOKEN,
+                                                             1.0 / 192.0 ** 0.5, out=o, ws=ws, prepare=True)
+            us_c = time_calls(fc, 2 * n)  # the dequantise-then-BF16 comparison kernel, same protocol
             byts = B * L * d + 4 * B * L
             ops = 2.0 * 2 * B * Hq * L * (576 + 512)
             out.append({"B": B, "Hq": Hq, "L": L, "us": round(us, 1), "GBps": round(byts / us / 1e3, 1),
                         "hbm_frac": round(byts / us / 1e3 / HBM, 4), "exec_TOPS": round(ops / us / 1e6, 1),
-                        "int8_mfma_frac": round(ops / us / 1e6 / INT8_TOPS, 4)})
+                        "int8_mfma_frac": round(ops / us / 1e6 / INT8_TOPS, 4), "dequant_us": round(us_c, 1),
+                        "speedup_vs_dequant": round(us_c / us, 3)})
             if L <= 4096:  # accuracy against an fp64 attention over the dequantised rows (two batch entries)
                 C0, s0 = sets[0]
                 msd.msd_mla_decode_int8kv(q, C0, s0, msd.MSD_PER_TOKEN, 1.0 / 192.0 ** 0.5, out=o, ws=ws)

@@ -349,6 +349,20 @@ int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const
 size_t msd_mla_decode_int8kv_workspace_bytes(int B, int Hq, int64_t L);
 
 /*
+ * Comparison kernel for msd_mla_decode_int8kv: the conventional path of paper Sec. 4.1 on the latent-cache
+ * shape (every cached byte lifted from INT8 to BF16 before Q C^T and P C), as one fused kernel plus the merge
+ * of the KV splits.  Same arguments, layouts, workspace size and errors; taps are ignored.  The bytes become
+ * BF16 exactly, both products run on BF16 matrix instructions with fp32 accumulation, P (times the row's scale
+ * in per-token mode) is rounded to BF16; a per-token scale multiplies the score column in fp32, a per-channel
+ * scale is folded into Q (rounded to BF16) and its first 512 entries multiply the output.  A workgroup serves
+ * 16 heads; further heads are further workgroups that read the same rows again.
+ */
+int msd_dequant_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale,
+                                  int scale_mode, int B, int Hq, int dk, int dv, float sm_scale,
+                                  const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                                  size_t workspace_bytes, const msd_debug_taps* taps, void* stream);
+
+/*
  * Comparison kernel for msd_attn_decode_int8kv: the conventional path of paper Sec. 4.1 (K and V
  * lifted from INT8 to BF16 before Q K^T and P V), as one fused kernel.  Same arguments, layouts,
  * workspace size (msd_attn_decode_int8kv_workspace_bytes) and errors; taps are ignored.  K and V

@@ -86,6 +86,7 @@ def lib():
                                              vp, vp]
         L.msd_mla_decode_int8kv.argtypes = [vp, vp, i64, vp, ci, ci, ci, ci, ci, C.c_float, vp, i64, vp, ci, vp, sz,
                                             vp, vp]
+        L.msd_dequant_mla_decode_int8kv.argtypes = L.msd_mla_decode_int8kv.argtypes
         L.msd_mla_decode_int8kv_workspace_bytes.argtypes = [ci, ci, i64]
         L.msd_mla_decode_int8kv_workspace_bytes.restype = sz
         L.msd_moe_gemm_w8a16.argtypes = [vp, i64, i64, i64, vp, ci, vp, vp, i64, vp, ci, i64, vp, sz, vp]
@@ -106,7 +107,7 @@ def lib():
                      "msd_dequant_gemm_w8a16", "msd_dequant_gemm_w4a16", "msd_stream_read", "msd_probe_mfma_w8a16",
                      "msd_probe_mfma_w4a16", "msd_decompose_variant", "msd_gemm_w8a16_variant",
                      "msd_gemm_w4a16_variant", "msd_dequant_attn_decode_int8kv", "msd_moe_gemm_w8a16",
-                     "msd_moe_gemm_w4a16", "msd_mla_decode_int8kv"):
+                     "msd_moe_gemm_w4a16", "msd_mla_decode_int8kv", "msd_dequant_mla_decode_int8kv"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -507,3 +508,26 @@ def msd_mla_decode_int8kv(q, C_lat, scale, scale_mode, sm_scale, kv_len=None, ou
                         "msd_mla_decode_int8kv", out)
     _check(L.msd_mla_decode_int8kv(*args), "msd_mla_decode_int8kv")
     return (out, keep) if taps else out
+
+
+def msd_dequant_mla_decode_int8kv(q, C_lat, scale, scale_mode, sm_scale, kv_len=None, out_dtype=torch.float32,
+                                  out=None, ws=None, prepare=False):
+    """The dequantise-then-BF16 comparison kernel on the arguments of msd_mla_decode_int8kv (no taps)."""
+    _dev(q, torch.bfloat16, "q"); _dev(C_lat, torch.int8, "C_lat"); _dev(scale, torch.float32, "scale")
+    B, Hq, dk = q.shape
+    _, Lmax, ld = C_lat.shape
+    assert q.is_contiguous() and C_lat.is_contiguous() and scale.is_contiguous()
+    L = lib()
+    if out is None:
+        out = torch.empty((B, Hq, 512), dtype=out_dtype, device=q.device)
+    if ws is None:
+        ws = workspace(L.msd_mla_decode_int8kv_workspace_bytes(B, Hq, Lmax), q.device)
+    if kv_len is not None:
+        _dev(kv_len, torch.int32, "kv_len")
+    args = (_ptr(q), _ptr(C_lat), ld, _ptr(scale), scale_mode, B, Hq, dk, 512, float(sm_scale), _ptr(kv_len), Lmax,
+            _ptr(out), _out_code(out.dtype), _ptr(ws), ws.numel(), None, _stream())
+    if prepare:
+        return Prepared(L.msd_dequant_mla_decode_int8kv, args, (q, C_lat, scale, kv_len, out, ws),
+                        "msd_dequant_mla_decode_int8kv", out)
+    _check(L.msd_dequant_mla_decode_int8kv(*args), "msd_dequant_mla_decode_int8kv")
+    return out

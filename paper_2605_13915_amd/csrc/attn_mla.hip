@@ -23,6 +23,7 @@
 //       more:           8 x 1 x 1, 64 heads per workgroup, further heads over blockIdx.y.
 //   * One workgroup per CU; the KV length is split over workgroups and over the token streams inside
 //     one; every (split, stream) writes its own partial (m, l, O) and a last kernel merges them.
+#include <algorithm>
 #include <type_traits>
 
 #include "attn_common.hpp"
@@ -652,13 +653,315 @@ int launch_mla_mode(const MlaParams& p, const MlaPlan& pl, hipStream_t stream) {
   }
 }
 
+// ------------------------------------------------------------------ comparison kernel (latent cache)
+// The conventional path of Sec. 4.1 on the latent-cache shape, as one fused kernel: every cache byte becomes BF16
+// on the vector ALU (exact), Q C^T and P C run on v_mfma_f32_16x16x32_bf16 with fp32 accumulation, P (times the
+// row's scale in per-token mode) is rounded to BF16; a per-channel scale is folded into Q (rounded to BF16) and
+// multiplies the output.  Split plan, partial results and their merge are those of the MSD kernel.
+//   A workgroup serves 16 heads (the rows of one A fragment) of a batch entry over one KV split; its four waves
+//   take alternate 32-token tiles and each keeps the 16 x 512 output of its tokens in registers (128 per lane):
+//   more heads per wave do not fit the register file, so further heads are further workgroups (blockIdx.y) that
+//   read the same rows again, from L2.  Operands come straight from global memory in fragment order, as in the
+//   grouped-query comparison kernel: the key reading as 16-byte loads (lane = token 16 tt + j, channels
+//   64 s + 16 g ..), the value reading as 8-byte loads (channels 128 cb + 8 j .. of token 16 tt + 4 g + jq, so that
+//   the bytes of the eight tokens of a B fragment sit in one lane).
+constexpr int kCmpTile = 32;      // tokens per wave and step: the contraction extent of the P C product
+constexpr int kCmpWaves = 4;
+constexpr int kCmpQPitch = 584;   // BF16 elements per query row in LDS (576 + pad)
+constexpr int kCmpPPitch = 40;    // BF16 elements per head row of a wave's P tile (32 + pad)
+constexpr size_t kCmpLds = 16 * kCmpQPitch * 2 + kCmpWaves * 16 * kCmpPPitch * 2 + kCmpWaves * 16 * kLatV * 4 +
+                           2 * kCmpWaves * 16 * 4;
+
+typedef float cmp_v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 cmp_v2bf __attribute__((ext_vector_type(2)));
+union CmpBf8 {
+  uint32_t u[4];
+  v8bf v;
+};
+__device__ __forceinline__ uint32_t cmp_pack2(float lo, float hi) {  // RNE, hardware convert
+  const cmp_v2f f = {lo, hi};
+  const cmp_v2bf b = __builtin_convertvector(f, cmp_v2bf);
+  return *reinterpret_cast<const uint32_t*>(&b);
+}
+__device__ __forceinline__ float cmp_byte(uint32_t w, int i) {  // signed byte i of w as float
+  return (float)(int)(int8_t)((w >> (8 * i)) & 0xFFu);
+}
+
+template <bool PER_TOKEN>
+__global__ __launch_bounds__(kCmpWaves * 64) void attn_mla_dequant_kernel(MlaParams p) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t s_cmp[];
+  uint16_t* sQ = reinterpret_cast<uint16_t*>(s_cmp);                                     // [16][kCmpQPitch]
+  uint16_t* sP = sQ + 16 * kCmpQPitch;                                                   // [waves][16][kCmpPPitch]
+  float* sO = reinterpret_cast<float*>(sP + kCmpWaves * 16 * kCmpPPitch);                // [waves][16][512]
+  float* sM = sO + kCmpWaves * 16 * kLatV;                                               // [waves][16]
+  float* sL = sM + kCmpWaves * 16;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int b = blockIdx.x / p.nsplit, split = blockIdx.x % p.nsplit;
+  const int h0 = blockIdx.y * 16;
+  int64_t len = p.kv_len ? (int64_t)p.kv_len[b] : p.L;
+  len = max((int64_t)0, min(len, p.L));
+  const int64_t t_begin = (int64_t)split * p.tokens_per_split;
+  const int64_t t_end = min(len, t_begin + p.tokens_per_split);
+  const int8_t* Cb = p.C + (int64_t)b * p.L * p.ld;
+  const float* sb = p.scale + (int64_t)b * p.L;  // per token only
+
+  // ---- the query rows as BF16 (per-channel mode: Q * scale rounded to BF16), zero rows past the last head
+  for (int idx = tid; idx < 16 * kLatK; idx += kCmpWaves * 64) {
+    const int h = idx / kLatK, c = idx % kLatK;
+    uint16_t v = 0;
+    if (h0 + h < p.Hq) {
+      v = p.q[((int64_t)b * p.Hq + h0 + h) * kLatK + c];
+      if (!PER_TOKEN) v = f32_to_bf16_bits(__uint_as_float((uint32_t)v << 16) * p.scale[c]);
+    }
+    sQ[h * kCmpQPitch + c] = v;
+  }
+  __syncthreads();
+
+  const v4f zero4f = {0.f, 0.f, 0.f, 0.f};
+  // per-lane state as a D lane: heads h0 + 4 g + r; output channels 128 cb + 8 j + c
+  float m_run[4], l_run[4], o_run[4][8][4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    m_run[r] = -INFINITY;
+    l_run[r] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o_run[cb][c][r] = 0.f;
+  }
+  const int64_t last = max(t_end - 1, (int64_t)0);
+  const int64_t t_first = t_begin + (int64_t)wave * kCmpTile;
+  constexpr int64_t kStride = kCmpWaves * kCmpTile;
+  v4i kx[2][9];      // [tt][s]: channels 64 s + 16 g .. + 15 of token 16 tt + j
+  v2i vx[4][2][4];   // [jq][tt][cb]: channels 128 cb + 8 j .. + 7 of token 16 tt + 4 g + jq
+  float sk[2];       // the row scale of token 16 tt + j (per token)
+  auto load_k = [&](int64_t t0) {
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int64_t tok = min(t0 + 16 * tt + j, last);
+#pragma unroll
+      for (int s = 0; s < 9; ++s)
+        kx[tt][s] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(Cb + tok * p.ld + 64 * s + 16 * g));
+      sk[tt] = PER_TOKEN ? sb[tok] : 1.f;
+    }
+  };
+  auto load_v = [&](int64_t t0) {
+#pragma unroll
+    for (int jq = 0; jq < 4; ++jq)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const int64_t tok = min(t0 + 16 * tt + 4 * g + jq, last);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+          vx[jq][tt][cb] = *reinterpret_cast<const v2i*>(Cb + tok * p.ld + 128 * cb + 8 * j);
+      }
+  };
+  if (t_first < t_end) {
+    load_k(t_first);
+    load_v(t_first);
+  }
+  uint16_t* sPw = sP + wave * 16 * kCmpPPitch;
+  for (int64_t t0 = t_first; t0 < t_end; t0 += kStride) {
+    bool live[2];
+    float sc_tok[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      live[tt] = t0 + 16 * tt + j < t_end;
+      sc_tok[tt] = sk[tt];
+    }
+    // ---- key reading to BF16, S = Q C^T
+    v4f sd[2] = {zero4f, zero4f};
+#pragma unroll
+    for (int s = 0; s < 9; ++s)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        CmpBf8 qa;
+        const uint4 qv = *reinterpret_cast<const uint4*>(&sQ[j * kCmpQPitch + 64 * s + 16 * g + 8 * h]);
+        qa.u[0] = qv.x; qa.u[1] = qv.y; qa.u[2] = qv.z; qa.u[3] = qv.w;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          CmpBf8 kb;
+#pragma unroll
+          for (int d = 0; d < 2; ++d) {
+            const uint32_t w = (uint32_t)kx[tt][s][2 * h + d];
+            kb.u[2 * d] = cmp_pack2(cmp_byte(w, 0), cmp_byte(w, 1));
+            kb.u[2 * d + 1] = cmp_pack2(cmp_byte(w, 2), cmp_byte(w, 3));
+          }
+          sd[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa.v, kb.v, sd[tt], 0, 0, 0);
+        }
+      }
+    if (t0 + kStride < t_end) load_k(t0 + kStride);  // the key registers are free: next tile under the rest of this one
+    // ---- online softmax; P (times the row scale) to BF16
+    float corr[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float sc[2];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const float v = sd[tt][r] * (p.sm_scale_log2 * sc_tok[tt]);
+        sc[tt] = live[tt] ? v : -INFINITY;
+        mx = fmaxf(mx, sc[tt]);
+      }
+      mx = row16_max(mx);
+      const float m_new = fmaxf(m_run[r], mx);
+      corr[r] = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[r] - m_new);
+      m_run[r] = m_new;
+      float lsum = 0.f;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const float pr = live[tt] ? __builtin_amdgcn_exp2f(sc[tt] - m_new) : 0.f;
+        lsum += pr;
+        sPw[(4 * g + r) * kCmpPPitch + 16 * tt + j] = f32_to_bf16_bits(PER_TOKEN ? pr * sc_tok[tt] : pr);
+      }
+      l_run[r] = l_run[r] * corr[r] + lsum;
+    }
+    __builtin_amdgcn_wave_barrier();
+    CmpBf8 pa;
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      const uint2 v = *reinterpret_cast<const uint2*>(&sPw[j * kCmpPPitch + 16 * t2 + 4 * g]);
+      pa.u[2 * t2] = v.x;
+      pa.u[2 * t2 + 1] = v.y;
+    }
+    __builtin_amdgcn_wave_barrier();
+    // ---- value reading to BF16 (channel 128 cb + 8 j + c of the eight tokens this lane holds), O += P C
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        CmpBf8 vb;
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+          float f[4];
+#pragma unroll
+          for (int jq = 0; jq < 4; ++jq) f[jq] = cmp_byte((uint32_t)vx[jq][t2][cb][c >> 2], c & 3);
+          vb.u[2 * t2] = cmp_pack2(f[0], f[1]);
+          vb.u[2 * t2 + 1] = cmp_pack2(f[2], f[3]);
+        }
+        const v4f od = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.v, vb.v, zero4f, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o_run[cb][c][r] = o_run[cb][c][r] * corr[r] + od[r];
+      }
+    if (t0 + kStride < t_end) load_v(t0 + kStride);
+  }
+
+  // ---- merge the waves of this workgroup; write the final rows (one split) or the split's partial (m, l, O)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const float lt = row16_sum(l_run[r]);
+    const int hs = 4 * g + r;
+    if (j == 0) {
+      sM[wave * 16 + hs] = m_run[r];
+      sL[wave * 16 + hs] = lt;
+    }
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) sO[(wave * 16 + hs) * kLatV + 128 * cb + 8 * j + c] = o_run[cb][c][r];
+  }
+  __syncthreads();
+  const int nh_here = min(16, p.Hq - h0);
+  for (int idx = tid; idx < nh_here * kLatV; idx += kCmpWaves * 64) {
+    const int hl = idx / kLatV, c = idx % kLatV;
+    float ms = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kCmpWaves; ++w) ms = fmaxf(ms, sM[w * 16 + hl]);
+    float o = 0.f, l = 0.f;
+#pragma unroll
+    for (int w = 0; w < kCmpWaves; ++w) {
+      const float mw = sM[w * 16 + hl];
+      const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - ms);
+      o += sO[(w * 16 + hl) * kLatV + c] * wgt;
+      l += sL[w * 16 + hl] * wgt;
+    }
+    const int64_t orow = (int64_t)b * p.Hq + h0 + hl;
+    if (p.nparts == 1) {
+      float v = l > 0.f ? __fdiv_rn(o, l) : 0.f;
+      if (!PER_TOKEN) v *= p.scale[c];
+      if (p.out_bf16)
+        reinterpret_cast<uint16_t*>(p.out)[orow * kLatV + c] = f32_to_bf16_bits(v);
+      else
+        reinterpret_cast<float*>(p.out)[orow * kLatV + c] = v;
+    } else {
+      const int64_t pr = ((int64_t)b * p.nparts + split) * p.Hq + h0 + hl;
+      p.part_o[pr * kLatV + c] = o;
+      if (c == 0) {
+        p.part_m[pr] = ms;
+        p.part_l[pr] = l;
+      }
+    }
+  }
+}
+
+// KV splits of the comparison kernel: about one workgroup per CU, every wave of a split at least two tiles
+struct MlaCmpPlan {
+  int head_blocks, nsplit;
+  int64_t tokens_per_split;
+};
+MlaCmpPlan mla_cmp_plan(int B, int Hq, int64_t L) {
+  MlaCmpPlan pl{};
+  pl.head_blocks = (Hq + 15) / 16;
+  int64_t ns = cdiv((int64_t)kMlaTargetWgs, (int64_t)B * pl.head_blocks);
+  const int64_t max_by_len = max((int64_t)1, L / (2 * kCmpWaves * kCmpTile));
+  ns = max((int64_t)1, min(min(ns, max_by_len), (int64_t)16));
+  pl.nsplit = (int)ns;
+  const int64_t tps = cdiv(L > 0 ? L : 1, ns);
+  pl.tokens_per_split = cdiv(tps, (int64_t)kCmpWaves * kCmpTile) * (kCmpWaves * kCmpTile);
+  return pl;
+}
+
 }  // namespace
+
+static size_t mla_partial_bytes(size_t rows) { return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256); }
 
 size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L) {
   const size_t rows = (size_t)B * Hq * mla_plan(B, Hq, L).nparts;
   const size_t qrows = (size_t)B * Hq;
-  return align_up(rows * kLatV * 4, 256) + 2 * align_up(rows * 4, 256) + 2 * align_up(qrows * kLatK, 256) +
-         align_up(qrows * 4, 256);
+  const size_t msd = mla_partial_bytes(rows) + 2 * align_up(qrows * kLatK, 256) + align_up(qrows * 4, 256);
+  // the comparison kernel shares the entry point's workspace contract (it never needs more in practice)
+  return std::max(msd, mla_partial_bytes((size_t)B * Hq * mla_cmp_plan(B, Hq, L).nsplit));
+}
+
+int launch_attn_mla_dequant(const AttnMlaArgs& a, hipStream_t stream) {
+  const MlaCmpPlan pl = mla_cmp_plan(a.B, a.Hq, a.L);
+  MlaParams p{};
+  p.q = a.q; p.C = a.C; p.scale = a.scale; p.kv_len = a.kv_len;
+  p.B = a.B; p.Hq = a.Hq; p.L = a.L; p.ld = a.ld;
+  p.nsplit = pl.nsplit;
+  p.nparts = pl.nsplit;
+  p.tokens_per_split = pl.tokens_per_split;
+  p.sm_scale_log2 = a.sm_scale * kLog2e;
+  const size_t rows = (size_t)a.B * a.Hq * p.nparts;
+  char* ws = (char*)a.workspace;
+  p.part_o = (float*)ws;
+  p.part_m = (float*)(ws + align_up(rows * kLatV * 4, 256));
+  p.part_l = (float*)(ws + align_up(rows * kLatV * 4, 256) + align_up(rows * 4, 256));
+  p.out = a.out;
+  p.out_bf16 = a.out_bf16;
+  const bool per_token = a.scale_mode == MSD_PER_TOKEN;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_dequant_kernel<true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCmpLds));
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mla_dequant_kernel<false>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCmpLds));
+    attr_set = true;
+  }
+  const dim3 grid((unsigned)((int64_t)a.B * p.nsplit), (unsigned)pl.head_blocks);
+  if (per_token)
+    hipLaunchKernelGGL((attn_mla_dequant_kernel<true>), grid, dim3(kCmpWaves * 64), kCmpLds, stream, p);
+  else
+    hipLaunchKernelGGL((attn_mla_dequant_kernel<false>), grid, dim3(kCmpWaves * 64), kCmpLds, stream, p);
+  MSD_LAUNCH_CHECK();
+  if (p.nparts > 1) {
+    hipLaunchKernelGGL(attn_mla_combine_kernel, dim3((unsigned)(a.B * a.Hq)), dim3(128), 0, stream, p,
+                       per_token ? 0 : 1);
+    MSD_LAUNCH_CHECK();
+  }
+  return MSD_OK;
 }
 
 int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream) {

@@ -194,6 +194,8 @@ struct AttnMlaArgs {
   const msd_debug_taps* taps;
 };
 int launch_attn_mla(const AttnMlaArgs& a, hipStream_t stream);
+// the dequantise-then-BF16 comparison kernel on the same arguments (taps ignored)
+int launch_attn_mla_dequant(const AttnMlaArgs& a, hipStream_t stream);
 size_t attn_mla_workspace_bytes(int B, int Hq, int64_t L);
 
 // ---- comparison kernels (dequant_gemm.hip)

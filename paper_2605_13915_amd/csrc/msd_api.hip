@@ -529,10 +529,10 @@ size_t msd_mla_decode_int8kv_workspace_bytes(int B, int Hq, int64_t L) {
   return attn_mla_workspace_bytes(B, Hq, L) + 256;
 }
 
-int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale, int scale_mode, int B,
-                          int Hq, int dk, int dv, float sm_scale, const int32_t* kv_len, int64_t L, void* out,
-                          int out_dtype, void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
-                          void* stream) {
+static int mla_decode_impl(bool dequant, const void* q_bf16, const int8_t* C, int64_t ld, const float* scale,
+                           int scale_mode, int B, int Hq, int dk, int dv, float sm_scale, const int32_t* kv_len,
+                           int64_t L, void* out, int out_dtype, void* workspace, size_t workspace_bytes,
+                           const msd_debug_taps* taps, void* stream) {
   if (out_dtype != MSD_F32 && out_dtype != MSD_BF16) return MSD_ERR_INVALID_ARG;
   if (scale_mode != MSD_PER_TOKEN && scale_mode != MSD_PER_CHANNEL) return MSD_ERR_INVALID_ARG;
   if (B < 0 || Hq <= 0 || L < 0) return MSD_ERR_SHAPE;
@@ -559,7 +559,23 @@ int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const
   a.out_bf16 = out_dtype == MSD_BF16;
   a.workspace = workspace;
   a.taps = taps;
-  return launch_attn_mla(a, (hipStream_t)stream);
+  return dequant ? launch_attn_mla_dequant(a, (hipStream_t)stream) : launch_attn_mla(a, (hipStream_t)stream);
+}
+
+int msd_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale, int scale_mode, int B,
+                          int Hq, int dk, int dv, float sm_scale, const int32_t* kv_len, int64_t L, void* out,
+                          int out_dtype, void* workspace, size_t workspace_bytes, const msd_debug_taps* taps,
+                          void* stream) {
+  return mla_decode_impl(false, q_bf16, C, ld, scale, scale_mode, B, Hq, dk, dv, sm_scale, kv_len, L, out, out_dtype,
+                         workspace, workspace_bytes, taps, stream);
+}
+
+int msd_dequant_mla_decode_int8kv(const void* q_bf16, const int8_t* C, int64_t ld, const float* scale,
+                                  int scale_mode, int B, int Hq, int dk, int dv, float sm_scale,
+                                  const int32_t* kv_len, int64_t L, void* out, int out_dtype, void* workspace,
+                                  size_t workspace_bytes, const msd_debug_taps* /*taps*/, void* stream) {
+  return mla_decode_impl(true, q_bf16, C, ld, scale, scale_mode, B, Hq, dk, dv, sm_scale, kv_len, L, out, out_dtype,
+                         workspace, workspace_bytes, nullptr, stream);
 }
 
 int msd_dequant_gemm_w8a16(const void* x_bf16, int64_t M, int64_t K, int64_t ldx, const int8_t* W,

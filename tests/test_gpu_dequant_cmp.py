@@ -118,3 +118,53 @@ def test_dequant_attention_against_fp64_truth(msd, B, Hq, Hkv, L, mode, kv_len):
     ob = msd.msd_dequant_attn_decode_int8kv(*args, kv_len=kld, out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
     assert rel_l2(ob.float().cpu().numpy()[live], truth[live]) <= 1e-2
+
+
+MLA_CASES = [
+    # B, Hq, L, mode, kv_len, ld
+    (2, 8, 96, "token", None, 576),             # part of one head block, three tiles
+    (1, 16, 700, "token", None, 576),           # ragged last tile, several splits
+    (3, 5, 300, "token", [300, 0, 77], 576),    # ragged lengths incl. an empty entry
+    (2, 8, 260, "channel", None, 576),
+    (1, 20, 2048, "channel", [1900], 576),      # two head blocks, the second partly filled; several KV splits
+    (2, 4, 130, "token", None, 640),            # padded cache rows
+    (1, 72, 200, "token", [131], 576),          # five head blocks, one split: final rows written by the kernel
+    (1, 16, 2300, "token", [2070], 576),        # the last split leaves waves without a tile
+]
+
+
+@pytest.mark.parametrize("B,Hq,L,mode,kv_len,ld", MLA_CASES)
+def test_dequant_mla_against_fp64_truth(msd, B, Hq, L, mode, kv_len, ld):
+    """The latent-cache comparison kernel rounds P (and, per channel, Q * scale) to BF16 and is otherwise exact
+    up to fp32 accumulation: within 5e-3 of the fp64 attention over the dequantised cache, per head; and the MSD
+    kernel, whose P carries 16 bits, is the closer of the two."""
+    seed = synth.seed_for(9, B * 1000 + L + Hq + 3)
+    q = synth.queries(seed, B, Hq, 576)
+    if mode == "token":
+        Cl, sc, _, _ = synth.kv_cache_per_token(seed, B, 1, L, ld)
+        Cl, sc = np.ascontiguousarray(Cl[:, 0]), np.ascontiguousarray(sc[:, 0])
+        omode, gmode = oracle.PER_TOKEN, msd.MSD_PER_TOKEN
+    else:
+        Cl, sc, _, _ = synth.kv_cache_per_channel(seed, B, 1, L, ld)
+        Cl, sc = np.ascontiguousarray(Cl[:, 0]), np.ascontiguousarray(sc[0, :576])
+        omode, gmode = oracle.PER_CHANNEL, msd.MSD_PER_CHANNEL
+    sm = 1.0 / np.sqrt(192.0)
+    kl = None if kv_len is None else np.array(kv_len, np.int32)
+    truth = oracle.truth_mla(q, Cl, sc, omode, 512, sm, kv_len=kl)
+    args = (bf16_to_dev(q), to_dev(Cl), to_dev(sc), gmode, sm)
+    kld = None if kl is None else to_dev(kl)
+    out = msd.msd_dequant_mla_decode_int8kv(*args, kv_len=kld)
+    out_msd = msd.msd_mla_decode_int8kv(*args, kv_len=kld)
+    torch.cuda.synchronize()
+    o, om = out.cpu().numpy(), out_msd.cpu().numpy()
+    lens = [L] * B if kl is None else list(kl)
+    live = np.array([l > 0 for l in lens])
+    assert np.all(np.isfinite(o)) and np.all(o[~live] == 0)
+    for b in range(B):
+        if lens[b] > 0:
+            for h in range(Hq):
+                assert rel_l2(o[b, h], truth[b, h]) <= 5e-3, (b, h)
+    assert rel_l2(om[live], truth[live]) < rel_l2(o[live], truth[live])
+    ob = msd.msd_dequant_mla_decode_int8kv(*args, kv_len=kld, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert rel_l2(ob.float().cpu().numpy()[live], truth[live]) <= 1e-2
