@@ -292,6 +292,205 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_grouped_kernel(GemmW4Args 
 
 bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t) { return M <= 1 && K > 0 && K <= 32768; }
 
+// ------------------------------------------------------------------ one or two rows on packed weights, one launch
+// One workgroup per CU and round: each of its waves owns one 16-channel tile over the whole K range, so the
+// activation rows are decomposed once per workgroup (Alg. 2; one 32-element block per thread and pass, into LDS)
+// instead of once per 16 channels, and that fits under the waves' first weight loads: kRowsDepth batches of
+// kRowsU super-steps (24 KB per wave) are requested before the decomposition starts, the thread's first x block
+// before those.  No separate decomposition launch, nothing materialised in HBM.
+// The result is bit-identical to the kernel above: the K range is accumulated in the same four contiguous parts
+// (the K ranges of that kernel's four waves), which are then added in the same order, and the two components
+// travel in the same stacked rows.
+constexpr int kRowsMaxWaves = 8;
+constexpr int kRowsU = 2;      // super-steps (512 k) per batch
+constexpr int kRowsDepth = 3;  // batches in flight per wave
+constexpr int kRowsMaxM = 2;  // (8192 x 28672: 29.7 -> 26.2 us at one row, 30.6 -> 29.8 at two; 31.6 -> 33.6 at three: the
+                               // decomposition before the first MFMA grows with the rows)
+constexpr size_t kRowsMaxLds = 144 * 1024;
+
+// NPRE: x blocks a thread requests before its weight batches (loads complete in order: an x block requested after
+// them would wait for all of them)
+template <int NPRE>
+__global__ __launch_bounds__(kRowsMaxWaves * 64) void gemm_w4_rows_kernel(GemmW4Args a, int tpw) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t s_rows[];  // [2M][KB][24 B] | [M][KB] | [waves][4][64] f32
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = lane & 15, g = lane >> 4;
+  const int M = (int)a.M;
+  const int64_t N = a.N, KB = a.K / 32, supers = KB / 16;
+  const int64_t wtiles = (N + 15) / 16;
+  const int64_t tile_raw = (int64_t)blockIdx.x * tpw + wave;
+  const int64_t tile = min(tile_raw, wtiles - 1);  // past the end: repeats the last tile, nothing stored
+  uint8_t* sA = s_rows;
+  uint8_t* sE = sA + (size_t)2 * M * KB * 24;
+  float* s_fin = reinterpret_cast<float*>(sE + (((size_t)M * KB + 15) & ~(size_t)15)) + wave * 256;
+  const int nblocks = M * (int)KB;
+  const bool al16 = a.x_aligned != 0;
+  auto load_x = [&](int c, uint32_t (&w)[16]) {
+    const int m = c / (int)KB, bb = c - m * (int)KB;
+    const uint16_t* xb = a.x + (int64_t)m * a.ldx + (int64_t)bb * 32;
+    if (al16) {
+      const uint4* q = reinterpret_cast<const uint4*>(xb);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint4 v = q[i];
+        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) w[i] = (uint32_t)xb[2 * i] | ((uint32_t)xb[2 * i + 1] << 16);
+    }
+  };
+  auto decompose = [&](int c, const uint32_t (&w)[16]) {
+    const int m = c / (int)KB, bb = c - m * (int)KB;
+    uint32_t p1[6], p2[6];
+    const int e = mx_block_pack_fp6(w, p1, p2, a.mv);
+    uint2* d1 = reinterpret_cast<uint2*>(sA + ((size_t)m * KB + bb) * 24);
+    uint2* d2 = reinterpret_cast<uint2*>(sA + ((size_t)(M + m) * KB + bb) * 24);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+      d1[i] = make_uint2(p1[2 * i], p1[2 * i + 1]);
+      d2[i] = make_uint2(p2[2 * i], p2[2 * i + 1]);
+    }
+    sE[(size_t)m * KB + bb] = (uint8_t)(e + 127);
+  };
+  // ---- this thread's first x block, then the first weight batches, then the decomposition
+  uint32_t w0[NPRE][16];
+#pragma unroll
+  for (int i = 0; i < NPRE; ++i) load_x(min(tid + i * (int)blockDim.x, nblocks - 1), w0[i]);
+  const uint8_t* wp = a.W + tile * 1024 + lane * 16;
+  const uint8_t* wep = a.We + tile * 256 + row * 16;
+  const int64_t wq = wtiles * 1024, weq = wtiles * 256;  // bytes between K units / super-steps
+  struct Batch {
+    v4i w[kRowsU][4], sc[kRowsU];
+  };
+  auto load_w = [&](int64_t b, Batch& t) {  // batches past the end repeat the last super-step (never multiplied)
+#pragma unroll
+    for (int u2 = 0; u2 < kRowsU; ++u2) {
+      const int64_t sp = min(b * kRowsU + u2, supers - 1);
+      t.sc[u2] = *reinterpret_cast<const v4i*>(wep + sp * weq);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        t.w[u2][u] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + (4 * sp + u) * wq));
+    }
+  };
+  Batch B0, B1, B2;
+  static_assert(kRowsDepth == 3, "three rotating batches are written out below");
+  load_w(0, B0);
+  load_w(1, B1);
+  load_w(2, B2);
+#pragma unroll
+  for (int i = 0; i < NPRE; ++i)
+    if (tid + i * (int)blockDim.x < nblocks) decompose(tid + i * (int)blockDim.x, w0[i]);
+#pragma unroll 1
+  for (int c = tid + NPRE * blockDim.x; c < nblocks; c += blockDim.x) {
+    uint32_t w[16];
+    load_x(c, w);
+    decompose(c, w);
+  }
+  // the operands are in LDS; a plain __syncthreads() would also wait for the weight batches in flight
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  // ---- K loop: four contiguous parts, each its own accumulator
+  const int64_t per = (supers + 3) / 4;
+  const v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+  v4f part[4] = {zero4, zero4, zero4, zero4};
+  const int r = min(row, 2 * M - 1);  // stacked fragment row: [0, M) first component, [M, 2M) residual
+  const int comp = r >= M ? 1 : 0, m = r - comp * M;
+  const uint8_t* arow = sA + (size_t)r * KB * 24;
+  const uint8_t* erow = sE + (size_t)m * KB;
+  const int shift = a.mv.shift * comp;  // beta = alpha / 2^shift
+  auto multiply = [&](int64_t b, const Batch& t) {
+#pragma unroll
+    for (int u2 = 0; u2 < kRowsU; ++u2) {
+      const int64_t sp = b * kRowsU + u2;
+      if (sp < supers) {
+        const int q = (int)(sp / per);
+        v4f acc = q == 0 ? part[0] : q == 1 ? part[1] : q == 2 ? part[2] : part[3];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int64_t bi = sp * 16 + 4 * u + g;
+          const v8i a1 = load_fp6_lds(arow + bi * 24);
+          const int sa = (int)erow[bi] - shift;
+          const v8i wb = {t.w[u2][u][0], t.w[u2][u][1], t.w[u2][u][2], t.w[u2][u][3], 0, 0, 0, 0};
+          acc = mfma_scaled(a1, wb, acc, sa, scale_byte(t.sc[u2], u, g));
+        }
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq)
+          if (qq == q) part[qq] = acc;
+      }
+    }
+  };
+  const int64_t nb = (supers + kRowsU - 1) / kRowsU;
+  for (int64_t b = 0; b < nb; b += kRowsDepth) {
+    multiply(b, B0);
+    load_w(b + 3, B0);
+    multiply(b + 1, B1);
+    load_w(b + 4, B1);
+    multiply(b + 2, B2);
+    load_w(b + 5, B2);
+  }
+  // ---- the four parts in order, then the two components: D[i][j] sits in register i % 4 of lane (i / 4) * 16 + j
+  v4f fin;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float v = 0.f;
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) v += part[qq][i];
+    fin[i] = v;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) s_fin[i * 64 + lane] = fin[i];
+  __builtin_amdgcn_wave_barrier();
+  if (tile_raw < wtiles) {
+    for (int t = lane; t < M * 16; t += 64) {
+      const int mm = t >> 4, j = t & 15, i2 = M + mm;
+      const float v = s_fin[(mm & 3) * 64 + (mm >> 2) * 16 + j] + s_fin[(i2 & 3) * 64 + (i2 >> 2) * 16 + j];
+      const int64_t n = tile * 16 + j;
+      if (n < N) {
+        if (a.out_bf16)
+          reinterpret_cast<uint16_t*>(a.y)[(int64_t)mm * a.ldy + n] = f32_to_bf16_bits(v);
+        else
+          reinterpret_cast<float*>(a.y)[(int64_t)mm * a.ldy + n] = v;
+      }
+    }
+  }
+}
+
+// tiles per workgroup: the 16-channel tiles dealt evenly to 256 CUs per round, at most eight (one per wave)
+static int w4_rows_tpw(int64_t N) {
+  const int64_t tiles = cdiv(N, 16);
+  const int64_t rounds = cdiv(tiles, (int64_t)kRowsMaxWaves * 256);
+  return (int)cdiv(tiles, 256 * rounds);
+}
+static size_t w4_rows_lds(int64_t M, int64_t K, int tpw) {
+  const size_t KB = (size_t)K / 32;
+  return 2 * (size_t)M * KB * 24 + align_up((size_t)M * KB, 16) + (size_t)tpw * 1024;
+}
+bool gemm_w4_rows_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned) {
+  if (M < 1 || M > kRowsMaxM || K < 512 || K % 512 != 0 || !scales_aligned) return false;
+  const int tpw = w4_rows_tpw(N);
+  // with few tiles per CU the waves of the K-split kernel pull more data at once
+  return tpw >= 4 && w4_rows_lds(M, K, tpw) <= kRowsMaxLds;
+}
+int launch_gemm_w4_rows(const GemmW4Args& a, hipStream_t stream) {
+  if (!a.w_packed || a.x == nullptr || !gemm_w4_rows_applies(a.M, a.K, a.N, a.scales_aligned != 0))
+    return MSD_ERR_INVALID_ARG;
+  const int tpw = w4_rows_tpw(a.N);
+  const size_t lds = w4_rows_lds(a.M, a.K, tpw);
+  static bool attr_set = false;
+  if (!attr_set) {
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_rows_kernel<2>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowsMaxLds));
+    attr_set = true;
+  }
+  const dim3 grid((unsigned)cdiv(cdiv(a.N, 16), tpw)), block(tpw * 64);
+  // two x blocks per thread requested up front (with fewer the second request repeats the last block; an instance
+  // with one spilled); long rows take further passes after the weight batches
+  hipLaunchKernelGGL(gemm_w4_rows_kernel<2>, grid, block, lds, stream, a, tpw);
+  MSD_LAUNCH_CHECK();
+  return MSD_OK;
+}
+
+
 template <int WAVES, int U, int RT, bool SELF, bool STACK = false>
 static int launch_w4(const GemmW4Args& a, hipStream_t stream) {
   size_t dyn = 0;

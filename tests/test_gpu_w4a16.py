@@ -129,6 +129,10 @@ def test_gemm_w4a16_bf16_out_and_errors(msd):
 PACKED_SHAPES = [
     (1, 8192, 512), (1, 512, 40), (2, 2048, 4096), (3, 1024, 300), (4, 512, 8300),          # register-operand kernel
     (9, 1024, 300), (32, 8192, 700), (24, 2048, 8300), (64, 1024, 300), (128, 1536, 4200),  # LDS-staged weight stream
+    (1, 1024, 12400), (2, 512, 17590), (2, 1536, 20000), (1, 2560, 28672), (1, 512, 40000), (2, 16384, 20000), (4, 512, 28672),
+    # one or two rows, many channels: the single-launch kernel with 4..8 tiles per workgroup, a ragged last tile,
+    # two rounds, K ranges that do not split evenly into four parts, more than two blocks per thread; four rows
+    # on the same channels stay on the two-launch form
     (24, 512, 17590), (32, 1024, 28672),   # up to 32 rows, many channels (more workgroups than CUs)
     (40, 512, 700), (64, 8192, 300), (100, 1024, 17590), (128, 512, 40),   # 33..128 rows: two and four row groups
     (256, 512, 256), (300, 2048, 600), (700, 512, 1000),                                     # many-row pipeline

@@ -95,8 +95,10 @@ def test_midp_loads_are_not_touched_before_their_wait(mid_isa, inst):
 @pytest.mark.parametrize("src,pattern,extra", [
     ("gemm_w4_prefill.hip", "gemm_w4_dma_kernelILi4ELb0ELb0E", ()),
     ("gemm_w8.hip", "gemm_w8_dma_kernelILi128ELi256ELi4ELi4ELi4ELb0ELb0ELi64ELi1E", ()),
+    ("gemm_w4.hip", "gemm_w4_rows_kernelILi2E", ()),   # three weight batches and two x blocks in registers
+    ("attn_mla.hip", "attn_mla_dequant_kernelILb1E", ()),   # 128 output registers per lane
 ])
-def test_many_row_kernels_use_no_scratch(tmp_path, src, pattern, extra):
+def test_register_bound_kernels_use_no_scratch(tmp_path, src, pattern, extra):
     txt = _isa(src, tmp_path, extra)
     name, _ = _kernel_body(txt, pattern)
     assert _scratch_bytes(txt, name) == 0
