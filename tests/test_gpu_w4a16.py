@@ -165,6 +165,32 @@ def test_gemm_w4a16_packed_weights(msd, M, K, N):
         assert rel_l2(y2.cpu().numpy(), y_ref) <= 2e-6
 
 
+@pytest.mark.parametrize("M,K,N,shift", [(1, 1024, 13000, 3), (2, 512, 17590, 8), (2, 1536, 12400, 1)])
+def test_gemm_w4a16_packed_single_launch_strided(msd, M, K, N, shift):
+    """The single-launch kernel for one or two rows on packed weights with ldx > K, rows of x that are not
+    16-byte aligned (shift not a multiple of 8 elements), ldy > N, and BF16 output: equal to the canonical entry
+    point bit for bit, pad columns untouched."""
+    seed = synth.seed_for(3, M * 23 + N)
+    x = synth.activations(seed, M, K, outliers=True)
+    codes, exps = synth.mxfp4_weights(seed, N, K)
+    y_ref = oracle.gemm_w4a16(x, codes, exps)
+    cd, ed = to_dev(codes), to_dev(exps)
+    Wp, Ep = msd.msd_pack_weights_w4(cd, ed)
+    xbig = torch.zeros((M, K + 40), dtype=torch.bfloat16, device="cuda")
+    xv = xbig[:, shift:shift + K]
+    xv.copy_(bf16_to_dev(x))
+    ybig = torch.full((M, N + 5), -7.0, dtype=torch.float32, device="cuda")
+    msd.msd_gemm_w4a16_packed(xv, Wp, Ep, N, y=ybig[:, :N])
+    torch.cuda.synchronize()
+    yh = ybig.cpu().numpy()
+    assert rel_l2(yh[:, :N], y_ref) <= 2e-6
+    assert np.all(yh[:, N:] == -7.0)
+    assert torch.equal(ybig[:, :N], msd.msd_gemm_w4a16(bf16_to_dev(x), cd, ed))
+    yb = msd.msd_gemm_w4a16_packed(xv, Wp, Ep, N, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(yb, msd.msd_gemm_w4a16(bf16_to_dev(x), cd, ed, out_dtype=torch.bfloat16))
+
+
 def test_pack_weights_w4_layout_and_errors(msd):
     """The packed arrays are exactly the documented permutations (zero / 0x7F padding past N); K % 512 != 0 is refused."""
     N, K = 40, 1024
