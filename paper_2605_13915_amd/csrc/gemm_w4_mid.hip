@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
 // MFMA t (a rotating window of five six-register operands), which also keeps every instance under 256 registers so
 // that the loader waves fit beside the multiplying ones.
 constexpr int kMidpGroupA = 3072;  // operand bytes of a 32-row group per K step
-constexpr int kMidpDepth = 2;      // batches in flight behind the current one (3 and 4 measured 4 % and 7 % slower)
+constexpr int kMidpDepth = 2;      // batches in flight behind the current one (3 measured 2 % slower, 4 spills)
 // RG groups of 32 rows, U K steps per batch: 8 steps for one or two groups, 4 for four (three LDS buffers of a
 // batch's operands have to fit)
 template <int RG, int U>
@@ -258,8 +258,9 @@ struct MidpCfg {
 //   issue order is W0 A0 W1 A1 ... from the first instruction on, so when phase b starts the loads younger than
 //   the operands of batch b are the D - 1 batches after it: "vmcnt((D - 1) * 16)" means weights and operands of
 //   batch b have landed; the barrier after it publishes the fills of all waves and says that every wave has left
-//   the buffer that batch b + D goes into (batch b - 1's).  Batch numbers past the end repeat the last batch (what
-//   they fetch is never used), so the count holds to the end; the kernel drains everything before its epilogue.
+//   the buffer that batch b + D goes into (batch b - 1's).  Batch numbers past the end issue the same number of
+//   loads, every lane reading the first 16 bytes of the last batch (one cache line per instruction; what they
+//   fetch is never used), so the count holds to the end; the kernel drains everything before its epilogue.
 __device__ __forceinline__ void midp_fill16(const uint8_t* gbase, uint32_t voff, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
@@ -321,8 +322,8 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   const int64_t wtiles = (N + 15) / 16, wq = wtiles * 1024;
   const int64_t nc = min(n_raw, n_end - 1);  // their loads repeat an address the workgroup reads anyway
   // this lane's 16 bytes of K step ks: unit ks / 2, half ks % 2 of the kilobyte of its channel tile
-  const uint32_t w_off = (uint32_t)((nc / 16) * 1024 + (kb * 16 + (nc & 15)) * 16);
-  const uint32_t e_off = (uint32_t)((nc / 16) * 256 + (nc & 15) * 16);
+  const uint32_t w_lane_off = (uint32_t)((nc / 16) * 1024 + (kb * 16 + (nc & 15)) * 16);
+  const uint32_t e_lane_off = (uint32_t)((nc / 16) * 256 + (nc & 15) * 16);
   const int NB = (int)(K / (64 * U));
   const uint32_t lds0 = (uint32_t)(uintptr_t)s_midp;
   struct WSet {
@@ -330,6 +331,8 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   };
   WSet w[NSETS];
   auto load_w = [&](int b, WSet& ws) __attribute__((always_inline)) {
+    // past the end: every lane re-reads the first 16 bytes of the last batch (one cache line per instruction)
+    const uint32_t w_off = b < NB ? w_lane_off : 0u, e_off = b < NB ? e_lane_off : 0u;
     b = min(b, NB - 1);
     const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Wp + (int64_t)b * (U / 2) * wq)));
     const uint64_t step = midp_uniform((uint64_t)wq);
@@ -344,10 +347,11 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   // the batch's operands are contiguous in qop: fill f copies kilobyte f (wave w: f = w, w + 4, ...); the scale
   // bytes are 256 per K step at 512-byte intervals: piece p = w * kScaleLanes + l of the batch (lane l < kScaleLanes of
   // wave w) is piece p % 16 of step p / 16
-  const uint32_t a_off = (uint32_t)(lane * 16);
+  const uint32_t a_lane_off = (uint32_t)(lane * 16);
   const int sp = wave * C::kScaleLanes + (lane & (C::kScaleLanes - 1));
-  const uint32_t s_off = (uint32_t)((sp >> 4) * 512 + (sp & 15) * 16);
+  const uint32_t s_lane_off = (uint32_t)((sp >> 4) * 512 + (sp & 15) * 16);
   auto fill_a = [&](int b) __attribute__((always_inline)) {
+    const uint32_t a_off = b < NB ? a_lane_off : 0u, s_off = b < NB ? s_lane_off : 0u;  // past the end: as above
     const int bb = min(b, NB - 1);
     const uint32_t dst = lds0 + (uint32_t)((b % NSETS) * C::kBufA);
     const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * C::kStepA) + wave * 1024)));
