@@ -22,7 +22,8 @@
 //       up to 16 heads: 2 x 2 x 2,   up to 32 heads: 4 x 2 x 1,
 //       more:           8 x 1 x 1, 64 heads per workgroup, further heads over blockIdx.y.
 //   * One workgroup per CU; the KV length is split over workgroups and over the token streams inside
-//     one; every (split, stream) writes its own partial (m, l, O) and a last kernel merges them.
+//     one; the streams of a workgroup merge through LDS at the end, every split writes one partial
+//     (m, l, O) and a last kernel merges the splits.
 #include <algorithm>
 #include <type_traits>
 
@@ -56,7 +57,7 @@ struct MlaParams {
   int B, Hq;
   int64_t L, ld;
   int nsplit;  // workgroups along the KV length
-  int nparts;  // partial results per (batch, head): nsplit x token streams
+  int nparts;  // partial results per (batch, head): one per KV split
   int64_t tokens_per_split;
   float sm_scale_log2;  // score scale times log2(e)
   int8_t* qc1;          // [B][Hq][576] query codes of both components and alpha_Q [B][Hq] (workspace; only
@@ -517,13 +518,70 @@ __global__ __launch_bounds__(NW * 64) void attn_mla_kernel(MlaParams p) {
     step(Buf0{}, it + 1);
   }
 
-  // ---- this wave's partial (m, l, O) of its 16 heads and its value channels
-  const int part = split * TS + ts;
+  float lsum[MG][2];
+#pragma unroll
+  for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) lsum[mg][hh] = row16_sum(l_run[mg][hh]);
+  if constexpr (TS == 2) {
+    // ---- the two token streams of the workgroup merge here, through the tile buffers (free now): the waves of
+    // stream 1 hand (m, l, O) to the waves of stream 0 that hold the same heads and channels, lane by lane, so
+    // that a split writes one partial instead of two (half the partial-result traffic of the call)
+    constexpr int NV = MG * 2 * (2 + NSL * 8);  // floats per lane
+    static_assert((size_t)WS * NV * 64 * 4 <= (size_t)2 * TS * kTileBytes, "exchange area");
+    float* xch = reinterpret_cast<float*>(sTiles) + (wave % WS) * NV * 64 + lane;
+    // each stream keeps its output in its own unit (the alpha_P / 254 of its last coded tile): plain values from here
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int sl = 0; sl < NSL; ++sl)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) o_run[mg][sl][hh][c] *= unit;
+    unit = 1.f;
+    __syncthreads();  // every wave has left the tile buffers
+    if (ts == 1) {
+      int idx = 0;
+#pragma unroll
+      for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          xch[64 * idx++] = m_run[mg][hh];
+          xch[64 * idx++] = lsum[mg][hh];
+#pragma unroll
+          for (int sl = 0; sl < NSL; ++sl)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) xch[64 * idx++] = o_run[mg][sl][hh][c];
+        }
+    }
+    __syncthreads();
+    if (ts == 1) return;
+    int idx = 0;
+#pragma unroll
+    for (int mg = 0; mg < MG; ++mg)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const float m0 = m_run[mg][hh], m1 = xch[64 * idx++], l1 = xch[64 * idx++];
+        const float mn = fmaxf(m0, m1);
+        const float w0 = m0 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m0 - mn);
+        const float w1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - mn);
+        m_run[mg][hh] = mn;
+        lsum[mg][hh] = lsum[mg][hh] * w0 + l1 * w1;
+#pragma unroll
+        for (int sl = 0; sl < NSL; ++sl)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) o_run[mg][sl][hh][c] = o_run[mg][sl][hh][c] * w0 + xch[64 * idx++] * w1;
+      }
+  }
+  // ---- the partial (m, l, O) of this wave's heads and value channels: one per KV split
+  static_assert(TS <= 2, "token streams are merged pairwise above");
+  const int part = split;
 #pragma unroll
   for (int mg = 0; mg < MG; ++mg)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-      const float l = row16_sum(l_run[mg][hh]);
+      const float l = lsum[mg][hh];
       const int head = hw + 8 * mg + g * 2 + hh;
       if (head >= Hq) continue;
       if (p.nparts == 1) {
@@ -621,9 +679,9 @@ MlaPlan mla_plan(int B, int Hq, int64_t L) {
   pl.head_blocks = (Hq + pl.heads_wg - 1) / pl.heads_wg;
   int64_t ns = cdiv((int64_t)kMlaTargetWgs, (int64_t)B * pl.head_blocks);
   const int64_t max_by_len = max((int64_t)1, L / (2 * pl.ts * kTile));
-  ns = max((int64_t)1, min(min(ns, max_by_len), (int64_t)(kMlaMaxParts / pl.ts)));
+  ns = max((int64_t)1, min(min(ns, max_by_len), (int64_t)kMlaMaxParts));
   pl.nsplit = (int)ns;
-  pl.nparts = pl.nsplit * pl.ts;
+  pl.nparts = pl.nsplit;  // the token streams of a workgroup merge inside it
   int64_t tps = cdiv(L > 0 ? L : 1, ns);
   pl.tokens_per_split = cdiv(tps, (int64_t)pl.ts * kTile) * (pl.ts * kTile);
   return pl;
