@@ -466,6 +466,22 @@ def leg_mla(msd, synth, time_calls, dev):
                 t = torch.einsum("bhl,bld->bhd", P, Cd[:, :, :512])
                 out[-1]["rel_l2_vs_fp64"] = float("%.3g" % ((o[:2].double() - t).norm() / t.norm()).item())
                 del Cd, P, t
+        if L == 4096:
+            # head-count sweep on the same cache (Sec. 4.4's crossover question on the latent shape): MSD against the
+            # comparison kernel
+            sweep = []
+            for Hq in (1, 2, 4, 8, 16, 32, 64, 128):
+                q = _bf16(synth.queries(synth.seed_for(9, 100 + Hq), B, Hq, d), dev)
+                o = torch.empty((B, Hq, 512), dtype=torch.float32, device=dev)
+                ws = torch.empty(msd.lib().msd_mla_decode_int8kv_workspace_bytes(B, Hq, L), dtype=torch.uint8, device=dev)
+                us = time_calls(lambda i: msd.msd_mla_decode_int8kv(q, sets[i % n][0], sets[i % n][1], msd.MSD_PER_TOKEN,
+                                                                    1.0 / 192.0 ** 0.5, out=o, ws=ws, prepare=True), 2 * n)
+                us_c = time_calls(lambda i: msd.msd_dequant_mla_decode_int8kv(q, sets[i % n][0], sets[i % n][1],
+                                                                              msd.MSD_PER_TOKEN, 1.0 / 192.0 ** 0.5, out=o,
+                                                                              ws=ws, prepare=True), 2 * n)
+                sweep.append({"Hq": Hq, "msd_us": round(us, 1), "dequant_us": round(us_c, 1),
+                              "speedup_vs_dequant": round(us_c / us, 3)})
+            out.append({"B": B, "L": L, "heads_sweep": sweep})
         del sets
         torch.cuda.empty_cache()
     return out
