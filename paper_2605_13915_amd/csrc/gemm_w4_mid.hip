@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
   }
 }
 
-// ------------------------------------------------------------------ 5..128 rows on packed weights
+// ------------------------------------------------------------------ 3..128 rows on packed weights
 // The packed layout (msd_pack_weights_w4) holds the B operand of the 32x32x64 instruction as two contiguous
 // 512-byte runs per wave and K step (the halves of the kilobytes of two adjacent channel tiles), so the weights go
 // HBM -> registers in operand order with no LDS stage, in batches of eight K steps (8 KB per wave).  The activation
@@ -520,7 +520,9 @@ int launch_mid(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W, const 
 bool gemm_w4_mid_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned) {
   // whole batches of 8 K steps (4 would do above 32 rows; one rule keeps the layout choice simple);
   // 16-byte loads of the weight scale rows
-  return M > 4 && M <= 128 && N >= 1 && K >= 512 && K % 512 == 0 && scales_aligned;
+  // from three rows on (8192 x 28672, packed / canonical weights, us: three rows 27.6 / 41.8 here against 31.6 / 40.9
+  // in the register-operand kernel, four rows 27.6 / 41.8 against 34.3 / 44.2; two rows 29.6 / 39.5 there)
+  return M > 2 && M <= 128 && N >= 1 && K >= 512 && K % 512 == 0 && scales_aligned;
 }
 
 W4MidLayout w4_mid_layout(int64_t M, int64_t K) {

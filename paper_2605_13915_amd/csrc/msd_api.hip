@@ -393,7 +393,7 @@ static int gemm_w4a16_impl(int variant, bool packed, const void* x_bf16, int64_t
     if (packed && ((t1 && M > 16) || (M > 128 && w4_prefill_layout(M, K, N).total >= ((size_t)1 << 31))))
       return MSD_ERR_UNSUPPORTED;
     if (!t1 && gemm_w4_mid_applies(M, K, N, a.scales_aligned != 0)) {
-      // 5..128 rows, no observation points: activation operands K-step-major, weights and operands
+      // 3..128 rows, no observation points: activation operands K-step-major, weights and operands
       // staged through LDS per 128 channels (the weight stream is the bound)
       return launch_gemm_w4_mid((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
                                 (uint8_t*)ws, mv, a.w_packed, s);

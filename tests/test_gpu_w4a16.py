@@ -64,14 +64,14 @@ def test_gemm_w4a16_parity(msd, M, K, N):
 
 
 @pytest.mark.parametrize("M,K,N", [(256, 512, 256), (300, 2048, 600), (40, 192, 70), (700, 64, 1000), (1, 8192, 512),
-                                   (33, 4096, 300),
+                                   (33, 4096, 300), (3, 512, 130), (4, 2048, 520), (3, 1024, 20000),
                                    # 9..32 rows with K a multiple of 512: weights straight to the matrix operand,
                                    # activation operands through LDS (one, two, three and many K batches)
                                    (32, 512, 128), (9, 1024, 300), (17, 1536, 1000), (32, 8192, 700), (24, 2048, 8300),
                                    # 33..128 rows: two or four 32-row groups, batches of four K steps
                                    (33, 512, 130), (64, 1024, 300), (100, 2048, 520), (128, 1536, 4200)])
 def test_gemm_w4a16_product_path_without_taps(msd, M, K, N):
-    """The path a caller without observation points takes: 5..128 rows with K a multiple of 512 go through
+    """The path a caller without observation points takes: 3..128 rows with K a multiple of 512 go through
     the LDS-staged weight-stream kernel, more rows (or other K that is a multiple of 64) through the many-row
     pipeline (own operand format, transposed scale bytes, 256 x 256 tiles).  y starts as NaN and is computed
     twice."""
