@@ -1351,7 +1351,11 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
     const bool deep = a.K % 128 == 0 && (a.a_step == 0 || a.a_bk == 128);
     // Up to one workgroup per CU of the smallest tile: eight waves as four K groups (measured 16.5 vs 20.5 us at
     // 128 x 4096 x 4096, 19 vs 22 us at 32 x 4096 x 14336; with more tiles than CUs the larger tiles win again).
-    if (deep && wgs(32, 64) <= 256)
+    // At most half a chip of those: tiles of 32 channels, four waves (the four K groups of one 32 x 32 tile), two
+    // workgroups per CU.
+    if (deep && wgs(32, 64) <= 128)
+      rc = launch_dma<32, 32, 1, 1, 4, false, false, 128, 4>(a, stream);
+    else if (deep && wgs(32, 64) <= 256)
       rc = launch_dma<32, 64, 1, 2, 4, false, false, 128, 4>(a, stream);
     else
     // eight waves measured 30 vs 31.6 us at 128 x 4096 x 14336; as 2 x 2 waves in two K groups (a third fewer

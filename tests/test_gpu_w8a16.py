@@ -324,6 +324,7 @@ PACKED_SHAPES = [
     (15, 8192, 8300), (9, 64, 20),
     (30, 512, 8300), (70, 320, 6500), (128, 256, 12800), (128, 4096, 1024), (100, 1024, 700),   # small LDS tiles
     (65, 192, 300), (96, 2112, 520), (64, 1024, 4100), (100, 256, 1000), (33, 640, 2000), (128, 128, 640),
+    (48, 512, 4096), (64, 256, 3000), (40, 1024, 4000),   # at most 128 tiles of 32 x 64: the 32 x 32 tile instance
     (1100, 512, 4200), (300, 1088, 520), (257, 256, 777),                                    # large LDS tiles
 ]
 
