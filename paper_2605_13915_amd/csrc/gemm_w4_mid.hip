@@ -1,4 +1,4 @@
-// W4A16 MSD GEMM for 5 to 128 activation rows, where the weight stream is the bound (batched
+// W4A16 MSD GEMM for 3 to 128 activation rows, where the weight stream is the bound (batched
 // decode): paper Sec. 3.2.1 / Alg. 2 feeding Sec. 3.4.1 on v_mfma_scale_f32_32x32x64_f8f6f4.
 //
 // Two launches per call: the K-step-major decomposition of gemm_w4_prefill.hip (per group of 32
