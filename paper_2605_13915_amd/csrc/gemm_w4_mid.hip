@@ -238,9 +238,16 @@ constexpr int kMidpGroupA = 3072;  // operand bytes of a 32-row group per K step
 constexpr int kMidpDepth = 2;      // batches in flight behind the current one (3 measured 2 % slower, 4 spills)
 // RG groups of 32 rows, U K steps per batch: 8 steps for one or two groups, 4 for four (three LDS buffers of a
 // batch's operands have to fit)
-template <int RG, int U>
+// H16 (up to 16 rows; one row group, eight steps): only the bytes of rows 0..15 of a group's record come to LDS --
+// half the operand traffic.  The record in memory is unchanged; the fills gather its eight pieces (the first half
+// of each 512-byte chunk, resp. of each block's part of the chunks with dwords 4, 5) into a packed image per pair of
+// K steps: [step 2i: 4 x 256 B][step 2i + 1: 4 x 256 B][step 2i: 4 x 128 B][step 2i + 1: 4 x 128 B], piece 2 c + b
+// for component c and block b.
+template <int RG, int U, bool H16 = false>
 struct MidpCfg {
-  static constexpr int kStepA = RG * kMidpGroupA;        // operand bytes per K step
+  static_assert(!H16 || (RG == 1 && U == 8), "the 16-row image is written for one group and eight steps");
+  static constexpr int kStepG = RG * kMidpGroupA;        // operand bytes per K step in memory
+  static constexpr int kStepA = H16 ? kMidpGroupA / 2 : kStepG;  // ... and in LDS
   static constexpr int kBufA = U * (kStepA + 256);       // a batch: operands, then 256 scale bytes per step
   static constexpr int kStageA = U * kStepA / 1024 / (kMidThreads / 64);  // operand kilobytes per wave and batch
   static constexpr int kScaleLanes = U * 256 / 16 / (kMidThreads / 64);   // lanes of a wave that copy scale bytes
@@ -293,7 +300,7 @@ __device__ __forceinline__ uint64_t midp_uniform(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-template <int D, int RG, int U, int LW, int WN>
+template <int D, int RG, int U, int LW, int WN, bool H16 = false>
 __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(const uint8_t* __restrict__ qop,
                                                                    const uint8_t* __restrict__ sa_t,
                                                                    const uint8_t* __restrict__ Wp,
@@ -302,7 +309,7 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
                                                                    int64_t N, int shift, int bn) {
   // bn: channels per workgroup, a multiple of 16, at most kMidBN (the host picks it so that the grid fills the CUs
   // evenly); a wave still multiplies 32 channels, those past bn or N repeat the workgroup's last one
-  using C = MidpCfg<RG, U>;
+  using C = MidpCfg<RG, U, H16>;
   constexpr int NSETS = D + 1;  // register sets and LDS buffers: the current batch and D in flight
   static_assert(U == 8 || U == 4, "a batch is a whole or half a 16-block scale record");
   extern __shared__ __attribute__((aligned(16))) uint8_t s_midp[];  // [NSETS][A batch]
@@ -348,15 +355,29 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   // bytes are 256 per K step at 512-byte intervals: piece p = w * kScaleLanes + l of the batch (lane l < kScaleLanes of
   // wave w) is piece p % 16 of step p / 16
   const uint32_t a_lane_off = (uint32_t)(lane * 16);
+  // H16: lane -> (piece, 16 bytes of it) in the record of a K step; the second 32 lanes of the 128-byte pieces
+  // take the next K step
+  const uint32_t h16_lo_off = (uint32_t)((3 * (lane >> 5) + ((lane >> 4) & 1)) * 512 + (lane & 15) * 16);
+  const uint32_t h16_hi_off = (uint32_t)((lane >> 5) * C::kStepG + (3 * ((lane >> 4) & 1) + 2) * 512 + ((lane >> 3) & 1) * 256 + (lane & 7) * 16);
   const int sp = wave * C::kScaleLanes + (lane & (C::kScaleLanes - 1));
   const uint32_t s_lane_off = (uint32_t)((sp >> 4) * 512 + (sp & 15) * 16);
   auto fill_a = [&](int b) __attribute__((always_inline)) {
     const uint32_t a_off = b < NB ? a_lane_off : 0u, s_off = b < NB ? s_lane_off : 0u;  // past the end: as above
     const int bb = min(b, NB - 1);
     const uint32_t dst = lds0 + (uint32_t)((b % NSETS) * C::kBufA);
-    const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * C::kStepA) + wave * 1024)));
+    if constexpr (H16) {
+      // wave w gathers the pair of K steps 2 w, 2 w + 1: one instruction per step for the 256-byte pieces, one for
+      // the 128-byte pieces of both
+      const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * C::kStepG) + wave * (2 * C::kStepG))));
+      const uint32_t lo_off = b < NB ? h16_lo_off : 0u, hi_off = b < NB ? h16_hi_off : 0u;
+      midp_fill16(src, lo_off, dst + (uint32_t)(wave * 3072));
+      midp_fill16(src + C::kStepG, lo_off, dst + (uint32_t)(wave * 3072 + 1024));
+      midp_fill16(src, hi_off, dst + (uint32_t)(wave * 3072 + 2048));
+    } else {
+      const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(qop + (int64_t)bb * (U * C::kStepA) + wave * 1024)));
 #pragma unroll
-    for (int i = 0; i < C::kStageA; ++i) midp_fill16(src + i * 4096, a_off, dst + (uint32_t)(wave * 1024 + i * 4096));
+      for (int i = 0; i < C::kStageA; ++i) midp_fill16(src + i * 4096, a_off, dst + (uint32_t)(wave * 1024 + i * 4096));
+    }
     midp_fill16_lanes<(uint32_t)((1ull << C::kScaleLanes) - 1)>(
         reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(sa_t + (int64_t)bb * U * 512))), s_off,
         dst + (uint32_t)(U * C::kStepA + wave * C::kScaleLanes * 16));
@@ -398,9 +419,17 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
     int sav[SV];
     auto read_unit = [&](int t, v8i& d) __attribute__((always_inline)) {
       const int u = t / UPS, rg = (t / 2) % RG, comp = t & 1;
-      const uint8_t* rec = sa_buf + u * C::kStepA + rg * kMidpGroupA;
-      const uint4 lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
-      const uint2 hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
+      uint4 lo;
+      uint2 hi;
+      if constexpr (H16) {  // lanes of rows 16..31 repeat rows 0..15: their products are never stored
+        const uint8_t* rec = sa_buf + (u >> 1) * (2 * C::kStepA);
+        lo = *reinterpret_cast<const uint4*>(rec + (u & 1) * 1024 + (2 * comp + kb) * 256 + (l32 & 15) * 16);
+        hi = *reinterpret_cast<const uint2*>(rec + 2048 + (u & 1) * 512 + (2 * comp + kb) * 128 + (l32 & 15) * 8);
+      } else {
+        const uint8_t* rec = sa_buf + u * C::kStepA + rg * kMidpGroupA;
+        lo = *reinterpret_cast<const uint4*>(rec + ((3 * comp + kb) * 32 + l32) * 16);
+        hi = *reinterpret_cast<const uint2*>(rec + (3 * comp + 2) * 512 + lane * 8);
+      }
       d = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
       // the step's row scales come with its first unit: byte rg of the dword is the scale of row 32 rg + l32 (block kb)
       if (t % UPS == 0) sav[u % SV] = *reinterpret_cast<const int*>(sa_buf + U * C::kStepA + u * 256 + kb * 128 + l32 * 4);
@@ -477,13 +506,13 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   }
 }
 
-template <int RG, int U, int LW, int WN>
+template <int RG, int U, int LW, int WN, bool H16 = false>
 static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* Wp, const uint8_t* Ep, void* y,
                        int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
-  constexpr int lds = MidpCfg<RG, U>::kLds;
+  constexpr int lds = MidpCfg<RG, U, H16>::kLds;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN, H16>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
@@ -493,7 +522,7 @@ static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W
   const int64_t rounds = cdiv(tiles, 8 * 256);
   const int64_t tpw = cdiv(tiles, 256 * rounds);
   const int bn = tpw >= 5 ? (int)tpw * 16 : kMidBN;
-  hipLaunchKernelGGL((gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads + LW * 64), lds,
+  hipLaunchKernelGGL((gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN, H16>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads + LW * 64), lds,
                      stream, qop, sa_t, Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift, bn);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -550,6 +579,8 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
   }
   if (w_packed) {  // weights straight into operand registers, hand-counted loads
     // (one row group: loader waves measured 30.6 against 31.7 us at 32 rows, 28.9 against 30.6 at 8)
+    // up to 16 rows: half the operand bytes per K step (8192 x 28672: 28.0 -> 26.1 us at 8 rows, 28.5 -> 26.8 at 16)
+    if (M <= 16) return launch_midp<1, 8, 4, 5, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     if (l.Mpad == 32) return launch_midp<1, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     if (l.Mpad == 64) return launch_midp<2, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     return launch_midp<4, 4, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);

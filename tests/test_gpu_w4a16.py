@@ -134,6 +134,7 @@ PACKED_SHAPES = [
     # two rounds, K ranges that do not split evenly into four parts, more than two blocks per thread; four rows
     # on the same channels stay on the two-launch form
     (24, 512, 17590), (32, 1024, 28672),   # up to 32 rows, many channels (more workgroups than CUs)
+    (16, 1024, 17590), (11, 512, 28672), (5, 8192, 300), (13, 1536, 40),   # up to 16 rows: the half-size operand image
     (40, 512, 700), (64, 8192, 300), (100, 1024, 17590), (128, 512, 40),   # 33..128 rows: two and four row groups
     (256, 512, 256), (300, 2048, 600), (700, 512, 1000),                                     # many-row pipeline
 ]

@@ -56,8 +56,8 @@ def mid_isa(tmp_path_factory):
     return _isa("gemm_w4_mid.hip", tmp_path_factory.mktemp("isa"))
 
 
-# <depth, row groups, steps per batch, loader waves>
-@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5E", "ILi2ELi2ELi8ELi4ELi5E", "ILi2ELi4ELi4ELi4ELi5E"])
+# <depth, row groups, steps per batch, loader waves, operand window, 16-row image>
+@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5ELb0E", "ILi2ELi1ELi8ELi4ELi5ELb1E", "ILi2ELi2ELi8ELi4ELi5ELb0E", "ILi2ELi4ELi4ELi4ELi5ELb0E"])
 def test_midp_loads_are_not_touched_before_their_wait(mid_isa, inst):
     txt = mid_isa
     name, body = _kernel_body(txt, "gemm_w4_midp_kernel" + inst)
