@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kMidThreads) void gemm_w4_mid_kernel(const uint8_t*
         }
       }
       // four row groups: keep the K steps apart in the schedule, or the hoisted fragment reads spill
-      if (RG == 4) __builtin_amdgcn_sched_barrier(0);
+      if (RG >= 3) __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -557,7 +557,7 @@ bool gemm_w4_mid_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned) {
 W4MidLayout w4_mid_layout(int64_t M, int64_t K) {
   W4MidLayout l{};
   const size_t steps = (size_t)K / 64;
-  l.Mpad = M <= 32 ? 32 : M <= 64 ? 64 : 128;
+  l.Mpad = M <= 32 ? 32 : M <= 64 ? 64 : M <= 96 ? 96 : 128;
   size_t off = 0;
   l.qop = off; off = align_up(off + steps * (l.Mpad / 32) * 3072, 256);
   l.sa_t = off; off = align_up(off + steps * 512, 256);
@@ -575,6 +575,7 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
   if (mv.e2m1) {  // E2M1-grid components as native FP4 operands
     if (l.Mpad == 32) return launch_mid<1, 8, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
     if (l.Mpad == 64) return launch_mid<2, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
+    if (l.Mpad == 96) return launch_mid<3, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
     return launch_mid<4, 4, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   }
   if (w_packed) {  // weights straight into operand registers, hand-counted loads
@@ -583,10 +584,12 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
     if (M <= 16) return launch_midp<1, 8, 4, 5, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     if (l.Mpad == 32) return launch_midp<1, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     if (l.Mpad == 64) return launch_midp<2, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 96) return launch_midp<3, 4, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     return launch_midp<4, 4, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
   }
   if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
+  if (l.Mpad == 96) return launch_mid<3, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   return launch_mid<4, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
 }
 

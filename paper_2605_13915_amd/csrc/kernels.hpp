@@ -145,7 +145,7 @@ int launch_decompose_mxfp4_pair(const uint16_t* x, int64_t ldx, int64_t M, int64
 
 // ---- W4A16, 128 rows or fewer with the weight stream as the bound (gemm_w4_mid.hip)
 struct W4MidLayout {
-  size_t qop, sa_t, total, Mpad;  // Mpad: rows rounded up to 32, 64 or 128
+  size_t qop, sa_t, total, Mpad;  // Mpad: rows rounded up to 32, 64, 96 or 128
 };
 bool gemm_w4_mid_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned);
 W4MidLayout w4_mid_layout(int64_t M, int64_t K);

@@ -69,7 +69,8 @@ def test_gemm_w4a16_parity(msd, M, K, N):
                                    # activation operands through LDS (one, two, three and many K batches)
                                    (32, 512, 128), (9, 1024, 300), (17, 1536, 1000), (32, 8192, 700), (24, 2048, 8300),
                                    # 33..128 rows: two or four 32-row groups, batches of four K steps
-                                   (33, 512, 130), (64, 1024, 300), (100, 2048, 520), (128, 1536, 4200)])
+                                   (33, 512, 130), (64, 1024, 300), (100, 2048, 520), (128, 1536, 4200),
+                                   (96, 1024, 300), (70, 2048, 520)])
 def test_gemm_w4a16_product_path_without_taps(msd, M, K, N):
     """The path a caller without observation points takes: 3..128 rows with K a multiple of 512 go through
     the LDS-staged weight-stream kernel, more rows (or other K that is a multiple of 64) through the many-row
@@ -136,6 +137,7 @@ PACKED_SHAPES = [
     (24, 512, 17590), (32, 1024, 28672),   # up to 32 rows, many channels (more workgroups than CUs)
     (16, 1024, 17590), (11, 512, 28672), (5, 8192, 300), (13, 1536, 40),   # up to 16 rows: the half-size operand image
     (40, 512, 700), (64, 8192, 300), (100, 1024, 17590), (128, 512, 40),   # 33..128 rows: two and four row groups
+    (65, 1024, 300), (96, 512, 17590), (80, 8192, 140),                     # 65..96 rows: three row groups
     (256, 512, 256), (300, 2048, 600), (700, 512, 1000),                                     # many-row pipeline
 ]
 

@@ -57,7 +57,7 @@ def mid_isa(tmp_path_factory):
 
 
 # <depth, row groups, steps per batch, loader waves, operand window, 16-row image>
-@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5ELb0E", "ILi2ELi1ELi8ELi4ELi5ELb1E", "ILi2ELi2ELi8ELi4ELi5ELb0E", "ILi2ELi4ELi4ELi4ELi5ELb0E"])
+@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5ELb0E", "ILi2ELi1ELi8ELi4ELi5ELb1E", "ILi2ELi2ELi8ELi4ELi5ELb0E", "ILi2ELi3ELi4ELi4ELi5ELb0E", "ILi2ELi4ELi4ELi4ELi5ELb0E"])
 def test_midp_loads_are_not_touched_before_their_wait(mid_isa, inst):
     txt = mid_isa
     name, body = _kernel_body(txt, "gemm_w4_midp_kernel" + inst)
