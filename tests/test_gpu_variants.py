@@ -85,7 +85,7 @@ def test_decompose_mxfp4_variants_bit_exact(msd, variant, M, K):
 # fused single launch, stacked components (M <= 8), M <= 16, 32-row tiles, many rows (taps: the
 # register-staged tile kernel; no taps: the asynchronous-fill kernel), K % 64 != 0
 W4_SHAPES = [(1, 2048, 600), (2, 544, 300), (8, 1024, 520), (16, 512, 1000), (30, 512, 2100), (64, 512, 300),
-             (100, 1024, 130), (200, 512, 700), (300, 544, 520)]
+             (100, 1024, 130), (200, 512, 700), (300, 544, 520), (90, 512, 260), (3, 512, 140)]
 
 
 @pytest.mark.parametrize("variant", [1, 2, 4])
