@@ -1290,7 +1290,7 @@ static W8Path w8_path(int64_t M, int64_t K, int64_t N) {
 int gemm_w8_frag_rt(int64_t M, int64_t K, int64_t N) {
   if (gemm_w8_is_fused(M, K, N) || K % 64 != 0 || K < 64) return 0;
   if (w8_path(M, K, N) != W8Path::kDecode) return 0;
-  return 2 * M <= 16 ? 1 : 2 * M <= 32 ? 2 : 4;
+  return 2 * M <= 16 ? 1 : 2 * M <= 32 ? 2 : 2 * M <= 48 ? 3 : 4;
 }
 
 // Stage depth (bytes of K per row) of the blocked code layout this shape's GEMM reads; 0: row-major.
@@ -1325,11 +1325,13 @@ int launch_gemm_w8(const GemmW8Args& a, hipStream_t stream) {
   } else if (a.a_frag != 0) {
     // fragment-major codes (gemm_w8_frag_rt): the register-operand kernel, with the whole K range of a wave in
     // one batch of loads where the registers allow it (measured against the instances below at K = 4096)
-    if (path != W8Path::kDecode || a.a_frag != (2 * M <= 16 ? 1 : 2 * M <= 32 ? 2 : 4)) return MSD_ERR_INVALID_ARG;
+    if (path != W8Path::kDecode || a.a_frag != (2 * M <= 16 ? 1 : 2 * M <= 32 ? 2 : 2 * M <= 48 ? 3 : 4)) return MSD_ERR_INVALID_ARG;
     if (a.a_frag == 1)
       rc = wide ? launch_decode<4, 8, 1, 2, false>(a, stream) : launch_decode<4, 16, 1, 1, false>(a, stream);
     else if (a.a_frag == 2)
       rc = wide ? launch_decode<8, 4, 2, 2, false>(a, stream) : launch_decode<4, 16, 2, 1, false>(a, stream);
+    else if (a.a_frag == 3)  // 17..24 rows: three fragments instead of four
+      rc = wide ? launch_decode<8, 2, 3, 4, false>(a, stream) : launch_decode<8, 8, 3, 1, false>(a, stream);
     else
       // (eight waves x 8 steps: a wave's whole K range at K = 4096 in one batch, 13.35 against 13.6 us at 32 rows;
       // sixteen waves x 4 steps 13.8)

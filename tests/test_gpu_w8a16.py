@@ -138,7 +138,7 @@ def test_gemm_w8a16_parity(msd, M, K, N, outl):
                                    # many column tiles, K with a partial last batch of steps, ragged N
                                    (5, 4096, 8300), (8, 4096, 4096), (16, 4096, 4100), (12, 2112, 700),
                                    (32, 4096, 4096), (27, 4096, 1000), (9, 64, 20), (15, 8192, 8300),
-                                   (20, 1088, 333), (6, 16384, 520),
+                                   (20, 1088, 333), (6, 16384, 520), (24, 4096, 4096), (18, 2112, 260),
                                    # single-launch kernel without observation points
                                    (4, 4096, 4096), (16, 1024, 1024), (7, 2048, 8300), (2, 8192, 4000)])
 def test_gemm_w8a16_product_path_without_taps(msd, M, K, N):
@@ -321,7 +321,7 @@ def test_extreme_magnitudes_stay_bit_exact(msd, ex):
 PACKED_SHAPES = [
     (1, 4096, 4096), (2, 4096, 8300), (4, 2048, 530), (8, 1024, 90), (3, 8192, 300),        # single-launch kernel
     (8, 4096, 4096), (5, 4096, 8300), (16, 4096, 4100), (12, 2112, 700), (32, 4096, 1000),  # register-operand kernels
-    (15, 8192, 8300), (9, 64, 20),
+    (15, 8192, 8300), (9, 64, 20), (20, 4096, 4100), (24, 1024, 90), (17, 2112, 700),   # ... 17..24 rows: three fragments
     (30, 512, 8300), (70, 320, 6500), (128, 256, 12800), (128, 4096, 1024), (100, 1024, 700),   # small LDS tiles
     (65, 192, 300), (96, 2112, 520), (64, 1024, 4100), (100, 256, 1000), (33, 640, 2000), (128, 128, 640),
     (48, 512, 4096), (64, 256, 3000), (40, 1024, 4000),   # at most 128 tiles of 32 x 64: the 32 x 32 tile instance
