@@ -310,9 +310,15 @@ constexpr size_t kRowsMaxLds = 144 * 1024;
 
 // NPRE: x blocks a thread requests before its weight batches (loads complete in order: an x block requested after
 // them would wait for all of them)
-template <int NPRE>
+// PACKED = false: the canonical layout W [N][K/2], We [N][K/32].  A B-operand load straight from it would touch 16
+// weight rows with 64 bytes each per instruction; instead a wave fetches 256 contiguous bytes of a row (4 rows per
+// instruction, four instructions per super-step of its 16 channels) and turns them into operand order through a
+// private 8 KB of LDS: 16-byte chunk c of row r is stored at chunk position c ^ r, so that both the stores (eight
+// consecutive lanes = one row's line) and the operand reads (sixteen rows at one chunk) are conflict-free.
+template <int NPRE, bool PACKED>
 __global__ __launch_bounds__(kRowsMaxWaves * 64) void gemm_w4_rows_kernel(GemmW4Args a, int tpw) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t s_rows[];  // [2M][KB][24 B] | [M][KB] | [waves][4][64] f32
+  // [2M][KB][24 B] | [M][KB] | [waves][4][64] f32 | canonical weights: [waves][kRowsU][16 rows][256 B]
+  extern __shared__ __attribute__((aligned(16))) uint8_t s_rows[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = lane & 15, g = lane >> 4;
   const int M = (int)a.M;
@@ -357,9 +363,15 @@ __global__ __launch_bounds__(kRowsMaxWaves * 64) void gemm_w4_rows_kernel(GemmW4
   uint32_t w0[NPRE][16];
 #pragma unroll
   for (int i = 0; i < NPRE; ++i) load_x(min(tid + i * (int)blockDim.x, nblocks - 1), w0[i]);
-  const uint8_t* wp = a.W + tile * 1024 + lane * 16;
-  const uint8_t* wep = a.We + tile * 256 + row * 16;
-  const int64_t wq = wtiles * 1024, weq = wtiles * 256;  // bytes between K units / super-steps
+  const int64_t wq = wtiles * 1024, weq = wtiles * 256;  // packed: bytes between K units / super-steps
+  // canonical: instruction u of a super-step covers the 256 bytes of rows 4 u .. 4 u + 3
+  int64_t crow[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) crow[u] = min(tile * 16 + 4 * u + (lane >> 4), N - 1) * (KB * 16);
+  const uint8_t* wp = PACKED ? a.W + tile * 1024 + lane * 16 : a.W + 16 * (lane & 15);
+  const uint8_t* wep = PACKED ? a.We + tile * 256 + row * 16 : a.We + min(tile * 16 + row, N - 1) * KB;
+  uint8_t* stage = reinterpret_cast<uint8_t*>(reinterpret_cast<float*>(sE + (((size_t)M * KB + 15) & ~(size_t)15)) +
+                                              (size_t)blockDim.x / 64 * 256) + (size_t)wave * (kRowsU * 4096);
   struct Batch {
     v4i w[kRowsU][4], sc[kRowsU];
   };
@@ -367,10 +379,12 @@ __global__ __launch_bounds__(kRowsMaxWaves * 64) void gemm_w4_rows_kernel(GemmW4
 #pragma unroll
     for (int u2 = 0; u2 < kRowsU; ++u2) {
       const int64_t sp = min(b * kRowsU + u2, supers - 1);
-      t.sc[u2] = *reinterpret_cast<const v4i*>(wep + sp * weq);
+      t.sc[u2] = *reinterpret_cast<const v4i*>(wep + (PACKED ? sp * weq : sp * 16));
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        t.w[u2][u] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + (4 * sp + u) * wq));
+      for (int u = 0; u < 4; ++u) {
+        const uint8_t* src = PACKED ? wp + (4 * sp + u) * wq : wp + crow[u] + sp * 256;
+        t.w[u2][u] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(src));
+      }
     }
   };
   Batch B0, B1, B2;
@@ -399,6 +413,17 @@ __global__ __launch_bounds__(kRowsMaxWaves * 64) void gemm_w4_rows_kernel(GemmW4
   const uint8_t* erow = sE + (size_t)m * KB;
   const int shift = a.mv.shift * comp;  // beta = alpha / 2^shift
   auto multiply = [&](int64_t b, const Batch& t) {
+    if constexpr (!PACKED) {
+      // the batch's lines into operand order: row r = 4 u + lane / 16, chunk c = lane % 16
+#pragma unroll
+      for (int u2 = 0; u2 < kRowsU; ++u2)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r4 = 4 * u + (lane >> 4), c = lane & 15;
+          *reinterpret_cast<v4i*>(stage + u2 * 4096 + r4 * 256 + ((c ^ r4) & 15) * 16) = t.w[u2][u];
+        }
+      __builtin_amdgcn_wave_barrier();
+    }
 #pragma unroll
     for (int u2 = 0; u2 < kRowsU; ++u2) {
       const int64_t sp = b * kRowsU + u2;
@@ -410,7 +435,10 @@ __global__ __launch_bounds__(kRowsMaxWaves * 64) void gemm_w4_rows_kernel(GemmW4
           const int64_t bi = sp * 16 + 4 * u + g;
           const v8i a1 = load_fp6_lds(arow + bi * 24);
           const int sa = (int)erow[bi] - shift;
-          const v8i wb = {t.w[u2][u][0], t.w[u2][u][1], t.w[u2][u][2], t.w[u2][u][3], 0, 0, 0, 0};
+          v4i wv = t.w[u2][u];
+          if constexpr (!PACKED)
+            wv = *reinterpret_cast<const v4i*>(stage + u2 * 4096 + row * 256 + (((4 * u + g) ^ row) & 15) * 16);
+          const v8i wb = {wv[0], wv[1], wv[2], wv[3], 0, 0, 0, 0};
           acc = mfma_scaled(a1, wb, acc, sa, scale_byte(t.sc[u2], u, g));
         }
 #pragma unroll
@@ -461,31 +489,36 @@ static int w4_rows_tpw(int64_t N) {
   const int64_t rounds = cdiv(tiles, (int64_t)kRowsMaxWaves * 256);
   return (int)cdiv(tiles, 256 * rounds);
 }
-static size_t w4_rows_lds(int64_t M, int64_t K, int tpw) {
+static size_t w4_rows_lds(int64_t M, int64_t K, int tpw, bool packed) {
   const size_t KB = (size_t)K / 32;
-  return 2 * (size_t)M * KB * 24 + align_up((size_t)M * KB, 16) + (size_t)tpw * 1024;
+  return 2 * (size_t)M * KB * 24 + align_up((size_t)M * KB, 16) + (size_t)tpw * 1024 +
+         (packed ? 0 : (size_t)tpw * kRowsU * 4096);
 }
 bool gemm_w4_rows_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned) {
   if (M < 1 || M > kRowsMaxM || K < 512 || K % 512 != 0 || !scales_aligned) return false;
   const int tpw = w4_rows_tpw(N);
   // with few tiles per CU the waves of the K-split kernel pull more data at once
-  return tpw >= 4 && w4_rows_lds(M, K, tpw) <= kRowsMaxLds;
+  return tpw >= 4 && w4_rows_lds(M, K, tpw, false) <= kRowsMaxLds;
 }
 int launch_gemm_w4_rows(const GemmW4Args& a, hipStream_t stream) {
-  if (!a.w_packed || a.x == nullptr || !gemm_w4_rows_applies(a.M, a.K, a.N, a.scales_aligned != 0))
-    return MSD_ERR_INVALID_ARG;
+  if (a.x == nullptr || !gemm_w4_rows_applies(a.M, a.K, a.N, a.scales_aligned != 0)) return MSD_ERR_INVALID_ARG;
   const int tpw = w4_rows_tpw(a.N);
-  const size_t lds = w4_rows_lds(a.M, a.K, tpw);
+  const size_t lds = w4_rows_lds(a.M, a.K, tpw, a.w_packed != 0);
   static bool attr_set = false;
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_rows_kernel<2>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_rows_kernel<2, true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowsMaxLds));
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_rows_kernel<2, false>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowsMaxLds));
     attr_set = true;
   }
   const dim3 grid((unsigned)cdiv(cdiv(a.N, 16), tpw)), block(tpw * 64);
   // two x blocks per thread requested up front (with fewer the second request repeats the last block; an instance
   // with one spilled); long rows take further passes after the weight batches
-  hipLaunchKernelGGL(gemm_w4_rows_kernel<2>, grid, block, lds, stream, a, tpw);
+  if (a.w_packed)
+    hipLaunchKernelGGL((gemm_w4_rows_kernel<2, true>), grid, block, lds, stream, a, tpw);
+  else
+    hipLaunchKernelGGL((gemm_w4_rows_kernel<2, false>), grid, block, lds, stream, a, tpw);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
 }

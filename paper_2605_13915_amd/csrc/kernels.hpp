@@ -101,7 +101,7 @@ bool gemm_w4_is_fused(int64_t M, int64_t K, int64_t N);
 // expert e owns rows [offs[e], offs[e+1]) (device array of E + 1 entries); a.M is unused
 int launch_gemm_w4_grouped(const GemmW4Args& a, const int32_t* offs, int E, hipStream_t stream);
 int launch_gemm_w4(const GemmW4Args& a, hipStream_t stream);
-// one or two rows on packed weights in one launch (a.x set; the kernel decomposes the rows once per workgroup)
+// one or two rows and many channels in one launch (a.x set; the kernel decomposes the rows once per workgroup)
 bool gemm_w4_rows_applies(int64_t M, int64_t K, int64_t N, bool scales_aligned);
 int launch_gemm_w4_rows(const GemmW4Args& a, hipStream_t stream);
 // W [N][K/2], We [N][K/32] -> the packed arrays of msd_pack_weights_w4 (K % 512 == 0)

@@ -404,8 +404,8 @@ static int gemm_w4a16_impl(int variant, bool packed, const void* x_bf16, int64_t
       return launch_gemm_w4_prefill((const uint16_t*)x_bf16, ldx, W_fp4, W_e8m0, y, a.out_bf16, ldy, M, K, N,
                                     (uint8_t*)ws, mv, s, false, a.w_packed);
     }
-    if (packed && !t1 && gemm_w4_rows_applies(M, K, N, a.scales_aligned != 0)) {
-      // one or two rows on packed weights: one launch, the rows decomposed once per workgroup
+    if (!t1 && gemm_w4_rows_applies(M, K, N, a.scales_aligned != 0)) {
+      // one or two rows, many channels: one launch, the rows decomposed once per workgroup
       a.x = (const uint16_t*)x_bf16;
       a.ldx = ldx;
       a.x_aligned = (aligned_to(x_bf16, 16) && ldx % 8 == 0) ? 1 : 0;

@@ -95,7 +95,8 @@ def test_midp_loads_are_not_touched_before_their_wait(mid_isa, inst):
 @pytest.mark.parametrize("src,pattern,extra", [
     ("gemm_w4_prefill.hip", "gemm_w4_dma_kernelILi4ELb0ELb0E", ()),
     ("gemm_w8.hip", "gemm_w8_dma_kernelILi128ELi256ELi4ELi4ELi4ELb0ELb0ELi64ELi1E", ()),
-    ("gemm_w4.hip", "gemm_w4_rows_kernelILi2E", ()),   # three weight batches and two x blocks in registers
+    ("gemm_w4.hip", "gemm_w4_rows_kernelILi2ELb1E", ()),   # three weight batches and two x blocks in registers
+    ("gemm_w4.hip", "gemm_w4_rows_kernelILi2ELb0E", ()),   # ... on the canonical layout
     ("attn_mla.hip", "attn_mla_dequant_kernelILb1E", ()),   # 128 output registers per lane
 ])
 def test_register_bound_kernels_use_no_scratch(tmp_path, src, pattern, extra):
