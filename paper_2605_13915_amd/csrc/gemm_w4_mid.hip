@@ -300,7 +300,14 @@ __device__ __forceinline__ uint64_t midp_uniform(uint64_t v) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-template <int D, int RG, int U, int LW, int WN, bool H16 = false>
+// CANON: the canonical layout W [N][K/2], We [N][K/32] (Wp / Ep then point at those).  A load straight into the B
+// operand would touch 32 weight rows with 32 bytes each; instead the U loads of a batch fetch whole row segments (16
+// lanes x 16 B = the batch's 256 bytes of a channel, four channels per instruction; with four steps per batch 8
+// lanes x 16 B, eight channels) -- the same number of loads as on packed weights, so the wait counts are the same
+// -- and after the batch's wait the wave turns them into operand order through U KB of LDS of its own (chunk c of
+// channel r at chunk position c ^ r: stores and operand reads conflict-free; no barrier, the LDS serves a wave in
+// order).
+template <int D, int RG, int U, int LW, int WN, bool H16 = false, bool CANON = false>
 __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(const uint8_t* __restrict__ qop,
                                                                    const uint8_t* __restrict__ sa_t,
                                                                    const uint8_t* __restrict__ Wp,
@@ -337,7 +344,29 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
     v4i w[U], sc;
   };
   WSet w[NSETS];
+  // CANON: load i of a batch covers channels RPL i .. RPL i + RPL - 1 of the wave's 32 (CPR 16-byte chunks each)
+  constexpr int CPR = U * 2, RPL = 64 / CPR;
+  uint32_t cw_off[CANON ? U : 1];
+  uint32_t ce_off = 0;
+  uint8_t* stage = s_midp + NSETS * C::kBufA + wave * (U * 1024);  // CANON: this wave's [32 channels][U * 32 B]
+  if constexpr (CANON) {
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int64_t nr = min(n0 + wave * 32 + RPL * i + lane / CPR, n_end - 1);
+      cw_off[i] = (uint32_t)(nr * (K / 2) + (lane % CPR) * 16);
+    }
+    ce_off = (uint32_t)(nc * (K / 32));
+  }
   auto load_w = [&](int b, WSet& ws) __attribute__((always_inline)) {
+    if constexpr (CANON) {
+      const bool live = b < NB;  // past the end: every lane re-reads the first 16 bytes of the array
+      b = min(b, NB - 1);
+      const uint8_t* src = reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Wp + (int64_t)b * (U * 32))));
+#pragma unroll
+      for (int i = 0; i < U; ++i) ws.w[i] = midp_load16(src, live ? cw_off[i] : 0u);
+      ws.sc = midp_load16(reinterpret_cast<const uint8_t*>(midp_uniform(reinterpret_cast<uint64_t>(Ep + (int64_t)(b * U / 8) * 16))), live ? ce_off : 0u);
+      return;
+    }
     // past the end: every lane re-reads the first 16 bytes of the last batch (one cache line per instruction)
     const uint32_t w_off = b < NB ? w_lane_off : 0u, e_off = b < NB ? e_lane_off : 0u;
     b = min(b, NB - 1);
@@ -417,6 +446,7 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
     v8i win[WN];
     constexpr int SV = (WN - 1 + UPS - 1) / UPS + 1;  // K steps whose row scales are live at once
     int sav[SV];
+    v4i bfr[CANON ? SV : 1];  // CANON: the steps' B operands, read with the row scales
     auto read_unit = [&](int t, v8i& d) __attribute__((always_inline)) {
       const int u = t / UPS, rg = (t / 2) % RG, comp = t & 1;
       uint4 lo;
@@ -433,6 +463,9 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
       d = v8i{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
       // the step's row scales come with its first unit: byte rg of the dword is the scale of row 32 rg + l32 (block kb)
       if (t % UPS == 0) sav[u % SV] = *reinterpret_cast<const int*>(sa_buf + U * C::kStepA + u * 256 + kb * 128 + l32 * 4);
+      if constexpr (CANON)
+        if (t % UPS == 0)
+          bfr[u % SV] = *reinterpret_cast<const v4i*>(stage + l32 * (CPR * 16) + (((2 * u + kb) ^ l32) & (CPR - 1)) * 16);
     };
 #pragma unroll
     for (int t = 0; t < WN - 1; ++t) read_unit(t, win[t]);
@@ -446,7 +479,8 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
       const int sx = comp ? sa1 - shift * 0x01010101 : sa1;  // beta = alpha / 2^shift (the bytes are >= 4)
       const uint32_t sw = u < 2 ? sd0 : u < 4 ? sd1 : (uint32_t)(u < 6 ? ws.sc[2] : ws.sc[3]);
       const int sb = (int)((sw >> (16 * (u & 1) + 8 * kb)) & 0xFFu);  // scale byte of block 2u + kb of the batch
-      const v8i bw = {ws.w[u][0], ws.w[u][1], ws.w[u][2], ws.w[u][3], 0, 0, 0, 0};
+      const v4i bq = CANON ? bfr[(CANON ? u % SV : 0)] : ws.w[u];
+      const v8i bw = {bq[0], bq[1], bq[2], bq[3], 0, 0, 0, 0};
       const v8i& av = win[t % WN];
       if (rg == 0) acc[rg] = mfma_mid<0, 2>(av, bw, acc[rg], sx, sb);
       else if (rg == 1) acc[rg] = mfma_mid<1, 2>(av, bw, acc[rg], sx, sb);
@@ -471,6 +505,13 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   };
   auto phase = [&](int b, WSet& cur, WSet& far) __attribute__((always_inline)) {
     wait_batch(cur);
+    if constexpr (CANON) {
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        const int r = RPL * i + lane / CPR, c = lane % CPR;
+        *reinterpret_cast<v4i*>(stage + r * (CPR * 16) + ((c ^ r) & (CPR - 1)) * 16) = cur.w[i];
+      }
+    }
     load_w(b + D, far);
     if constexpr (LW == 0) fill_a(b + D);
     multiply(b % NSETS, b, cur);
@@ -506,13 +547,14 @@ __global__ __launch_bounds__(kMidThreads + LW * 64) void gemm_w4_midp_kernel(con
   }
 }
 
-template <int RG, int U, int LW, int WN, bool H16 = false>
+template <int RG, int U, int LW, int WN, bool H16 = false, bool CANON = false, int D = kMidpDepth>
 static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* Wp, const uint8_t* Ep, void* y,
                        int out_bf16, int64_t ldy, int64_t M, int64_t K, int64_t N, int shift, hipStream_t stream) {
-  constexpr int lds = MidpCfg<RG, U, H16>::kLds;
+  constexpr int lds = (D + 1) * MidpCfg<RG, U, H16>::kBufA + (CANON ? (kMidThreads / 64) * U * 1024 : 0);
+  static_assert(lds <= 160 * 1024, "LDS");
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN, H16>),
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w4_midp_kernel<D, RG, U, LW, WN, H16, CANON>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
@@ -522,7 +564,7 @@ static int launch_midp(const uint8_t* qop, const uint8_t* sa_t, const uint8_t* W
   const int64_t rounds = cdiv(tiles, 8 * 256);
   const int64_t tpw = cdiv(tiles, 256 * rounds);
   const int bn = tpw >= 5 ? (int)tpw * 16 : kMidBN;
-  hipLaunchKernelGGL((gemm_w4_midp_kernel<kMidpDepth, RG, U, LW, WN, H16>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads + LW * 64), lds,
+  hipLaunchKernelGGL((gemm_w4_midp_kernel<D, RG, U, LW, WN, H16, CANON>), dim3((unsigned)cdiv(N, bn)), dim3(kMidThreads + LW * 64), lds,
                      stream, qop, sa_t, Wp, Ep, y, out_bf16, ldy, (int)M, K, N, shift, bn);
   MSD_LAUNCH_CHECK();
   return MSD_OK;
@@ -586,6 +628,17 @@ int launch_gemm_w4_mid(const uint16_t* x, int64_t ldx, const uint8_t* W, const u
     if (l.Mpad == 64) return launch_midp<2, 8, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     if (l.Mpad == 96) return launch_midp<3, 4, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
     return launch_midp<4, 4, 4, 5>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+  }
+  // canonical layout: the same kernel with the weights turned into operand order in LDS; its loads address the
+  // array with 32-bit offsets
+  if (N * (K / 2) < ((int64_t)1 << 32)) {
+    if (M <= 16) return launch_midp<1, 8, 4, 5, true, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 32) return launch_midp<1, 8, 4, 5, false, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 64) return launch_midp<2, 4, 4, 5, false, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    if (l.Mpad == 96) return launch_midp<3, 4, 4, 5, false, true>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
+    // four row groups: LDS holds two operand batches instead of three (one batch in flight), no loader waves (with
+    // them this instance spills)
+    return launch_midp<4, 4, 0, 5, false, true, 1>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, stream);
   }
   if (l.Mpad == 32) return launch_mid<1, 8, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);
   if (l.Mpad == 64) return launch_mid<2, 4, false>(qop, sa, W, We, y, out_bf16, ldy, M, K, N, mv.shift, w_packed, stream);

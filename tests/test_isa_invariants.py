@@ -56,8 +56,12 @@ def mid_isa(tmp_path_factory):
     return _isa("gemm_w4_mid.hip", tmp_path_factory.mktemp("isa"))
 
 
-# <depth, row groups, steps per batch, loader waves, operand window, 16-row image>
-@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5ELb0E", "ILi2ELi1ELi8ELi4ELi5ELb1E", "ILi2ELi2ELi8ELi4ELi5ELb0E", "ILi2ELi3ELi4ELi4ELi5ELb0E", "ILi2ELi4ELi4ELi4ELi5ELb0E"])
+# <depth, row groups, steps per batch, loader waves, operand window, 16-row image, canonical weights>
+@pytest.mark.parametrize("inst", ["ILi2ELi1ELi8ELi4ELi5ELb0ELb0E", "ILi2ELi1ELi8ELi4ELi5ELb1ELb0E", "ILi2ELi2ELi8ELi4ELi5ELb0ELb0E",
+                                  "ILi2ELi3ELi4ELi4ELi5ELb0ELb0E", "ILi2ELi4ELi4ELi4ELi5ELb0ELb0E",
+                                  # the canonical weight layout
+                                  "ILi2ELi1ELi8ELi4ELi5ELb0ELb1E", "ILi2ELi1ELi8ELi4ELi5ELb1ELb1E", "ILi2ELi2ELi4ELi4ELi5ELb0ELb1E",
+                                  "ILi2ELi3ELi4ELi4ELi5ELb0ELb1E", "ILi1ELi4ELi4ELi0ELi5ELb0ELb1E"])
 def test_midp_loads_are_not_touched_before_their_wait(mid_isa, inst):
     txt = mid_isa
     name, body = _kernel_body(txt, "gemm_w4_midp_kernel" + inst)
