@@ -2,8 +2,11 @@
 // decode): paper Sec. 3.2.1 / Alg. 2 feeding Sec. 3.4.1 on v_mfma_scale_f32_32x32x64_f8f6f4.
 //
 // Two launches per call: the K-step-major decomposition of gemm_w4_prefill.hip (per group of 32
-// rows 3 KB of FP6 operands per K step of 64 elements, plus one scale record per K step), then this
-// kernel.
+// rows 3 KB of FP6 operands per K step of 64 elements, plus one scale record per K step), then one of
+// the two kernels of this file: gemm_w4_midp_kernel (further down; weights straight into operand
+// registers, hand-counted loads, packed or canonical weight layout) serves the product path;
+// gemm_w4_mid_kernel, the first version, described next, remains for the E2M1-grid ablation and for
+// weight arrays past 4 GiB.
 //
 // One workgroup = 4 waves = 128 output channels, the whole K range, all rows (one, two or four
 // groups of 32); a wave owns 32 channels (lane l: channel l%32, MX block l/32 of each K step).  (Eight waves in
