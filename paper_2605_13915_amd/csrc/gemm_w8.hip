@@ -87,9 +87,17 @@ constexpr int64_t kSelfMaxCodeBytes = 136 * 1024;  // LDS budget for the self-de
 
 // FAST: K % 64 == 0, so no load of the main loop is predicated per lane (predicated loads do not
 // batch); fragment rows past 2M then re-read row 0 -- their products are never looked at.
-template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST>
+// SEG (canonical weights, FAST, every wave's K range a whole number of 256-byte segments): a B-operand load straight
+// from [N][K] touches 16 weight rows with 64 bytes each; instead a wave fetches 256 contiguous bytes of a row per
+// 16 lanes (four rows per instruction, four instructions per tile and four K steps) and turns them into operand
+// order through 4 KB of LDS of its own per tile: chunk c of row r at chunk position c ^ r, so that the stores (eight
+// consecutive lanes = half a row segment) and the operand reads (sixteen rows at one chunk) are conflict-free; no
+// barrier, the LDS serves a wave in order.
+template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST, bool SEG = false>
 __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const int64_t n0) {
   constexpr int THREADS = WAVES * 64;
+  static_assert(!SEG || (FAST && !SELF && UNROLL % 4 == 0), "row segments cover four K steps");
+  __shared__ __attribute__((aligned(16))) int8_t s_seg[SEG ? WAVES * 4096 : 16];
   __shared__ int s_acc[RT][NT][4][64];
   __shared__ float s_red[SELF ? kSelfMaxRows * WAVES : 1];
   __shared__ float s_alpha[kSelfMaxRows];
@@ -112,6 +120,15 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
   for (int t = 0; t < NT; ++t)
     wp[t] = a.w_packed ? a.W + min(n0 / 16 + t, wtiles - 1) * 1024 + lane * 16
                        : a.W + min(n0 + 16 * t + row, N - 1) * K + 16 * g;
+  // SEG: instruction j of a group of four K steps covers rows 4 j .. 4 j + 3 of the tile, 16 lanes per row
+  const int8_t* wseg[SEG ? NT : 1][4];
+  int8_t* my_seg = s_seg + (SEG ? wave * 4096 : 0);
+  if constexpr (SEG) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) wseg[t][j] = a.W + min(n0 + 16 * t + 4 * j + (lane >> 4), N - 1) * K + 16 * (lane & 15);
+  }
   // A-fragment source of this lane: stacked row i = f*16 + row; [0,M) -> x1, [M,2M) -> x2
   int8_t* my_codes = s_codes + (int64_t)wave * 2 * M * kw;
   const int8_t* ap[RT];
@@ -156,7 +173,11 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         wv[t][u] = zero;
-        if (ok[u]) wv[t][u] = ldg16_stream(wp[t] + (ks + u) * wstep);
+        if constexpr (SEG) {  // register u of a group: rows 4 (u % 4) .., the 256 bytes of K steps ks + u - u % 4 ..
+          if (ok[u]) wv[t][u] = ldg16_stream(wseg[t][u & 3] + (int64_t)(ks + (u & ~3)) * 64);
+        } else {
+          if (ok[u]) wv[t][u] = ldg16_stream(wp[t] + (ks + u) * wstep);
+        }
       }
     }
     if (SELF && !ready) {
@@ -220,12 +241,34 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
         if (ok[u] && (FAST || ap[f])) av[f][u] = ldg16(ap[f] + (ks + u) * astep);
       }
     }
+    if constexpr (SEG) {
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
+      for (int q = 0; q < UNROLL / 4; ++q) {
 #pragma unroll
-      for (int f = 0; f < RT; ++f)
+        for (int t = 0; t < NT; ++t) {  // one tile at a time through the wave's 4 KB
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[f][t] = mfma16(av[f][u], wv[t][u], acc[f][t]);
+          for (int j = 0; j < 4; ++j) {
+            const int r = 4 * j + (lane >> 4), c = lane & 15;
+            *reinterpret_cast<v4i*>(my_seg + r * 256 + ((c ^ r) & 15) * 16) = wv[t][4 * q + j];
+          }
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int sub = 0; sub < 4; ++sub) {
+            const v4i bf = *reinterpret_cast<const v4i*>(my_seg + row * 256 + (((4 * sub + g) ^ row) & 15) * 16);
+#pragma unroll
+            for (int f = 0; f < RT; ++f) acc[f][t] = mfma16(av[f][4 * q + sub], bf, acc[f][t]);
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+        for (int f = 0; f < RT; ++f)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) acc[f][t] = mfma16(av[f][u], wv[t][u], acc[f][t]);
+    }
   }
   __syncthreads();  // s_acc zeroed
   if (ks0 < ks1) {
@@ -260,9 +303,9 @@ __device__ __forceinline__ void gemm_w8_decode_body(const GemmW8Args& a, const i
   }
 }
 
-template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST>
+template <int WAVES, int UNROLL, int RT, int NT, bool SELF, bool FAST, bool SEG = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a) {
-  gemm_w8_decode_body<WAVES, UNROLL, RT, NT, SELF, FAST>(a, (int64_t)blockIdx.x * (16 * NT));
+  gemm_w8_decode_body<WAVES, UNROLL, RT, NT, SELF, FAST, SEG>(a, (int64_t)blockIdx.x * (16 * NT));
 }
 
 // Grouped form for mixture-of-experts layers (paper Sec. 7.5: the decomposition is per activation
@@ -270,7 +313,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_decode_kernel(GemmW8Args a
 // e = blockIdx.y owns rows [offs[e], offs[e+1]) and its own weight matrix and scales.  The
 // workgroup reads its expert's row range on the device (no host synchronisation), skips empty
 // experts, and runs the decode body on chunks of 8*RT rows.
-template <int WAVES, int UNROLL, int RT, int NT, bool FAST>
+template <int WAVES, int UNROLL, int RT, int NT, bool FAST, bool SEG = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_grouped_kernel(GemmW8Args a, const int32_t* __restrict__ offs) {
   const int e = blockIdx.y;
   // a.M is the total number of rows: offsets outside [0, M] (a malformed routing table) are clamped, so
@@ -287,7 +330,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_grouped_kernel(GemmW8Args 
     b.y = a.out_bf16 ? (void*)(reinterpret_cast<uint16_t*>(a.y) + c0 * a.ldy)
                      : (void*)(reinterpret_cast<float*>(a.y) + c0 * a.ldy);
     b.M = min((int64_t)(8 * RT), r1 - c0);
-    gemm_w8_decode_body<WAVES, UNROLL, RT, NT, false, FAST>(b, n0);
+    gemm_w8_decode_body<WAVES, UNROLL, RT, NT, false, FAST, SEG>(b, n0);
     __syncthreads();  // the accumulators in LDS are zeroed again by the next chunk
   }
 }
@@ -324,9 +367,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_rowsplit_kernel(GemmW8Args
 // atomics (exact).  Every workgroup repeats the decomposition, which is why the row count is bounded by work:
 // at 16384 elements (about 18 vector instructions each) it costs about as much as the launch it saves.
 // MR: compile-time bound on the rows (chunks of x held per lane: MR * STEPS / 16, at most 4).
-template <int WAVES, int STEPS, int NT, int MR>
+// SEG: canonical weights fetched as 256-byte row segments and turned into operand order through 4 KB of LDS per
+// wave, as in gemm_w8_decode_body.
+template <int WAVES, int STEPS, int NT, int MR, bool SEG = false>
 __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a) {
   constexpr int THREADS = WAVES * 64, KW = STEPS * 64, CPR = KW / 16, PITCH = KW + 16;
+  static_assert(!SEG || STEPS % 4 == 0, "row segments cover four K steps");
+  __shared__ __attribute__((aligned(16))) int8_t s_seg[SEG ? WAVES * 4096 : 16];
   constexpr int XC = (MR * CPR + 63) / 64;
   constexpr int RT = (2 * MR + 15) / 16;
   static_assert(MR <= kFusedMaxRows && (CPR & (CPR - 1)) == 0 && XC <= 4, "rows / K range");
@@ -362,8 +409,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a)
     const int8_t* wp = a.w_packed ? a.W + ((int64_t)wave * STEPS * wtiles + min(n0 / 16 + t, wtiles - 1)) * 1024 + lane * 16
                                   : a.W + min(n0 + 16 * t + row, N - 1) * K + k_lo + 16 * g;
     const int64_t wstep = a.w_packed ? wtiles * 1024 : 64;
+    if constexpr (SEG) {  // register 4 q + j: rows 4 j .. 4 j + 3 of the tile, the 256 bytes of K steps 4 q .. 4 q + 3
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) wv[t][s] = ldg16_stream(wp + s * wstep);
+      for (int s = 0; s < STEPS; ++s)
+        wv[t][s] = ldg16_stream(a.W + min(n0 + 16 * t + 4 * (s & 3) + (lane >> 4), N - 1) * K + k_lo + (s >> 2) * 256 +
+                                16 * (lane & 15));
+    } else {
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s) wv[t][s] = ldg16_stream(wp + s * wstep);
+    }
   }
   // the weight scale of this thread's first output: requested now, needed after the last barrier
   const int64_t n_pre = n0 + (int)threadIdx.x / M;
@@ -428,13 +482,36 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w8_fused_kernel(GemmW8Args a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[f][t] = zero;
   }
+  if constexpr (SEG) {
+    int8_t* my_seg = s_seg + wave * 4096;
 #pragma unroll
-  for (int s = 0; s < STEPS; ++s) {
+    for (int q = 0; q < STEPS / 4; ++q)
 #pragma unroll
-    for (int f = 0; f < RT; ++f) {
-      const v4i av = *reinterpret_cast<const v4i*>(afrag[f] + s * 64);
+      for (int t = 0; t < NT; ++t) {  // one tile at a time through the wave's 4 KB
 #pragma unroll
-      for (int t = 0; t < NT; ++t) acc[f][t] = mfma16(av, wv[t][s], acc[f][t]);
+        for (int j = 0; j < 4; ++j) {
+          const int r = 4 * j + (lane >> 4), c = lane & 15;
+          *reinterpret_cast<v4i*>(my_seg + r * 256 + ((c ^ r) & 15) * 16) = wv[t][4 * q + j];
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+          const v4i bf = *reinterpret_cast<const v4i*>(my_seg + row * 256 + (((4 * sub + g) ^ row) & 15) * 16);
+#pragma unroll
+          for (int f = 0; f < RT; ++f)
+            acc[f][t] = mfma16(*reinterpret_cast<const v4i*>(afrag[f] + (4 * q + sub) * 64), bf, acc[f][t]);
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
+  } else {
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+#pragma unroll
+      for (int f = 0; f < RT; ++f) {
+        const v4i av = *reinterpret_cast<const v4i*>(afrag[f] + s * 64);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[f][t] = mfma16(av, wv[t][s], acc[f][t]);
+      }
     }
   }
 #pragma unroll
@@ -1193,9 +1270,16 @@ static int launch_fused_mr(const GemmW8Args& a, hipStream_t stream) {
   if (!attr_set) {
     MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_fused_kernel<WAVES, STEPS, NT, MR>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelfMaxCodeBytes));
+    MSD_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_w8_fused_kernel<WAVES, STEPS, NT, MR, true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kSelfMaxCodeBytes - WAVES * 4096)));
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_w8_fused_kernel<WAVES, STEPS, NT, MR>), grid, dim3(WAVES * 64), dyn, stream, a);
+  // canonical weights and many column tiles: row-segment loads (4096 x 14336, one row: 14.2 -> 12.7 us; with few
+  // tiles the call is latency-bound and the trip through LDS shows: 5.75 -> 6.0 us at 4096 x 4096)
+  if (!a.w_packed && cdiv(a.N, 16) > 512)
+    hipLaunchKernelGGL((gemm_w8_fused_kernel<WAVES, STEPS, NT, MR, true>), grid, dim3(WAVES * 64), dyn, stream, a);
+  else
+    hipLaunchKernelGGL((gemm_w8_fused_kernel<WAVES, STEPS, NT, MR>), grid, dim3(WAVES * 64), dyn, stream, a);
   return MSD_OK;
 }
 
@@ -1236,6 +1320,13 @@ static int launch_decode(const GemmW8Args& a, hipStream_t stream) {
       allowed = kSelfMaxCodeBytes;
     }
   }
+  if constexpr (!SELF && UNROLL % 4 == 0) {
+    // canonical weights, every wave's K range a whole number of 256-byte row segments
+    if (!a.w_packed && a.K % (WAVES * 256) == 0) {
+      hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, false, true, true>), grid, dim3(WAVES * 64), 0, stream, a);
+      return MSD_OK;
+    }
+  }
   if (a.K % 64 == 0)
     hipLaunchKernelGGL((gemm_w8_decode_kernel<WAVES, UNROLL, RT, NT, SELF, true>), grid, dim3(WAVES * 64), dyn, stream, a);
   else
@@ -1257,7 +1348,10 @@ int launch_gemm_w8_grouped(const GemmW8Args& a, const int32_t* offs, int E, hipS
   if (E <= 0 || a.N == 0) return MSD_OK;
   constexpr int NT = 2;
   const dim3 grid((unsigned)cdiv(a.N, 16 * NT), (unsigned)E);
-  if (a.K % 64 == 0)
+  // (canonical weights only; the K range of each of the eight waves a whole number of 256-byte row segments)
+  if (a.K % 2048 == 0 && !a.w_packed)
+    hipLaunchKernelGGL((gemm_w8_grouped_kernel<8, 4, 2, NT, true, true>), grid, dim3(8 * 64), 0, stream, a, offs);
+  else if (a.K % 64 == 0)
     hipLaunchKernelGGL((gemm_w8_grouped_kernel<8, 4, 2, NT, true>), grid, dim3(8 * 64), 0, stream, a, offs);
   else
     hipLaunchKernelGGL((gemm_w8_grouped_kernel<8, 4, 2, NT, false>), grid, dim3(8 * 64), 0, stream, a, offs);

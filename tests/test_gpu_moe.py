@@ -37,6 +37,7 @@ CASES = [
     (3, 520, 1040, [17, 40, 1]),                 # several chunks per expert, K not a multiple of 64
     (6, 64, 256, [0, 0, 0, 0, 0, 4]),            # all but one expert empty
     (2, 4096, 4096, [2, 7]),                     # decode-sized matrices
+    (5, 330, 2048, [16, 0, 3, 9, 1]),            # row-segment weight loads (K a multiple of 2048), ragged N
 ]
 
 
