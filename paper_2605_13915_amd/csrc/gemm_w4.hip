@@ -63,11 +63,16 @@ __device__ __forceinline__ v8i load_fp6_lds(const uint8_t* p) {  // 24 B, 8-byte
 // the weight stream itself.
 // EXPORT (SELF only): workgroup 0 also writes the ABI-format codes for the observation points; a
 // separate instantiation because that path keeps 64 code registers alive.
-template <int WAVES, int U, int RT, bool SELF, bool FAST, bool STACK, bool EXPORT = false>
+// SEG (FAST, canonical weights): the four loads of a super-step fetch the 256 bytes of a weight row per 16 lanes
+// (four rows per instruction) instead of 64 bytes of each of 16 rows, and the wave turns them into operand order
+// through 4 KB of LDS of its own (chunk c of row r at position c ^ r; no barrier), as in gemm_w4_rows_kernel.
+template <int WAVES, int U, int RT, bool SELF, bool FAST, bool STACK, bool EXPORT = false, bool SEG = false>
 __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const int64_t n0, const int64_t m0) {
   static_assert(!STACK || RT == 1, "stacked components use a single row fragment");
+  static_assert(!SEG || FAST, "row segments need whole super-steps");
   constexpr bool CONTIG = true;
   __shared__ float s_part[WAVES][RT][4][64];
+  __shared__ __attribute__((aligned(16))) uint8_t s_seg[SEG ? WAVES * 4096 : 16];
   extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];  // SELF: per wave [2][M][bpw][24 B] + [M][bpw]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = lane & 15, g = lane >> 4;
@@ -109,7 +114,10 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
         const bool ok = s < s1 && (FAST || bi < KB);
         wb[u2][u] = zero8;
         if (ok) {
-          const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wp + (packed ? (4 * s + u) * wq : bi * 16)));
+          const uint8_t* src = wp + (packed ? (4 * s + u) * wq : bi * 16);
+          if constexpr (SEG)  // rows 4 u .. 4 u + 3 of the tile, chunk lane % 16 of the super-step's 256 bytes
+            src = a.W + min(n0 + 4 * u + (lane >> 4), N - 1) * (KB * 16) + s * 256 + (lane & 15) * 16;
+          const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(src));
           wb[u2][u] = v8i{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
         }
         wsc[u2][u] = fast ? (CONTIG ? scale_byte(sc16, u, g) : scale_byte(sc16, g, u)) : (ok ? (int)wep[bi] : 0x7F);
@@ -182,6 +190,23 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
     for (int u2 = 0; u2 < U; ++u2) {
       const int64_t s = sb + u2;
       if (s >= s1) continue;
+      v8i wseg[SEG ? 4 : 1];
+      if constexpr (SEG) {
+        uint8_t* my_seg = s_seg + wave * 4096;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = 4 * u + (lane >> 4), c = lane & 15;
+          *reinterpret_cast<v4i*>(my_seg + r * 256 + ((c ^ r) & 15) * 16) =
+              v4i{wb[u2][u][0], wb[u2][u][1], wb[u2][u][2], wb[u2][u][3]};
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const v4i v = *reinterpret_cast<const v4i*>(my_seg + row * 256 + (((4 * u + g) ^ row) & 15) * 16);
+          wseg[u] = v8i{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
 #pragma unroll
       for (int f = 0; f < RT; ++f) {
         // source of this lane's fragment row: activation row m, component comp
@@ -222,11 +247,12 @@ __device__ __forceinline__ void gemm_w4_skinny_body(const GemmW4Args& a, const i
               sa = fast ? (CONTIG ? scale_byte(asc16, u, g) : scale_byte(asc16, g, u)) : (int)a.e8m0[m * KB + bi];
             }
           }
+          const v8i wop = SEG ? wseg[SEG ? u : 0] : wb[u2][u];
           if (STACK) {
-            acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa - a.mv.shift * comp, wsc[u2][u]);  // beta = alpha / 2^shift
+            acc[f] = mfma_scaled(a1, wop, acc[f], sa - a.mv.shift * comp, wsc[u2][u]);  // beta = alpha / 2^shift
           } else {
-            acc[f] = mfma_scaled(a1, wb[u2][u], acc[f], sa, wsc[u2][u]);
-            acc[f] = mfma_scaled(a2, wb[u2][u], acc[f], sa - a.mv.shift, wsc[u2][u]);  // beta = alpha / 2^shift
+            acc[f] = mfma_scaled(a1, wop, acc[f], sa, wsc[u2][u]);
+            acc[f] = mfma_scaled(a2, wop, acc[f], sa - a.mv.shift, wsc[u2][u]);  // beta = alpha / 2^shift
           }
         }
       }
@@ -285,7 +311,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4_grouped_kernel(GemmW4Args 
     b.y = a.out_bf16 ? (void*)(reinterpret_cast<uint16_t*>(a.y) + c0 * a.ldy)
                      : (void*)(reinterpret_cast<float*>(a.y) + c0 * a.ldy);
     b.M = min((int64_t)8, r1 - c0);
-    gemm_w4_skinny_body<WAVES, U, 1, false, FAST, true>(b, (int64_t)blockIdx.x * 16, 0);
+    gemm_w4_skinny_body<WAVES, U, 1, false, FAST, true, false, FAST>(b, (int64_t)blockIdx.x * 16, 0);
     __syncthreads();  // the wave partials in LDS are rewritten by the next chunk
   }
 }
