@@ -320,6 +320,7 @@ def test_extreme_magnitudes_stay_bit_exact(msd, ex):
 # ---------------------------------------------------------------- packed weights (msd_pack_weights_w8)
 PACKED_SHAPES = [
     (1, 4096, 4096), (2, 4096, 8300), (4, 2048, 530), (8, 1024, 90), (3, 8192, 300),        # single-launch kernel
+    (4, 4096, 9000), (2, 8192, 8400), (1, 2048, 8200),   # ... many column tiles: row-segment loads on the canonical layout
     (8, 4096, 4096), (5, 4096, 8300), (16, 4096, 4100), (12, 2112, 700), (32, 4096, 1000),  # register-operand kernels
     (15, 8192, 8300), (9, 64, 20), (20, 4096, 4100), (24, 1024, 90), (17, 2112, 700),   # ... 17..24 rows: three fragments
     (30, 512, 8300), (70, 320, 6500), (128, 256, 12800), (128, 4096, 1024), (100, 1024, 700),   # small LDS tiles
