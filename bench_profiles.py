@@ -120,6 +120,36 @@ def do_trace():
     print("".join(out))
 
 
+# ------------------------------------------------------------------ kernel trace of the other configurations
+def do_trace_extras():
+    legs = "prefill,w4,attn,mla,moe"
+    d = run_pass("prof_extras", ["--kernel-trace", "--stats"], ["--extras", legs, "--no-cpu-baseline", "--one-layout"], limit=500)
+    out = ["Prefill, W4, attention, latent-cache and grouped legs: rocprofv3 kernel-trace summary\n",
+           "=====================================================================================\n",
+           "Command (from the repository root, on one MI355X):  python3 bench_profiles.py trace_extras\n",
+           "  = rocprofv3 --kernel-trace --stats -d gpurun_out/prof_extras -o p --output-format csv -- \\\n",
+           "        python3 bench.py --extras %s --no-cpu-baseline --one-layout        (cwd /tmp, TMPDIR=/tmp)\n" % legs, stamp(),
+           "Workload: bench.py's legs for cfg2 (W8A16 prefill), cfg3 (W4A16, M = 1 / 32 / 4096), cfg4 (attention decode,\n",
+           "L = 4096 / 32768), attention over a latent cache and the grouped GEMMs, each with its comparison kernel,\n",
+           "replayed from HIP graphs; the headline step runs first (its kernels are in w8a16_decode_bench_kernel_stats.txt\n",
+           "too).  One template instantiation serves several shapes: the grid size tells them apart.\n\n",
+           "Columns: kernel, grid threads, workgroup, VGPRs, scratch, dispatches, avg / min / median / max us:\n"]
+    rows = list(csv.DictReader(open(find_csv(d, "kernel_trace.csv"))))
+    g = collections.defaultdict(list)
+    for r in rows:
+        if "msd::" not in r["Kernel_Name"] or "pack_weights" in r["Kernel_Name"]:
+            continue
+        g[(short(r["Kernel_Name"]), int(r["Grid_Size_X"]) * int(r.get("Grid_Size_Y", 1) or 1), r["Workgroup_Size_X"],
+           r["VGPR_Count"], r["Scratch_Size"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    for k, v in sorted(g.items()):
+        v2 = sorted(v)
+        out.append("  %-66s grid %8d wg %4s vgpr %3s scratch %s  n %4d  avg %8.2f  min %8.2f  med %8.2f  max %8.2f\n"
+                   % (k[0][:66], k[1], k[2], k[3], k[4], len(v), sum(v) / len(v) / 1e3, v2[0] / 1e3, v2[len(v) // 2] / 1e3,
+                      v2[-1] / 1e3))
+    write_summary("prefill_w4_attn_kernel_stats.txt", "".join(out))
+    print("".join(out))
+
+
 # ------------------------------------------------------------------ HBM traffic
 def counter_rows(d):
     """dispatches of the counter run, without the one-time weight repack kernels of the set-up (the probes run on
@@ -280,6 +310,8 @@ if __name__ == "__main__":
     os.makedirs(PROF, exist_ok=True)
     if what in ("trace", "all"):
         do_trace()
+    if what in ("trace_extras", "all"):
+        do_trace_extras()
     if what in ("traffic", "all"):
         do_traffic()
     if what in ("counters", "all"):
